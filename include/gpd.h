@@ -1,0 +1,254 @@
+/*
+ * gpd.h — C ABI of the MI355X (gfx950) Generalized PolyDot coded-computation library.
+ *
+ * Implements the hot path of "A Unified Coded Deep Neural Network Training Strategy Based
+ * on Generalized PolyDot Codes for Matrix Multiplication" (arXiv 1811.10751): encode, the
+ * coded products of all P nodes (simulated on one GPU), decode with erasures and
+ * soft-error correction, and the coded DNN layer step that keeps the weights encoded.
+ *
+ * Notation (paper -> here): W -> A (N1 x N0, split into an m x n block grid), X -> B
+ * (N0 x Nc, split n x d), S -> C (N1 x Nc, split m x d); b_p, p = 0..P-1, are the distinct
+ * evaluation points; K is the recovery threshold = number of coefficients of the product
+ * polynomial.
+ *
+ * Conventions
+ *   - Every matrix is row-major with an explicit leading dimension (in elements).
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are
+ *     ordinary host memory owned by the caller.  The library owns only the opaque
+ *     plan / layer objects and their small coefficient tables.
+ *   - Coded stacks are contiguous [P][rows][cols]; fp32 unless stated.
+ *   - Calls enqueue work on the stream given at plan creation and return without
+ *     waiting, except where a host-side report is requested (then the call waits for the
+ *     stream before returning).
+ *   - Every call returns a gpd_status_t, never throws, never aborts; gpd_last_error()
+ *     gives a thread-local message for the last non-OK status.
+ *   - A missing GPU or a failed launch is GPD_E_DEVICE; there is no CPU fallback.
+ */
+#ifndef GPD_H
+#define GPD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GPD_MAX_P 64          /* largest number of nodes P */
+#define GPD_MAX_BLOCKS 64     /* largest m*n, n*d, m*d (blocks combined by one kernel) */
+
+typedef enum {
+  GPD_OK = 0,
+  GPD_E_INVALID = 1,      /* null pointer, bad enum, m/n/d/P < 1 or above the limits      */
+  GPD_E_SHAPE = 2,        /* m does not divide N1, n not N0, d not Nc; or K > P            */
+  GPD_E_POINTS = 3,       /* evaluation points not finite or not distinct                  */
+  GPD_E_TOO_FEW = 4,      /* fewer than K responses present                                */
+  GPD_E_DECODE_FAIL = 5,  /* errors detected that cannot be corrected ("decoding failure",
+                             Sec. V Algorithm 1 last step); the output is still written    */
+  GPD_E_WORKSPACE = 6,    /* workspace missing, too small or misaligned                    */
+  GPD_E_DEVICE = 7,       /* HIP error or no GPU                                           */
+  GPD_E_UNSUPPORTED = 8   /* valid request this build has no kernel for                    */
+} gpd_status_t;
+
+typedef enum { GPD_F32 = 0, GPD_BF16 = 1 } gpd_dtype_t;      /* operand type of the worker products */
+
+/* Substitution that turns the multivariate product polynomial into one variable
+ * (Sec. IV proof of Thm 2; appendix on error tolerance, second case):
+ *   U_VN: u = v^n, w = v^(mn)   K = mnd + n - 1
+ *   V_UM: v = u^m, w = u^(mn)   K = mnd + mn - m
+ * AUTO = U_VN for a matmul plan; for a layer, the one with the smaller max(K_f, K_b). */
+typedef enum { GPD_SUB_AUTO = 0, GPD_SUB_U_VN = 1, GPD_SUB_V_UM = 2 } gpd_subst_t;
+
+typedef enum {
+  GPD_DEC_FIRST_K = 0,    /* interpolate from the first K present nodes, by node index
+                             (remark after Thm 2: the master waits for K nodes)            */
+  GPD_DEC_LSQ_ALL = 1     /* least squares over every present node                         */
+} gpd_decmode_t;
+
+typedef struct gpd_plan gpd_plan_t;
+typedef struct gpd_layer gpd_layer_t;
+
+/* ------------------------------------------------------------------ coded matmul */
+
+typedef struct {
+  int64_t N1, N0, Nc;       /* A is N1 x N0, B is N0 x Nc                                   */
+  int32_t m, n, d;          /* block grids: A m x n, B n x d                                */
+  int32_t P;                /* number of nodes / evaluation points, K <= P <= GPD_MAX_P     */
+  const double* points;     /* host, P distinct finite reals; NULL = Chebyshev points of the
+                               first kind cos((2p+1)pi/(2P))                               */
+  int32_t worker_dtype;     /* gpd_dtype_t: type A~_p and B~_p are stored and multiplied in  */
+  int32_t subst;            /* gpd_subst_t                                                  */
+  double rho_detect;        /* relative detection threshold rho; 0 = default (2^-12 for
+                               fp32 workers, 2^-3 for bf16 workers)                        */
+  double abs_floor;         /* tau(z) = rho * max(||z||_2, abs_floor)                       */
+  void* hip_stream;         /* hipStream_t all work of this plan is enqueued on (0 = null
+                               stream)                                                     */
+} gpd_problem_t;
+
+/* Code construction (Sec. IV, Thm 2): exponent tables, K, evaluation points, coefficient
+ * tables b_p^e (computed in fp64 on the host, stored as fp32 on the device).  Host work
+ * plus one small upload.  *out is owned by the library until gpd_plan_destroy. */
+gpd_status_t gpd_plan(const gpd_problem_t* problem, gpd_plan_t** out);
+
+/* K = recovery threshold; t_max = P - K - 1 = errors correctable per codeword under the
+ * probabilistic model (Thm 3); workspace_bytes = device bytes gpd_decode needs when
+ * correct_errors != 0 (0 otherwise is fine).  Any output pointer may be NULL. */
+gpd_status_t gpd_plan_info(const gpd_plan_t* plan, int32_t* K, int32_t* t_max,
+                           size_t* workspace_bytes);
+
+/* Copies the P evaluation points (fp64) and the exponents of the blocks of A (m*n, row-major
+ * over (i,j)), of B (n*d over (j,k)) and the useful exponents of C (m*d over (i,k)) to host
+ * arrays; any pointer may be NULL. */
+gpd_status_t gpd_plan_tables(const gpd_plan_t* plan, double* points, int32_t* eA,
+                             int32_t* eB, int32_t* eC);
+
+void gpd_plan_destroy(gpd_plan_t* plan);
+
+/* Encode (Sec. IV, equations for W~(u,v) and X~(v,w)):
+ *   At[p] = sum_{i,j} b_p^eA(i,j) A_{i,j}      At: device [P][N1/m][N0/n]
+ *   Bt[p] = sum_{j,k} b_p^eB(j,k) B_{j,k}      Bt: device [P][N0/n][Nc/d]
+ * A, B: device fp32, leading dimensions lda, ldb.  Either pair (A, At) or (B, Bt) may be
+ * NULL to skip it.  At/Bt hold fp32 or bf16 (round-to-nearest-even) per worker_dtype. */
+gpd_status_t gpd_encode(const gpd_plan_t* plan, const float* A, int64_t lda,
+                        const float* B, int64_t ldb, void* At, void* Bt);
+
+/* Worker products (proof of Thm 2: node p multiplies its two coded blocks):
+ *   Ct[p] = At[p] * Bt[p]   for all p; Ct: device fp32 [P][N1/m][Nc/d].
+ * fp32 operands use fp32 MFMA; bf16 operands use bf16 MFMA with fp32 accumulation. */
+gpd_status_t gpd_worker_products(const gpd_plan_t* plan, const void* At, const void* Bt,
+                                 float* Ct);
+
+typedef struct { int32_t node, row, col; float magnitude; } gpd_located_t;
+
+/* Host-side decode report.  Before the call the caller sets located (may be NULL) and
+ * located_cap; everything else is written by the library. */
+typedef struct {
+  int32_t status;                      /* gpd_status_t of the decode                         */
+  int32_t n_present;                   /* |S|                                                */
+  int64_t n_screened;                  /* codewords the fp32 screen passed to the fp64 check  */
+  int64_t n_flagged;                   /* codewords with ||Hz|| > tau or a non-finite entry   */
+  int64_t n_located;                   /* located (node, row, col) errors in total            */
+  int64_t n_failed;                    /* codewords declared "decoding failure"               */
+  int32_t node_err_count[GPD_MAX_P];   /* located errors per node                             */
+  float max_syndrome_ratio;            /* max over unflagged codewords of ||Hz|| / tau (fp32) */
+  int32_t reserved;
+  int64_t located_cap;                 /* in: capacity of located[]                           */
+  gpd_located_t* located;              /* out: first min(n_located, cap) entries, sorted by
+                                          (node, row, col); magnitude = estimated error value,
+                                          NaN for a non-finite response                      */
+} gpd_report_t;
+
+/* Decode (remark after Thm 2; Sec. V Algorithm 1; appendix "Decoding Methods"):
+ * every element position (row, col) of the P blocks of Ct is a received word z of a
+ * (|S|, K) real-number MDS code; block (i,k) of C is the coefficient of b^eC(i,k).
+ *   present: host uint8[P], non-zero = node responded; NULL = all.  Fewer than K present
+ *            -> GPD_E_TOO_FEW, nothing written.
+ *   mode:    which present nodes the interpolation uses (see gpd_decmode_t).
+ *   correct_errors != 0: all present nodes are used.  Step 1: ||Hz||_2 <= tau(z) with H
+ *            an orthonormal parity check of the present nodes; steps 2-3: smallest support
+ *            (at most |S| - K - 1 nodes, smallest least-squares residual inside one size)
+ *            whose columns of H explain Hz up to tau(z); then least squares from the
+ *            remaining nodes.  Non-finite responses count as located errors.  A codeword
+ *            with no such support is a decoding failure: GPD_E_DECODE_FAIL is returned in
+ *            the report and its output is the uncorrected least-squares value.
+ *            Requires workspace (device, 256-byte aligned, workspace_bytes from
+ *            gpd_plan_info).
+ *   C:       device fp32 N1 x Nc, leading dimension ldc.
+ *   report:  host, or NULL.  With a report the call waits for the stream; without one it
+ *            is asynchronous and GPD_E_DECODE_FAIL cannot be returned.
+ */
+gpd_status_t gpd_decode(const gpd_plan_t* plan, const float* Ct, const uint8_t* present,
+                        int32_t mode, int32_t correct_errors, float* C, int64_t ldc,
+                        void* workspace, size_t workspace_bytes, gpd_report_t* report);
+
+/* ------------------------------------------------------------------ coded DNN layer */
+
+typedef struct {
+  int64_t N_out, N_in, batch;   /* W is N_out x N_in; X is N_in x batch; Delta N_out x batch  */
+  int32_t m, n;                 /* W split m x n (rows / cols zero-padded up to multiples)    */
+  int32_t d1, d2;               /* X split n x d1 (forward), Delta^T split d2 x m (backward)  */
+  int32_t P;
+  const double* points;         /* as in gpd_problem_t                                        */
+  int32_t worker_dtype;         /* GPD_BF16: forward/backward products in bf16 MFMA; W~ itself,
+                                   encode, decode and update stay fp32                       */
+  int32_t subst;
+  double rho_detect, abs_floor;
+  void* hip_stream;
+} gpd_layer_desc_t;
+
+typedef enum { GPD_STEP_FORWARD = 0, GPD_STEP_BACKWARD_UPDATE = 1 } gpd_phase_t;
+
+/* One coded layer (Sec. VII for batch 1, Sec. IX for batch > 1). */
+gpd_status_t gpd_layer_create(const gpd_layer_desc_t* desc, gpd_layer_t** out);
+
+/* K_f, K_b: thresholds of the forward / backward product polynomials (Tables I and III give
+ * P - K - 1 as the error tolerances); wt_rows x wt_cols: shape of one coded block W~_p;
+ * workspace_bytes: device bytes gpd_coded_layer_step needs. */
+gpd_status_t gpd_layer_info(const gpd_layer_t* layer, int32_t* Kf, int32_t* Kb,
+                            int64_t* wt_rows, int64_t* wt_cols, size_t* workspace_bytes);
+
+/* Initial encoding of W (Sec. VII pre-processing step): Wt device fp32 [P][wt_rows][wt_cols]. */
+gpd_status_t gpd_layer_encode_weights(const gpd_layer_t* layer, const float* W, int64_t ldw,
+                                      float* Wt);
+
+/* W back from the coded blocks (degree mn-1 polynomial, footnote on regeneration, Sec. VII):
+ * least squares over the present nodes (at least mn of them). */
+gpd_status_t gpd_layer_decode_weights(const gpd_layer_t* layer, const float* Wt,
+                                      const uint8_t* present, float* W, int64_t ldw);
+
+/* One phase of one training iteration of this layer.
+ *   FORWARD (step O1):  encode X, S~_p = W~_p X~_p for all p, decode -> out = S = W X,
+ *                       device fp32 N_out x batch (pre-activation).
+ *   BACKWARD_UPDATE (steps O2, O3): encode Delta^T, C~^T_p = Delta~^T_p W~_p with the
+ *                       pre-update W~_p, decode -> out = C = W^T Delta, device fp32
+ *                       N_in x batch (before the Hadamard product; NULL skips O2); then
+ *                       W~_p <- (1 - decay) W~_p + eta * (sum_i Delta_i a_p^i)(sum_j X_j b_p^j)^T
+ *                       in place (Eq. "coded update"; decay = eta * lambda).
+ *   X:   device fp32 N_in x batch (ld = batch), the layer input.
+ *   Dlt: device fp32 N_out x batch (ld = batch), ignored in FORWARD.
+ *   present / correct_errors / report: as in gpd_decode, applied to the P node outputs.
+ *   workspace: device, 256-byte aligned, workspace_bytes from gpd_layer_info.
+ */
+gpd_status_t gpd_coded_layer_step(gpd_layer_t* layer, int32_t phase, float* Wt,
+                                  const float* X, const float* Dlt, float eta, float decay,
+                                  float* out, const uint8_t* present, int32_t correct_errors,
+                                  void* workspace, size_t workspace_bytes, gpd_report_t* report);
+
+void gpd_layer_destroy(gpd_layer_t* layer);
+
+/* Element-wise steps C1 / C2 and the last-layer error (Sec. II background; logistic f):
+ *   gpd_sigmoid_fwd:  y = 1 / (1 + exp(-s))
+ *   gpd_sigmoid_bwd:  delta_prev = c * y * (1 - y)          (g(f(u)) = f'(u))
+ *   gpd_l2_delta:     delta = scale * (y - yhat) * yhat * (1 - yhat), scale = 2 / batch
+ * All pointers device fp32, count elements, enqueued on hip_stream. */
+gpd_status_t gpd_sigmoid_fwd(const float* s, float* y, int64_t count, void* hip_stream);
+gpd_status_t gpd_sigmoid_bwd(const float* c, const float* y, float* delta_prev, int64_t count,
+                             void* hip_stream);
+gpd_status_t gpd_l2_delta(const float* y, const float* yhat, float scale, float* delta,
+                          int64_t count, void* hip_stream);
+
+/* ------------------------------------------------------------------ host-only helpers */
+
+/* The code construction of gpd_plan without a GPU (Sec. IV, Thm 2): K and the exponent tables
+ * (eA m*n, eB n*d, eC m*d, row-major) and the P evaluation points.  Output pointers may be NULL. */
+gpd_status_t gpd_host_code(int32_t m, int32_t n, int32_t d, int32_t P, int32_t subst,
+                           const double* points, int32_t* K, int32_t* eA, int32_t* eB, int32_t* eC,
+                           double* points_out);
+
+/* The fp64 decoding matrices gpd_decode uploads, without a GPU (appendix on decoding):
+ *   D: host [m*d][n_present], rows eC of the inverse (first_k != 0: of the first K present
+ *      nodes, other columns zero) or pseudo-inverse (all present nodes) of the Vandermonde matrix;
+ *   H: host [(n_present-K)][n_present], orthonormal parity check of the present nodes, or NULL. */
+gpd_status_t gpd_host_decode_matrices(int32_t m, int32_t n, int32_t d, int32_t P, int32_t subst,
+                                      const double* points, const uint8_t* present, int32_t first_k,
+                                      double* D, double* H, int32_t* n_present);
+
+/* ------------------------------------------------------------------ misc */
+
+const char* gpd_last_error(void);     /* thread-local, never NULL */
+const char* gpd_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GPD_H */

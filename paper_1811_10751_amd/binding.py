@@ -1,0 +1,478 @@
+"""ctypes binding of libgpd.so: same names as the C ABI in include/gpd.h.
+
+Argument marshalling only: every function here hands device pointers of torch tensors
+(torch is used for device memory and streams) to the library and returns what the library
+wrote.  There is no fallback: without the built library or without a GPU the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass, field
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgpd.so")
+
+GPD_MAX_P = 64
+GPD_OK, GPD_E_INVALID, GPD_E_SHAPE, GPD_E_POINTS, GPD_E_TOO_FEW, GPD_E_DECODE_FAIL, \
+    GPD_E_WORKSPACE, GPD_E_DEVICE, GPD_E_UNSUPPORTED = range(9)
+GPD_F32, GPD_BF16 = 0, 1
+GPD_SUB_AUTO, GPD_SUB_U_VN, GPD_SUB_V_UM = 0, 1, 2
+GPD_DEC_FIRST_K, GPD_DEC_LSQ_ALL = 0, 1
+GPD_STEP_FORWARD, GPD_STEP_BACKWARD_UPDATE = 0, 1
+
+STATUS_NAMES = ["OK", "E_INVALID", "E_SHAPE", "E_POINTS", "E_TOO_FEW", "E_DECODE_FAIL",
+                "E_WORKSPACE", "E_DEVICE", "E_UNSUPPORTED"]
+
+EXPORTS = [
+    "gpd_plan", "gpd_plan_info", "gpd_plan_tables", "gpd_plan_destroy", "gpd_encode",
+    "gpd_worker_products", "gpd_decode", "gpd_layer_create", "gpd_layer_info",
+    "gpd_layer_encode_weights", "gpd_layer_decode_weights", "gpd_coded_layer_step",
+    "gpd_layer_destroy", "gpd_sigmoid_fwd", "gpd_sigmoid_bwd", "gpd_l2_delta",
+    "gpd_host_code", "gpd_host_decode_matrices", "gpd_last_error", "gpd_version",
+]
+
+
+class GpdError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"gpd status {STATUS_NAMES[status] if 0 <= status < 9 else status}: {msg}")
+        self.status = status
+
+
+class _Problem(C.Structure):
+    _fields_ = [("N1", C.c_int64), ("N0", C.c_int64), ("Nc", C.c_int64),
+                ("m", C.c_int32), ("n", C.c_int32), ("d", C.c_int32), ("P", C.c_int32),
+                ("points", C.POINTER(C.c_double)),
+                ("worker_dtype", C.c_int32), ("subst", C.c_int32),
+                ("rho_detect", C.c_double), ("abs_floor", C.c_double),
+                ("hip_stream", C.c_void_p)]
+
+
+class _Located(C.Structure):
+    _fields_ = [("node", C.c_int32), ("row", C.c_int32), ("col", C.c_int32),
+                ("magnitude", C.c_float)]
+
+
+class _Report(C.Structure):
+    _fields_ = [("status", C.c_int32), ("n_present", C.c_int32),
+                ("n_screened", C.c_int64), ("n_flagged", C.c_int64),
+                ("n_located", C.c_int64), ("n_failed", C.c_int64),
+                ("node_err_count", C.c_int32 * GPD_MAX_P),
+                ("max_syndrome_ratio", C.c_float), ("reserved", C.c_int32),
+                ("located_cap", C.c_int64), ("located", C.POINTER(_Located))]
+
+
+class _LayerDesc(C.Structure):
+    _fields_ = [("N_out", C.c_int64), ("N_in", C.c_int64), ("batch", C.c_int64),
+                ("m", C.c_int32), ("n", C.c_int32), ("d1", C.c_int32), ("d2", C.c_int32),
+                ("P", C.c_int32),
+                ("points", C.POINTER(C.c_double)),
+                ("worker_dtype", C.c_int32), ("subst", C.c_int32),
+                ("rho_detect", C.c_double), ("abs_floor", C.c_double),
+                ("hip_stream", C.c_void_p)]
+
+
+_lib = None
+
+
+def load_library():
+    """Loads libgpd.so (built in-tree by paper_1811_10751_amd.build); raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is not built; run `python -m paper_1811_10751_amd.build`")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+    lib.gpd_plan.argtypes = [C.POINTER(_Problem), C.POINTER(vp)]
+    lib.gpd_plan_info.argtypes = [vp, C.POINTER(i32), C.POINTER(i32), C.POINTER(sz)]
+    lib.gpd_plan_tables.argtypes = [vp, vp, vp, vp, vp]
+    lib.gpd_plan_destroy.argtypes = [vp]
+    lib.gpd_plan_destroy.restype = None
+    lib.gpd_encode.argtypes = [vp, vp, i64, vp, i64, vp, vp]
+    lib.gpd_worker_products.argtypes = [vp, vp, vp, vp]
+    lib.gpd_decode.argtypes = [vp, vp, vp, i32, i32, vp, i64, vp, sz, C.POINTER(_Report)]
+    lib.gpd_layer_create.argtypes = [C.POINTER(_LayerDesc), C.POINTER(vp)]
+    lib.gpd_layer_info.argtypes = [vp, C.POINTER(i32), C.POINTER(i32), C.POINTER(i64),
+                                   C.POINTER(i64), C.POINTER(sz)]
+    lib.gpd_layer_encode_weights.argtypes = [vp, vp, i64, vp]
+    lib.gpd_layer_decode_weights.argtypes = [vp, vp, vp, vp, i64]
+    lib.gpd_coded_layer_step.argtypes = [vp, i32, vp, vp, vp, C.c_float, C.c_float, vp, vp, i32,
+                                         vp, sz, C.POINTER(_Report)]
+    lib.gpd_layer_destroy.argtypes = [vp]
+    lib.gpd_layer_destroy.restype = None
+    lib.gpd_sigmoid_fwd.argtypes = [vp, vp, i64, vp]
+    lib.gpd_sigmoid_bwd.argtypes = [vp, vp, vp, i64, vp]
+    lib.gpd_l2_delta.argtypes = [vp, vp, C.c_float, vp, i64, vp]
+    lib.gpd_host_code.argtypes = [i32, i32, i32, i32, i32, vp, C.POINTER(i32), vp, vp, vp, vp]
+    lib.gpd_host_decode_matrices.argtypes = [i32, i32, i32, i32, i32, vp, vp, i32, vp, vp,
+                                             C.POINTER(i32)]
+    lib.gpd_last_error.restype = C.c_char_p
+    lib.gpd_version.restype = C.c_char_p
+    for name in EXPORTS:
+        fn = getattr(lib, name)
+        if fn.restype is C.c_int:
+            fn.restype = C.c_int32
+    _lib = lib
+    return lib
+
+
+def _check(st: int, ok=(GPD_OK,)):
+    if st not in ok:
+        raise GpdError(st, load_library().gpd_last_error().decode())
+    return st
+
+
+def _ptr(t):
+    """Device (or host) pointer of a torch tensor / numpy array / None."""
+    if t is None:
+        return None
+    if isinstance(t, np.ndarray):
+        return t.ctypes.data
+    return t.data_ptr()
+
+
+def _stream_handle(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return getattr(stream, "cuda_stream", stream)
+
+
+def _require_f32_cuda(t, name):
+    import torch
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.float32):
+        raise TypeError(f"{name} must be a float32 CUDA tensor")
+
+
+@dataclass
+class Report:
+    status: int = 0
+    n_present: int = 0
+    n_screened: int = 0
+    n_flagged: int = 0
+    n_located: int = 0
+    n_failed: int = 0
+    node_err_count: np.ndarray | None = None
+    max_syndrome_ratio: float = 0.0
+    located: list = field(default_factory=list)   # (node, row, col, magnitude), sorted
+
+
+def _make_report(cap: int):
+    buf = (_Located * max(cap, 1))()
+    rep = _Report()
+    rep.located = C.cast(buf, C.POINTER(_Located))
+    rep.located_cap = cap
+    return rep, buf
+
+
+def _read_report(rep: _Report, buf, P: int) -> Report:
+    n = int(min(rep.n_located, rep.located_cap))
+    return Report(status=rep.status, n_present=rep.n_present, n_screened=rep.n_screened,
+                  n_flagged=rep.n_flagged, n_located=rep.n_located, n_failed=rep.n_failed,
+                  node_err_count=np.array(rep.node_err_count[:P], dtype=np.int64),
+                  max_syndrome_ratio=float(rep.max_syndrome_ratio),
+                  located=[(buf[i].node, buf[i].row, buf[i].col, buf[i].magnitude) for i in range(n)])
+
+
+def _present_array(present, P):
+    if present is None:
+        return None
+    arr = np.ascontiguousarray(np.asarray(present, dtype=np.uint8))
+    if arr.shape != (P,):
+        raise ValueError("present must have P entries")
+    return arr
+
+
+class Plan:
+    """Owns a gpd_plan_t*."""
+
+    def __init__(self, handle, problem: _Problem, keep):
+        self.handle = handle
+        self.problem = problem
+        self._keep = keep
+        lib = load_library()
+        K, t, ws = C.c_int32(), C.c_int32(), C.c_size_t()
+        _check(lib.gpd_plan_info(handle, C.byref(K), C.byref(t), C.byref(ws)))
+        self.K, self.t_max, self.workspace_bytes = K.value, t.value, ws.value
+        self.m, self.n, self.d, self.P = problem.m, problem.n, problem.d, problem.P
+        self.N1, self.N0, self.Nc = problem.N1, problem.N0, problem.Nc
+        self.worker_dtype = problem.worker_dtype
+
+    def tables(self):
+        lib = load_library()
+        pts = np.zeros(self.P)
+        eA = np.zeros(self.m * self.n, dtype=np.int32)
+        eB = np.zeros(self.n * self.d, dtype=np.int32)
+        eC = np.zeros(self.m * self.d, dtype=np.int32)
+        _check(lib.gpd_plan_tables(self.handle, pts.ctypes.data, eA.ctypes.data, eB.ctypes.data,
+                                   eC.ctypes.data))
+        return pts, eA.reshape(self.m, self.n), eB.reshape(self.n, self.d), eC.reshape(self.m, self.d)
+
+    def close(self):
+        if self.handle:
+            load_library().gpd_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def gpd_plan(N1, N0, Nc, m, n, d, P, points=None, worker_dtype=GPD_F32, subst=GPD_SUB_AUTO,
+             rho_detect=0.0, abs_floor=0.0, stream=None) -> Plan:
+    lib = load_library()
+    pr = _Problem()
+    pr.N1, pr.N0, pr.Nc, pr.m, pr.n, pr.d, pr.P = N1, N0, Nc, m, n, d, P
+    keep = None
+    if points is not None:
+        keep = np.ascontiguousarray(np.asarray(points, dtype=np.float64))
+        if keep.shape != (P,):
+            raise ValueError("points must have P entries")
+        pr.points = keep.ctypes.data_as(C.POINTER(C.c_double))
+    pr.worker_dtype, pr.subst = worker_dtype, subst
+    pr.rho_detect, pr.abs_floor = rho_detect, abs_floor
+    pr.hip_stream = _stream_handle(stream)
+    h = C.c_void_p()
+    _check(lib.gpd_plan(C.byref(pr), C.byref(h)))
+    return Plan(h, pr, keep)
+
+
+def gpd_encode(plan: Plan, A=None, B=None, At=None, Bt=None):
+    """At[P, N1/m, N0/n], Bt[P, N0/n, Nc/d] (allocated here if not given)."""
+    import torch
+    lib = load_library()
+    dt = torch.float32 if plan.worker_dtype == GPD_F32 else torch.bfloat16
+    lda = ldb = 0
+    if A is not None:
+        _require_f32_cuda(A, "A")
+        if A.dim() != 2 or A.shape != (plan.N1, plan.N0) or A.stride(1) != 1:
+            raise ValueError("A must be N1 x N0 with unit column stride")
+        lda = A.stride(0)
+        if At is None:
+            At = torch.empty((plan.P, plan.N1 // plan.m, plan.N0 // plan.n), dtype=dt, device=A.device)
+    if B is not None:
+        _require_f32_cuda(B, "B")
+        if B.dim() != 2 or B.shape != (plan.N0, plan.Nc) or B.stride(1) != 1:
+            raise ValueError("B must be N0 x Nc with unit column stride")
+        ldb = B.stride(0)
+        if Bt is None:
+            Bt = torch.empty((plan.P, plan.N0 // plan.n, plan.Nc // plan.d), dtype=dt, device=B.device)
+    for t in (At, Bt):
+        if t is not None and (not t.is_contiguous() or t.dtype != dt):
+            raise ValueError("coded stacks must be contiguous and of the worker dtype")
+    _check(lib.gpd_encode(plan.handle, _ptr(A), lda, _ptr(B), ldb,
+                          _ptr(At) if A is not None else None, _ptr(Bt) if B is not None else None))
+    return At, Bt
+
+
+def gpd_worker_products(plan: Plan, At, Bt, Ct=None):
+    import torch
+    lib = load_library()
+    dt = torch.float32 if plan.worker_dtype == GPD_F32 else torch.bfloat16
+    shA = (plan.P, plan.N1 // plan.m, plan.N0 // plan.n)
+    shB = (plan.P, plan.N0 // plan.n, plan.Nc // plan.d)
+    if tuple(At.shape) != shA or tuple(Bt.shape) != shB or At.dtype != dt or Bt.dtype != dt \
+            or not At.is_contiguous() or not Bt.is_contiguous():
+        raise ValueError("At/Bt do not match the plan")
+    if Ct is None:
+        Ct = torch.empty((plan.P, shA[1], shB[2]), dtype=torch.float32, device=At.device)
+    elif tuple(Ct.shape) != (plan.P, shA[1], shB[2]) or Ct.dtype != torch.float32 or not Ct.is_contiguous():
+        raise ValueError("Ct does not match the plan")
+    _check(lib.gpd_worker_products(plan.handle, _ptr(At), _ptr(Bt), _ptr(Ct)))
+    return Ct
+
+
+def gpd_decode(plan: Plan, Ct, present=None, mode=GPD_DEC_FIRST_K, correct_errors=False, C_out=None,
+               workspace=None, want_report=True, located_cap=4096, raise_on_fail=False):
+    """Returns (C, Report or None)."""
+    import torch
+    lib = load_library()
+    _require_f32_cuda(Ct, "Ct")
+    sh = (plan.P, plan.N1 // plan.m, plan.Nc // plan.d)
+    if tuple(Ct.shape) != sh or not Ct.is_contiguous():
+        raise ValueError("Ct does not match the plan")
+    if C_out is None:
+        C_out = torch.empty((plan.N1, plan.Nc), dtype=torch.float32, device=Ct.device)
+    elif tuple(C_out.shape) != (plan.N1, plan.Nc) or C_out.stride(1) != 1 or C_out.dtype != torch.float32:
+        raise ValueError("C_out does not match the plan")
+    pres = _present_array(present, plan.P)
+    ws_ptr, ws_bytes = None, 0
+    if correct_errors:
+        if workspace is None:
+            workspace = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device=Ct.device)
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    rep = buf = None
+    if want_report:
+        rep, buf = _make_report(located_cap)
+    st = lib.gpd_decode(plan.handle, _ptr(Ct), _ptr(pres), mode, int(bool(correct_errors)),
+                        _ptr(C_out), C_out.stride(0), ws_ptr, ws_bytes,
+                        C.byref(rep) if rep is not None else None)
+    _check(st, ok=(GPD_OK,) if raise_on_fail else (GPD_OK, GPD_E_DECODE_FAIL))
+    return C_out, (_read_report(rep, buf, plan.P) if rep is not None else None)
+
+
+# ------------------------------------------------------------------ coded DNN layer
+
+
+class Layer:
+    """Owns a gpd_layer_t*."""
+
+    def __init__(self, handle, desc: _LayerDesc, keep):
+        self.handle, self.desc, self._keep = handle, desc, keep
+        lib = load_library()
+        kf, kb, r, c, ws = C.c_int32(), C.c_int32(), C.c_int64(), C.c_int64(), C.c_size_t()
+        _check(lib.gpd_layer_info(handle, C.byref(kf), C.byref(kb), C.byref(r), C.byref(c), C.byref(ws)))
+        self.Kf, self.Kb, self.wt_rows, self.wt_cols, self.workspace_bytes = \
+            kf.value, kb.value, r.value, c.value, ws.value
+        self.N_out, self.N_in, self.batch, self.P = desc.N_out, desc.N_in, desc.batch, desc.P
+        self._ws = None
+
+    def workspace(self, device):
+        import torch
+        if self._ws is None:
+            self._ws = torch.empty(max(self.workspace_bytes, 256), dtype=torch.uint8, device=device)
+        return self._ws
+
+    def close(self):
+        if self.handle:
+            load_library().gpd_layer_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def gpd_layer_create(N_out, N_in, batch, m, n, d1, d2, P, points=None, worker_dtype=GPD_F32,
+                     subst=GPD_SUB_AUTO, rho_detect=0.0, abs_floor=0.0, stream=None) -> Layer:
+    lib = load_library()
+    d = _LayerDesc()
+    d.N_out, d.N_in, d.batch, d.m, d.n, d.d1, d.d2, d.P = N_out, N_in, batch, m, n, d1, d2, P
+    keep = None
+    if points is not None:
+        keep = np.ascontiguousarray(np.asarray(points, dtype=np.float64))
+        d.points = keep.ctypes.data_as(C.POINTER(C.c_double))
+    d.worker_dtype, d.subst, d.rho_detect, d.abs_floor = worker_dtype, subst, rho_detect, abs_floor
+    d.hip_stream = _stream_handle(stream)
+    h = C.c_void_p()
+    _check(lib.gpd_layer_create(C.byref(d), C.byref(h)))
+    return Layer(h, d, keep)
+
+
+def gpd_layer_encode_weights(layer: Layer, W, Wt=None):
+    import torch
+    _require_f32_cuda(W, "W")
+    if tuple(W.shape) != (layer.N_out, layer.N_in) or W.stride(1) != 1:
+        raise ValueError("W must be N_out x N_in")
+    if Wt is None:
+        Wt = torch.empty((layer.P, layer.wt_rows, layer.wt_cols), dtype=torch.float32, device=W.device)
+    _check(load_library().gpd_layer_encode_weights(layer.handle, _ptr(W), W.stride(0), _ptr(Wt)))
+    return Wt
+
+
+def gpd_layer_decode_weights(layer: Layer, Wt, present=None, W=None):
+    import torch
+    _require_f32_cuda(Wt, "Wt")
+    if W is None:
+        W = torch.empty((layer.N_out, layer.N_in), dtype=torch.float32, device=Wt.device)
+    pres = _present_array(present, layer.P)
+    _check(load_library().gpd_layer_decode_weights(layer.handle, _ptr(Wt), _ptr(pres), _ptr(W), W.stride(0)))
+    return W
+
+
+def gpd_coded_layer_step(layer: Layer, phase, Wt, X, Dlt=None, eta=0.0, decay=0.0, out=None,
+                         present=None, correct_errors=False, want_report=False, located_cap=4096,
+                         skip_output=False):
+    """FORWARD: returns (S, report); BACKWARD_UPDATE: returns (C or None, report); Wt updated in place."""
+    import torch
+    lib = load_library()
+    _require_f32_cuda(Wt, "Wt")
+    _require_f32_cuda(X, "X")
+    if tuple(Wt.shape) != (layer.P, layer.wt_rows, layer.wt_cols) or not Wt.is_contiguous():
+        raise ValueError("Wt does not match the layer")
+    if tuple(X.shape) != (layer.N_in, layer.batch) or not X.is_contiguous():
+        raise ValueError("X must be contiguous N_in x batch")
+    if phase == GPD_STEP_BACKWARD_UPDATE:
+        _require_f32_cuda(Dlt, "Dlt")
+        if tuple(Dlt.shape) != (layer.N_out, layer.batch) or not Dlt.is_contiguous():
+            raise ValueError("Dlt must be contiguous N_out x batch")
+    rows = layer.N_out if phase == GPD_STEP_FORWARD else layer.N_in
+    if out is None and not skip_output:
+        out = torch.empty((rows, layer.batch), dtype=torch.float32, device=X.device)
+    if out is not None and (tuple(out.shape) != (rows, layer.batch) or not out.is_contiguous()):
+        raise ValueError("out has the wrong shape")
+    ws = layer.workspace(X.device)
+    pres = _present_array(present, layer.P)
+    rep = buf = None
+    if want_report:
+        rep, buf = _make_report(located_cap)
+    st = lib.gpd_coded_layer_step(layer.handle, phase, _ptr(Wt), _ptr(X), _ptr(Dlt), eta, decay,
+                                  _ptr(out), _ptr(pres), int(bool(correct_errors)),
+                                  ws.data_ptr(), ws.numel(), C.byref(rep) if rep is not None else None)
+    _check(st, ok=(GPD_OK, GPD_E_DECODE_FAIL))
+    return out, (_read_report(rep, buf, layer.P) if rep is not None else None)
+
+
+def gpd_sigmoid_fwd(s, y=None, stream=None):
+    import torch
+    y = torch.empty_like(s) if y is None else y
+    _check(load_library().gpd_sigmoid_fwd(_ptr(s), _ptr(y), s.numel(), _stream_handle(stream)))
+    return y
+
+
+def gpd_sigmoid_bwd(c, y, out=None, stream=None):
+    import torch
+    out = torch.empty_like(c) if out is None else out
+    _check(load_library().gpd_sigmoid_bwd(_ptr(c), _ptr(y), _ptr(out), c.numel(), _stream_handle(stream)))
+    return out
+
+
+def gpd_l2_delta(y, yhat, scale, out=None, stream=None):
+    import torch
+    out = torch.empty_like(yhat) if out is None else out
+    _check(load_library().gpd_l2_delta(_ptr(y), _ptr(yhat), scale, _ptr(out), yhat.numel(),
+                                       _stream_handle(stream)))
+    return out
+
+
+def gpd_host_code(m, n, d, P, subst=GPD_SUB_AUTO, points=None):
+    """(K, eA[m,n], eB[n,d], eC[m,d], points[P]) from the library's host code; no GPU needed."""
+    lib = load_library()
+    K = C.c_int32()
+    eA = np.zeros(m * n, dtype=np.int32)
+    eB = np.zeros(n * d, dtype=np.int32)
+    eC = np.zeros(m * d, dtype=np.int32)
+    pts = np.zeros(P)
+    pin = None if points is None else np.ascontiguousarray(np.asarray(points, dtype=np.float64))
+    _check(lib.gpd_host_code(m, n, d, P, subst, _ptr(pin), C.byref(K), eA.ctypes.data, eB.ctypes.data,
+                             eC.ctypes.data, pts.ctypes.data))
+    return K.value, eA.reshape(m, n), eB.reshape(n, d), eC.reshape(m, d), pts
+
+
+def gpd_host_decode_matrices(m, n, d, P, subst=GPD_SUB_AUTO, points=None, present=None, first_k=False,
+                             want_H=True):
+    """(D[m*d, n_present], H[n_present-K, n_present] or None); no GPU needed."""
+    lib = load_library()
+    K = gpd_host_code(m, n, d, P, subst, points)[0]
+    pres = _present_array(present, P)
+    ns = P if pres is None else int(np.count_nonzero(pres))
+    if ns < K:
+        raise GpdError(GPD_E_TOO_FEW, "too few responses")
+    D = np.zeros((m * d, ns))
+    H = np.zeros((ns - K, ns)) if want_H else None
+    pin = None if points is None else np.ascontiguousarray(np.asarray(points, dtype=np.float64))
+    nsv = C.c_int32()
+    _check(lib.gpd_host_decode_matrices(m, n, d, P, subst, _ptr(pin), _ptr(pres), int(first_k),
+                                        D.ctypes.data, _ptr(H), C.byref(nsv)))
+    return D, H
+
+
+def gpd_version() -> str:
+    return load_library().gpd_version().decode()

@@ -1,0 +1,391 @@
+// C ABI of the coded matrix multiplication: gpd_plan / gpd_encode / gpd_worker_products /
+// gpd_decode.  Host-side bookkeeping only; every step of the path runs in the kernels of
+// gpd_combine.hip, gpd_gemm.hip and gpd_locate.hip.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "gpd_internal.hpp"
+
+namespace gpd {
+
+// ---------------------------------------------------------------- table ring
+
+gpd_status_t TableRing::init(size_t bytes_per_slot) {
+  slot_bytes = (bytes_per_slot + 255) / 256 * 256;
+  GPD_HIP(hipHostMalloc((void**)&host, slot_bytes * kSlots, hipHostMallocDefault));
+  GPD_HIP(hipMalloc((void**)&dev, slot_bytes * kSlots));
+  for (int i = 0; i < kSlots; ++i) GPD_HIP(hipEventCreateWithFlags(&ev[i], hipEventDisableTiming));
+  return GPD_OK;
+}
+
+void TableRing::destroy() {
+  for (int i = 0; i < kSlots; ++i)
+    if (ev[i]) { (void)hipEventDestroy(ev[i]); ev[i] = nullptr; }
+  if (host) { (void)hipHostFree(host); host = nullptr; }
+  if (dev) { (void)hipFree(dev); dev = nullptr; }
+}
+
+gpd_status_t TableRing::upload(const HostCombineTable& t, hipStream_t stream, CombineTable* out) {
+  const size_t need = t.bytes();
+  if (need > slot_bytes) return fail(GPD_E_INVALID, "table of %zu bytes exceeds slot of %zu", need, slot_bytes);
+  const int s = next;
+  next = (next + 1) % kSlots;
+  if (used[s]) GPD_HIP(hipEventSynchronize(ev[s]));     // the copy that last used this slot is done
+  char* h = host + (size_t)s * slot_bytes;
+  char* d = dev + (size_t)s * slot_bytes;
+  *out = t.pack(h, d);
+  GPD_HIP(hipMemcpyAsync(d, h, need, hipMemcpyHostToDevice, stream));
+  GPD_HIP(hipEventRecord(ev[s], stream));
+  used[s] = true;
+  return GPD_OK;
+}
+
+static size_t max_table_bytes(int nin, int nout, int r) {
+  HostCombineTable t;
+  t.nin = nin; t.nout = nout; t.r = r;
+  return t.bytes();
+}
+
+}  // namespace gpd
+
+using namespace gpd;
+
+// ---------------------------------------------------------------- plan object
+
+struct gpd_plan {
+  gpd_problem_t prob;
+  Code code;
+  hipStream_t stream = nullptr;
+  int64_t ahA = 0, awA = 0;     // block of A: (N1/m) x (N0/n)
+  int64_t ahB = 0, awB = 0;     // block of B: (N0/n) x (Nc/d)
+  int64_t ahC = 0, awC = 0;     // block of C: (N1/m) x (Nc/d)
+  double rho = 0, abs_floor = 0;
+  // static tables (device): encode A and encode B for the caller's leading dimensions are
+  // built per call because in_off depends on lda/ldb; the coefficient part is fixed.
+  TableRing ring;
+  int64_t flag_cap = 0, loc_cap = 0;
+  size_t workspace_bytes = 0;
+};
+
+namespace gpd {
+
+constexpr size_t kHeaderBytes = 512;        // counters[64] + node_err[64]
+
+void decode_workspace_layout(int64_t n_codewords, int64_t* flag_cap, int64_t* loc_cap, size_t* bytes) {
+  int64_t cap = std::min<int64_t>(n_codewords, 1 << 18);
+  if (cap < 1) cap = 1;
+  *flag_cap = cap;
+  *loc_cap = cap * 8;
+  size_t b = kHeaderBytes;
+  b += ((size_t)cap * 4 + 255) / 256 * 256;
+  b += (size_t)(*loc_cap) * sizeof(gpd_located_t);
+  *bytes = (b + 255) / 256 * 256;
+}
+
+}  // namespace gpd
+
+extern "C" gpd_status_t gpd_plan(const gpd_problem_t* pr, gpd_plan_t** out) {
+  if (!pr || !out) return fail(GPD_E_INVALID, "gpd_plan: null argument");
+  *out = nullptr;
+  if (pr->N1 < 0 || pr->N0 < 0 || pr->Nc < 0) return fail(GPD_E_INVALID, "negative matrix size");
+  if (pr->worker_dtype != GPD_F32 && pr->worker_dtype != GPD_BF16)
+    return fail(GPD_E_INVALID, "unknown worker dtype %d", pr->worker_dtype);
+  if (pr->subst < GPD_SUB_AUTO || pr->subst > GPD_SUB_V_UM)
+    return fail(GPD_E_INVALID, "unknown substitution %d", pr->subst);
+  if (!(pr->rho_detect >= 0.0) || !(pr->abs_floor >= 0.0) || !std::isfinite(pr->rho_detect) ||
+      !std::isfinite(pr->abs_floor))
+    return fail(GPD_E_INVALID, "rho_detect and abs_floor must be finite and >= 0");
+  gpd_plan_t* pl = new (std::nothrow) gpd_plan_t();
+  if (!pl) return fail(GPD_E_DEVICE, "out of host memory");
+  pl->prob = *pr;
+  pl->prob.points = nullptr;
+  gpd_status_t st = make_code(pr->m, pr->n, pr->d, pr->P, pr->subst, pr->points, &pl->code);
+  if (st != GPD_OK) { delete pl; return st; }
+  if (pr->N1 % pr->m || pr->N0 % pr->n || pr->Nc % pr->d) {
+    delete pl;
+    return fail(GPD_E_SHAPE, "m, n, d must divide N1, N0, Nc (%lld %lld %lld by %d %d %d)",
+                (long long)pr->N1, (long long)pr->N0, (long long)pr->Nc, pr->m, pr->n, pr->d);
+  }
+  pl->stream = (hipStream_t)pr->hip_stream;
+  pl->ahA = pr->N1 / pr->m; pl->awA = pr->N0 / pr->n;
+  pl->ahB = pr->N0 / pr->n; pl->awB = pr->Nc / pr->d;
+  pl->ahC = pr->N1 / pr->m; pl->awC = pr->Nc / pr->d;
+  pl->rho = pr->rho_detect > 0 ? pr->rho_detect
+                               : (pr->worker_dtype == GPD_BF16 ? 0.125 : 1.0 / 4096.0);
+  pl->abs_floor = pr->abs_floor;
+  decode_workspace_layout(pl->ahC * pl->awC, &pl->flag_cap, &pl->loc_cap, &pl->workspace_bytes);
+
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) {
+    delete pl;
+    return fail(GPD_E_DEVICE, "no HIP device");
+  }
+  const int mn = pr->m * pr->n, nd = pr->n * pr->d, md = pr->m * pr->d;
+  size_t slot = max_table_bytes(mn, pr->P, 0);
+  slot = std::max(slot, max_table_bytes(nd, pr->P, 0));
+  slot = std::max(slot, max_table_bytes(pr->P, md, pr->P));
+  st = pl->ring.init(slot);
+  if (st != GPD_OK) { pl->ring.destroy(); delete pl; return st; }
+  *out = pl;
+  return GPD_OK;
+}
+
+extern "C" gpd_status_t gpd_plan_info(const gpd_plan_t* pl, int32_t* K, int32_t* t_max,
+                                      size_t* workspace_bytes) {
+  if (!pl) return fail(GPD_E_INVALID, "gpd_plan_info: null plan");
+  if (K) *K = pl->code.K;
+  if (t_max) *t_max = std::max(0, pl->code.P - pl->code.K - 1);
+  if (workspace_bytes) *workspace_bytes = pl->workspace_bytes;
+  return GPD_OK;
+}
+
+extern "C" gpd_status_t gpd_plan_tables(const gpd_plan_t* pl, double* points, int32_t* eA,
+                                        int32_t* eB, int32_t* eC) {
+  if (!pl) return fail(GPD_E_INVALID, "gpd_plan_tables: null plan");
+  const Code& c = pl->code;
+  if (points) std::copy(c.pts.begin(), c.pts.end(), points);
+  if (eA) std::copy(c.eA.begin(), c.eA.end(), eA);
+  if (eB) std::copy(c.eB.begin(), c.eB.end(), eB);
+  if (eC) std::copy(c.eC.begin(), c.eC.end(), eC);
+  return GPD_OK;
+}
+
+extern "C" void gpd_plan_destroy(gpd_plan_t* pl) {
+  if (!pl) return;
+  pl->ring.destroy();
+  delete pl;
+}
+
+// ---------------------------------------------------------------- encode
+
+namespace gpd {
+
+// Table that evaluates sum_blocks b_p^e(block) * block for every node p.
+//   grid_r x grid_c blocks of bh x bw inside a matrix with leading dimension ld;
+//   exps[grid_r*grid_c]; output stack [P][bh][bw].
+HostCombineTable encode_table(const std::vector<double>& pts, const std::vector<int>& exps,
+                              int grid_r, int grid_c, int64_t bh, int64_t bw, int64_t ld) {
+  HostCombineTable t;
+  const int P = (int)pts.size();
+  t.nin = grid_r * grid_c; t.nout = P; t.r = 0;
+  t.in_off.resize(t.nin); t.out_off.resize(P); t.coef.resize((size_t)P * t.nin);
+  t.node.assign(t.nin, 0);
+  for (int i = 0; i < grid_r; ++i)
+    for (int j = 0; j < grid_c; ++j) t.in_off[i * grid_c + j] = (int64_t)i * bh * ld + (int64_t)j * bw;
+  for (int p = 0; p < P; ++p) {
+    t.out_off[p] = (int64_t)p * bh * bw;
+    for (int s = 0; s < t.nin; ++s) t.coef[(size_t)p * t.nin + s] = ipow(pts[p], exps[s]);
+  }
+  return t;
+}
+
+// Table that decodes the useful coefficients from the present nodes.
+//   inputs: stack [P][bh][bw]; outputs: grid_r x grid_c blocks in a matrix with leading
+//   dimension ld, block q <-> exponent useful[q].
+gpd_status_t decode_table(const std::vector<double>& pts, int K, const uint8_t* present,
+                          bool first_k, bool with_H, const std::vector<int>& useful, int grid_r,
+                          int grid_c, int64_t bh, int64_t bw, int64_t ld, HostCombineTable* t,
+                          int* n_present) {
+  const int P = (int)pts.size();
+  std::vector<int> S;
+  for (int p = 0; p < P; ++p)
+    if (!present || present[p]) S.push_back(p);
+  if (n_present) *n_present = (int)S.size();
+  std::vector<double> D, H;
+  gpd_status_t st = decode_matrices(pts, S, K, useful, first_k, &D, with_H ? &H : nullptr);
+  if (st != GPD_OK) return st;
+  const int ns = (int)S.size();
+  // nodes whose column of D is zero everywhere need not be read unless the screen needs them
+  std::vector<int> keep;
+  for (int s = 0; s < ns; ++s) {
+    bool nz = with_H;
+    for (size_t u = 0; u < useful.size() && !nz; ++u) nz = D[u * ns + s] != 0.0;
+    if (nz) keep.push_back(s);
+  }
+  t->nin = (int)keep.size(); t->nout = (int)useful.size(); t->r = with_H ? ns - K : 0;
+  t->in_off.resize(t->nin); t->node.resize(t->nin);
+  t->out_off.resize(t->nout);
+  t->coef.resize((size_t)t->nout * t->nin);
+  t->H.resize((size_t)t->r * t->nin);
+  for (int c = 0; c < t->nin; ++c) {
+    t->node[c] = S[keep[c]];
+    t->in_off[c] = (int64_t)S[keep[c]] * bh * bw;
+    for (int u = 0; u < t->nout; ++u) t->coef[(size_t)u * t->nin + c] = D[(size_t)u * ns + keep[c]];
+    for (int i = 0; i < t->r; ++i) t->H[(size_t)i * t->nin + c] = H[(size_t)i * ns + keep[c]];
+  }
+  for (int i = 0; i < grid_r; ++i)
+    for (int j = 0; j < grid_c; ++j) t->out_off[i * grid_c + j] = (int64_t)i * bh * ld + (int64_t)j * bw;
+  return GPD_OK;
+}
+
+}  // namespace gpd
+
+extern "C" gpd_status_t gpd_encode(const gpd_plan_t* plc, const float* A, int64_t lda,
+                                   const float* B, int64_t ldb, void* At, void* Bt) {
+  gpd_plan_t* pl = const_cast<gpd_plan_t*>(plc);
+  if (!pl) return fail(GPD_E_INVALID, "gpd_encode: null plan");
+  if ((A == nullptr) != (At == nullptr) || (B == nullptr) != (Bt == nullptr))
+    return fail(GPD_E_INVALID, "gpd_encode: A/At and B/Bt must be given in pairs");
+  const Code& c = pl->code;
+  const bool bf16 = pl->prob.worker_dtype == GPD_BF16;
+  ScreenArgs none;
+  if (A) {
+    if (lda < pl->prob.N0) return fail(GPD_E_SHAPE, "lda smaller than N0");
+    HostCombineTable ht = encode_table(c.pts, c.eA, c.m, c.n, pl->ahA, pl->awA, lda);
+    CombineTable t;
+    gpd_status_t st = pl->ring.upload(ht, pl->stream, &t);
+    if (st != GPD_OK) return st;
+    st = launch_combine(pl->stream, t, A, lda, At, pl->awA, bf16, pl->ahA, pl->awA, none);
+    if (st != GPD_OK) return st;
+  }
+  if (B) {
+    if (ldb < pl->prob.Nc) return fail(GPD_E_SHAPE, "ldb smaller than Nc");
+    HostCombineTable ht = encode_table(c.pts, c.eB, c.n, c.d, pl->ahB, pl->awB, ldb);
+    CombineTable t;
+    gpd_status_t st = pl->ring.upload(ht, pl->stream, &t);
+    if (st != GPD_OK) return st;
+    st = launch_combine(pl->stream, t, B, ldb, Bt, pl->awB, bf16, pl->ahB, pl->awB, none);
+    if (st != GPD_OK) return st;
+  }
+  return GPD_OK;
+}
+
+// ---------------------------------------------------------------- worker products
+
+extern "C" gpd_status_t gpd_worker_products(const gpd_plan_t* pl, const void* At, const void* Bt,
+                                            float* Ct) {
+  if (!pl || !At || !Bt || !Ct) return fail(GPD_E_INVALID, "gpd_worker_products: null argument");
+  GemmArgs g;
+  g.A = At; g.B = Bt; g.C = Ct;
+  g.M = pl->ahA; g.K = pl->awA; g.N = pl->awB;
+  g.lda = pl->awA; g.ldb = pl->awB; g.ldc = pl->awC;
+  g.strideA = pl->ahA * pl->awA; g.strideB = pl->ahB * pl->awB; g.strideC = pl->ahC * pl->awC;
+  g.batch = pl->code.P;
+  const bool bf16 = pl->prob.worker_dtype == GPD_BF16;
+  g.a_bf16 = g.b_bf16 = g.mfma_bf16 = bf16;
+  return launch_gemm(pl->stream, g);
+}
+
+// ---------------------------------------------------------------- decode
+
+namespace gpd {
+
+gpd_status_t run_decode(hipStream_t stream, TableRing* ring, const DecodeJob& job, const float* Zt,
+                        const uint8_t* present, int mode, int correct, float* out, int64_t ld_out,
+                        void* workspace, size_t workspace_bytes, gpd_report_t* report) {
+  if (!Zt || !out) return fail(GPD_E_INVALID, "decode: null buffer");
+  if (mode != GPD_DEC_FIRST_K && mode != GPD_DEC_LSQ_ALL) return fail(GPD_E_INVALID, "decode: bad mode");
+  if (ld_out < job.grid_c * job.bw) return fail(GPD_E_SHAPE, "decode: output leading dimension too small");
+  const bool corr = correct != 0;
+  if (corr) {
+    if (!workspace || workspace_bytes < job.workspace_bytes || ((uintptr_t)workspace & 255))
+      return fail(GPD_E_WORKSPACE, "decode: workspace of %zu aligned bytes needed", job.workspace_bytes);
+  }
+  HostCombineTable ht;
+  int n_present = 0;
+  gpd_status_t st = decode_table(*job.pts, job.K, present, !corr && mode == GPD_DEC_FIRST_K, corr,
+                                 job.useful, job.grid_r, job.grid_c, job.bh, job.bw, ld_out, &ht,
+                                 &n_present);
+  if (report) {
+    gpd_located_t* keep_ptr = report->located;
+    const int64_t keep_cap = report->located_cap;
+    std::memset(report, 0, sizeof(*report));
+    report->located = keep_ptr; report->located_cap = keep_cap;
+    report->n_present = n_present;
+    report->status = st;
+  }
+  if (st != GPD_OK) return st;
+  ht.out_rows = job.out_rows; ht.out_cols = job.out_cols;
+  CombineTable t;
+  st = ring->upload(ht, stream, &t);
+  if (st != GPD_OK) return st;
+
+  ScreenArgs sc;
+  char* ws = (char*)workspace;
+  uint32_t* counters = nullptr;
+  int32_t* node_err = nullptr;
+  int32_t* list = nullptr;
+  gpd_located_t* located = nullptr;
+  if (corr) {
+    counters = (uint32_t*)ws;
+    node_err = (int32_t*)(ws + 256);
+    list = (int32_t*)(ws + kHeaderBytes);
+    located = (gpd_located_t*)(ws + kHeaderBytes + ((size_t)job.flag_cap * 4 + 255) / 256 * 256);
+    st = launch_zero_words(stream, ws, (int)(kHeaderBytes / 4));
+    if (st != GPD_OK) return st;
+    sc.enabled = true; sc.rho = (float)job.rho; sc.abs_floor = (float)job.abs_floor;
+    sc.counters = counters; sc.list = list; sc.cap = (int32_t)job.flag_cap;
+  }
+  st = launch_combine(stream, t, Zt, job.bw, out, ld_out, false, job.bh, job.bw, sc);
+  if (st != GPD_OK) return st;
+  if (corr) {
+    LocateArgs la;
+    la.t = t; la.in = Zt; la.in_ld = job.bw; la.out = out; la.out_ld = ld_out;
+    la.rows = job.bh; la.cols = job.bw; la.rho = job.rho; la.abs_floor = job.abs_floor;
+    la.counters = counters; la.list = list; la.n_list = (int32_t)job.flag_cap;
+    la.located = located; la.located_cap = job.loc_cap; la.node_err = node_err;
+    st = launch_locate(stream, la);
+    if (st != GPD_OK) return st;
+  }
+  if (!report) return GPD_OK;
+
+  GPD_HIP(hipStreamSynchronize(stream));
+  if (corr) {
+    uint32_t hc[64];
+    int32_t hn[64];
+    GPD_HIP(hipMemcpy(hc, counters, sizeof(hc), hipMemcpyDeviceToHost));
+    GPD_HIP(hipMemcpy(hn, node_err, sizeof(hn), hipMemcpyDeviceToHost));
+    report->n_screened = hc[0];
+    report->n_flagged = hc[2];
+    report->n_failed = hc[3];
+    report->n_located = hc[4];
+    float ratio;
+    std::memcpy(&ratio, &hc[1], 4);
+    report->max_syndrome_ratio = ratio;
+    for (int p = 0; p < GPD_MAX_P; ++p) report->node_err_count[p] = hn[p];
+    if ((int64_t)hc[0] > job.flag_cap) {
+      report->status = GPD_E_WORKSPACE;
+      return fail(GPD_E_WORKSPACE, "decode: %u codewords screened, list holds %lld", hc[0],
+                  (long long)job.flag_cap);
+    }
+    const int64_t have = std::min<int64_t>(hc[4], job.loc_cap);
+    if (have > 0) {
+      std::vector<gpd_located_t> tmp((size_t)have);
+      GPD_HIP(hipMemcpy(tmp.data(), located, sizeof(gpd_located_t) * have, hipMemcpyDeviceToHost));
+      std::sort(tmp.begin(), tmp.end(), [](const gpd_located_t& a, const gpd_located_t& b) {
+        if (a.node != b.node) return a.node < b.node;
+        if (a.row != b.row) return a.row < b.row;
+        return a.col < b.col;
+      });
+      if (report->located && report->located_cap > 0) {
+        const int64_t n = std::min<int64_t>(have, report->located_cap);
+        std::memcpy(report->located, tmp.data(), sizeof(gpd_located_t) * n);
+      }
+    }
+    if (hc[3] > 0) {
+      report->status = GPD_E_DECODE_FAIL;
+      return fail(GPD_E_DECODE_FAIL, "decoding failure on %u codewords", hc[3]);
+    }
+  }
+  report->status = GPD_OK;
+  return GPD_OK;
+}
+
+}  // namespace gpd
+
+extern "C" gpd_status_t gpd_decode(const gpd_plan_t* plc, const float* Ct, const uint8_t* present,
+                                   int32_t mode, int32_t correct_errors, float* C, int64_t ldc,
+                                   void* workspace, size_t workspace_bytes, gpd_report_t* report) {
+  gpd_plan_t* pl = const_cast<gpd_plan_t*>(plc);
+  if (!pl) return fail(GPD_E_INVALID, "gpd_decode: null plan");
+  DecodeJob job;
+  job.pts = &pl->code.pts; job.K = pl->code.K; job.useful = pl->code.eC;
+  job.grid_r = pl->code.m; job.grid_c = pl->code.d;
+  job.bh = pl->ahC; job.bw = pl->awC;
+  job.rho = pl->rho; job.abs_floor = pl->abs_floor;
+  job.flag_cap = pl->flag_cap; job.loc_cap = pl->loc_cap; job.workspace_bytes = pl->workspace_bytes;
+  return run_decode(pl->stream, &pl->ring, job, Ct, present, mode, correct_errors, C, ldc,
+                    workspace, workspace_bytes, report);
+}

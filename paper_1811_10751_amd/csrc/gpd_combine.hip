@@ -1,0 +1,264 @@
+// Streaming "linear combination of blocks" kernel: the encode step (Sec. IV, equations for
+// W~(u,v) and X~(v,w)), the erasure decode (remark after Thm 2) and, fused into the decode
+// pass, the fp32 soft-error screen (Sec. V Algorithm 1 step 1; appendix "Decoding Methods").
+//
+//   out_q[r][c] = sum_s coef[q][s] * in_s[r][c]        q < nout, s < nin
+//
+// HBM-bound: every input element is read once, every output element written once.  Each
+// thread owns VEC consecutive columns of one row, holds the nin input values in registers
+// and produces the nout outputs one after the other; the coefficient table is read with
+// wave-uniform addresses (scalar loads), so no LDS is needed.
+#include "gpd_internal.hpp"
+
+namespace gpd {
+
+namespace {
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);   // quiet NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+template <int VEC> struct VecT;
+template <> struct VecT<4> { using f = float4; };
+template <> struct VecT<2> { using f = float2; };
+template <> struct VecT<1> { using f = float; };
+
+template <int VEC>
+__device__ __forceinline__ void load_vec(const float* p, float (&v)[VEC]) {
+  if constexpr (VEC == 4) {
+    float4 t = *reinterpret_cast<const float4*>(p);
+    v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+  } else if constexpr (VEC == 2) {
+    float2 t = *reinterpret_cast<const float2*>(p);
+    v[0] = t.x; v[1] = t.y;
+  } else {
+    v[0] = *p;
+  }
+}
+
+template <int VEC>
+__device__ __forceinline__ void store_vec(float* p, const float (&v)[VEC]) {
+  if constexpr (VEC == 4) {
+    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+  } else if constexpr (VEC == 2) {
+    *reinterpret_cast<float2*>(p) = make_float2(v[0], v[1]);
+  } else {
+    *p = v[0];
+  }
+}
+
+template <int VEC>
+__device__ __forceinline__ void store_vec_bf16(uint16_t* p, const float (&v)[VEC]) {
+  if constexpr (VEC == 4) {
+    uint2 t;
+    t.x = (uint32_t)f32_to_bf16_rne(v[0]) | ((uint32_t)f32_to_bf16_rne(v[1]) << 16);
+    t.y = (uint32_t)f32_to_bf16_rne(v[2]) | ((uint32_t)f32_to_bf16_rne(v[3]) << 16);
+    *reinterpret_cast<uint2*>(p) = t;
+  } else if constexpr (VEC == 2) {
+    *reinterpret_cast<uint32_t*>(p) =
+        (uint32_t)f32_to_bf16_rne(v[0]) | ((uint32_t)f32_to_bf16_rne(v[1]) << 16);
+  } else {
+    *p = f32_to_bf16_rne(v[0]);
+  }
+}
+
+struct CombineParams {
+  const float* in;
+  int64_t in_ld;
+  void* out;
+  int64_t out_ld;
+  int64_t rows, cols;        // block shape in elements
+  int64_t cols_vec;          // cols / VEC
+  int nin, nout, r;
+  const int64_t* in_off;
+  const int64_t* out_off;
+  const float* coef;         // [nout][nin]
+  const float* H;            // [r][nin]
+  const int32_t* in_rows; const int32_t* in_cols;      // block limits (LIMITS only)
+  const int32_t* out_rows; const int32_t* out_cols;
+  float rho_screen;          // flagged iff !(sigma <= rho_screen*max(|z|,floor) - margin*|z|)
+  float abs_floor;
+  float rho;                 // for the ratio statistic
+  uint32_t* counters;
+  int32_t* list;
+  int32_t cap;
+};
+
+// NIN_MAX: compile-time bound on nin (register array); VEC: columns per thread.
+template <int NIN_MAX, int VEC, bool OUT_BF16, bool SCREEN, bool LIMITS>
+__global__ __launch_bounds__(256) void combine_kernel(CombineParams p) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t total = p.rows * p.cols_vec;
+  const bool active = idx < total;
+  const int64_t row = active ? idx / p.cols_vec : 0;
+  const int64_t col = active ? (idx - row * p.cols_vec) * VEC : 0;
+
+  float z[NIN_MAX][VEC];
+#pragma unroll
+  for (int s = 0; s < NIN_MAX; ++s) {
+    bool take = s < p.nin && active;
+    if constexpr (LIMITS) take = take && row < p.in_rows[s] && col < p.in_cols[s];
+    if (take) {
+      load_vec<VEC>(p.in + p.in_off[s] + row * p.in_ld + col, z[s]);
+    } else {
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) z[s][v] = 0.f;
+    }
+  }
+
+  if constexpr (SCREEN) {
+    // Algorithm 1 step 1 in fp32, with a threshold below tau so that every codeword the
+    // fp64 check could flag is passed on; non-finite responses are replaced by zero and
+    // always passed on.
+    bool bad[VEC];
+    float nz2[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) { bad[v] = false; nz2[v] = 0.f; }
+#pragma unroll
+    for (int s = 0; s < NIN_MAX; ++s) {
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) {
+        const float x = z[s][v];
+        if (!(fabsf(x) <= 3.4028234664e38f)) { bad[v] = true; z[s][v] = 0.f; }
+        nz2[v] = fmaf(z[s][v], z[s][v], nz2[v]);
+      }
+    }
+    float sig2[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) sig2[v] = 0.f;
+    for (int i = 0; i < p.r; ++i) {
+      float y[VEC];
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) y[v] = 0.f;
+      const float* __restrict__ hrow = p.H + (int64_t)i * p.nin;
+#pragma unroll
+      for (int s = 0; s < NIN_MAX; ++s) {
+        if (s < p.nin) {
+          const float h = hrow[s];
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) y[v] = fmaf(h, z[s][v], y[v]);
+        }
+      }
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) sig2[v] = fmaf(y[v], y[v], sig2[v]);
+    }
+    float ratio = 0.f;
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) {
+      const float nz = sqrtf(nz2[v]);
+      const float sig = sqrtf(sig2[v]);
+      const float base = fmaxf(nz, p.abs_floor);
+      const float thr = fmaxf(p.rho_screen * base - 1.52587890625e-05f * nz, 0.f);
+      const bool flag = active && (bad[v] || !(sig <= thr));
+      if (flag) {
+        const uint32_t pos = atomicAdd(&p.counters[0], 1u);
+        if (pos < (uint32_t)p.cap) p.list[pos] = (int32_t)(row * p.cols + col + v);
+      } else if (active) {
+        const float tau = p.rho * base;
+        if (tau > 0.f) ratio = fmaxf(ratio, sig / tau);
+      }
+    }
+    // wave-wide maximum, one atomic per wave
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) ratio = fmaxf(ratio, __shfl_xor(ratio, off));
+    if ((threadIdx.x & 63) == 0 && ratio > 0.f) atomicMax(&p.counters[1], __float_as_uint(ratio));
+  }
+
+  if (!active) return;
+  for (int q = 0; q < p.nout; ++q) {
+    float acc[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
+    const float* __restrict__ crow = p.coef + (int64_t)q * p.nin;
+#pragma unroll
+    for (int s = 0; s < NIN_MAX; ++s) {
+      if (s < p.nin) {
+        const float c = crow[s];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc[v] = fmaf(c, z[s][v], acc[v]);
+      }
+    }
+    if constexpr (LIMITS) {
+      if (!(row < p.out_rows[q] && col < p.out_cols[q])) continue;
+    }
+    const int64_t o = p.out_off[q] + row * p.out_ld + col;
+    if constexpr (OUT_BF16) store_vec_bf16<VEC>(reinterpret_cast<uint16_t*>(p.out) + o, acc);
+    else store_vec<VEC>(reinterpret_cast<float*>(p.out) + o, acc);
+  }
+}
+
+template <int NIN_MAX, int VEC>
+gpd_status_t launch_t(hipStream_t stream, const CombineParams& p, bool out_bf16, bool screen) {
+  const int64_t total = p.rows * p.cols_vec;
+  if (total == 0) return GPD_OK;
+  const int64_t blocks = (total + 255) / 256;
+  if (blocks > 0x7fffffffLL) return fail(GPD_E_SHAPE, "block too large for one launch");
+  dim3 grid((unsigned)blocks), block(256);
+  const bool lim = p.in_rows != nullptr;
+  if (screen) {
+    if (out_bf16) return fail(GPD_E_UNSUPPORTED, "screen with bf16 output");
+    if (lim) hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, false, true, true>), grid, block, 0, stream, p);
+    else hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, false, true, false>), grid, block, 0, stream, p);
+  } else if (out_bf16) {
+    if (lim) hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, true, false, true>), grid, block, 0, stream, p);
+    else hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, true, false, false>), grid, block, 0, stream, p);
+  } else {
+    if (lim) hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, false, false, true>), grid, block, 0, stream, p);
+    else hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, false, false, false>), grid, block, 0, stream, p);
+  }
+  GPD_HIP(hipGetLastError());
+  return GPD_OK;
+}
+
+template <int VEC>
+gpd_status_t launch_v(hipStream_t stream, const CombineParams& p, bool out_bf16, bool screen) {
+  if (p.nin <= 4) return launch_t<4, VEC>(stream, p, out_bf16, screen);
+  if (p.nin <= 8) return launch_t<8, VEC>(stream, p, out_bf16, screen);
+  if (p.nin <= 16) return launch_t<16, VEC>(stream, p, out_bf16, screen);
+  if constexpr (VEC <= 2) {
+    if (p.nin <= 32) return launch_t<32, VEC>(stream, p, out_bf16, screen);
+  }
+  if constexpr (VEC == 1) {
+    if (p.nin <= 64) return launch_t<64, VEC>(stream, p, out_bf16, screen);
+  }
+  return fail(GPD_E_UNSUPPORTED, "combine: nin = %d too large for VEC = %d", p.nin, VEC);
+}
+
+}  // namespace
+
+gpd_status_t launch_combine(hipStream_t stream, const CombineTable& t, const float* in,
+                            int64_t in_ld, void* out, int64_t out_ld, bool out_bf16,
+                            int64_t rows, int64_t cols, const ScreenArgs& screen) {
+  if (t.nin < 1 || t.nin > GPD_MAX_BLOCKS || t.nout < 1)
+    return fail(GPD_E_INVALID, "combine: nin = %d, nout = %d", t.nin, t.nout);
+  if (rows * cols > 0x7fffffffLL) return fail(GPD_E_SHAPE, "block has more than 2^31 elements");
+  CombineParams p;
+  p.in = in; p.in_ld = in_ld; p.out = out; p.out_ld = out_ld;
+  p.rows = rows; p.cols = cols;
+  p.nin = t.nin; p.nout = t.nout; p.r = screen.enabled ? t.r : 0;
+  p.in_off = t.in_off; p.out_off = t.out_off; p.coef = t.coef; p.H = t.H;
+  p.in_rows = t.in_rows; p.in_cols = t.in_cols; p.out_rows = t.out_rows; p.out_cols = t.out_cols;
+  p.rho = screen.rho; p.rho_screen = 0.5f * screen.rho; p.abs_floor = screen.abs_floor;
+  p.counters = screen.counters; p.list = screen.list; p.cap = screen.cap;
+
+  // widest vector the shapes, leading dimensions, block offsets and base addresses allow
+  const size_t out_elem = out_bf16 ? 2 : 4;
+  auto ok = [&](int vec) {
+    if (cols % vec || in_ld % vec || out_ld % vec || t.off_align % vec) return false;
+    if (t.in_rows && t.limit_align % vec) return false;
+    if (((uintptr_t)in) % (4 * vec) || ((uintptr_t)out) % (out_elem * vec)) return false;
+    return true;
+  };
+  int vec = 1;
+  if (t.nin <= 16 && ok(4)) vec = 4;
+  else if (t.nin <= 32 && ok(2)) vec = 2;
+  p.cols_vec = cols / vec;
+  if (vec == 4) return launch_v<4>(stream, p, out_bf16, screen.enabled);
+  if (vec == 2) return launch_v<2>(stream, p, out_bf16, screen.enabled);
+  return launch_v<1>(stream, p, out_bf16, screen.enabled);
+}
+
+}  // namespace gpd

@@ -1,0 +1,261 @@
+// Batched dense products on the matrix cores: the P worker products C~_p = A~_p B~_p
+// (Sec. IV, proof of Thm 2), the coded forward / backward products and the rank-B coded
+// update of the DNN layer step (Sec. IX).
+//
+// fp32 path: v_mfma_f32_32x32x2_f32.  A workgroup of 4 wavefronts computes a 128 x 128
+// tile of C; each wavefront owns a 64 x 64 sub-tile = 2 x 2 MFMA blocks (64 accumulator
+// registers).  Operand tiles of 16 k-values are staged through double-buffered LDS.  The
+// order of k inside a tile is permuted so that a lane fetches its four consecutive
+// k-values of a k-contiguous operand with one 128-bit LDS read.
+#include "gpd_internal.hpp"
+
+namespace gpd {
+
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int BM = 128, BN = 128, BK = 16;
+constexpr int KC_STRIDE = BK + 4;      // row stride (floats) of a k-contiguous tile  [rows][BK]
+constexpr int MC_STRIDE = BM + 4;      // row stride of an m/n-contiguous tile        [BK][rows]
+constexpr int TILE_FLOATS = (BM * KC_STRIDE > BK * MC_STRIDE) ? BM * KC_STRIDE : BK * MC_STRIDE;
+
+struct GemmParams {
+  const float* A; const float* B; float* C;
+  int M, N, K;
+  int64_t lda, ldb, ldc;
+  int64_t sA, sB, sC;
+  int batch, tiles_m, tiles_n;
+  int total_tiles, tiles_per_xcd;
+  float alpha, beta;
+};
+
+// Loads a 128 x 16 operand tile as two float4 per thread.
+//   KCONTIG: memory is [rows][k] (ld = stride between rows): thread f -> row f/4, k 4*(f%4)
+//   else   : memory is [k][rows]:                            thread f -> k f/32, row 4*(f%32)
+// MODE 0: tile fully inside, 16-byte aligned; 1: guarded, aligned; 2: guarded, scalar.
+struct TileRegs { float4 q0, q1; };
+
+template <bool KCONTIG, int MODE>
+__device__ __forceinline__ TileRegs load_tile(const float* __restrict__ base, int64_t ld, int row0,
+                                              int k0, int nrows, int nk, int tid) {
+  float4 r[2];
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    const int f = tid + 256 * q;
+    int row, k;
+    if constexpr (KCONTIG) { row = row0 + (f >> 2); k = k0 + 4 * (f & 3); }
+    else { k = k0 + (f >> 5); row = row0 + 4 * (f & 31); }
+    if constexpr (MODE == 0) {
+      const float* p = KCONTIG ? base + (int64_t)row * ld + k : base + (int64_t)k * ld + row;
+      r[q] = *reinterpret_cast<const float4*>(p);
+    } else {
+      float v[4] = {0.f, 0.f, 0.f, 0.f};
+      if constexpr (KCONTIG) {
+        if (row < nrows) {
+          const float* p = base + (int64_t)row * ld + k;
+          if (MODE == 1 && k + 3 < nk) {
+            const float4 t = *reinterpret_cast<const float4*>(p);
+            v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) if (k + e < nk) v[e] = p[e];
+          }
+        }
+      } else {
+        if (k < nk) {
+          const float* p = base + (int64_t)k * ld + row;
+          if (MODE == 1 && row + 3 < nrows) {
+            const float4 t = *reinterpret_cast<const float4*>(p);
+            v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) if (row + e < nrows) v[e] = p[e];
+          }
+        }
+      }
+      r[q] = make_float4(v[0], v[1], v[2], v[3]);
+    }
+  }
+  TileRegs t;
+  t.q0 = r[0]; t.q1 = r[1];
+  return t;
+}
+
+template <bool KCONTIG>
+__device__ __forceinline__ void store_tile(float* __restrict__ lds, int tid, const TileRegs& t) {
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    const int f = tid + 256 * q;
+    const float4 v = q == 0 ? t.q0 : t.q1;
+    if constexpr (KCONTIG) {
+      *reinterpret_cast<float4*>(lds + (f >> 2) * KC_STRIDE + 4 * (f & 3)) = v;
+    } else {
+      *reinterpret_cast<float4*>(lds + (f >> 5) * MC_STRIDE + 4 * (f & 31)) = v;
+    }
+  }
+}
+
+// Fragment of one 32-row block for the four MFMA steps of one 8-wide k group `h`:
+// step t multiplies k = 8h + t (lanes 0-31) and k = 8h + 4 + t (lanes 32-63).
+template <bool KCONTIG>
+__device__ __forceinline__ void read_frag(const float* __restrict__ lds, int row, int h, int g,
+                                          float (&f)[4]) {
+  if constexpr (KCONTIG) {
+    const float4 t = *reinterpret_cast<const float4*>(lds + row * KC_STRIDE + 8 * h + 4 * g);
+    f[0] = t.x; f[1] = t.y; f[2] = t.z; f[3] = t.w;
+  } else {
+#pragma unroll
+    for (int t = 0; t < 4; ++t) f[t] = lds[(8 * h + 4 * g + t) * MC_STRIDE + row];
+  }
+}
+
+// A_KC: op(A) rows are k-contiguous in memory (A not transposed).
+// B_KC: op(B) columns are k-contiguous in memory (B transposed, stored N x K).
+template <bool A_KC, bool B_KC, int MODE>
+__global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams g) {
+  __shared__ __attribute__((aligned(16))) float lds[2][2][TILE_FLOATS];
+
+  // XCD-aware tile order: consecutive workgroup ids go to different XCDs (each with its own
+  // L2), so give every XCD one contiguous range of tiles.
+  const int xcd = blockIdx.x & 7;
+  const int slot = blockIdx.x >> 3;
+  const int tile = xcd * g.tiles_per_xcd + slot;
+  if (tile >= g.total_tiles) return;
+  const int per_batch = g.tiles_m * g.tiles_n;
+  const int p = tile / per_batch;
+  const int rem = tile - p * per_batch;
+  const int tm = rem / g.tiles_n;
+  const int tn = rem - tm * g.tiles_n;
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  const float* __restrict__ A = g.A + (int64_t)p * g.sA;
+  const float* __restrict__ B = g.B + (int64_t)p * g.sB;
+  float* __restrict__ C = g.C + (int64_t)p * g.sC;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 31, lg = lane >> 5;
+  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const int nchunks = (g.K + BK - 1) / BK;
+  TileRegs ra = load_tile<A_KC, MODE>(A, g.lda, m0, 0, g.M, g.K, tid);
+  TileRegs rb = load_tile<B_KC, MODE>(B, g.ldb, n0, 0, g.N, g.K, tid);
+  store_tile<A_KC>(lds[0][0], tid, ra);
+  store_tile<B_KC>(lds[0][1], tid, rb);
+  __syncthreads();
+
+  for (int c = 0; c < nchunks; ++c) {
+    const int cur = c & 1;
+    if (c + 1 < nchunks) {
+      ra = load_tile<A_KC, MODE>(A, g.lda, m0, (c + 1) * BK, g.M, g.K, tid);
+      rb = load_tile<B_KC, MODE>(B, g.ldb, n0, (c + 1) * BK, g.N, g.K, tid);
+    }
+    const float* __restrict__ as = lds[cur][0];
+    const float* __restrict__ bs = lds[cur][1];
+#pragma unroll
+    for (int h = 0; h < BK / 8; ++h) {
+      float fa[2][4], fb[2][4];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) read_frag<A_KC>(as, wm + 32 * i + li, h, lg, fa[i]);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) read_frag<B_KC>(bs, wn + 32 * j + li, h, lg, fb[j]);
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][t], fb[j][t], acc[i][j], 0, 0, 0);
+    }
+    if (c + 1 < nchunks) {
+      store_tile<A_KC>(lds[cur ^ 1][0], tid, ra);
+      store_tile<B_KC>(lds[cur ^ 1][1], tid, rb);
+    }
+    __syncthreads();
+  }
+
+  // epilogue: accumulator register v of lane (li, lg) holds row 8*(v/4) + 4*lg + v%4, column li
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int col = n0 + wn + 32 * j + li;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * lg + (v & 3);
+        if (MODE == 0 || (row < g.M && col < g.N)) {
+          float* dst = C + (int64_t)row * g.ldc + col;
+          float val = g.alpha * acc[i][j][v];
+          if (g.beta != 0.f) val = fmaf(g.beta, *dst, val);
+          *dst = val;
+        }
+      }
+    }
+}
+
+template <bool A_KC, bool B_KC>
+gpd_status_t launch_f32(hipStream_t stream, const GemmParams& p, int mode) {
+  dim3 grid((unsigned)(p.tiles_per_xcd * 8)), block(256);
+  if (mode == 0) hipLaunchKernelGGL((gemm_f32_kernel<A_KC, B_KC, 0>), grid, block, 0, stream, p);
+  else if (mode == 1) hipLaunchKernelGGL((gemm_f32_kernel<A_KC, B_KC, 1>), grid, block, 0, stream, p);
+  else hipLaunchKernelGGL((gemm_f32_kernel<A_KC, B_KC, 2>), grid, block, 0, stream, p);
+  GPD_HIP(hipGetLastError());
+  return GPD_OK;
+}
+
+}  // namespace
+
+gpd_status_t launch_gemm(hipStream_t stream, const GemmArgs& a) {
+  if (a.M < 0 || a.N < 0 || a.K < 0 || a.batch < 0) return fail(GPD_E_INVALID, "gemm: negative size");
+  if (a.M == 0 || a.N == 0 || a.batch == 0) return GPD_OK;
+  if (a.M > 0x7fffffff || a.N > 0x7fffffff || a.K > 0x7fffffff)
+    return fail(GPD_E_SHAPE, "gemm: dimension above 2^31");
+  if (a.a_bf16 || a.b_bf16 || a.mfma_bf16)
+    return fail(GPD_E_UNSUPPORTED, "gemm: bf16 path not built yet");
+  // operand shapes must match what the kernel and its grid assume
+  const int64_t a_rows = a.transA ? a.K : a.M, a_cols = a.transA ? a.M : a.K;
+  const int64_t b_rows = a.transB ? a.N : a.K, b_cols = a.transB ? a.K : a.N;
+  if (a.lda < a_cols || a.ldb < b_cols || a.ldc < a.N)
+    return fail(GPD_E_SHAPE, "gemm: leading dimension smaller than the row length");
+  if (a.batch > 1 && (a.strideA < (a_rows - 1) * a.lda + a_cols && a.strideA != 0))
+    return fail(GPD_E_SHAPE, "gemm: batch stride of A overlaps");
+  if (a.batch > 1 && (a.strideB < (b_rows - 1) * a.ldb + b_cols && a.strideB != 0))
+    return fail(GPD_E_SHAPE, "gemm: batch stride of B overlaps");
+  if (a.batch > 1 && a.strideC < (a.M - 1) * a.ldc + a.N)
+    return fail(GPD_E_SHAPE, "gemm: batch stride of C overlaps");
+
+  GemmParams p;
+  p.A = (const float*)a.A; p.B = (const float*)a.B; p.C = a.C;
+  p.M = (int)a.M; p.N = (int)a.N; p.K = (int)a.K;
+  p.lda = a.lda; p.ldb = a.ldb; p.ldc = a.ldc;
+  p.sA = a.strideA; p.sB = a.strideB; p.sC = a.strideC;
+  p.batch = a.batch;
+  p.tiles_m = (int)((a.M + BM - 1) / BM);
+  p.tiles_n = (int)((a.N + BN - 1) / BN);
+  const int64_t total = (int64_t)p.tiles_m * p.tiles_n * a.batch;
+  if (total > 0x0fffffff) return fail(GPD_E_SHAPE, "gemm: too many tiles");
+  p.total_tiles = (int)total;
+  p.tiles_per_xcd = (int)((total + 7) / 8);
+  p.alpha = a.alpha; p.beta = a.beta;
+
+  const bool aligned = ((uintptr_t)a.A % 16 == 0) && ((uintptr_t)a.B % 16 == 0) &&
+                       a.lda % 4 == 0 && a.ldb % 4 == 0 && a.strideA % 4 == 0 && a.strideB % 4 == 0;
+  const bool full = a.M % BM == 0 && a.N % BN == 0 && a.K % BK == 0 && a.K > 0;
+  const int mode = !aligned ? 2 : (full ? 0 : 1);
+  const bool a_kc = !a.transA, b_kc = a.transB;
+  if (a_kc && b_kc) return launch_f32<true, true>(stream, p, mode);
+  if (a_kc && !b_kc) return launch_f32<true, false>(stream, p, mode);
+  if (!a_kc && b_kc) return launch_f32<false, true>(stream, p, mode);
+  return launch_f32<false, false>(stream, p, mode);
+}
+
+}  // namespace gpd

@@ -1,0 +1,176 @@
+// Internal declarations shared by the translation units of libgpd (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <string>
+#include <vector>
+
+#include "gpd.h"
+
+namespace gpd {
+
+// ---------------------------------------------------------------- errors
+void set_error(const char* fmt, ...);
+gpd_status_t fail(gpd_status_t st, const char* fmt, ...);
+
+#define GPD_HIP(expr)                                                                      \
+  do {                                                                                     \
+    hipError_t e__ = (expr);                                                               \
+    if (e__ != hipSuccess)                                                                 \
+      return ::gpd::fail(GPD_E_DEVICE, "%s: %s (%s:%d)", #expr, hipGetErrorString(e__),    \
+                         __FILE__, __LINE__);                                              \
+  } while (0)
+
+// ---------------------------------------------------------------- host mathematics (gpd_host.cpp)
+
+// Exponents of one coded product after substitution (Sec. IV, Thm 2).
+struct Code {
+  int m = 0, n = 0, d = 0, P = 0;
+  int eu = 0, ev = 0, ew = 0;          // u = b^eu, v = b^ev, w = b^ew
+  int K = 0;                           // 1 + degree of the product polynomial
+  std::vector<int> eA, eB, eC;         // [m*n], [n*d], [m*d]
+  std::vector<double> pts;             // [P]
+};
+
+gpd_status_t substitution(int m, int n, int subst, int* eu, int* ev, int* ew);
+gpd_status_t make_points(int P, const double* user, std::vector<double>* out);
+gpd_status_t make_code(int m, int n, int d, int P, int subst, const double* points, Code* out);
+double ipow(double b, int e);
+
+// Decoding matrices for the present nodes `S` (indices into pts), in fp64:
+//   D [useful.size()][S.size()]: rows `useful` of the (pseudo-)inverse of the Vandermonde
+//     matrix of the nodes used (first K of S for first_k; all of S for lsq);
+//     columns of nodes not used are zero.
+//   H [(S.size()-K)][S.size()]: orthonormal parity check of the (|S|, K) code (optional).
+gpd_status_t decode_matrices(const std::vector<double>& pts, const std::vector<int>& S, int K,
+                             const std::vector<int>& useful, bool first_k,
+                             std::vector<double>* D, std::vector<double>* H);
+
+// ---------------------------------------------------------------- device tables
+
+// One "combine" operation: out_q = sum_s coef[q][s] * in_s over equally shaped blocks.
+// The table lives in device memory as
+//   int64 in_off[nin]; int64 out_off[nout]; float coef[nout*nin]; float H[r*nin];
+//   double coef64[nout*nin]; double H64[r*nin]; int32 node[nin];
+//   int32 in_rows[nin], in_cols[nin], out_rows[nout], out_cols[nout]   (only with limits)
+// With limits, rows/columns of a block at or beyond its limit read as zero (inputs) or are
+// not written (outputs): this is how zero-padded ragged edge blocks are handled.
+struct CombineTable {
+  int nin = 0, nout = 0, r = 0;
+  int off_align = 1;                   // largest of 1, 2, 4 dividing every block offset
+  const int64_t* in_off = nullptr;
+  const int64_t* out_off = nullptr;
+  const float* coef = nullptr;
+  const float* H = nullptr;
+  const double* coef64 = nullptr;
+  const double* H64 = nullptr;
+  const int32_t* node = nullptr;
+  const int32_t* in_rows = nullptr;    // all four null when there are no limits
+  const int32_t* in_cols = nullptr;
+  const int32_t* out_rows = nullptr;
+  const int32_t* out_cols = nullptr;
+  int limit_align = 4;                 // largest of 1, 2, 4 dividing every column limit
+};
+
+struct HostCombineTable {
+  int nin = 0, nout = 0, r = 0;
+  std::vector<int64_t> in_off, out_off;
+  std::vector<double> coef, H;         // fp64 masters
+  std::vector<int32_t> node;
+  std::vector<int32_t> in_rows, in_cols, out_rows, out_cols;   // empty = no limits
+  size_t bytes() const;
+  // serialise into `dst` (host) and return the device-side view relative to `dev_base`
+  CombineTable pack(void* dst, const void* dev_base) const;
+};
+
+// Ring of pinned staging buffers + device slots for per-call tables.
+struct TableRing {
+  static constexpr int kSlots = 8;
+  size_t slot_bytes = 0;
+  char* host = nullptr;                // pinned, kSlots * slot_bytes
+  char* dev = nullptr;                 // device, kSlots * slot_bytes
+  hipEvent_t ev[kSlots] = {};
+  bool used[kSlots] = {};
+  int next = 0;
+  gpd_status_t init(size_t bytes_per_slot);
+  void destroy();
+  // uploads `t` asynchronously on `stream`; the returned view stays valid until kSlots
+  // further uploads have been made.
+  gpd_status_t upload(const HostCombineTable& t, hipStream_t stream, CombineTable* out);
+};
+
+// ---------------------------------------------------------------- kernels (launchers)
+
+struct ScreenArgs {               // soft-error screen fused into the decode pass
+  bool enabled = false;
+  float rho = 0.f, abs_floor = 0.f;
+  uint32_t* counters = nullptr;   // [0] number of screened codewords, [1] max ratio bits
+  int32_t* list = nullptr;        // codeword indices row*cols+col
+  int32_t cap = 0;
+};
+
+// out_q[r][c] = sum_s coef[q][s] in_s[r][c]; blocks are rows x cols; fp32 in; OutT fp32/bf16.
+gpd_status_t launch_combine(hipStream_t stream, const CombineTable& t, const float* in,
+                            int64_t in_ld, void* out, int64_t out_ld, bool out_bf16,
+                            int64_t rows, int64_t cols, const ScreenArgs& screen);
+
+struct GemmArgs {
+  const void* A = nullptr;        // op(A) is M x K
+  const void* B = nullptr;        // op(B) is K x N
+  float* C = nullptr;             // M x N fp32
+  int64_t M = 0, N = 0, K = 0;
+  int64_t lda = 0, ldb = 0, ldc = 0;
+  int64_t strideA = 0, strideB = 0, strideC = 0;
+  int batch = 1;
+  bool transA = false;            // A stored K x M
+  bool transB = false;            // B stored N x K
+  bool a_bf16 = false, b_bf16 = false;   // element types in memory (fp32 otherwise)
+  bool mfma_bf16 = false;         // multiply in bf16 (fp32 inputs are rounded on the way)
+  float alpha = 1.f, beta = 0.f;  // C = beta*C + alpha*op(A)op(B)
+};
+gpd_status_t launch_gemm(hipStream_t stream, const GemmArgs& g);
+
+struct LocateArgs {
+  CombineTable t;
+  const float* in = nullptr; int64_t in_ld = 0;
+  float* out = nullptr; int64_t out_ld = 0;
+  int64_t rows = 0, cols = 0;
+  double rho = 0, abs_floor = 0;
+  uint32_t* counters = nullptr;   // see gpd_decode.hip for the layout
+  const int32_t* list = nullptr; int32_t n_list = 0;
+  gpd_located_t* located = nullptr; int64_t located_cap = 0;
+  int32_t* node_err = nullptr;    // [GPD_MAX_P]
+};
+gpd_status_t launch_locate(hipStream_t stream, const LocateArgs& a);
+
+gpd_status_t launch_zero_words(hipStream_t stream, void* p, int n_words);
+
+// ---------------------------------------------------------------- shared host helpers (gpd_api.hip)
+
+// Table that evaluates sum_blocks b_p^e(block) * block for every node p: grid_r x grid_c
+// blocks of bh x bw inside a matrix with leading dimension ld; output stack [P][bh][bw].
+HostCombineTable encode_table(const std::vector<double>& pts, const std::vector<int>& exps,
+                              int grid_r, int grid_c, int64_t bh, int64_t bw, int64_t ld);
+
+// One decode of a stack of P responses [P][bh][bw] into a grid_r x grid_c grid of blocks.
+struct DecodeJob {
+  const std::vector<double>* pts = nullptr;
+  int K = 0;
+  std::vector<int> useful;                     // exponent of output block q (row-major grid)
+  int grid_r = 0, grid_c = 0;
+  int64_t bh = 0, bw = 0;
+  double rho = 0, abs_floor = 0;
+  int64_t flag_cap = 0, loc_cap = 0;
+  size_t workspace_bytes = 0;
+  std::vector<int32_t> out_rows, out_cols;     // limits of the output blocks (empty = none)
+};
+gpd_status_t run_decode(hipStream_t stream, TableRing* ring, const DecodeJob& job, const float* Zt,
+                        const uint8_t* present, int mode, int correct, float* out, int64_t ld_out,
+                        void* workspace, size_t workspace_bytes, gpd_report_t* report);
+void decode_workspace_layout(int64_t n_codewords, int64_t* flag_cap, int64_t* loc_cap, size_t* bytes);
+
+}  // namespace gpd

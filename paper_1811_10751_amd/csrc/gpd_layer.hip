@@ -1,0 +1,582 @@
+// Coded DNN layer step (Sec. VII for mini-batch 1, Sec. IX for mini-batch > 1): the weight
+// stays encoded as W~_p = sum_ij W_ij a_p^i b_p^j on every node; only X and Delta are
+// encoded and decoded per iteration, and the update is applied to W~_p directly.
+//
+// Kernels here are the small-batch ("skinny") streaming products, which are HBM-bound on
+// reading / rewriting W~:
+//   skinny_forward   S~_p = W~_p X~_p                 one wavefront per row of W~_p
+//   skinny_backward_update
+//                    C~_p = W~_p^T Delta~_p (pre-update W~_p) and
+//                    W~_p <- (1-decay) W~_p + eta Dhat_p Xhat_p^T in ONE pass over W~_p
+// Larger batches go through the MFMA GEMMs of gpd_gemm.hip.  Element-wise steps C1 / C2
+// are at the end.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "gpd_internal.hpp"
+
+namespace gpd {
+
+namespace {
+
+constexpr int kSkinnyMaxBatch = 8;      // widest per-node batch the streaming kernels take
+constexpr int kRowChunk = 64;           // rows of W~_p one workgroup of the backward pass owns
+
+// ---------------------------------------------------------------- skinny forward
+
+// S~[p][r][b] = sum_c W~[p][r][c] * X~[p][c][b];  NB = per-node batch (columns of X~_p).
+template <int NB>
+__global__ __launch_bounds__(256) void skinny_forward_kernel(const float* __restrict__ Wt,
+                                                             const float* __restrict__ Xt,
+                                                             float* __restrict__ St, int rows,
+                                                             int cols) {
+  const int p = blockIdx.y;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + wave;
+  if (row >= rows) return;
+  const float* __restrict__ w = Wt + ((int64_t)p * rows + row) * cols;
+  const float* __restrict__ x = Xt + (int64_t)p * cols * NB;
+  float acc[NB];
+#pragma unroll
+  for (int b = 0; b < NB; ++b) acc[b] = 0.f;
+  const int cols4 = cols & ~3;
+  for (int c = lane * 4; c < cols4; c += 256) {
+    const float4 wv = *reinterpret_cast<const float4*>(w + c);
+    const float we[4] = {wv.x, wv.y, wv.z, wv.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+      for (int b = 0; b < NB; ++b) acc[b] = fmaf(we[e], x[(int64_t)(c + e) * NB + b], acc[b]);
+  }
+  for (int c = cols4 + lane; c < cols; c += 64)
+#pragma unroll
+    for (int b = 0; b < NB; ++b) acc[b] = fmaf(w[c], x[(int64_t)c * NB + b], acc[b]);
+#pragma unroll
+  for (int b = 0; b < NB; ++b) {
+    float v = acc[b];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    if (lane == 0) St[((int64_t)p * rows + row) * NB + b] = v;
+  }
+}
+
+// ---------------------------------------------------------------- skinny backward + update
+
+// One workgroup owns rows [chunk*kRowChunk, ...) of W~_p and all columns; a thread owns 4
+// consecutive columns per 1024-column strip.
+//   part[p][chunk][c][b2] = sum_{r in chunk} W~[p][r][c] * Dt[p][r][b2]        (DO_BWD)
+//   W~[p][r][c] = keep * W~[p][r][c] + eta * sum_b Dh[p][r][b] * Xh[p][c][b]   (DO_UPD)
+template <int NB2, int NBU, bool DO_BWD, bool DO_UPD>
+__global__ __launch_bounds__(256) void skinny_backward_update_kernel(
+    float* __restrict__ Wt, const float* __restrict__ Dt, const float* __restrict__ Dh,
+    const float* __restrict__ Xh, float* __restrict__ part, int rows, int cols, int nchunks,
+    float keep, float eta) {
+  const int p = blockIdx.z, chunk = blockIdx.y;
+  const int c0 = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (c0 >= cols) return;
+  const int r0 = chunk * kRowChunk;
+  const int r1 = min(rows, r0 + kRowChunk);
+  const bool vec = c0 + 3 < cols;
+  float xh[4][NBU > 0 ? NBU : 1];
+  if constexpr (DO_UPD) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+      for (int b = 0; b < NBU; ++b)
+        xh[e][b] = (c0 + e < cols) ? Xh[((int64_t)p * cols + c0 + e) * NBU + b] : 0.f;
+  }
+  float cs[4][NB2 > 0 ? NB2 : 1];
+#pragma unroll
+  for (int e = 0; e < 4; ++e)
+#pragma unroll
+    for (int b = 0; b < (NB2 > 0 ? NB2 : 1); ++b) cs[e][b] = 0.f;
+
+  for (int r = r0; r < r1; ++r) {
+    float* wp = Wt + ((int64_t)p * rows + r) * cols + c0;
+    float w[4] = {0.f, 0.f, 0.f, 0.f};
+    if (vec) {
+      const float4 t = *reinterpret_cast<const float4*>(wp);
+      w[0] = t.x; w[1] = t.y; w[2] = t.z; w[3] = t.w;
+    } else {
+      for (int e = 0; e < 4; ++e) if (c0 + e < cols) w[e] = wp[e];
+    }
+    if constexpr (DO_BWD) {
+      const float* __restrict__ d = Dt + ((int64_t)p * rows + r) * NB2;
+#pragma unroll
+      for (int b = 0; b < NB2; ++b) {
+        const float dv = d[b];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) cs[e][b] = fmaf(w[e], dv, cs[e][b]);
+      }
+    }
+    if constexpr (DO_UPD) {
+      const float* __restrict__ dh = Dh + ((int64_t)p * rows + r) * NBU;
+      float nw[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float u = 0.f;
+#pragma unroll
+        for (int b = 0; b < NBU; ++b) u = fmaf(dh[b], xh[e][b], u);
+        nw[e] = fmaf(keep, w[e], eta * u);
+      }
+      if (vec) {
+        *reinterpret_cast<float4*>(wp) = make_float4(nw[0], nw[1], nw[2], nw[3]);
+      } else {
+        for (int e = 0; e < 4; ++e) if (c0 + e < cols) wp[e] = nw[e];
+      }
+    }
+  }
+  if constexpr (DO_BWD) {
+    float* __restrict__ out = part + (((int64_t)p * nchunks + chunk) * cols + c0) * NB2;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (c0 + e < cols)
+#pragma unroll
+        for (int b = 0; b < NB2; ++b) out[e * NB2 + b] = cs[e][b];
+  }
+}
+
+// Ct[p][c][b] = sum_chunk part[p][chunk][c][b], in chunk order (deterministic).
+__global__ void reduce_chunks_kernel(const float* __restrict__ part, float* __restrict__ Ct,
+                                     int64_t per_node, int nchunks, int64_t total) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const int64_t p = i / per_node, e = i - p * per_node;
+  float s = 0.f;
+  for (int k = 0; k < nchunks; ++k) s += part[((int64_t)p * nchunks + k) * per_node + e];
+  Ct[i] = s;
+}
+
+// ---------------------------------------------------------------- element-wise steps
+
+__global__ void sigmoid_fwd_kernel(const float* __restrict__ s, float* __restrict__ y, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) y[i] = 1.f / (1.f + expf(-s[i]));
+}
+__global__ void sigmoid_bwd_kernel(const float* __restrict__ c, const float* __restrict__ y,
+                                   float* __restrict__ d, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) d[i] = c[i] * y[i] * (1.f - y[i]);
+}
+__global__ void l2_delta_kernel(const float* __restrict__ y, const float* __restrict__ yh, float scale,
+                                float* __restrict__ d, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) d[i] = scale * (y[i] - yh[i]) * yh[i] * (1.f - yh[i]);
+}
+
+size_t align256(size_t x) { return (x + 255) / 256 * 256; }
+
+}  // namespace
+}  // namespace gpd
+
+using namespace gpd;
+
+// ---------------------------------------------------------------- layer object
+
+struct gpd_layer {
+  gpd_layer_desc_t desc;
+  Code fwd;                        // plan of W~ X~ (m, n, d1)
+  std::vector<int> eD, eCb;        // [m*d2] exponent of Delta block (i,k); [n*d2] useful of C block (j,k)
+  int Kb = 0;
+  std::vector<int> eUd, eUx;       // update exponents of Delta_i and X_j
+  int64_t N_out_pad = 0, N_in_pad = 0, wr = 0, wc = 0, nb1 = 0, nb2 = 0;
+  hipStream_t stream = nullptr;
+  double rho = 0, abs_floor = 0;
+  TableRing ring;
+  // workspace layout (byte offsets)
+  size_t off_Xt = 0, off_St = 0, off_Dt = 0, off_Ct = 0, off_Dh = 0, off_Xh = 0, off_part = 0,
+         off_dec = 0, ws_bytes = 0;
+  int nchunks = 0;
+  int64_t flag_cap = 0, loc_cap = 0;
+  size_t dec_bytes = 0;
+};
+
+namespace {
+
+std::vector<int32_t> limits(int64_t total, int64_t block, int nblocks) {
+  std::vector<int32_t> v(nblocks);
+  for (int i = 0; i < nblocks; ++i) {
+    int64_t left = total - (int64_t)i * block;
+    v[i] = (int32_t)std::max<int64_t>(0, std::min<int64_t>(block, left));
+  }
+  return v;
+}
+
+// limits for a grid_r x grid_c grid of bh x bw blocks covering a rows x cols matrix
+void grid_limits(int64_t rows, int64_t cols, int grid_r, int grid_c, int64_t bh, int64_t bw,
+                 std::vector<int32_t>* lr, std::vector<int32_t>* lc) {
+  lr->clear(); lc->clear();
+  if (rows == grid_r * bh && cols == grid_c * bw) return;      // nothing ragged
+  std::vector<int32_t> r = limits(rows, bh, grid_r), c = limits(cols, bw, grid_c);
+  for (int i = 0; i < grid_r; ++i)
+    for (int j = 0; j < grid_c; ++j) { lr->push_back(r[i]); lc->push_back(c[j]); }
+}
+
+}  // namespace
+
+extern "C" gpd_status_t gpd_layer_create(const gpd_layer_desc_t* d, gpd_layer_t** out) {
+  if (!d || !out) return fail(GPD_E_INVALID, "gpd_layer_create: null argument");
+  *out = nullptr;
+  if (d->N_out < 1 || d->N_in < 1 || d->batch < 1 || d->d1 < 1 || d->d2 < 1)
+    return fail(GPD_E_INVALID, "layer sizes must be >= 1");
+  if (d->batch % d->d1 || d->batch % d->d2) return fail(GPD_E_SHAPE, "d1 and d2 must divide the batch");
+  if (d->worker_dtype != GPD_F32 && d->worker_dtype != GPD_BF16)
+    return fail(GPD_E_INVALID, "unknown worker dtype");
+  if (d->m < 1 || d->n < 1) return fail(GPD_E_INVALID, "m, n must be >= 1");
+  if (d->m * d->d2 > GPD_MAX_BLOCKS || d->n * d->d2 > GPD_MAX_BLOCKS)
+    return fail(GPD_E_INVALID, "block grid larger than GPD_MAX_BLOCKS");
+  gpd_layer_t* L = new (std::nothrow) gpd_layer_t();
+  if (!L) return fail(GPD_E_DEVICE, "out of host memory");
+  L->desc = *d;
+  L->desc.points = nullptr;
+  int subst = d->subst;
+  if (subst == GPD_SUB_AUTO) subst = d->m > d->n ? GPD_SUB_V_UM : GPD_SUB_U_VN;
+  gpd_status_t st = make_code(d->m, d->n, d->d1, d->P, subst, d->points, &L->fwd);
+  if (st != GPD_OK) { delete L; return st; }
+  const Code& c = L->fwd;
+  const int m = d->m, n = d->n, d2 = d->d2;
+  // Sec. IX backpropagation stage: Delta~^T(w,u) = sum Delta^T_{k,i} w^k u^(m-1-i); C^T_{k,j} is
+  // the coefficient of w^k u^(m-1) v^j.
+  L->eD.resize(m * d2); L->eCb.resize(n * d2);
+  int maxD = 0, maxA = 0;
+  for (int i = 0; i < m; ++i)
+    for (int k = 0; k < d2; ++k) {
+      L->eD[i * d2 + k] = c.ew * k + c.eu * (m - 1 - i);
+      maxD = std::max(maxD, L->eD[i * d2 + k]);
+    }
+  for (int j = 0; j < n; ++j)
+    for (int k = 0; k < d2; ++k) L->eCb[j * d2 + k] = c.ew * k + c.eu * (m - 1) + c.ev * j;
+  for (int e : c.eA) maxA = std::max(maxA, e);
+  L->Kb = maxD + maxA + 1;
+  if (L->Kb > d->P) {
+    delete L;
+    return fail(GPD_E_SHAPE, "backward threshold K_b = %d exceeds P = %d", maxD + maxA + 1, d->P);
+  }
+  L->eUd.resize(m); L->eUx.resize(n);
+  for (int i = 0; i < m; ++i) L->eUd[i] = c.eu * i;      // update: sum_i Delta_i u^i
+  for (int j = 0; j < n; ++j) L->eUx[j] = c.ev * j;      //         sum_j X_j v^j
+  L->N_out_pad = (d->N_out + m - 1) / m * m;
+  L->N_in_pad = (d->N_in + n - 1) / n * n;
+  L->wr = L->N_out_pad / m; L->wc = L->N_in_pad / n;
+  L->nb1 = d->batch / d->d1; L->nb2 = d->batch / d->d2;
+  L->stream = (hipStream_t)d->hip_stream;
+  L->rho = d->rho_detect > 0 ? d->rho_detect : (d->worker_dtype == GPD_BF16 ? 0.125 : 1.0 / 4096.0);
+  L->abs_floor = d->abs_floor;
+  L->nchunks = (int)((L->wr + kRowChunk - 1) / kRowChunk);
+
+  const int64_t P = d->P;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return o; };
+  L->off_Xt = take((size_t)P * L->wc * L->nb1 * 4);
+  L->off_St = take((size_t)P * L->wr * L->nb1 * 4);
+  L->off_Dt = take((size_t)P * L->wr * L->nb2 * 4);
+  L->off_Ct = take((size_t)P * L->wc * L->nb2 * 4);
+  L->off_Dh = take((size_t)P * L->wr * d->batch * 4);
+  L->off_Xh = take((size_t)P * L->wc * d->batch * 4);
+  L->off_part = take((size_t)P * L->nchunks * L->wc * L->nb2 * 4);
+  const int64_t ncw = std::max(L->wr * L->nb1, L->wc * L->nb2);
+  decode_workspace_layout(ncw, &L->flag_cap, &L->loc_cap, &L->dec_bytes);
+  L->off_dec = take(L->dec_bytes);
+  L->ws_bytes = off;
+
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) { delete L; return fail(GPD_E_DEVICE, "no HIP device"); }
+  HostCombineTable probe;
+  size_t slot = 0;
+  auto grow = [&](int nin, int nout, int r) {
+    probe.nin = nin; probe.nout = nout; probe.r = r;
+    slot = std::max(slot, probe.bytes());
+  };
+  grow(m * n, (int)P, 0); grow(n * d->d1, (int)P, 0); grow(m * d2, (int)P, 0);
+  grow((int)P, m * d->d1, (int)P); grow((int)P, n * d2, (int)P); grow((int)P, m * n, 0);
+  st = L->ring.init(slot);
+  if (st != GPD_OK) { L->ring.destroy(); delete L; return st; }
+  *out = L;
+  return GPD_OK;
+}
+
+extern "C" gpd_status_t gpd_layer_info(const gpd_layer_t* L, int32_t* Kf, int32_t* Kb, int64_t* wt_rows,
+                                       int64_t* wt_cols, size_t* workspace_bytes) {
+  if (!L) return fail(GPD_E_INVALID, "gpd_layer_info: null layer");
+  if (Kf) *Kf = L->fwd.K;
+  if (Kb) *Kb = L->Kb;
+  if (wt_rows) *wt_rows = L->wr;
+  if (wt_cols) *wt_cols = L->wc;
+  if (workspace_bytes) *workspace_bytes = L->ws_bytes;
+  return GPD_OK;
+}
+
+extern "C" void gpd_layer_destroy(gpd_layer_t* L) {
+  if (!L) return;
+  L->ring.destroy();
+  delete L;
+}
+
+extern "C" gpd_status_t gpd_layer_encode_weights(const gpd_layer_t* Lc, const float* W, int64_t ldw,
+                                                 float* Wt) {
+  gpd_layer_t* L = const_cast<gpd_layer_t*>(Lc);
+  if (!L || !W || !Wt) return fail(GPD_E_INVALID, "gpd_layer_encode_weights: null argument");
+  if (ldw < L->desc.N_in) return fail(GPD_E_SHAPE, "ldw smaller than N_in");
+  const Code& c = L->fwd;
+  HostCombineTable ht = encode_table(c.pts, c.eA, c.m, c.n, L->wr, L->wc, ldw);
+  grid_limits(L->desc.N_out, L->desc.N_in, c.m, c.n, L->wr, L->wc, &ht.in_rows, &ht.in_cols);
+  CombineTable t;
+  gpd_status_t st = L->ring.upload(ht, L->stream, &t);
+  if (st != GPD_OK) return st;
+  ScreenArgs none;
+  return launch_combine(L->stream, t, W, ldw, Wt, L->wc, false, L->wr, L->wc, none);
+}
+
+extern "C" gpd_status_t gpd_layer_decode_weights(const gpd_layer_t* Lc, const float* Wt,
+                                                 const uint8_t* present, float* W, int64_t ldw) {
+  gpd_layer_t* L = const_cast<gpd_layer_t*>(Lc);
+  if (!L || !W || !Wt) return fail(GPD_E_INVALID, "gpd_layer_decode_weights: null argument");
+  if (ldw < L->desc.N_in) return fail(GPD_E_SHAPE, "ldw smaller than N_in");
+  const Code& c = L->fwd;
+  // W~(b) = sum W_ij b^eA(i,j): a polynomial with mn coefficients (footnote on regeneration)
+  DecodeJob job;
+  job.pts = &c.pts; job.K = c.m * c.n; job.useful = c.eA;
+  job.grid_r = c.m; job.grid_c = c.n; job.bh = L->wr; job.bw = L->wc;
+  job.rho = L->rho; job.abs_floor = L->abs_floor;
+  job.flag_cap = 0; job.loc_cap = 0; job.workspace_bytes = 0;
+  grid_limits(L->desc.N_out, L->desc.N_in, c.m, c.n, L->wr, L->wc, &job.out_rows, &job.out_cols);
+  return run_decode(L->stream, &L->ring, job, Wt, present, GPD_DEC_LSQ_ALL, 0, W, ldw, nullptr, 0, nullptr);
+}
+
+// ---------------------------------------------------------------- products
+
+namespace {
+
+template <int NB>
+void launch_skinny_fwd(hipStream_t s, const float* Wt, const float* Xt, float* St, int rows, int cols, int P) {
+  hipLaunchKernelGGL((skinny_forward_kernel<NB>), dim3((rows + 3) / 4, P), dim3(256), 0, s, Wt, Xt, St, rows, cols);
+}
+
+gpd_status_t skinny_forward(hipStream_t s, const float* Wt, const float* Xt, float* St, int64_t rows,
+                            int64_t cols, int P, int nb) {
+  if (rows == 0 || cols == 0) return GPD_OK;
+  switch (nb) {
+    case 1: launch_skinny_fwd<1>(s, Wt, Xt, St, (int)rows, (int)cols, P); break;
+    case 2: launch_skinny_fwd<2>(s, Wt, Xt, St, (int)rows, (int)cols, P); break;
+    case 3: launch_skinny_fwd<3>(s, Wt, Xt, St, (int)rows, (int)cols, P); break;
+    case 4: launch_skinny_fwd<4>(s, Wt, Xt, St, (int)rows, (int)cols, P); break;
+    case 5: launch_skinny_fwd<5>(s, Wt, Xt, St, (int)rows, (int)cols, P); break;
+    case 6: launch_skinny_fwd<6>(s, Wt, Xt, St, (int)rows, (int)cols, P); break;
+    case 7: launch_skinny_fwd<7>(s, Wt, Xt, St, (int)rows, (int)cols, P); break;
+    case 8: launch_skinny_fwd<8>(s, Wt, Xt, St, (int)rows, (int)cols, P); break;
+    default: return fail(GPD_E_UNSUPPORTED, "skinny forward: batch %d", nb);
+  }
+  GPD_HIP(hipGetLastError());
+  return GPD_OK;
+}
+
+template <int NB2, int NBU>
+gpd_status_t launch_skinny_bu(hipStream_t s, float* Wt, const float* Dt, const float* Dh, const float* Xh,
+                              float* part, int rows, int cols, int nchunks, int P, float keep, float eta,
+                              bool do_bwd) {
+  dim3 grid((cols + 1023) / 1024, nchunks, P), block(256);
+  if (do_bwd)
+    hipLaunchKernelGGL((skinny_backward_update_kernel<NB2, NBU, true, true>), grid, block, 0, s, Wt, Dt, Dh, Xh,
+                       part, rows, cols, nchunks, keep, eta);
+  else
+    hipLaunchKernelGGL((skinny_backward_update_kernel<0, NBU, false, true>), grid, block, 0, s, Wt, Dt, Dh, Xh,
+                       part, rows, cols, nchunks, keep, eta);
+  GPD_HIP(hipGetLastError());
+  return GPD_OK;
+}
+
+template <int NB2>
+gpd_status_t skinny_bu_nbu(hipStream_t s, float* Wt, const float* Dt, const float* Dh, const float* Xh,
+                           float* part, int rows, int cols, int nchunks, int P, float keep, float eta,
+                           bool do_bwd, int nbu) {
+  switch (nbu) {
+    case 1: return launch_skinny_bu<NB2, 1>(s, Wt, Dt, Dh, Xh, part, rows, cols, nchunks, P, keep, eta, do_bwd);
+    case 2: return launch_skinny_bu<NB2, 2>(s, Wt, Dt, Dh, Xh, part, rows, cols, nchunks, P, keep, eta, do_bwd);
+    case 4: return launch_skinny_bu<NB2, 4>(s, Wt, Dt, Dh, Xh, part, rows, cols, nchunks, P, keep, eta, do_bwd);
+    case 8: return launch_skinny_bu<NB2, 8>(s, Wt, Dt, Dh, Xh, part, rows, cols, nchunks, P, keep, eta, do_bwd);
+    default: return fail(GPD_E_UNSUPPORTED, "skinny update: batch %d", nbu);
+  }
+}
+
+bool skinny_ok(const gpd_layer_t* L) {
+  const int64_t b = L->desc.batch;
+  const bool bu = b == 1 || b == 2 || b == 4 || b == 8;
+  const int64_t n2 = L->nb2;
+  return bu && L->nb1 <= kSkinnyMaxBatch && (n2 == 1 || n2 == 2 || n2 == 4 || n2 == 8);
+}
+
+}  // namespace
+
+extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, float* Wt, const float* X,
+                                             const float* Dlt, float eta, float decay, float* out,
+                                             const uint8_t* present, int32_t correct_errors,
+                                             void* workspace, size_t workspace_bytes,
+                                             gpd_report_t* report) {
+  if (!L || !Wt || !X) return fail(GPD_E_INVALID, "gpd_coded_layer_step: null argument");
+  if (phase != GPD_STEP_FORWARD && phase != GPD_STEP_BACKWARD_UPDATE)
+    return fail(GPD_E_INVALID, "unknown phase %d", phase);
+  if (!workspace || workspace_bytes < L->ws_bytes || ((uintptr_t)workspace & 255))
+    return fail(GPD_E_WORKSPACE, "layer step: workspace of %zu aligned bytes needed", L->ws_bytes);
+  const gpd_layer_desc_t& d = L->desc;
+  const Code& c = L->fwd;
+  const int P = d.P;
+  char* ws = (char*)workspace;
+  float* Xt = (float*)(ws + L->off_Xt);
+  float* St = (float*)(ws + L->off_St);
+  float* Dt = (float*)(ws + L->off_Dt);
+  float* Ct = (float*)(ws + L->off_Ct);
+  float* Dh = (float*)(ws + L->off_Dh);
+  float* Xh = (float*)(ws + L->off_Xh);
+  float* part = (float*)(ws + L->off_part);
+  void* dec_ws = ws + L->off_dec;
+  hipStream_t s = L->stream;
+  ScreenArgs none;
+  gpd_status_t st;
+  const bool bf16 = d.worker_dtype == GPD_BF16;
+  const bool skinny = skinny_ok(L) && !bf16;
+
+  if (phase == GPD_STEP_FORWARD) {
+    if (!out) return fail(GPD_E_INVALID, "forward: out is null");
+    // X~_p = sum_jk X_jk b_p^eB(j,k)   (feedforward stage)
+    HostCombineTable ht = encode_table(c.pts, c.eB, c.n, c.d, L->wc, L->nb1, d.batch);
+    grid_limits(d.N_in, d.batch, c.n, c.d, L->wc, L->nb1, &ht.in_rows, &ht.in_cols);
+    CombineTable t;
+    st = L->ring.upload(ht, s, &t);
+    if (st != GPD_OK) return st;
+    st = launch_combine(s, t, X, d.batch, Xt, L->nb1, false, L->wc, L->nb1, none);
+    if (st != GPD_OK) return st;
+    // S~_p = W~_p X~_p   (step O1 on every node)
+    if (skinny) {
+      st = skinny_forward(s, Wt, Xt, St, L->wr, L->wc, P, (int)L->nb1);
+    } else {
+      GemmArgs g;
+      g.A = Wt; g.B = Xt; g.C = St;
+      g.M = L->wr; g.K = L->wc; g.N = L->nb1;
+      g.lda = L->wc; g.ldb = L->nb1; g.ldc = L->nb1;
+      g.strideA = L->wr * L->wc; g.strideB = L->wc * L->nb1; g.strideC = L->wr * L->nb1;
+      g.batch = P; g.mfma_bf16 = bf16;
+      st = launch_gemm(s, g);
+    }
+    if (st != GPD_OK) return st;
+    DecodeJob job;
+    job.pts = &c.pts; job.K = c.K; job.useful = c.eC;
+    job.grid_r = c.m; job.grid_c = c.d; job.bh = L->wr; job.bw = L->nb1;
+    job.rho = L->rho; job.abs_floor = L->abs_floor;
+    job.flag_cap = L->flag_cap; job.loc_cap = L->loc_cap; job.workspace_bytes = L->dec_bytes;
+    grid_limits(d.N_out, d.batch, c.m, c.d, L->wr, L->nb1, &job.out_rows, &job.out_cols);
+    return run_decode(s, &L->ring, job, St, present, GPD_DEC_LSQ_ALL, correct_errors, out, d.batch, dec_ws,
+                      L->dec_bytes, report);
+  }
+
+  // ---- BACKWARD_UPDATE
+  if (!Dlt) return fail(GPD_E_INVALID, "backward: Dlt is null");
+  const bool do_bwd = out != nullptr;
+  CombineTable t;
+  if (do_bwd) {
+    // Delta~_p = sum_{i,k} Delta_{i,k} b_p^eD(i,k), stored (N_out/m) x (batch/d2)
+    HostCombineTable ht = encode_table(c.pts, L->eD, c.m, d.d2, L->wr, L->nb2, d.batch);
+    grid_limits(d.N_out, d.batch, c.m, d.d2, L->wr, L->nb2, &ht.in_rows, &ht.in_cols);
+    st = L->ring.upload(ht, s, &t);
+    if (st != GPD_OK) return st;
+    st = launch_combine(s, t, Dlt, d.batch, Dt, L->nb2, false, L->wr, L->nb2, none);
+    if (st != GPD_OK) return st;
+  }
+  {
+    // update operands: Dhat_p = sum_i Delta_i a_p^i,  Xhat_p = sum_j X_j b_p^j
+    HostCombineTable hd = encode_table(c.pts, L->eUd, c.m, 1, L->wr, d.batch, d.batch);
+    grid_limits(d.N_out, d.batch, c.m, 1, L->wr, d.batch, &hd.in_rows, &hd.in_cols);
+    st = L->ring.upload(hd, s, &t);
+    if (st != GPD_OK) return st;
+    st = launch_combine(s, t, Dlt, d.batch, Dh, d.batch, false, L->wr, d.batch, none);
+    if (st != GPD_OK) return st;
+    HostCombineTable hx = encode_table(c.pts, L->eUx, c.n, 1, L->wc, d.batch, d.batch);
+    grid_limits(d.N_in, d.batch, c.n, 1, L->wc, d.batch, &hx.in_rows, &hx.in_cols);
+    st = L->ring.upload(hx, s, &t);
+    if (st != GPD_OK) return st;
+    st = launch_combine(s, t, X, d.batch, Xh, d.batch, false, L->wc, d.batch, none);
+    if (st != GPD_OK) return st;
+  }
+  const float keep = 1.f - decay;
+  if (skinny) {
+    // one pass over W~: C~_p from the pre-update values, then the coded update in place
+    const int nb2 = (int)L->nb2, nbu = (int)d.batch;
+    const int rows = (int)L->wr, cols = (int)L->wc;
+    switch (do_bwd ? nb2 : 1) {
+      case 1: st = skinny_bu_nbu<1>(s, Wt, Dt, Dh, Xh, part, rows, cols, L->nchunks, P, keep, eta, do_bwd, nbu); break;
+      case 2: st = skinny_bu_nbu<2>(s, Wt, Dt, Dh, Xh, part, rows, cols, L->nchunks, P, keep, eta, do_bwd, nbu); break;
+      case 4: st = skinny_bu_nbu<4>(s, Wt, Dt, Dh, Xh, part, rows, cols, L->nchunks, P, keep, eta, do_bwd, nbu); break;
+      case 8: st = skinny_bu_nbu<8>(s, Wt, Dt, Dh, Xh, part, rows, cols, L->nchunks, P, keep, eta, do_bwd, nbu); break;
+      default: st = fail(GPD_E_UNSUPPORTED, "skinny backward: batch %d", nb2);
+    }
+    if (st != GPD_OK) return st;
+    if (do_bwd) {
+      const int64_t per_node = L->wc * L->nb2, total = per_node * P;
+      hipLaunchKernelGGL(reduce_chunks_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, part, Ct,
+                         per_node, L->nchunks, total);
+      GPD_HIP(hipGetLastError());
+    }
+  } else {
+    if (do_bwd) {
+      // C~_p = W~_p^T Delta~_p   (step O2, pre-update weights)
+      GemmArgs g;
+      g.A = Wt; g.transA = true; g.B = Dt; g.C = Ct;
+      g.M = L->wc; g.K = L->wr; g.N = L->nb2;
+      g.lda = L->wc; g.ldb = L->nb2; g.ldc = L->nb2;
+      g.strideA = L->wr * L->wc; g.strideB = L->wr * L->nb2; g.strideC = L->wc * L->nb2;
+      g.batch = P; g.mfma_bf16 = bf16;
+      st = launch_gemm(s, g);
+      if (st != GPD_OK) return st;
+    }
+    // W~_p <- keep * W~_p + eta * Dhat_p Xhat_p^T   (step O3 in coded form, fp32)
+    GemmArgs g;
+    g.A = Dh; g.B = Xh; g.transB = true; g.C = Wt;
+    g.M = L->wr; g.K = d.batch; g.N = L->wc;
+    g.lda = d.batch; g.ldb = d.batch; g.ldc = L->wc;
+    g.strideA = L->wr * d.batch; g.strideB = L->wc * d.batch; g.strideC = L->wr * L->wc;
+    g.batch = P; g.alpha = eta; g.beta = keep;
+    st = launch_gemm(s, g);
+    if (st != GPD_OK) return st;
+  }
+  if (!do_bwd) {
+    if (report) { std::memset(report, 0, sizeof(*report)); report->n_present = P; }
+    return GPD_OK;
+  }
+  DecodeJob job;
+  job.pts = &c.pts; job.K = L->Kb; job.useful = L->eCb;
+  job.grid_r = c.n; job.grid_c = d.d2; job.bh = L->wc; job.bw = L->nb2;
+  job.rho = L->rho; job.abs_floor = L->abs_floor;
+  job.flag_cap = L->flag_cap; job.loc_cap = L->loc_cap; job.workspace_bytes = L->dec_bytes;
+  grid_limits(d.N_in, d.batch, c.n, d.d2, L->wc, L->nb2, &job.out_rows, &job.out_cols);
+  return run_decode(s, &L->ring, job, Ct, present, GPD_DEC_LSQ_ALL, correct_errors, out, d.batch, dec_ws,
+                    L->dec_bytes, report);
+}
+
+// ---------------------------------------------------------------- element-wise steps
+
+extern "C" gpd_status_t gpd_sigmoid_fwd(const float* s, float* y, int64_t n, void* stream) {
+  if (n < 0 || (n > 0 && (!s || !y))) return fail(GPD_E_INVALID, "gpd_sigmoid_fwd: bad argument");
+  if (n == 0) return GPD_OK;
+  hipLaunchKernelGGL(sigmoid_fwd_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, s, y, n);
+  GPD_HIP(hipGetLastError());
+  return GPD_OK;
+}
+
+extern "C" gpd_status_t gpd_sigmoid_bwd(const float* c, const float* y, float* d, int64_t n, void* stream) {
+  if (n < 0 || (n > 0 && (!c || !y || !d))) return fail(GPD_E_INVALID, "gpd_sigmoid_bwd: bad argument");
+  if (n == 0) return GPD_OK;
+  hipLaunchKernelGGL(sigmoid_bwd_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, c, y, d, n);
+  GPD_HIP(hipGetLastError());
+  return GPD_OK;
+}
+
+extern "C" gpd_status_t gpd_l2_delta(const float* y, const float* yhat, float scale, float* d, int64_t n,
+                                     void* stream) {
+  if (n < 0 || (n > 0 && (!y || !yhat || !d))) return fail(GPD_E_INVALID, "gpd_l2_delta: bad argument");
+  if (n == 0) return GPD_OK;
+  hipLaunchKernelGGL(l2_delta_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, y, yhat,
+                     scale, d, n);
+  GPD_HIP(hipGetLastError());
+  return GPD_OK;
+}
