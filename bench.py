@@ -1,0 +1,173 @@
+#!/usr/bin/env python3
+"""Benchmark of the coded matrix multiplication hot path on one MI355X.
+
+One step = encode A and B, the P coded worker products, and the erasure decode of one
+straggler trial of the 4096 x 4096 workload (m = n = d = 2, P = 16, K = 9: a seeded random
+set of P - K nodes is dropped every step).  Inputs are resident in HBM before the timed
+region.  Prints ONE JSON line:
+
+  value     effective coded GEMM TFLOP/s = 2 N1 N0 Nc / (time of one whole step)
+  roofline  the dominant kernel (the batched fp32 MFMA worker product): its flops per
+            launch over its average duration, measured with events on the launch stream
+  cpu_baseline  the numpy fp64 oracle timed on the host cores on one step of the same
+            workload
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3     # MI355X published dense fp32 matrix peak
+PEAK_HBM_GBS = 8000.0             # MI355X published HBM3E bandwidth
+
+
+def cpu_baseline(cfg, n_threads):
+    """The oracle as it stands, timed on one step (one erasure trial) of the same workload."""
+    import numpy as np
+
+    import gpd_workloads as WL
+    from oracle import gpd_oracle as O
+
+    A, B = WL.matmul_inputs(cfg["N1"], cfg["N0"], cfg["Nc"], cfg["seed"])
+    pl = O.make_plan(cfg["m"], cfg["n"], cfg["d"], cfg["P"])
+    present = WL.erasure_trial(cfg["trial_seed0"], cfg["P"], cfg["P"] - pl.K)
+    t0 = time.perf_counter()
+    At, Bt = O.encode_A(A, pl), O.encode_B(B, pl)
+    t1 = time.perf_counter()
+    Ct = O.worker_products(At, Bt, round_outputs="f32")
+    t2 = time.perf_counter()
+    C, _ = O.decode(Ct, pl, present, "first_k")
+    t3 = time.perf_counter()
+    flops = 2.0 * cfg["N1"] * cfg["N0"] * cfg["Nc"]
+    return {
+        "value": flops / (t3 - t0) / 1e12, "unit": "TFLOP/s", "cores": n_threads, "kind": "oracle",
+        "sample": "one full step (encode + 16 products + decode of erasure trial 0) of the "
+                  "4096^3 workload, numpy fp64",
+        "seconds": {"encode": t1 - t0, "products": t2 - t1, "decode": t3 - t2},
+    }, C
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=1, help="matmul workload index (0 or 1)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (all P nodes are simulated on it); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import gpd_workloads as WL
+    import paper_1811_10751_amd as G
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU", file=sys.stderr)
+        sys.exit(1)
+    G.load_library()
+    dev = "cuda:0"
+    cfg = dict(WL.CONFIGS[args.config])
+    cfg.setdefault("trial_seed0", 1000)
+    N1, N0, Nc, m, n, d, P = (cfg[k] for k in ("N1", "N0", "Nc", "m", "n", "d", "P"))
+
+    A_h, B_h = WL.matmul_inputs(N1, N0, Nc, cfg["seed"])
+    A, B = torch.from_numpy(A_h).to(dev), torch.from_numpy(B_h).to(dev)
+    plan = G.gpd_plan(N1, N0, Nc, m, n, d, P)
+    K = plan.K
+    At = torch.empty((P, N1 // m, N0 // n), dtype=torch.float32, device=dev)
+    Bt = torch.empty((P, N0 // n, Nc // d), dtype=torch.float32, device=dev)
+    Ct = torch.empty((P, N1 // m, Nc // d), dtype=torch.float32, device=dev)
+    C = torch.empty((N1, Nc), dtype=torch.float32, device=dev)
+    masks = [WL.erasure_trial(cfg["trial_seed0"] + t, P, P - K) for t in range(args.warmup + args.steps)]
+
+    def step(t, ev=None):
+        if ev: ev[0].record()
+        G.gpd_encode(plan, A, B, At, Bt)
+        if ev: ev[1].record()
+        G.gpd_worker_products(plan, At, Bt, Ct)
+        if ev: ev[2].record()
+        G.gpd_decode(plan, Ct, present=masks[t], mode=G.GPD_DEC_FIRST_K, C_out=C, want_report=False)
+        if ev: ev[3].record()
+
+    for t in range(args.warmup):
+        step(t)
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for t in range(args.steps):
+        step(args.warmup + t, evs[t])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    enc_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
+    gemm_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in evs]))
+    dec_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in evs]))
+
+    useful_flops = 2.0 * N1 * N0 * Nc
+    worker_flops = 2.0 * P * (N1 // m) * (N0 // n) * (Nc // d)
+    blkC = (N1 // m) * (Nc // d)
+    enc_bytes = 4.0 * (N1 * N0 * (1 + P / (m * n)) + N0 * Nc * (1 + P / (n * d)))
+    dec_bytes = 4.0 * blkC * (K + m * d)
+    value = useful_flops / (ms_step * 1e-3) / 1e12
+    achieved = worker_flops / (gemm_ms * 1e-3) / 1e12
+
+    out = {
+        "metric": "effective coded GEMM TFLOP/s (encode+P products+decode)",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"coded matmul with erasures: A {N1}x{N0}, B {N0}x{Nc} fp32 U[-1,1], "
+                               f"m={m} n={n} d={d} P={P} K={K}, {P - K} seeded stragglers per step, "
+                               f"decode from the first K present nodes"},
+        "stages_ms": {"encode": enc_ms, "worker_products": gemm_ms, "decode": dec_ms},
+        "encode_GBps": enc_bytes / (enc_ms * 1e-3) / 1e9,
+        "decode_GBps": dec_bytes / (dec_ms * 1e-3) / 1e9,
+        "worker_TFLOPs": achieved,
+        "roofline": {"kernel": "gemm_f32_kernel (batched worker products)", "bound": "mfma",
+                     "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": None},
+        "roofline_hbm": {
+            "encode": {"achieved": enc_bytes / (enc_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                       "frac": enc_bytes / (enc_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
+            "decode": {"achieved": dec_bytes / (dec_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                       "frac": dec_bytes / (dec_ms * 1e-3) / 1e9 / PEAK_HBM_GBS}},
+    }
+
+    if not args.no_cpu_baseline:
+        n_threads = os.cpu_count() or 1
+        try:
+            n_threads = len(os.sched_getaffinity(0))
+        except Exception:
+            pass
+        env_threads = os.environ.get("OMP_NUM_THREADS")
+        if env_threads:
+            n_threads = min(n_threads, int(env_threads))
+        base, C_oracle = cpu_baseline(cfg, n_threads)
+        out["cpu_baseline"] = base
+        # the last timed step decoded trial (warmup + steps - 1); re-run trial 0 for the check
+        step(0)
+        G.gpd_decode(plan, Ct, present=WL.erasure_trial(cfg["trial_seed0"], P, P - K),
+                     mode=G.GPD_DEC_FIRST_K, C_out=C, want_report=False)
+        torch.cuda.synchronize()
+        got = C.cpu().numpy().astype(np.float64)
+        out["rel_err_vs_oracle"] = float(np.linalg.norm(got - C_oracle) / np.linalg.norm(C_oracle))
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -226,8 +226,15 @@ extern "C" gpd_status_t gpd_encode(const gpd_plan_t* plc, const float* A, int64_
                                    const float* B, int64_t ldb, void* At, void* Bt) {
   gpd_plan_t* pl = const_cast<gpd_plan_t*>(plc);
   if (!pl) return fail(GPD_E_INVALID, "gpd_encode: null plan");
-  if ((A == nullptr) != (At == nullptr) || (B == nullptr) != (Bt == nullptr))
-    return fail(GPD_E_INVALID, "gpd_encode: A/At and B/Bt must be given in pairs");
+  // a pair is skipped when both of its pointers are NULL or when it has no elements
+  const bool emptyA = pl->prob.N1 == 0 || pl->prob.N0 == 0;
+  const bool emptyB = pl->prob.N0 == 0 || pl->prob.Nc == 0;
+  if (!emptyA && (A == nullptr) != (At == nullptr))
+    return fail(GPD_E_INVALID, "gpd_encode: A and At must be given together");
+  if (!emptyB && (B == nullptr) != (Bt == nullptr))
+    return fail(GPD_E_INVALID, "gpd_encode: B and Bt must be given together");
+  if (emptyA) A = nullptr;
+  if (emptyB) B = nullptr;
   const Code& c = pl->code;
   const bool bf16 = pl->prob.worker_dtype == GPD_BF16;
   ScreenArgs none;
@@ -256,7 +263,10 @@ extern "C" gpd_status_t gpd_encode(const gpd_plan_t* plc, const float* A, int64_
 
 extern "C" gpd_status_t gpd_worker_products(const gpd_plan_t* pl, const void* At, const void* Bt,
                                             float* Ct) {
-  if (!pl || !At || !Bt || !Ct) return fail(GPD_E_INVALID, "gpd_worker_products: null argument");
+  if (!pl) return fail(GPD_E_INVALID, "gpd_worker_products: null plan");
+  if (pl->ahC == 0 || pl->awC == 0) return GPD_OK;                    // no output elements
+  if (!Ct || (pl->awA > 0 && (!At || !Bt)))
+    return fail(GPD_E_INVALID, "gpd_worker_products: null argument");
   GemmArgs g;
   g.A = At; g.B = Bt; g.C = Ct;
   g.M = pl->ahA; g.K = pl->awA; g.N = pl->awB;
@@ -275,7 +285,8 @@ namespace gpd {
 gpd_status_t run_decode(hipStream_t stream, TableRing* ring, const DecodeJob& job, const float* Zt,
                         const uint8_t* present, int mode, int correct, float* out, int64_t ld_out,
                         void* workspace, size_t workspace_bytes, gpd_report_t* report) {
-  if (!Zt || !out) return fail(GPD_E_INVALID, "decode: null buffer");
+  const bool empty = job.bh == 0 || job.bw == 0;
+  if (!empty && (!Zt || !out)) return fail(GPD_E_INVALID, "decode: null buffer");
   if (mode != GPD_DEC_FIRST_K && mode != GPD_DEC_LSQ_ALL) return fail(GPD_E_INVALID, "decode: bad mode");
   if (ld_out < job.grid_c * job.bw) return fail(GPD_E_SHAPE, "decode: output leading dimension too small");
   const bool corr = correct != 0;
@@ -297,6 +308,7 @@ gpd_status_t run_decode(hipStream_t stream, TableRing* ring, const DecodeJob& jo
     report->status = st;
   }
   if (st != GPD_OK) return st;
+  if (empty) return GPD_OK;
   ht.out_rows = job.out_rows; ht.out_cols = job.out_cols;
   CombineTable t;
   st = ring->upload(ht, stream, &t);
