@@ -288,7 +288,9 @@ gpd_status_t run_decode(hipStream_t stream, TableRing* ring, const DecodeJob& jo
   const bool empty = job.bh == 0 || job.bw == 0;
   if (!empty && (!Zt || !out)) return fail(GPD_E_INVALID, "decode: null buffer");
   if (mode != GPD_DEC_FIRST_K && mode != GPD_DEC_LSQ_ALL) return fail(GPD_E_INVALID, "decode: bad mode");
-  if (ld_out < job.grid_c * job.bw) return fail(GPD_E_SHAPE, "decode: output leading dimension too small");
+  // with block limits (zero-padded ragged edges) the caller of run_decode vouches for ld_out
+  if (job.out_cols.empty() && ld_out < job.grid_c * job.bw)
+    return fail(GPD_E_SHAPE, "decode: output leading dimension too small");
   const bool corr = correct != 0;
   if (corr) {
     if (!workspace || workspace_bytes < job.workspace_bytes || ((uintptr_t)workspace & 255))

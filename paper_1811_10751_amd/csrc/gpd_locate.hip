@@ -208,12 +208,31 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
         ++x;
       }
     }
+    // The located entries are now treated as erasures: set them to zero, recompute the
+    // syndrome and solve H_A e' = H z' for the values the code predicts there (-e').  This
+    // keeps all arithmetic at the scale of the clean responses however large the error was.
+    double z_orig[S_MAX];
+    for (int j = 0; j < best_size; ++j) z_orig[j] = zs[supp[j]];
+    __syncthreads();
+    if (lane == 0)
+      for (int j = 0; j < best_size; ++j) zs[supp[j]] = 0.0;
+    __syncthreads();
+    double y2 = 0.0;
+    if (lane < r) {
+      const double* __restrict__ hrow = p.t.H64 + (int64_t)lane * ns;
+      for (int s = 0; s < ns; ++s) y2 += hrow[s] * zs[s];
+    }
+    __syncthreads();
+    ys[lane] = y2;
+    __syncthreads();
     double e_hat[S_MAX];
     support_residual(p.t.H64, r, ns, ys, supp, best_size, e_hat);
     __syncthreads();
     if (lane == 0)
-      for (int j = 0; j < best_size; ++j) zs[supp[j]] -= e_hat[j];
+      for (int j = 0; j < best_size; ++j) zs[supp[j]] = -e_hat[j];
     __syncthreads();
+    // estimated error value = received - predicted
+    for (int j = 0; j < best_size; ++j) e_hat[j] = z_orig[j] + e_hat[j];
     bool write = lane < nout;
     if (write && p.t.out_rows) write = row < p.t.out_rows[lane] && col < p.t.out_cols[lane];
     if (write) {

@@ -1,0 +1,49 @@
+"""Coded MLP training loop: a sequence of C-ABI calls (no arithmetic in Python).
+
+One iteration follows Sec. VII / IX of arXiv 1811.10751: for every layer the coded forward
+step O1 and the element-wise C1; the last-layer error; then for every layer, from the last
+to the first, the coded backward step O2, the coded update O3 and the element-wise C2.
+"""
+from __future__ import annotations
+
+from . import binding as B
+
+
+class CodedMLP:
+    def __init__(self, sizes, batch, m, n, d1, d2, P, worker_dtype=B.GPD_F32, subst=B.GPD_SUB_AUTO,
+                 rho_detect=0.0, stream=None):
+        self.sizes, self.batch = tuple(sizes), batch
+        self.layers = [B.gpd_layer_create(sizes[l + 1], sizes[l], batch, m, n, d1, d2, P,
+                                          worker_dtype=worker_dtype, subst=subst,
+                                          rho_detect=rho_detect, stream=stream)
+                       for l in range(len(sizes) - 1)]
+        self.Wts = [None] * len(self.layers)
+        self.stream = stream
+
+    def encode_weights(self, Ws):
+        """Ws: list of float32 CUDA tensors (N_out x N_in).  Done once before training."""
+        self.Wts = [B.gpd_layer_encode_weights(L, W) for L, W in zip(self.layers, Ws)]
+
+    def decode_weights(self):
+        return [B.gpd_layer_decode_weights(L, Wt) for L, Wt in zip(self.layers, self.Wts)]
+
+    def step(self, X, Y, eta, decay=0.0, correct_errors=False, want_report=False):
+        """One training iteration on the mini-batch X (N_0 x batch), labels Y (N_L x batch).
+        Returns (network output, per-layer list of (forward report, backward report))."""
+        acts = [X]
+        reps = []
+        for L, Wt in zip(self.layers, self.Wts):
+            S, rf = B.gpd_coded_layer_step(L, B.GPD_STEP_FORWARD, Wt, acts[-1],
+                                           correct_errors=correct_errors, want_report=want_report)
+            acts.append(B.gpd_sigmoid_fwd(S, stream=self.stream))
+            reps.append([rf, None])
+        delta = B.gpd_l2_delta(Y, acts[-1], 2.0 / self.batch, stream=self.stream)
+        for l in range(len(self.layers) - 1, -1, -1):
+            C, rb = B.gpd_coded_layer_step(self.layers[l], B.GPD_STEP_BACKWARD_UPDATE, self.Wts[l],
+                                           acts[l], Dlt=delta, eta=eta, decay=decay,
+                                           correct_errors=correct_errors, want_report=want_report,
+                                           skip_output=(l == 0))
+            reps[l][1] = rb
+            if l > 0:
+                delta = B.gpd_sigmoid_bwd(C, acts[l], stream=self.stream)
+        return acts[-1], reps

@@ -1,0 +1,225 @@
+"""GPU parity of the soft-error path (syndrome screen, Algorithm 1 location, correction)
+against the oracle: decisions (flagged / located / failed) must be identical, outputs within
+tolerance.  The oracle always decodes the GPU's own response stack, so both sides see the
+same fp32 words."""
+import numpy as np
+import pytest
+import torch
+
+import gpd_workloads as WL
+import paper_1811_10751_amd as G
+from oracle import gpd_oracle as O
+from gpu_util import DEV, rel_fro, say, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def gpu_responses(N1, N0, Nc, m, n, d, P, seed, **kw):
+    A, B = WL.matmul_inputs(N1, N0, Nc, seed)
+    plan = G.gpd_plan(N1, N0, Nc, m, n, d, P, **kw)
+    At, Bt = G.gpd_encode(plan, to_dev(A), to_dev(B))
+    Ct = G.gpd_worker_products(plan, At, Bt)
+    torch.cuda.synchronize()
+    return A, B, plan, Ct
+
+
+def compare_reports(rep, orep, P):
+    assert rep.n_flagged == orep.n_flagged
+    assert rep.n_failed == orep.n_failed
+    assert [x[:3] for x in rep.located] == [x[:3] for x in orep.located]
+    assert rep.n_located == len(orep.located)
+    assert rep.node_err_count.tolist() == orep.node_err_count.tolist()
+    for g, o in zip(rep.located, orep.located):
+        if np.isnan(o[3]):
+            assert np.isnan(g[3])
+        else:
+            assert abs(g[3] - o[3]) <= 1e-5 * abs(o[3]) + 1e-30
+    assert (rep.status == G.GPD_E_DECODE_FAIL) == (orep.status == "decode_fail")
+    assert rep.n_screened >= rep.n_flagged
+
+
+def failed_mask(orep, shape):
+    m = np.zeros(shape, dtype=bool)
+    for (r, c) in orep.failed:
+        m[r, c] = True
+    return m
+
+
+def check_outputs(C, C_o, orep, plan, tol=2e-5):
+    """Outputs agree except on codewords declared failed (their value is best effort)."""
+    rows, cols = plan.N1 // plan.m, plan.Nc // plan.d
+    bad = np.tile(failed_mask(orep, (rows, cols)), (plan.m, plan.d))
+    Cg = np.where(bad, 0.0, to_np(C).astype(np.float64))
+    Co = np.where(bad, 0.0, C_o)
+    assert rel_fro(Cg, Co) <= tol
+
+
+@pytest.mark.parametrize("t", [0, 1, 2, 3, 4, 5])
+def test_whole_node_gaussian_errors(t):
+    # the paper's error model: every element of t nodes gets additive Gaussian noise;
+    # (P, K) = (14, 9): t <= 4 is corrected, t = 5 may or may not be explained by a smaller
+    # support at the default tolerance; the GPU must take exactly the oracle's decisions.
+    say("whole-node errors t =", t)
+    A, B, plan, Ct = gpu_responses(24, 40, 16, 2, 2, 2, 14, 1)
+    Ct_h = to_np(Ct).copy()
+    if t:
+        bad, noise = WL.gaussian_node_errors(40 + t, 14, t, Ct_h.shape[1:])
+        Ct_h[bad] += noise
+    opl = O.make_plan(2, 2, 2, 14)
+    C_o, orep = O.decode(Ct_h, opl, correct=True)
+    C, rep = G.gpd_decode(plan, to_dev(Ct_h), mode=G.GPD_DEC_LSQ_ALL, correct_errors=True, located_cap=10000)
+    compare_reports(rep, orep, 14)
+    check_outputs(C, C_o, orep, plan)
+    if 0 < t <= 4:
+        assert rep.status == G.GPD_OK and sorted(set(x[0] for x in rep.located)) == sorted(bad.tolist())
+        # against the definition A.B: fp32 rounding of the responses times the amplification of
+        # the decoder that is left once the bad nodes are excluded
+        pm = np.ones(14, dtype=np.uint8)
+        pm[bad] = 0
+        amp = O.amplification(opl, pm, "lsq_all")
+        e2e = rel_fro(to_np(C), O.uncoded_matmul(A, B))
+        say("  vs A.B: %.3g (amp %.3g)" % (e2e, amp))
+        # ... plus what a noise value too small to detect (below tau) leaves behind
+        assert e2e <= max(1e-3, 4 * amp * 2.0 ** -21) + amp * 2.0 ** -12
+    if t == 0:
+        assert rep.n_flagged == 0 and rep.n_screened == 0
+        assert abs(rep.max_syndrome_ratio - orep.max_syndrome_ratio) <= 0.05 * orep.max_syndrome_ratio + 1e-3
+
+
+def test_detection_only_code_reports_failure():
+    A, B, plan, Ct = gpu_responses(32, 32, 32, 2, 2, 2, 10, 3)
+    Ct_h = to_np(Ct).copy()
+    Ct_h[4, 3, 5] += 0.5
+    C_o, orep = O.decode(Ct_h, O.make_plan(2, 2, 2, 10), correct=True)
+    C, rep = G.gpd_decode(plan, to_dev(Ct_h), mode=G.GPD_DEC_LSQ_ALL, correct_errors=True)
+    compare_reports(rep, orep, 10)
+    assert rep.status == G.GPD_E_DECODE_FAIL and rep.n_failed == 1
+    with pytest.raises(G.GpdError) as e:
+        G.gpd_decode(plan, to_dev(Ct_h), mode=G.GPD_DEC_LSQ_ALL, correct_errors=True, raise_on_fail=True)
+    assert e.value.status == G.GPD_E_DECODE_FAIL
+
+
+def test_erasures_and_errors_and_non_finite_together():
+    A, B, plan, Ct = gpu_responses(64, 48, 80, 2, 2, 2, 16, 4)
+    Ct_h = to_np(Ct).copy()
+    present = np.ones(16, dtype=np.uint8)
+    present[[2, 9, 15]] = 0
+    Ct_h[5] += 1.0                       # a whole bad node
+    Ct_h[11, 0, 1] -= 3.0                # a single bad element
+    Ct_h[2] = 1e9                        # erased node: must not matter
+    Ct_h[7, 3, 3] = np.inf
+    Ct_h[0, 3, 3] = np.nan               # two non-finite + node 5 in one codeword = 3 = capacity
+    Ct_h[12, 9, 9] = -np.inf
+    opl = O.make_plan(2, 2, 2, 16)
+    C_o, orep = O.decode(Ct_h, opl, present, correct=True)
+    C, rep = G.gpd_decode(plan, to_dev(Ct_h), present=present, mode=G.GPD_DEC_LSQ_ALL, correct_errors=True,
+                          located_cap=100000)
+    compare_reports(rep, orep, 16)
+    check_outputs(C, C_o, orep, plan)
+    assert rep.status == G.GPD_OK and rep.n_present == 13
+    assert np.all(np.isfinite(to_np(C)))
+    assert rel_fro(to_np(C), O.uncoded_matmul(A, B)) < 1e-3
+
+
+def test_tight_threshold_sends_everything_to_the_fp64_check():
+    # with rho far below fp32 rounding noise the screen passes every codeword on and the fp64
+    # kernel alone decides: its decisions must still equal the oracle's
+    A, B, plan, Ct = gpu_responses(16, 24, 16, 2, 2, 2, 13, 8, rho_detect=1e-9)
+    Ct_h = to_np(Ct).copy()
+    C_o, orep = O.decode(Ct_h, O.make_plan(2, 2, 2, 13), correct=True, rho=1e-9)
+    C, rep = G.gpd_decode(plan, Ct, mode=G.GPD_DEC_LSQ_ALL, correct_errors=True, located_cap=100000)
+    assert rep.n_screened == 64
+    compare_reports(rep, orep, 13)
+    check_outputs(C, C_o, orep, plan)
+
+
+def flip_on_gpu(Ct, flips, cols_total):
+    w = Ct.view(torch.int32).view(Ct.shape[0], -1)
+    for (p, elem, bit) in flips:
+        w[p, elem] ^= (1 << bit) if bit < 31 else -(1 << 31)
+
+
+@pytest.mark.parametrize("size,trials", [(512, 40)])
+def test_bit_flips_medium(size, trials):
+    # cfg4's fault model at a size the oracle decodes in full every trial
+    A, B, plan, Ct = gpu_responses(size, size, size, 2, 2, 2, 16, 0)
+    opl = O.make_plan(2, 2, 2, 16)
+    C_def = O.uncoded_matmul(A, B)
+    blk = (size // 2) ** 2
+    n_flips = n_loc = 0
+    for t in range(trials):
+        flips = WL.bitflip_trial(5000 + t, 16, blk, 6, prob=0.25)
+        Cf = Ct.clone()
+        flip_on_gpu(Cf, flips, size // 2)
+        torch.cuda.synchronize()
+        C, rep = G.gpd_decode(plan, Cf, mode=G.GPD_DEC_LSQ_ALL, correct_errors=True)
+        C_o, orep = O.decode(to_np(Cf), opl, correct=True)
+        compare_reports(rep, orep, 16)
+        check_outputs(C, C_o, orep, plan)
+        assert rep.status == G.GPD_OK
+        n_flips += len(flips)
+        n_loc += rep.n_located
+        # what stays uncorrected is below the detection threshold: harmless at this size
+        assert rel_fro(to_np(C), C_def) < 1e-3
+    say("bit flips injected", n_flips, "located", n_loc)
+    assert n_flips > trials and 0 < n_loc <= n_flips
+
+
+def test_cfg4_full_size_bit_flips():
+    # 4096^2, P = 16: the GPU decodes all 2048^2 codewords per trial; the oracle decodes the
+    # whole stack once (no faults) and, per trial, exactly the touched codewords (every other
+    # codeword holds the same words as in the fault-free stack).
+    c = WL.CONFIGS[4]
+    A, B, plan, Ct = gpu_responses(c["N1"], c["N0"], c["Nc"], c["m"], c["n"], c["d"], c["P"], c["seed"])
+    opl = O.make_plan(c["m"], c["n"], c["d"], c["P"])
+    rows = cols = 2048
+    ws = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device=DEV)
+    C0, rep0 = G.gpd_decode(plan, Ct, mode=G.GPD_DEC_LSQ_ALL, correct_errors=True, workspace=ws)
+    say("fault-free: screened", rep0.n_screened, "flagged", rep0.n_flagged, "max ratio", rep0.max_syndrome_ratio)
+    Ct_h = to_np(Ct)
+    C_o, orep0 = O.decode(Ct_h, opl, correct=True)
+    say("oracle fault-free: flagged", orep0.n_flagged, "max ratio", orep0.max_syndrome_ratio)
+    assert rep0.n_flagged == orep0.n_flagged == 0 and rep0.status == G.GPD_OK
+    assert rel_fro(to_np(C0), C_o) < 2e-5
+    assert rel_fro(to_np(C0), O.uncoded_matmul(A, B)) < 1e-3
+    assert abs(rep0.max_syndrome_ratio - orep0.max_syndrome_ratio) < 0.05 * orep0.max_syndrome_ratio
+    n_trials = c["trials"]
+    n_flips = n_loc = n_marginal = 0
+    Cf = Ct.clone()
+    C = torch.empty_like(C0)
+    Ct_flat = Ct.view(16, -1)
+    useful = sorted(int(e) for e in opl.eC.ravel())
+    for t in range(n_trials):
+        flips = WL.bitflip_trial(c["trial_seed0"] + t, c["P"], rows * cols, c["P"] - plan.K - 1, c["flip_prob"])
+        flip_on_gpu(Cf, flips, cols)
+        _, rep = G.gpd_decode(plan, Cf, mode=G.GPD_DEC_LSQ_ALL, correct_errors=True, workspace=ws, C_out=C)
+        elems = sorted(set(e for (_, e, _) in flips))
+        touched = set()
+        if elems:
+            sub = to_np(Ct_flat[:, torch.tensor(elems, device=DEV)]).reshape(16, 1, len(elems)).copy()
+            sub_f = WL.apply_bitflips(sub, [(p, elems.index(e), b) for (p, e, b) in flips])
+            coeffs, orep = O.decode_coefficients(sub_f, opl.points, opl.K, useful, correct=True)
+            want = [(node, elems[cc] // cols, elems[cc] % cols) for (node, _, cc, _) in orep.located]
+            assert sorted(want) == [x[:3] for x in rep.located], (t, flips)
+            assert rep.n_flagged == orep.n_flagged and rep.n_failed == orep.n_failed == 0
+            for cc, e in enumerate(elems):
+                r_, c_ = divmod(e, cols)
+                for i in range(2):
+                    for k in range(2):
+                        o = coeffs[int(opl.eC[i, k])][0, cc]
+                        g = float(C[i * rows + r_, k * cols + c_])
+                        assert np.isfinite(g) and abs(g - o) <= 1e-3 * max(1.0, abs(o)), (t, e, g, o)
+                        touched.add((i * rows + r_, k * cols + c_))
+        else:
+            assert rep.n_flagged == 0 and rep.n_located == 0
+        # every untouched codeword decodes to exactly the fault-free words
+        diff = torch.nonzero(C != C0).cpu().numpy()
+        assert len(diff) <= len(touched)
+        for (r_, c_) in diff:
+            assert (int(r_), int(c_)) in touched
+        n_flips += len(flips)
+        n_loc += rep.n_located
+        flip_on_gpu(Cf, flips, cols)             # undo
+    say("cfg4:", n_trials, "trials,", n_flips, "flips,", n_loc, "located")
+    assert torch.equal(Cf, Ct)
+    assert n_flips > 300 and n_loc > 100

@@ -1,0 +1,161 @@
+"""GPU parity of the coded DNN layer step (forward O1, backward O2, coded update O3) against
+the oracle, fp32 workers: small shapes with padding and both substitutions, a few training
+iterations of a small MLP, and the B=1 benchmark MLP (4096-4096-4096-10) at full size."""
+import numpy as np
+import pytest
+import torch
+
+import gpd_workloads as WL
+import paper_1811_10751_amd as G
+from paper_1811_10751_amd.mlp import CodedMLP
+from oracle import gpd_oracle as O
+from gpu_util import DEV, rel_fro, say, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+SUB = {"u=v^n": G.GPD_SUB_U_VN, "v=u^m": G.GPD_SUB_V_UM, "auto": G.GPD_SUB_AUTO}
+
+CASES = [
+    # N_out, N_in, batch, m, n, d1, d2, P, subst
+    (64, 96, 1, 4, 2, 1, 1, 24, "auto"),          # cfg2's code at a small size (skinny kernels)
+    (64, 96, 1, 4, 2, 1, 1, 24, "u=v^n"),
+    (10, 96, 1, 4, 2, 1, 1, 24, "auto"),          # 10 rows, m = 4: padded to 12
+    (70, 50, 4, 2, 4, 1, 1, 20, "u=v^n"),         # N_in = 50, n = 4: padded to 52; batch 4 skinny
+    (130, 260, 8, 2, 2, 2, 2, 16, "u=v^n"),       # d1 = d2 = 2, skinny kernels
+    (66, 36, 8, 2, 2, 1, 4, 24, "u=v^n"),         # d2 = 4: K_b = 18, ill-conditioned (amp ~1e5)
+    (300, 200, 24, 2, 4, 1, 1, 32, "auto"),       # cfg3's code, MFMA GEMM path, ragged tiles
+    (256, 384, 48, 2, 2, 2, 3, 20, "v=u^m"),      # GEMM path with d1, d2 > 1
+]
+
+
+@pytest.mark.parametrize("N_out,N_in,batch,m,n,d1,d2,P,subst", CASES)
+def test_layer_forward_backward_update(N_out, N_in, batch, m, n, d1, d2, P, subst):
+    say("layer case", N_out, N_in, batch, m, n, d1, d2, P, subst)
+    rng = np.random.default_rng(N_out + 7 * N_in + batch)
+    W = (rng.standard_normal((N_out, N_in)) / np.sqrt(N_in)).astype(np.float32)
+    X = rng.uniform(-1, 1, (N_in, batch)).astype(np.float32)
+    D = rng.standard_normal((N_out, batch)).astype(np.float32)
+    olp = O.make_layer_plan(N_out, N_in, batch, m, n, d1, d2, P, subst)
+    L = G.gpd_layer_create(N_out, N_in, batch, m, n, d1, d2, P, subst=SUB[subst])
+    assert (L.Kf, L.Kb) == (olp.Kf, olp.Kb)
+    assert (L.wt_rows, L.wt_cols) == (olp.N_out_pad // m, olp.N_in_pad // n)
+
+    Wt = G.gpd_layer_encode_weights(L, to_dev(W))
+    torch.cuda.synchronize()
+    Wt_o = O.layer_encode_weights(W, olp)
+    assert np.abs(to_np(Wt) - Wt_o).max() <= 4e-7 * m * n * np.abs(W).max()
+    Wt_h = to_np(Wt).copy()
+
+    # weights back from the coded blocks (all nodes, then exactly mn of them)
+    W_back = G.gpd_layer_decode_weights(L, Wt)
+    assert rel_fro(to_np(W_back), W) < 1e-5
+    present = np.zeros(P, dtype=np.uint8)
+    present[rng.choice(P, m * n, replace=False)] = 1
+    W_back = G.gpd_layer_decode_weights(L, Wt, present=present)
+    W_back_o = O.layer_decode_weights(Wt_h, olp, present)
+    amp_w = np.linalg.norm(np.linalg.pinv(O.vandermonde(olp.points[present.astype(bool)], m * n)), axis=1).max()
+    say("  weight decode from mn nodes: err %.3g (amp %.3g)" % (rel_fro(to_np(W_back), W_back_o), amp_w))
+    assert rel_fro(to_np(W_back), W_back_o) <= 2e-6 * max(amp_w, 1.0)
+
+    # forward: oracle works from the GPU's own coded weights (fp32 words)
+    S, _ = G.gpd_coded_layer_step(L, G.GPD_STEP_FORWARD, Wt, to_dev(X))
+    S_o, _ = O.layer_forward(Wt_h, X, olp)
+    ampf = O.amplification(olp.fwd, None, "lsq_all")
+    say("  forward err %.3g (amp %.3g)" % (rel_fro(to_np(S), S_o), ampf))
+    assert rel_fro(to_np(S), S_o) <= 2e-6 * max(ampf, 1.0)
+    assert rel_fro(to_np(S), W.astype(np.float64) @ X) <= max(1e-3, 4e-6 * ampf)
+
+    # backward + update in one call; backward uses the pre-update weights
+    eta, decay = 0.05, 0.01
+    C, _ = G.gpd_coded_layer_step(L, G.GPD_STEP_BACKWARD_UPDATE, Wt, to_dev(X), Dlt=to_dev(D), eta=eta, decay=decay)
+    torch.cuda.synchronize()
+    C_o, _ = O.layer_backward(Wt_h, D, olp)
+    Db = np.linalg.pinv(O.vandermonde(olp.points, olp.Kb))
+    ampb = max(np.linalg.norm(Db[int(e)]) for e in olp.eCb.ravel())
+    say("  backward err %.3g (amp %.3g)" % (rel_fro(to_np(C), C_o), ampb))
+    assert rel_fro(to_np(C), C_o) <= 2e-6 * max(ampb, 1.0)
+    assert rel_fro(to_np(C), W.astype(np.float64).T @ D) <= max(2e-3, 4e-6 * ampb)
+    Wt2_o = O.layer_update(Wt_h, D, X, olp, eta, np.float32(decay))
+    scale = np.abs(Wt2_o).max()
+    assert np.abs(to_np(Wt) - Wt2_o).max() <= 1e-5 * scale
+    # the updated blocks are still a codeword: decoding them gives the updated W
+    W2 = (1 - decay) * W.astype(np.float64) + eta * D.astype(np.float64) @ X.astype(np.float64).T
+    assert rel_fro(to_np(G.gpd_layer_decode_weights(L, Wt)), W2) < 1e-4
+
+    # update only (out skipped)
+    Wt_before = to_np(Wt).copy()
+    out, _ = G.gpd_coded_layer_step(L, G.GPD_STEP_BACKWARD_UPDATE, Wt, to_dev(X), Dlt=to_dev(D), eta=eta,
+                                    decay=0.0, skip_output=True)
+    assert out is None
+    Wt3_o = O.layer_update(Wt_before, D, X, olp, eta, 0.0)
+    assert np.abs(to_np(Wt) - Wt3_o).max() <= 1e-5 * scale
+
+
+def test_forward_with_erasures_and_a_corrupted_node():
+    # stragglers among the nodes + one node whose stored W~_p was corrupted (shows up as an
+    # erroneous response in step O1 and is located there)
+    N_out, N_in, P = 64, 96, 24
+    rng = np.random.default_rng(3)
+    W = (rng.standard_normal((N_out, N_in)) / 8).astype(np.float32)
+    X = rng.uniform(-1, 1, (N_in, 1)).astype(np.float32)
+    olp = O.make_layer_plan(N_out, N_in, 1, 4, 2, 1, 1, P, "auto")
+    L = G.gpd_layer_create(N_out, N_in, 1, 4, 2, 1, 1, P)
+    Wt = G.gpd_layer_encode_weights(L, to_dev(W))
+    Wt[7] += 0.05 * torch.randn_like(Wt[7])
+    present = np.ones(P, dtype=np.uint8)
+    present[[1, 20]] = 0
+    S, rep = G.gpd_coded_layer_step(L, G.GPD_STEP_FORWARD, Wt, to_dev(X), present=present, correct_errors=True,
+                                    want_report=True)
+    S_o, orep = O.layer_forward(to_np(Wt), X, olp, present, correct=True)
+    assert rep.status == G.GPD_OK and rep.n_present == 22
+    assert [x[:3] for x in rep.located] == [x[:3] for x in orep.located]
+    assert set(x[0] for x in rep.located) == {7}
+    assert rel_fro(to_np(S), S_o) < 1e-4
+    assert rel_fro(to_np(S), W.astype(np.float64) @ X) < 1e-3
+
+
+@pytest.mark.parametrize("batch,m,n,P", [(1, 4, 2, 24), (4, 2, 4, 32), (24, 2, 4, 32)])
+def test_small_mlp_training_tracks_the_oracle(batch, m, n, P):
+    sizes = (96, 128, 64, 10)
+    Ws = WL.mlp_init(sizes, seed=2)
+    Ws = [(w * 8).astype(np.float32) for w in Ws]
+    olps = [O.make_layer_plan(sizes[l + 1], sizes[l], batch, m, n, 1, 1, P, "auto") for l in range(3)]
+    mlp = CodedMLP(sizes, batch, m, n, 1, 1, P)
+    mlp.encode_weights([to_dev(w) for w in Ws])
+    Wts_o = [to_np(wt).astype(np.float64) for wt in mlp.Wts]
+    Ws_plain = [w.astype(np.float64) for w in Ws]
+    eta = 0.5
+    for step in range(6):
+        X, Y = WL.mlp_batch(2, step, sizes[0], sizes[-1], batch)
+        yhat, _ = mlp.step(to_dev(X), to_dev(Y), eta)
+        Wts_o, yhat_o, _ = O.mlp_coded_step(Wts_o, olps, X, Y, np.float32(eta))
+        Ws_plain, yhat_p, _ = O.mlp_uncoded_step(Ws_plain, X, Y, np.float32(eta))
+        e1, e2 = rel_fro(to_np(yhat), yhat_o), rel_fro(to_np(yhat), yhat_p)
+        say("  step", step, "yhat err vs coded oracle %.3g, vs plain SGD %.3g" % (e1, e2))
+        assert e1 < 1e-3 and e2 < 1e-3
+    for l in range(3):
+        assert rel_fro(to_np(mlp.Wts[l]), Wts_o[l]) < 1e-3
+    for W_dec, W_ref in zip(mlp.decode_weights(), Ws_plain):
+        assert rel_fro(to_np(W_dec), W_ref) < 1e-3
+
+
+def test_cfg2_full_size_steps():
+    c = WL.CONFIGS[2]
+    sizes, batch, m, n, P = c["sizes"], c["batch"], c["m"], c["n"], c["P"]
+    Ws = WL.mlp_init(sizes, c["seed"])
+    olps = [O.make_layer_plan(sizes[l + 1], sizes[l], batch, m, n, 1, 1, P, "auto") for l in range(3)]
+    mlp = CodedMLP(sizes, batch, m, n, 1, 1, P)
+    mlp.encode_weights([to_dev(w) for w in Ws])
+    assert [(L.Kf, L.Kb) for L in mlp.layers] == [(12, 11)] * 3
+    Wts_o = [to_np(wt).astype(np.float64) for wt in mlp.Wts]
+    Ws_plain = [w.astype(np.float64) for w in Ws]
+    for step in range(3):
+        X, Y = WL.mlp_batch(c["seed"], step, sizes[0], sizes[-1], batch)
+        yhat, _ = mlp.step(to_dev(X), to_dev(Y), c["eta"])
+        Wts_o, yhat_o, tr = O.mlp_coded_step(Wts_o, olps, X, Y, np.float32(c["eta"]))
+        Ws_plain, yhat_p, _ = O.mlp_uncoded_step(Ws_plain, X, Y, np.float32(c["eta"]))
+        e1, e2 = rel_fro(to_np(yhat), yhat_o), rel_fro(to_np(yhat), yhat_p)
+        say("  cfg2 step", step, "yhat err vs coded oracle %.3g, vs plain SGD %.3g" % (e1, e2))
+        assert e1 < 1e-3 and e2 < 1e-3
+    for l in range(3):
+        assert rel_fro(to_np(mlp.Wts[l]), Wts_o[l]) < 1e-5
