@@ -214,6 +214,14 @@ gpd_status_t gpd_coded_layer_step(gpd_layer_t* layer, int32_t phase, float* Wt,
                                   float* out, const uint8_t* present, int32_t correct_errors,
                                   void* workspace, size_t workspace_bytes, gpd_report_t* report);
 
+/* Where the per-node intermediates of the last gpd_coded_layer_step live inside the caller's
+ * workspace: fp32 stacks [P][rows][cols] at byte_offset.  which: 0 = X~_p (encoded input),
+ * 1 = S~_p (forward node outputs, what the all-gather of Sec. VII would carry), 2 = Delta~_p
+ * stored (N_out/m) x (batch/d2), 3 = C~_p stored (N_in/n) x (batch/d2) (backward node
+ * outputs), 4 = Dhat_p, 5 = Xhat_p (update operands).  For inspection and fault injection. */
+gpd_status_t gpd_layer_workspace_view(const gpd_layer_t* layer, int32_t which, size_t* byte_offset,
+                                      int64_t* rows, int64_t* cols);
+
 void gpd_layer_destroy(gpd_layer_t* layer);
 
 /* Element-wise steps C1 / C2 and the last-layer error (Sec. II background; logistic f):

@@ -30,7 +30,7 @@ EXPORTS = [
     "gpd_plan", "gpd_plan_info", "gpd_plan_tables", "gpd_plan_destroy", "gpd_encode",
     "gpd_worker_products", "gpd_decode", "gpd_layer_create", "gpd_layer_info",
     "gpd_layer_encode_weights", "gpd_layer_decode_weights", "gpd_coded_layer_step",
-    "gpd_layer_destroy", "gpd_sigmoid_fwd", "gpd_sigmoid_bwd", "gpd_l2_delta",
+    "gpd_layer_workspace_view", "gpd_layer_destroy", "gpd_sigmoid_fwd", "gpd_sigmoid_bwd", "gpd_l2_delta",
     "gpd_host_code", "gpd_host_decode_matrices", "gpd_last_error", "gpd_version",
 ]
 
@@ -101,6 +101,7 @@ def load_library():
     lib.gpd_layer_decode_weights.argtypes = [vp, vp, vp, vp, i64]
     lib.gpd_coded_layer_step.argtypes = [vp, i32, vp, vp, vp, C.c_float, C.c_float, vp, vp, i32,
                                          vp, sz, C.POINTER(_Report)]
+    lib.gpd_layer_workspace_view.argtypes = [vp, i32, C.POINTER(sz), C.POINTER(i64), C.POINTER(i64)]
     lib.gpd_layer_destroy.argtypes = [vp]
     lib.gpd_layer_destroy.restype = None
     lib.gpd_sigmoid_fwd.argtypes = [vp, vp, i64, vp]
@@ -337,6 +338,16 @@ class Layer:
         if self._ws is None:
             self._ws = torch.empty(max(self.workspace_bytes, 256), dtype=torch.uint8, device=device)
         return self._ws
+
+    def view(self, which, device):
+        """fp32 tensor [P, rows, cols] aliasing one of the per-node intermediates in the workspace
+        (0 X~, 1 S~, 2 Delta~, 3 C~, 4 Dhat, 5 Xhat)."""
+        import torch
+        off, r, c = C.c_size_t(), C.c_int64(), C.c_int64()
+        _check(load_library().gpd_layer_workspace_view(self.handle, which, C.byref(off), C.byref(r), C.byref(c)))
+        ws = self.workspace(device)
+        n = self.P * r.value * c.value
+        return ws[off.value:off.value + 4 * n].view(torch.float32).view(self.P, r.value, c.value)
 
     def close(self):
         if self.handle:

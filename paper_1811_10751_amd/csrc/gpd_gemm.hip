@@ -202,6 +202,276 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams g) {
     }
 }
 
+// ------------------------------------------------------------------ bf16 path
+//
+// v_mfma_f32_32x32x16_bf16: same 128 x 128 workgroup tile and 2 x 2 blocks per wavefront,
+// 32 k-values per LDS stage.  Both operand tiles live in LDS as bf16, k-contiguous
+// ([row][32 k], row stride 80 bytes), so a lane fetches its 8 consecutive k-values with one
+// 128-bit read.  Operands may be fp32 in memory (rounded to nearest even on the way to LDS:
+// the coded weights stay fp32 in HBM) and may be k-strided in memory (B of a plain product,
+// A of the backward product W~^T Delta~): those are transposed while they are written to
+// LDS, with a per-lane rotation of the store order that keeps the 32-bit stores of a
+// half-wavefront on 32 different banks.
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int HBK = 32;                 // k-values per stage
+constexpr int HSTRIDE = HBK + 8;        // bf16 elements per LDS row (80 bytes)
+constexpr int HTILE = 128 * HSTRIDE;    // bf16 elements per operand tile
+
+enum { SRC_F32_KC = 0, SRC_BF16_KC = 1, SRC_F32_RC = 2, SRC_BF16_RC = 3 };
+
+struct HGemmParams {
+  const void* A; const void* B; float* C;
+  int M, N, K;
+  int64_t lda, ldb, ldc;
+  int64_t sA, sB, sC;
+  int tiles_m, tiles_n, total_tiles, tiles_per_xcd;
+  float alpha, beta;
+};
+
+__device__ __forceinline__ uint32_t bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x0040u;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  return bf16_bits(lo) | (bf16_bits(hi) << 16);
+}
+
+// up to 4 consecutive floats; elements at or beyond nvalid read as zero
+template <int MODE>
+__device__ __forceinline__ float4 load4f(const float* p, int nvalid) {
+  if (MODE == 0 || (nvalid >= 4 && (((uintptr_t)p) & 15) == 0)) return *reinterpret_cast<const float4*>(p);
+  float v[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int e = 0; e < 4; ++e) if (e < nvalid) v[e] = p[e];
+  return make_float4(v[0], v[1], v[2], v[3]);
+}
+// up to 8 consecutive bf16
+template <int MODE>
+__device__ __forceinline__ uint4 load8h(const uint16_t* p, int nvalid) {
+  if (MODE == 0 || (nvalid >= 8 && (((uintptr_t)p) & 15) == 0)) return *reinterpret_cast<const uint4*>(p);
+  uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+  for (int e = 0; e < 8; ++e) if (e < nvalid) w[e >> 1] |= (uint32_t)p[e] << (16 * (e & 1));
+  return make_uint4(w[0], w[1], w[2], w[3]);
+}
+__device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
+
+// One operand tile of 128 rows x 32 k in flight: 16 bf16 per thread, still in source form.
+template <int SRC> struct HStage;
+template <> struct HStage<SRC_F32_KC> { float4 v[4]; };
+template <> struct HStage<SRC_BF16_KC> { uint4 v[2]; };
+template <> struct HStage<SRC_F32_RC> { float4 v[2][2]; };
+template <> struct HStage<SRC_BF16_RC> { uint4 v[2]; };
+
+// base: start of the operand for this batch entry; "row" is the m (or n) index, k the
+// contraction index.  KC sources are [row][k] with leading dimension ld, RC sources [k][row].
+template <int SRC, int MODE>
+__device__ __forceinline__ void hload(HStage<SRC>& st, const void* base, int64_t ld, int row0, int k0,
+                                      int nrows, int nk, int tid) {
+  if constexpr (SRC == SRC_F32_KC) {
+    const float* b = (const float*)base;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int f = tid + 256 * q;
+      const int row = row0 + (f >> 3), k = k0 + 4 * (f & 7);
+      const int nv = (MODE == 0) ? 4 : (row < nrows ? clampi(nk - k, 0, 4) : 0);
+      st.v[q] = (MODE == 0 || nv > 0) ? load4f<MODE>(b + (int64_t)row * ld + k, nv) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  } else if constexpr (SRC == SRC_BF16_KC) {
+    const uint16_t* b = (const uint16_t*)base;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const int f = tid + 256 * q;
+      const int row = row0 + (f >> 2), k = k0 + 8 * (f & 3);
+      const int nv = (MODE == 0) ? 8 : (row < nrows ? clampi(nk - k, 0, 8) : 0);
+      st.v[q] = (MODE == 0 || nv > 0) ? load8h<MODE>(b + (int64_t)row * ld + k, nv) : make_uint4(0u, 0u, 0u, 0u);
+    }
+  } else if constexpr (SRC == SRC_F32_RC) {
+    const float* b = (const float*)base;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const int f = tid + 256 * q;
+      const int kp = (f & 3) + 4 * (f >> 7), rq = (f >> 2) & 31;
+      const int row = row0 + 4 * rq;
+#pragma unroll
+      for (int par = 0; par < 2; ++par) {
+        const int k = k0 + 2 * kp + par;
+        const int nv = (MODE == 0) ? 4 : (k < nk ? clampi(nrows - row, 0, 4) : 0);
+        st.v[q][par] = (MODE == 0 || nv > 0) ? load4f<MODE>(b + (int64_t)k * ld + row, nv)
+                                             : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+    }
+  } else {
+    const uint16_t* b = (const uint16_t*)base;
+    const int kp = (tid & 3) + 4 * (tid >> 6), rq = (tid >> 2) & 15;
+    const int row = row0 + 8 * rq;
+#pragma unroll
+    for (int par = 0; par < 2; ++par) {
+      const int k = k0 + 2 * kp + par;
+      const int nv = (MODE == 0) ? 8 : (k < nk ? clampi(nrows - row, 0, 8) : 0);
+      st.v[par] = (MODE == 0 || nv > 0) ? load8h<MODE>(b + (int64_t)k * ld + row, nv) : make_uint4(0u, 0u, 0u, 0u);
+    }
+  }
+}
+
+// Writes the staged tile to LDS as bf16 [row][k] (row stride HSTRIDE elements).
+template <int SRC>
+__device__ __forceinline__ void hstore(const HStage<SRC>& st, uint16_t* __restrict__ lds, int tid) {
+  if constexpr (SRC == SRC_F32_KC) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int f = tid + 256 * q;
+      uint2 w;
+      w.x = pack_bf16(st.v[q].x, st.v[q].y);
+      w.y = pack_bf16(st.v[q].z, st.v[q].w);
+      *reinterpret_cast<uint2*>(lds + (f >> 3) * HSTRIDE + 4 * (f & 7)) = w;
+    }
+  } else if constexpr (SRC == SRC_BF16_KC) {
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const int f = tid + 256 * q;
+      *reinterpret_cast<uint4*>(lds + (f >> 2) * HSTRIDE + 8 * (f & 3)) = st.v[q];
+    }
+  } else if constexpr (SRC == SRC_F32_RC) {
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const int f = tid + 256 * q;
+      const int kp = (f & 3) + 4 * (f >> 7), rq = (f >> 2) & 31;
+      const float lo[4] = {st.v[q][0].x, st.v[q][0].y, st.v[q][0].z, st.v[q][0].w};
+      const float hi[4] = {st.v[q][1].x, st.v[q][1].y, st.v[q][1].z, st.v[q][1].w};
+      const int rot = (rq >> 1) & 3;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int ee = (e + rot) & 3;
+        float l = lo[0], h = hi[0];
+#pragma unroll
+        for (int c = 1; c < 4; ++c) { if (ee == c) { l = lo[c]; h = hi[c]; } }
+        *reinterpret_cast<uint32_t*>(lds + (4 * rq + ee) * HSTRIDE + 2 * kp) = pack_bf16(l, h);
+      }
+    }
+  } else {
+    const int kp = (tid & 3) + 4 * (tid >> 6), rq = (tid >> 2) & 15;
+    const uint32_t lo[4] = {st.v[0].x, st.v[0].y, st.v[0].z, st.v[0].w};
+    const uint32_t hi[4] = {st.v[1].x, st.v[1].y, st.v[1].z, st.v[1].w};
+    const int rot = rq & 7;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int ee = (e + rot) & 7;
+      uint32_t l = lo[0], h = hi[0];
+#pragma unroll
+      for (int c = 1; c < 4; ++c) { if ((ee >> 1) == c) { l = lo[c]; h = hi[c]; } }
+      const uint32_t sh = 16u * (ee & 1);
+      const uint32_t w = ((l >> sh) & 0xffffu) | (((h >> sh) & 0xffffu) << 16);
+      *reinterpret_cast<uint32_t*>(lds + (8 * rq + ee) * HSTRIDE + 2 * kp) = w;
+    }
+  }
+}
+
+template <int ASRC, int BSRC, int MODE>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(HGemmParams g) {
+  __shared__ __attribute__((aligned(16))) uint16_t lds[2][2][HTILE];
+
+  const int xcd = blockIdx.x & 7;
+  const int slot = blockIdx.x >> 3;
+  const int tile = xcd * g.tiles_per_xcd + slot;
+  if (tile >= g.total_tiles) return;
+  const int per_batch = g.tiles_m * g.tiles_n;
+  const int p = tile / per_batch;
+  const int rem = tile - p * per_batch;
+  const int tm = rem / g.tiles_n;
+  const int tn = rem - tm * g.tiles_n;
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  constexpr int A_ES = (ASRC == SRC_BF16_KC || ASRC == SRC_BF16_RC) ? 2 : 4;
+  constexpr int B_ES = (BSRC == SRC_BF16_KC || BSRC == SRC_BF16_RC) ? 2 : 4;
+  const char* A = (const char*)g.A + (int64_t)p * g.sA * A_ES;
+  const char* B = (const char*)g.B + (int64_t)p * g.sB * B_ES;
+  float* __restrict__ C = g.C + (int64_t)p * g.sC;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 31, lg = lane >> 5;
+  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const int nchunks = (g.K + HBK - 1) / HBK;
+  HStage<ASRC> sa;
+  HStage<BSRC> sb;
+  hload<ASRC, MODE>(sa, A, g.lda, m0, 0, g.M, g.K, tid);
+  hload<BSRC, MODE>(sb, B, g.ldb, n0, 0, g.N, g.K, tid);
+  hstore<ASRC>(sa, lds[0][0], tid);
+  hstore<BSRC>(sb, lds[0][1], tid);
+  __syncthreads();
+
+  for (int c = 0; c < nchunks; ++c) {
+    const int cur = c & 1;
+    if (c + 1 < nchunks) {
+      hload<ASRC, MODE>(sa, A, g.lda, m0, (c + 1) * HBK, g.M, g.K, tid);
+      hload<BSRC, MODE>(sb, B, g.ldb, n0, (c + 1) * HBK, g.N, g.K, tid);
+    }
+    const uint16_t* __restrict__ as = lds[cur][0];
+    const uint16_t* __restrict__ bs = lds[cur][1];
+#pragma unroll
+    for (int h = 0; h < HBK / 16; ++h) {
+      union Frag { uint4 u; bf16x8 v; };
+      Frag fa[2], fb[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+        fa[i].u = *reinterpret_cast<const uint4*>(as + (wm + 32 * i + li) * HSTRIDE + 16 * h + 8 * lg);
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        fb[j].u = *reinterpret_cast<const uint4*>(bs + (wn + 32 * j + li) * HSTRIDE + 16 * h + 8 * lg);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i].v, fb[j].v, acc[i][j], 0, 0, 0);
+    }
+    if (c + 1 < nchunks) {
+      hstore<ASRC>(sa, lds[cur ^ 1][0], tid);
+      hstore<BSRC>(sb, lds[cur ^ 1][1], tid);
+    }
+    __syncthreads();
+  }
+
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int col = n0 + wn + 32 * j + li;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * lg + (v & 3);
+        if (MODE == 0 || (row < g.M && col < g.N)) {
+          float* dst = C + (int64_t)row * g.ldc + col;
+          float val = g.alpha * acc[i][j][v];
+          if (g.beta != 0.f) val = fmaf(g.beta, *dst, val);
+          *dst = val;
+        }
+      }
+    }
+}
+
+template <int ASRC, int BSRC>
+gpd_status_t launch_bf16_t(hipStream_t stream, const HGemmParams& p, int mode) {
+  dim3 grid((unsigned)(p.tiles_per_xcd * 8)), block(256);
+  if (mode == 0) hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 0>), grid, block, 0, stream, p);
+  else hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 1>), grid, block, 0, stream, p);
+  GPD_HIP(hipGetLastError());
+  return GPD_OK;
+}
+
 template <bool A_KC, bool B_KC>
 gpd_status_t launch_f32(hipStream_t stream, const GemmParams& p, int mode) {
   dim3 grid((unsigned)(p.tiles_per_xcd * 8)), block(256);
@@ -219,8 +489,10 @@ gpd_status_t launch_gemm(hipStream_t stream, const GemmArgs& a) {
   if (a.M == 0 || a.N == 0 || a.batch == 0) return GPD_OK;
   if (a.M > 0x7fffffff || a.N > 0x7fffffff || a.K > 0x7fffffff)
     return fail(GPD_E_SHAPE, "gemm: dimension above 2^31");
-  if (a.a_bf16 || a.b_bf16 || a.mfma_bf16)
-    return fail(GPD_E_UNSUPPORTED, "gemm: bf16 path not built yet");
+  if ((a.a_bf16 || a.b_bf16) && !a.mfma_bf16)
+    return fail(GPD_E_INVALID, "gemm: bf16 operands need the bf16 multiply");
+  if (a.mfma_bf16 && (a.transB || (a.transA && a.a_bf16)))
+    return fail(GPD_E_UNSUPPORTED, "gemm: this operand layout has no bf16 kernel");
   // operand shapes must match what the kernel and its grid assume
   const int64_t a_rows = a.transA ? a.K : a.M, a_cols = a.transA ? a.M : a.K;
   const int64_t b_rows = a.transB ? a.N : a.K, b_cols = a.transB ? a.K : a.N;
@@ -232,6 +504,33 @@ gpd_status_t launch_gemm(hipStream_t stream, const GemmArgs& a) {
     return fail(GPD_E_SHAPE, "gemm: batch stride of B overlaps");
   if (a.batch > 1 && a.strideC < (a.M - 1) * a.ldc + a.N)
     return fail(GPD_E_SHAPE, "gemm: batch stride of C overlaps");
+
+  if (a.mfma_bf16) {
+    HGemmParams h;
+    h.A = a.A; h.B = a.B; h.C = a.C;
+    h.M = (int)a.M; h.N = (int)a.N; h.K = (int)a.K;
+    h.lda = a.lda; h.ldb = a.ldb; h.ldc = a.ldc;
+    h.sA = a.strideA; h.sB = a.strideB; h.sC = a.strideC;
+    h.tiles_m = (int)((a.M + BM - 1) / BM);
+    h.tiles_n = (int)((a.N + BN - 1) / BN);
+    const int64_t tot = (int64_t)h.tiles_m * h.tiles_n * a.batch;
+    if (tot > 0x0fffffff) return fail(GPD_E_SHAPE, "gemm: too many tiles");
+    h.total_tiles = (int)tot;
+    h.tiles_per_xcd = (int)((tot + 7) / 8);
+    h.alpha = a.alpha; h.beta = a.beta;
+    const int a_es = a.a_bf16 ? 2 : 4, b_es = a.b_bf16 ? 2 : 4;
+    const bool al = ((uintptr_t)a.A % 16 == 0) && ((uintptr_t)a.B % 16 == 0) &&
+                    (a.lda * a_es) % 16 == 0 && (a.ldb * b_es) % 16 == 0 &&
+                    (a.strideA * a_es) % 16 == 0 && (a.strideB * b_es) % 16 == 0;
+    const bool fullh = a.M % BM == 0 && a.N % BN == 0 && a.K % HBK == 0 && a.K > 0;
+    const int mode = (al && fullh) ? 0 : 1;
+    if (!a.transA && !a.a_bf16 && !a.b_bf16) return launch_bf16_t<SRC_F32_KC, SRC_F32_RC>(stream, h, mode);
+    if (!a.transA && !a.a_bf16 && a.b_bf16) return launch_bf16_t<SRC_F32_KC, SRC_BF16_RC>(stream, h, mode);
+    if (!a.transA && a.a_bf16 && a.b_bf16) return launch_bf16_t<SRC_BF16_KC, SRC_BF16_RC>(stream, h, mode);
+    if (!a.transA && a.a_bf16 && !a.b_bf16) return launch_bf16_t<SRC_BF16_KC, SRC_F32_RC>(stream, h, mode);
+    if (a.transA && !a.b_bf16) return launch_bf16_t<SRC_F32_RC, SRC_F32_RC>(stream, h, mode);
+    return launch_bf16_t<SRC_F32_RC, SRC_BF16_RC>(stream, h, mode);
+  }
 
   GemmParams p;
   p.A = (const float*)a.A; p.B = (const float*)a.B; p.C = a.C;

@@ -308,6 +308,21 @@ extern "C" gpd_status_t gpd_layer_info(const gpd_layer_t* L, int32_t* Kf, int32_
   return GPD_OK;
 }
 
+extern "C" gpd_status_t gpd_layer_workspace_view(const gpd_layer_t* L, int32_t which, size_t* byte_offset,
+                                                 int64_t* rows, int64_t* cols) {
+  if (!L || !byte_offset || !rows || !cols) return fail(GPD_E_INVALID, "gpd_layer_workspace_view: null argument");
+  switch (which) {
+    case 0: *byte_offset = L->off_Xt; *rows = L->wc; *cols = L->nb1; break;
+    case 1: *byte_offset = L->off_St; *rows = L->wr; *cols = L->nb1; break;
+    case 2: *byte_offset = L->off_Dt; *rows = L->wr; *cols = L->nb2; break;
+    case 3: *byte_offset = L->off_Ct; *rows = L->wc; *cols = L->nb2; break;
+    case 4: *byte_offset = L->off_Dh; *rows = L->wr; *cols = L->desc.batch; break;
+    case 5: *byte_offset = L->off_Xh; *rows = L->wc; *cols = L->desc.batch; break;
+    default: return fail(GPD_E_INVALID, "gpd_layer_workspace_view: unknown buffer %d", which);
+  }
+  return GPD_OK;
+}
+
 extern "C" void gpd_layer_destroy(gpd_layer_t* L) {
   if (!L) return;
   L->ring.destroy();

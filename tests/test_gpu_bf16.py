@@ -1,0 +1,154 @@
+"""GPU parity of the bf16 worker products (bf16 MFMA, fp32 accumulation), stage by stage:
+encode (fp32 -> bf16 round-to-nearest-even), products (the oracle multiplies the GPU's own
+bf16 operands in fp64), decode (the oracle decodes the GPU's own responses).  End-to-end
+figures against the exact product are printed and bounded by the rounding of the operands
+times the amplification of the decoder."""
+import numpy as np
+import pytest
+import torch
+
+import gpd_workloads as WL
+import paper_1811_10751_amd as G
+from paper_1811_10751_amd.mlp import CodedMLP
+from oracle import gpd_oracle as O
+from gpu_util import DEV, rel_fro, say, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def bf16_to_f64(t):
+    return t.to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+@pytest.mark.parametrize("N1,N0,Nc,m,n,d,P", [(256, 256, 256, 2, 2, 2, 12), (512, 320, 384, 2, 2, 2, 16),
+                                              (300, 204, 140, 2, 2, 2, 11), (264, 520, 136, 1, 4, 1, 9)])
+def test_bf16_matmul_stagewise(N1, N0, Nc, m, n, d, P):
+    say("bf16 matmul", N1, N0, Nc, m, n, d, P)
+    A, B = WL.matmul_inputs(N1, N0, Nc, seed=N1)
+    opl = O.make_plan(m, n, d, P)
+    plan = G.gpd_plan(N1, N0, Nc, m, n, d, P, worker_dtype=G.GPD_BF16)
+    At, Bt = G.gpd_encode(plan, to_dev(A), to_dev(B))
+    assert At.dtype == torch.bfloat16 and Bt.dtype == torch.bfloat16
+    # encode: equal to the oracle's bf16 rounding except where fp32 summation order moves a value
+    # across a bf16 rounding boundary (then off by one bf16 step)
+    for got, want in ((bf16_to_f64(At), O.round_to_bf16(O.encode_A(A, opl))),
+                      (bf16_to_f64(Bt), O.round_to_bf16(O.encode_B(B, opl)))):
+        diff = np.abs(got - want)
+        assert (diff > 0).mean() < 1e-3
+        # one bf16 step, or (for sums that cancel to almost nothing) the fp32 rounding of the sum
+        assert np.all(diff <= 2.0 ** -7 * np.abs(want) + 4e-7 * 4)
+    # products
+    Ct = G.gpd_worker_products(plan, At, Bt)
+    torch.cuda.synchronize()
+    Ct_o = O.worker_products(bf16_to_f64(At), bf16_to_f64(Bt))
+    assert rel_fro(to_np(Ct), Ct_o) < 2e-6
+    # decode of the GPU's responses
+    for present in (None, WL.erasure_trial(3, P, P - opl.K)):
+        C, _ = G.gpd_decode(plan, Ct, present=present, mode=G.GPD_DEC_LSQ_ALL)
+        C_o, _ = O.decode(to_np(Ct), opl, present, "lsq_all")
+        amp = O.amplification(opl, present, "lsq_all")
+        assert rel_fro(to_np(C), C_o) <= 1e-6 * max(amp, 1.0)
+    # end to end vs the exact product: bf16 operand rounding (2^-9 each) amplified by the decoder
+    C, _ = G.gpd_decode(plan, Ct, mode=G.GPD_DEC_LSQ_ALL)
+    e2e = rel_fro(to_np(C), O.uncoded_matmul(A, B))
+    amp = O.amplification(opl, None, "lsq_all")
+    say("  bf16 end-to-end vs exact A.B: %.3g (amp %.3g)" % (e2e, amp))
+    assert e2e <= 4 * amp * 2.0 ** -9
+
+
+LAYER_CASES = [
+    (256, 384, 128, 2, 4, 1, 1, 32),      # cfg3's code, full tiles
+    (300, 200, 24, 2, 4, 1, 1, 32),       # ragged tiles
+    (130, 260, 48, 2, 2, 2, 3, 20),       # d1, d2 > 1
+]
+
+
+@pytest.mark.parametrize("N_out,N_in,batch,m,n,d1,d2,P", LAYER_CASES)
+def test_bf16_layer_stagewise(N_out, N_in, batch, m, n, d1, d2, P):
+    say("bf16 layer", N_out, N_in, batch, m, n, d1, d2, P)
+    rng = np.random.default_rng(N_out + N_in)
+    W = (rng.standard_normal((N_out, N_in)) / np.sqrt(N_in)).astype(np.float32)
+    X = rng.uniform(-1, 1, (N_in, batch)).astype(np.float32)
+    D = rng.standard_normal((N_out, batch)).astype(np.float32)
+    olp = O.make_layer_plan(N_out, N_in, batch, m, n, d1, d2, P, "auto")
+    L = G.gpd_layer_create(N_out, N_in, batch, m, n, d1, d2, P, worker_dtype=G.GPD_BF16)
+    Wt = G.gpd_layer_encode_weights(L, to_dev(W))
+    Wt_h = to_np(Wt).copy()
+
+    # ---- forward
+    S, _ = G.gpd_coded_layer_step(L, G.GPD_STEP_FORWARD, Wt, to_dev(X))
+    torch.cuda.synchronize()
+    Xt = to_np(L.view(0, DEV))
+    St = to_np(L.view(1, DEV))
+    assert np.abs(Xt - O.layer_encode_x(X, olp)).max() <= 4e-7 * n * d1          # fp32 encode
+    St_o = O.worker_products(Wt_h, Xt, operands="bf16")                          # bf16 products
+    assert rel_fro(St, St_o) < 2e-6
+    S_o, _ = O.decode(St, olp.fwd, None, "lsq_all")                              # fp32 decode
+    ampf = O.amplification(olp.fwd, None, "lsq_all")
+    assert rel_fro(to_np(S), S_o[:N_out]) <= 1e-6 * max(ampf, 1.0)
+    e2e = rel_fro(to_np(S), W.astype(np.float64) @ X)
+    say("  forward vs exact W X: %.3g (amp %.3g)" % (e2e, ampf))
+    assert e2e <= 4 * ampf * 2.0 ** -9
+
+    # ---- backward + update
+    eta, decay = 0.05, 0.01
+    C, _ = G.gpd_coded_layer_step(L, G.GPD_STEP_BACKWARD_UPDATE, Wt, to_dev(X), Dlt=to_dev(D), eta=eta, decay=decay)
+    torch.cuda.synchronize()
+    Dt = to_np(L.view(2, DEV))                      # [P][N_out/m][batch/d2]
+    Ct = to_np(L.view(3, DEV))                      # [P][N_in/n][batch/d2]
+    Dt_o = np.transpose(O.layer_encode_delta(D, olp), (0, 2, 1))
+    assert np.abs(Dt - Dt_o).max() <= 4e-7 * m * d2 * np.abs(D).max()
+    Ct_o = np.matmul(np.transpose(O.round_to_bf16(Wt_h), (0, 2, 1)), O.round_to_bf16(Dt))
+    assert rel_fro(Ct, Ct_o) < 2e-6
+    useful = sorted(set(int(e) for e in olp.eCb.ravel()))
+    coeffs, _ = O.decode_coefficients(Ct, olp.points, olp.Kb, useful, mode="lsq_all")
+    rows, cols = Ct.shape[1], Ct.shape[2]
+    C_o = np.zeros((n * rows, d2 * cols))
+    for j in range(n):
+        for k in range(d2):
+            C_o[j * rows:(j + 1) * rows, k * cols:(k + 1) * cols] = coeffs[int(olp.eCb[k, j])]
+    Db = np.linalg.pinv(O.vandermonde(olp.points, olp.Kb))
+    ampb = max(np.linalg.norm(Db[int(e)]) for e in olp.eCb.ravel())
+    assert rel_fro(to_np(C), C_o[:N_in]) <= 1e-6 * max(ampb, 1.0)
+    say("  backward vs exact W^T D: %.3g (amp %.3g)" % (rel_fro(to_np(C), W.astype(np.float64).T @ D), ampb))
+    # the update stays fp32
+    Wt2_o = O.layer_update(Wt_h, D, X, olp, eta, np.float32(decay))
+    assert np.abs(to_np(Wt) - Wt2_o).max() <= 1e-5 * np.abs(Wt2_o).max()
+
+
+def test_cfg3_full_size_one_layer_step():
+    # cfg3's middle layer (8192 x 8192, batch 256, m=2, n=4, P=32), bf16 products: stage-wise
+    # parity on the full-size launch configuration, with the oracle checking sampled node outputs
+    c = WL.CONFIGS[3]
+    N, batch, m, n, P = 8192, c["batch"], c["m"], c["n"], c["P"]
+    rng = np.random.default_rng(c["seed"])
+    W = (rng.standard_normal((N, N)) / 64).astype(np.float32)
+    X = rng.uniform(-1, 1, (N, batch)).astype(np.float32)
+    D = (rng.standard_normal((N, batch)) / 16).astype(np.float32)
+    olp = O.make_layer_plan(N, N, batch, m, n, 1, 1, P, "auto")
+    L = G.gpd_layer_create(N, N, batch, m, n, 1, 1, P, worker_dtype=G.GPD_BF16)
+    assert (L.Kf, L.Kb) == (11, 12)
+    Wd = to_dev(W)
+    Wt = G.gpd_layer_encode_weights(L, Wd)
+    S, _ = G.gpd_coded_layer_step(L, G.GPD_STEP_FORWARD, Wt, to_dev(X))
+    torch.cuda.synchronize()
+    Xt, St = to_np(L.view(0, DEV)), to_np(L.view(1, DEV))
+    sample_p = [0, 13, 31]
+    rows_s = rng.choice(N // m, 64, replace=False)
+    for p in sample_p:
+        ref = O.round_to_bf16(to_np(Wt[p][torch.from_numpy(rows_s).to(DEV)])) @ O.round_to_bf16(Xt[p])
+        assert rel_fro(St[p][rows_s], ref) < 2e-6
+    S_o, _ = O.decode(St, olp.fwd, None, "lsq_all")
+    assert rel_fro(to_np(S), S_o) <= 1e-6 * O.amplification(olp.fwd, None, "lsq_all")
+    say("  cfg3 L2 forward vs exact: %.3g" % rel_fro(to_np(S), W.astype(np.float64) @ X))
+    Wt_rows_before = {p: to_np(Wt[p][torch.from_numpy(rows_s).to(DEV)]).copy() for p in sample_p}
+    C, _ = G.gpd_coded_layer_step(L, G.GPD_STEP_BACKWARD_UPDATE, Wt, to_dev(X), Dlt=to_dev(D), eta=0.01, decay=0.0)
+    torch.cuda.synchronize()
+    Dt, Ct = to_np(L.view(2, DEV)), to_np(L.view(3, DEV))
+    Dh, Xh = to_np(L.view(4, DEV)), to_np(L.view(5, DEV))
+    for p in sample_p:
+        # update on sampled rows: W~_p[r,:] + eta * Dh_p[r,:] Xh_p^T
+        ref = Wt_rows_before[p] + np.float32(0.01) * (Dh[p][rows_s].astype(np.float64) @ Xh[p].astype(np.float64).T)
+        got = to_np(Wt[p][torch.from_numpy(rows_s).to(DEV)])
+        assert np.abs(got - ref).max() <= 1e-5 * np.abs(ref).max()
+    say("  cfg3 L2 backward vs exact: %.3g" % rel_fro(to_np(C), W.astype(np.float64).T @ D))
