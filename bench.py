@@ -56,13 +56,65 @@ def cpu_baseline(cfg, n_threads):
     }, C
 
 
+def bench_mlp(args, cfg):
+    """Coded MLP training iterations (workloads 2 and 3): extra evidence for the layer-step
+    kernels; not the headline metric."""
+    import numpy as np
+    import torch
+
+    import gpd_workloads as WL
+    import paper_1811_10751_amd as G
+    from paper_1811_10751_amd.mlp import CodedMLP
+
+    dev = "cuda:0"
+    sizes, batch, m, n, P = cfg["sizes"], cfg["batch"], cfg["m"], cfg["n"], cfg["P"]
+    wd = G.GPD_BF16 if cfg["worker"] == "bf16" else G.GPD_F32
+    mlp = CodedMLP(sizes, batch, m, n, cfg["d1"], cfg["d2"], P, worker_dtype=wd)
+    Ws = WL.mlp_init(sizes, cfg["seed"])
+    mlp.encode_weights([torch.from_numpy(w).to(dev) for w in Ws])
+    data = [WL.mlp_batch(cfg["seed"], t, sizes[0], sizes[-1], batch) for t in range(4)]
+    data = [(torch.from_numpy(x).to(dev), torch.from_numpy(y).to(dev)) for x, y in data]
+    use_graph = args.graph
+    graph = None
+    if use_graph:
+        Xs, Ys = data[0][0].clone(), data[0][1].clone()
+        side = torch.cuda.Stream()
+        raise SystemExit("bench.py: --graph needs layers created on the capture stream; not wired up")
+    for t in range(args.warmup):
+        mlp.step(*data[t % 4], cfg["eta"])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(args.steps):
+        mlp.step(*data[t % 4], cfg["eta"])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms = (t1 - t0) * 1e3 / args.steps
+    flops = sum(6.0 * sizes[l + 1] * sizes[l] * batch for l in range(len(sizes) - 1))
+    wbytes = sum(4.0 * P * L.wt_rows * L.wt_cols for L in mlp.layers)
+    alg_bytes = 3.0 * wbytes          # forward reads W~ once; backward+update reads and rewrites it
+    out = {"metric": "coded MLP training step (forward + backward + coded update, all layers)",
+           "value": flops / (ms * 1e-3) / 1e12, "unit": "TFLOP/s (useful, uncoded flops)", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+           "dtype": cfg["worker"], "data": "synthetic",
+           "config": {"workload": f"coded MLP {sizes} batch {batch} m={m} n={n} P={P} "
+                                  f"K_f={mlp.layers[0].Kf} K_b={mlp.layers[0].Kb}"},
+           "weight_stream_GBps": alg_bytes / (ms * 1e-3) / 1e9,
+           "weight_stream_bytes_per_step": alg_bytes}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=1, help="matmul workload index (0 or 1)")
+    ap.add_argument("--config", type=int, default=1,
+                    help="workload index: 0/1 coded matmul (1 = headline), 2/3 coded MLP training")
+    ap.add_argument("--graph", action="store_true", help="(MLP workloads) replay the step as a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 256 MiB device copy 5 times (reference for scaling the "
+                         "FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (all P nodes are simulated on it); "
@@ -80,7 +132,19 @@ def main():
         sys.exit(1)
     G.load_library()
     dev = "cuda:0"
+    if args.copy_calibration:
+        src = torch.rand(64 * 1024 * 1024, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4,
+                                               "launches": 5}}))
+        return
     cfg = dict(WL.CONFIGS[args.config])
+    if cfg["kind"] == "mlp":
+        bench_mlp(args, cfg)
+        return
     cfg.setdefault("trial_seed0", 1000)
     N1, N0, Nc, m, n, d, P = (cfg[k] for k in ("N1", "N0", "Nc", "m", "n", "d", "P"))
 

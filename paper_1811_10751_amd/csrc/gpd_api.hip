@@ -17,6 +17,33 @@ gpd_status_t TableRing::init(size_t bytes_per_slot) {
   GPD_HIP(hipHostMalloc((void**)&host, slot_bytes * kSlots, hipHostMallocDefault));
   GPD_HIP(hipMalloc((void**)&dev, slot_bytes * kSlots));
   for (int i = 0; i < kSlots; ++i) GPD_HIP(hipEventCreateWithFlags(&ev[i], hipEventDisableTiming));
+  GPD_HIP(hipMalloc((void**)&arena, kArenaBytes));
+  arena_used = 0;
+  return GPD_OK;
+}
+
+gpd_status_t TableRing::cached(const std::string& key,
+                               const std::function<gpd_status_t(HostCombineTable*)>& build,
+                               hipStream_t stream, CombineTable* out) {
+  auto it = cache.find(key);
+  if (it != cache.end()) { *out = it->second; return GPD_OK; }
+  HostCombineTable ht;
+  gpd_status_t st = build(&ht);
+  if (st != GPD_OK) return st;
+  const size_t need = ht.bytes();
+  if (arena_used + need > kArenaBytes || need > slot_bytes) return upload(ht, stream, out);
+  // stage in a pinned ring slot, copy to the arena in stream order (no host wait)
+  const int sl = next;
+  next = (next + 1) % kSlots;
+  if (used[sl]) GPD_HIP(hipEventSynchronize(ev[sl]));
+  char* h = host + (size_t)sl * slot_bytes;
+  char* d = arena + arena_used;
+  *out = ht.pack(h, d);
+  GPD_HIP(hipMemcpyAsync(d, h, need, hipMemcpyHostToDevice, stream));
+  GPD_HIP(hipEventRecord(ev[sl], stream));
+  used[sl] = true;
+  arena_used += need;
+  cache.emplace(key, *out);
   return GPD_OK;
 }
 
@@ -25,6 +52,8 @@ void TableRing::destroy() {
     if (ev[i]) { (void)hipEventDestroy(ev[i]); ev[i] = nullptr; }
   if (host) { (void)hipHostFree(host); host = nullptr; }
   if (dev) { (void)hipFree(dev); dev = nullptr; }
+  if (arena) { (void)hipFree(arena); arena = nullptr; }
+  cache.clear();
 }
 
 gpd_status_t TableRing::upload(const HostCombineTable& t, hipStream_t stream, CombineTable* out) {
@@ -240,18 +269,26 @@ extern "C" gpd_status_t gpd_encode(const gpd_plan_t* plc, const float* A, int64_
   ScreenArgs none;
   if (A) {
     if (lda < pl->prob.N0) return fail(GPD_E_SHAPE, "lda smaller than N0");
-    HostCombineTable ht = encode_table(c.pts, c.eA, c.m, c.n, pl->ahA, pl->awA, lda);
     CombineTable t;
-    gpd_status_t st = pl->ring.upload(ht, pl->stream, &t);
+    std::string key("encA");
+    key_add(&key, lda);
+    gpd_status_t st = pl->ring.cached(key, [&](HostCombineTable* ht) {
+      *ht = encode_table(c.pts, c.eA, c.m, c.n, pl->ahA, pl->awA, lda);
+      return GPD_OK;
+    }, pl->stream, &t);
     if (st != GPD_OK) return st;
     st = launch_combine(pl->stream, t, A, lda, At, pl->awA, bf16, pl->ahA, pl->awA, none);
     if (st != GPD_OK) return st;
   }
   if (B) {
     if (ldb < pl->prob.Nc) return fail(GPD_E_SHAPE, "ldb smaller than Nc");
-    HostCombineTable ht = encode_table(c.pts, c.eB, c.n, c.d, pl->ahB, pl->awB, ldb);
     CombineTable t;
-    gpd_status_t st = pl->ring.upload(ht, pl->stream, &t);
+    std::string key("encB");
+    key_add(&key, ldb);
+    gpd_status_t st = pl->ring.cached(key, [&](HostCombineTable* ht) {
+      *ht = encode_table(c.pts, c.eB, c.n, c.d, pl->ahB, pl->awB, ldb);
+      return GPD_OK;
+    }, pl->stream, &t);
     if (st != GPD_OK) return st;
     st = launch_combine(pl->stream, t, B, ldb, Bt, pl->awB, bf16, pl->ahB, pl->awB, none);
     if (st != GPD_OK) return st;
@@ -296,24 +333,39 @@ gpd_status_t run_decode(hipStream_t stream, TableRing* ring, const DecodeJob& jo
     if (!workspace || workspace_bytes < job.workspace_bytes || ((uintptr_t)workspace & 255))
       return fail(GPD_E_WORKSPACE, "decode: workspace of %zu aligned bytes needed", job.workspace_bytes);
   }
-  HostCombineTable ht;
+  const int P = (int)job.pts->size();
   int n_present = 0;
-  gpd_status_t st = decode_table(*job.pts, job.K, present, !corr && mode == GPD_DEC_FIRST_K, corr,
-                                 job.useful, job.grid_r, job.grid_c, job.bh, job.bw, ld_out, &ht,
-                                 &n_present);
+  for (int p = 0; p < P; ++p) n_present += (!present || present[p]) ? 1 : 0;
   if (report) {
     gpd_located_t* keep_ptr = report->located;
     const int64_t keep_cap = report->located_cap;
     std::memset(report, 0, sizeof(*report));
     report->located = keep_ptr; report->located_cap = keep_cap;
     report->n_present = n_present;
-    report->status = st;
   }
-  if (st != GPD_OK) return st;
+  if (n_present < job.K) {
+    if (report) report->status = GPD_E_TOO_FEW;
+    return fail(GPD_E_TOO_FEW, "%d responses present, %d needed", n_present, job.K);
+  }
   if (empty) return GPD_OK;
-  ht.out_rows = job.out_rows; ht.out_cols = job.out_cols;
+  const bool first_k = !corr && mode == GPD_DEC_FIRST_K;
+  std::string key("dec");
+  key_add(&key, job.K); key_add(&key, job.grid_r); key_add(&key, job.grid_c);
+  key_add(&key, job.bh); key_add(&key, job.bw); key_add(&key, ld_out);
+  key_add(&key, first_k); key_add(&key, corr);
+  key_add_bytes(&key, job.useful.data(), job.useful.size() * sizeof(int));
+  key_add_bytes(&key, job.out_rows.data(), job.out_rows.size() * sizeof(int32_t));
+  key_add_bytes(&key, job.out_cols.data(), job.out_cols.size() * sizeof(int32_t));
+  for (int p = 0; p < P; ++p) key.push_back((!present || present[p]) ? 1 : 0);
   CombineTable t;
-  st = ring->upload(ht, stream, &t);
+  gpd_status_t st = ring->cached(key, [&](HostCombineTable* ht) {
+    gpd_status_t s2 = decode_table(*job.pts, job.K, present, first_k, corr, job.useful, job.grid_r,
+                                   job.grid_c, job.bh, job.bw, ld_out, ht, nullptr);
+    if (s2 != GPD_OK) return s2;
+    ht->out_rows = job.out_rows; ht->out_cols = job.out_cols;
+    return GPD_OK;
+  }, stream, &t);
+  if (report) report->status = st;
   if (st != GPD_OK) return st;
 
   ScreenArgs sc;

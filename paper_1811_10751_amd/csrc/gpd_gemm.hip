@@ -15,10 +15,19 @@ namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int BM = 128, BN = 128, BK = 16;
+constexpr int BM = 128, BN = 128;      // workgroup tile of the bf16 kernel
+constexpr int BK = 16;                 // k-values per LDS stage (fp32 kernel)
 constexpr int KC_STRIDE = BK + 4;      // row stride (floats) of a k-contiguous tile  [rows][BK]
-constexpr int MC_STRIDE = BM + 4;      // row stride of an m/n-contiguous tile        [BK][rows]
-constexpr int TILE_FLOATS = (BM * KC_STRIDE > BK * MC_STRIDE) ? BM * KC_STRIDE : BK * MC_STRIDE;
+
+// The fp32 kernel comes in two workgroup shapes:
+//   small: 128 x 128 tile, 2 x 2 wavefronts (3 workgroups per CU): many tiles, for small or
+//          ragged problems;
+//   large: 256 x 256 tile, 4 x 4 wavefronts (one 1024-thread workgroup per CU): a quarter of
+//          the global-to-LDS traffic per flop; used when both M and N are multiples of 256 and
+//          there are enough tiles to fill the chip.
+// floats of one LDS operand tile of ROWS rows: k-contiguous [ROWS][BK+4] or row-contiguous [BK][ROWS+4]
+template <bool KCONTIG, int ROWS>
+constexpr int tile_floats() { return KCONTIG ? ROWS * KC_STRIDE : BK * (ROWS + 4); }
 
 struct GemmParams {
   const float* A; const float* B; float* C;
@@ -30,33 +39,33 @@ struct GemmParams {
   float alpha, beta;
 };
 
-// Loads a 128 x 16 operand tile as two float4 per thread.
-//   KCONTIG: memory is [rows][k] (ld = stride between rows): thread f -> row f/4, k 4*(f%4)
-//   else   : memory is [k][rows]:                            thread f -> k f/32, row 4*(f%32)
+// One ROWS x 16 operand tile in flight: ROWS*4/NT float4 per thread (NT threads).
+//   KCONTIG: memory is [rows][k] (ld = stride between rows): item f -> row f/4, k 4*(f%4)
+//   else   : memory is [k][rows]:                  item f -> k f/(ROWS/4), row 4*(f%(ROWS/4))
 // MODE 0: tile fully inside, 16-byte aligned; 1: guarded, aligned; 2: guarded, scalar.
-struct TileRegs { float4 q0, q1; };
+template <int ROWS, int NT> struct TileRegs { float4 q[ROWS * 4 / NT]; };
 
-template <bool KCONTIG, int MODE>
-__device__ __forceinline__ TileRegs load_tile(const float* __restrict__ base, int64_t ld, int row0,
-                                              int k0, int nrows, int nk, int tid) {
-  float4 r[2];
+template <bool KCONTIG, int MODE, int ROWS, int NT>
+__device__ __forceinline__ TileRegs<ROWS, NT> load_tile(const float* __restrict__ base, int64_t ld, int row0,
+                                                        int k0, int nrows, int nk, int tid) {
+  TileRegs<ROWS, NT> t;
 #pragma unroll
-  for (int q = 0; q < 2; ++q) {
-    const int f = tid + 256 * q;
+  for (int q = 0; q < ROWS * 4 / NT; ++q) {
+    const int f = tid + NT * q;
     int row, k;
     if constexpr (KCONTIG) { row = row0 + (f >> 2); k = k0 + 4 * (f & 3); }
-    else { k = k0 + (f >> 5); row = row0 + 4 * (f & 31); }
+    else { k = k0 + f / (ROWS / 4); row = row0 + 4 * (f % (ROWS / 4)); }
     if constexpr (MODE == 0) {
       const float* p = KCONTIG ? base + (int64_t)row * ld + k : base + (int64_t)k * ld + row;
-      r[q] = *reinterpret_cast<const float4*>(p);
+      t.q[q] = *reinterpret_cast<const float4*>(p);
     } else {
       float v[4] = {0.f, 0.f, 0.f, 0.f};
       if constexpr (KCONTIG) {
         if (row < nrows) {
           const float* p = base + (int64_t)row * ld + k;
           if (MODE == 1 && k + 3 < nk) {
-            const float4 t = *reinterpret_cast<const float4*>(p);
-            v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+            const float4 x = *reinterpret_cast<const float4*>(p);
+            v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
           } else {
 #pragma unroll
             for (int e = 0; e < 4; ++e) if (k + e < nk) v[e] = p[e];
@@ -66,39 +75,36 @@ __device__ __forceinline__ TileRegs load_tile(const float* __restrict__ base, in
         if (k < nk) {
           const float* p = base + (int64_t)k * ld + row;
           if (MODE == 1 && row + 3 < nrows) {
-            const float4 t = *reinterpret_cast<const float4*>(p);
-            v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+            const float4 x = *reinterpret_cast<const float4*>(p);
+            v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
           } else {
 #pragma unroll
             for (int e = 0; e < 4; ++e) if (row + e < nrows) v[e] = p[e];
           }
         }
       }
-      r[q] = make_float4(v[0], v[1], v[2], v[3]);
+      t.q[q] = make_float4(v[0], v[1], v[2], v[3]);
     }
   }
-  TileRegs t;
-  t.q0 = r[0]; t.q1 = r[1];
   return t;
 }
 
-template <bool KCONTIG>
-__device__ __forceinline__ void store_tile(float* __restrict__ lds, int tid, const TileRegs& t) {
+template <bool KCONTIG, int ROWS, int NT>
+__device__ __forceinline__ void store_tile(float* __restrict__ lds, int tid, const TileRegs<ROWS, NT>& t) {
 #pragma unroll
-  for (int q = 0; q < 2; ++q) {
-    const int f = tid + 256 * q;
-    const float4 v = q == 0 ? t.q0 : t.q1;
+  for (int q = 0; q < ROWS * 4 / NT; ++q) {
+    const int f = tid + NT * q;
     if constexpr (KCONTIG) {
-      *reinterpret_cast<float4*>(lds + (f >> 2) * KC_STRIDE + 4 * (f & 3)) = v;
+      *reinterpret_cast<float4*>(lds + (f >> 2) * KC_STRIDE + 4 * (f & 3)) = t.q[q];
     } else {
-      *reinterpret_cast<float4*>(lds + (f >> 5) * MC_STRIDE + 4 * (f & 31)) = v;
+      *reinterpret_cast<float4*>(lds + (f / (ROWS / 4)) * (ROWS + 4) + 4 * (f % (ROWS / 4))) = t.q[q];
     }
   }
 }
 
 // Fragment of one 32-row block for the four MFMA steps of one 8-wide k group `h`:
 // step t multiplies k = 8h + t (lanes 0-31) and k = 8h + 4 + t (lanes 32-63).
-template <bool KCONTIG>
+template <bool KCONTIG, int ROWS>
 __device__ __forceinline__ void read_frag(const float* __restrict__ lds, int row, int h, int g,
                                           float (&f)[4]) {
   if constexpr (KCONTIG) {
@@ -106,15 +112,21 @@ __device__ __forceinline__ void read_frag(const float* __restrict__ lds, int row
     f[0] = t.x; f[1] = t.y; f[2] = t.z; f[3] = t.w;
   } else {
 #pragma unroll
-    for (int t = 0; t < 4; ++t) f[t] = lds[(8 * h + 4 * g + t) * MC_STRIDE + row];
+    for (int t = 0; t < 4; ++t) f[t] = lds[(8 * h + 4 * g + t) * (ROWS + 4) + row];
   }
 }
 
 // A_KC: op(A) rows are k-contiguous in memory (A not transposed).
 // B_KC: op(B) columns are k-contiguous in memory (B transposed, stored N x K).
-template <bool A_KC, bool B_KC, int MODE>
-__global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams g) {
-  __shared__ __attribute__((aligned(16))) float lds[2][2][TILE_FLOATS];
+// TBM x TBN: workgroup tile; the WGM x WGN wavefronts own (TBM/WGM) x (TBN/WGN) sub-tiles.
+template <bool A_KC, bool B_KC, int MODE, int TBM, int TBN, int WGM, int WGN>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_f32_kernel(GemmParams g) {
+  constexpr int NT = 64 * WGM * WGN;
+  constexpr int TA = tile_floats<A_KC, TBM>();
+  constexpr int TB = tile_floats<B_KC, TBN>();
+  constexpr int WM = TBM / WGM, WN = TBN / WGN, MI = WM / 32, NJ = WN / 32;
+  __shared__ __attribute__((aligned(16))) float lds_a[2][TA];
+  __shared__ __attribute__((aligned(16))) float lds_b[2][TB];
 
   // XCD-aware tile order: consecutive workgroup ids go to different XCDs (each with its own
   // L2), so give every XCD one contiguous range of tiles.
@@ -127,7 +139,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams g) {
   const int rem = tile - p * per_batch;
   const int tm = rem / g.tiles_n;
   const int tn = rem - tm * g.tiles_n;
-  const int m0 = tm * BM, n0 = tn * BN;
+  const int m0 = tm * TBM, n0 = tn * TBN;
 
   const float* __restrict__ A = g.A + (int64_t)p * g.sA;
   const float* __restrict__ B = g.B + (int64_t)p * g.sB;
@@ -136,58 +148,58 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams g) {
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int li = lane & 31, lg = lane >> 5;
-  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+  const int wm = (wave / WGN) * WM, wn = (wave % WGN) * WN;
 
-  floatx16 acc[2][2];
+  floatx16 acc[MI][NJ];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   const int nchunks = (g.K + BK - 1) / BK;
-  TileRegs ra = load_tile<A_KC, MODE>(A, g.lda, m0, 0, g.M, g.K, tid);
-  TileRegs rb = load_tile<B_KC, MODE>(B, g.ldb, n0, 0, g.N, g.K, tid);
-  store_tile<A_KC>(lds[0][0], tid, ra);
-  store_tile<B_KC>(lds[0][1], tid, rb);
+  TileRegs<TBM, NT> ra = load_tile<A_KC, MODE, TBM, NT>(A, g.lda, m0, 0, g.M, g.K, tid);
+  TileRegs<TBN, NT> rb = load_tile<B_KC, MODE, TBN, NT>(B, g.ldb, n0, 0, g.N, g.K, tid);
+  store_tile<A_KC, TBM, NT>(lds_a[0], tid, ra);
+  store_tile<B_KC, TBN, NT>(lds_b[0], tid, rb);
   __syncthreads();
 
   for (int c = 0; c < nchunks; ++c) {
     const int cur = c & 1;
     if (c + 1 < nchunks) {
-      ra = load_tile<A_KC, MODE>(A, g.lda, m0, (c + 1) * BK, g.M, g.K, tid);
-      rb = load_tile<B_KC, MODE>(B, g.ldb, n0, (c + 1) * BK, g.N, g.K, tid);
+      ra = load_tile<A_KC, MODE, TBM, NT>(A, g.lda, m0, (c + 1) * BK, g.M, g.K, tid);
+      rb = load_tile<B_KC, MODE, TBN, NT>(B, g.ldb, n0, (c + 1) * BK, g.N, g.K, tid);
     }
-    const float* __restrict__ as = lds[cur][0];
-    const float* __restrict__ bs = lds[cur][1];
+    const float* __restrict__ as = lds_a[cur];
+    const float* __restrict__ bs = lds_b[cur];
 #pragma unroll
     for (int h = 0; h < BK / 8; ++h) {
-      float fa[2][4], fb[2][4];
+      float fa[MI][4], fb[NJ][4];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) read_frag<A_KC>(as, wm + 32 * i + li, h, lg, fa[i]);
+      for (int i = 0; i < MI; ++i) read_frag<A_KC, TBM>(as, wm + 32 * i + li, h, lg, fa[i]);
 #pragma unroll
-      for (int j = 0; j < 2; ++j) read_frag<B_KC>(bs, wn + 32 * j + li, h, lg, fb[j]);
+      for (int j = 0; j < NJ; ++j) read_frag<B_KC, TBN>(bs, wn + 32 * j + li, h, lg, fb[j]);
 #pragma unroll
       for (int t = 0; t < 4; ++t)
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
-          for (int j = 0; j < 2; ++j)
+          for (int j = 0; j < NJ; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][t], fb[j][t], acc[i][j], 0, 0, 0);
     }
     if (c + 1 < nchunks) {
-      store_tile<A_KC>(lds[cur ^ 1][0], tid, ra);
-      store_tile<B_KC>(lds[cur ^ 1][1], tid, rb);
+      store_tile<A_KC, TBM, NT>(lds_a[cur ^ 1], tid, ra);
+      store_tile<B_KC, TBN, NT>(lds_b[cur ^ 1], tid, rb);
     }
     __syncthreads();
   }
 
   // epilogue: accumulator register v of lane (li, lg) holds row 8*(v/4) + 4*lg + v%4, column li
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+    for (int j = 0; j < NJ; ++j) {
       const int col = n0 + wn + 32 * j + li;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
@@ -472,14 +484,31 @@ gpd_status_t launch_bf16_t(hipStream_t stream, const HGemmParams& p, int mode) {
   return GPD_OK;
 }
 
-template <bool A_KC, bool B_KC>
-gpd_status_t launch_f32(hipStream_t stream, const GemmParams& p, int mode) {
-  dim3 grid((unsigned)(p.tiles_per_xcd * 8)), block(256);
-  if (mode == 0) hipLaunchKernelGGL((gemm_f32_kernel<A_KC, B_KC, 0>), grid, block, 0, stream, p);
-  else if (mode == 1) hipLaunchKernelGGL((gemm_f32_kernel<A_KC, B_KC, 1>), grid, block, 0, stream, p);
-  else hipLaunchKernelGGL((gemm_f32_kernel<A_KC, B_KC, 2>), grid, block, 0, stream, p);
+template <bool A_KC, bool B_KC, int TBM, int TBN, int WGM, int WGN>
+gpd_status_t launch_f32_shape(hipStream_t stream, const GemmParams& p, int mode) {
+  dim3 grid((unsigned)(p.tiles_per_xcd * 8)), block(64 * WGM * WGN);
+  if (mode == 0) hipLaunchKernelGGL((gemm_f32_kernel<A_KC, B_KC, 0, TBM, TBN, WGM, WGN>), grid, block, 0, stream, p);
+  else if (mode == 1) hipLaunchKernelGGL((gemm_f32_kernel<A_KC, B_KC, 1, TBM, TBN, WGM, WGN>), grid, block, 0, stream, p);
+  else hipLaunchKernelGGL((gemm_f32_kernel<A_KC, B_KC, 2, TBM, TBN, WGM, WGN>), grid, block, 0, stream, p);
   GPD_HIP(hipGetLastError());
   return GPD_OK;
+}
+
+template <bool A_KC, bool B_KC>
+gpd_status_t launch_f32(hipStream_t stream, GemmParams p, int64_t batch, bool aligned) {
+  const bool large = aligned && p.M % 256 == 0 && p.N % 256 == 0 && p.K % BK == 0 && p.K > 0 &&
+                     (int64_t)(p.M / 256) * (p.N / 256) * batch >= 256;
+  const int tbm = large ? 256 : 128, tbn = large ? 256 : 128;
+  p.tiles_m = (p.M + tbm - 1) / tbm;
+  p.tiles_n = (p.N + tbn - 1) / tbn;
+  const int64_t total = (int64_t)p.tiles_m * p.tiles_n * batch;
+  if (total > 0x0fffffff) return fail(GPD_E_SHAPE, "gemm: too many tiles");
+  p.total_tiles = (int)total;
+  p.tiles_per_xcd = (int)((total + 7) / 8);
+  if (large) return launch_f32_shape<A_KC, B_KC, 256, 256, 4, 4>(stream, p, 0);
+  const bool full = p.M % 128 == 0 && p.N % 128 == 0 && p.K % BK == 0 && p.K > 0;
+  const int mode = !aligned ? 2 : (full ? 0 : 1);
+  return launch_f32_shape<A_KC, B_KC, 128, 128, 2, 2>(stream, p, mode);
 }
 
 }  // namespace
@@ -538,23 +567,15 @@ gpd_status_t launch_gemm(hipStream_t stream, const GemmArgs& a) {
   p.lda = a.lda; p.ldb = a.ldb; p.ldc = a.ldc;
   p.sA = a.strideA; p.sB = a.strideB; p.sC = a.strideC;
   p.batch = a.batch;
-  p.tiles_m = (int)((a.M + BM - 1) / BM);
-  p.tiles_n = (int)((a.N + BN - 1) / BN);
-  const int64_t total = (int64_t)p.tiles_m * p.tiles_n * a.batch;
-  if (total > 0x0fffffff) return fail(GPD_E_SHAPE, "gemm: too many tiles");
-  p.total_tiles = (int)total;
-  p.tiles_per_xcd = (int)((total + 7) / 8);
   p.alpha = a.alpha; p.beta = a.beta;
 
   const bool aligned = ((uintptr_t)a.A % 16 == 0) && ((uintptr_t)a.B % 16 == 0) &&
                        a.lda % 4 == 0 && a.ldb % 4 == 0 && a.strideA % 4 == 0 && a.strideB % 4 == 0;
-  const bool full = a.M % BM == 0 && a.N % BN == 0 && a.K % BK == 0 && a.K > 0;
-  const int mode = !aligned ? 2 : (full ? 0 : 1);
   const bool a_kc = !a.transA, b_kc = a.transB;
-  if (a_kc && b_kc) return launch_f32<true, true>(stream, p, mode);
-  if (a_kc && !b_kc) return launch_f32<true, false>(stream, p, mode);
-  if (!a_kc && b_kc) return launch_f32<false, true>(stream, p, mode);
-  return launch_f32<false, false>(stream, p, mode);
+  if (a_kc && b_kc) return launch_f32<true, true>(stream, p, a.batch, aligned);
+  if (a_kc && !b_kc) return launch_f32<true, false>(stream, p, a.batch, aligned);
+  if (!a_kc && b_kc) return launch_f32<false, true>(stream, p, a.batch, aligned);
+  return launch_f32<false, false>(stream, p, a.batch, aligned);
 }
 
 }  // namespace gpd

@@ -6,6 +6,8 @@
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
+#include <functional>
+#include <map>
 #include <string>
 #include <vector>
 
@@ -101,7 +103,25 @@ struct TableRing {
   // uploads `t` asynchronously on `stream`; the returned view stays valid until kSlots
   // further uploads have been made.
   gpd_status_t upload(const HostCombineTable& t, hipStream_t stream, CombineTable* out);
+
+  // Tables that recur (same code, same leading dimension, same erasure pattern) are built and
+  // uploaded once and then stay in a device arena: `key` identifies the table, `build` makes
+  // it on a miss.  A miss stages the table in a pinned ring slot and copies it in stream
+  // order, so a caller that wants to capture its calls in a HIP graph has to make each
+  // distinct call once before capturing (a captured copy would re-read a recycled slot).
+  // When the arena is full the table goes through the ring instead.
+  static constexpr size_t kArenaBytes = 1 << 20;
+  char* arena = nullptr;
+  size_t arena_used = 0;
+  std::map<std::string, CombineTable> cache;
+  gpd_status_t cached(const std::string& key, const std::function<gpd_status_t(HostCombineTable*)>& build,
+                      hipStream_t stream, CombineTable* out);
 };
+
+// appends the raw bytes of v to a cache key
+template <typename T>
+inline void key_add(std::string* k, const T& v) { k->append((const char*)&v, sizeof(T)); }
+inline void key_add_bytes(std::string* k, const void* p, size_t n) { k->append((const char*)p, n); }
 
 // ---------------------------------------------------------------- kernels (launchers)
 

@@ -335,10 +335,14 @@ extern "C" gpd_status_t gpd_layer_encode_weights(const gpd_layer_t* Lc, const fl
   if (!L || !W || !Wt) return fail(GPD_E_INVALID, "gpd_layer_encode_weights: null argument");
   if (ldw < L->desc.N_in) return fail(GPD_E_SHAPE, "ldw smaller than N_in");
   const Code& c = L->fwd;
-  HostCombineTable ht = encode_table(c.pts, c.eA, c.m, c.n, L->wr, L->wc, ldw);
-  grid_limits(L->desc.N_out, L->desc.N_in, c.m, c.n, L->wr, L->wc, &ht.in_rows, &ht.in_cols);
   CombineTable t;
-  gpd_status_t st = L->ring.upload(ht, L->stream, &t);
+  std::string key("encW");
+  key_add(&key, ldw);
+  gpd_status_t st = L->ring.cached(key, [&](HostCombineTable* ht) {
+    *ht = encode_table(c.pts, c.eA, c.m, c.n, L->wr, L->wc, ldw);
+    grid_limits(L->desc.N_out, L->desc.N_in, c.m, c.n, L->wr, L->wc, &ht->in_rows, &ht->in_cols);
+    return GPD_OK;
+  }, L->stream, &t);
   if (st != GPD_OK) return st;
   ScreenArgs none;
   return launch_combine(L->stream, t, W, ldw, Wt, L->wc, false, L->wr, L->wc, none);
@@ -455,10 +459,12 @@ extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, floa
   if (phase == GPD_STEP_FORWARD) {
     if (!out) return fail(GPD_E_INVALID, "forward: out is null");
     // X~_p = sum_jk X_jk b_p^eB(j,k)   (feedforward stage)
-    HostCombineTable ht = encode_table(c.pts, c.eB, c.n, c.d, L->wc, L->nb1, d.batch);
-    grid_limits(d.N_in, d.batch, c.n, c.d, L->wc, L->nb1, &ht.in_rows, &ht.in_cols);
     CombineTable t;
-    st = L->ring.upload(ht, s, &t);
+    st = L->ring.cached("encX", [&](HostCombineTable* ht) {
+      *ht = encode_table(c.pts, c.eB, c.n, c.d, L->wc, L->nb1, d.batch);
+      grid_limits(d.N_in, d.batch, c.n, c.d, L->wc, L->nb1, &ht->in_rows, &ht->in_cols);
+      return GPD_OK;
+    }, s, &t);
     if (st != GPD_OK) return st;
     st = launch_combine(s, t, X, d.batch, Xt, L->nb1, false, L->wc, L->nb1, none);
     if (st != GPD_OK) return st;
@@ -491,24 +497,30 @@ extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, floa
   CombineTable t;
   if (do_bwd) {
     // Delta~_p = sum_{i,k} Delta_{i,k} b_p^eD(i,k), stored (N_out/m) x (batch/d2)
-    HostCombineTable ht = encode_table(c.pts, L->eD, c.m, d.d2, L->wr, L->nb2, d.batch);
-    grid_limits(d.N_out, d.batch, c.m, d.d2, L->wr, L->nb2, &ht.in_rows, &ht.in_cols);
-    st = L->ring.upload(ht, s, &t);
+    st = L->ring.cached("encD", [&](HostCombineTable* ht) {
+      *ht = encode_table(c.pts, L->eD, c.m, d.d2, L->wr, L->nb2, d.batch);
+      grid_limits(d.N_out, d.batch, c.m, d.d2, L->wr, L->nb2, &ht->in_rows, &ht->in_cols);
+      return GPD_OK;
+    }, s, &t);
     if (st != GPD_OK) return st;
     st = launch_combine(s, t, Dlt, d.batch, Dt, L->nb2, false, L->wr, L->nb2, none);
     if (st != GPD_OK) return st;
   }
   {
     // update operands: Dhat_p = sum_i Delta_i a_p^i,  Xhat_p = sum_j X_j b_p^j
-    HostCombineTable hd = encode_table(c.pts, L->eUd, c.m, 1, L->wr, d.batch, d.batch);
-    grid_limits(d.N_out, d.batch, c.m, 1, L->wr, d.batch, &hd.in_rows, &hd.in_cols);
-    st = L->ring.upload(hd, s, &t);
+    st = L->ring.cached("encDh", [&](HostCombineTable* hd) {
+      *hd = encode_table(c.pts, L->eUd, c.m, 1, L->wr, d.batch, d.batch);
+      grid_limits(d.N_out, d.batch, c.m, 1, L->wr, d.batch, &hd->in_rows, &hd->in_cols);
+      return GPD_OK;
+    }, s, &t);
     if (st != GPD_OK) return st;
     st = launch_combine(s, t, Dlt, d.batch, Dh, d.batch, false, L->wr, d.batch, none);
     if (st != GPD_OK) return st;
-    HostCombineTable hx = encode_table(c.pts, L->eUx, c.n, 1, L->wc, d.batch, d.batch);
-    grid_limits(d.N_in, d.batch, c.n, 1, L->wc, d.batch, &hx.in_rows, &hx.in_cols);
-    st = L->ring.upload(hx, s, &t);
+    st = L->ring.cached("encXh", [&](HostCombineTable* hx) {
+      *hx = encode_table(c.pts, L->eUx, c.n, 1, L->wc, d.batch, d.batch);
+      grid_limits(d.N_in, d.batch, c.n, 1, L->wc, d.batch, &hx->in_rows, &hx->in_cols);
+      return GPD_OK;
+    }, s, &t);
     if (st != GPD_OK) return st;
     st = launch_combine(s, t, X, d.batch, Xh, d.batch, false, L->wc, d.batch, none);
     if (st != GPD_OK) return st;

@@ -101,7 +101,8 @@ def test_forward_with_erasures_and_a_corrupted_node():
     olp = O.make_layer_plan(N_out, N_in, 1, 4, 2, 1, 1, P, "auto")
     L = G.gpd_layer_create(N_out, N_in, 1, 4, 2, 1, 1, P)
     Wt = G.gpd_layer_encode_weights(L, to_dev(W))
-    Wt[7] += 0.05 * torch.randn_like(Wt[7])
+    noise = np.random.default_rng(11).standard_normal(tuple(Wt[7].shape)).astype(np.float32)
+    Wt[7] += 0.05 * to_dev(noise)
     present = np.ones(P, dtype=np.uint8)
     present[[1, 20]] = 0
     S, rep = G.gpd_coded_layer_step(L, G.GPD_STEP_FORWARD, Wt, to_dev(X), present=present, correct_errors=True,
@@ -111,7 +112,9 @@ def test_forward_with_erasures_and_a_corrupted_node():
     assert [x[:3] for x in rep.located] == [x[:3] for x in orep.located]
     assert set(x[0] for x in rep.located) == {7}
     assert rel_fro(to_np(S), S_o) < 1e-4
-    assert rel_fro(to_np(S), W.astype(np.float64) @ X) < 1e-3
+    # a corrupted response whose error is below tau is not corrected; it moves the result by at
+    # most tau times the amplification
+    assert rel_fro(to_np(S), W.astype(np.float64) @ X) < 1e-3 + O.amplification(olp.fwd, present, "lsq_all") * 2.0 ** -12
 
 
 @pytest.mark.parametrize("batch,m,n,P", [(1, 4, 2, 24), (4, 2, 4, 32), (24, 2, 4, 32)])
