@@ -28,6 +28,10 @@ if ROOT not in sys.path:
 
 PEAK_FP32_MFMA_TFLOPS = 157.3     # MI355X published dense fp32 matrix peak
 PEAK_HBM_GBS = 8000.0             # MI355X published HBM3E bandwidth
+# HBM bytes per launch of the worker-product kernel on the default workload, from the committed
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/coded_matmul_4096_fp32.md):
+# 393672 KiB x 2.0 (copy-kernel calibration) fetched + 262144 KiB written
+GEMM_TRAFFIC_BYTES_CFG1 = (393672 * 2.0 + 262144) * 1024
 
 
 def cpu_baseline(cfg, n_threads):
@@ -204,7 +208,8 @@ def main():
         "worker_TFLOPs": achieved,
         "roofline": {"kernel": "gemm_f32_kernel (batched worker products)", "bound": "mfma",
                      "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": None},
+                     "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
+                     "traffic": GEMM_TRAFFIC_BYTES_CFG1 if args.config == 1 else None},
         "roofline_hbm": {
             "encode": {"achieved": enc_bytes / (enc_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                        "frac": enc_bytes / (enc_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},

@@ -14,11 +14,15 @@ namespace gpd {
 
 namespace {
 
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);   // quiet NaN
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+
+// two fp32 -> packed bf16, round to nearest even (one v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  const floatx2 f = {lo, hi};
+  union { bf16x2 h; uint32_t u; } cv;
+  cv.h = __builtin_convertvector(f, bf16x2);
+  return cv.u;
 }
 
 template <int VEC> struct VecT;
@@ -54,14 +58,13 @@ template <int VEC>
 __device__ __forceinline__ void store_vec_bf16(uint16_t* p, const float (&v)[VEC]) {
   if constexpr (VEC == 4) {
     uint2 t;
-    t.x = (uint32_t)f32_to_bf16_rne(v[0]) | ((uint32_t)f32_to_bf16_rne(v[1]) << 16);
-    t.y = (uint32_t)f32_to_bf16_rne(v[2]) | ((uint32_t)f32_to_bf16_rne(v[3]) << 16);
+    t.x = pack_bf16(v[0], v[1]);
+    t.y = pack_bf16(v[2], v[3]);
     *reinterpret_cast<uint2*>(p) = t;
   } else if constexpr (VEC == 2) {
-    *reinterpret_cast<uint32_t*>(p) =
-        (uint32_t)f32_to_bf16_rne(v[0]) | ((uint32_t)f32_to_bf16_rne(v[1]) << 16);
+    *reinterpret_cast<uint32_t*>(p) = pack_bf16(v[0], v[1]);
   } else {
-    *p = f32_to_bf16_rne(v[0]);
+    *p = (uint16_t)(pack_bf16(v[0], 0.f) & 0xffffu);
   }
 }
 
@@ -73,6 +76,7 @@ struct CombineParams {
   int64_t rows, cols;        // block shape in elements
   int64_t cols_vec;          // cols / VEC
   int nin, nout, r;
+  int q_chunk;               // outputs per thread: blockIdx.y selects [y*q_chunk, (y+1)*q_chunk)
   const int64_t* in_off;
   const int64_t* out_off;
   const float* coef;         // [nout][nin]
@@ -109,12 +113,10 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineParams p) {
     }
   }
 
+  // non-finite responses are replaced by zero everywhere (and always passed on, below)
+  bool bad[VEC];
+  float nz2[VEC];
   if constexpr (SCREEN) {
-    // Algorithm 1 step 1 in fp32, with a threshold below tau so that every codeword the
-    // fp64 check could flag is passed on; non-finite responses are replaced by zero and
-    // always passed on.
-    bool bad[VEC];
-    float nz2[VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) { bad[v] = false; nz2[v] = 0.f; }
 #pragma unroll
@@ -126,6 +128,10 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineParams p) {
         nz2[v] = fmaf(z[s][v], z[s][v], nz2[v]);
       }
     }
+  }
+  if (SCREEN && blockIdx.y == 0) {
+    // Algorithm 1 step 1 in fp32, with a threshold below tau so that every codeword the
+    // fp64 check could flag is passed on.
     float sig2[VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) sig2[v] = 0.f;
@@ -168,7 +174,9 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineParams p) {
   }
 
   if (!active) return;
-  for (int q = 0; q < p.nout; ++q) {
+  const int q_begin = blockIdx.y * p.q_chunk;
+  const int q_end = min(p.nout, q_begin + p.q_chunk);
+  for (int q = q_begin; q < q_end; ++q) {
     float acc[VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
@@ -196,7 +204,7 @@ gpd_status_t launch_t(hipStream_t stream, const CombineParams& p, bool out_bf16,
   if (total == 0) return GPD_OK;
   const int64_t blocks = (total + 255) / 256;
   if (blocks > 0x7fffffffLL) return fail(GPD_E_SHAPE, "block too large for one launch");
-  dim3 grid((unsigned)blocks), block(256);
+  dim3 grid((unsigned)blocks, (unsigned)((p.nout + p.q_chunk - 1) / p.q_chunk)), block(256);
   const bool lim = p.in_rows != nullptr;
   if (screen) {
     if (out_bf16) return fail(GPD_E_UNSUPPORTED, "screen with bf16 output");
@@ -256,6 +264,9 @@ gpd_status_t launch_combine(hipStream_t stream, const CombineTable& t, const flo
   if (t.nin <= 16 && ok(4)) vec = 4;
   else if (t.nin <= 32 && ok(2)) vec = 2;
   p.cols_vec = cols / vec;
+  // small launches (the vectors of the batch-1 layer step) are latency-bound: give every
+  // output block its own threads instead of looping over the outputs inside one thread
+  p.q_chunk = (rows * p.cols_vec < 16384) ? 1 : t.nout;
   if (vec == 4) return launch_v<4>(stream, p, out_bf16, screen.enabled);
   if (vec == 2) return launch_v<2>(stream, p, out_bf16, screen.enabled);
   return launch_v<1>(stream, p, out_bf16, screen.enabled);

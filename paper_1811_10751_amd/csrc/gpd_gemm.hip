@@ -201,15 +201,23 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_f32_kernel(GemmParams g) 
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
       const int col = n0 + wn + 32 * j + li;
+      // with beta != 0 all 16 old values of the block are requested before any is used
+      float old[16];
+      if (g.beta != 0.f) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * lg + (v & 3);
+          old[v] = (MODE == 0 || (row < g.M && col < g.N)) ? C[(int64_t)row * g.ldc + col] : 0.f;
+        }
+      } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) old[v] = 0.f;
+      }
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * lg + (v & 3);
-        if (MODE == 0 || (row < g.M && col < g.N)) {
-          float* dst = C + (int64_t)row * g.ldc + col;
-          float val = g.alpha * acc[i][j][v];
-          if (g.beta != 0.f) val = fmaf(g.beta, *dst, val);
-          *dst = val;
-        }
+        if (MODE == 0 || (row < g.M && col < g.N))
+          C[(int64_t)row * g.ldc + col] = fmaf(g.beta, old[v], g.alpha * acc[i][j][v]);
       }
     }
 }
@@ -242,14 +250,15 @@ struct HGemmParams {
   float alpha, beta;
 };
 
-__device__ __forceinline__ uint32_t bf16_bits(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x0040u;
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return u >> 16;
-}
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+
+// two fp32 -> packed bf16, round to nearest even (one v_cvt_pk_bf16_f32)
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-  return bf16_bits(lo) | (bf16_bits(hi) << 16);
+  const floatx2 f = {lo, hi};
+  union { bf16x2 h; uint32_t u; } cv;
+  cv.h = __builtin_convertvector(f, bf16x2);
+  return cv.u;
 }
 
 // up to 4 consecutive floats; elements at or beyond nvalid read as zero
@@ -462,15 +471,23 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(HGemmParams g) {
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const int col = n0 + wn + 32 * j + li;
+      // with beta != 0 all 16 old values of the block are requested before any is used
+      float old[16];
+      if (g.beta != 0.f) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * lg + (v & 3);
+          old[v] = (MODE == 0 || (row < g.M && col < g.N)) ? C[(int64_t)row * g.ldc + col] : 0.f;
+        }
+      } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) old[v] = 0.f;
+      }
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * lg + (v & 3);
-        if (MODE == 0 || (row < g.M && col < g.N)) {
-          float* dst = C + (int64_t)row * g.ldc + col;
-          float val = g.alpha * acc[i][j][v];
-          if (g.beta != 0.f) val = fmaf(g.beta, *dst, val);
-          *dst = val;
-        }
+        if (MODE == 0 || (row < g.M && col < g.N))
+          C[(int64_t)row * g.ldc + col] = fmaf(g.beta, old[v], g.alpha * acc[i][j][v]);
       }
     }
 }
@@ -496,8 +513,12 @@ gpd_status_t launch_f32_shape(hipStream_t stream, const GemmParams& p, int mode)
 
 template <bool A_KC, bool B_KC>
 gpd_status_t launch_f32(hipStream_t stream, GemmParams p, int64_t batch, bool aligned) {
+#ifdef GPD_FORCE_SMALL
+  const bool large = false;
+#else
   const bool large = aligned && p.M % 256 == 0 && p.N % 256 == 0 && p.K % BK == 0 && p.K > 0 &&
                      (int64_t)(p.M / 256) * (p.N / 256) * batch >= 256;
+#endif
   const int tbm = large ? 256 : 128, tbn = large ? 256 : 128;
   p.tiles_m = (p.M + tbm - 1) / tbm;
   p.tiles_n = (p.N + tbn - 1) / tbn;

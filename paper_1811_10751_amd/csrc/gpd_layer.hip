@@ -27,38 +27,72 @@ constexpr int kRowChunk = 64;           // rows of W~_p one workgroup of the bac
 // ---------------------------------------------------------------- skinny forward
 
 // S~[p][r][b] = sum_c W~[p][r][c] * X~[p][c][b];  NB = per-node batch (columns of X~_p).
+// A workgroup owns kFwdRows consecutive rows of W~_p, i.e. one contiguous piece of memory, and
+// walks through it like a copy kernel (thread t reads 16 bytes at column 4t, 4t+1024, ...), so
+// that concurrent workgroups spread over all HBM channels.  The X~ values of a thread's
+// columns are fetched once and reused for every row.  Row sums: wavefront shuffle, then LDS.
+constexpr int kFwdRows = 8;
+
 template <int NB>
 __global__ __launch_bounds__(256) void skinny_forward_kernel(const float* __restrict__ Wt,
                                                              const float* __restrict__ Xt,
                                                              float* __restrict__ St, int rows,
                                                              int cols) {
+  __shared__ float part[4][kFwdRows][NB];
   const int p = blockIdx.y;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + wave;
-  if (row >= rows) return;
-  const float* __restrict__ w = Wt + ((int64_t)p * rows + row) * cols;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int row0 = blockIdx.x * kFwdRows;
   const float* __restrict__ x = Xt + (int64_t)p * cols * NB;
-  float acc[NB];
+  const float* __restrict__ w0 = Wt + ((int64_t)p * rows + row0) * cols;
+  const int nrows = min(kFwdRows, rows - row0);
+  float acc[kFwdRows][NB];
 #pragma unroll
-  for (int b = 0; b < NB; ++b) acc[b] = 0.f;
-  const int cols4 = cols & ~3;
-  for (int c = lane * 4; c < cols4; c += 256) {
-    const float4 wv = *reinterpret_cast<const float4*>(w + c);
-    const float we[4] = {wv.x, wv.y, wv.z, wv.w};
+  for (int r = 0; r < kFwdRows; ++r)
 #pragma unroll
-    for (int e = 0; e < 4; ++e)
+    for (int b = 0; b < NB; ++b) acc[r][b] = 0.f;
+  const bool vec_ok = (cols & 3) == 0;
+  if (vec_ok) {
+    for (int c = tid * 4; c < cols; c += 1024) {
+      float xv[4][NB];
 #pragma unroll
-      for (int b = 0; b < NB; ++b) acc[b] = fmaf(we[e], x[(int64_t)(c + e) * NB + b], acc[b]);
+      for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int b = 0; b < NB; ++b) xv[e][b] = x[(int64_t)(c + e) * NB + b];
+#pragma unroll
+      for (int r = 0; r < kFwdRows; ++r) {
+        if (r < nrows) {
+          const float4 wv = *reinterpret_cast<const float4*>(w0 + (int64_t)r * cols + c);
+          const float we[4] = {wv.x, wv.y, wv.z, wv.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int b = 0; b < NB; ++b) acc[r][b] = fmaf(we[e], xv[e][b], acc[r][b]);
+        }
+      }
+    }
+  } else {
+    for (int c = tid; c < cols; c += 256)
+#pragma unroll
+      for (int r = 0; r < kFwdRows; ++r)
+        if (r < nrows)
+#pragma unroll
+          for (int b = 0; b < NB; ++b)
+            acc[r][b] = fmaf(w0[(int64_t)r * cols + c], x[(int64_t)c * NB + b], acc[r][b]);
   }
-  for (int c = cols4 + lane; c < cols; c += 64)
 #pragma unroll
-    for (int b = 0; b < NB; ++b) acc[b] = fmaf(w[c], x[(int64_t)c * NB + b], acc[b]);
+  for (int r = 0; r < kFwdRows; ++r)
 #pragma unroll
-  for (int b = 0; b < NB; ++b) {
-    float v = acc[b];
+    for (int b = 0; b < NB; ++b) {
+      float v = acc[r][b];
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
-    if (lane == 0) St[((int64_t)p * rows + row) * NB + b] = v;
+      for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+      if (lane == 0) part[wave][r][b] = v;
+    }
+  __syncthreads();
+  if (tid < kFwdRows * NB) {
+    const int r = tid / NB, b = tid % NB;
+    if (r < nrows)
+      St[((int64_t)p * rows + row0 + r) * NB + b] = (part[0][r][b] + part[1][r][b]) + (part[2][r][b] + part[3][r][b]);
   }
 }
 
@@ -370,7 +404,8 @@ namespace {
 
 template <int NB>
 void launch_skinny_fwd(hipStream_t s, const float* Wt, const float* Xt, float* St, int rows, int cols, int P) {
-  hipLaunchKernelGGL((skinny_forward_kernel<NB>), dim3((rows + 3) / 4, P), dim3(256), 0, s, Wt, Xt, St, rows, cols);
+  hipLaunchKernelGGL((skinny_forward_kernel<NB>), dim3((rows + kFwdRows - 1) / kFwdRows, P), dim3(256), 0, s, Wt, Xt,
+                     St, rows, cols);
 }
 
 gpd_status_t skinny_forward(hipStream_t s, const float* Wt, const float* Xt, float* St, int64_t rows,
