@@ -15,7 +15,6 @@ namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int BM = 128, BN = 128;      // workgroup tile of the bf16 kernel
 constexpr int BK = 16;                 // k-values per LDS stage (fp32 kernel)
 constexpr int KC_STRIDE = BK + 4;      // row stride (floats) of a k-contiguous tile  [rows][BK]
 
@@ -120,7 +119,8 @@ __device__ __forceinline__ void read_frag(const float* __restrict__ lds, int row
 // B_KC: op(B) columns are k-contiguous in memory (B transposed, stored N x K).
 // TBM x TBN: workgroup tile; the WGM x WGN wavefronts own (TBM/WGM) x (TBN/WGN) sub-tiles.
 template <bool A_KC, bool B_KC, int MODE, int TBM, int TBN, int WGM, int WGN>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_f32_kernel(GemmParams g) {
+// (4-wavefront shape: at least 3 wavefronts per SIMD, i.e. 3 workgroups per CU)
+__global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? 3 : 1) void gemm_f32_kernel(GemmParams g) {
   constexpr int NT = 64 * WGM * WGN;
   constexpr int TA = tile_floats<A_KC, TBM>();
   constexpr int TB = tile_floats<B_KC, TBN>();
@@ -237,7 +237,6 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int HBK = 32;                 // k-values per stage
 constexpr int HSTRIDE = HBK + 8;        // bf16 elements per LDS row (80 bytes)
-constexpr int HTILE = 128 * HSTRIDE;    // bf16 elements per operand tile
 
 enum { SRC_F32_KC = 0, SRC_BF16_KC = 1, SRC_F32_RC = 2, SRC_BF16_RC = 3 };
 
@@ -281,23 +280,25 @@ __device__ __forceinline__ uint4 load8h(const uint16_t* p, int nvalid) {
 }
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
-// One operand tile of 128 rows x 32 k in flight: 16 bf16 per thread, still in source form.
-template <int SRC> struct HStage;
-template <> struct HStage<SRC_F32_KC> { float4 v[4]; };
-template <> struct HStage<SRC_BF16_KC> { uint4 v[2]; };
-template <> struct HStage<SRC_F32_RC> { float4 v[2][2]; };
-template <> struct HStage<SRC_BF16_RC> { uint4 v[2]; };
+// One operand tile of ROWS rows x 32 k in flight, still in source form, spread over NT threads.
+// Items per thread: F32_KC ROWS*8/NT float4; BF16_KC ROWS*4/NT uint4; F32_RC 4*ROWS/NT patches of
+// 2 k x 4 rows; BF16_RC 2*ROWS/NT patches of 2 k x 8 rows (threads beyond the patch count idle).
+template <int SRC, int ROWS, int NT> struct HStage;
+template <int ROWS, int NT> struct HStage<SRC_F32_KC, ROWS, NT> { float4 v[ROWS * 8 / NT]; };
+template <int ROWS, int NT> struct HStage<SRC_BF16_KC, ROWS, NT> { uint4 v[ROWS * 4 / NT]; };
+template <int ROWS, int NT> struct HStage<SRC_F32_RC, ROWS, NT> { float4 v[4 * ROWS / NT][2]; };
+template <int ROWS, int NT> struct HStage<SRC_BF16_RC, ROWS, NT> { uint4 v[(2 * ROWS + NT - 1) / NT][2]; };
 
 // base: start of the operand for this batch entry; "row" is the m (or n) index, k the
 // contraction index.  KC sources are [row][k] with leading dimension ld, RC sources [k][row].
-template <int SRC, int MODE>
-__device__ __forceinline__ void hload(HStage<SRC>& st, const void* base, int64_t ld, int row0, int k0,
-                                      int nrows, int nk, int tid) {
+template <int SRC, int MODE, int ROWS, int NT>
+__device__ __forceinline__ void hload(HStage<SRC, ROWS, NT>& st, const void* base, int64_t ld, int row0,
+                                      int k0, int nrows, int nk, int tid) {
   if constexpr (SRC == SRC_F32_KC) {
     const float* b = (const float*)base;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int f = tid + 256 * q;
+    for (int q = 0; q < ROWS * 8 / NT; ++q) {
+      const int f = tid + NT * q;
       const int row = row0 + (f >> 3), k = k0 + 4 * (f & 7);
       const int nv = (MODE == 0) ? 4 : (row < nrows ? clampi(nk - k, 0, 4) : 0);
       st.v[q] = (MODE == 0 || nv > 0) ? load4f<MODE>(b + (int64_t)row * ld + k, nv) : make_float4(0.f, 0.f, 0.f, 0.f);
@@ -305,8 +306,8 @@ __device__ __forceinline__ void hload(HStage<SRC>& st, const void* base, int64_t
   } else if constexpr (SRC == SRC_BF16_KC) {
     const uint16_t* b = (const uint16_t*)base;
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const int f = tid + 256 * q;
+    for (int q = 0; q < ROWS * 4 / NT; ++q) {
+      const int f = tid + NT * q;
       const int row = row0 + (f >> 2), k = k0 + 8 * (f & 3);
       const int nv = (MODE == 0) ? 8 : (row < nrows ? clampi(nk - k, 0, 8) : 0);
       st.v[q] = (MODE == 0 || nv > 0) ? load8h<MODE>(b + (int64_t)row * ld + k, nv) : make_uint4(0u, 0u, 0u, 0u);
@@ -314,9 +315,9 @@ __device__ __forceinline__ void hload(HStage<SRC>& st, const void* base, int64_t
   } else if constexpr (SRC == SRC_F32_RC) {
     const float* b = (const float*)base;
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const int f = tid + 256 * q;
-      const int kp = (f & 3) + 4 * (f >> 7), rq = (f >> 2) & 31;
+    for (int q = 0; q < 4 * ROWS / NT; ++q) {
+      const int f = tid + NT * q;
+      const int kp = (f & 3) + 4 * (f / ROWS), rq = (f >> 2) % (ROWS / 4);
       const int row = row0 + 4 * rq;
 #pragma unroll
       for (int par = 0; par < 2; ++par) {
@@ -328,24 +329,29 @@ __device__ __forceinline__ void hload(HStage<SRC>& st, const void* base, int64_t
     }
   } else {
     const uint16_t* b = (const uint16_t*)base;
-    const int kp = (tid & 3) + 4 * (tid >> 6), rq = (tid >> 2) & 15;
-    const int row = row0 + 8 * rq;
 #pragma unroll
-    for (int par = 0; par < 2; ++par) {
-      const int k = k0 + 2 * kp + par;
-      const int nv = (MODE == 0) ? 8 : (k < nk ? clampi(nrows - row, 0, 8) : 0);
-      st.v[par] = (MODE == 0 || nv > 0) ? load8h<MODE>(b + (int64_t)k * ld + row, nv) : make_uint4(0u, 0u, 0u, 0u);
+    for (int q = 0; q < (2 * ROWS + NT - 1) / NT; ++q) {
+      const int f = tid + NT * q;
+      const int kp = (f & 3) + 4 * (f / (ROWS / 2)), rq = (f >> 2) % (ROWS / 8);
+      const int row = row0 + 8 * rq;
+#pragma unroll
+      for (int par = 0; par < 2; ++par) {
+        const int k = k0 + 2 * kp + par;
+        const bool mine = f < 2 * ROWS;
+        const int nv = !mine ? 0 : ((MODE == 0) ? 8 : (k < nk ? clampi(nrows - row, 0, 8) : 0));
+        st.v[q][par] = (nv > 0) ? load8h<MODE>(b + (int64_t)k * ld + row, nv) : make_uint4(0u, 0u, 0u, 0u);
+      }
     }
   }
 }
 
 // Writes the staged tile to LDS as bf16 [row][k] (row stride HSTRIDE elements).
-template <int SRC>
-__device__ __forceinline__ void hstore(const HStage<SRC>& st, uint16_t* __restrict__ lds, int tid) {
+template <int SRC, int ROWS, int NT>
+__device__ __forceinline__ void hstore(const HStage<SRC, ROWS, NT>& st, uint16_t* __restrict__ lds, int tid) {
   if constexpr (SRC == SRC_F32_KC) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int f = tid + 256 * q;
+    for (int q = 0; q < ROWS * 8 / NT; ++q) {
+      const int f = tid + NT * q;
       uint2 w;
       w.x = pack_bf16(st.v[q].x, st.v[q].y);
       w.y = pack_bf16(st.v[q].z, st.v[q].w);
@@ -353,15 +359,15 @@ __device__ __forceinline__ void hstore(const HStage<SRC>& st, uint16_t* __restri
     }
   } else if constexpr (SRC == SRC_BF16_KC) {
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const int f = tid + 256 * q;
+    for (int q = 0; q < ROWS * 4 / NT; ++q) {
+      const int f = tid + NT * q;
       *reinterpret_cast<uint4*>(lds + (f >> 2) * HSTRIDE + 8 * (f & 3)) = st.v[q];
     }
   } else if constexpr (SRC == SRC_F32_RC) {
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const int f = tid + 256 * q;
-      const int kp = (f & 3) + 4 * (f >> 7), rq = (f >> 2) & 31;
+    for (int q = 0; q < 4 * ROWS / NT; ++q) {
+      const int f = tid + NT * q;
+      const int kp = (f & 3) + 4 * (f / ROWS), rq = (f >> 2) % (ROWS / 4);
       const float lo[4] = {st.v[q][0].x, st.v[q][0].y, st.v[q][0].z, st.v[q][0].w};
       const float hi[4] = {st.v[q][1].x, st.v[q][1].y, st.v[q][1].z, st.v[q][1].w};
       const int rot = (rq >> 1) & 3;
@@ -375,26 +381,36 @@ __device__ __forceinline__ void hstore(const HStage<SRC>& st, uint16_t* __restri
       }
     }
   } else {
-    const int kp = (tid & 3) + 4 * (tid >> 6), rq = (tid >> 2) & 15;
-    const uint32_t lo[4] = {st.v[0].x, st.v[0].y, st.v[0].z, st.v[0].w};
-    const uint32_t hi[4] = {st.v[1].x, st.v[1].y, st.v[1].z, st.v[1].w};
-    const int rot = rq & 7;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int ee = (e + rot) & 7;
-      uint32_t l = lo[0], h = hi[0];
+    for (int q = 0; q < (2 * ROWS + NT - 1) / NT; ++q) {
+      const int f = tid + NT * q;
+      if (f < 2 * ROWS) {
+        const int kp = (f & 3) + 4 * (f / (ROWS / 2)), rq = (f >> 2) % (ROWS / 8);
+        const uint32_t lo[4] = {st.v[q][0].x, st.v[q][0].y, st.v[q][0].z, st.v[q][0].w};
+        const uint32_t hi[4] = {st.v[q][1].x, st.v[q][1].y, st.v[q][1].z, st.v[q][1].w};
+        const int rot = rq & 7;
 #pragma unroll
-      for (int c = 1; c < 4; ++c) { if ((ee >> 1) == c) { l = lo[c]; h = hi[c]; } }
-      const uint32_t sh = 16u * (ee & 1);
-      const uint32_t w = ((l >> sh) & 0xffffu) | (((h >> sh) & 0xffffu) << 16);
-      *reinterpret_cast<uint32_t*>(lds + (8 * rq + ee) * HSTRIDE + 2 * kp) = w;
+        for (int e = 0; e < 8; ++e) {
+          const int ee = (e + rot) & 7;
+          uint32_t l = lo[0], h = hi[0];
+#pragma unroll
+          for (int c = 1; c < 4; ++c) { if ((ee >> 1) == c) { l = lo[c]; h = hi[c]; } }
+          const uint32_t sh = 16u * (ee & 1);
+          const uint32_t w = ((l >> sh) & 0xffffu) | (((h >> sh) & 0xffffu) << 16);
+          *reinterpret_cast<uint32_t*>(lds + (8 * rq + ee) * HSTRIDE + 2 * kp) = w;
+        }
+      }
     }
   }
 }
 
-template <int ASRC, int BSRC, int MODE>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(HGemmParams g) {
-  __shared__ __attribute__((aligned(16))) uint16_t lds[2][2][HTILE];
+// TBM x TBN workgroup tile, WGM x WGN wavefronts, each owning (TBM/WGM) x (TBN/WGN).
+template <int ASRC, int BSRC, int MODE, int TBM, int TBN, int WGM, int WGN>
+__global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? 3 : 1) void gemm_bf16_kernel(HGemmParams g) {
+  constexpr int NT = 64 * WGM * WGN;
+  constexpr int WM = TBM / WGM, WN = TBN / WGN, MI = WM / 32, NJ = WN / 32;
+  __shared__ __attribute__((aligned(16))) uint16_t lds_a[2][TBM * HSTRIDE];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_b[2][TBN * HSTRIDE];
 
   const int xcd = blockIdx.x & 7;
   const int slot = blockIdx.x >> 3;
@@ -405,7 +421,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(HGemmParams g) {
   const int rem = tile - p * per_batch;
   const int tm = rem / g.tiles_n;
   const int tn = rem - tm * g.tiles_n;
-  const int m0 = tm * BM, n0 = tn * BN;
+  const int m0 = tm * TBM, n0 = tn * TBN;
 
   constexpr int A_ES = (ASRC == SRC_BF16_KC || ASRC == SRC_BF16_RC) ? 2 : 4;
   constexpr int B_ES = (BSRC == SRC_BF16_KC || BSRC == SRC_BF16_RC) ? 2 : 4;
@@ -416,60 +432,60 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(HGemmParams g) {
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int li = lane & 31, lg = lane >> 5;
-  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+  const int wm = (wave / WGN) * WM, wn = (wave % WGN) * WN;
 
-  floatx16 acc[2][2];
+  floatx16 acc[MI][NJ];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   const int nchunks = (g.K + HBK - 1) / HBK;
-  HStage<ASRC> sa;
-  HStage<BSRC> sb;
-  hload<ASRC, MODE>(sa, A, g.lda, m0, 0, g.M, g.K, tid);
-  hload<BSRC, MODE>(sb, B, g.ldb, n0, 0, g.N, g.K, tid);
-  hstore<ASRC>(sa, lds[0][0], tid);
-  hstore<BSRC>(sb, lds[0][1], tid);
+  HStage<ASRC, TBM, NT> sa;
+  HStage<BSRC, TBN, NT> sb;
+  hload<ASRC, MODE, TBM, NT>(sa, A, g.lda, m0, 0, g.M, g.K, tid);
+  hload<BSRC, MODE, TBN, NT>(sb, B, g.ldb, n0, 0, g.N, g.K, tid);
+  hstore<ASRC, TBM, NT>(sa, lds_a[0], tid);
+  hstore<BSRC, TBN, NT>(sb, lds_b[0], tid);
   __syncthreads();
 
   for (int c = 0; c < nchunks; ++c) {
     const int cur = c & 1;
     if (c + 1 < nchunks) {
-      hload<ASRC, MODE>(sa, A, g.lda, m0, (c + 1) * HBK, g.M, g.K, tid);
-      hload<BSRC, MODE>(sb, B, g.ldb, n0, (c + 1) * HBK, g.N, g.K, tid);
+      hload<ASRC, MODE, TBM, NT>(sa, A, g.lda, m0, (c + 1) * HBK, g.M, g.K, tid);
+      hload<BSRC, MODE, TBN, NT>(sb, B, g.ldb, n0, (c + 1) * HBK, g.N, g.K, tid);
     }
-    const uint16_t* __restrict__ as = lds[cur][0];
-    const uint16_t* __restrict__ bs = lds[cur][1];
+    const uint16_t* __restrict__ as = lds_a[cur];
+    const uint16_t* __restrict__ bs = lds_b[cur];
 #pragma unroll
     for (int h = 0; h < HBK / 16; ++h) {
       union Frag { uint4 u; bf16x8 v; };
-      Frag fa[2], fb[2];
+      Frag fa[MI], fb[NJ];
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < MI; ++i)
         fa[i].u = *reinterpret_cast<const uint4*>(as + (wm + 32 * i + li) * HSTRIDE + 16 * h + 8 * lg);
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < NJ; ++j)
         fb[j].u = *reinterpret_cast<const uint4*>(bs + (wn + 32 * j + li) * HSTRIDE + 16 * h + 8 * lg);
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < NJ; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i].v, fb[j].v, acc[i][j], 0, 0, 0);
     }
     if (c + 1 < nchunks) {
-      hstore<ASRC>(sa, lds[cur ^ 1][0], tid);
-      hstore<BSRC>(sb, lds[cur ^ 1][1], tid);
+      hstore<ASRC, TBM, NT>(sa, lds_a[cur ^ 1], tid);
+      hstore<BSRC, TBN, NT>(sb, lds_b[cur ^ 1], tid);
     }
     __syncthreads();
   }
 
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+    for (int j = 0; j < NJ; ++j) {
       const int col = n0 + wn + 32 * j + li;
       // with beta != 0 all 16 old values of the block are requested before any is used
       float old[16];
@@ -493,10 +509,25 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(HGemmParams g) {
 }
 
 template <int ASRC, int BSRC>
-gpd_status_t launch_bf16_t(hipStream_t stream, const HGemmParams& p, int mode) {
-  dim3 grid((unsigned)(p.tiles_per_xcd * 8)), block(256);
-  if (mode == 0) hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 0>), grid, block, 0, stream, p);
-  else hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 1>), grid, block, 0, stream, p);
+gpd_status_t launch_bf16_t(hipStream_t stream, HGemmParams p, int64_t batch, bool aligned) {
+  // same two workgroup shapes as the fp32 kernel; the large one needs full aligned tiles
+  const bool large = aligned && p.M % 256 == 0 && p.N % 256 == 0 && p.K % HBK == 0 && p.K > 0 &&
+                     (int64_t)(p.M / 256) * (p.N / 256) * batch >= 256;
+  const int tbm = large ? 256 : 128, tbn = large ? 256 : 128;
+  p.tiles_m = (p.M + tbm - 1) / tbm;
+  p.tiles_n = (p.N + tbn - 1) / tbn;
+  const int64_t total = (int64_t)p.tiles_m * p.tiles_n * batch;
+  if (total > 0x0fffffff) return fail(GPD_E_SHAPE, "gemm: too many tiles");
+  p.total_tiles = (int)total;
+  p.tiles_per_xcd = (int)((total + 7) / 8);
+  dim3 grid((unsigned)(p.tiles_per_xcd * 8));
+  if (large) {
+    hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 0, 256, 256, 4, 4>), grid, dim3(1024), 0, stream, p);
+  } else {
+    const bool full = aligned && p.M % 128 == 0 && p.N % 128 == 0 && p.K % HBK == 0 && p.K > 0;
+    if (full) hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 0, 128, 128, 2, 2>), grid, dim3(256), 0, stream, p);
+    else hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 1, 128, 128, 2, 2>), grid, dim3(256), 0, stream, p);
+  }
   GPD_HIP(hipGetLastError());
   return GPD_OK;
 }
@@ -516,7 +547,9 @@ gpd_status_t launch_f32(hipStream_t stream, GemmParams p, int64_t batch, bool al
 #ifdef GPD_FORCE_SMALL
   const bool large = false;
 #else
-  const bool large = aligned && p.M % 256 == 0 && p.N % 256 == 0 && p.K % BK == 0 && p.K > 0 &&
+  // short contractions are dominated by per-tile prologue / epilogue, which only overlap with
+  // matrix work when several workgroups share a CU: keep the small shape for them
+  const bool large = aligned && p.M % 256 == 0 && p.N % 256 == 0 && p.K % BK == 0 && p.K >= 1024 &&
                      (int64_t)(p.M / 256) * (p.N / 256) * batch >= 256;
 #endif
   const int tbm = large ? 256 : 128, tbn = large ? 256 : 128;
@@ -561,25 +594,17 @@ gpd_status_t launch_gemm(hipStream_t stream, const GemmArgs& a) {
     h.M = (int)a.M; h.N = (int)a.N; h.K = (int)a.K;
     h.lda = a.lda; h.ldb = a.ldb; h.ldc = a.ldc;
     h.sA = a.strideA; h.sB = a.strideB; h.sC = a.strideC;
-    h.tiles_m = (int)((a.M + BM - 1) / BM);
-    h.tiles_n = (int)((a.N + BN - 1) / BN);
-    const int64_t tot = (int64_t)h.tiles_m * h.tiles_n * a.batch;
-    if (tot > 0x0fffffff) return fail(GPD_E_SHAPE, "gemm: too many tiles");
-    h.total_tiles = (int)tot;
-    h.tiles_per_xcd = (int)((tot + 7) / 8);
     h.alpha = a.alpha; h.beta = a.beta;
     const int a_es = a.a_bf16 ? 2 : 4, b_es = a.b_bf16 ? 2 : 4;
     const bool al = ((uintptr_t)a.A % 16 == 0) && ((uintptr_t)a.B % 16 == 0) &&
                     (a.lda * a_es) % 16 == 0 && (a.ldb * b_es) % 16 == 0 &&
                     (a.strideA * a_es) % 16 == 0 && (a.strideB * b_es) % 16 == 0;
-    const bool fullh = a.M % BM == 0 && a.N % BN == 0 && a.K % HBK == 0 && a.K > 0;
-    const int mode = (al && fullh) ? 0 : 1;
-    if (!a.transA && !a.a_bf16 && !a.b_bf16) return launch_bf16_t<SRC_F32_KC, SRC_F32_RC>(stream, h, mode);
-    if (!a.transA && !a.a_bf16 && a.b_bf16) return launch_bf16_t<SRC_F32_KC, SRC_BF16_RC>(stream, h, mode);
-    if (!a.transA && a.a_bf16 && a.b_bf16) return launch_bf16_t<SRC_BF16_KC, SRC_BF16_RC>(stream, h, mode);
-    if (!a.transA && a.a_bf16 && !a.b_bf16) return launch_bf16_t<SRC_BF16_KC, SRC_F32_RC>(stream, h, mode);
-    if (a.transA && !a.b_bf16) return launch_bf16_t<SRC_F32_RC, SRC_F32_RC>(stream, h, mode);
-    return launch_bf16_t<SRC_F32_RC, SRC_BF16_RC>(stream, h, mode);
+    if (!a.transA && !a.a_bf16 && !a.b_bf16) return launch_bf16_t<SRC_F32_KC, SRC_F32_RC>(stream, h, a.batch, al);
+    if (!a.transA && !a.a_bf16 && a.b_bf16) return launch_bf16_t<SRC_F32_KC, SRC_BF16_RC>(stream, h, a.batch, al);
+    if (!a.transA && a.a_bf16 && a.b_bf16) return launch_bf16_t<SRC_BF16_KC, SRC_BF16_RC>(stream, h, a.batch, al);
+    if (!a.transA && a.a_bf16 && !a.b_bf16) return launch_bf16_t<SRC_BF16_KC, SRC_F32_RC>(stream, h, a.batch, al);
+    if (a.transA && !a.b_bf16) return launch_bf16_t<SRC_F32_RC, SRC_F32_RC>(stream, h, a.batch, al);
+    return launch_bf16_t<SRC_F32_RC, SRC_BF16_RC>(stream, h, a.batch, al);
   }
 
   GemmParams p;
