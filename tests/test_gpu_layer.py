@@ -162,3 +162,39 @@ def test_cfg2_full_size_steps():
         assert e1 < 1e-3 and e2 < 1e-3
     for l in range(3):
         assert rel_fro(to_np(mlp.Wts[l]), Wts_o[l]) < 1e-5
+
+
+def test_hip_graph_replay_matches_eager():
+    # a whole training iteration captured once as a HIP graph and replayed must leave exactly
+    # the coded weights the same calls leave when made one by one (the kernels are deterministic;
+    # tables are uploaded on first use, so every distinct call is made before the capture)
+    sizes, batch, m, n, P = (96, 128, 64, 10), 1, 4, 2, 24
+    Ws = [to_dev((w * 8).astype(np.float32)) for w in WL.mlp_init(sizes, seed=5)]
+    data = [WL.mlp_batch(5, t, sizes[0], sizes[-1], batch) for t in range(5)]
+    eager = CodedMLP(sizes, batch, m, n, 1, 1, P)
+    eager.encode_weights(Ws)
+    for X, Y in data:
+        eager.step(to_dev(X), to_dev(Y), 0.5)
+    torch.cuda.synchronize()
+
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        gm = CodedMLP(sizes, batch, m, n, 1, 1, P, stream=side)
+        gm.encode_weights(Ws)
+        Xs, Ys = to_dev(data[0][0]).clone(), to_dev(data[0][1]).clone()
+        snapshot = [w.clone() for w in gm.Wts]
+        gm.step(Xs, Ys, 0.5)                       # warm-up call: fills the table cache
+        for w, s0 in zip(gm.Wts, snapshot):
+            w.copy_(s0)                            # undo its update
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        yhat, _ = gm.step(Xs, Ys, 0.5)
+    for X, Y in data:
+        Xs.copy_(to_dev(X))
+        Ys.copy_(to_dev(Y))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+    for a, b in zip(eager.Wts, gm.Wts):
+        assert torch.equal(a, b)
