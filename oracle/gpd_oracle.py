@@ -23,7 +23,9 @@ Readings taken where the paper is silent (all restated in the design notes):
   * non-finite responses are treated as located errors (forced members of the
     support) and replaced by zero before any arithmetic;
   * after location the coefficients are interpolated by least squares from all
-    remaining (clean, present) nodes.
+    remaining (clean, present) nodes;
+  * whole-node errors (Sec. III error models) are located once for a whole stack
+    by the same search run on the aggregate of all element codewords (locate_nodes).
 Parity pins: see tests/test_oracle_*.py.  Unpinned: the numeric value of rho
 (this build's choice).
 """
@@ -580,6 +582,147 @@ def layer_update(Wt, Dlt, X, lp: LayerPlan, eta: float, decay: float = 0.0) -> n
         Dh = sum(dblk[i] * int_power(lp.points[p], lp.eUd[i]) for i in range(lp.m))
         Xh = sum(xblk[j] * int_power(lp.points[p], lp.eUx[j]) for j in range(lp.n))
         out[p] = (1.0 - decay) * Wt[p] + eta * (Dh @ Xh.T)
+    return out
+
+
+# --------------------------------------------------------------------------- node-level faults
+
+
+WILD = 2.0 ** 40      # responses of this magnitude or more are handled like non-finite ones
+
+
+@dataclass
+class NodeReport:
+    status: str = "clean"                    # 'clean' | 'located' | 'failed'
+    bad: tuple = ()                          # sorted global node indices found erroneous
+    energy: float = 0.0                      # sum over codewords of ||z||^2 (sanitised)
+    syndrome_energy: float = 0.0             # sum over codewords of ||Hz||^2
+    residual: float = 0.0                    # syndrome energy left outside span(H_bad)
+    threshold: float = 0.0                   # tau^2 of the aggregate test
+    gram: np.ndarray | None = None           # sum over codewords of (Hz)(Hz)^T
+
+
+def locate_nodes(Zt: np.ndarray, points: np.ndarray, K: int, present=None,
+                 rho: float = 2.0 ** -12, abs_floor: float = 0.0) -> NodeReport:
+    """Algorithm 1 (Sec. V) under the error models of Sec. III, where an erroneous node's
+    whole output is wrong: every element codeword z_c of the stack Zt[P, rows, cols] has
+    its errors on the same set of nodes, so the set is searched once for all codewords.
+
+      step 1: no errors if sum_c ||H z_c||^2 <= tau^2,
+              tau^2 = rho^2 * max(sum_c ||z_c||^2, n_codewords * abs_floor^2);
+      step 2: the smallest node set A such that every H z_c lies in span(H_A), tested in
+              aggregate: sum_c min_e ||H z_c - H_A e||^2 <= tau^2; inside one size the
+              set with the smallest residual wins;
+      step 3: accept only if |A| <= (number of rows of H) - 1, else decoding failure.
+    Nodes holding a non-finite value, or one of magnitude >= 2^40, are forced members of
+    A and those values are replaced by zero before any arithmetic."""
+    Zt = np.asarray(Zt, dtype=np.float64)
+    P = Zt.shape[0]
+    pres = np.ones(P, dtype=bool) if present is None else np.asarray(present).astype(bool)
+    S = np.flatnonzero(pres)
+    if len(S) < K:
+        raise TooFewResponses(f"{len(S)} responses present, {K} needed")
+    Z = Zt[S].reshape(len(S), -1)
+    ncw = Z.shape[1]
+    wild = ~np.isfinite(Z) | (np.abs(np.where(np.isfinite(Z), Z, 0.0)) >= WILD)
+    forced = tuple(int(q) for q in np.flatnonzero(wild.any(axis=1)))
+    Zs = np.where(wild, 0.0, Z)
+    rep = NodeReport()
+    r = len(S) - K
+    rep.energy = float((Zs * Zs).sum())
+    rep.threshold = rho * rho * max(rep.energy, ncw * abs_floor * abs_floor)
+    if r == 0:
+        rep.gram = np.zeros((0, 0))
+        if forced:
+            rep.status, rep.bad = "failed", tuple(int(S[q]) for q in forced)
+        return rep
+    H = parity_check(np.asarray(points, dtype=np.float64)[S], K)
+    Y = H @ Zs
+    rep.gram = Y @ Y.T
+    rep.syndrome_energy = float((Y * Y).sum())
+    rep.residual = rep.syndrome_energy
+    if not forced and rep.syndrome_energy <= rep.threshold:
+        return rep
+    free = [q for q in range(len(S)) if q not in forced]
+    for size in range(max(len(forced), 1), r):
+        best = None
+        for extra in itertools.combinations(free, size - len(forced)):
+            supp = tuple(sorted(forced + extra))
+            Hs = H[:, list(supp)]
+            E, *_ = np.linalg.lstsq(Hs, Y, rcond=None)
+            R = Y - Hs @ E
+            res = float((R * R).sum())
+            if res <= rep.threshold and (best is None or res < best[0]):
+                best = (res, supp)
+        if best is not None:
+            rep.status, rep.residual = "located", best[0]
+            rep.bad = tuple(int(S[q]) for q in best[1])
+            return rep
+    rep.status, rep.bad = "failed", tuple(int(S[q]) for q in forced)
+    return rep
+
+
+def decode_nodes(Ct: np.ndarray, plan: Plan, present=None, mode: str = "lsq_all",
+                 rho: float = 2.0 ** -12, abs_floor: float = 0.0):
+    """Locate the erroneous nodes once for the whole response stack, then decode with
+    those nodes left out like stragglers (Sec. V: errors whose locations are known are
+    erasures).  Returns (C or None on failure, NodeReport)."""
+    rep = locate_nodes(Ct, plan.points, plan.K, present, rho, abs_floor)
+    if rep.status == "failed":
+        return None, rep
+    pres = np.ones(plan.P, dtype=bool) if present is None else np.asarray(present).astype(bool).copy()
+    pres[list(rep.bad)] = False
+    C, _ = decode(Ct, plan, pres, mode)
+    return C, rep
+
+
+def weight_polynomial_terms(lp: LayerPlan) -> int:
+    """Number of coefficients of W~(b) after the substitution: max exponent + 1 = mn
+    (footnote on regeneration, Sec. VII)."""
+    return int(lp.fwd.eA.max()) + 1
+
+
+def layer_regenerate(Wt: np.ndarray, lp: LayerPlan, bad, mode: str = "lsq_all") -> np.ndarray:
+    """Regeneration (Sec. VII): the coded block of every node in `bad` is re-evaluated from
+    the polynomial W~(b) (mn coefficients) interpolated through nodes known to be correct:
+    'first_k' takes the first mn good nodes by index, 'lsq_all' all good nodes."""
+    Wt = np.asarray(Wt, dtype=np.float64)
+    P = Wt.shape[0]
+    Kw = weight_polynomial_terms(lp)
+    isbad = np.zeros(P, dtype=bool)
+    isbad[list(bad)] = True
+    good = np.flatnonzero(~isbad)
+    if len(good) < Kw:
+        raise TooFewResponses(f"{len(good)} good nodes, {Kw} needed")
+    coef = interpolate(Wt[good].reshape(len(good), -1), lp.points[good], Kw, mode)
+    out = Wt.copy()
+    for p in np.flatnonzero(isbad):
+        acc = np.zeros(coef.shape[1])
+        for e in range(Kw):
+            acc += coef[e] * int_power(lp.points[p], e)
+        out[p] = acc.reshape(Wt.shape[1:])
+    return out
+
+
+def layer_project(Wt: np.ndarray, lp: LayerPlan, present=None) -> np.ndarray:
+    """Nearest stack (least squares, node by node) whose element codewords are exact
+    evaluations of a polynomial with mn coefficients: interpolate from the present nodes,
+    re-evaluate at every node.  (Regeneration applied to all nodes at once; this build
+    uses it to remove the rounding drift of many coded updates.)"""
+    Wt = np.asarray(Wt, dtype=np.float64)
+    P = Wt.shape[0]
+    Kw = weight_polynomial_terms(lp)
+    pres = np.ones(P, dtype=bool) if present is None else np.asarray(present).astype(bool)
+    S = np.flatnonzero(pres)
+    if len(S) < Kw:
+        raise TooFewResponses(f"{len(S)} nodes present, {Kw} needed")
+    coef = interpolate(Wt[S].reshape(len(S), -1), lp.points[S], Kw, "lsq_all")
+    out = np.empty_like(Wt)
+    for p in range(P):
+        acc = np.zeros(coef.shape[1])
+        for e in range(Kw):
+            acc += coef[e] * int_power(lp.points[p], e)
+        out[p] = acc.reshape(Wt.shape[1:])
     return out
 
 
