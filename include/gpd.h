@@ -65,6 +65,13 @@ typedef enum {
   GPD_DEC_LSQ_ALL = 1     /* least squares over every present node                         */
 } gpd_decmode_t;
 
+typedef enum {
+  GPD_CORRECT_NONE = 0,     /* erasures only                                                  */
+  GPD_CORRECT_ELEMENTS = 1, /* Algorithm 1 on every element codeword (errors anywhere)        */
+  GPD_CORRECT_NODES = 2     /* Algorithm 1 once for the whole stack: an erroneous node's whole
+                               output is wrong (error models of Sec. III); see gpd_locate_nodes */
+} gpd_correct_t;
+
 typedef struct gpd_plan gpd_plan_t;
 typedef struct gpd_layer gpd_layer_t;
 
@@ -144,8 +151,9 @@ typedef struct {
  *   present: host uint8[P], non-zero = node responded; NULL = all.  Fewer than K present
  *            -> GPD_E_TOO_FEW, nothing written.
  *   mode:    which present nodes the interpolation uses (see gpd_decmode_t).
- *   correct_errors != 0: all present nodes are used.  Step 1: ||Hz||_2 <= tau(z) with H
- *            an orthonormal parity check of the present nodes; steps 2-3: smallest support
+ *   correct_errors == GPD_CORRECT_ELEMENTS: all present nodes are used.  Step 1:
+ *            ||Hz||_2 <= tau(z) with H an orthonormal parity check of the present nodes;
+ *            steps 2-3: smallest support
  *            (at most |S| - K - 1 nodes, smallest least-squares residual inside one size)
  *            whose columns of H explain Hz up to tau(z); then least squares from the
  *            remaining nodes.  Non-finite responses count as located errors.  A codeword
@@ -153,6 +161,12 @@ typedef struct {
  *            the report and its output is the uncorrected least-squares value.
  *            Requires workspace (device, 256-byte aligned, workspace_bytes from
  *            gpd_plan_info).
+ *   correct_errors == GPD_CORRECT_NODES: gpd_locate_nodes first (the call waits for the
+ *            stream), then the nodes found erroneous are left out like stragglers and the
+ *            rest is decoded with `mode`.  In the report n_located = number of bad nodes
+ *            times the codewords, node_err_count[p] = codewords for a bad node p, n_flagged
+ *            = all codewords if any error was detected; on failure (GPD_E_DECODE_FAIL)
+ *            the output is decoded from all present nodes.
  *   C:       device fp32 N1 x Nc, leading dimension ldc.
  *   report:  host, or NULL.  With a report the call waits for the stream; without one it
  *            is asynchronous and GPD_E_DECODE_FAIL cannot be returned.
@@ -160,6 +174,40 @@ typedef struct {
 gpd_status_t gpd_decode(const gpd_plan_t* plan, const float* Ct, const uint8_t* present,
                         int32_t mode, int32_t correct_errors, float* C, int64_t ldc,
                         void* workspace, size_t workspace_bytes, gpd_report_t* report);
+
+/* ------------------------------------------------------------------ node-level faults */
+
+/* Host-side result of a node search. */
+typedef struct {
+  int32_t status;               /* GPD_OK (no errors, or erroneous nodes located) or
+                                   GPD_E_DECODE_FAIL (errors detected, too many to locate)     */
+  int32_t n_present;
+  int32_t n_bad;                /* number of nodes found erroneous                             */
+  int32_t exhaustive;           /* 1 = every node set of each size tried; 0 = some size had more
+                                   than 2^22 sets and only the most likely one was tested      */
+  uint8_t bad[GPD_MAX_P];       /* 1 = node found erroneous                                    */
+  uint8_t wild[GPD_MAX_P];      /* 1 = node held a non-finite value or one of magnitude >= 2^40 */
+  double energy;                /* sum over codewords of ||z||^2 (wild values taken as 0)      */
+  double syndrome_energy;       /* sum over codewords of ||Hz||^2                              */
+  double residual;              /* syndrome energy not explained by the bad nodes              */
+  double threshold;             /* tau^2 = rho^2 max(energy, codewords * abs_floor^2)          */
+} gpd_node_report_t;
+
+/* Location of erroneous nodes for a whole response stack (Sec. V Algorithm 1 under the error
+ * models of Sec. III, where a faulty node's entire output is wrong, so every element codeword
+ * has its errors on the same nodes).  One pass over Ct accumulates G = sum_c (H z_c)(H z_c)^T
+ * and sum_c ||z_c||^2 on the GPU (fp64 accumulation); the search runs on the host:
+ *   step 1: no errors if trace(G) <= tau^2;
+ *   step 2: smallest node set A with trace((I - Pi_A) G) <= tau^2, Pi_A the projector on the
+ *           span of A's columns of H; inside one size the smallest residual wins;
+ *   step 3: at most |S| - K - 1 nodes, else decoding failure.
+ * Nodes holding a non-finite value or one of magnitude >= 2^40 are always in A and such
+ * values count as zero.  Ct is not modified.  The call waits for the stream.
+ *   workspace: device, 256-byte aligned, workspace_bytes from gpd_plan_info.
+ * Returns GPD_E_DECODE_FAIL (also in report->status) on failure. */
+gpd_status_t gpd_locate_nodes(const gpd_plan_t* plan, const float* Ct, const uint8_t* present,
+                              void* workspace, size_t workspace_bytes, gpd_node_report_t* report,
+                              double* gram /* host [(|S|-K)^2], basis of gpd_host_parity_check; or NULL */);
 
 /* ------------------------------------------------------------------ coded DNN layer */
 
@@ -206,7 +254,8 @@ gpd_status_t gpd_layer_decode_weights(const gpd_layer_t* layer, const float* Wt,
  *                       in place (Eq. "coded update"; decay = eta * lambda).
  *   X:   device fp32 N_in x batch (ld = batch), the layer input.
  *   Dlt: device fp32 N_out x batch (ld = batch), ignored in FORWARD.
- *   present / correct_errors / report: as in gpd_decode, applied to the P node outputs.
+ *   present / correct_errors / report: as in gpd_decode (gpd_correct_t), applied to the P
+ *        node outputs.
  *   workspace: device, 256-byte aligned, workspace_bytes from gpd_layer_info.
  */
 gpd_status_t gpd_coded_layer_step(gpd_layer_t* layer, int32_t phase, float* Wt,
@@ -221,6 +270,36 @@ gpd_status_t gpd_coded_layer_step(gpd_layer_t* layer, int32_t phase, float* Wt,
  * outputs), 4 = Dhat_p, 5 = Xhat_p (update operands).  For inspection and fault injection. */
 gpd_status_t gpd_layer_workspace_view(const gpd_layer_t* layer, int32_t which, size_t* byte_offset,
                                       int64_t* rows, int64_t* cols);
+
+typedef enum {
+  GPD_STACK_WEIGHTS = 0,    /* W~: [P][wt_rows][wt_cols], code of mn coefficients               */
+  GPD_STACK_FORWARD = 1,    /* S~: [P][wt_rows][batch/d1], K_f coefficients                     */
+  GPD_STACK_BACKWARD = 2    /* C~: [P][wt_cols][batch/d2], K_b coefficients                     */
+} gpd_stack_t;
+
+/* gpd_locate_nodes for one of the layer's coded stacks: the stored weights themselves (every
+ * element position of the P blocks W~_p is a word of the (P, mn) code, footnote on regeneration,
+ * Sec. VII) or the node outputs of the last forward / backward product (the views 1 and 3 of
+ * gpd_layer_workspace_view, or any stack of that shape).  The weights are always screened with
+ * the fp32 threshold.  workspace: the layer's. */
+gpd_status_t gpd_layer_locate_nodes(const gpd_layer_t* layer, int32_t which, const float* stack,
+                                    const uint8_t* present, void* workspace, size_t workspace_bytes,
+                                    gpd_node_report_t* report, double* gram);
+
+/* Regeneration (Sec. VII): W~_p of every node with bad[p] != 0 is recomputed in place from
+ * nodes known to be correct, W~_p = sum_q L_q(b_p) W~_q, where L interpolates the degree mn-1
+ * polynomial W~(b): mode GPD_DEC_FIRST_K uses the first mn good nodes by index (the paper's
+ * count), GPD_DEC_LSQ_ALL all good nodes.  bad: host uint8[P].  Fewer than mn good nodes ->
+ * GPD_E_TOO_FEW.  Asynchronous. */
+gpd_status_t gpd_layer_regenerate(const gpd_layer_t* layer, float* Wt, const uint8_t* bad,
+                                  int32_t mode);
+
+/* Projection of the stored stack onto the code: every element codeword of W~ is replaced by
+ * the nearest word (least squares over the present nodes) that is an exact evaluation of a
+ * polynomial with mn coefficients; all P blocks are rewritten in place.  Removes the part of
+ * the rounding drift of many coded updates that the decoder would not see anyway and
+ * regenerates absent nodes.  Asynchronous. */
+gpd_status_t gpd_layer_project(const gpd_layer_t* layer, float* Wt, const uint8_t* present);
 
 void gpd_layer_destroy(gpd_layer_t* layer);
 
@@ -250,6 +329,18 @@ gpd_status_t gpd_host_code(int32_t m, int32_t n, int32_t d, int32_t P, int32_t s
 gpd_status_t gpd_host_decode_matrices(int32_t m, int32_t n, int32_t d, int32_t P, int32_t subst,
                                       const double* points, const uint8_t* present, int32_t first_k,
                                       double* D, double* H, int32_t* n_present);
+
+/* Orthonormal parity check H [(n_present-K)][n_present] of the (n_present, K) code on the
+ * present nodes (Sec. V, paragraph before Algorithm 1), as the library computes it. */
+gpd_status_t gpd_host_parity_check(int32_t P, int32_t K, const double* points,
+                                   const uint8_t* present, double* H, int32_t* n_present);
+
+/* The host half of gpd_locate_nodes without a GPU: gram = sum_c (H z_c)(H z_c)^T, row-major
+ * [(n_present-K)^2] in the basis of gpd_host_parity_check; forced: host uint8[P] or NULL. */
+gpd_status_t gpd_host_locate_nodes(int32_t P, int32_t K, const double* points,
+                                   const uint8_t* present, const double* gram, double energy,
+                                   int64_t n_codewords, double rho, double abs_floor,
+                                   const uint8_t* forced, gpd_node_report_t* report);
 
 /* ------------------------------------------------------------------ misc */
 

@@ -4,4 +4,6 @@ from .binding import *  # noqa: F401,F403
 from .binding import (GpdError, Layer, Plan, Report, load_library, gpd_coded_layer_step, gpd_decode,
                       gpd_encode, gpd_host_code, gpd_host_decode_matrices, gpd_l2_delta,
                       gpd_layer_create, gpd_layer_decode_weights, gpd_layer_encode_weights, gpd_plan,
-                      gpd_sigmoid_bwd, gpd_sigmoid_fwd, gpd_version, gpd_worker_products)
+                      gpd_sigmoid_bwd, gpd_sigmoid_fwd, gpd_version, gpd_worker_products,
+                      NodeReport, gpd_locate_nodes, gpd_layer_locate_nodes, gpd_layer_regenerate,
+                      gpd_layer_project, gpd_host_parity_check, gpd_host_locate_nodes)

@@ -22,6 +22,8 @@ GPD_F32, GPD_BF16 = 0, 1
 GPD_SUB_AUTO, GPD_SUB_U_VN, GPD_SUB_V_UM = 0, 1, 2
 GPD_DEC_FIRST_K, GPD_DEC_LSQ_ALL = 0, 1
 GPD_STEP_FORWARD, GPD_STEP_BACKWARD_UPDATE = 0, 1
+GPD_CORRECT_NONE, GPD_CORRECT_ELEMENTS, GPD_CORRECT_NODES = 0, 1, 2
+GPD_STACK_WEIGHTS, GPD_STACK_FORWARD, GPD_STACK_BACKWARD = 0, 1, 2
 
 STATUS_NAMES = ["OK", "E_INVALID", "E_SHAPE", "E_POINTS", "E_TOO_FEW", "E_DECODE_FAIL",
                 "E_WORKSPACE", "E_DEVICE", "E_UNSUPPORTED"]
@@ -32,6 +34,8 @@ EXPORTS = [
     "gpd_layer_encode_weights", "gpd_layer_decode_weights", "gpd_coded_layer_step",
     "gpd_layer_workspace_view", "gpd_layer_destroy", "gpd_sigmoid_fwd", "gpd_sigmoid_bwd", "gpd_l2_delta",
     "gpd_host_code", "gpd_host_decode_matrices", "gpd_last_error", "gpd_version",
+    "gpd_locate_nodes", "gpd_layer_locate_nodes", "gpd_layer_regenerate", "gpd_layer_project",
+    "gpd_host_parity_check", "gpd_host_locate_nodes",
 ]
 
 
@@ -62,6 +66,13 @@ class _Report(C.Structure):
                 ("node_err_count", C.c_int32 * GPD_MAX_P),
                 ("max_syndrome_ratio", C.c_float), ("reserved", C.c_int32),
                 ("located_cap", C.c_int64), ("located", C.POINTER(_Located))]
+
+
+class _NodeReport(C.Structure):
+    _fields_ = [("status", C.c_int32), ("n_present", C.c_int32), ("n_bad", C.c_int32),
+                ("exhaustive", C.c_int32), ("bad", C.c_uint8 * GPD_MAX_P), ("wild", C.c_uint8 * GPD_MAX_P),
+                ("energy", C.c_double), ("syndrome_energy", C.c_double), ("residual", C.c_double),
+                ("threshold", C.c_double)]
 
 
 class _LayerDesc(C.Structure):
@@ -110,6 +121,13 @@ def load_library():
     lib.gpd_host_code.argtypes = [i32, i32, i32, i32, i32, vp, C.POINTER(i32), vp, vp, vp, vp]
     lib.gpd_host_decode_matrices.argtypes = [i32, i32, i32, i32, i32, vp, vp, i32, vp, vp,
                                              C.POINTER(i32)]
+    lib.gpd_locate_nodes.argtypes = [vp, vp, vp, vp, sz, C.POINTER(_NodeReport), vp]
+    lib.gpd_layer_locate_nodes.argtypes = [vp, i32, vp, vp, vp, sz, C.POINTER(_NodeReport), vp]
+    lib.gpd_layer_regenerate.argtypes = [vp, vp, vp, i32]
+    lib.gpd_layer_project.argtypes = [vp, vp, vp]
+    lib.gpd_host_parity_check.argtypes = [i32, i32, vp, vp, vp, C.POINTER(i32)]
+    lib.gpd_host_locate_nodes.argtypes = [i32, i32, vp, vp, vp, C.c_double, i64, C.c_double, C.c_double,
+                                          vp, C.POINTER(_NodeReport)]
     lib.gpd_last_error.restype = C.c_char_p
     lib.gpd_version.restype = C.c_char_p
     for name in EXPORTS:
@@ -310,7 +328,7 @@ def gpd_decode(plan: Plan, Ct, present=None, mode=GPD_DEC_FIRST_K, correct_error
     rep = buf = None
     if want_report:
         rep, buf = _make_report(located_cap)
-    st = lib.gpd_decode(plan.handle, _ptr(Ct), _ptr(pres), mode, int(bool(correct_errors)),
+    st = lib.gpd_decode(plan.handle, _ptr(Ct), _ptr(pres), mode, int(correct_errors),
                         _ptr(C_out), C_out.stride(0), ws_ptr, ws_bytes,
                         C.byref(rep) if rep is not None else None)
     _check(st, ok=(GPD_OK,) if raise_on_fail else (GPD_OK, GPD_E_DECODE_FAIL))
@@ -425,10 +443,138 @@ def gpd_coded_layer_step(layer: Layer, phase, Wt, X, Dlt=None, eta=0.0, decay=0.
     if want_report:
         rep, buf = _make_report(located_cap)
     st = lib.gpd_coded_layer_step(layer.handle, phase, _ptr(Wt), _ptr(X), _ptr(Dlt), eta, decay,
-                                  _ptr(out), _ptr(pres), int(bool(correct_errors)),
+                                  _ptr(out), _ptr(pres), int(correct_errors),
                                   ws.data_ptr(), ws.numel(), C.byref(rep) if rep is not None else None)
     _check(st, ok=(GPD_OK, GPD_E_DECODE_FAIL))
     return out, (_read_report(rep, buf, layer.P) if rep is not None else None)
+
+
+# ------------------------------------------------------------------ node-level faults
+
+
+@dataclass
+class NodeReport:
+    status: int = 0
+    n_present: int = 0
+    bad: tuple = ()                 # node indices found erroneous, ascending
+    wild: tuple = ()                # nodes that held a non-finite or huge value
+    exhaustive: bool = True
+    energy: float = 0.0
+    syndrome_energy: float = 0.0
+    residual: float = 0.0
+    threshold: float = 0.0
+
+
+def _read_node_report(rep: _NodeReport, P: int) -> NodeReport:
+    return NodeReport(rep.status, rep.n_present, tuple(p for p in range(P) if rep.bad[p]),
+                      tuple(p for p in range(P) if rep.wild[p]), bool(rep.exhaustive), rep.energy,
+                      rep.syndrome_energy, rep.residual, rep.threshold)
+
+
+def _gram_buffer(want, P, K, pres):
+    if not want:
+        return None
+    ns = P if pres is None else int(np.count_nonzero(pres))
+    return np.zeros((max(ns - K, 0), max(ns - K, 0)))
+
+
+def gpd_locate_nodes(plan: Plan, Ct, present=None, workspace=None, want_gram=False):
+    """NodeReport, or (NodeReport, gram) with want_gram."""
+    import torch
+    lib = load_library()
+    _require_f32_cuda(Ct, "Ct")
+    sh = (plan.P, plan.N1 // plan.m, plan.Nc // plan.d)
+    if tuple(Ct.shape) != sh or not Ct.is_contiguous():
+        raise ValueError("Ct does not match the plan")
+    if workspace is None:
+        workspace = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device=Ct.device)
+    pres = _present_array(present, plan.P)
+    rep = _NodeReport()
+    gram = _gram_buffer(want_gram, plan.P, plan.K, pres)
+    st = lib.gpd_locate_nodes(plan.handle, _ptr(Ct), _ptr(pres), workspace.data_ptr(), workspace.numel(),
+                              C.byref(rep), gram.ctypes.data if gram is not None and gram.size else None)
+    _check(st, ok=(GPD_OK, GPD_E_DECODE_FAIL))
+    out = _read_node_report(rep, plan.P)
+    return (out, gram) if want_gram else out
+
+
+def gpd_layer_locate_nodes(layer: Layer, which, stack, present=None, want_gram=False):
+    lib = load_library()
+    _require_f32_cuda(stack, "stack")
+    shapes = {GPD_STACK_WEIGHTS: (layer.wt_rows, layer.wt_cols),
+              GPD_STACK_FORWARD: (layer.wt_rows, layer.batch // layer.desc.d1),
+              GPD_STACK_BACKWARD: (layer.wt_cols, layer.batch // layer.desc.d2)}
+    if which not in shapes or tuple(stack.shape) != (layer.P,) + shapes[which] or not stack.is_contiguous():
+        raise ValueError("stack does not match the layer")
+    ws = layer.workspace(stack.device)
+    pres = _present_array(present, layer.P)
+    rep = _NodeReport()
+    K = {GPD_STACK_WEIGHTS: layer.desc.m * layer.desc.n, GPD_STACK_FORWARD: layer.Kf,
+         GPD_STACK_BACKWARD: layer.Kb}[which]
+    gram = _gram_buffer(want_gram, layer.P, K, pres)
+    st = lib.gpd_layer_locate_nodes(layer.handle, which, _ptr(stack), _ptr(pres), ws.data_ptr(), ws.numel(),
+                                    C.byref(rep), gram.ctypes.data if gram is not None and gram.size else None)
+    _check(st, ok=(GPD_OK, GPD_E_DECODE_FAIL))
+    out = _read_node_report(rep, layer.P)
+    return (out, gram) if want_gram else out
+
+
+def _weights_ok(layer: Layer, Wt):
+    _require_f32_cuda(Wt, "Wt")
+    if tuple(Wt.shape) != (layer.P, layer.wt_rows, layer.wt_cols) or not Wt.is_contiguous():
+        raise ValueError("Wt does not match the layer")
+
+
+def gpd_layer_regenerate(layer: Layer, Wt, bad, mode=GPD_DEC_LSQ_ALL):
+    """bad: iterable of node indices; their blocks of Wt are recomputed in place."""
+    lib = load_library()
+    _weights_ok(layer, Wt)
+    mask = np.zeros(layer.P, dtype=np.uint8)
+    for p in bad:
+        mask[int(p)] = 1
+    _check(lib.gpd_layer_regenerate(layer.handle, _ptr(Wt), mask.ctypes.data, mode))
+    return Wt
+
+
+def gpd_layer_project(layer: Layer, Wt, present=None):
+    lib = load_library()
+    _weights_ok(layer, Wt)
+    pres = _present_array(present, layer.P)
+    _check(lib.gpd_layer_project(layer.handle, _ptr(Wt), _ptr(pres)))
+    return Wt
+
+
+def gpd_host_parity_check(P, K, points=None, present=None):
+    """H[n_present-K, n_present] as the library computes it; no GPU needed."""
+    lib = load_library()
+    pres = _present_array(present, P)
+    ns = P if pres is None else int(np.count_nonzero(pres))
+    if ns < K:
+        raise GpdError(GPD_E_TOO_FEW, "too few responses")
+    H = np.zeros((ns - K, ns))
+    pin = None if points is None else np.ascontiguousarray(np.asarray(points, dtype=np.float64))
+    nsv = C.c_int32()
+    _check(lib.gpd_host_parity_check(P, K, _ptr(pin), _ptr(pres), H.ctypes.data, C.byref(nsv)))
+    return H
+
+
+def gpd_host_locate_nodes(P, K, gram, energy, n_codewords, rho, abs_floor=0.0, points=None, present=None,
+                          forced=None) -> NodeReport:
+    """The host half of gpd_locate_nodes on a Gram matrix given in the basis of gpd_host_parity_check."""
+    lib = load_library()
+    pres = _present_array(present, P)
+    pin = None if points is None else np.ascontiguousarray(np.asarray(points, dtype=np.float64))
+    g = np.ascontiguousarray(np.asarray(gram, dtype=np.float64))
+    f = None
+    if forced is not None:
+        f = np.zeros(P, dtype=np.uint8)
+        f[list(forced)] = 1
+    rep = _NodeReport()
+    st = lib.gpd_host_locate_nodes(P, K, _ptr(pin), _ptr(pres), g.ctypes.data if g.size else None,
+                                   float(energy), int(n_codewords), float(rho), float(abs_floor),
+                                   _ptr(f), C.byref(rep))
+    _check(st, ok=(GPD_OK, GPD_E_DECODE_FAIL))
+    return _read_node_report(rep, P)
 
 
 def gpd_sigmoid_fwd(s, y=None, stream=None):

@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgpd.so")
 
-SOURCES = ["gpd_host.cpp", "gpd_combine.hip", "gpd_gemm.hip", "gpd_locate.hip", "gpd_api.hip",
+SOURCES = ["gpd_host.cpp", "gpd_combine.hip", "gpd_gemm.hip", "gpd_locate.hip", "gpd_nodes.hip", "gpd_api.hip",
            "gpd_layer.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",

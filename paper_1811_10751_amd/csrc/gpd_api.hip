@@ -145,6 +145,8 @@ extern "C" gpd_status_t gpd_plan(const gpd_problem_t* pr, gpd_plan_t** out) {
                                : (pr->worker_dtype == GPD_BF16 ? 0.125 : 1.0 / 4096.0);
   pl->abs_floor = pr->abs_floor;
   decode_workspace_layout(pl->ahC * pl->awC, &pl->flag_cap, &pl->loc_cap, &pl->workspace_bytes);
+  pl->workspace_bytes = std::max(pl->workspace_bytes,
+                                 gram_workspace_bytes(pl->ahC * pl->awC, pl->code.P - pl->code.K));
 
   int ndev = 0;
   if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) {
@@ -328,6 +330,11 @@ gpd_status_t run_decode(hipStream_t stream, TableRing* ring, const DecodeJob& jo
   // with block limits (zero-padded ragged edges) the caller of run_decode vouches for ld_out
   if (job.out_cols.empty() && ld_out < job.grid_c * job.bw)
     return fail(GPD_E_SHAPE, "decode: output leading dimension too small");
+  if (correct == GPD_CORRECT_NODES)
+    return run_decode_nodes(stream, ring, job, Zt, present, mode, out, ld_out, workspace,
+                            workspace_bytes, report);
+  if (correct != GPD_CORRECT_NONE && correct != GPD_CORRECT_ELEMENTS)
+    return fail(GPD_E_INVALID, "decode: unknown correct_errors %d", correct);
   const bool corr = correct != 0;
   if (corr) {
     if (!workspace || workspace_bytes < job.workspace_bytes || ((uintptr_t)workspace & 255))
@@ -439,7 +446,55 @@ gpd_status_t run_decode(hipStream_t stream, TableRing* ring, const DecodeJob& jo
   return GPD_OK;
 }
 
+gpd_status_t run_decode_nodes(hipStream_t stream, TableRing* ring, const DecodeJob& job, const float* Zt,
+                              const uint8_t* present, int mode, float* out, int64_t ld_out,
+                              void* workspace, size_t workspace_bytes, gpd_report_t* report) {
+  const int P = (int)job.pts->size();
+  const int64_t ncw = job.bh * job.bw;
+  gpd_located_t* keep_ptr = report ? report->located : nullptr;
+  const int64_t keep_cap = report ? report->located_cap : 0;
+  gpd_node_report_t nr;
+  gpd_status_t st = run_locate_nodes(stream, ring, *job.pts, job.K, ncw, Zt, present, job.rho,
+                                     job.abs_floor, workspace, workspace_bytes, &nr);
+  if (report) {
+    std::memset(report, 0, sizeof(*report));
+    report->located = keep_ptr; report->located_cap = keep_cap;
+    report->n_present = nr.n_present;
+    report->status = st;
+  }
+  if (st != GPD_OK && st != GPD_E_DECODE_FAIL) return st;
+  const bool failed = st == GPD_E_DECODE_FAIL;
+  const std::string why = failed ? std::string(gpd_last_error()) : std::string();
+  // nodes found erroneous are left out like stragglers; after a failure all present nodes are used
+  uint8_t keep[GPD_MAX_P];
+  for (int p = 0; p < P; ++p) keep[p] = ((!present || present[p]) && (failed || !nr.bad[p])) ? 1 : 0;
+  st = run_decode(stream, ring, job, Zt, keep, mode, GPD_CORRECT_NONE, out, ld_out, nullptr, 0, nullptr);
+  if (st != GPD_OK) { if (report) report->status = st; return st; }
+  if (report) {
+    const bool detected = failed || nr.n_bad > 0;
+    report->n_flagged = detected ? ncw : 0;
+    report->n_failed = failed ? ncw : 0;
+    report->n_located = failed ? 0 : (int64_t)nr.n_bad * ncw;
+    for (int p = 0; p < P; ++p)
+      report->node_err_count[p] = (!failed && nr.bad[p]) ? (int32_t)std::min<int64_t>(ncw, 0x7fffffff) : 0;
+    report->max_syndrome_ratio = nr.threshold > 0 ? (float)std::sqrt(nr.residual / nr.threshold) : 0.f;
+    report->status = failed ? GPD_E_DECODE_FAIL : GPD_OK;
+    GPD_HIP(hipStreamSynchronize(stream));
+  }
+  if (failed) return fail(GPD_E_DECODE_FAIL, "%s", why.c_str());
+  return GPD_OK;
+}
+
 }  // namespace gpd
+
+extern "C" gpd_status_t gpd_locate_nodes(const gpd_plan_t* plc, const float* Ct, const uint8_t* present,
+                                         void* workspace, size_t workspace_bytes,
+                                         gpd_node_report_t* report, double* gram) {
+  gpd_plan_t* pl = const_cast<gpd_plan_t*>(plc);
+  if (!pl || !report) return fail(GPD_E_INVALID, "gpd_locate_nodes: null argument");
+  return run_locate_nodes(pl->stream, &pl->ring, pl->code.pts, pl->code.K, pl->ahC * pl->awC, Ct, present,
+                          pl->rho, pl->abs_floor, workspace, workspace_bytes, report, gram);
+}
 
 extern "C" gpd_status_t gpd_decode(const gpd_plan_t* plc, const float* Ct, const uint8_t* present,
                                    int32_t mode, int32_t correct_errors, float* C, int64_t ldc,

@@ -267,6 +267,9 @@ gpd_status_t launch_combine(hipStream_t stream, const CombineTable& t, const flo
   // small launches (the vectors of the batch-1 layer step) are latency-bound: give every
   // output block its own threads instead of looping over the outputs inside one thread
   p.q_chunk = (rows * p.cols_vec < 16384) ? 1 : t.nout;
+  // in place (outputs overwrite inputs): a thread must hold all its inputs before any output
+  // of its element is written, so the outputs cannot be split over several workgroups
+  if ((const void*)in == (const void*)out) p.q_chunk = t.nout;
   if (vec == 4) return launch_v<4>(stream, p, out_bf16, screen.enabled);
   if (vec == 2) return launch_v<2>(stream, p, out_bf16, screen.enabled);
   return launch_v<1>(stream, p, out_bf16, screen.enabled);

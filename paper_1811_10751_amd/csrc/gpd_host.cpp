@@ -196,6 +196,215 @@ gpd_status_t decode_matrices(const std::vector<double>& pts, const std::vector<i
   return GPD_OK;
 }
 
+// ---------------------------------------------------------------- node-level error location
+
+namespace {
+
+// Eigenvalues (descending) and eigenvectors (columns of `vec`, row-major n x n) of the symmetric
+// n x n matrix a: cyclic Jacobi rotations.
+void jacobi_eigen(std::vector<double> a, int n, std::vector<double>* val, std::vector<double>* vec) {
+  std::vector<double>& v = *vec;
+  v.assign((size_t)n * n, 0.0);
+  for (int i = 0; i < n; ++i) v[(size_t)i * n + i] = 1.0;
+  for (int sweep = 0; sweep < 60; ++sweep) {
+    double off = 0.0, diag = 0.0;
+    for (int i = 0; i < n; ++i)
+      for (int j = 0; j < n; ++j) (i == j ? diag : off) += a[(size_t)i * n + j] * a[(size_t)i * n + j];
+    if (off <= 1e-30 * diag || off == 0.0) break;
+    for (int p = 0; p < n - 1; ++p)
+      for (int q = p + 1; q < n; ++q) {
+        const double apq = a[(size_t)p * n + q];
+        if (apq == 0.0) continue;
+        const double theta = (a[(size_t)q * n + q] - a[(size_t)p * n + p]) / (2.0 * apq);
+        const double t = (theta >= 0 ? 1.0 : -1.0) / (std::fabs(theta) + std::sqrt(theta * theta + 1.0));
+        const double c = 1.0 / std::sqrt(t * t + 1.0), sn = t * c;
+        for (int k = 0; k < n; ++k) {          // columns p, q of a
+          const double akp = a[(size_t)k * n + p], akq = a[(size_t)k * n + q];
+          a[(size_t)k * n + p] = c * akp - sn * akq;
+          a[(size_t)k * n + q] = sn * akp + c * akq;
+        }
+        for (int k = 0; k < n; ++k) {          // rows p, q of a
+          const double apk = a[(size_t)p * n + k], aqk = a[(size_t)q * n + k];
+          a[(size_t)p * n + k] = c * apk - sn * aqk;
+          a[(size_t)q * n + k] = sn * apk + c * aqk;
+        }
+        for (int k = 0; k < n; ++k) {
+          const double vkp = v[(size_t)k * n + p], vkq = v[(size_t)k * n + q];
+          v[(size_t)k * n + p] = c * vkp - sn * vkq;
+          v[(size_t)k * n + q] = sn * vkp + c * vkq;
+        }
+      }
+  }
+  std::vector<int> order(n);
+  for (int i = 0; i < n; ++i) order[i] = i;
+  std::sort(order.begin(), order.end(), [&](int x, int y) { return a[(size_t)x * n + x] > a[(size_t)y * n + y]; });
+  val->resize(n);
+  std::vector<double> sorted((size_t)n * n);
+  for (int c = 0; c < n; ++c) {
+    (*val)[c] = a[(size_t)order[c] * n + order[c]];
+    for (int k = 0; k < n; ++k) sorted[(size_t)k * n + c] = v[(size_t)k * n + order[c]];
+  }
+  v.swap(sorted);
+}
+
+// Depth-first enumeration of the node sets of one size, in lexicographic order, with the
+// orthonormal basis of span(H_A) grown one column at a time: the syndrome energy left
+// outside span(H_A) is trace(G) - sum_k q_k^T G q_k.
+struct SupportSearch {
+  int r = 0, ns = 0, size = 0;
+  const double* H = nullptr;       // r x ns
+  const double* G = nullptr;       // r x r
+  std::vector<int> free_nodes;
+  double threshold = 0;
+  std::vector<double> Q;           // size x r
+  std::vector<int> cur, best;
+  double best_res = 0;
+  bool found = false;
+
+  // appends column `node` at depth k; returns the energy it explains
+  double push(int k, int node) {
+    double* q = &Q[(size_t)k * r];
+    double n0 = 0.0;
+    for (int i = 0; i < r; ++i) { q[i] = H[(size_t)i * ns + node]; n0 += q[i] * q[i]; }
+    for (int pass = 0; pass < 2; ++pass)
+      for (int l = 0; l < k; ++l) {
+        const double* ql = &Q[(size_t)l * r];
+        double dot = 0.0;
+        for (int i = 0; i < r; ++i) dot += ql[i] * q[i];
+        for (int i = 0; i < r; ++i) q[i] -= dot * ql[i];
+      }
+    double n1 = 0.0;
+    for (int i = 0; i < r; ++i) n1 += q[i] * q[i];
+    if (!(n1 > 1e-24 * n0)) {                  // numerically inside the span already
+      for (int i = 0; i < r; ++i) q[i] = 0.0;
+      return 0.0;
+    }
+    const double inv = 1.0 / std::sqrt(n1);
+    for (int i = 0; i < r; ++i) q[i] *= inv;
+    double gain = 0.0;
+    for (int i = 0; i < r; ++i) {
+      double gi = 0.0;
+      for (int j = 0; j < r; ++j) gi += G[(size_t)i * r + j] * q[j];
+      gain += q[i] * gi;
+    }
+    return gain;
+  }
+
+  void go(int depth, int first_free, double res) {
+    if (depth == size) {
+      if (res <= threshold && (!found || res < best_res)) { found = true; best_res = res; best = cur; }
+      return;
+    }
+    const int need = size - depth;
+    for (int f = first_free; f + need <= (int)free_nodes.size(); ++f) {
+      cur[depth] = free_nodes[f];
+      const double gain = push(depth, free_nodes[f]);
+      go(depth + 1, f + 1, res - gain);
+    }
+  }
+};
+
+double binomial(int n, int k) {
+  double b = 1.0;
+  for (int i = 1; i <= k; ++i) b = b * (n - k + i) / i;
+  return b;
+}
+
+}  // namespace
+
+gpd_status_t locate_nodes_host(const std::vector<double>& H, int r, int ns, const std::vector<double>& G,
+                               double energy, int64_t n_codewords, double rho, double abs_floor,
+                               const std::vector<int>& forced, NodeSearchResult* out) {
+  NodeSearchResult& o = *out;
+  o = NodeSearchResult();
+  o.energy = energy;
+  o.threshold = rho * rho * std::max(energy, (double)n_codewords * abs_floor * abs_floor);
+  double trace = 0.0;
+  for (int i = 0; i < r; ++i) trace += G[(size_t)i * r + i];
+  o.syndrome_energy = trace;
+  o.residual = trace;
+  if (r == 0) {
+    o.status = forced.empty() ? 0 : 2;
+    o.bad = forced;
+    return GPD_OK;
+  }
+  if (forced.empty() && trace <= o.threshold) return GPD_OK;          // step 1: no errors
+
+  std::vector<double> lam, vec;
+  jacobi_eigen(G, r, &lam, &vec);
+  std::vector<char> is_forced(ns, 0);
+  for (int f : forced) is_forced[f] = 1;
+  SupportSearch ss;
+  ss.r = r; ss.ns = ns; ss.H = H.data(); ss.G = G.data(); ss.threshold = o.threshold;
+  for (int q = 0; q < ns; ++q)
+    if (!is_forced[q]) ss.free_nodes.push_back(q);
+  const int nf = (int)forced.size();
+  for (int size = std::max(nf, 1); size <= r - 1; ++size) {
+    // no set of `size` nodes can leave less than the sum of the r - size smallest
+    // eigenvalues of G outside its span: skip sizes that cannot reach the threshold
+    double tail = 0.0;
+    for (int i = size; i < r; ++i) tail += std::max(lam[i], 0.0);
+    if (tail > o.threshold * (1.0 + 1e-6) + 1e-12 * trace) continue;
+    ss.size = size;
+    ss.Q.assign((size_t)size * r, 0.0);
+    ss.cur.assign(size, 0);
+    ss.found = false;
+    double res = trace;
+    for (int k = 0; k < nf; ++k) { ss.cur[k] = forced[k]; res -= ss.push(k, forced[k]); }
+    if (binomial((int)ss.free_nodes.size(), size - nf) <= kNodeSearchBudget) {
+      ss.go(nf, 0, res);
+    } else {
+      // too many sets of this size to try them all: test the one set made of the nodes whose
+      // columns of H lie closest to the span of the `size` dominant eigenvectors of G
+      o.exhaustive = false;
+      std::vector<std::pair<double, int>> dist;
+      for (int q : ss.free_nodes) {
+        double n0 = 0.0, inside = 0.0;
+        for (int i = 0; i < r; ++i) n0 += H[(size_t)i * ns + q] * H[(size_t)i * ns + q];
+        for (int c = 0; c < size; ++c) {
+          double dot = 0.0;
+          for (int i = 0; i < r; ++i) dot += vec[(size_t)i * r + c] * H[(size_t)i * ns + q];
+          inside += dot * dot;
+        }
+        dist.push_back({1.0 - inside / n0, q});
+      }
+      std::sort(dist.begin(), dist.end());
+      std::vector<int> pick;
+      for (int k = 0; k < size - nf; ++k) pick.push_back(dist[k].second);
+      std::sort(pick.begin(), pick.end());
+      for (int k = 0; k < size - nf; ++k) { ss.cur[nf + k] = pick[k]; res -= ss.push(nf + k, pick[k]); }
+      if (res <= o.threshold) { ss.found = true; ss.best_res = res; ss.best = ss.cur; }
+    }
+    if (ss.found) {
+      o.status = 1;
+      o.residual = std::max(ss.best_res, 0.0);
+      o.bad = ss.best;
+      std::sort(o.bad.begin(), o.bad.end());
+      return GPD_OK;
+    }
+  }
+  o.status = 2;                                                      // decoding failure
+  o.bad = forced;
+  return GPD_OK;
+}
+
+gpd_status_t parity_check_host(const std::vector<double>& pts, const std::vector<int>& S, int K,
+                               std::vector<double>* H) {
+  std::vector<double> D;
+  return decode_matrices(pts, S, K, std::vector<int>(), false, &D, H);
+}
+
+void fill_node_report(const NodeSearchResult& res, const std::vector<int>& S, gpd_node_report_t* rep) {
+  rep->n_bad = (int32_t)res.bad.size();
+  for (int q : res.bad) rep->bad[S[q]] = 1;
+  rep->exhaustive = res.exhaustive ? 1 : 0;
+  rep->energy = res.energy;
+  rep->syndrome_energy = res.syndrome_energy;
+  rep->residual = res.residual;
+  rep->threshold = res.threshold;
+  rep->status = res.status == 2 ? GPD_E_DECODE_FAIL : GPD_OK;
+}
+
 // ---------------------------------------------------------------- table packing
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -285,6 +494,55 @@ extern "C" gpd_status_t gpd_host_decode_matrices(int32_t m, int32_t n, int32_t d
   if (st != GPD_OK) return st;
   if (D) std::copy(Dv.begin(), Dv.end(), D);
   if (H) std::copy(Hv.begin(), Hv.end(), H);
+  return GPD_OK;
+}
+
+extern "C" gpd_status_t gpd_host_parity_check(int32_t P, int32_t K, const double* points,
+                                              const uint8_t* present, double* H, int32_t* n_present) {
+  if (P < 1 || P > GPD_MAX_P || K < 1) return gpd::fail(GPD_E_INVALID, "gpd_host_parity_check: bad P or K");
+  std::vector<double> pts;
+  gpd_status_t st = gpd::make_points(P, points, &pts);
+  if (st != GPD_OK) return st;
+  std::vector<int> S;
+  for (int p = 0; p < P; ++p)
+    if (!present || present[p]) S.push_back(p);
+  if (n_present) *n_present = (int32_t)S.size();
+  std::vector<double> Hv;
+  st = gpd::parity_check_host(pts, S, K, &Hv);
+  if (st != GPD_OK) return st;
+  if (H) std::copy(Hv.begin(), Hv.end(), H);
+  return GPD_OK;
+}
+
+extern "C" gpd_status_t gpd_host_locate_nodes(int32_t P, int32_t K, const double* points,
+                                              const uint8_t* present, const double* gram,
+                                              double energy, int64_t n_codewords, double rho,
+                                              double abs_floor, const uint8_t* forced,
+                                              gpd_node_report_t* report) {
+  if (P < 1 || P > GPD_MAX_P || K < 1 || !report || n_codewords < 0)
+    return gpd::fail(GPD_E_INVALID, "gpd_host_locate_nodes: bad argument");
+  std::vector<double> pts;
+  gpd_status_t st = gpd::make_points(P, points, &pts);
+  if (st != GPD_OK) return st;
+  std::vector<int> S;
+  for (int p = 0; p < P; ++p)
+    if (!present || present[p]) S.push_back(p);
+  std::memset(report, 0, sizeof(*report));
+  report->n_present = (int32_t)S.size();
+  std::vector<double> H;
+  st = gpd::parity_check_host(pts, S, K, &H);
+  if (st != GPD_OK) { report->status = st; return st; }
+  const int ns = (int)S.size(), r = ns - K;
+  if (r > 0 && !gram) return gpd::fail(GPD_E_INVALID, "gpd_host_locate_nodes: null Gram matrix");
+  std::vector<double> G(gram, gram + (size_t)r * r);
+  std::vector<int> f;
+  for (int q = 0; q < ns; ++q)
+    if (forced && forced[S[q]]) { f.push_back(q); report->wild[S[q]] = 1; }
+  gpd::NodeSearchResult res;
+  st = gpd::locate_nodes_host(H, r, ns, G, energy, n_codewords, rho, abs_floor, f, &res);
+  if (st != GPD_OK) { report->status = st; return st; }
+  gpd::fill_node_report(res, S, report);
+  if (res.status == 2) return gpd::fail(GPD_E_DECODE_FAIL, "more erroneous nodes than can be located");
   return GPD_OK;
 }
 

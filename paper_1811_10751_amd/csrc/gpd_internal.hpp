@@ -52,6 +52,29 @@ gpd_status_t decode_matrices(const std::vector<double>& pts, const std::vector<i
                              const std::vector<int>& useful, bool first_k,
                              std::vector<double>* D, std::vector<double>* H);
 
+// Orthonormal parity check H [(S.size()-K)][S.size()] of the (|S|, K) code alone.
+gpd_status_t parity_check_host(const std::vector<double>& pts, const std::vector<int>& S, int K,
+                               std::vector<double>* H);
+
+// Algorithm 1 (Sec. V) for errors that sit on the same nodes in every codeword of a stack,
+// run on the aggregate G = sum_c (H z_c)(H z_c)^T (r x r, in the basis of H):
+//   step 1: trace(G) <= tau^2 = rho^2 max(energy, n_codewords abs_floor^2) -> no errors;
+//   step 2: the smallest node set A (containing `forced`) with trace((I - Pi_A) G) <= tau^2,
+//           Pi_A the projector on span(H_A); the smallest residual wins inside one size;
+//   step 3: only sets of at most r - 1 nodes are accepted.
+// Sets of one size are tried exhaustively while there are at most kNodeSearchBudget of them.
+constexpr double kNodeSearchBudget = 4194304.0;
+struct NodeSearchResult {
+  int status = 0;                      // 0 clean, 1 located, 2 failure
+  std::vector<int> bad;                // positions in S, ascending
+  bool exhaustive = true;
+  double energy = 0, syndrome_energy = 0, residual = 0, threshold = 0;
+};
+gpd_status_t locate_nodes_host(const std::vector<double>& H, int r, int ns, const std::vector<double>& G,
+                               double energy, int64_t n_codewords, double rho, double abs_floor,
+                               const std::vector<int>& forced, NodeSearchResult* out);
+void fill_node_report(const NodeSearchResult& res, const std::vector<int>& S, gpd_node_report_t* rep);
+
 // ---------------------------------------------------------------- device tables
 
 // One "combine" operation: out_q = sum_s coef[q][s] * in_s over equally shaped blocks.
@@ -192,5 +215,22 @@ gpd_status_t run_decode(hipStream_t stream, TableRing* ring, const DecodeJob& jo
                         const uint8_t* present, int mode, int correct, float* out, int64_t ld_out,
                         void* workspace, size_t workspace_bytes, gpd_report_t* report);
 void decode_workspace_layout(int64_t n_codewords, int64_t* flag_cap, int64_t* loc_cap, size_t* bytes);
+
+// ---------------------------------------------------------------- node-level faults (gpd_nodes.hip)
+
+// device bytes run_locate_nodes needs for a stack of n_codewords-element blocks and r syndromes
+size_t gram_workspace_bytes(int64_t n_codewords, int r);
+
+// Gram pass over the stack Zt [P][n_codewords] + host search; waits for the stream.
+gpd_status_t run_locate_nodes(hipStream_t stream, TableRing* ring, const std::vector<double>& pts,
+                              int K, int64_t n_codewords, const float* Zt, const uint8_t* present,
+                              double rho, double abs_floor, void* workspace, size_t workspace_bytes,
+                              gpd_node_report_t* rep, double* gram_out = nullptr);
+
+// decode for correct == GPD_CORRECT_NODES: run_locate_nodes, then run_decode without the nodes
+// found erroneous; fills the gpd_report_t as documented for gpd_decode.
+gpd_status_t run_decode_nodes(hipStream_t stream, TableRing* ring, const DecodeJob& job, const float* Zt,
+                              const uint8_t* present, int mode, float* out, int64_t ld_out,
+                              void* workspace, size_t workspace_bytes, gpd_report_t* report);
 
 }  // namespace gpd

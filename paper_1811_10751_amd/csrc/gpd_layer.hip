@@ -312,6 +312,10 @@ extern "C" gpd_status_t gpd_layer_create(const gpd_layer_desc_t* d, gpd_layer_t*
   L->off_part = take((size_t)P * L->nchunks * L->wc * L->nb2 * 4);
   const int64_t ncw = std::max(L->wr * L->nb1, L->wc * L->nb2);
   decode_workspace_layout(ncw, &L->flag_cap, &L->loc_cap, &L->dec_bytes);
+  // the node search needs room for its partial Gram matrices (forward, backward and weight stacks)
+  L->dec_bytes = std::max(L->dec_bytes, gram_workspace_bytes(L->wr * L->nb1, (int)P - c.K));
+  L->dec_bytes = std::max(L->dec_bytes, gram_workspace_bytes(L->wc * L->nb2, (int)P - L->Kb));
+  L->dec_bytes = std::max(L->dec_bytes, gram_workspace_bytes(L->wr * L->wc, (int)P - m * n));
   L->off_dec = take(L->dec_bytes);
   L->ws_bytes = off;
 
@@ -325,6 +329,7 @@ extern "C" gpd_status_t gpd_layer_create(const gpd_layer_desc_t* d, gpd_layer_t*
   };
   grow(m * n, (int)P, 0); grow(n * d->d1, (int)P, 0); grow(m * d2, (int)P, 0);
   grow((int)P, m * d->d1, (int)P); grow((int)P, n * d2, (int)P); grow((int)P, m * n, 0);
+  grow((int)P, (int)P, 0);                    // projection onto the code
   st = L->ring.init(slot);
   if (st != GPD_OK) { L->ring.destroy(); delete L; return st; }
   *out = L;
@@ -396,6 +401,116 @@ extern "C" gpd_status_t gpd_layer_decode_weights(const gpd_layer_t* Lc, const fl
   job.flag_cap = 0; job.loc_cap = 0; job.workspace_bytes = 0;
   grid_limits(L->desc.N_out, L->desc.N_in, c.m, c.n, L->wr, L->wc, &job.out_rows, &job.out_cols);
   return run_decode(L->stream, &L->ring, job, Wt, present, GPD_DEC_LSQ_ALL, 0, W, ldw, nullptr, 0, nullptr);
+}
+
+// ---------------------------------------------------------------- node-level faults
+
+extern "C" gpd_status_t gpd_layer_locate_nodes(const gpd_layer_t* Lc, int32_t which, const float* stack,
+                                               const uint8_t* present, void* workspace,
+                                               size_t workspace_bytes, gpd_node_report_t* report,
+                                               double* gram) {
+  gpd_layer_t* L = const_cast<gpd_layer_t*>(Lc);
+  if (!L || !stack || !report) return fail(GPD_E_INVALID, "gpd_layer_locate_nodes: null argument");
+  if (!workspace || workspace_bytes < L->ws_bytes || ((uintptr_t)workspace & 255))
+    return fail(GPD_E_WORKSPACE, "layer: workspace of %zu aligned bytes needed", L->ws_bytes);
+  const Code& c = L->fwd;
+  int K = 0;
+  int64_t ncw = 0;
+  double rho = L->rho;
+  switch (which) {
+    case GPD_STACK_WEIGHTS:
+      K = c.m * c.n; ncw = L->wr * L->wc;
+      rho = L->desc.rho_detect > 0 ? L->desc.rho_detect : 1.0 / 4096.0;    // stored in fp32
+      break;
+    case GPD_STACK_FORWARD: K = c.K; ncw = L->wr * L->nb1; break;
+    case GPD_STACK_BACKWARD: K = L->Kb; ncw = L->wc * L->nb2; break;
+    default: return fail(GPD_E_INVALID, "gpd_layer_locate_nodes: unknown stack %d", which);
+  }
+  return run_locate_nodes(L->stream, &L->ring, c.pts, K, ncw, stack, present, rho, L->abs_floor,
+                          (char*)workspace + L->off_dec, L->dec_bytes, report, gram);
+}
+
+namespace {
+
+// Table that re-evaluates the polynomial W~(b) (mn coefficients), interpolated through the
+// nodes in `from` (all of them by least squares, or the first mn), at the nodes in `to`.
+gpd_status_t reevaluate_table(const gpd_layer_t* L, const std::vector<int>& from, const std::vector<int>& to,
+                              bool first_k, HostCombineTable* ht) {
+  const Code& c = L->fwd;
+  const int Kw = c.m * c.n;
+  std::vector<int> all_e(Kw);
+  for (int e = 0; e < Kw; ++e) all_e[e] = e;
+  std::vector<double> D;                       // [Kw][from.size()]: coefficients from node values
+  gpd_status_t st = decode_matrices(c.pts, from, Kw, all_e, first_k, &D, nullptr);
+  if (st != GPD_OK) return st;
+  const int nf = (int)from.size();
+  std::vector<int> used;
+  for (int q = 0; q < nf; ++q) {
+    bool nz = false;
+    for (int e = 0; e < Kw && !nz; ++e) nz = D[(size_t)e * nf + q] != 0.0;
+    if (nz) used.push_back(q);
+  }
+  ht->nin = (int)used.size(); ht->nout = (int)to.size(); ht->r = 0;
+  ht->in_off.resize(ht->nin); ht->node.resize(ht->nin); ht->out_off.resize(ht->nout);
+  ht->coef.assign((size_t)ht->nout * ht->nin, 0.0);
+  const int64_t blk = L->wr * L->wc;
+  for (int u = 0; u < ht->nin; ++u) { ht->in_off[u] = from[used[u]] * blk; ht->node[u] = from[used[u]]; }
+  for (int o = 0; o < ht->nout; ++o) {
+    ht->out_off[o] = to[o] * blk;
+    for (int u = 0; u < ht->nin; ++u) {
+      double acc = 0.0;                        // sum_e b_to^e D[e][q]
+      for (int e = 0; e < Kw; ++e) acc += ipow(c.pts[to[o]], e) * D[(size_t)e * nf + used[u]];
+      ht->coef[(size_t)o * ht->nin + u] = acc;
+    }
+  }
+  return GPD_OK;
+}
+
+}  // namespace
+
+extern "C" gpd_status_t gpd_layer_regenerate(const gpd_layer_t* Lc, float* Wt, const uint8_t* bad,
+                                             int32_t mode) {
+  gpd_layer_t* L = const_cast<gpd_layer_t*>(Lc);
+  if (!L || !Wt || !bad) return fail(GPD_E_INVALID, "gpd_layer_regenerate: null argument");
+  if (mode != GPD_DEC_FIRST_K && mode != GPD_DEC_LSQ_ALL)
+    return fail(GPD_E_INVALID, "gpd_layer_regenerate: bad mode");
+  const int P = L->desc.P, Kw = L->fwd.m * L->fwd.n;
+  std::vector<int> good, todo;
+  for (int p = 0; p < P; ++p) (bad[p] ? todo : good).push_back(p);
+  if ((int)good.size() < Kw) return fail(GPD_E_TOO_FEW, "%d good nodes, %d needed", (int)good.size(), Kw);
+  if (todo.empty()) return GPD_OK;
+  std::string key("regen");
+  key_add(&key, mode);
+  key_add_bytes(&key, bad, P);
+  CombineTable t;
+  gpd_status_t st = L->ring.cached(key, [&](HostCombineTable* ht) {
+    return reevaluate_table(L, good, todo, mode == GPD_DEC_FIRST_K, ht);
+  }, L->stream, &t);
+  if (st != GPD_OK) return st;
+  ScreenArgs none;
+  return launch_combine(L->stream, t, Wt, L->wc, Wt, L->wc, false, L->wr, L->wc, none);
+}
+
+extern "C" gpd_status_t gpd_layer_project(const gpd_layer_t* Lc, float* Wt, const uint8_t* present) {
+  gpd_layer_t* L = const_cast<gpd_layer_t*>(Lc);
+  if (!L || !Wt) return fail(GPD_E_INVALID, "gpd_layer_project: null argument");
+  const int P = L->desc.P, Kw = L->fwd.m * L->fwd.n;
+  std::vector<int> from, all;
+  for (int p = 0; p < P; ++p) {
+    all.push_back(p);
+    if (!present || present[p]) from.push_back(p);
+  }
+  if ((int)from.size() < Kw) return fail(GPD_E_TOO_FEW, "%d nodes present, %d needed", (int)from.size(), Kw);
+  std::string key("proj");
+  for (int p = 0; p < P; ++p) key.push_back((!present || present[p]) ? 1 : 0);
+  CombineTable t;
+  gpd_status_t st = L->ring.cached(key, [&](HostCombineTable* ht) {
+    return reevaluate_table(L, from, all, false, ht);
+  }, L->stream, &t);
+  if (st != GPD_OK) return st;
+  // in place: a thread reads every input block's value of its element before it writes any output
+  ScreenArgs none;
+  return launch_combine(L->stream, t, Wt, L->wc, Wt, L->wc, false, L->wr, L->wc, none);
 }
 
 // ---------------------------------------------------------------- products

@@ -1,0 +1,310 @@
+// Node-level error location: the aggregate of Algorithm 1 (Sec. V) over all element codewords
+// of a stack, for the error models of Sec. III where a faulty node's whole output is wrong.
+//
+// gram_kernel makes one pass over the stack and accumulates
+//     G = sum_c (H z_c)(H z_c)^T      and      sum_c ||z_c||^2
+// The syndromes H z_c are a dense contraction over the nodes (fp32 MFMA 16x16x4: 16 codewords
+// x 16 syndromes per instruction, 4 nodes per step), the Gram matrix a contraction over the
+// codewords (fp64 MFMA 16x16x4 fed with the syndrome accumulators as they come out of the
+// first product: the sum over codewords does not care in which order they are taken).  The
+// Gram matrix has to be exact to fp64 rounding: the search subtracts the energy explained by
+// a node set from the total, and the total can exceed the threshold by many orders of
+// magnitude.  The search itself runs on the host (gpd_host.cpp).
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+
+#include "gpd_internal.hpp"
+
+namespace gpd {
+namespace {
+
+typedef double v4d __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+constexpr float kWild = 1099511627776.0f;      // 2^40
+
+struct GramParams {
+  const float* in;
+  const int64_t* in_off;     // [ns] element offset of each present node's block
+  const float* H;            // [r][ns] fp32
+  int ns, r;
+  int64_t ncw;               // codewords = elements per block
+  double* part;              // [gridDim.x][NT][256]
+  double* part_energy;       // [gridDim.x]
+  int32_t* wild;             // [ns], zeroed before the launch
+};
+
+// NK: steps of 4 nodes (ns <= 4 NK); RT: tiles of 16 syndromes (r <= 16 RT); VEC: codewords
+// per lane and load.  A wavefront handles 16 VEC consecutive codewords per iteration: lane l
+// loads VEC codewords starting at 16 VEC it + VEC (l % 16) from node 4 kk + l / 16.
+template <int NK, int RT, int VEC>
+__global__ __launch_bounds__(256) void gram_kernel(GramParams p) {
+  constexpr int NT = RT * (RT + 1) / 2;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lj = lane & 15, lk = lane >> 4;
+
+  // B operand of the syndrome product: B[k = node][j = syndrome] = H[j][node]
+  float hreg[NK][RT];
+  int64_t off[NK];
+#pragma unroll
+  for (int kk = 0; kk < NK; ++kk) {
+    const int node = 4 * kk + lk;
+    off[kk] = node < p.ns ? p.in_off[node] : -1;
+#pragma unroll
+    for (int t = 0; t < RT; ++t) {
+      const int j = 16 * t + lj;
+      hreg[kk][t] = (node < p.ns && j < p.r) ? p.H[(int64_t)j * p.ns + node] : 0.f;
+    }
+  }
+
+  v4d G[NT];
+#pragma unroll
+  for (int i = 0; i < NT; ++i) G[i] = v4d{0.0, 0.0, 0.0, 0.0};
+  double energy = 0.0;
+  uint32_t wildmask = 0;
+
+  const int64_t chunk = 16 * VEC;
+  const int64_t n_iter = (p.ncw + chunk - 1) / chunk;
+  const int64_t n_waves = (int64_t)gridDim.x * 4;
+  for (int64_t it = (int64_t)blockIdx.x * 4 + wave; it < n_iter; it += n_waves) {
+    const int64_t c0 = it * chunk + VEC * lj;
+    float z[NK][VEC];
+#pragma unroll
+    for (int kk = 0; kk < NK; ++kk) {
+      if (off[kk] >= 0 && c0 < p.ncw) {            // VEC = 4 only when 4 divides ncw
+        if constexpr (VEC == 4) {
+          const float4 v = *reinterpret_cast<const float4*>(p.in + off[kk] + c0);
+          z[kk][0] = v.x; z[kk][1] = v.y; z[kk][2] = v.z; z[kk][3] = v.w;
+        } else {
+          z[kk][0] = p.in[off[kk] + c0];
+        }
+      } else {
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) z[kk][c] = 0.f;
+      }
+    }
+    // non-finite and huge values: remember the node, take the value as zero
+#pragma unroll
+    for (int kk = 0; kk < NK; ++kk) {
+#pragma unroll
+      for (int c = 0; c < VEC; ++c) {
+        if (!(fabsf(z[kk][c]) < kWild)) { wildmask |= 1u << kk; z[kk][c] = 0.f; }
+        const double x = (double)z[kk][c];
+        energy = fma(x, x, energy);
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) {
+      // S^T tile t: rows = 16 codewords, columns = syndromes 16 t .. 16 t + 15
+      v4f S[RT];
+#pragma unroll
+      for (int t = 0; t < RT; ++t) S[t] = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < NK; ++kk) {
+#pragma unroll
+        for (int t = 0; t < RT; ++t)
+          S[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(z[kk][c], hreg[kk][t], S[t], 0, 0, 0);
+      }
+      // register v of lane l holds syndrome 16 t + l % 16 of codeword 4 (l / 16) + v: as the
+      // A (and B) operand of the next product that is a 16 x 4 matrix [syndrome][codeword]
+      int ti = 0;
+#pragma unroll
+      for (int t = 0; t < RT; ++t) {
+#pragma unroll
+        for (int t2 = t; t2 < RT; ++t2) {
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            G[ti] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)S[t][v], (double)S[t2][v], G[ti], 0, 0, 0);
+          ++ti;
+        }
+      }
+    }
+  }
+
+  // nodes that held a wild value
+#pragma unroll
+  for (int kk = 0; kk < NK; ++kk) {
+    const int node = 4 * kk + lk;
+    if (((wildmask >> kk) & 1u) && node < p.ns) atomicOr(&p.wild[node], 1);
+  }
+
+  // sum the four wavefronts of the workgroup (fixed order), one partial per workgroup
+  __shared__ double red[3][256];
+  __shared__ double red_e[4];
+#pragma unroll
+  for (int off2 = 32; off2 > 0; off2 >>= 1) energy += __shfl_xor(energy, off2);
+  if (lane == 0) red_e[wave] = energy;
+#pragma unroll
+  for (int ti = 0; ti < NT; ++ti) {
+    if (wave > 0) {
+#pragma unroll
+      for (int v = 0; v < 4; ++v) red[wave - 1][v * 64 + lane] = G[ti][v];
+    }
+    __syncthreads();
+    if (wave == 0) {
+      double* dst = p.part + ((int64_t)blockIdx.x * NT + ti) * 256;
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        dst[v * 64 + lane] = ((G[ti][v] + red[0][v * 64 + lane]) + red[1][v * 64 + lane]) + red[2][v * 64 + lane];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) p.part_energy[blockIdx.x] = ((red_e[0] + red_e[1]) + red_e[2]) + red_e[3];
+}
+
+// out[ti][i] = sum over workgroups of part[wg][ti][i]; block NT sums the energies.
+__global__ __launch_bounds__(256) void gram_reduce_kernel(const double* __restrict__ part,
+                                                          const double* __restrict__ part_energy,
+                                                          int n_wg, int NT, double* __restrict__ out,
+                                                          double* __restrict__ out_energy) {
+  const int ti = blockIdx.x;
+  if (ti < NT) {
+    double acc = 0.0;
+    for (int w = 0; w < n_wg; ++w) acc += part[((int64_t)w * NT + ti) * 256 + threadIdx.x];
+    out[ti * 256 + threadIdx.x] = acc;
+  } else {
+    __shared__ double sh[256];
+    double acc = 0.0;
+    for (int w = threadIdx.x; w < n_wg; w += 256) acc += part_energy[w];
+    sh[threadIdx.x] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      double tot = 0.0;
+      for (int i = 0; i < 256; ++i) tot += sh[i];
+      *out_energy = tot;
+    }
+  }
+}
+
+int tiles_of(int r) { return r <= 16 ? 1 : (r <= 32 ? 2 : 4); }
+
+int gram_grid(int64_t ncw, int RT, int vec) {
+  const int64_t n_iter = (ncw + 16 * vec - 1) / (16 * vec);
+  const int64_t max_wg = RT == 1 ? 1024 : (RT == 2 ? 512 : 256);
+  return (int)std::max<int64_t>(1, std::min<int64_t>(max_wg, (n_iter + 3) / 4));
+}
+
+constexpr size_t kGramHeader = 512;      // wild[64] int32 at 0, energy (double) at 256
+
+template <int NK, int RT>
+gpd_status_t launch_gram_v(hipStream_t s, const GramParams& p, int vec, int n_wg) {
+  if (vec == 4) hipLaunchKernelGGL((gram_kernel<NK, RT, 4>), dim3(n_wg), dim3(256), 0, s, p);
+  else hipLaunchKernelGGL((gram_kernel<NK, RT, 1>), dim3(n_wg), dim3(256), 0, s, p);
+  GPD_HIP(hipGetLastError());
+  return GPD_OK;
+}
+
+gpd_status_t launch_gram(hipStream_t s, const GramParams& p, int RT, int vec, int n_wg) {
+  const int NK = p.ns <= 16 ? 4 : (p.ns <= 32 ? 8 : 16);
+  if (NK == 4) return launch_gram_v<4, 1>(s, p, vec, n_wg);             // r < ns <= 16
+  if (NK == 8) return RT == 1 ? launch_gram_v<8, 1>(s, p, vec, n_wg) : launch_gram_v<8, 2>(s, p, vec, n_wg);
+  if (RT == 1) return launch_gram_v<16, 1>(s, p, vec, n_wg);
+  if (RT == 2) return launch_gram_v<16, 2>(s, p, vec, n_wg);
+  return launch_gram_v<16, 4>(s, p, vec, n_wg);
+}
+
+}  // namespace
+
+size_t gram_workspace_bytes(int64_t ncw, int r) {
+  const int RT = tiles_of(r), NT = RT * (RT + 1) / 2;
+  const int n_wg = gram_grid(ncw, RT, 1);            // the scalar path has the most workgroups
+  size_t b = kGramHeader + (size_t)NT * 2048;
+  b += ((size_t)n_wg * 8 + 255) / 256 * 256;
+  b += (size_t)n_wg * NT * 2048;
+  return (b + 255) / 256 * 256;
+}
+
+gpd_status_t run_locate_nodes(hipStream_t stream, TableRing* ring, const std::vector<double>& pts,
+                              int K, int64_t ncw, const float* Zt, const uint8_t* present, double rho,
+                              double abs_floor, void* workspace, size_t workspace_bytes,
+                              gpd_node_report_t* rep, double* gram_out) {
+  if (!rep) return fail(GPD_E_INVALID, "locate nodes: null report");
+  std::memset(rep, 0, sizeof(*rep));
+  const int P = (int)pts.size();
+  std::vector<int> S;
+  for (int p = 0; p < P; ++p)
+    if (!present || present[p]) S.push_back(p);
+  const int ns = (int)S.size(), r = ns - K;
+  rep->n_present = ns;
+  if (ns < K) {
+    rep->status = GPD_E_TOO_FEW;
+    return fail(GPD_E_TOO_FEW, "%d responses present, %d needed", ns, K);
+  }
+  if (ncw == 0) return GPD_OK;
+  if (!Zt) return fail(GPD_E_INVALID, "locate nodes: null stack");
+  if (ncw > 0x7fffffffLL) return fail(GPD_E_SHAPE, "block has more than 2^31 elements");
+  const size_t need = gram_workspace_bytes(ncw, r);
+  if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))
+    return fail(GPD_E_WORKSPACE, "locate nodes: workspace of %zu aligned bytes needed", need);
+
+  std::vector<double> H;
+  gpd_status_t st = parity_check_host(pts, S, K, &H);
+  if (st != GPD_OK) { rep->status = st; return st; }
+
+  std::string key("gram");
+  key_add(&key, K); key_add(&key, ncw);
+  for (int p = 0; p < P; ++p) key.push_back((!present || present[p]) ? 1 : 0);
+  CombineTable t;
+  st = ring->cached(key, [&](HostCombineTable* ht) {
+    ht->nin = ns; ht->nout = 0; ht->r = r;
+    ht->in_off.resize(ns); ht->node.resize(ns);
+    for (int q = 0; q < ns; ++q) { ht->in_off[q] = (int64_t)S[q] * ncw; ht->node[q] = S[q]; }
+    ht->H = H;
+    return GPD_OK;
+  }, stream, &t);
+  if (st != GPD_OK) { rep->status = st; return st; }
+
+  const int RT = tiles_of(r), NT = RT * (RT + 1) / 2;
+  const int vec = (ncw % 4 == 0 && ((uintptr_t)Zt % 16) == 0) ? 4 : 1;
+  const int n_wg = gram_grid(ncw, RT, vec);
+  char* ws = (char*)workspace;
+  GramParams gp;
+  gp.in = Zt; gp.in_off = t.in_off; gp.H = t.H; gp.ns = ns; gp.r = r; gp.ncw = ncw;
+  gp.wild = (int32_t*)ws;
+  double* d_energy = (double*)(ws + 256);
+  double* d_gram = (double*)(ws + kGramHeader);
+  gp.part_energy = (double*)(ws + kGramHeader + (size_t)NT * 2048);
+  gp.part = (double*)(ws + kGramHeader + (size_t)NT * 2048 + ((size_t)n_wg * 8 + 255) / 256 * 256);
+  st = launch_zero_words(stream, ws, (int)(kGramHeader / 4));
+  if (st != GPD_OK) return st;
+  st = launch_gram(stream, gp, RT, vec, n_wg);
+  if (st != GPD_OK) return st;
+  hipLaunchKernelGGL(gram_reduce_kernel, dim3(NT + 1), dim3(256), 0, stream, gp.part, gp.part_energy,
+                     n_wg, NT, d_gram, d_energy);
+  GPD_HIP(hipGetLastError());
+
+  // one copy brings wild flags, energy and the Gram tiles back
+  std::vector<char> host(kGramHeader + (size_t)NT * 2048);
+  GPD_HIP(hipMemcpyAsync(host.data(), ws, host.size(), hipMemcpyDeviceToHost, stream));
+  GPD_HIP(hipStreamSynchronize(stream));
+  const int32_t* h_wild = (const int32_t*)host.data();
+  double energy;
+  std::memcpy(&energy, host.data() + 256, 8);
+  const double* tiles = (const double*)(host.data() + kGramHeader);
+  // tile (t, t2), register v of lane l: row 16 t + 4 v + l / 16, column 16 t2 + l % 16
+  std::vector<double> G((size_t)r * r, 0.0);
+  int ti = 0;
+  for (int a = 0; a < RT; ++a)
+    for (int b = a; b < RT; ++b, ++ti)
+      for (int v = 0; v < 4; ++v)
+        for (int l = 0; l < 64; ++l) {
+          const int i = 16 * a + 4 * v + l / 16, j = 16 * b + l % 16;
+          if (i >= r || j >= r) continue;
+          const double x = tiles[(size_t)ti * 256 + v * 64 + l];
+          G[(size_t)i * r + j] = x;
+          if (a != b) G[(size_t)j * r + i] = x;
+        }
+  if (gram_out) std::copy(G.begin(), G.end(), gram_out);
+  std::vector<int> forced;
+  for (int q = 0; q < ns; ++q)
+    if (h_wild[q]) { forced.push_back(q); rep->wild[S[q]] = 1; }
+  NodeSearchResult res;
+  st = locate_nodes_host(H, r, ns, G, energy, ncw, rho, abs_floor, forced, &res);
+  if (st != GPD_OK) { rep->status = st; return st; }
+  fill_node_report(res, S, rep);
+  if (res.status == 2) return fail(GPD_E_DECODE_FAIL, "more erroneous nodes than can be located");
+  return GPD_OK;
+}
+
+}  // namespace gpd

@@ -99,3 +99,96 @@ def test_product_path_does_not_import_the_oracle():
                 text = open(os.path.join(dirpath, f)).read()
                 for needle in ("gpd_oracle", "from oracle", "import oracle", "oracle/"):
                     assert needle not in text, (f, needle)
+
+
+# ----------------------------------------------------------------------------- node search (host half)
+
+
+def _gram_in_library_basis(Z, P, K, present=None):
+    """Gram matrix of the syndromes of the stack Z[P, ncw] in the basis the library uses."""
+    H = G.gpd_host_parity_check(P, K, present=present)
+    S = np.arange(P) if present is None else np.flatnonzero(present)
+    Y = H @ Z[S]
+    return Y @ Y.T, float((Z[S] ** 2).sum()), H
+
+
+def test_host_parity_check_spans_the_same_space_as_the_oracle():
+    P, K = 16, 9
+    pts = O.chebyshev_points(P)
+    present = np.ones(P, dtype=np.uint8)
+    present[[3, 12]] = 0
+    H = G.gpd_host_parity_check(P, K, present=present)
+    Ho = O.parity_check(pts[np.flatnonzero(present)], K)
+    assert H.shape == Ho.shape == (5, 14)
+    assert np.abs(H @ H.T - np.eye(5)).max() < 1e-12
+    assert np.abs(H.T @ H - Ho.T @ Ho).max() < 1e-10          # same projector
+
+
+@pytest.mark.parametrize("t", [0, 1, 2, 3, 4, 5, 6])
+def test_host_node_search_matches_oracle(t):
+    # (P, K) = (16, 9): up to 6 bad nodes can be located, 7 cannot
+    P, K, ncw = 16, 9, 40
+    pts = O.chebyshev_points(P)
+    rng = np.random.default_rng(100 + t)
+    Z = O.vandermonde(pts, K) @ rng.standard_normal((K, ncw))
+    Z = O.round_to_f32(Z)
+    bad = np.sort(rng.choice(P, t, replace=False))
+    Z[bad] += rng.standard_normal((t, ncw))
+    want = O.locate_nodes(Z.reshape(P, ncw, 1), pts, K)
+    gram, energy, _ = _gram_in_library_basis(Z, P, K)
+    rep = G.gpd_host_locate_nodes(P, K, gram, energy, ncw, 2.0 ** -12)
+    assert rep.bad == want.bad == tuple(int(b) for b in bad)
+    assert rep.status == G.GPD_OK and rep.exhaustive
+    assert np.isclose(rep.threshold, want.threshold, rtol=1e-12)
+    assert np.isclose(rep.syndrome_energy, want.syndrome_energy, rtol=1e-9)
+    if t:
+        assert rep.residual <= rep.threshold
+
+
+def test_host_node_search_failure_forced_and_erasures():
+    P, K, ncw = 16, 9, 24
+    pts = O.chebyshev_points(P)
+    rng = np.random.default_rng(7)
+    Z = O.vandermonde(pts, K) @ rng.standard_normal((K, ncw))
+    # seven bad nodes: failure in the exact regime
+    Zb = Z.copy()
+    bad7 = np.sort(rng.choice(P, 7, replace=False))
+    Zb[bad7] += rng.standard_normal((7, ncw))
+    gram, energy, _ = _gram_in_library_basis(Zb, P, K)
+    rep = G.gpd_host_locate_nodes(P, K, gram, energy, ncw, 1e-11)
+    want = O.locate_nodes(Zb.reshape(P, ncw, 1), pts, K, rho=1e-11)
+    assert rep.status == G.GPD_E_DECODE_FAIL and want.status == "failed"
+    # erasures + a forced node + a noisy node
+    present = np.ones(P, dtype=np.uint8)
+    present[[1, 8]] = 0
+    Zc = Z.copy()
+    Zc[5] += rng.standard_normal(ncw)
+    Zo = Zc.copy()
+    Zo[11, 3] = np.inf
+    want = O.locate_nodes(Zo.reshape(P, ncw, 1), pts, K, present)
+    Zc[11, 3] = 0.0                                           # the kernel takes a wild value as zero
+    gram, energy, _ = _gram_in_library_basis(Zc, P, K, present)
+    rep = G.gpd_host_locate_nodes(P, K, gram, energy, ncw, 2.0 ** -12, present=present, forced=[11])
+    assert rep.bad == want.bad == (5, 11) and rep.wild == (11,)
+    # correlated errors on two nodes (rank-one Gram matrix): the pair is found
+    Zd = Z.copy()
+    e = rng.standard_normal(ncw)
+    Zd[2] += e
+    Zd[13] -= 0.5 * e
+    gram, energy, _ = _gram_in_library_basis(Zd, P, K)
+    assert G.gpd_host_locate_nodes(P, K, gram, energy, ncw, 2.0 ** -12).bad == (2, 13)
+
+
+def test_host_node_search_beyond_the_exhaustive_budget():
+    # (P, K) = (48, 12): sets of 14 nodes out of 48 are far more than the budget; the set read
+    # off the dominant eigenvectors of the Gram matrix is tested instead, and is right
+    P, K, ncw, t = 48, 12, 64, 14
+    pts = O.chebyshev_points(P)
+    rng = np.random.default_rng(3)
+    Z = O.vandermonde(pts, K) @ rng.standard_normal((K, ncw))
+    bad = np.sort(rng.choice(P, t, replace=False))
+    Z[bad] += rng.standard_normal((t, ncw))
+    gram, energy, _ = _gram_in_library_basis(Z, P, K)
+    rep = G.gpd_host_locate_nodes(P, K, gram, energy, ncw, 2.0 ** -12)
+    assert rep.status == G.GPD_OK and not rep.exhaustive
+    assert rep.bad == tuple(int(b) for b in bad)
