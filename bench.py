@@ -125,13 +125,129 @@ def bench_mlp(args, cfg):
     print(json.dumps(out), flush=True)
 
 
+def bench_faults(args, cfg):
+    """Workload 4 (the 4096^3 product with soft errors) and the node-level fault paths at the
+    same shapes: times the decode with the per-codeword screen on bit-flipped responses, the
+    node search on whole-node errors, and regeneration / projection of one 4096 x 4096 coded
+    layer (m = 4, n = 2, P = 24).  Extra evidence, not the headline metric."""
+    import numpy as np
+    import torch
+
+    import gpd_workloads as WL
+    import paper_1811_10751_amd as G
+
+    dev = "cuda:0"
+    N1, N0, Nc, m, n, d, P = (cfg[k] for k in ("N1", "N0", "Nc", "m", "n", "d", "P"))
+    A_h, B_h = WL.matmul_inputs(N1, N0, Nc, cfg["seed"])
+    plan = G.gpd_plan(N1, N0, Nc, m, n, d, P)
+    K = plan.K
+    At, Bt = G.gpd_encode(plan, torch.from_numpy(A_h).to(dev), torch.from_numpy(B_h).to(dev))
+    Ct = G.gpd_worker_products(plan, At, Bt)
+    del At, Bt
+    rows, cols = N1 // m, Nc // d
+    blk = rows * cols
+    ws = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device=dev)
+    C = torch.empty((N1, Nc), dtype=torch.float32, device=dev)
+    words = Ct.view(torch.int32).view(P, -1)
+    n_steps = args.warmup + args.steps
+
+    def timed(fn, before=None, after=None):
+        """Mean GPU time of fn(t) in ms (events around the library call only; fault injection in
+        `before` / `after` is not timed)."""
+        total = 0.0
+        for t in range(n_steps):
+            if before:
+                before(t)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn(t)
+            e1.record()
+            e1.synchronize()
+            if t >= args.warmup:
+                total += e0.elapsed_time(e1)
+            if after:
+                after(t)
+        return total / args.steps
+
+    # (1) decode + per-codeword screen + Algorithm 1 on the flagged codewords, bit flips per trial
+    located = [0]
+    trials = [WL.bitflip_trial(cfg["trial_seed0"] + t, P, blk, P - K - 1, cfg["flip_prob"]) for t in range(n_steps)]
+
+    def flip(t):
+        for (p, e, b) in trials[t]:
+            words[p, e] ^= (1 << b) if b < 31 else -(1 << 31)
+
+    def elements(t):
+        _, rep = G.gpd_decode(plan, Ct, mode=G.GPD_DEC_LSQ_ALL, correct_errors=G.GPD_CORRECT_ELEMENTS,
+                              workspace=ws, C_out=C)
+        located[0] += rep.n_located
+
+    ms_elem = timed(elements, flip, flip)
+    ms_elem_async = timed(lambda t: G.gpd_decode(plan, Ct, mode=G.GPD_DEC_LSQ_ALL,
+                                                 correct_errors=G.GPD_CORRECT_ELEMENTS, workspace=ws, C_out=C,
+                                                 want_report=False), flip, flip)
+
+    # (2) whole-node errors: Gram pass + host search, then the decode without the bad nodes
+    noise = torch.randn((rows, cols), generator=torch.Generator(device=dev).manual_seed(1), device=dev)
+    bad_sets = [tuple(sorted(np.random.default_rng(9000 + t).choice(P, 1 + t % 3, replace=False).tolist()))
+                for t in range(n_steps)]
+    ok = [True]
+
+    def inject(t):
+        for p in bad_sets[t]:
+            Ct[p] += noise
+
+    def remove(t):
+        for p in bad_sets[t]:
+            Ct[p] -= noise
+
+    def nodes_only(t):
+        rep = G.gpd_locate_nodes(plan, Ct, workspace=ws)
+        ok[0] = ok[0] and rep.bad == bad_sets[t]
+
+    ms_nodes = timed(nodes_only, inject, remove)
+    ms_nodes_dec = timed(lambda t: G.gpd_decode(plan, Ct, mode=G.GPD_DEC_LSQ_ALL,
+                                                correct_errors=G.GPD_CORRECT_NODES, workspace=ws, C_out=C),
+                         inject, remove)
+    del Ct, C, ws, words
+
+    # (3) regeneration and projection of one coded layer of workload 2
+    c2 = WL.CONFIGS[2]
+    L = G.gpd_layer_create(c2["sizes"][1], c2["sizes"][0], 1, c2["m"], c2["n"], 1, 1, c2["P"])
+    W = torch.from_numpy(WL.mlp_init(c2["sizes"], c2["seed"])[0]).to(dev)
+    Wt = G.gpd_layer_encode_weights(L, W)
+    wbytes = 4.0 * L.wt_rows * L.wt_cols
+    ms_regen = timed(lambda t: G.gpd_layer_regenerate(L, Wt, [t % L.P]))
+    ms_proj = timed(lambda t: G.gpd_layer_project(L, Wt))
+    ms_scrub = timed(lambda t: G.gpd_layer_locate_nodes(L, G.GPD_STACK_WEIGHTS, Wt))
+
+    gb = lambda b, ms: b / (ms * 1e-3) / 1e9
+    out = {"metric": "fault-path stage times", "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "data": "synthetic", "dtype": "f32",
+           "config": {"workload": f"coded matmul {N1}^3 m={m} n={n} d={d} P={P} K={K} with soft errors; "
+                                  f"coded layer 4096x4096 m={c2['m']} n={c2['n']} P={c2['P']}"},
+           "decode_screen_correct": {"ms": ms_elem, "GBps": gb(4.0 * blk * (P + m * d), ms_elem),
+                                     "located_total": located[0],
+                                     "note": "with the host report (stream wait + copies)",
+                                     "ms_without_report": ms_elem_async,
+                                     "GBps_without_report": gb(4.0 * blk * (P + m * d), ms_elem_async)},
+           "locate_nodes": {"ms": ms_nodes, "GBps": gb(4.0 * blk * P, ms_nodes), "all_sets_found": ok[0],
+                            "note": "Gram pass over 16 x 16 MiB + reduction + host search"},
+           "decode_nodes": {"ms": ms_nodes_dec, "GBps": gb(4.0 * blk * (2 * P - 2 + m * d), ms_nodes_dec)},
+           "layer_regenerate_one_node": {"ms": ms_regen, "GBps": gb(wbytes * L.P, ms_regen)},
+           "layer_project": {"ms": ms_proj, "GBps": gb(wbytes * 2 * L.P, ms_proj)},
+           "layer_locate_nodes_weights": {"ms": ms_scrub, "GBps": gb(wbytes * L.P, ms_scrub)}}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=1,
-                    help="workload index: 0/1 coded matmul (1 = headline), 2/3 coded MLP training")
+                    help="workload index: 0/1 coded matmul (1 = headline), 2/3 coded MLP training, "
+                         "4 soft-error and node-fault paths")
     ap.add_argument("--graph", action="store_true", help="(MLP workloads) replay the step as a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -166,6 +282,9 @@ def main():
     cfg = dict(WL.CONFIGS[args.config])
     if cfg["kind"] == "mlp":
         bench_mlp(args, cfg)
+        return
+    if "flip_prob" in cfg:
+        bench_faults(args, cfg)
         return
     cfg.setdefault("trial_seed0", 1000)
     N1, N0, Nc, m, n, d, P = (cfg[k] for k in ("N1", "N0", "Nc", "m", "n", "d", "P"))

@@ -165,8 +165,8 @@ typedef struct {
  *            stream), then the nodes found erroneous are left out like stragglers and the
  *            rest is decoded with `mode`.  In the report n_located = number of bad nodes
  *            times the codewords, node_err_count[p] = codewords for a bad node p, n_flagged
- *            = all codewords if any error was detected; on failure (GPD_E_DECODE_FAIL)
- *            the output is decoded from all present nodes.
+ *            = all codewords if any error was detected, located[] is not written; on
+ *            failure (GPD_E_DECODE_FAIL) the output is decoded from all present nodes.
  *   C:       device fp32 N1 x Nc, leading dimension ldc.
  *   report:  host, or NULL.  With a report the call waits for the stream; without one it
  *            is asynchronous and GPD_E_DECODE_FAIL cannot be returned.

@@ -187,8 +187,9 @@ def _make_report(cap: int):
     return rep, buf
 
 
-def _read_report(rep: _Report, buf, P: int) -> Report:
-    n = int(min(rep.n_located, rep.located_cap))
+def _read_report(rep: _Report, buf, P: int, listed: bool = True) -> Report:
+    # with node-level correction whole nodes are located and no per-element list is written
+    n = int(min(rep.n_located, rep.located_cap)) if listed else 0
     return Report(status=rep.status, n_present=rep.n_present, n_screened=rep.n_screened,
                   n_flagged=rep.n_flagged, n_located=rep.n_located, n_failed=rep.n_failed,
                   node_err_count=np.array(rep.node_err_count[:P], dtype=np.int64),
@@ -332,7 +333,8 @@ def gpd_decode(plan: Plan, Ct, present=None, mode=GPD_DEC_FIRST_K, correct_error
                         _ptr(C_out), C_out.stride(0), ws_ptr, ws_bytes,
                         C.byref(rep) if rep is not None else None)
     _check(st, ok=(GPD_OK,) if raise_on_fail else (GPD_OK, GPD_E_DECODE_FAIL))
-    return C_out, (_read_report(rep, buf, plan.P) if rep is not None else None)
+    return C_out, (_read_report(rep, buf, plan.P, int(correct_errors) != GPD_CORRECT_NODES)
+                   if rep is not None else None)
 
 
 # ------------------------------------------------------------------ coded DNN layer
@@ -446,7 +448,8 @@ def gpd_coded_layer_step(layer: Layer, phase, Wt, X, Dlt=None, eta=0.0, decay=0.
                                   _ptr(out), _ptr(pres), int(correct_errors),
                                   ws.data_ptr(), ws.numel(), C.byref(rep) if rep is not None else None)
     _check(st, ok=(GPD_OK, GPD_E_DECODE_FAIL))
-    return out, (_read_report(rep, buf, layer.P) if rep is not None else None)
+    return out, (_read_report(rep, buf, layer.P, int(correct_errors) != GPD_CORRECT_NODES)
+                 if rep is not None else None)
 
 
 # ------------------------------------------------------------------ node-level faults

@@ -170,7 +170,12 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineParams p) {
     // wave-wide maximum, one atomic per wave
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) ratio = fmaxf(ratio, __shfl_xor(ratio, off));
-    if ((threadIdx.x & 63) == 0 && ratio > 0.f) atomicMax(&p.counters[1], __float_as_uint(ratio));
+    // (a running maximum: after the first few wavefronts almost none has a larger value, and a
+    // plain read that may be stale only costs an unnecessary atomic)
+    if ((threadIdx.x & 63) == 0 && ratio > 0.f) {
+      const uint32_t bits = __float_as_uint(ratio);
+      if (bits > *reinterpret_cast<volatile uint32_t*>(&p.counters[1])) atomicMax(&p.counters[1], bits);
+    }
   }
 
   if (!active) return;

@@ -97,17 +97,17 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
   const int lane = threadIdx.x;
   const int ns = p.t.nin, r = p.t.r, nout = p.t.nout;
 
-  if (lane == 0) {
-    for (int a = 0; a <= 64; ++a) {
-      binom[a][0] = 1ull;
-      for (int b = 1; b <= S_MAX; ++b)
-        binom[a][b] = (a == 0) ? 0ull : binom[a - 1][b - 1] + binom[a - 1][b];
-    }
-  }
-  __syncthreads();
-
   uint32_t n_list = p.counters[0];
   if (n_list > (uint32_t)p.cap) n_list = (uint32_t)p.cap;
+  if (blockIdx.x >= n_list) return;                        // nothing screened for this wavefront
+
+  // Pascal's triangle for the unranking of supports: row a is built by lane b from row a - 1
+  if (lane <= S_MAX) binom[0][lane] = lane == 0 ? 1ull : 0ull;
+  __syncthreads();
+  for (int a = 1; a <= 64; ++a) {
+    if (lane <= S_MAX) binom[a][lane] = lane == 0 ? 1ull : binom[a - 1][lane - 1] + binom[a - 1][lane];
+    __syncthreads();
+  }
 
   for (uint32_t w = blockIdx.x; w < n_list; w += gridDim.x) {
     const int32_t cw = p.list[w];

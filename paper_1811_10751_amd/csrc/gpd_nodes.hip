@@ -30,96 +30,151 @@ struct GramParams {
   const float* H;            // [r][ns] fp32
   int ns, r;
   int64_t ncw;               // codewords = elements per block
-  double* part;              // [gridDim.x][NT][256]
-  double* part_energy;       // [gridDim.x]
+  double* part;              // [gridDim.x][NT * 256 + 64]: Gram tiles, then the energy
   int32_t* wild;             // [ns], zeroed before the launch
 };
 
+template <int NK, int VEC>
+struct ZTile { float v[NK][VEC]; };
+
+// lane l loads VEC codewords starting at 16 VEC it + VEC (l % 16) from node 4 kk + l / 16
+template <int NK, int VEC>
+__device__ __forceinline__ ZTile<NK, VEC> load_ztile(const GramParams& p, const int64_t (&off)[NK], int64_t it,
+                                                     int64_t n_iter, int lj) {
+  ZTile<NK, VEC> z;
+  const int64_t c0 = it * (16 * VEC) + VEC * lj;
+#pragma unroll
+  for (int kk = 0; kk < NK; ++kk) {
+    if (it < n_iter && off[kk] >= 0 && c0 < p.ncw) {          // VEC = 4 only when 4 divides ncw
+      if constexpr (VEC == 4) {
+        const float4 v = *reinterpret_cast<const float4*>(p.in + off[kk] + c0);
+        z.v[kk][0] = v.x; z.v[kk][1] = v.y; z.v[kk][2] = v.z; z.v[kk][3] = v.w;
+      } else {
+        z.v[kk][0] = p.in[off[kk] + c0];
+      }
+    } else {
+#pragma unroll
+      for (int c = 0; c < VEC; ++c) z.v[kk][c] = 0.f;
+    }
+  }
+  return z;
+}
+
 // NK: steps of 4 nodes (ns <= 4 NK); RT: tiles of 16 syndromes (r <= 16 RT); VEC: codewords
-// per lane and load.  A wavefront handles 16 VEC consecutive codewords per iteration: lane l
-// loads VEC codewords starting at 16 VEC it + VEC (l % 16) from node 4 kk + l / 16.
-template <int NK, int RT, int VEC>
+// per lane and load.  A wavefront handles 16 VEC consecutive codewords per iteration; the loads
+// of its next iteration are in flight while the current one is multiplied.
+// PACK (RT = 1, VEC = 4, r <= 16 / PACK): the 16 columns of the syndrome tile are shared by
+// PACK groups of codewords (group g owns columns g (16 / PACK) ..., its syndromes come from the
+// codewords of load component g (4 / PACK) + q), so one fp64 product gives PACK diagonal
+// blocks of Gram matrix at once; the blocks off the diagonal mix two groups and are dropped.
+template <int NK, int RT, int VEC, int PACK>
 __global__ __launch_bounds__(256) void gram_kernel(GramParams p) {
+  static_assert(PACK == 1 || (RT == 1 && VEC == 4), "packing needs one tile and four components");
   constexpr int NT = RT * (RT + 1) / 2;
+  constexpr int NH = PACK > 1 ? PACK : RT;       // B operands per node step
+  constexpr int WCOL = 16 / PACK;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lj = lane & 15, lk = lane >> 4;
 
   // B operand of the syndrome product: B[k = node][j = syndrome] = H[j][node]
-  float hreg[NK][RT];
+  float hreg[NK][NH];
   int64_t off[NK];
 #pragma unroll
   for (int kk = 0; kk < NK; ++kk) {
     const int node = 4 * kk + lk;
     off[kk] = node < p.ns ? p.in_off[node] : -1;
 #pragma unroll
-    for (int t = 0; t < RT; ++t) {
-      const int j = 16 * t + lj;
-      hreg[kk][t] = (node < p.ns && j < p.r) ? p.H[(int64_t)j * p.ns + node] : 0.f;
+    for (int t = 0; t < NH; ++t) {
+      if constexpr (PACK > 1) {
+        const int j = lj % WCOL;
+        hreg[kk][t] = (node < p.ns && lj / WCOL == t && j < p.r) ? p.H[(int64_t)j * p.ns + node] : 0.f;
+      } else {
+        const int j = 16 * t + lj;
+        hreg[kk][t] = (node < p.ns && j < p.r) ? p.H[(int64_t)j * p.ns + node] : 0.f;
+      }
     }
   }
 
-  v4d G[NT];
+  // two accumulators per tile (RT <= 2): consecutive fp64 MFMAs do not wait for each other
+  constexpr int NACC = RT <= 2 ? 2 : 1;
+  v4d G[NT], G2[NACC == 2 ? NT : 1];
 #pragma unroll
   for (int i = 0; i < NT; ++i) G[i] = v4d{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+  for (int i = 0; i < (NACC == 2 ? NT : 1); ++i) G2[i] = v4d{0.0, 0.0, 0.0, 0.0};
   double energy = 0.0;
   uint32_t wildmask = 0;
 
-  const int64_t chunk = 16 * VEC;
-  const int64_t n_iter = (p.ncw + chunk - 1) / chunk;
+  const int64_t n_iter = (p.ncw + 16 * VEC - 1) / (16 * VEC);
   const int64_t n_waves = (int64_t)gridDim.x * 4;
-  for (int64_t it = (int64_t)blockIdx.x * 4 + wave; it < n_iter; it += n_waves) {
-    const int64_t c0 = it * chunk + VEC * lj;
-    float z[NK][VEC];
-#pragma unroll
-    for (int kk = 0; kk < NK; ++kk) {
-      if (off[kk] >= 0 && c0 < p.ncw) {            // VEC = 4 only when 4 divides ncw
-        if constexpr (VEC == 4) {
-          const float4 v = *reinterpret_cast<const float4*>(p.in + off[kk] + c0);
-          z[kk][0] = v.x; z[kk][1] = v.y; z[kk][2] = v.z; z[kk][3] = v.w;
-        } else {
-          z[kk][0] = p.in[off[kk] + c0];
-        }
-      } else {
-#pragma unroll
-        for (int c = 0; c < VEC; ++c) z[kk][c] = 0.f;
-      }
-    }
+  int64_t it = (int64_t)blockIdx.x * 4 + wave;
+  ZTile<NK, VEC> zn = load_ztile<NK, VEC>(p, off, it, n_iter, lj);
+  for (; it < n_iter; it += n_waves) {
+    ZTile<NK, VEC> z = zn;
+    zn = load_ztile<NK, VEC>(p, off, it + n_waves, n_iter, lj);
     // non-finite and huge values: remember the node, take the value as zero
 #pragma unroll
     for (int kk = 0; kk < NK; ++kk) {
 #pragma unroll
       for (int c = 0; c < VEC; ++c) {
-        if (!(fabsf(z[kk][c]) < kWild)) { wildmask |= 1u << kk; z[kk][c] = 0.f; }
-        const double x = (double)z[kk][c];
+        if (!(fabsf(z.v[kk][c]) < kWild)) { wildmask |= 1u << kk; z.v[kk][c] = 0.f; }
+        const double x = (double)z.v[kk][c];
         energy = fma(x, x, energy);
       }
     }
+    if constexpr (PACK > 1) {
 #pragma unroll
-    for (int c = 0; c < VEC; ++c) {
-      // S^T tile t: rows = 16 codewords, columns = syndromes 16 t .. 16 t + 15
-      v4f S[RT];
+      for (int q = 0; q < VEC / PACK; ++q) {
+        v4f S = v4f{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int t = 0; t < RT; ++t) S[t] = v4f{0.f, 0.f, 0.f, 0.f};
+        for (int g = 0; g < PACK; ++g) {
 #pragma unroll
-      for (int kk = 0; kk < NK; ++kk) {
+          for (int kk = 0; kk < NK; ++kk)
+            S = __builtin_amdgcn_mfma_f32_16x16x4f32(z.v[kk][g * (VEC / PACK) + q], hreg[kk][g], S, 0, 0, 0);
+        }
 #pragma unroll
-        for (int t = 0; t < RT; ++t)
-          S[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(z[kk][c], hreg[kk][t], S[t], 0, 0, 0);
+        for (int v = 0; v < 4; ++v) {
+          if (v & 1) G2[0] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)S[v], (double)S[v], G2[0], 0, 0, 0);
+          else G[0] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)S[v], (double)S[v], G[0], 0, 0, 0);
+        }
       }
-      // register v of lane l holds syndrome 16 t + l % 16 of codeword 4 (l / 16) + v: as the
-      // A (and B) operand of the next product that is a 16 x 4 matrix [syndrome][codeword]
-      int ti = 0;
+    } else {
 #pragma unroll
-      for (int t = 0; t < RT; ++t) {
+      for (int c = 0; c < VEC; ++c) {
+        // S^T tile t: rows = 16 codewords, columns = syndromes 16 t .. 16 t + 15
+        v4f S[RT];
 #pragma unroll
-        for (int t2 = t; t2 < RT; ++t2) {
+        for (int t = 0; t < RT; ++t) S[t] = v4f{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-          for (int v = 0; v < 4; ++v)
-            G[ti] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)S[t][v], (double)S[t2][v], G[ti], 0, 0, 0);
-          ++ti;
+        for (int kk = 0; kk < NK; ++kk) {
+#pragma unroll
+          for (int t = 0; t < RT; ++t)
+            S[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(z.v[kk][c], hreg[kk][t], S[t], 0, 0, 0);
+        }
+        // register v of lane l holds syndrome 16 t + l % 16 of codeword 4 (l / 16) + v: as the
+        // A (and B) operand of the next product that is a 16 x 4 matrix [syndrome][codeword]
+        int ti = 0;
+#pragma unroll
+        for (int t = 0; t < RT; ++t) {
+#pragma unroll
+          for (int t2 = t; t2 < RT; ++t2) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+              if (NACC == 2 && (v & 1))
+                G2[ti] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)S[t][v], (double)S[t2][v], G2[ti], 0, 0, 0);
+              else
+                G[ti] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)S[t][v], (double)S[t2][v], G[ti], 0, 0, 0);
+            }
+            ++ti;
+          }
         }
       }
     }
+  }
+
+  if constexpr (NACC == 2) {
+#pragma unroll
+    for (int i = 0; i < NT; ++i) G[i] += G2[i];
   }
 
   // nodes that held a wild value
@@ -135,6 +190,7 @@ __global__ __launch_bounds__(256) void gram_kernel(GramParams p) {
 #pragma unroll
   for (int off2 = 32; off2 > 0; off2 >>= 1) energy += __shfl_xor(energy, off2);
   if (lane == 0) red_e[wave] = energy;
+  double* dst = p.part + (int64_t)blockIdx.x * (NT * 256 + 64);
 #pragma unroll
   for (int ti = 0; ti < NT; ++ti) {
     if (wave > 0) {
@@ -143,54 +199,59 @@ __global__ __launch_bounds__(256) void gram_kernel(GramParams p) {
     }
     __syncthreads();
     if (wave == 0) {
-      double* dst = p.part + ((int64_t)blockIdx.x * NT + ti) * 256;
 #pragma unroll
       for (int v = 0; v < 4; ++v)
-        dst[v * 64 + lane] = ((G[ti][v] + red[0][v * 64 + lane]) + red[1][v * 64 + lane]) + red[2][v * 64 + lane];
+        dst[ti * 256 + v * 64 + lane] =
+            ((G[ti][v] + red[0][v * 64 + lane]) + red[1][v * 64 + lane]) + red[2][v * 64 + lane];
     }
     __syncthreads();
   }
-  if (threadIdx.x == 0) p.part_energy[blockIdx.x] = ((red_e[0] + red_e[1]) + red_e[2]) + red_e[3];
+  if (wave == 0) dst[NT * 256 + lane] = lane == 0 ? ((red_e[0] + red_e[1]) + red_e[2]) + red_e[3] : 0.0;
 }
 
-// out[ti][i] = sum over workgroups of part[wg][ti][i]; block NT sums the energies.
-__global__ __launch_bounds__(256) void gram_reduce_kernel(const double* __restrict__ part,
-                                                          const double* __restrict__ part_energy,
-                                                          int n_wg, int NT, double* __restrict__ out,
-                                                          double* __restrict__ out_energy) {
-  const int ti = blockIdx.x;
-  if (ti < NT) {
-    double acc = 0.0;
-    for (int w = 0; w < n_wg; ++w) acc += part[((int64_t)w * NT + ti) * 256 + threadIdx.x];
-    out[ti * 256 + threadIdx.x] = acc;
-  } else {
-    __shared__ double sh[256];
-    double acc = 0.0;
-    for (int w = threadIdx.x; w < n_wg; w += 256) acc += part_energy[w];
-    sh[threadIdx.x] = acc;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      double tot = 0.0;
-      for (int i = 0; i < 256; ++i) tot += sh[i];
-      *out_energy = tot;
-    }
+// dst[g][i] = sum of src[w][i] over the g-th of gridDim.y equal ranges of w (fixed order).
+__global__ __launch_bounds__(64) void sum_partials_kernel(const double* __restrict__ src, int n_src, int width,
+                                                          double* __restrict__ dst) {
+  const int i = blockIdx.x * 64 + threadIdx.x;
+  const int per = (n_src + gridDim.y - 1) / gridDim.y;
+  const int w0 = blockIdx.y * per, w1 = min(n_src, w0 + per);
+  double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+  int w = w0;
+  for (; w + 4 <= w1; w += 4) {
+    a0 += src[(int64_t)w * width + i];
+    a1 += src[(int64_t)(w + 1) * width + i];
+    a2 += src[(int64_t)(w + 2) * width + i];
+    a3 += src[(int64_t)(w + 3) * width + i];
   }
+  for (; w < w1; ++w) a0 += src[(int64_t)w * width + i];
+  dst[(int64_t)blockIdx.y * width + i] = (a0 + a1) + (a2 + a3);
 }
 
 int tiles_of(int r) { return r <= 16 ? 1 : (r <= 32 ? 2 : 4); }
 
 int gram_grid(int64_t ncw, int RT, int vec) {
   const int64_t n_iter = (ncw + 16 * vec - 1) / (16 * vec);
-  const int64_t max_wg = RT == 1 ? 1024 : (RT == 2 ? 512 : 256);
+  const int64_t max_wg = RT == 1 ? 2048 : (RT == 2 ? 512 : 256);
   return (int)std::max<int64_t>(1, std::min<int64_t>(max_wg, (n_iter + 3) / 4));
 }
 
-constexpr size_t kGramHeader = 512;      // wild[64] int32 at 0, energy (double) at 256
+constexpr size_t kGramHeader = 512;      // wild[64] int32
+constexpr int kGramGroups = 32;          // first reduction stage
+
+// how many groups of codewords share one syndrome tile
+int gram_pack(int r, int vec) { return (vec == 4 && r <= 16) ? (r <= 4 ? 4 : (r <= 8 ? 2 : 1)) : 1; }
 
 template <int NK, int RT>
 gpd_status_t launch_gram_v(hipStream_t s, const GramParams& p, int vec, int n_wg) {
-  if (vec == 4) hipLaunchKernelGGL((gram_kernel<NK, RT, 4>), dim3(n_wg), dim3(256), 0, s, p);
-  else hipLaunchKernelGGL((gram_kernel<NK, RT, 1>), dim3(n_wg), dim3(256), 0, s, p);
+  const int pack = RT == 1 ? gram_pack(p.r, vec) : 1;
+  if constexpr (RT == 1) {
+    if (pack == 4) hipLaunchKernelGGL((gram_kernel<NK, 1, 4, 4>), dim3(n_wg), dim3(256), 0, s, p);
+    else if (pack == 2) hipLaunchKernelGGL((gram_kernel<NK, 1, 4, 2>), dim3(n_wg), dim3(256), 0, s, p);
+  }
+  if (pack == 1) {
+    if (vec == 4) hipLaunchKernelGGL((gram_kernel<NK, RT, 4, 1>), dim3(n_wg), dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((gram_kernel<NK, RT, 1, 1>), dim3(n_wg), dim3(256), 0, s, p);
+  }
   GPD_HIP(hipGetLastError());
   return GPD_OK;
 }
@@ -208,10 +269,9 @@ gpd_status_t launch_gram(hipStream_t s, const GramParams& p, int RT, int vec, in
 
 size_t gram_workspace_bytes(int64_t ncw, int r) {
   const int RT = tiles_of(r), NT = RT * (RT + 1) / 2;
+  const size_t width = (size_t)NT * 256 + 64;
   const int n_wg = gram_grid(ncw, RT, 1);            // the scalar path has the most workgroups
-  size_t b = kGramHeader + (size_t)NT * 2048;
-  b += ((size_t)n_wg * 8 + 255) / 256 * 256;
-  b += (size_t)n_wg * NT * 2048;
+  const size_t b = kGramHeader + (1 + kGramGroups + (size_t)n_wg) * width * 8;
   return (b + 255) / 256 * 256;
 }
 
@@ -259,33 +319,47 @@ gpd_status_t run_locate_nodes(hipStream_t stream, TableRing* ring, const std::ve
   const int vec = (ncw % 4 == 0 && ((uintptr_t)Zt % 16) == 0) ? 4 : 1;
   const int n_wg = gram_grid(ncw, RT, vec);
   char* ws = (char*)workspace;
+  const int width = NT * 256 + 64;
   GramParams gp;
   gp.in = Zt; gp.in_off = t.in_off; gp.H = t.H; gp.ns = ns; gp.r = r; gp.ncw = ncw;
   gp.wild = (int32_t*)ws;
-  double* d_energy = (double*)(ws + 256);
-  double* d_gram = (double*)(ws + kGramHeader);
-  gp.part_energy = (double*)(ws + kGramHeader + (size_t)NT * 2048);
-  gp.part = (double*)(ws + kGramHeader + (size_t)NT * 2048 + ((size_t)n_wg * 8 + 255) / 256 * 256);
+  double* d_out = (double*)(ws + kGramHeader);                 // [width]
+  double* d_stage = d_out + width;                             // [kGramGroups][width]
+  gp.part = d_stage + (size_t)kGramGroups * width;             // [n_wg][width]
   st = launch_zero_words(stream, ws, (int)(kGramHeader / 4));
   if (st != GPD_OK) return st;
   st = launch_gram(stream, gp, RT, vec, n_wg);
   if (st != GPD_OK) return st;
-  hipLaunchKernelGGL(gram_reduce_kernel, dim3(NT + 1), dim3(256), 0, stream, gp.part, gp.part_energy,
-                     n_wg, NT, d_gram, d_energy);
+  // two reduction stages, both in a fixed order
+  const int groups = std::min(kGramGroups, n_wg);
+  hipLaunchKernelGGL(sum_partials_kernel, dim3(width / 64, groups), dim3(64), 0, stream, gp.part, n_wg, width,
+                     d_stage);
+  GPD_HIP(hipGetLastError());
+  hipLaunchKernelGGL(sum_partials_kernel, dim3(width / 64, 1), dim3(64), 0, stream, d_stage, groups, width, d_out);
   GPD_HIP(hipGetLastError());
 
-  // one copy brings wild flags, energy and the Gram tiles back
-  std::vector<char> host(kGramHeader + (size_t)NT * 2048);
+  // one copy brings the wild flags, the Gram tiles and the energy back
+  std::vector<char> host(kGramHeader + (size_t)width * 8);
   GPD_HIP(hipMemcpyAsync(host.data(), ws, host.size(), hipMemcpyDeviceToHost, stream));
   GPD_HIP(hipStreamSynchronize(stream));
   const int32_t* h_wild = (const int32_t*)host.data();
-  double energy;
-  std::memcpy(&energy, host.data() + 256, 8);
   const double* tiles = (const double*)(host.data() + kGramHeader);
+  const double energy = tiles[(size_t)NT * 256];
   // tile (t, t2), register v of lane l: row 16 t + 4 v + l / 16, column 16 t2 + l % 16
   std::vector<double> G((size_t)r * r, 0.0);
+  const int pack = RT == 1 ? gram_pack(r, vec) : 1;
+  if (pack > 1) {
+    // diagonal blocks of the one tile, one per group of codewords
+    const int w = 16 / pack;
+    for (int v = 0; v < 4; ++v)
+      for (int l = 0; l < 64; ++l) {
+        const int row = 4 * v + l / 16, col = l % 16;
+        if (row / w != col / w || row % w >= r || col % w >= r) continue;
+        G[(size_t)(row % w) * r + col % w] += tiles[v * 64 + l];
+      }
+  }
   int ti = 0;
-  for (int a = 0; a < RT; ++a)
+  for (int a = 0; a < RT && pack == 1; ++a)
     for (int b = a; b < RT; ++b, ++ti)
       for (int v = 0; v < 4; ++v)
         for (int l = 0; l < 64; ++l) {
