@@ -27,14 +27,29 @@ class CodedMLP:
     def decode_weights(self):
         return [B.gpd_layer_decode_weights(L, Wt) for L, Wt in zip(self.layers, self.Wts)]
 
-    def step(self, X, Y, eta, decay=0.0, correct_errors=False, want_report=False):
+    def _regenerate(self, l, rep):
+        """Regeneration (Sec. VII): the coded weights of the nodes a node-level decode has just
+        found erroneous are recomputed from the other nodes.  Returns the nodes repaired."""
+        bad = [p for p in range(self.layers[l].P) if rep.node_err_count[p] > 0]
+        if bad and rep.status == B.GPD_OK:
+            B.gpd_layer_regenerate(self.layers[l], self.Wts[l], bad)
+        return bad
+
+    def step(self, X, Y, eta, decay=0.0, correct_errors=False, want_report=False, regenerate=False):
         """One training iteration on the mini-batch X (N_0 x batch), labels Y (N_L x batch).
-        Returns (network output, per-layer list of (forward report, backward report))."""
+        Returns (network output, per-layer list of (forward report, backward report)).
+        regenerate (with correct_errors = GPD_CORRECT_NODES): nodes located as erroneous get
+        their coded weights regenerated right after the decode that found them."""
+        regenerate = regenerate and int(correct_errors) == B.GPD_CORRECT_NODES
+        want_report = want_report or regenerate
         acts = [X]
         reps = []
-        for L, Wt in zip(self.layers, self.Wts):
+        self.repaired = []
+        for l, (L, Wt) in enumerate(zip(self.layers, self.Wts)):
             S, rf = B.gpd_coded_layer_step(L, B.GPD_STEP_FORWARD, Wt, acts[-1],
                                            correct_errors=correct_errors, want_report=want_report)
+            if regenerate:
+                self.repaired += [(l, "forward", p) for p in self._regenerate(l, rf)]
             acts.append(B.gpd_sigmoid_fwd(S, stream=self.stream))
             reps.append([rf, None])
         delta = B.gpd_l2_delta(Y, acts[-1], 2.0 / self.batch, stream=self.stream)
@@ -44,6 +59,8 @@ class CodedMLP:
                                            correct_errors=correct_errors, want_report=want_report,
                                            skip_output=(l == 0))
             reps[l][1] = rb
+            if regenerate and l > 0:
+                self.repaired += [(l, "backward", p) for p in self._regenerate(l, rb)]
             if l > 0:
                 delta = B.gpd_sigmoid_bwd(C, acts[l], stream=self.stream)
         return acts[-1], reps

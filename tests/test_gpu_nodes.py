@@ -327,3 +327,39 @@ def test_cfg4_size_stack_node_search():
     assert np.isclose(rep.energy, energy, rtol=1e-9)
     C, drep = G.gpd_decode(plan, Ct, mode=G.GPD_DEC_LSQ_ALL, correct_errors=G.GPD_CORRECT_NODES)
     assert drep.status == G.GPD_OK and tuple(p for p in range(P) if drep.node_err_count[p]) == bad
+
+
+@pytest.mark.parametrize("batch,m,n,P", [(1, 4, 2, 24), (8, 2, 4, 32)])
+def test_training_with_node_faults_and_regeneration(batch, m, n, P):
+    # the paper's strategy end to end (Sec. VII): stored coded weights of a node are overwritten
+    # between iterations; the next product exposes the node, the decode leaves it out, its
+    # weights are regenerated, and training stays on the trajectory of plain SGD
+    from paper_1811_10751_amd.mlp import CodedMLP
+    sizes = (96, 128, 64, 10)
+    Ws = [(w * 8).astype(np.float32) for w in WL.mlp_init(sizes, seed=2)]
+    mlp = CodedMLP(sizes, batch, m, n, 1, 1, P)
+    mlp.encode_weights([to_dev(w) for w in Ws])
+    Ws_plain = [w.astype(np.float64) for w in Ws]
+    eta = 0.5
+    faults = {2: (1, 5), 4: (0, P - 1), 5: (2, 3)}           # step -> (layer, node)
+    g = torch.Generator(device=DEV).manual_seed(8)
+    for step in range(7):
+        if step in faults:
+            l, p = faults[step]
+            mlp.Wts[l][p] += 0.5 * torch.randn(mlp.Wts[l].shape[1:], generator=g, device=DEV)
+        X, Y = WL.mlp_batch(2, step, sizes[0], sizes[-1], batch)
+        yhat, reps = mlp.step(to_dev(X), to_dev(Y), eta, correct_errors=G.GPD_CORRECT_NODES, regenerate=True)
+        Ws_plain, yhat_p, _ = O.mlp_uncoded_step(Ws_plain, X, Y, np.float32(eta))
+        err = rel_fro(to_np(yhat), yhat_p)
+        say("  step", step, "repaired", mlp.repaired, "yhat err vs plain SGD %.3g" % err)
+        if step in faults:
+            l, p = faults[step]
+            assert mlp.repaired == [(l, "forward", p)]
+        else:
+            assert mlp.repaired == []
+        assert all(r[0].status == G.GPD_OK for r in reps)
+        assert err < 1e-3
+    for L, Wt, W_ref in zip(mlp.layers, mlp.Wts, Ws_plain):
+        assert rel_fro(to_np(G.gpd_layer_decode_weights(L, Wt)), W_ref) < 1e-3
+        rep = G.gpd_layer_locate_nodes(L, G.GPD_STACK_WEIGHTS, Wt)
+        assert rep.bad == ()
