@@ -50,7 +50,15 @@ typedef enum {
   GPD_E_UNSUPPORTED = 8   /* valid request this build has no kernel for                    */
 } gpd_status_t;
 
-typedef enum { GPD_F32 = 0, GPD_BF16 = 1 } gpd_dtype_t;      /* operand type of the worker products */
+/* How the worker products are multiplied.
+ *   GPD_F32:       fp32 operands, fp32 MFMA.
+ *   GPD_BF16:      operands stored and multiplied in bf16 (round-to-nearest-even), fp32 accumulation.
+ *   GPD_F32_SPLIT: fp32 operands in memory; on the way to the bf16 matrix cores every value is
+ *                  written as the sum of three bf16 values and the six partial products of
+ *                  weight >= 2^-16 are accumulated in fp32: the error of a product of two
+ *                  elements stays below 2^-24, that of one fp32 rounding, at about twice the
+ *                  speed of fp32 MFMA.  Values above the bf16 range (3.39e38) overflow. */
+typedef enum { GPD_F32 = 0, GPD_BF16 = 1, GPD_F32_SPLIT = 2 } gpd_dtype_t;
 
 /* Substitution that turns the multivariate product polynomial into one variable
  * (Sec. IV proof of Thm 2; appendix on error tolerance, second case):
@@ -218,7 +226,9 @@ typedef struct {
   int32_t P;
   const double* points;         /* as in gpd_problem_t                                        */
   int32_t worker_dtype;         /* GPD_BF16: forward/backward products in bf16 MFMA; W~ itself,
-                                   encode, decode and update stay fp32                       */
+                                   encode and decode stay fp32.  The update W~_p += eta Dhat Xhat^T
+                                   is an fp32 product: fp32 MFMA for GPD_F32 layers, the
+                                   three-way bf16 split (see gpd_dtype_t) otherwise           */
   int32_t subst;
   double rho_detect, abs_floor;
   void* hip_stream;

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libgpd.so")
 GPD_MAX_P = 64
 GPD_OK, GPD_E_INVALID, GPD_E_SHAPE, GPD_E_POINTS, GPD_E_TOO_FEW, GPD_E_DECODE_FAIL, \
     GPD_E_WORKSPACE, GPD_E_DEVICE, GPD_E_UNSUPPORTED = range(9)
-GPD_F32, GPD_BF16 = 0, 1
+GPD_F32, GPD_BF16, GPD_F32_SPLIT = 0, 1, 2
 GPD_SUB_AUTO, GPD_SUB_U_VN, GPD_SUB_V_UM = 0, 1, 2
 GPD_DEC_FIRST_K, GPD_DEC_LSQ_ALL = 0, 1
 GPD_STEP_FORWARD, GPD_STEP_BACKWARD_UPDATE = 0, 1
@@ -266,7 +266,7 @@ def gpd_encode(plan: Plan, A=None, B=None, At=None, Bt=None):
     """At[P, N1/m, N0/n], Bt[P, N0/n, Nc/d] (allocated here if not given)."""
     import torch
     lib = load_library()
-    dt = torch.float32 if plan.worker_dtype == GPD_F32 else torch.bfloat16
+    dt = torch.bfloat16 if plan.worker_dtype == GPD_BF16 else torch.float32
     lda = ldb = 0
     if A is not None:
         _require_f32_cuda(A, "A")
@@ -293,7 +293,7 @@ def gpd_encode(plan: Plan, A=None, B=None, At=None, Bt=None):
 def gpd_worker_products(plan: Plan, At, Bt, Ct=None):
     import torch
     lib = load_library()
-    dt = torch.float32 if plan.worker_dtype == GPD_F32 else torch.bfloat16
+    dt = torch.bfloat16 if plan.worker_dtype == GPD_BF16 else torch.float32
     shA = (plan.P, plan.N1 // plan.m, plan.N0 // plan.n)
     shB = (plan.P, plan.N0 // plan.n, plan.Nc // plan.d)
     if tuple(At.shape) != shA or tuple(Bt.shape) != shB or At.dtype != dt or Bt.dtype != dt \

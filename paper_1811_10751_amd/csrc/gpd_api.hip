@@ -119,7 +119,7 @@ extern "C" gpd_status_t gpd_plan(const gpd_problem_t* pr, gpd_plan_t** out) {
   if (!pr || !out) return fail(GPD_E_INVALID, "gpd_plan: null argument");
   *out = nullptr;
   if (pr->N1 < 0 || pr->N0 < 0 || pr->Nc < 0) return fail(GPD_E_INVALID, "negative matrix size");
-  if (pr->worker_dtype != GPD_F32 && pr->worker_dtype != GPD_BF16)
+  if (pr->worker_dtype != GPD_F32 && pr->worker_dtype != GPD_BF16 && pr->worker_dtype != GPD_F32_SPLIT)
     return fail(GPD_E_INVALID, "unknown worker dtype %d", pr->worker_dtype);
   if (pr->subst < GPD_SUB_AUTO || pr->subst > GPD_SUB_V_UM)
     return fail(GPD_E_INVALID, "unknown substitution %d", pr->subst);
@@ -313,7 +313,9 @@ extern "C" gpd_status_t gpd_worker_products(const gpd_plan_t* pl, const void* At
   g.strideA = pl->ahA * pl->awA; g.strideB = pl->ahB * pl->awB; g.strideC = pl->ahC * pl->awC;
   g.batch = pl->code.P;
   const bool bf16 = pl->prob.worker_dtype == GPD_BF16;
-  g.a_bf16 = g.b_bf16 = g.mfma_bf16 = bf16;
+  g.a_bf16 = g.b_bf16 = bf16;
+  g.split3 = pl->prob.worker_dtype == GPD_F32_SPLIT;
+  g.mfma_bf16 = bf16 || g.split3;
   return launch_gemm(pl->stream, g);
 }
 

@@ -345,17 +345,39 @@ __device__ __forceinline__ void hload(HStage<SRC, ROWS, NT>& st, const void* bas
   }
 }
 
-// Writes the staged tile to LDS as bf16 [row][k] (row stride HSTRIDE elements).
-template <int SRC, int ROWS, int NT>
+// An fp32 value as the sum of three bf16 values (8 + 8 + 8 significand bits; what is left is
+// below 2^-26 of the value): hi = bf16(x), mid = bf16(x - hi), lo = bf16(x - hi - mid), all
+// round-to-nearest-even, both subtractions exact.  Two values at a time, packed.
+__device__ __forceinline__ void split3_pack(float x0, float x1, uint32_t (&w)[3]) {
+  w[0] = pack_bf16(x0, x1);
+  const float r0 = x0 - __uint_as_float(w[0] << 16), r1 = x1 - __uint_as_float(w[0] & 0xffff0000u);
+  w[1] = pack_bf16(r0, r1);
+  const float s0 = r0 - __uint_as_float(w[1] << 16), s1 = r1 - __uint_as_float(w[1] & 0xffff0000u);
+  w[2] = pack_bf16(s0, s1);
+}
+
+// Writes the staged tile to LDS as bf16 [row][k] (row stride HSTRIDE elements).  With SPLIT = 3
+// (fp32 sources only) three such planes, PLANE elements apart, hold hi / mid / lo.
+template <int SRC, int ROWS, int NT, int SPLIT, int PLANE>
 __device__ __forceinline__ void hstore(const HStage<SRC, ROWS, NT>& st, uint16_t* __restrict__ lds, int tid) {
+  static_assert(SPLIT == 1 || SRC == SRC_F32_KC || SRC == SRC_F32_RC, "only fp32 sources are split");
   if constexpr (SRC == SRC_F32_KC) {
 #pragma unroll
     for (int q = 0; q < ROWS * 8 / NT; ++q) {
       const int f = tid + NT * q;
-      uint2 w;
-      w.x = pack_bf16(st.v[q].x, st.v[q].y);
-      w.y = pack_bf16(st.v[q].z, st.v[q].w);
-      *reinterpret_cast<uint2*>(lds + (f >> 3) * HSTRIDE + 4 * (f & 7)) = w;
+      uint16_t* dst = lds + (f >> 3) * HSTRIDE + 4 * (f & 7);
+      if constexpr (SPLIT == 1) {
+        uint2 w;
+        w.x = pack_bf16(st.v[q].x, st.v[q].y);
+        w.y = pack_bf16(st.v[q].z, st.v[q].w);
+        *reinterpret_cast<uint2*>(dst) = w;
+      } else {
+        uint32_t a[3], b[3];
+        split3_pack(st.v[q].x, st.v[q].y, a);
+        split3_pack(st.v[q].z, st.v[q].w, b);
+#pragma unroll
+        for (int pl = 0; pl < 3; ++pl) *reinterpret_cast<uint2*>(dst + pl * PLANE) = make_uint2(a[pl], b[pl]);
+      }
     }
   } else if constexpr (SRC == SRC_BF16_KC) {
 #pragma unroll
@@ -377,7 +399,15 @@ __device__ __forceinline__ void hstore(const HStage<SRC, ROWS, NT>& st, uint16_t
         float l = lo[0], h = hi[0];
 #pragma unroll
         for (int c = 1; c < 4; ++c) { if (ee == c) { l = lo[c]; h = hi[c]; } }
-        *reinterpret_cast<uint32_t*>(lds + (4 * rq + ee) * HSTRIDE + 2 * kp) = pack_bf16(l, h);
+        uint16_t* dst = lds + (4 * rq + ee) * HSTRIDE + 2 * kp;
+        if constexpr (SPLIT == 1) {
+          *reinterpret_cast<uint32_t*>(dst) = pack_bf16(l, h);
+        } else {
+          uint32_t w[3];
+          split3_pack(l, h, w);
+#pragma unroll
+          for (int pl = 0; pl < 3; ++pl) *reinterpret_cast<uint32_t*>(dst + pl * PLANE) = w[pl];
+        }
       }
     }
   } else {
@@ -405,12 +435,19 @@ __device__ __forceinline__ void hstore(const HStage<SRC, ROWS, NT>& st, uint16_t
 }
 
 // TBM x TBN workgroup tile, WGM x WGN wavefronts, each owning (TBM/WGM) x (TBN/WGN).
-template <int ASRC, int BSRC, int MODE, int TBM, int TBN, int WGM, int WGN>
-__global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? 3 : 1) void gemm_bf16_kernel(HGemmParams g) {
+// SPLIT = 3: both operands are fp32 in memory and are multiplied as sums of three bf16 values;
+// the six partial products of weight >= 2^-16 are accumulated (hi*hi, hi*mid, mid*hi, hi*lo,
+// mid*mid, lo*hi), which leaves a relative error below 2^-24 per product of two elements, the
+// rounding of one fp32 multiplication.  The three planes of a stage share one LDS buffer, so
+// the stage is single-buffered with two barriers.
+template <int ASRC, int BSRC, int MODE, int TBM, int TBN, int WGM, int WGN, int SPLIT>
+__global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4 && SPLIT == 1) ? 3 : 1) void gemm_bf16_kernel(HGemmParams g) {
   constexpr int NT = 64 * WGM * WGN;
   constexpr int WM = TBM / WGM, WN = TBN / WGN, MI = WM / 32, NJ = WN / 32;
-  __shared__ __attribute__((aligned(16))) uint16_t lds_a[2][TBM * HSTRIDE];
-  __shared__ __attribute__((aligned(16))) uint16_t lds_b[2][TBN * HSTRIDE];
+  constexpr int NBUF = SPLIT == 1 ? 2 : 1;
+  constexpr int PA = TBM * HSTRIDE, PB = TBN * HSTRIDE;          // elements per plane
+  __shared__ __attribute__((aligned(16))) uint16_t lds_a[NBUF][SPLIT * PA];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_b[NBUF][SPLIT * PB];
 
   const int xcd = blockIdx.x & 7;
   const int slot = blockIdx.x >> 3;
@@ -447,12 +484,12 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? 3 : 1) void gemm
   HStage<BSRC, TBN, NT> sb;
   hload<ASRC, MODE, TBM, NT>(sa, A, g.lda, m0, 0, g.M, g.K, tid);
   hload<BSRC, MODE, TBN, NT>(sb, B, g.ldb, n0, 0, g.N, g.K, tid);
-  hstore<ASRC, TBM, NT>(sa, lds_a[0], tid);
-  hstore<BSRC, TBN, NT>(sb, lds_b[0], tid);
+  hstore<ASRC, TBM, NT, SPLIT, PA>(sa, lds_a[0], tid);
+  hstore<BSRC, TBN, NT, SPLIT, PB>(sb, lds_b[0], tid);
   __syncthreads();
 
   for (int c = 0; c < nchunks; ++c) {
-    const int cur = c & 1;
+    const int cur = (NBUF == 2) ? (c & 1) : 0;
     if (c + 1 < nchunks) {
       hload<ASRC, MODE, TBM, NT>(sa, A, g.lda, m0, (c + 1) * HBK, g.M, g.K, tid);
       hload<BSRC, MODE, TBN, NT>(sb, B, g.ldb, n0, (c + 1) * HBK, g.N, g.K, tid);
@@ -462,22 +499,48 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? 3 : 1) void gemm
 #pragma unroll
     for (int h = 0; h < HBK / 16; ++h) {
       union Frag { uint4 u; bf16x8 v; };
-      Frag fa[MI], fb[NJ];
+      if constexpr (SPLIT == 1) {
+        Frag fa[MI], fb[NJ];
 #pragma unroll
-      for (int i = 0; i < MI; ++i)
-        fa[i].u = *reinterpret_cast<const uint4*>(as + (wm + 32 * i + li) * HSTRIDE + 16 * h + 8 * lg);
-#pragma unroll
-      for (int j = 0; j < NJ; ++j)
-        fb[j].u = *reinterpret_cast<const uint4*>(bs + (wn + 32 * j + li) * HSTRIDE + 16 * h + 8 * lg);
-#pragma unroll
-      for (int i = 0; i < MI; ++i)
+        for (int i = 0; i < MI; ++i)
+          fa[i].u = *reinterpret_cast<const uint4*>(as + (wm + 32 * i + li) * HSTRIDE + 16 * h + 8 * lg);
 #pragma unroll
         for (int j = 0; j < NJ; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i].v, fb[j].v, acc[i][j], 0, 0, 0);
+          fb[j].u = *reinterpret_cast<const uint4*>(bs + (wn + 32 * j + li) * HSTRIDE + 16 * h + 8 * lg);
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+          for (int j = 0; j < NJ; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i].v, fb[j].v, acc[i][j], 0, 0, 0);
+      } else {
+        // all planes of A stay in registers; the planes of B are fetched one at a time, the
+        // smallest first, each multiplied with the planes of A that keep the weight >= 2^-16
+        Frag fa[MI][3];
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+          for (int pl = 0; pl < 3; ++pl)
+            fa[i][pl].u = *reinterpret_cast<const uint4*>(as + pl * PA + (wm + 32 * i + li) * HSTRIDE + 16 * h + 8 * lg);
+#pragma unroll
+        for (int pb = 2; pb >= 0; --pb) {
+          Frag fb[NJ];
+#pragma unroll
+          for (int j = 0; j < NJ; ++j)
+            fb[j].u = *reinterpret_cast<const uint4*>(bs + pb * PB + (wn + 32 * j + li) * HSTRIDE + 16 * h + 8 * lg);
+#pragma unroll
+          for (int pa = 2 - pb; pa >= 0; --pa)
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+              for (int j = 0; j < NJ; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i][pa].v, fb[j].v, acc[i][j], 0, 0, 0);
+        }
+      }
     }
     if (c + 1 < nchunks) {
-      hstore<ASRC, TBM, NT>(sa, lds_a[cur ^ 1], tid);
-      hstore<BSRC, TBN, NT>(sb, lds_b[cur ^ 1], tid);
+      if constexpr (NBUF == 1) __syncthreads();              // every wavefront is done reading the stage
+      hstore<ASRC, TBM, NT, SPLIT, PA>(sa, lds_a[NBUF == 2 ? (cur ^ 1) : 0], tid);
+      hstore<BSRC, TBN, NT, SPLIT, PB>(sb, lds_b[NBUF == 2 ? (cur ^ 1) : 0], tid);
     }
     __syncthreads();
   }
@@ -508,7 +571,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? 3 : 1) void gemm
     }
 }
 
-template <int ASRC, int BSRC>
+template <int ASRC, int BSRC, int SPLIT>
 gpd_status_t launch_bf16_t(hipStream_t stream, HGemmParams p, int64_t batch, bool aligned) {
   // same two workgroup shapes as the fp32 kernel; the large one needs full aligned tiles
   const bool large = aligned && p.M % 256 == 0 && p.N % 256 == 0 && p.K % HBK == 0 && p.K > 0 &&
@@ -522,11 +585,16 @@ gpd_status_t launch_bf16_t(hipStream_t stream, HGemmParams p, int64_t batch, boo
   p.tiles_per_xcd = (int)((total + 7) / 8);
   dim3 grid((unsigned)(p.tiles_per_xcd * 8));
   if (large) {
-    hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 0, 256, 256, 4, 4>), grid, dim3(1024), 0, stream, p);
+    // the split kernel keeps three planes of A in registers: 8 wavefronts of 128 x 64 (256
+    // registers each) instead of 16 of 64 x 64 (128 registers)
+    if constexpr (SPLIT == 3)
+      hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 0, 256, 256, 2, 4, SPLIT>), grid, dim3(512), 0, stream, p);
+    else
+      hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 0, 256, 256, 4, 4, SPLIT>), grid, dim3(1024), 0, stream, p);
   } else {
     const bool full = aligned && p.M % 128 == 0 && p.N % 128 == 0 && p.K % HBK == 0 && p.K > 0;
-    if (full) hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 0, 128, 128, 2, 2>), grid, dim3(256), 0, stream, p);
-    else hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 1, 128, 128, 2, 2>), grid, dim3(256), 0, stream, p);
+    if (full) hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 0, 128, 128, 2, 2, SPLIT>), grid, dim3(256), 0, stream, p);
+    else hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 1, 128, 128, 2, 2, SPLIT>), grid, dim3(256), 0, stream, p);
   }
   GPD_HIP(hipGetLastError());
   return GPD_OK;
@@ -574,7 +642,9 @@ gpd_status_t launch_gemm(hipStream_t stream, const GemmArgs& a) {
     return fail(GPD_E_SHAPE, "gemm: dimension above 2^31");
   if ((a.a_bf16 || a.b_bf16) && !a.mfma_bf16)
     return fail(GPD_E_INVALID, "gemm: bf16 operands need the bf16 multiply");
-  if (a.mfma_bf16 && (a.transB || (a.transA && a.a_bf16)))
+  if (a.split3 && (!a.mfma_bf16 || a.a_bf16 || a.b_bf16))
+    return fail(GPD_E_INVALID, "gemm: the three-way split needs fp32 operands and the bf16 multiply");
+  if (a.mfma_bf16 && !a.split3 && (a.transB || (a.transA && a.a_bf16)))
     return fail(GPD_E_UNSUPPORTED, "gemm: this operand layout has no bf16 kernel");
   // operand shapes must match what the kernel and its grid assume
   const int64_t a_rows = a.transA ? a.K : a.M, a_cols = a.transA ? a.M : a.K;
@@ -599,12 +669,18 @@ gpd_status_t launch_gemm(hipStream_t stream, const GemmArgs& a) {
     const bool al = ((uintptr_t)a.A % 16 == 0) && ((uintptr_t)a.B % 16 == 0) &&
                     (a.lda * a_es) % 16 == 0 && (a.ldb * b_es) % 16 == 0 &&
                     (a.strideA * a_es) % 16 == 0 && (a.strideB * b_es) % 16 == 0;
-    if (!a.transA && !a.a_bf16 && !a.b_bf16) return launch_bf16_t<SRC_F32_KC, SRC_F32_RC>(stream, h, a.batch, al);
-    if (!a.transA && !a.a_bf16 && a.b_bf16) return launch_bf16_t<SRC_F32_KC, SRC_BF16_RC>(stream, h, a.batch, al);
-    if (!a.transA && a.a_bf16 && a.b_bf16) return launch_bf16_t<SRC_BF16_KC, SRC_BF16_RC>(stream, h, a.batch, al);
-    if (!a.transA && a.a_bf16 && !a.b_bf16) return launch_bf16_t<SRC_BF16_KC, SRC_F32_RC>(stream, h, a.batch, al);
-    if (a.transA && !a.b_bf16) return launch_bf16_t<SRC_F32_RC, SRC_F32_RC>(stream, h, a.batch, al);
-    return launch_bf16_t<SRC_F32_RC, SRC_BF16_RC>(stream, h, a.batch, al);
+    if (a.split3) {
+      if (!a.transA && !a.transB) return launch_bf16_t<SRC_F32_KC, SRC_F32_RC, 3>(stream, h, a.batch, al);
+      if (!a.transA && a.transB) return launch_bf16_t<SRC_F32_KC, SRC_F32_KC, 3>(stream, h, a.batch, al);
+      if (a.transA && !a.transB) return launch_bf16_t<SRC_F32_RC, SRC_F32_RC, 3>(stream, h, a.batch, al);
+      return launch_bf16_t<SRC_F32_RC, SRC_F32_KC, 3>(stream, h, a.batch, al);
+    }
+    if (!a.transA && !a.a_bf16 && !a.b_bf16) return launch_bf16_t<SRC_F32_KC, SRC_F32_RC, 1>(stream, h, a.batch, al);
+    if (!a.transA && !a.a_bf16 && a.b_bf16) return launch_bf16_t<SRC_F32_KC, SRC_BF16_RC, 1>(stream, h, a.batch, al);
+    if (!a.transA && a.a_bf16 && a.b_bf16) return launch_bf16_t<SRC_BF16_KC, SRC_BF16_RC, 1>(stream, h, a.batch, al);
+    if (!a.transA && a.a_bf16 && !a.b_bf16) return launch_bf16_t<SRC_BF16_KC, SRC_F32_RC, 1>(stream, h, a.batch, al);
+    if (a.transA && !a.b_bf16) return launch_bf16_t<SRC_F32_RC, SRC_F32_RC, 1>(stream, h, a.batch, al);
+    return launch_bf16_t<SRC_F32_RC, SRC_BF16_RC, 1>(stream, h, a.batch, al);
   }
 
   GemmParams p;

@@ -173,6 +173,8 @@ struct GemmArgs {
   bool transB = false;            // B stored N x K
   bool a_bf16 = false, b_bf16 = false;   // element types in memory (fp32 otherwise)
   bool mfma_bf16 = false;         // multiply in bf16 (fp32 inputs are rounded on the way)
+  bool split3 = false;            // with mfma_bf16 and fp32 operands: each operand as the sum of three
+                                  // bf16 values, six partial products: fp32-level accuracy
   float alpha = 1.f, beta = 0.f;  // C = beta*C + alpha*op(A)op(B)
 };
 gpd_status_t launch_gemm(hipStream_t stream, const GemmArgs& g);

@@ -256,7 +256,7 @@ extern "C" gpd_status_t gpd_layer_create(const gpd_layer_desc_t* d, gpd_layer_t*
   if (d->N_out < 1 || d->N_in < 1 || d->batch < 1 || d->d1 < 1 || d->d2 < 1)
     return fail(GPD_E_INVALID, "layer sizes must be >= 1");
   if (d->batch % d->d1 || d->batch % d->d2) return fail(GPD_E_SHAPE, "d1 and d2 must divide the batch");
-  if (d->worker_dtype != GPD_F32 && d->worker_dtype != GPD_BF16)
+  if (d->worker_dtype != GPD_F32 && d->worker_dtype != GPD_BF16 && d->worker_dtype != GPD_F32_SPLIT)
     return fail(GPD_E_INVALID, "unknown worker dtype");
   if (d->m < 1 || d->n < 1) return fail(GPD_E_INVALID, "m, n must be >= 1");
   if (d->m * d->d2 > GPD_MAX_BLOCKS || d->n * d->d2 > GPD_MAX_BLOCKS)
@@ -603,7 +603,8 @@ extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, floa
   hipStream_t s = L->stream;
   ScreenArgs none;
   gpd_status_t st;
-  const bool bf16 = d.worker_dtype == GPD_BF16;
+  const bool split = d.worker_dtype == GPD_F32_SPLIT;
+  const bool bf16 = d.worker_dtype == GPD_BF16 || split;       // products on the bf16 matrix cores
   const bool skinny = skinny_ok(L) && !bf16;
 
   if (phase == GPD_STEP_FORWARD) {
@@ -627,7 +628,7 @@ extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, floa
       g.M = L->wr; g.K = L->wc; g.N = L->nb1;
       g.lda = L->wc; g.ldb = L->nb1; g.ldc = L->nb1;
       g.strideA = L->wr * L->wc; g.strideB = L->wc * L->nb1; g.strideC = L->wr * L->nb1;
-      g.batch = P; g.mfma_bf16 = bf16;
+      g.batch = P; g.mfma_bf16 = bf16; g.split3 = split;
       st = launch_gemm(s, g);
     }
     if (st != GPD_OK) return st;
@@ -702,17 +703,19 @@ extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, floa
       g.M = L->wc; g.K = L->wr; g.N = L->nb2;
       g.lda = L->wc; g.ldb = L->nb2; g.ldc = L->nb2;
       g.strideA = L->wr * L->wc; g.strideB = L->wr * L->nb2; g.strideC = L->wc * L->nb2;
-      g.batch = P; g.mfma_bf16 = bf16;
+      g.batch = P; g.mfma_bf16 = bf16; g.split3 = split;
       st = launch_gemm(s, g);
       if (st != GPD_OK) return st;
     }
-    // W~_p <- keep * W~_p + eta * Dhat_p Xhat_p^T   (step O3 in coded form, fp32)
+    // W~_p <- keep * W~_p + eta * Dhat_p Xhat_p^T   (step O3 in coded form, fp32: on the fp32
+    // matrix cores for fp32 layers, as six bf16 partial products otherwise)
     GemmArgs g;
     g.A = Dh; g.B = Xh; g.transB = true; g.C = Wt;
     g.M = L->wr; g.K = d.batch; g.N = L->wc;
     g.lda = d.batch; g.ldb = d.batch; g.ldc = L->wc;
     g.strideA = L->wr * d.batch; g.strideB = L->wc * d.batch; g.strideC = L->wr * L->wc;
     g.batch = P; g.alpha = eta; g.beta = keep;
+    g.mfma_bf16 = g.split3 = bf16;
     st = launch_gemm(s, g);
     if (st != GPD_OK) return st;
   }
