@@ -19,6 +19,7 @@ gpd_status_t TableRing::init(size_t bytes_per_slot) {
   for (int i = 0; i < kSlots; ++i) GPD_HIP(hipEventCreateWithFlags(&ev[i], hipEventDisableTiming));
   GPD_HIP(hipMalloc((void**)&arena, kArenaBytes));
   arena_used = 0;
+  GPD_HIP(hipStreamCreateWithFlags(&up, hipStreamNonBlocking));
   return GPD_OK;
 }
 
@@ -32,15 +33,18 @@ gpd_status_t TableRing::cached(const std::string& key,
   if (st != GPD_OK) return st;
   const size_t need = ht.bytes();
   if (arena_used + need > kArenaBytes || need > slot_bytes) return upload(ht, stream, out);
-  // stage in a pinned ring slot, copy to the arena in stream order (no host wait)
+  // stage in a pinned ring slot and copy to the arena on the upload stream: the region is written
+  // once and never again, so the copy may run while earlier work of `stream` (a long product,
+  // say) is still executing; `stream` only waits for the copy's event
   const int sl = next;
   next = (next + 1) % kSlots;
   if (used[sl]) GPD_HIP(hipEventSynchronize(ev[sl]));
   char* h = host + (size_t)sl * slot_bytes;
   char* d = arena + arena_used;
   *out = ht.pack(h, d);
-  GPD_HIP(hipMemcpyAsync(d, h, need, hipMemcpyHostToDevice, stream));
-  GPD_HIP(hipEventRecord(ev[sl], stream));
+  GPD_HIP(hipMemcpyAsync(d, h, need, hipMemcpyHostToDevice, up));
+  GPD_HIP(hipEventRecord(ev[sl], up));
+  GPD_HIP(hipStreamWaitEvent(stream, ev[sl], 0));
   used[sl] = true;
   arena_used += need;
   cache.emplace(key, *out);
@@ -50,6 +54,7 @@ gpd_status_t TableRing::cached(const std::string& key,
 void TableRing::destroy() {
   for (int i = 0; i < kSlots; ++i)
     if (ev[i]) { (void)hipEventDestroy(ev[i]); ev[i] = nullptr; }
+  if (up) { (void)hipStreamSynchronize(up); (void)hipStreamDestroy(up); up = nullptr; }
   if (host) { (void)hipHostFree(host); host = nullptr; }
   if (dev) { (void)hipFree(dev); dev = nullptr; }
   if (arena) { (void)hipFree(arena); arena = nullptr; }

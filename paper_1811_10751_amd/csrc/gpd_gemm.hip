@@ -441,7 +441,7 @@ __device__ __forceinline__ void hstore(const HStage<SRC, ROWS, NT>& st, uint16_t
 // rounding of one fp32 multiplication.  The three planes of a stage share one LDS buffer, so
 // the stage is single-buffered with two barriers.
 template <int ASRC, int BSRC, int MODE, int TBM, int TBN, int WGM, int WGN, int SPLIT>
-__global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4 && SPLIT == 1) ? 3 : 1) void gemm_bf16_kernel(HGemmParams g) {
+__global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 : 2) : 1) void gemm_bf16_kernel(HGemmParams g) {
   constexpr int NT = 64 * WGM * WGN;
   constexpr int WM = TBM / WGM, WN = TBN / WGN, MI = WM / 32, NJ = WN / 32;
   constexpr int NBUF = SPLIT == 1 ? 2 : 1;
@@ -574,8 +574,10 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4 && SPLIT == 1) ? 3 
 template <int ASRC, int BSRC, int SPLIT>
 gpd_status_t launch_bf16_t(hipStream_t stream, HGemmParams p, int64_t batch, bool aligned) {
   // same two workgroup shapes as the fp32 kernel; the large one needs full aligned tiles
+  // (the split kernel with a short contraction is dominated by the read-modify-write of its
+  // output tile: two small workgroups per CU overlap one's epilogue with the other's products)
   const bool large = aligned && p.M % 256 == 0 && p.N % 256 == 0 && p.K % HBK == 0 && p.K > 0 &&
-                     (int64_t)(p.M / 256) * (p.N / 256) * batch >= 256;
+                     (int64_t)(p.M / 256) * (p.N / 256) * batch >= 256 && (SPLIT == 1 || p.K >= 1024);
   const int tbm = large ? 256 : 128, tbn = large ? 256 : 128;
   p.tiles_m = (p.M + tbm - 1) / tbm;
   p.tiles_n = (p.N + tbn - 1) / tbn;

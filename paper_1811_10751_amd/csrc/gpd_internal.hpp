@@ -129,13 +129,15 @@ struct TableRing {
 
   // Tables that recur (same code, same leading dimension, same erasure pattern) are built and
   // uploaded once and then stay in a device arena: `key` identifies the table, `build` makes
-  // it on a miss.  A miss stages the table in a pinned ring slot and copies it in stream
-  // order, so a caller that wants to capture its calls in a HIP graph has to make each
-  // distinct call once before capturing (a captured copy would re-read a recycled slot).
+  // it on a miss.  A miss stages the table in a pinned ring slot and copies it on an upload
+  // stream of the ring's own (the caller's stream waits for the copy's event), so a caller
+  // that wants to capture its calls in a HIP graph has to make each distinct call once before
+  // capturing (a captured copy would re-read a recycled slot).
   // When the arena is full the table goes through the ring instead.
   static constexpr size_t kArenaBytes = 1 << 20;
   char* arena = nullptr;
   size_t arena_used = 0;
+  hipStream_t up = nullptr;            // uploads into the arena (default priority, non-blocking)
   std::map<std::string, CombineTable> cache;
   gpd_status_t cached(const std::string& key, const std::function<gpd_status_t(HostCombineTable*)>& build,
                       hipStream_t stream, CombineTable* out);
