@@ -235,8 +235,10 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? 3 : 1) void gemm
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int HBK = 32;                 // k-values per stage
-constexpr int HSTRIDE = HBK + 8;        // bf16 elements per LDS row (80 bytes)
+// k-values per LDS stage: HK = 32 for the plain kernel, 16 for the three-way split (three planes
+// per operand, still double-buffered); a row of a tile is HK + 8 bf16 elements apart from the
+// next (80 or 48 bytes: the 128-bit reads of 8 consecutive rows fall on 32 different banks)
+constexpr int hk_of(int split) { return split == 1 ? 32 : 16; }
 
 enum { SRC_F32_KC = 0, SRC_BF16_KC = 1, SRC_F32_RC = 2, SRC_BF16_RC = 3 };
 
@@ -280,42 +282,44 @@ __device__ __forceinline__ uint4 load8h(const uint16_t* p, int nvalid) {
 }
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
-// One operand tile of ROWS rows x 32 k in flight, still in source form, spread over NT threads.
-// Items per thread: F32_KC ROWS*8/NT float4; BF16_KC ROWS*4/NT uint4; F32_RC 4*ROWS/NT patches of
-// 2 k x 4 rows; BF16_RC 2*ROWS/NT patches of 2 k x 8 rows (threads beyond the patch count idle).
-template <int SRC, int ROWS, int NT> struct HStage;
-template <int ROWS, int NT> struct HStage<SRC_F32_KC, ROWS, NT> { float4 v[ROWS * 8 / NT]; };
-template <int ROWS, int NT> struct HStage<SRC_BF16_KC, ROWS, NT> { uint4 v[ROWS * 4 / NT]; };
-template <int ROWS, int NT> struct HStage<SRC_F32_RC, ROWS, NT> { float4 v[4 * ROWS / NT][2]; };
-template <int ROWS, int NT> struct HStage<SRC_BF16_RC, ROWS, NT> { uint4 v[(2 * ROWS + NT - 1) / NT][2]; };
+// One operand tile of ROWS rows x HK k in flight, still in source form, spread over NT threads.
+// Items per thread: F32_KC ROWS*(HK/4)/NT float4; BF16_KC ROWS*(HK/8)/NT uint4; F32_RC
+// ROWS*HK/8/NT patches of 2 k x 4 rows; BF16_RC ROWS*HK/16/NT patches of 2 k x 8 rows (threads
+// beyond the patch count idle).
+template <int SRC, int ROWS, int NT, int HK> struct HStage;
+template <int ROWS, int NT, int HK> struct HStage<SRC_F32_KC, ROWS, NT, HK> { float4 v[ROWS * (HK / 4) / NT]; };
+template <int ROWS, int NT, int HK> struct HStage<SRC_BF16_KC, ROWS, NT, HK> { uint4 v[(ROWS * (HK / 8) + NT - 1) / NT]; };
+template <int ROWS, int NT, int HK> struct HStage<SRC_F32_RC, ROWS, NT, HK> { float4 v[ROWS * HK / 8 / NT][2]; };
+template <int ROWS, int NT, int HK> struct HStage<SRC_BF16_RC, ROWS, NT, HK> { uint4 v[(ROWS * HK / 16 + NT - 1) / NT][2]; };
 
 // base: start of the operand for this batch entry; "row" is the m (or n) index, k the
 // contraction index.  KC sources are [row][k] with leading dimension ld, RC sources [k][row].
-template <int SRC, int MODE, int ROWS, int NT>
-__device__ __forceinline__ void hload(HStage<SRC, ROWS, NT>& st, const void* base, int64_t ld, int row0,
+template <int SRC, int MODE, int ROWS, int NT, int HK>
+__device__ __forceinline__ void hload(HStage<SRC, ROWS, NT, HK>& st, const void* base, int64_t ld, int row0,
                                       int k0, int nrows, int nk, int tid) {
   if constexpr (SRC == SRC_F32_KC) {
     const float* b = (const float*)base;
 #pragma unroll
-    for (int q = 0; q < ROWS * 8 / NT; ++q) {
+    for (int q = 0; q < ROWS * (HK / 4) / NT; ++q) {
       const int f = tid + NT * q;
-      const int row = row0 + (f >> 3), k = k0 + 4 * (f & 7);
+      const int row = row0 + f / (HK / 4), k = k0 + 4 * (f % (HK / 4));
       const int nv = (MODE == 0) ? 4 : (row < nrows ? clampi(nk - k, 0, 4) : 0);
       st.v[q] = (MODE == 0 || nv > 0) ? load4f<MODE>(b + (int64_t)row * ld + k, nv) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
   } else if constexpr (SRC == SRC_BF16_KC) {
     const uint16_t* b = (const uint16_t*)base;
 #pragma unroll
-    for (int q = 0; q < ROWS * 4 / NT; ++q) {
+    for (int q = 0; q < (ROWS * (HK / 8) + NT - 1) / NT; ++q) {
       const int f = tid + NT * q;
-      const int row = row0 + (f >> 2), k = k0 + 8 * (f & 3);
-      const int nv = (MODE == 0) ? 8 : (row < nrows ? clampi(nk - k, 0, 8) : 0);
-      st.v[q] = (MODE == 0 || nv > 0) ? load8h<MODE>(b + (int64_t)row * ld + k, nv) : make_uint4(0u, 0u, 0u, 0u);
+      const int row = row0 + f / (HK / 8), k = k0 + 8 * (f % (HK / 8));
+      const bool mine = f < ROWS * (HK / 8);
+      const int nv = !mine ? 0 : ((MODE == 0) ? 8 : (row < nrows ? clampi(nk - k, 0, 8) : 0));
+      st.v[q] = (nv > 0) ? load8h<MODE>(b + (int64_t)row * ld + k, nv) : make_uint4(0u, 0u, 0u, 0u);
     }
   } else if constexpr (SRC == SRC_F32_RC) {
     const float* b = (const float*)base;
 #pragma unroll
-    for (int q = 0; q < 4 * ROWS / NT; ++q) {
+    for (int q = 0; q < ROWS * HK / 8 / NT; ++q) {
       const int f = tid + NT * q;
       const int kp = (f & 3) + 4 * (f / ROWS), rq = (f >> 2) % (ROWS / 4);
       const int row = row0 + 4 * rq;
@@ -330,14 +334,14 @@ __device__ __forceinline__ void hload(HStage<SRC, ROWS, NT>& st, const void* bas
   } else {
     const uint16_t* b = (const uint16_t*)base;
 #pragma unroll
-    for (int q = 0; q < (2 * ROWS + NT - 1) / NT; ++q) {
+    for (int q = 0; q < (ROWS * HK / 16 + NT - 1) / NT; ++q) {
       const int f = tid + NT * q;
       const int kp = (f & 3) + 4 * (f / (ROWS / 2)), rq = (f >> 2) % (ROWS / 8);
       const int row = row0 + 8 * rq;
 #pragma unroll
       for (int par = 0; par < 2; ++par) {
         const int k = k0 + 2 * kp + par;
-        const bool mine = f < 2 * ROWS;
+        const bool mine = f < ROWS * HK / 16;
         const int nv = !mine ? 0 : ((MODE == 0) ? 8 : (k < nk ? clampi(nrows - row, 0, 8) : 0));
         st.v[q][par] = (nv > 0) ? load8h<MODE>(b + (int64_t)k * ld + row, nv) : make_uint4(0u, 0u, 0u, 0u);
       }
@@ -356,98 +360,103 @@ __device__ __forceinline__ void split3_pack(float x0, float x1, uint32_t (&w)[3]
   w[2] = pack_bf16(s0, s1);
 }
 
-// Writes the staged tile to LDS as bf16 [row][k] (row stride HSTRIDE elements).  With SPLIT = 3
+// Writes the staged tile to LDS as bf16 [row][k] (row stride HK + 8 elements).  With SPLIT = 3
 // (fp32 sources only) three such planes, PLANE elements apart, hold hi / mid / lo.
-template <int SRC, int ROWS, int NT, int SPLIT, int PLANE>
-__device__ __forceinline__ void hstore(const HStage<SRC, ROWS, NT>& st, uint16_t* __restrict__ lds, int tid) {
+template <int SRC, int ROWS, int NT, int HK>
+constexpr int hstage_items() {
+  return SRC == SRC_F32_KC ? ROWS * (HK / 4) / NT
+       : SRC == SRC_BF16_KC ? (ROWS * (HK / 8) + NT - 1) / NT
+       : SRC == SRC_F32_RC ? ROWS * HK / 8 / NT
+                           : (ROWS * HK / 16 + NT - 1) / NT;
+}
+
+// item q of the staged tile (one global load's worth per thread)
+template <int SRC, int ROWS, int NT, int SPLIT, int PLANE, int HK>
+__device__ __forceinline__ void hstore_item(const HStage<SRC, ROWS, NT, HK>& st, int q,
+                                            uint16_t* __restrict__ lds, int tid) {
+  constexpr int HSTRIDE = HK + 8;
   static_assert(SPLIT == 1 || SRC == SRC_F32_KC || SRC == SRC_F32_RC, "only fp32 sources are split");
+  const int f = tid + NT * q;
   if constexpr (SRC == SRC_F32_KC) {
+    uint16_t* dst = lds + (f / (HK / 4)) * HSTRIDE + 4 * (f % (HK / 4));
+    if constexpr (SPLIT == 1) {
+      uint2 w;
+      w.x = pack_bf16(st.v[q].x, st.v[q].y);
+      w.y = pack_bf16(st.v[q].z, st.v[q].w);
+      *reinterpret_cast<uint2*>(dst) = w;
+    } else {
+      uint32_t a[3], b[3];
+      split3_pack(st.v[q].x, st.v[q].y, a);
+      split3_pack(st.v[q].z, st.v[q].w, b);
 #pragma unroll
-    for (int q = 0; q < ROWS * 8 / NT; ++q) {
-      const int f = tid + NT * q;
-      uint16_t* dst = lds + (f >> 3) * HSTRIDE + 4 * (f & 7);
-      if constexpr (SPLIT == 1) {
-        uint2 w;
-        w.x = pack_bf16(st.v[q].x, st.v[q].y);
-        w.y = pack_bf16(st.v[q].z, st.v[q].w);
-        *reinterpret_cast<uint2*>(dst) = w;
-      } else {
-        uint32_t a[3], b[3];
-        split3_pack(st.v[q].x, st.v[q].y, a);
-        split3_pack(st.v[q].z, st.v[q].w, b);
-#pragma unroll
-        for (int pl = 0; pl < 3; ++pl) *reinterpret_cast<uint2*>(dst + pl * PLANE) = make_uint2(a[pl], b[pl]);
-      }
+      for (int pl = 0; pl < 3; ++pl) *reinterpret_cast<uint2*>(dst + pl * PLANE) = make_uint2(a[pl], b[pl]);
     }
   } else if constexpr (SRC == SRC_BF16_KC) {
-#pragma unroll
-    for (int q = 0; q < ROWS * 4 / NT; ++q) {
-      const int f = tid + NT * q;
-      *reinterpret_cast<uint4*>(lds + (f >> 2) * HSTRIDE + 8 * (f & 3)) = st.v[q];
-    }
+    if (f < ROWS * (HK / 8))
+      *reinterpret_cast<uint4*>(lds + (f / (HK / 8)) * HSTRIDE + 8 * (f % (HK / 8))) = st.v[q];
   } else if constexpr (SRC == SRC_F32_RC) {
+    const int kp = (f & 3) + 4 * (f / ROWS), rq = (f >> 2) % (ROWS / 4);
+    const float lo[4] = {st.v[q][0].x, st.v[q][0].y, st.v[q][0].z, st.v[q][0].w};
+    const float hi[4] = {st.v[q][1].x, st.v[q][1].y, st.v[q][1].z, st.v[q][1].w};
+    const int rot = (rq >> 1) & 3;
 #pragma unroll
-    for (int q = 0; q < 4 * ROWS / NT; ++q) {
-      const int f = tid + NT * q;
-      const int kp = (f & 3) + 4 * (f / ROWS), rq = (f >> 2) % (ROWS / 4);
-      const float lo[4] = {st.v[q][0].x, st.v[q][0].y, st.v[q][0].z, st.v[q][0].w};
-      const float hi[4] = {st.v[q][1].x, st.v[q][1].y, st.v[q][1].z, st.v[q][1].w};
-      const int rot = (rq >> 1) & 3;
+    for (int e = 0; e < 4; ++e) {
+      const int ee = (e + rot) & 3;
+      float l = lo[0], h = hi[0];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int ee = (e + rot) & 3;
-        float l = lo[0], h = hi[0];
+      for (int c = 1; c < 4; ++c) { if (ee == c) { l = lo[c]; h = hi[c]; } }
+      uint16_t* dst = lds + (4 * rq + ee) * HSTRIDE + 2 * kp;
+      if constexpr (SPLIT == 1) {
+        *reinterpret_cast<uint32_t*>(dst) = pack_bf16(l, h);
+      } else {
+        uint32_t w[3];
+        split3_pack(l, h, w);
 #pragma unroll
-        for (int c = 1; c < 4; ++c) { if (ee == c) { l = lo[c]; h = hi[c]; } }
-        uint16_t* dst = lds + (4 * rq + ee) * HSTRIDE + 2 * kp;
-        if constexpr (SPLIT == 1) {
-          *reinterpret_cast<uint32_t*>(dst) = pack_bf16(l, h);
-        } else {
-          uint32_t w[3];
-          split3_pack(l, h, w);
-#pragma unroll
-          for (int pl = 0; pl < 3; ++pl) *reinterpret_cast<uint32_t*>(dst + pl * PLANE) = w[pl];
-        }
+        for (int pl = 0; pl < 3; ++pl) *reinterpret_cast<uint32_t*>(dst + pl * PLANE) = w[pl];
       }
     }
   } else {
+    if (f < ROWS * HK / 16) {
+      const int kp = (f & 3) + 4 * (f / (ROWS / 2)), rq = (f >> 2) % (ROWS / 8);
+      const uint32_t lo[4] = {st.v[q][0].x, st.v[q][0].y, st.v[q][0].z, st.v[q][0].w};
+      const uint32_t hi[4] = {st.v[q][1].x, st.v[q][1].y, st.v[q][1].z, st.v[q][1].w};
+      const int rot = rq & 7;
 #pragma unroll
-    for (int q = 0; q < (2 * ROWS + NT - 1) / NT; ++q) {
-      const int f = tid + NT * q;
-      if (f < 2 * ROWS) {
-        const int kp = (f & 3) + 4 * (f / (ROWS / 2)), rq = (f >> 2) % (ROWS / 8);
-        const uint32_t lo[4] = {st.v[q][0].x, st.v[q][0].y, st.v[q][0].z, st.v[q][0].w};
-        const uint32_t hi[4] = {st.v[q][1].x, st.v[q][1].y, st.v[q][1].z, st.v[q][1].w};
-        const int rot = rq & 7;
+      for (int e = 0; e < 8; ++e) {
+        const int ee = (e + rot) & 7;
+        uint32_t l = lo[0], h = hi[0];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const int ee = (e + rot) & 7;
-          uint32_t l = lo[0], h = hi[0];
-#pragma unroll
-          for (int c = 1; c < 4; ++c) { if ((ee >> 1) == c) { l = lo[c]; h = hi[c]; } }
-          const uint32_t sh = 16u * (ee & 1);
-          const uint32_t w = ((l >> sh) & 0xffffu) | (((h >> sh) & 0xffffu) << 16);
-          *reinterpret_cast<uint32_t*>(lds + (8 * rq + ee) * HSTRIDE + 2 * kp) = w;
-        }
+        for (int c = 1; c < 4; ++c) { if ((ee >> 1) == c) { l = lo[c]; h = hi[c]; } }
+        const uint32_t sh = 16u * (ee & 1);
+        const uint32_t w = ((l >> sh) & 0xffffu) | (((h >> sh) & 0xffffu) << 16);
+        *reinterpret_cast<uint32_t*>(lds + (8 * rq + ee) * HSTRIDE + 2 * kp) = w;
       }
     }
   }
+}
+
+template <int SRC, int ROWS, int NT, int SPLIT, int PLANE, int HK>
+__device__ __forceinline__ void hstore(const HStage<SRC, ROWS, NT, HK>& st, uint16_t* __restrict__ lds, int tid) {
+#pragma unroll
+  for (int q = 0; q < hstage_items<SRC, ROWS, NT, HK>(); ++q)
+    hstore_item<SRC, ROWS, NT, SPLIT, PLANE, HK>(st, q, lds, tid);
 }
 
 // TBM x TBN workgroup tile, WGM x WGN wavefronts, each owning (TBM/WGM) x (TBN/WGN).
 // SPLIT = 3: both operands are fp32 in memory and are multiplied as sums of three bf16 values;
 // the six partial products of weight >= 2^-16 are accumulated (hi*hi, hi*mid, mid*hi, hi*lo,
 // mid*mid, lo*hi), which leaves a relative error below 2^-24 per product of two elements, the
-// rounding of one fp32 multiplication.  The three planes of a stage share one LDS buffer, so
-// the stage is single-buffered with two barriers.
+// rounding of one fp32 multiplication.  A stage holds 16 k-values of all three planes of both
+// operands; the conversion of the next stage (plain ALU work) overlaps with the products of
+// the wavefronts that are still multiplying.
 template <int ASRC, int BSRC, int MODE, int TBM, int TBN, int WGM, int WGN, int SPLIT>
 __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 : 2) : 1) void gemm_bf16_kernel(HGemmParams g) {
   constexpr int NT = 64 * WGM * WGN;
   constexpr int WM = TBM / WGM, WN = TBN / WGN, MI = WM / 32, NJ = WN / 32;
-  constexpr int NBUF = SPLIT == 1 ? 2 : 1;
+  constexpr int HK = hk_of(SPLIT), HSTRIDE = HK + 8;
   constexpr int PA = TBM * HSTRIDE, PB = TBN * HSTRIDE;          // elements per plane
-  __shared__ __attribute__((aligned(16))) uint16_t lds_a[NBUF][SPLIT * PA];
-  __shared__ __attribute__((aligned(16))) uint16_t lds_b[NBUF][SPLIT * PB];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_a[2][SPLIT * PA];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_b[2][SPLIT * PB];
 
   const int xcd = blockIdx.x & 7;
   const int slot = blockIdx.x >> 3;
@@ -479,27 +488,27 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  const int nchunks = (g.K + HBK - 1) / HBK;
-  HStage<ASRC, TBM, NT> sa;
-  HStage<BSRC, TBN, NT> sb;
-  hload<ASRC, MODE, TBM, NT>(sa, A, g.lda, m0, 0, g.M, g.K, tid);
-  hload<BSRC, MODE, TBN, NT>(sb, B, g.ldb, n0, 0, g.N, g.K, tid);
-  hstore<ASRC, TBM, NT, SPLIT, PA>(sa, lds_a[0], tid);
-  hstore<BSRC, TBN, NT, SPLIT, PB>(sb, lds_b[0], tid);
-  __syncthreads();
+  const int nchunks = (g.K + HK - 1) / HK;
+  HStage<ASRC, TBM, NT, HK> sa;
+  HStage<BSRC, TBN, NT, HK> sb;
+  hload<ASRC, MODE, TBM, NT, HK>(sa, A, g.lda, m0, 0, g.M, g.K, tid);
+  hload<BSRC, MODE, TBN, NT, HK>(sb, B, g.ldb, n0, 0, g.N, g.K, tid);
+  hstore<ASRC, TBM, NT, SPLIT, PA, HK>(sa, lds_a[0], tid);
+  hstore<BSRC, TBN, NT, SPLIT, PB, HK>(sb, lds_b[0], tid);
+  union Frag { uint4 u; bf16x8 v; };
 
-  for (int c = 0; c < nchunks; ++c) {
-    const int cur = (NBUF == 2) ? (c & 1) : 0;
-    if (c + 1 < nchunks) {
-      hload<ASRC, MODE, TBM, NT>(sa, A, g.lda, m0, (c + 1) * HBK, g.M, g.K, tid);
-      hload<BSRC, MODE, TBN, NT>(sb, B, g.ldb, n0, (c + 1) * HBK, g.N, g.K, tid);
-    }
-    const uint16_t* __restrict__ as = lds_a[cur];
-    const uint16_t* __restrict__ bs = lds_b[cur];
+  if constexpr (SPLIT == 1) {
+    __syncthreads();
+    for (int c = 0; c < nchunks; ++c) {
+      const int cur = c & 1;
+      if (c + 1 < nchunks) {
+        hload<ASRC, MODE, TBM, NT, HK>(sa, A, g.lda, m0, (c + 1) * HK, g.M, g.K, tid);
+        hload<BSRC, MODE, TBN, NT, HK>(sb, B, g.ldb, n0, (c + 1) * HK, g.N, g.K, tid);
+      }
+      const uint16_t* __restrict__ as = lds_a[cur];
+      const uint16_t* __restrict__ bs = lds_b[cur];
 #pragma unroll
-    for (int h = 0; h < HBK / 16; ++h) {
-      union Frag { uint4 u; bf16x8 v; };
-      if constexpr (SPLIT == 1) {
+      for (int h = 0; h < HK / 16; ++h) {
         Frag fa[MI], fb[NJ];
 #pragma unroll
         for (int i = 0; i < MI; ++i)
@@ -512,37 +521,68 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
 #pragma unroll
           for (int j = 0; j < NJ; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i].v, fb[j].v, acc[i][j], 0, 0, 0);
-      } else {
-        // all planes of A stay in registers; the planes of B are fetched one at a time, the
-        // smallest first, each multiplied with the planes of A that keep the weight >= 2^-16
-        Frag fa[MI][3];
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-          for (int pl = 0; pl < 3; ++pl)
-            fa[i][pl].u = *reinterpret_cast<const uint4*>(as + pl * PA + (wm + 32 * i + li) * HSTRIDE + 16 * h + 8 * lg);
-#pragma unroll
-        for (int pb = 2; pb >= 0; --pb) {
-          Frag fb[NJ];
-#pragma unroll
-          for (int j = 0; j < NJ; ++j)
-            fb[j].u = *reinterpret_cast<const uint4*>(bs + pb * PB + (wn + 32 * j + li) * HSTRIDE + 16 * h + 8 * lg);
-#pragma unroll
-          for (int pa = 2 - pb; pa >= 0; --pa)
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-              for (int j = 0; j < NJ; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i][pa].v, fb[j].v, acc[i][j], 0, 0, 0);
-        }
       }
+      if (c + 1 < nchunks) {
+        hstore<ASRC, TBM, NT, SPLIT, PA, HK>(sa, lds_a[cur ^ 1], tid);
+        hstore<BSRC, TBN, NT, SPLIT, PB, HK>(sb, lds_b[cur ^ 1], tid);
+      }
+      __syncthreads();
     }
-    if (c + 1 < nchunks) {
-      if constexpr (NBUF == 1) __syncthreads();              // every wavefront is done reading the stage
-      hstore<ASRC, TBM, NT, SPLIT, PA>(sa, lds_a[NBUF == 2 ? (cur ^ 1) : 0], tid);
-      hstore<BSRC, TBN, NT, SPLIT, PB>(sb, lds_b[NBUF == 2 ? (cur ^ 1) : 0], tid);
+  } else {
+    // Three stages in flight: stage c is multiplied from LDS, stage c + 1 (loaded one iteration
+    // ago, so already in registers) is split and written to the other LDS buffer in pieces
+    // placed between the groups of matrix instructions, so that the plain ALU work runs while
+    // the matrix pipe is busy, and the global loads of stage c + 2 are issued.
+    static_assert(HK == 16, "one matrix-instruction step per stage");
+    constexpr int IA = hstage_items<ASRC, TBM, NT, HK>(), IB = hstage_items<BSRC, TBN, NT, HK>();
+    static_assert(IA + IB <= 6, "one conversion slot per partial product");
+    if (nchunks > 1) {
+      hload<ASRC, MODE, TBM, NT, HK>(sa, A, g.lda, m0, HK, g.M, g.K, tid);
+      hload<BSRC, MODE, TBN, NT, HK>(sb, B, g.ldb, n0, HK, g.N, g.K, tid);
     }
     __syncthreads();
+    for (int c = 0; c < nchunks; ++c) {
+      const int cur = c & 1;
+      HStage<ASRC, TBM, NT, HK> na = sa;
+      HStage<BSRC, TBN, NT, HK> nb = sb;
+      if (c + 2 < nchunks) {
+        hload<ASRC, MODE, TBM, NT, HK>(na, A, g.lda, m0, (c + 2) * HK, g.M, g.K, tid);
+        hload<BSRC, MODE, TBN, NT, HK>(nb, B, g.ldb, n0, (c + 2) * HK, g.N, g.K, tid);
+      }
+      const bool conv = c + 1 < nchunks;
+      const uint16_t* __restrict__ as = lds_a[cur];
+      const uint16_t* __restrict__ bs = lds_b[cur];
+      Frag fa[MI][3];
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int pl = 0; pl < 3; ++pl)
+          fa[i][pl].u = *reinterpret_cast<const uint4*>(as + pl * PA + (wm + 32 * i + li) * HSTRIDE + 8 * lg);
+      int slot_id = 0;
+#pragma unroll
+      for (int pb = 2; pb >= 0; --pb) {
+        Frag fb[NJ];
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+          fb[j].u = *reinterpret_cast<const uint4*>(bs + pb * PB + (wn + 32 * j + li) * HSTRIDE + 8 * lg);
+#pragma unroll
+        for (int pa = 2 - pb; pa >= 0; --pa) {
+#pragma unroll
+          for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i][pa].v, fb[j].v, acc[i][j], 0, 0, 0);
+          if (conv) {
+            if (slot_id < IA) hstore_item<ASRC, TBM, NT, SPLIT, PA, HK>(sa, slot_id, lds_a[cur ^ 1], tid);
+            else if (slot_id < IA + IB) hstore_item<BSRC, TBN, NT, SPLIT, PB, HK>(sb, slot_id - IA, lds_b[cur ^ 1], tid);
+          }
+          ++slot_id;
+        }
+      }
+      __syncthreads();
+      sa = na;
+      sb = nb;
+    }
   }
 
 #pragma unroll
@@ -576,7 +616,7 @@ gpd_status_t launch_bf16_t(hipStream_t stream, HGemmParams p, int64_t batch, boo
   // same two workgroup shapes as the fp32 kernel; the large one needs full aligned tiles
   // (the split kernel with a short contraction is dominated by the read-modify-write of its
   // output tile: two small workgroups per CU overlap one's epilogue with the other's products)
-  const bool large = aligned && p.M % 256 == 0 && p.N % 256 == 0 && p.K % HBK == 0 && p.K > 0 &&
+  const bool large = aligned && p.M % 256 == 0 && p.N % 256 == 0 && p.K % hk_of(SPLIT) == 0 && p.K > 0 &&
                      (int64_t)(p.M / 256) * (p.N / 256) * batch >= 256 && (SPLIT == 1 || p.K >= 1024);
   const int tbm = large ? 256 : 128, tbn = large ? 256 : 128;
   p.tiles_m = (p.M + tbm - 1) / tbm;
@@ -594,7 +634,7 @@ gpd_status_t launch_bf16_t(hipStream_t stream, HGemmParams p, int64_t batch, boo
     else
       hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 0, 256, 256, 4, 4, SPLIT>), grid, dim3(1024), 0, stream, p);
   } else {
-    const bool full = aligned && p.M % 128 == 0 && p.N % 128 == 0 && p.K % HBK == 0 && p.K > 0;
+    const bool full = aligned && p.M % 128 == 0 && p.N % 128 == 0 && p.K % hk_of(SPLIT) == 0 && p.K > 0;
     if (full) hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 0, 128, 128, 2, 2, SPLIT>), grid, dim3(256), 0, stream, p);
     else hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 1, 128, 128, 2, 2, SPLIT>), grid, dim3(256), 0, stream, p);
   }
