@@ -31,7 +31,7 @@ PEAK_HBM_GBS = 8000.0             # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the worker-product kernel on the default workload, from the committed
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/coded_matmul_4096_fp32.md):
 # 393672 KiB x 2.0 (copy-kernel calibration) fetched + 262144 KiB written
-GEMM_TRAFFIC_BYTES_CFG1 = (393672 * 2.0 + 262144) * 1024
+GEMM_TRAFFIC_BYTES_CFG1 = (393562 * 2.0 + 262144) * 1024   # FETCH_SIZE x 2.0 + WRITE_SIZE, KiB per launch (profiles/coded_matmul_4096_fp32.md)
 
 
 def cpu_baseline(cfg, n_threads):
@@ -243,8 +243,9 @@ def bench_faults(args, cfg):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10,
+                    help="untimed steps first (the clocks of an idle GPU take some 30 ms of load to settle)")
     ap.add_argument("--config", type=int, default=1,
                     help="workload index: 0/1 coded matmul (1 = headline), 2/3 coded MLP training, "
                          "4 soft-error and node-fault paths")
