@@ -488,6 +488,30 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
+  // Read-modify-write of the output tile (the coded update): with two workgroups of this shape on
+  // a CU there are registers to spare, so the old values are requested before the first stage
+  // and have arrived long before the epilogue needs them.
+  constexpr bool kPrefetchC = SPLIT == 3 && MI * NJ <= 4;
+  float oldc[kPrefetchC ? MI * NJ * 16 : 1];
+  if constexpr (kPrefetchC) {
+    if (g.beta != 0.f) {
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * lg + (v & 3);
+            const int col = n0 + wn + 32 * j + li;
+            oldc[(i * NJ + j) * 16 + v] =
+                (MODE == 0 || (row < g.M && col < g.N)) ? C[(int64_t)row * g.ldc + col] : 0.f;
+          }
+    } else {
+#pragma unroll
+      for (int v = 0; v < MI * NJ * 16; ++v) oldc[v] = 0.f;
+    }
+  }
+
   const int nchunks = (g.K + HK - 1) / HK;
   HStage<ASRC, TBM, NT, HK> sa;
   HStage<BSRC, TBN, NT, HK> sb;
@@ -592,7 +616,10 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
       const int col = n0 + wn + 32 * j + li;
       // with beta != 0 all 16 old values of the block are requested before any is used
       float old[16];
-      if (g.beta != 0.f) {
+      if constexpr (kPrefetchC) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) old[v] = oldc[(i * NJ + j) * 16 + v];
+      } else if (g.beta != 0.f) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * lg + (v & 3);
