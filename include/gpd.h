@@ -47,7 +47,8 @@ typedef enum {
                              Sec. V Algorithm 1 last step); the output is still written    */
   GPD_E_WORKSPACE = 6,    /* workspace missing, too small or misaligned                    */
   GPD_E_DEVICE = 7,       /* HIP error or no GPU                                           */
-  GPD_E_UNSUPPORTED = 8   /* valid request this build has no kernel for                    */
+  GPD_E_UNSUPPORTED = 8,  /* valid request this build has no kernel for                    */
+  GPD_E_VERIFY = 9        /* gpd_verify_decode: the second decoder disagrees                */
 } gpd_status_t;
 
 /* How the worker products are multiplied.
@@ -216,6 +217,34 @@ typedef struct {
 gpd_status_t gpd_locate_nodes(const gpd_plan_t* plan, const float* Ct, const uint8_t* present,
                               void* workspace, size_t workspace_bytes, gpd_node_report_t* report,
                               double* gram /* host [(|S|-K)^2], basis of gpd_host_parity_check; or NULL */);
+
+/* Host-side result of gpd_verify_decode. */
+typedef struct {
+  int32_t status;               /* GPD_OK or GPD_E_VERIFY                                      */
+  int32_t n_checked;            /* element codewords looked at                                 */
+  int32_t n_value_mismatch;     /* of those, how many have a decoded value that disagrees      */
+  int32_t locations_agree;      /* 1 = the second node search names exactly the nodes in `bad` */
+  uint8_t bad[GPD_MAX_P];       /* nodes the second search found erroneous                     */
+  double max_ratio;             /* max |difference| / tolerance over the values compared       */
+} gpd_verify_report_t;
+
+/* Verification step for decoding errors (Sec. VII under error model 2; "crosscheck" item of the
+ * complexity appendix): n_check pre-decided values of the decoded result (0 = P of them; element
+ * t of the block is floor(t * elements / n_check)) are recomputed by a second decoder that shares
+ * nothing with gpd_decode's kernels, and compared; the list of nodes found erroneous is compared
+ * too.  The second decoder gathers the n_check element codewords and the matching entries of C,
+ * and works on the host in fp64: node search on the sampled codewords, then least squares over
+ * the present nodes it leaves.  A value disagrees if it differs by more than
+ * 2^-20 (a_main + a_check) ||z||, a_* = norm of the decoding row used by either decoder.
+ *   present, mode, bad: what the main decode used (bad: host uint8[P] nodes it left out as
+ *                       erroneous, or NULL).
+ *   C, ldc: the decoded result under test (device).
+ * Returns GPD_E_VERIFY (also in report->status) on any disagreement: the caller restores its
+ * last checkpoint.  The call waits for the stream.  workspace as for gpd_decode. */
+gpd_status_t gpd_verify_decode(const gpd_plan_t* plan, const float* Ct, const uint8_t* present,
+                               int32_t mode, const uint8_t* bad, const float* C, int64_t ldc,
+                               int32_t n_check, void* workspace, size_t workspace_bytes,
+                               gpd_verify_report_t* report);
 
 /* ------------------------------------------------------------------ coded DNN layer */
 

@@ -676,6 +676,78 @@ def decode_nodes(Ct: np.ndarray, plan: Plan, present=None, mode: str = "lsq_all"
     return C, rep
 
 
+def check_positions(n_codewords: int, n_check: int) -> np.ndarray:
+    """The pre-decided element positions of the verification step: n_check positions spread
+    evenly over the block, position t = floor(t * n_codewords / n_check)."""
+    n_check = min(n_check, n_codewords)
+    return (np.arange(n_check, dtype=np.int64) * n_codewords) // max(n_check, 1)
+
+
+@dataclass
+class VerifyReport:
+    status: str = "ok"                       # 'ok' | 'mismatch'
+    n_checked: int = 0
+    n_value_mismatch: int = 0
+    locations_agree: bool = True
+    bad: tuple = ()                          # nodes the independent search found erroneous
+    max_ratio: float = 0.0                   # max |difference| / tolerance
+
+
+def verify_decode(Ct: np.ndarray, plan: Plan, C: np.ndarray, present=None, mode: str = "first_k",
+                  bad=(), n_check: int = 0, rho: float = 2.0 ** -12, abs_floor: float = 0.0) -> VerifyReport:
+    """Verification step for decoding errors (Sec. VII, Error Model 2, and the crosscheck item of
+    the complexity appendix): P pre-decided values of the decoded result are recomputed by a
+    second, independent decoder and compared, and the vector saying which nodes were found
+    erroneous is compared as well.  Here the second decoder works in fp64 on the P sampled
+    element codewords only: node search on those codewords (locate_nodes), then least squares
+    over the present nodes it leaves.  A decoded value disagrees if it differs by more than
+    2^-20 (a_main + a_check) ||z||, a_* the norms of the decoding rows used by the two decoders
+    (`mode` over `present` without `bad` for the main one)."""
+    Ct = np.asarray(Ct, dtype=np.float64)
+    P, rows, cols = Ct.shape
+    ncw = rows * cols
+    n_check = P if n_check <= 0 else n_check
+    pos = check_positions(ncw, n_check)
+    rep = VerifyReport(n_checked=len(pos))
+    pres = np.ones(P, dtype=bool) if present is None else np.asarray(present).astype(bool)
+    Z = Ct.reshape(P, ncw)[:, pos]                               # [P, n_check]
+    nrep = locate_nodes(Z.reshape(P, len(pos), 1), plan.points, plan.K, pres, rho, abs_floor)
+    rep.bad = nrep.bad
+    rep.locations_agree = nrep.status != "failed" and tuple(sorted(int(b) for b in bad)) == nrep.bad
+    main = pres.copy()
+    main[list(bad)] = False
+    check = pres.copy()
+    check[list(nrep.bad)] = False
+    S_main = np.flatnonzero(main)
+    if mode == "first_k":
+        S_main = S_main[:plan.K]
+    S_chk = np.flatnonzero(check)
+    D_main = np.linalg.pinv(vandermonde(plan.points[S_main], plan.K))
+    D_chk = np.linalg.pinv(vandermonde(plan.points[S_chk], plan.K))
+    C = np.asarray(C, dtype=np.float64)
+    for t, e in enumerate(pos):
+        r_, c_ = divmod(int(e), cols)
+        z = np.where(np.isfinite(Z[:, t]), Z[:, t], 0.0)
+        znorm = float(np.linalg.norm(z[S_chk]))
+        worst = 0.0
+        for i in range(plan.m):
+            for k in range(plan.d):
+                ex = int(plan.eC[i, k])
+                want = float(D_chk[ex] @ z[S_chk])
+                tol = 2.0 ** -20 * (np.linalg.norm(D_main[ex]) + np.linalg.norm(D_chk[ex])) * znorm
+                got = C[i * rows + r_, k * cols + c_]
+                ratio = abs(got - want) / tol if tol > 0 else (0.0 if got == want else np.inf)
+                if not np.isfinite(got):
+                    ratio = np.inf
+                worst = max(worst, ratio)
+        rep.max_ratio = max(rep.max_ratio, worst)
+        if worst > 1.0:
+            rep.n_value_mismatch += 1
+    if rep.n_value_mismatch or not rep.locations_agree:
+        rep.status = "mismatch"
+    return rep
+
+
 def weight_polynomial_terms(lp: LayerPlan) -> int:
     """Number of coefficients of W~(b) after the substitution: max exponent + 1 = mn
     (footnote on regeneration, Sec. VII)."""

@@ -6,4 +6,5 @@ from .binding import (GpdError, Layer, Plan, Report, load_library, gpd_coded_lay
                       gpd_layer_create, gpd_layer_decode_weights, gpd_layer_encode_weights, gpd_plan,
                       gpd_sigmoid_bwd, gpd_sigmoid_fwd, gpd_version, gpd_worker_products,
                       NodeReport, gpd_locate_nodes, gpd_layer_locate_nodes, gpd_layer_regenerate,
-                      gpd_layer_project, gpd_host_parity_check, gpd_host_locate_nodes)
+                      gpd_layer_project, gpd_host_parity_check, gpd_host_locate_nodes,
+                      VerifyReport, gpd_verify_decode)

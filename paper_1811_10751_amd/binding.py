@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libgpd.so")
 
 GPD_MAX_P = 64
 GPD_OK, GPD_E_INVALID, GPD_E_SHAPE, GPD_E_POINTS, GPD_E_TOO_FEW, GPD_E_DECODE_FAIL, \
-    GPD_E_WORKSPACE, GPD_E_DEVICE, GPD_E_UNSUPPORTED = range(9)
+    GPD_E_WORKSPACE, GPD_E_DEVICE, GPD_E_UNSUPPORTED, GPD_E_VERIFY = range(10)
 GPD_F32, GPD_BF16, GPD_F32_SPLIT = 0, 1, 2
 GPD_SUB_AUTO, GPD_SUB_U_VN, GPD_SUB_V_UM = 0, 1, 2
 GPD_DEC_FIRST_K, GPD_DEC_LSQ_ALL = 0, 1
@@ -26,7 +26,7 @@ GPD_CORRECT_NONE, GPD_CORRECT_ELEMENTS, GPD_CORRECT_NODES = 0, 1, 2
 GPD_STACK_WEIGHTS, GPD_STACK_FORWARD, GPD_STACK_BACKWARD = 0, 1, 2
 
 STATUS_NAMES = ["OK", "E_INVALID", "E_SHAPE", "E_POINTS", "E_TOO_FEW", "E_DECODE_FAIL",
-                "E_WORKSPACE", "E_DEVICE", "E_UNSUPPORTED"]
+                "E_WORKSPACE", "E_DEVICE", "E_UNSUPPORTED", "E_VERIFY"]
 
 EXPORTS = [
     "gpd_plan", "gpd_plan_info", "gpd_plan_tables", "gpd_plan_destroy", "gpd_encode",
@@ -35,13 +35,13 @@ EXPORTS = [
     "gpd_layer_workspace_view", "gpd_layer_destroy", "gpd_sigmoid_fwd", "gpd_sigmoid_bwd", "gpd_l2_delta",
     "gpd_host_code", "gpd_host_decode_matrices", "gpd_last_error", "gpd_version",
     "gpd_locate_nodes", "gpd_layer_locate_nodes", "gpd_layer_regenerate", "gpd_layer_project",
-    "gpd_host_parity_check", "gpd_host_locate_nodes",
+    "gpd_host_parity_check", "gpd_host_locate_nodes", "gpd_verify_decode",
 ]
 
 
 class GpdError(RuntimeError):
     def __init__(self, status: int, msg: str):
-        super().__init__(f"gpd status {STATUS_NAMES[status] if 0 <= status < 9 else status}: {msg}")
+        super().__init__(f"gpd status {STATUS_NAMES[status] if 0 <= status < 10 else status}: {msg}")
         self.status = status
 
 
@@ -73,6 +73,11 @@ class _NodeReport(C.Structure):
                 ("exhaustive", C.c_int32), ("bad", C.c_uint8 * GPD_MAX_P), ("wild", C.c_uint8 * GPD_MAX_P),
                 ("energy", C.c_double), ("syndrome_energy", C.c_double), ("residual", C.c_double),
                 ("threshold", C.c_double)]
+
+
+class _VerifyReport(C.Structure):
+    _fields_ = [("status", C.c_int32), ("n_checked", C.c_int32), ("n_value_mismatch", C.c_int32),
+                ("locations_agree", C.c_int32), ("bad", C.c_uint8 * GPD_MAX_P), ("max_ratio", C.c_double)]
 
 
 class _LayerDesc(C.Structure):
@@ -128,6 +133,7 @@ def load_library():
     lib.gpd_host_parity_check.argtypes = [i32, i32, vp, vp, vp, C.POINTER(i32)]
     lib.gpd_host_locate_nodes.argtypes = [i32, i32, vp, vp, vp, C.c_double, i64, C.c_double, C.c_double,
                                           vp, C.POINTER(_NodeReport)]
+    lib.gpd_verify_decode.argtypes = [vp, vp, vp, i32, vp, vp, i64, i32, vp, sz, C.POINTER(_VerifyReport)]
     lib.gpd_last_error.restype = C.c_char_p
     lib.gpd_version.restype = C.c_char_p
     for name in EXPORTS:
@@ -499,6 +505,45 @@ def gpd_locate_nodes(plan: Plan, Ct, present=None, workspace=None, want_gram=Fal
     _check(st, ok=(GPD_OK, GPD_E_DECODE_FAIL))
     out = _read_node_report(rep, plan.P)
     return (out, gram) if want_gram else out
+
+
+@dataclass
+class VerifyReport:
+    status: int = 0
+    n_checked: int = 0
+    n_value_mismatch: int = 0
+    locations_agree: bool = True
+    bad: tuple = ()
+    max_ratio: float = 0.0
+
+
+def gpd_verify_decode(plan: Plan, Ct, C_dec, present=None, mode=GPD_DEC_FIRST_K, bad=(), n_check=0,
+                      workspace=None) -> VerifyReport:
+    """Second, independent decode of n_check (default P) pre-decided values of C_dec; status
+    GPD_E_VERIFY in the report on disagreement."""
+    import torch
+    lib = load_library()
+    _require_f32_cuda(Ct, "Ct")
+    _require_f32_cuda(C_dec, "C")
+    sh = (plan.P, plan.N1 // plan.m, plan.Nc // plan.d)
+    if tuple(Ct.shape) != sh or not Ct.is_contiguous():
+        raise ValueError("Ct does not match the plan")
+    if tuple(C_dec.shape) != (plan.N1, plan.Nc) or C_dec.stride(1) != 1:
+        raise ValueError("C does not match the plan")
+    if workspace is None:
+        workspace = torch.empty(max(plan.workspace_bytes, 1 << 20), dtype=torch.uint8, device=Ct.device)
+    pres = _present_array(present, plan.P)
+    mask = None
+    if bad is not None and len(tuple(bad)):
+        mask = np.zeros(plan.P, dtype=np.uint8)
+        for p in bad:
+            mask[int(p)] = 1
+    rep = _VerifyReport()
+    st = lib.gpd_verify_decode(plan.handle, _ptr(Ct), _ptr(pres), mode, _ptr(mask), _ptr(C_dec), C_dec.stride(0),
+                               n_check, workspace.data_ptr(), workspace.numel(), C.byref(rep))
+    _check(st, ok=(GPD_OK, GPD_E_VERIFY))
+    return VerifyReport(rep.status, rep.n_checked, rep.n_value_mismatch, bool(rep.locations_agree),
+                        tuple(p for p in range(plan.P) if rep.bad[p]), rep.max_ratio)
 
 
 def gpd_layer_locate_nodes(layer: Layer, which, stack, present=None, want_gram=False):

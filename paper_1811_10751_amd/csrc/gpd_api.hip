@@ -503,6 +503,20 @@ extern "C" gpd_status_t gpd_locate_nodes(const gpd_plan_t* plc, const float* Ct,
                           pl->rho, pl->abs_floor, workspace, workspace_bytes, report, gram);
 }
 
+extern "C" gpd_status_t gpd_verify_decode(const gpd_plan_t* plc, const float* Ct, const uint8_t* present,
+                                          int32_t mode, const uint8_t* bad, const float* C, int64_t ldc,
+                                          int32_t n_check, void* workspace, size_t workspace_bytes,
+                                          gpd_verify_report_t* report) {
+  gpd_plan_t* pl = const_cast<gpd_plan_t*>(plc);
+  if (!pl || !report) return fail(GPD_E_INVALID, "gpd_verify_decode: null argument");
+  DecodeJob job;
+  job.pts = &pl->code.pts; job.K = pl->code.K; job.useful = pl->code.eC;
+  job.grid_r = pl->code.m; job.grid_c = pl->code.d;
+  job.bh = pl->ahC; job.bw = pl->awC;
+  job.rho = pl->rho; job.abs_floor = pl->abs_floor;
+  return run_verify(pl->stream, job, Ct, present, mode, bad, C, ldc, n_check, workspace, workspace_bytes, report);
+}
+
 extern "C" gpd_status_t gpd_decode(const gpd_plan_t* plc, const float* Ct, const uint8_t* present,
                                    int32_t mode, int32_t correct_errors, float* C, int64_t ldc,
                                    void* workspace, size_t workspace_bytes, gpd_report_t* report) {

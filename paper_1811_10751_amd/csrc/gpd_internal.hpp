@@ -231,6 +231,12 @@ gpd_status_t run_locate_nodes(hipStream_t stream, TableRing* ring, const std::ve
                               double rho, double abs_floor, void* workspace, size_t workspace_bytes,
                               gpd_node_report_t* rep, double* gram_out = nullptr);
 
+// Verification step: gathers n_check element codewords of Zt and the matching entries of the
+// decoded grid, decodes them again on the host in fp64 and compares (see gpd_verify_decode).
+gpd_status_t run_verify(hipStream_t stream, const DecodeJob& job, const float* Zt, const uint8_t* present,
+                        int mode, const uint8_t* bad, const float* out, int64_t ld_out, int n_check,
+                        void* workspace, size_t workspace_bytes, gpd_verify_report_t* rep);
+
 // decode for correct == GPD_CORRECT_NODES: run_locate_nodes, then run_decode without the nodes
 // found erroneous; fills the gpd_report_t as documented for gpd_decode.
 gpd_status_t run_decode_nodes(hipStream_t stream, TableRing* ring, const DecodeJob& job, const float* Zt,

@@ -381,4 +381,155 @@ gpd_status_t run_locate_nodes(hipStream_t stream, TableRing* ring, const std::ve
   return GPD_OK;
 }
 
+// ---------------------------------------------------------------- verification step
+
+namespace {
+
+// z[t][p] = Zt[p][pos_t] for every node p; c[t][q] = entry of output block q at element pos_t
+__global__ void gather_check_kernel(const float* __restrict__ Zt, int P, int64_t ncw, int n_check,
+                                    const float* __restrict__ out, int64_t ld_out, int grid_r, int grid_c,
+                                    int64_t bh, int64_t bw, float* __restrict__ z, float* __restrict__ c) {
+  const int t = blockIdx.x;
+  if (t >= n_check) return;
+  const int64_t pos = ((int64_t)t * ncw) / n_check;
+  const int64_t r = pos / bw, col = pos - r * bw;
+  for (int p = threadIdx.x; p < P; p += blockDim.x) z[(int64_t)t * P + p] = Zt[(int64_t)p * ncw + pos];
+  const int nq = grid_r * grid_c;
+  for (int q = threadIdx.x; q < nq; q += blockDim.x) {
+    const int i = q / grid_c, k = q - i * grid_c;
+    c[(int64_t)t * nq + q] = out[((int64_t)i * bh + r) * ld_out + (int64_t)k * bw + col];
+  }
+}
+
+}  // namespace
+
+gpd_status_t run_verify(hipStream_t stream, const DecodeJob& job, const float* Zt, const uint8_t* present,
+                        int mode, const uint8_t* bad, const float* out, int64_t ld_out, int n_check,
+                        void* workspace, size_t workspace_bytes, gpd_verify_report_t* rep) {
+  if (!rep) return fail(GPD_E_INVALID, "verify: null report");
+  std::memset(rep, 0, sizeof(*rep));
+  if (mode != GPD_DEC_FIRST_K && mode != GPD_DEC_LSQ_ALL) return fail(GPD_E_INVALID, "verify: bad mode");
+  if (!job.out_cols.empty()) return fail(GPD_E_UNSUPPORTED, "verify: padded output grids are not supported");
+  const int P = (int)job.pts->size(), K = job.K;
+  const int64_t ncw = job.bh * job.bw;
+  const int nq = job.grid_r * job.grid_c;
+  if (n_check <= 0) n_check = P;
+  if (n_check > 4096) return fail(GPD_E_INVALID, "verify: at most 4096 values are checked");
+  if ((int64_t)n_check > ncw) n_check = (int)ncw;
+  rep->locations_agree = 1;
+  if (ncw == 0) return GPD_OK;
+  if (!Zt || !out) return fail(GPD_E_INVALID, "verify: null buffer");
+  if (ld_out < job.grid_c * job.bw) return fail(GPD_E_SHAPE, "verify: output leading dimension too small");
+  const size_t need = 512 + sizeof(float) * (size_t)n_check * (P + nq);
+  if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))
+    return fail(GPD_E_WORKSPACE, "verify: workspace of %zu aligned bytes needed", need);
+
+  std::vector<int> S, S_main;
+  for (int p = 0; p < P; ++p)
+    if (!present || present[p]) {
+      S.push_back(p);
+      if (!bad || !bad[p]) S_main.push_back(p);
+    }
+  if ((int)S_main.size() < K) return fail(GPD_E_TOO_FEW, "%d responses left, %d needed", (int)S_main.size(), K);
+
+  float* d_z = (float*)((char*)workspace + 512);
+  float* d_c = d_z + (size_t)n_check * P;
+  hipLaunchKernelGGL(gather_check_kernel, dim3(n_check), dim3(64), 0, stream, Zt, P, ncw, n_check, out, ld_out,
+                     job.grid_r, job.grid_c, job.bh, job.bw, d_z, d_c);
+  GPD_HIP(hipGetLastError());
+  std::vector<float> hz((size_t)n_check * P), hc((size_t)n_check * nq);
+  GPD_HIP(hipMemcpyAsync(hz.data(), d_z, sizeof(float) * hz.size(), hipMemcpyDeviceToHost, stream));
+  GPD_HIP(hipMemcpyAsync(hc.data(), d_c, sizeof(float) * hc.size(), hipMemcpyDeviceToHost, stream));
+  GPD_HIP(hipStreamSynchronize(stream));
+
+  // ---- second node search, on the sampled codewords only
+  const int ns = (int)S.size(), r = ns - K;
+  std::vector<double> H;
+  gpd_status_t st = parity_check_host(*job.pts, S, K, &H);
+  if (st != GPD_OK) return st;
+  std::vector<double> Zs((size_t)n_check * ns), G((size_t)r * r, 0.0), y(r);
+  std::vector<char> wild(ns, 0);
+  double energy = 0.0;
+  for (int t = 0; t < n_check; ++t) {
+    for (int q = 0; q < ns; ++q) {
+      double v = hz[(size_t)t * P + S[q]];
+      if (!(std::fabs(v) < 1099511627776.0)) { wild[q] = 1; v = 0.0; }
+      Zs[(size_t)t * ns + q] = v;
+      energy += v * v;
+    }
+    for (int i = 0; i < r; ++i) {
+      double acc = 0.0;
+      for (int q = 0; q < ns; ++q) acc += H[(size_t)i * ns + q] * Zs[(size_t)t * ns + q];
+      y[i] = acc;
+    }
+    for (int i = 0; i < r; ++i)
+      for (int j = 0; j < r; ++j) G[(size_t)i * r + j] += y[i] * y[j];
+  }
+  std::vector<int> forced;
+  for (int q = 0; q < ns; ++q)
+    if (wild[q]) forced.push_back(q);
+  NodeSearchResult res;
+  st = locate_nodes_host(H, r, ns, G, energy, n_check, job.rho, job.abs_floor, forced, &res);
+  if (st != GPD_OK) return st;
+  std::vector<char> chk_bad(P, 0);
+  for (int q : res.bad) { chk_bad[S[q]] = 1; rep->bad[S[q]] = 1; }
+  bool agree = res.status != 2;
+  for (int p = 0; p < P; ++p)
+    if ((!present || present[p]) && ((bad && bad[p]) != (chk_bad[p] != 0))) agree = false;
+  rep->locations_agree = agree ? 1 : 0;
+
+  // ---- second decode of the sampled codewords: least squares over what the search leaves
+  std::vector<int> S_chk;
+  for (int q = 0; q < ns; ++q)
+    if (!chk_bad[S[q]]) S_chk.push_back(S[q]);
+  rep->n_checked = n_check;
+  if ((int)S_chk.size() < K) {
+    rep->status = GPD_E_VERIFY;
+    return fail(GPD_E_VERIFY, "verification: the second node search leaves fewer than K nodes");
+  }
+  std::vector<double> D_main, D_chk;
+  st = decode_matrices(*job.pts, S_main, K, job.useful, mode == GPD_DEC_FIRST_K, &D_main, nullptr);
+  if (st != GPD_OK) return st;
+  st = decode_matrices(*job.pts, S_chk, K, job.useful, false, &D_chk, nullptr);
+  if (st != GPD_OK) return st;
+  const int nm = (int)S_main.size(), nc = (int)S_chk.size();
+  std::vector<double> a_main(nq), a_chk(nq);
+  for (int q = 0; q < nq; ++q) {
+    double s1 = 0.0, s2 = 0.0;
+    for (int x = 0; x < nm; ++x) s1 += D_main[(size_t)q * nm + x] * D_main[(size_t)q * nm + x];
+    for (int x = 0; x < nc; ++x) s2 += D_chk[(size_t)q * nc + x] * D_chk[(size_t)q * nc + x];
+    a_main[q] = std::sqrt(s1); a_chk[q] = std::sqrt(s2);
+  }
+  for (int t = 0; t < n_check; ++t) {
+    double zn = 0.0;
+    std::vector<double> zc(nc);
+    for (int x = 0; x < nc; ++x) {
+      double v = hz[(size_t)t * P + S_chk[x]];
+      if (!std::isfinite(v)) v = 0.0;
+      zc[x] = v; zn += v * v;
+    }
+    zn = std::sqrt(zn);
+    double worst = 0.0;
+    for (int q = 0; q < nq; ++q) {
+      double want = 0.0;
+      for (int x = 0; x < nc; ++x) want += D_chk[(size_t)q * nc + x] * zc[x];
+      const double tol = std::ldexp(1.0, -20) * (a_main[q] + a_chk[q]) * zn;
+      const double got = hc[(size_t)t * nq + q];
+      double ratio;
+      if (!std::isfinite(got)) ratio = INFINITY;
+      else if (tol > 0) ratio = std::fabs(got - want) / tol;
+      else ratio = got == want ? 0.0 : INFINITY;
+      worst = std::max(worst, ratio);
+    }
+    rep->max_ratio = std::max(rep->max_ratio, worst);
+    if (worst > 1.0) rep->n_value_mismatch += 1;
+  }
+  if (rep->n_value_mismatch > 0 || !agree) {
+    rep->status = GPD_E_VERIFY;
+    return fail(GPD_E_VERIFY, "verification: %d of %d checked values disagree, node lists %s", rep->n_value_mismatch,
+                n_check, agree ? "agree" : "differ");
+  }
+  return GPD_OK;
+}
+
 }  // namespace gpd

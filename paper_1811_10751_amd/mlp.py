@@ -19,6 +19,9 @@ class CodedMLP:
                        for l in range(len(sizes) - 1)]
         self.Wts = [None] * len(self.layers)
         self.stream = stream
+        self._ckpt = None
+        self.repaired = []
+        self.restored = False
 
     def encode_weights(self, Ws):
         """Ws: list of float32 CUDA tensors (N_out x N_in).  Done once before training."""
@@ -26,6 +29,18 @@ class CodedMLP:
 
     def decode_weights(self):
         return [B.gpd_layer_decode_weights(L, Wt) for L, Wt in zip(self.layers, self.Wts)]
+
+    def checkpoint(self):
+        """Keeps a copy of the coded weights (Sec. VII, error model 2: the network is checkpointed
+        at regular intervals; here in device memory)."""
+        self._ckpt = [wt.clone() for wt in self.Wts]
+
+    def restore(self):
+        """Puts the last checkpoint back (after a decoding failure or a failed verification)."""
+        if self._ckpt is None:
+            raise RuntimeError("no checkpoint taken")
+        for wt, c in zip(self.Wts, self._ckpt):
+            wt.copy_(c)
 
     def _regenerate(self, l, rep):
         """Regeneration (Sec. VII): the coded weights of the nodes a node-level decode has just
@@ -35,23 +50,38 @@ class CodedMLP:
             B.gpd_layer_regenerate(self.layers[l], self.Wts[l], bad)
         return bad
 
-    def step(self, X, Y, eta, decay=0.0, correct_errors=False, want_report=False, regenerate=False):
+    def step(self, X, Y, eta, decay=0.0, correct_errors=False, want_report=False, regenerate=False,
+             restore_on_failure=False):
         """One training iteration on the mini-batch X (N_0 x batch), labels Y (N_L x batch).
         Returns (network output, per-layer list of (forward report, backward report)).
         regenerate (with correct_errors = GPD_CORRECT_NODES): nodes located as erroneous get
-        their coded weights regenerated right after the decode that found them."""
+        their coded weights regenerated right after the decode that found them.
+        restore_on_failure: a decode that reports errors it cannot locate (GPD_E_DECODE_FAIL)
+        stops the iteration at once and puts the last checkpoint back; the call then returns
+        (None, reports so far) with self.restored set."""
         regenerate = regenerate and int(correct_errors) == B.GPD_CORRECT_NODES
-        want_report = want_report or regenerate
+        want_report = want_report or regenerate or restore_on_failure
         acts = [X]
         reps = []
         self.repaired = []
+        self.restored = False
+
+        def failed(rep):
+            if restore_on_failure and rep is not None and rep.status == B.GPD_E_DECODE_FAIL:
+                self.restore()
+                self.restored = True
+                return True
+            return False
+
         for l, (L, Wt) in enumerate(zip(self.layers, self.Wts)):
             S, rf = B.gpd_coded_layer_step(L, B.GPD_STEP_FORWARD, Wt, acts[-1],
                                            correct_errors=correct_errors, want_report=want_report)
+            reps.append([rf, None])
+            if failed(rf):
+                return None, reps
             if regenerate:
                 self.repaired += [(l, "forward", p) for p in self._regenerate(l, rf)]
             acts.append(B.gpd_sigmoid_fwd(S, stream=self.stream))
-            reps.append([rf, None])
         delta = B.gpd_l2_delta(Y, acts[-1], 2.0 / self.batch, stream=self.stream)
         for l in range(len(self.layers) - 1, -1, -1):
             C, rb = B.gpd_coded_layer_step(self.layers[l], B.GPD_STEP_BACKWARD_UPDATE, self.Wts[l],
@@ -59,6 +89,8 @@ class CodedMLP:
                                            correct_errors=correct_errors, want_report=want_report,
                                            skip_output=(l == 0))
             reps[l][1] = rb
+            if failed(rb):
+                return None, reps
             if regenerate and l > 0:
                 self.repaired += [(l, "backward", p) for p in self._regenerate(l, rb)]
             if l > 0:

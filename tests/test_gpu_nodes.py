@@ -363,3 +363,91 @@ def test_training_with_node_faults_and_regeneration(batch, m, n, P):
         assert rel_fro(to_np(G.gpd_layer_decode_weights(L, Wt)), W_ref) < 1e-3
         rep = G.gpd_layer_locate_nodes(L, G.GPD_STACK_WEIGHTS, Wt)
         assert rep.bad == ()
+
+
+# ----------------------------------------------------------------------------- verification step
+
+
+def test_verification_step_against_the_oracle():
+    N = 128
+    A, B = WL.matmul_inputs(N, N, N, seed=21)
+    plan = G.gpd_plan(N, N, N, 2, 2, 2, 16)
+    opl = O.make_plan(2, 2, 2, 16)
+    At, Bt = G.gpd_encode(plan, to_dev(A), to_dev(B))
+    Ct = G.gpd_worker_products(plan, At, Bt)
+    rows = cols = N // 2
+    pos = O.check_positions(rows * cols, 16)
+    # (1) erasures, both modes: a correct decode passes, with the oracle's ratio
+    present = WL.erasure_trial(4, 16, 5)
+    for mode, oname in ((G.GPD_DEC_FIRST_K, "first_k"), (G.GPD_DEC_LSQ_ALL, "lsq_all")):
+        C, _ = G.gpd_decode(plan, Ct, present=present, mode=mode)
+        rep = G.gpd_verify_decode(plan, Ct, C, present=present, mode=mode)
+        want = O.verify_decode(to_np(Ct), opl, to_np(C), present, oname)
+        assert rep.status == G.GPD_OK and want.status == "ok"
+        assert rep.n_checked == want.n_checked == 16 and rep.locations_agree and rep.bad == ()
+        assert abs(rep.max_ratio - want.max_ratio) <= 1e-6 + 1e-3 * want.max_ratio and rep.max_ratio < 1.0
+    # (2) a wrong value at a checked position is caught, one elsewhere is not
+    C, _ = G.gpd_decode(plan, Ct, present=present, mode=G.GPD_DEC_FIRST_K)
+    r_, c_ = divmod(int(pos[7]), cols)
+    Cbad = C.clone()
+    Cbad[rows + r_, cols + c_] += 100.0                           # block (1, 1); far above the tolerance
+    rep = G.gpd_verify_decode(plan, Ct, Cbad, present=present, mode=G.GPD_DEC_FIRST_K)
+    want = O.verify_decode(to_np(Ct), opl, to_np(Cbad), present, "first_k")
+    assert rep.status == G.GPD_E_VERIFY and rep.n_value_mismatch == want.n_value_mismatch == 1
+    unchecked = [e for e in range(rows * cols) if e not in set(pos.tolist())][0]
+    Cbad = C.clone()
+    Cbad[unchecked // cols, unchecked % cols] += 1.0
+    assert G.gpd_verify_decode(plan, Ct, Cbad, present=present, mode=G.GPD_DEC_FIRST_K).status == G.GPD_OK
+    # (3) erroneous nodes: the decode in node mode passes when it reports its nodes, a naive decode fails,
+    #     a wrong claim about the nodes fails the crosscheck
+    bad, noise = WL.gaussian_node_errors(9, 16, 2, (rows, cols))
+    Cb = Ct.clone()
+    Cb[torch.from_numpy(np.asarray(bad)).to(DEV)] += to_dev(noise)
+    Cd, drep = G.gpd_decode(plan, Cb, mode=G.GPD_DEC_LSQ_ALL, correct_errors=G.GPD_CORRECT_NODES)
+    found = tuple(p for p in range(16) if drep.node_err_count[p] > 0)
+    assert found == tuple(int(b) for b in bad)
+    rep = G.gpd_verify_decode(plan, Cb, Cd, mode=G.GPD_DEC_LSQ_ALL, bad=found)
+    want = O.verify_decode(to_np(Cb), opl, to_np(Cd), None, "lsq_all", bad=found)
+    assert rep.status == G.GPD_OK and want.status == "ok" and rep.bad == want.bad == found
+    Cnaive, _ = G.gpd_decode(plan, Cb, mode=G.GPD_DEC_LSQ_ALL)
+    rep = G.gpd_verify_decode(plan, Cb, Cnaive, mode=G.GPD_DEC_LSQ_ALL, bad=found)
+    assert rep.status == G.GPD_E_VERIFY and rep.n_value_mismatch > 0 and rep.locations_agree
+    rep = G.gpd_verify_decode(plan, Cb, Cd, mode=G.GPD_DEC_LSQ_ALL, bad=found[:1])
+    assert rep.status == G.GPD_E_VERIFY and not rep.locations_agree
+    # (4) more values than codewords, and a non-finite decoded value
+    rep = G.gpd_verify_decode(plan, Ct, C, present=present, mode=G.GPD_DEC_FIRST_K, n_check=4096)
+    assert rep.status == G.GPD_OK and rep.n_checked == 4096
+    Cnan = C.clone()
+    Cnan[0, 0] = float("nan")
+    assert G.gpd_verify_decode(plan, Ct, Cnan, present=present, mode=G.GPD_DEC_FIRST_K).status == G.GPD_E_VERIFY
+
+
+def test_decoding_failure_restores_the_checkpoint():
+    # more erroneous nodes than the code can locate: the failure is reported, the iteration is
+    # abandoned and the coded weights go back to the last checkpoint (Sec. VII, error model 2)
+    from paper_1811_10751_amd.mlp import CodedMLP
+    sizes, batch, m, n, P = (96, 128, 64, 10), 4, 2, 4, 16          # K_f = 11, K_b = 12: capacity 4 / 3
+    Ws = [(w * 8).astype(np.float32) for w in WL.mlp_init(sizes, seed=2)]
+    mlp = CodedMLP(sizes, batch, m, n, 1, 1, P, rho_detect=1e-6)
+    mlp.encode_weights([to_dev(w) for w in Ws])
+    X, Y = WL.mlp_batch(2, 0, sizes[0], sizes[-1], batch)
+    mlp.step(to_dev(X), to_dev(Y), 0.5, correct_errors=G.GPD_CORRECT_NODES, regenerate=True)
+    mlp.checkpoint()
+    saved = [to_np(w).copy() for w in mlp.Wts]
+    X, Y = WL.mlp_batch(2, 1, sizes[0], sizes[-1], batch)
+    mlp.step(to_dev(X), to_dev(Y), 0.5, correct_errors=G.GPD_CORRECT_NODES, regenerate=True)
+    assert not mlp.restored and any(not np.array_equal(to_np(w), s0) for w, s0 in zip(mlp.Wts, saved))
+    g = torch.Generator(device=DEV).manual_seed(2)
+    for p in (0, 3, 5, 8, 9, 12):                                    # six bad nodes in layer 1
+        mlp.Wts[1][p] += torch.randn(mlp.Wts[1].shape[1:], generator=g, device=DEV)
+    X, Y = WL.mlp_batch(2, 2, sizes[0], sizes[-1], batch)
+    yhat, reps = mlp.step(to_dev(X), to_dev(Y), 0.5, correct_errors=G.GPD_CORRECT_NODES, regenerate=True,
+                          restore_on_failure=True)
+    assert yhat is None and mlp.restored
+    assert reps[1][0].status == G.GPD_E_DECODE_FAIL and reps[0][0].status == G.GPD_OK
+    for w, s0 in zip(mlp.Wts, saved):
+        assert np.array_equal(to_np(w), s0)
+    # training goes on from the checkpoint
+    yhat, reps = mlp.step(to_dev(X), to_dev(Y), 0.5, correct_errors=G.GPD_CORRECT_NODES, regenerate=True,
+                          restore_on_failure=True)
+    assert yhat is not None and not mlp.restored and mlp.repaired == []

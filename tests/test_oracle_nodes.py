@@ -262,3 +262,58 @@ def test_projection_from_a_subset_of_nodes():
     stack = Wt.copy()
     stack[[0, 6]] = 123.0
     assert np.abs(O.layer_project(stack, lp, present) - Wt).max() <= 1e-9 * np.abs(Wt).max()
+
+
+# ----------------------------------------------------------------------------- verification step
+
+
+def test_check_positions_are_spread_evenly():
+    assert O.check_positions(100, 10).tolist() == [0, 10, 20, 30, 40, 50, 60, 70, 80, 90]
+    assert O.check_positions(7, 3).tolist() == [0, 2, 4]
+    assert O.check_positions(4, 16).tolist() == [0, 1, 2, 3]
+
+
+def test_verification_passes_on_a_correct_decode_and_catches_a_wrong_one():
+    A, B, pl, Ct = coded_outputs(8, 8, 8, 2, 2, 2, 14, 12, round_outputs="f32")
+    present = np.ones(14, dtype=bool)
+    present[[2, 11]] = False
+    C, _ = O.decode(Ct, pl, present, "first_k")
+    rep = O.verify_decode(Ct, pl, C, present, "first_k")
+    assert rep.status == "ok" and rep.n_checked == 14 and rep.max_ratio < 1.0 and rep.bad == ()
+    pos = O.check_positions(16, 14)
+    rows = cols = 4
+    # a decoding error at a checked position is caught ...
+    Cbad = C.copy()
+    r_, c_ = divmod(int(pos[5]), cols)
+    Cbad[rows + r_, c_] += 1e-2                                     # block (1, 0)
+    rep = O.verify_decode(Ct, pl, Cbad, present, "first_k")
+    assert rep.status == "mismatch" and rep.n_value_mismatch == 1
+    # ... one at an unchecked position is not (the step looks at P values only)
+    unchecked = [e for e in range(16) if e not in pos.tolist()][0]
+    Cbad = C.copy()
+    Cbad[unchecked // cols, unchecked % cols] += 1.0
+    assert O.verify_decode(Ct, pl, Cbad, present, "first_k").status == "ok"
+    # a decode from the wrong nodes (an erased node's garbage used) is caught
+    Cgar = Ct.copy()
+    Cgar[2] = 5.0
+    Cwrong, _ = O.decode(Cgar, pl, np.ones(14, dtype=bool), "first_k")
+    assert O.verify_decode(Cgar, pl, Cwrong, present, "first_k").status == "mismatch"
+
+
+def test_verification_crosschecks_the_located_nodes():
+    A, B, pl, Ct = coded_outputs(8, 8, 8, 2, 2, 2, 14, 13, round_outputs="f32")
+    bad, noise = WL.gaussian_node_errors(5, 14, 2, Ct.shape[1:])
+    Cb = Ct.copy()
+    Cb[bad] += noise
+    C, nrep = O.decode_nodes(Cb, pl)
+    assert nrep.bad == tuple(int(b) for b in bad)
+    rep = O.verify_decode(Cb, pl, C, None, "lsq_all", bad=nrep.bad)
+    assert rep.status == "ok" and rep.locations_agree and rep.bad == nrep.bad
+    # claiming a different set of erroneous nodes fails the crosscheck
+    other = (int(bad[0]),)
+    rep = O.verify_decode(Cb, pl, C, None, "lsq_all", bad=other)
+    assert rep.status == "mismatch" and not rep.locations_agree
+    # a decode that did not leave the erroneous nodes out has wrong values
+    Cnaive, _ = O.decode(Cb, pl, None, "lsq_all")
+    rep = O.verify_decode(Cb, pl, Cnaive, None, "lsq_all", bad=nrep.bad)
+    assert rep.status == "mismatch" and rep.n_value_mismatch > 0
