@@ -353,6 +353,18 @@ gpd_status_t gpd_sigmoid_bwd(const float* c, const float* y, float* delta_prev, 
 gpd_status_t gpd_l2_delta(const float* y, const float* yhat, float scale, float* delta,
                           int64_t count, void* hip_stream);
 
+/* The two extra element-wise steps of the sparse autoencoder (Sec. X; lemma on autoencoder
+ * backpropagation), y = hidden activations, device fp32 rows x cols (cols = batch):
+ *   gpd_row_mean:           rho_hat[i] = (1 / cols) sum_b y[i][b]
+ *   gpd_sigmoid_bwd_sparse: delta[i][b] = (c[i][b] - scale * Q(rho_hat[i])) * y (1 - y),
+ *                           Q(r) = -rho / r + (1 - rho) / (1 - r); scale = beta / batch makes
+ *                           delta the step direction of the loss with the term beta * sum KL.
+ * 0 < rho < 1.  Enqueued on hip_stream. */
+gpd_status_t gpd_row_mean(const float* y, int64_t rows, int64_t cols, float* mean, void* hip_stream);
+gpd_status_t gpd_sigmoid_bwd_sparse(const float* c, const float* y, const float* rho_hat, float rho,
+                                    float scale, float* delta, int64_t rows, int64_t cols,
+                                    void* hip_stream);
+
 /* ------------------------------------------------------------------ host-only helpers */
 
 /* The code construction of gpd_plan without a GPU (Sec. IV, Thm 2): K and the exponent tables

@@ -863,3 +863,67 @@ def mlp_coded_step(Wts, lps, X, Y, eta, decay=0.0, operands="f64", round_outputs
         if l > 0:
             delta = C * sigmoid_grad_from_output(acts[l])
     return new_Wts, acts[-1], trace[::-1]
+
+
+# --------------------------------------------------------------------------- sparse autoencoder
+
+
+def kl_slope(rho: float, rho_hat: np.ndarray) -> np.ndarray:
+    """Q(rho_hat) = d KL(rho || rho_hat) / d rho_hat = -rho / rho_hat + (1 - rho) / (1 - rho_hat)
+    (Sec. X, definition under Eq. for Delta_auto)."""
+    rho_hat = np.asarray(rho_hat, dtype=np.float64)
+    return -rho / rho_hat + (1.0 - rho) / (1.0 - rho_hat)
+
+
+def autoencoder_loss(W1, W2, X, rho: float, beta: float) -> float:
+    """Mini-batch loss of the sparse autoencoder without the weight-decay term (Sec. X):
+    (1/B) sum_b ||x_b - xhat_b||^2 + beta sum_i KL(rho || rho_hat_i)."""
+    X = np.asarray(X, dtype=np.float64)
+    Y1 = sigmoid(np.asarray(W1, dtype=np.float64) @ X)
+    Y2 = sigmoid(np.asarray(W2, dtype=np.float64) @ Y1)
+    rh = Y1.mean(axis=1)
+    kl = rho * np.log(rho / rh) + (1.0 - rho) * np.log((1.0 - rho) / (1.0 - rh))
+    return float(((X - Y2) ** 2).sum() / X.shape[1] + beta * kl.sum())
+
+
+def autoencoder_delta1(C2, Y1, rho: float, beta: float) -> np.ndarray:
+    """Delta_auto^1 = (C^2 - (beta / B) Q_rhohat) o f'(S^1) (Lemma on autoencoder
+    backpropagation; the factor beta / B, dropped in the printed lemma, is what makes
+    W^1 + eta Delta_auto^1 X^T a step along minus the gradient of the loss above, in the same
+    units as Delta^2 = (2 / B)(X - Xhat) o f'(S^2))."""
+    Y1 = np.asarray(Y1, dtype=np.float64)
+    B = Y1.shape[1]
+    q = kl_slope(rho, Y1.mean(axis=1))
+    return (np.asarray(C2, dtype=np.float64) - (beta / B) * q[:, None]) * sigmoid_grad_from_output(Y1)
+
+
+def autoencoder_uncoded_step(W1, W2, X, eta, rho: float, beta: float, decay=0.0):
+    """One SGD iteration of the plain sparse autoencoder (Sec. X, Eqs. for the update of
+    W^1 and for Delta_auto^1; W^2 is updated as in any network).  Returns (W1', W2', Xhat)."""
+    W1 = np.asarray(W1, dtype=np.float64)
+    W2 = np.asarray(W2, dtype=np.float64)
+    X = np.asarray(X, dtype=np.float64)
+    Y1 = sigmoid(W1 @ X)
+    Y2 = sigmoid(W2 @ Y1)
+    d2 = last_layer_delta(X, Y2)
+    C2 = W2.T @ d2
+    d1 = autoencoder_delta1(C2, Y1, rho, beta)
+    return ((1.0 - decay) * W1 + eta * d1 @ X.T, (1.0 - decay) * W2 + eta * d2 @ Y1.T, Y2)
+
+
+def autoencoder_coded_step(Wt1, Wt2, lp1: LayerPlan, lp2: LayerPlan, X, eta, rho: float, beta: float,
+                           decay=0.0, mode="lsq_all"):
+    """The same iteration with both weight matrices kept encoded (Sec. X, list of key steps):
+    coded feedforward twice, coded backpropagation at layer 2, Delta_auto^1 from the decoded
+    C^2 and rho_hat, coded updates of both layers."""
+    X = np.asarray(X, dtype=np.float64)
+    S1, _ = layer_forward(Wt1, X, lp1, None, mode)
+    Y1 = sigmoid(S1)
+    S2, _ = layer_forward(Wt2, Y1, lp2, None, mode)
+    Y2 = sigmoid(S2)
+    d2 = last_layer_delta(X, Y2)
+    C2, _ = layer_backward(Wt2, d2, lp2, None, mode)
+    new2 = layer_update(Wt2, d2, Y1, lp2, eta, decay)
+    d1 = autoencoder_delta1(C2, Y1, rho, beta)
+    new1 = layer_update(Wt1, d1, X, lp1, eta, decay)
+    return new1, new2, Y2

@@ -36,6 +36,7 @@ EXPORTS = [
     "gpd_host_code", "gpd_host_decode_matrices", "gpd_last_error", "gpd_version",
     "gpd_locate_nodes", "gpd_layer_locate_nodes", "gpd_layer_regenerate", "gpd_layer_project",
     "gpd_host_parity_check", "gpd_host_locate_nodes", "gpd_verify_decode",
+    "gpd_row_mean", "gpd_sigmoid_bwd_sparse",
 ]
 
 
@@ -123,6 +124,8 @@ def load_library():
     lib.gpd_sigmoid_fwd.argtypes = [vp, vp, i64, vp]
     lib.gpd_sigmoid_bwd.argtypes = [vp, vp, vp, i64, vp]
     lib.gpd_l2_delta.argtypes = [vp, vp, C.c_float, vp, i64, vp]
+    lib.gpd_row_mean.argtypes = [vp, i64, i64, vp, vp]
+    lib.gpd_sigmoid_bwd_sparse.argtypes = [vp, vp, vp, C.c_float, C.c_float, vp, i64, i64, vp]
     lib.gpd_host_code.argtypes = [i32, i32, i32, i32, i32, vp, C.POINTER(i32), vp, vp, vp, vp]
     lib.gpd_host_decode_matrices.argtypes = [i32, i32, i32, i32, i32, vp, vp, i32, vp, vp,
                                              C.POINTER(i32)]
@@ -644,6 +647,30 @@ def gpd_l2_delta(y, yhat, scale, out=None, stream=None):
     out = torch.empty_like(yhat) if out is None else out
     _check(load_library().gpd_l2_delta(_ptr(y), _ptr(yhat), scale, _ptr(out), yhat.numel(),
                                        _stream_handle(stream)))
+    return out
+
+
+def gpd_row_mean(y, out=None, stream=None):
+    import torch
+    _require_f32_cuda(y, "y")
+    if y.dim() != 2 or not y.is_contiguous():
+        raise ValueError("y must be a contiguous matrix")
+    if out is None:
+        out = torch.empty(y.shape[0], dtype=torch.float32, device=y.device)
+    _check(load_library().gpd_row_mean(_ptr(y), y.shape[0], y.shape[1], _ptr(out), _stream_handle(stream)))
+    return out
+
+
+def gpd_sigmoid_bwd_sparse(c, y, rho_hat, rho, scale, out=None, stream=None):
+    import torch
+    for t, name in ((c, "c"), (y, "y"), (rho_hat, "rho_hat")):
+        _require_f32_cuda(t, name)
+    if c.shape != y.shape or y.dim() != 2 or rho_hat.numel() != y.shape[0] or not (c.is_contiguous() and y.is_contiguous()):
+        raise ValueError("shapes do not match")
+    if out is None:
+        out = torch.empty_like(c)
+    _check(load_library().gpd_sigmoid_bwd_sparse(_ptr(c), _ptr(y), _ptr(rho_hat), rho, scale, _ptr(out), y.shape[0],
+                                                 y.shape[1], _stream_handle(stream)))
     return out
 
 

@@ -194,6 +194,29 @@ __global__ void sigmoid_bwd_kernel(const float* __restrict__ c, const float* __r
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) d[i] = c[i] * y[i] * (1.f - y[i]);
 }
+// rho_hat[i] = mean over the batch of y[i][:]: one wavefront per row, lanes stride over the
+// columns, tree sum in a fixed order
+__global__ __launch_bounds__(256) void row_mean_kernel(const float* __restrict__ y, int64_t rows, int64_t cols,
+                                                       float* __restrict__ mean) {
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int lane = threadIdx.x & 63;
+  float acc = 0.f;
+  for (int64_t c = lane; c < cols; c += 64) acc += y[row * cols + c];
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+  if (lane == 0) mean[row] = acc / (float)cols;
+}
+// delta = (c - scale * Q(rho_hat_row)) * y (1 - y),  Q(r) = -rho / r + (1 - rho) / (1 - r)
+__global__ void sigmoid_bwd_sparse_kernel(const float* __restrict__ c, const float* __restrict__ y,
+                                          const float* __restrict__ rho_hat, float rho, float scale,
+                                          float* __restrict__ d, int64_t cols, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const float r = rho_hat[i / cols];
+  const float q = -rho / r + (1.f - rho) / (1.f - r);
+  d[i] = (c[i] - scale * q) * y[i] * (1.f - y[i]);
+}
 __global__ void l2_delta_kernel(const float* __restrict__ y, const float* __restrict__ yh, float scale,
                                 float* __restrict__ d, int64_t n) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -747,6 +770,27 @@ extern "C" gpd_status_t gpd_sigmoid_bwd(const float* c, const float* y, float* d
   if (n < 0 || (n > 0 && (!c || !y || !d))) return fail(GPD_E_INVALID, "gpd_sigmoid_bwd: bad argument");
   if (n == 0) return GPD_OK;
   hipLaunchKernelGGL(sigmoid_bwd_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, c, y, d, n);
+  GPD_HIP(hipGetLastError());
+  return GPD_OK;
+}
+
+extern "C" gpd_status_t gpd_row_mean(const float* y, int64_t rows, int64_t cols, float* mean, void* stream) {
+  if (rows < 0 || cols < 1 || (rows > 0 && (!y || !mean))) return fail(GPD_E_INVALID, "gpd_row_mean: bad argument");
+  if (rows == 0) return GPD_OK;
+  hipLaunchKernelGGL(row_mean_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, (hipStream_t)stream, y, rows,
+                     cols, mean);
+  GPD_HIP(hipGetLastError());
+  return GPD_OK;
+}
+
+extern "C" gpd_status_t gpd_sigmoid_bwd_sparse(const float* c, const float* y, const float* rho_hat, float rho,
+                                               float scale, float* d, int64_t rows, int64_t cols, void* stream) {
+  const int64_t n = rows * cols;
+  if (rows < 0 || cols < 1 || (n > 0 && (!c || !y || !rho_hat || !d)) || !(rho > 0.f && rho < 1.f))
+    return fail(GPD_E_INVALID, "gpd_sigmoid_bwd_sparse: bad argument");
+  if (n == 0) return GPD_OK;
+  hipLaunchKernelGGL(sigmoid_bwd_sparse_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                     c, y, rho_hat, rho, scale, d, cols, n);
   GPD_HIP(hipGetLastError());
   return GPD_OK;
 }

@@ -96,3 +96,36 @@ class CodedMLP:
             if l > 0:
                 delta = B.gpd_sigmoid_bwd(C, acts[l], stream=self.stream)
         return acts[-1], reps
+
+
+class CodedAutoencoder:
+    """Sparse autoencoder with one hidden layer (Sec. X): N0 -> N1 -> N0, both weight matrices
+    kept encoded; the loss is the reconstruction error plus beta * sum_i KL(rho || rho_hat_i)."""
+
+    def __init__(self, N0, N1, batch, m, n, P, d1=1, d2=1, worker_dtype=B.GPD_F32, stream=None):
+        self.N0, self.N1, self.batch, self.stream = N0, N1, batch, stream
+        self.l1 = B.gpd_layer_create(N1, N0, batch, m, n, d1, d2, P, worker_dtype=worker_dtype, stream=stream)
+        self.l2 = B.gpd_layer_create(N0, N1, batch, m, n, d1, d2, P, worker_dtype=worker_dtype, stream=stream)
+        self.Wt1 = self.Wt2 = None
+
+    def encode_weights(self, W1, W2):
+        self.Wt1 = B.gpd_layer_encode_weights(self.l1, W1)
+        self.Wt2 = B.gpd_layer_encode_weights(self.l2, W2)
+
+    def decode_weights(self):
+        return B.gpd_layer_decode_weights(self.l1, self.Wt1), B.gpd_layer_decode_weights(self.l2, self.Wt2)
+
+    def step(self, X, eta, rho, beta, decay=0.0):
+        """One iteration on the mini-batch X (N0 x batch); returns the reconstruction."""
+        S1, _ = B.gpd_coded_layer_step(self.l1, B.GPD_STEP_FORWARD, self.Wt1, X)
+        Y1 = B.gpd_sigmoid_fwd(S1, stream=self.stream)
+        S2, _ = B.gpd_coded_layer_step(self.l2, B.GPD_STEP_FORWARD, self.Wt2, Y1)
+        Y2 = B.gpd_sigmoid_fwd(S2, stream=self.stream)
+        d2 = B.gpd_l2_delta(X, Y2, 2.0 / self.batch, stream=self.stream)
+        C2, _ = B.gpd_coded_layer_step(self.l2, B.GPD_STEP_BACKWARD_UPDATE, self.Wt2, Y1, Dlt=d2, eta=eta,
+                                       decay=decay)
+        rho_hat = B.gpd_row_mean(Y1, stream=self.stream)
+        d1 = B.gpd_sigmoid_bwd_sparse(C2, Y1, rho_hat, rho, beta / self.batch, stream=self.stream)
+        B.gpd_coded_layer_step(self.l1, B.GPD_STEP_BACKWARD_UPDATE, self.Wt1, X, Dlt=d1, eta=eta, decay=decay,
+                               skip_output=True)
+        return Y2

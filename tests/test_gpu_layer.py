@@ -198,3 +198,33 @@ def test_hip_graph_replay_matches_eager():
         torch.cuda.synchronize()
     for a, b in zip(eager.Wts, gm.Wts):
         assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("N0,N1,batch,m,n,P", [(96, 160, 8, 2, 2, 12), (130, 70, 1, 4, 2, 24), (256, 512, 64, 2, 4, 32)])
+def test_sparse_autoencoder_training_tracks_the_oracle(N0, N1, batch, m, n, P):
+    from paper_1811_10751_amd.mlp import CodedAutoencoder
+    rng = np.random.default_rng(N0)
+    W1 = (rng.standard_normal((N1, N0)) / np.sqrt(N0)).astype(np.float32)
+    W2 = (rng.standard_normal((N0, N1)) / np.sqrt(N1)).astype(np.float32)
+    ae = CodedAutoencoder(N0, N1, batch, m, n, P)
+    ae.encode_weights(to_dev(W1), to_dev(W2))
+    P1, P2 = W1.astype(np.float64), W2.astype(np.float64)
+    eta, rho, beta, decay = 0.5, 0.2, 0.3, 0.001
+    for step in range(5):
+        X = rng.uniform(0.05, 0.95, (N0, batch)).astype(np.float32)
+        xh = ae.step(to_dev(X), eta, rho, beta, decay)
+        P1, P2, xh_o = O.autoencoder_uncoded_step(P1, P2, X, np.float32(eta), np.float32(rho), np.float32(beta),
+                                                  np.float32(decay))
+        err = rel_fro(to_np(xh), xh_o)
+        say("  autoencoder step", step, "reconstruction err vs plain SGD %.3g" % err)
+        assert err < 1e-3
+    D1, D2 = ae.decode_weights()
+    assert rel_fro(to_np(D1), P1) < 1e-3 and rel_fro(to_np(D2), P2) < 1e-3
+    # the two extra element-wise steps alone
+    Y = torch.rand((37, 19), device=DEV) * 0.9 + 0.05
+    Cm = torch.randn((37, 19), device=DEV)
+    rh = G.gpd_row_mean(Y)
+    assert np.abs(to_np(rh) - to_np(Y).astype(np.float64).mean(axis=1)).max() < 1e-6
+    d = G.gpd_sigmoid_bwd_sparse(Cm, Y, rh, 0.2, 0.3 / 19)
+    want = O.autoencoder_delta1(to_np(Cm), to_np(Y), 0.2, 0.3)
+    assert np.abs(to_np(d) - want).max() <= 1e-5 * np.abs(want).max()

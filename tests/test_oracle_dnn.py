@@ -125,3 +125,58 @@ def test_substitution_choice():
     assert (a.Kf, a.Kb) == (9, 14) and (b.Kf, b.Kb) == (12, 11)
     c = O.make_layer_plan(16, 16, 4, 2, 4, 1, 1, 32, "auto")
     assert (c.Kf, c.Kb) == (11, 12)
+
+
+# ----------------------------------------------------------------------------- sparse autoencoder (Sec. X)
+
+
+def test_autoencoder_step_is_minus_the_gradient_of_its_loss():
+    # finite differences of the printed loss (data term + beta KL term) against the update direction
+    rng = np.random.default_rng(0)
+    N0, N1, B = 7, 5, 4
+    W1 = rng.standard_normal((N1, N0)) * 0.5
+    W2 = rng.standard_normal((N0, N1)) * 0.5
+    X = rng.uniform(0.1, 0.9, (N0, B))
+    rho, beta, eta = 0.2, 0.7, 1.0
+    n1, n2, _ = O.autoencoder_uncoded_step(W1, W2, X, eta, rho, beta)
+    g1, g2 = (n1 - W1) / eta, (n2 - W2) / eta                   # claimed minus-gradients
+    h = 1e-6
+    for (W, g, which) in ((W1, g1, 1), (W2, g2, 2)):
+        for _ in range(12):
+            i, j = rng.integers(0, W.shape[0]), rng.integers(0, W.shape[1])
+            Wp, Wm = W.copy(), W.copy()
+            Wp[i, j] += h
+            Wm[i, j] -= h
+            if which == 1:
+                fd = (O.autoencoder_loss(Wp, W2, X, rho, beta) - O.autoencoder_loss(Wm, W2, X, rho, beta)) / (2 * h)
+            else:
+                fd = (O.autoencoder_loss(W1, Wp, X, rho, beta) - O.autoencoder_loss(W1, Wm, X, rho, beta)) / (2 * h)
+            assert abs(-fd - g[i, j]) <= 1e-6 * max(1.0, abs(fd))
+
+
+def test_autoencoder_sparsity_term_vanishes_at_the_target_and_reduces_to_the_mlp():
+    assert np.allclose(O.kl_slope(0.3, np.array([0.3, 0.3])), 0.0)
+    assert O.kl_slope(0.3, np.array([0.5]))[0] > 0 > O.kl_slope(0.3, np.array([0.1]))[0]
+    rng = np.random.default_rng(1)
+    W1, W2 = rng.standard_normal((6, 8)) * 0.3, rng.standard_normal((8, 6)) * 0.3
+    X = rng.uniform(0, 1, (8, 3))
+    # beta = 0: an ordinary two-layer network trained to reproduce its input
+    a1, a2, _ = O.autoencoder_uncoded_step(W1, W2, X, 0.1, 0.2, 0.0)
+    (m1, m2), _, _ = O.mlp_uncoded_step([W1, W2], X, X, 0.1)
+    assert np.allclose(a1, m1) and np.allclose(a2, m2)
+
+
+def test_coded_autoencoder_step_equals_the_plain_one():
+    rng = np.random.default_rng(2)
+    N0, N1, B, m, n, P = 12, 8, 4, 2, 2, 12
+    lp1 = O.make_layer_plan(N1, N0, B, m, n, 1, 1, P)
+    lp2 = O.make_layer_plan(N0, N1, B, m, n, 1, 1, P)
+    W1, W2 = rng.standard_normal((N1, N0)) * 0.4, rng.standard_normal((N0, N1)) * 0.4
+    Wt1, Wt2 = O.layer_encode_weights(W1, lp1), O.layer_encode_weights(W2, lp2)
+    for step in range(3):
+        X = rng.uniform(0.05, 0.95, (N0, B))
+        Wt1, Wt2, xh_c = O.autoencoder_coded_step(Wt1, Wt2, lp1, lp2, X, 0.3, 0.15, 0.5, decay=0.01)
+        W1, W2, xh_p = O.autoencoder_uncoded_step(W1, W2, X, 0.3, 0.15, 0.5, decay=0.01)
+        assert np.abs(xh_c - xh_p).max() < 1e-9
+    assert np.abs(O.layer_decode_weights(Wt1, lp1) - W1).max() < 1e-9
+    assert np.abs(O.layer_decode_weights(Wt2, lp2) - W2).max() < 1e-9
