@@ -513,21 +513,23 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
   }
 
   const int nchunks = (g.K + HK - 1) / HK;
+  auto kof = [&](int c) { return c * HK; };
   HStage<ASRC, TBM, NT, HK> sa;
   HStage<BSRC, TBN, NT, HK> sb;
-  hload<ASRC, MODE, TBM, NT, HK>(sa, A, g.lda, m0, 0, g.M, g.K, tid);
-  hload<BSRC, MODE, TBN, NT, HK>(sb, B, g.ldb, n0, 0, g.N, g.K, tid);
+  hload<ASRC, MODE, TBM, NT, HK>(sa, A, g.lda, m0, kof(0), g.M, g.K, tid);
+  hload<BSRC, MODE, TBN, NT, HK>(sb, B, g.ldb, n0, kof(0), g.N, g.K, tid);
   hstore<ASRC, TBM, NT, SPLIT, PA, HK>(sa, lds_a[0], tid);
   hstore<BSRC, TBN, NT, SPLIT, PB, HK>(sb, lds_b[0], tid);
   union Frag { uint4 u; bf16x8 v; };
 
-  if constexpr (SPLIT == 1) {
+  constexpr bool kDeep = SPLIT == 3 || WGM * WGN == 8;
+  if constexpr (!kDeep) {
     __syncthreads();
     for (int c = 0; c < nchunks; ++c) {
       const int cur = c & 1;
       if (c + 1 < nchunks) {
-        hload<ASRC, MODE, TBM, NT, HK>(sa, A, g.lda, m0, (c + 1) * HK, g.M, g.K, tid);
-        hload<BSRC, MODE, TBN, NT, HK>(sb, B, g.ldb, n0, (c + 1) * HK, g.N, g.K, tid);
+        hload<ASRC, MODE, TBM, NT, HK>(sa, A, g.lda, m0, kof(c + 1), g.M, g.K, tid);
+        hload<BSRC, MODE, TBN, NT, HK>(sb, B, g.ldb, n0, kof(c + 1), g.N, g.K, tid);
       }
       const uint16_t* __restrict__ as = lds_a[cur];
       const uint16_t* __restrict__ bs = lds_b[cur];
@@ -552,6 +554,56 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
       }
       __syncthreads();
     }
+  } else if constexpr (SPLIT == 1) {
+    // Three stages in flight (8 wavefronts with 256 registers each): stage c is multiplied from
+    // LDS, stage c + 1 (loaded one iteration ago) is converted and written to the other LDS
+    // buffer after each half of the products, the global loads of stage c + 2 are issued.  Two
+    // stages of global loads in flight is what keeps HBM busy when the kernel streams fp32
+    // weights with one workgroup per CU.
+    constexpr int IA = hstage_items<ASRC, TBM, NT, HK>(), IB = hstage_items<BSRC, TBN, NT, HK>();
+    constexpr int HALF = (IA + IB + 1) / 2;
+    if (nchunks > 1) {
+      hload<ASRC, MODE, TBM, NT, HK>(sa, A, g.lda, m0, kof(1), g.M, g.K, tid);
+      hload<BSRC, MODE, TBN, NT, HK>(sb, B, g.ldb, n0, kof(1), g.N, g.K, tid);
+    }
+    __syncthreads();
+    for (int c = 0; c < nchunks; ++c) {
+      const int cur = c & 1;
+      HStage<ASRC, TBM, NT, HK> na = sa;
+      HStage<BSRC, TBN, NT, HK> nb = sb;
+      if (c + 2 < nchunks) {
+        hload<ASRC, MODE, TBM, NT, HK>(na, A, g.lda, m0, kof(c + 2), g.M, g.K, tid);
+        hload<BSRC, MODE, TBN, NT, HK>(nb, B, g.ldb, n0, kof(c + 2), g.N, g.K, tid);
+      }
+      const bool conv = c + 1 < nchunks;
+      const uint16_t* __restrict__ as = lds_a[cur];
+      const uint16_t* __restrict__ bs = lds_b[cur];
+#pragma unroll
+      for (int h = 0; h < HK / 16; ++h) {
+        Frag fa[MI], fb[NJ];
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+          fa[i].u = *reinterpret_cast<const uint4*>(as + (wm + 32 * i + li) * HSTRIDE + 16 * h + 8 * lg);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+          fb[j].u = *reinterpret_cast<const uint4*>(bs + (wn + 32 * j + li) * HSTRIDE + 16 * h + 8 * lg);
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+          for (int j = 0; j < NJ; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i].v, fb[j].v, acc[i][j], 0, 0, 0);
+        if (conv) {
+#pragma unroll
+          for (int it = h * HALF; it < (h + 1) * HALF && it < IA + IB; ++it) {
+            if (it < IA) hstore_item<ASRC, TBM, NT, SPLIT, PA, HK>(sa, it, lds_a[cur ^ 1], tid);
+            else hstore_item<BSRC, TBN, NT, SPLIT, PB, HK>(sb, it - IA, lds_b[cur ^ 1], tid);
+          }
+        }
+      }
+      __syncthreads();
+      sa = na;
+      sb = nb;
+    }
   } else {
     // Three stages in flight: stage c is multiplied from LDS, stage c + 1 (loaded one iteration
     // ago, so already in registers) is split and written to the other LDS buffer in pieces
@@ -561,8 +613,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
     constexpr int IA = hstage_items<ASRC, TBM, NT, HK>(), IB = hstage_items<BSRC, TBN, NT, HK>();
     static_assert(IA + IB <= 6, "one conversion slot per partial product");
     if (nchunks > 1) {
-      hload<ASRC, MODE, TBM, NT, HK>(sa, A, g.lda, m0, HK, g.M, g.K, tid);
-      hload<BSRC, MODE, TBN, NT, HK>(sb, B, g.ldb, n0, HK, g.N, g.K, tid);
+      hload<ASRC, MODE, TBM, NT, HK>(sa, A, g.lda, m0, kof(1), g.M, g.K, tid);
+      hload<BSRC, MODE, TBN, NT, HK>(sb, B, g.ldb, n0, kof(1), g.N, g.K, tid);
     }
     __syncthreads();
     for (int c = 0; c < nchunks; ++c) {
@@ -570,8 +622,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
       HStage<ASRC, TBM, NT, HK> na = sa;
       HStage<BSRC, TBN, NT, HK> nb = sb;
       if (c + 2 < nchunks) {
-        hload<ASRC, MODE, TBM, NT, HK>(na, A, g.lda, m0, (c + 2) * HK, g.M, g.K, tid);
-        hload<BSRC, MODE, TBN, NT, HK>(nb, B, g.ldb, n0, (c + 2) * HK, g.N, g.K, tid);
+        hload<ASRC, MODE, TBM, NT, HK>(na, A, g.lda, m0, kof(c + 2), g.M, g.K, tid);
+        hload<BSRC, MODE, TBN, NT, HK>(nb, B, g.ldb, n0, kof(c + 2), g.N, g.K, tid);
       }
       const bool conv = c + 1 < nchunks;
       const uint16_t* __restrict__ as = lds_a[cur];
@@ -654,9 +706,10 @@ gpd_status_t launch_bf16_t(hipStream_t stream, HGemmParams p, int64_t batch, boo
   p.tiles_per_xcd = (int)((total + 7) / 8);
   dim3 grid((unsigned)(p.tiles_per_xcd * 8));
   if (large) {
-    // the split kernel keeps three planes of A in registers: 8 wavefronts of 128 x 64 (256
+    // the split kernel keeps three planes of A in registers, and a kernel that streams fp32
+    // weights needs two stages of global loads in flight: 8 wavefronts of 128 x 64 (256
     // registers each) instead of 16 of 64 x 64 (128 registers)
-    if constexpr (SPLIT == 3)
+    if constexpr (SPLIT == 3 || ASRC == SRC_F32_KC || ASRC == SRC_F32_RC)
       hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 0, 256, 256, 2, 4, SPLIT>), grid, dim3(512), 0, stream, p);
     else
       hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 0, 256, 256, 4, 4, SPLIT>), grid, dim3(1024), 0, stream, p);
