@@ -21,6 +21,7 @@ SHAPES = [
     (96, 90, 66, 3, 2, 2, 16, "v=u^m"),           # blocks 32 x 45 x 33: odd widths (scalar path)
     (520, 136, 264, 4, 1, 3, 14, "u=v^n"),        # polynomial-code special case (n = 1)
     (136, 1040, 264, 1, 5, 1, 10, "u=v^n"),       # MatDot special case (m = d = 1)
+    (64, 64, 96, 2, 2, 4, 64, "u=v^n"),           # the largest number of nodes (64), K = 17
 ]
 
 
@@ -72,7 +73,14 @@ def test_encode_products_decode_stagewise(N1, N0, Nc, m, n, d, P, subst):
     e2e = rel_fro(to_np(C), O.uncoded_matmul(A, B))
     amp = O.amplification(opl, None, "first_k")
     say("  end-to-end vs A.B: %.3g (amp %.3g)" % (e2e, amp))
-    assert e2e <= max(1e-3, 4 * amp * 2.0 ** -21)
+    if amp < 1e6:
+        assert e2e <= max(1e-3, 4 * amp * 2.0 ** -21)
+    else:
+        # the first K of 64 Chebyshev points sit in a corner of the interval: nothing can be decoded
+        # from them in fp32; least squares over all nodes still gives the product
+        C, _ = G.gpd_decode(plan, Ct, mode=G.GPD_DEC_LSQ_ALL)
+        amp_all = O.amplification(opl, None, "lsq_all")
+        assert rel_fro(to_np(C), O.uncoded_matmul(A, B)) <= max(1e-3, 4 * amp_all * 2.0 ** -21)
 
 
 def test_too_few_responses_and_bad_arguments():
