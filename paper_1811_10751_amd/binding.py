@@ -360,6 +360,7 @@ class Layer:
         self.Kf, self.Kb, self.wt_rows, self.wt_cols, self.workspace_bytes = \
             kf.value, kb.value, r.value, c.value, ws.value
         self.N_out, self.N_in, self.batch, self.P = desc.N_out, desc.N_in, desc.batch, desc.P
+        self.worker_dtype = desc.worker_dtype
         self._ws = None
 
     def workspace(self, device):
@@ -376,6 +377,9 @@ class Layer:
         _check(load_library().gpd_layer_workspace_view(self.handle, which, C.byref(off), C.byref(r), C.byref(c)))
         ws = self.workspace(device)
         n = self.P * r.value * c.value
+        if which >= 4 and self.worker_dtype != GPD_F32 and self.batch % 64 == 0:
+            # three bf16 planes (hi, mid, lo), each [P][cols/16][rows][16]
+            return ws[off.value:off.value + 6 * n].view(torch.bfloat16).view(3, self.P, c.value // 16, r.value, 16)
         return ws[off.value:off.value + 4 * n].view(torch.float32).view(self.P, r.value, c.value)
 
     def close(self):

@@ -68,11 +68,32 @@ __device__ __forceinline__ void store_vec_bf16(uint16_t* p, const float (&v)[VEC
   }
 }
 
+// An fp32 value as three bf16 values (hi = bf16(x), mid = bf16(x - hi), lo = bf16(x - hi - mid),
+// round-to-nearest-even, both subtractions exact), stored in three planes `plane` elements apart.
+template <int VEC>
+__device__ __forceinline__ void store_vec_split3(uint16_t* p, int64_t plane, const float (&v)[VEC]) {
+  float r[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) r[e] = v[e];
+#pragma unroll
+  for (int pl = 0; pl < 3; ++pl) {
+    store_vec_bf16<VEC>(p + pl * plane, r);
+    if (pl < 2) {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        const uint32_t h = pack_bf16(r[e], 0.f) & 0xffffu;
+        r[e] -= __uint_as_float(h << 16);
+      }
+    }
+  }
+}
+
 struct CombineParams {
   const float* in;
   int64_t in_ld;
   void* out;
   int64_t out_ld;
+  int64_t out_plane;         // elements between the three planes of a split output
   int64_t rows, cols;        // block shape in elements
   int64_t cols_vec;          // cols / VEC
   int nin, nout, r;
@@ -92,13 +113,27 @@ struct CombineParams {
 };
 
 // NIN_MAX: compile-time bound on nin (register array); VEC: columns per thread.
-template <int NIN_MAX, int VEC, bool OUT_BF16, bool SCREEN, bool LIMITS>
+// OUT: 0 fp32, 1 bf16, 2 three bf16 planes (hi, mid, lo of the fp32 value), each block stored
+// k-blocked: 16 consecutive columns of a row are contiguous, rows next, column groups outermost
+template <int NIN_MAX, int VEC, int OUT, bool SCREEN, bool LIMITS>
 __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t total = p.rows * p.cols_vec;
   const bool active = idx < total;
-  const int64_t row = active ? idx / p.cols_vec : 0;
-  const int64_t col = active ? (idx - row * p.cols_vec) * VEC : 0;
+  int64_t row, col;
+  if constexpr (OUT == 2) {
+    // threads follow the k-blocked output order (16 / VEC threads per row of a 16-column group,
+    // rows next): the stores of a wavefront are contiguous in every plane, and the inputs, whose
+    // rows are then read in pieces, are P times smaller than the outputs
+    constexpr int TPR = 16 / VEC;
+    const int64_t rc = active ? idx / TPR : 0;
+    const int64_t kb = rc / p.rows;
+    row = rc - kb * p.rows;
+    col = kb * 16 + (active ? idx % TPR : 0) * VEC;
+  } else {
+    row = active ? idx / p.cols_vec : 0;
+    col = active ? (idx - row * p.cols_vec) * VEC : 0;
+  }
 
   float z[NIN_MAX][VEC];
 #pragma unroll
@@ -198,13 +233,17 @@ __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
       if (!(row < p.out_rows[q] && col < p.out_cols[q])) continue;
     }
     const int64_t o = p.out_off[q] + row * p.out_ld + col;
-    if constexpr (OUT_BF16) store_vec_bf16<VEC>(reinterpret_cast<uint16_t*>(p.out) + o, acc);
+    if constexpr (OUT == 2) {
+      // k-blocked: [col / 16][row][col % 16], what the split GEMM reads as one contiguous stage
+      const int64_t ob = p.out_off[q] + ((col >> 4) * p.rows + row) * 16 + (col & 15);
+      store_vec_split3<VEC>(reinterpret_cast<uint16_t*>(p.out) + ob, p.out_plane, acc);
+    } else if constexpr (OUT == 1) store_vec_bf16<VEC>(reinterpret_cast<uint16_t*>(p.out) + o, acc);
     else store_vec<VEC>(reinterpret_cast<float*>(p.out) + o, acc);
   }
 }
 
 template <int NIN_MAX, int VEC>
-gpd_status_t launch_t(hipStream_t stream, const CombineParams& p, bool out_bf16, bool screen) {
+gpd_status_t launch_t(hipStream_t stream, const CombineParams& p, int out_kind, bool screen) {
   const int64_t total = p.rows * p.cols_vec;
   if (total == 0) return GPD_OK;
   // one wavefront per workgroup: a finished wavefront is replaced at once instead of waiting for
@@ -214,30 +253,33 @@ gpd_status_t launch_t(hipStream_t stream, const CombineParams& p, bool out_bf16,
   dim3 grid((unsigned)blocks, (unsigned)((p.nout + p.q_chunk - 1) / p.q_chunk)), block(64);
   const bool lim = p.in_rows != nullptr;
   if (screen) {
-    if (out_bf16) return fail(GPD_E_UNSUPPORTED, "screen with bf16 output");
-    if (lim) hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, false, true, true>), grid, block, 0, stream, p);
-    else hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, false, true, false>), grid, block, 0, stream, p);
-  } else if (out_bf16) {
-    if (lim) hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, true, false, true>), grid, block, 0, stream, p);
-    else hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, true, false, false>), grid, block, 0, stream, p);
+    if (out_kind != 0) return fail(GPD_E_UNSUPPORTED, "screen with bf16 output");
+    if (lim) hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, 0, true, true>), grid, block, 0, stream, p);
+    else hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, 0, true, false>), grid, block, 0, stream, p);
+  } else if (out_kind == 2) {
+    if (lim) hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, 2, false, true>), grid, block, 0, stream, p);
+    else hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, 2, false, false>), grid, block, 0, stream, p);
+  } else if (out_kind == 1) {
+    if (lim) hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, 1, false, true>), grid, block, 0, stream, p);
+    else hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, 1, false, false>), grid, block, 0, stream, p);
   } else {
-    if (lim) hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, false, false, true>), grid, block, 0, stream, p);
-    else hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, false, false, false>), grid, block, 0, stream, p);
+    if (lim) hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, 0, false, true>), grid, block, 0, stream, p);
+    else hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, 0, false, false>), grid, block, 0, stream, p);
   }
   GPD_HIP(hipGetLastError());
   return GPD_OK;
 }
 
 template <int VEC>
-gpd_status_t launch_v(hipStream_t stream, const CombineParams& p, bool out_bf16, bool screen) {
-  if (p.nin <= 4) return launch_t<4, VEC>(stream, p, out_bf16, screen);
-  if (p.nin <= 8) return launch_t<8, VEC>(stream, p, out_bf16, screen);
-  if (p.nin <= 16) return launch_t<16, VEC>(stream, p, out_bf16, screen);
+gpd_status_t launch_v(hipStream_t stream, const CombineParams& p, int out_kind, bool screen) {
+  if (p.nin <= 4) return launch_t<4, VEC>(stream, p, out_kind, screen);
+  if (p.nin <= 8) return launch_t<8, VEC>(stream, p, out_kind, screen);
+  if (p.nin <= 16) return launch_t<16, VEC>(stream, p, out_kind, screen);
   if constexpr (VEC <= 2) {
-    if (p.nin <= 32) return launch_t<32, VEC>(stream, p, out_bf16, screen);
+    if (p.nin <= 32) return launch_t<32, VEC>(stream, p, out_kind, screen);
   }
   if constexpr (VEC == 1) {
-    if (p.nin <= 64) return launch_t<64, VEC>(stream, p, out_bf16, screen);
+    if (p.nin <= 64) return launch_t<64, VEC>(stream, p, out_kind, screen);
   }
   return fail(GPD_E_UNSUPPORTED, "combine: nin = %d too large for VEC = %d", p.nin, VEC);
 }
@@ -245,13 +287,16 @@ gpd_status_t launch_v(hipStream_t stream, const CombineParams& p, bool out_bf16,
 }  // namespace
 
 gpd_status_t launch_combine(hipStream_t stream, const CombineTable& t, const float* in,
-                            int64_t in_ld, void* out, int64_t out_ld, bool out_bf16,
-                            int64_t rows, int64_t cols, const ScreenArgs& screen) {
+                            int64_t in_ld, void* out, int64_t out_ld, int out_kind,
+                            int64_t rows, int64_t cols, const ScreenArgs& screen, int64_t out_plane) {
   if (t.nin < 1 || t.nin > GPD_MAX_BLOCKS || t.nout < 1)
     return fail(GPD_E_INVALID, "combine: nin = %d, nout = %d", t.nin, t.nout);
   if (rows * cols > 0x7fffffffLL) return fail(GPD_E_SHAPE, "block has more than 2^31 elements");
   CombineParams p;
-  p.in = in; p.in_ld = in_ld; p.out = out; p.out_ld = out_ld;
+  p.in = in; p.in_ld = in_ld; p.out = out; p.out_ld = out_ld; p.out_plane = out_plane;
+  if (out_kind < 0 || out_kind > 2) return fail(GPD_E_INVALID, "combine: unknown output kind");
+  if (out_kind == 2 && (out_plane % 8 || cols % 16 || out_ld != cols || screen.enabled))
+    return fail(GPD_E_INVALID, "combine: split planes need full blocks of a multiple of 16 columns");
   p.rows = rows; p.cols = cols;
   p.nin = t.nin; p.nout = t.nout; p.r = screen.enabled ? t.r : 0;
   p.in_off = t.in_off; p.out_off = t.out_off; p.coef = t.coef; p.H = t.H;
@@ -260,7 +305,7 @@ gpd_status_t launch_combine(hipStream_t stream, const CombineTable& t, const flo
   p.counters = screen.counters; p.list = screen.list; p.cap = screen.cap;
 
   // widest vector the shapes, leading dimensions, block offsets and base addresses allow
-  const size_t out_elem = out_bf16 ? 2 : 4;
+  const size_t out_elem = out_kind ? 2 : 4;
   auto ok = [&](int vec) {
     if (cols % vec || in_ld % vec || out_ld % vec || t.off_align % vec) return false;
     if (t.in_rows && t.limit_align % vec) return false;
@@ -277,9 +322,9 @@ gpd_status_t launch_combine(hipStream_t stream, const CombineTable& t, const flo
   // in place (outputs overwrite inputs): a thread must hold all its inputs before any output
   // of its element is written, so the outputs cannot be split over several workgroups
   if ((const void*)in == (const void*)out) p.q_chunk = t.nout;
-  if (vec == 4) return launch_v<4>(stream, p, out_bf16, screen.enabled);
-  if (vec == 2) return launch_v<2>(stream, p, out_bf16, screen.enabled);
-  return launch_v<1>(stream, p, out_bf16, screen.enabled);
+  if (vec == 4) return launch_v<4>(stream, p, out_kind, screen.enabled);
+  if (vec == 2) return launch_v<2>(stream, p, out_kind, screen.enabled);
+  return launch_v<1>(stream, p, out_kind, screen.enabled);
 }
 
 }  // namespace gpd

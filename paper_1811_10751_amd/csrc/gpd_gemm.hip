@@ -8,6 +8,8 @@
 // order of k inside a tile is permuted so that a lane fetches its four consecutive
 // k-values of a k-contiguous operand with one 128-bit LDS read.
 #include "gpd_internal.hpp"
+#include <type_traits>
+#include <utility>
 
 namespace gpd {
 
@@ -235,18 +237,40 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? 3 : 1) void gemm
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>): a loop whose index is a
+// compile-time constant inside the body
+template <typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
 // k-values per LDS stage: HK = 32 for the plain kernel, 16 for the three-way split (three planes
 // per operand, still double-buffered); a row of a tile is HK + 8 bf16 elements apart from the
 // next (80 or 48 bytes: the 128-bit reads of 8 consecutive rows fall on 32 different banks)
 constexpr int hk_of(int split) { return split == 1 ? 32 : 16; }
 
-enum { SRC_F32_KC = 0, SRC_BF16_KC = 1, SRC_F32_RC = 2, SRC_BF16_RC = 3 };
+
+// SRC_BF16P_KB: the fp32 operand already split into three bf16 planes (hi, mid, lo), each stored
+// k-blocked, [k / 16][row][k % 16]: one stage of a tile is one contiguous run per plane
+enum { SRC_F32_KC = 0, SRC_BF16_KC = 1, SRC_F32_RC = 2, SRC_BF16_RC = 3, SRC_BF16P_KB = 4 };
+
+// register sets of staged global loads the deep pipeline keeps (R - 1 stages ahead of the one
+// being multiplied, plus the one being written to LDS): plane sources need 6 registers per
+// operand and stage, fp32 sources 8 to 16
+constexpr int kRingOf(int asrc, int bsrc, int tbm) {
+  return (asrc == SRC_BF16P_KB && bsrc == SRC_BF16P_KB) ? (tbm <= 128 ? 4 : 2) : 2;
+}
 
 struct HGemmParams {
   const void* A; const void* B; float* C;
   int M, N, K;
   int64_t lda, ldb, ldc;
   int64_t sA, sB, sC;
+  int64_t planeA, planeB;    // elements between the planes of a SRC_BF16P_KB operand
   int tiles_m, tiles_n, total_tiles, tiles_per_xcd;
   float alpha, beta;
 };
@@ -291,9 +315,11 @@ template <int ROWS, int NT, int HK> struct HStage<SRC_F32_KC, ROWS, NT, HK> { fl
 template <int ROWS, int NT, int HK> struct HStage<SRC_BF16_KC, ROWS, NT, HK> { uint4 v[(ROWS * (HK / 8) + NT - 1) / NT]; };
 template <int ROWS, int NT, int HK> struct HStage<SRC_F32_RC, ROWS, NT, HK> { float4 v[ROWS * HK / 8 / NT][2]; };
 template <int ROWS, int NT, int HK> struct HStage<SRC_BF16_RC, ROWS, NT, HK> { uint4 v[(ROWS * HK / 16 + NT - 1) / NT][2]; };
+template <int ROWS, int NT, int HK> struct HStage<SRC_BF16P_KB, ROWS, NT, HK> { uint4 v[(ROWS * (HK / 8) + NT - 1) / NT][3]; };
 
 // base: start of the operand for this batch entry; "row" is the m (or n) index, k the
-// contraction index.  KC sources are [row][k] with leading dimension ld, RC sources [k][row].
+// contraction index.  KC sources are [row][k] with leading dimension ld, RC sources [k][row];
+// for the k-blocked planes ld is the distance between planes and nk a multiple of 16.
 template <int SRC, int MODE, int ROWS, int NT, int HK>
 __device__ __forceinline__ void hload(HStage<SRC, ROWS, NT, HK>& st, const void* base, int64_t ld, int row0,
                                       int k0, int nrows, int nk, int tid) {
@@ -315,6 +341,20 @@ __device__ __forceinline__ void hload(HStage<SRC, ROWS, NT, HK>& st, const void*
       const bool mine = f < ROWS * (HK / 8);
       const int nv = !mine ? 0 : ((MODE == 0) ? 8 : (row < nrows ? clampi(nk - k, 0, 8) : 0));
       st.v[q] = (nv > 0) ? load8h<MODE>(b + (int64_t)row * ld + k, nv) : make_uint4(0u, 0u, 0u, 0u);
+    }
+  } else if constexpr (SRC == SRC_BF16P_KB) {
+    static_assert(HK == 16, "a stage is one 16-k block");
+    // one stage of a tile is ROWS * 32 contiguous bytes per plane: a uniform base (scalar
+    // registers) plus 16 bytes per item, the same 32-bit lane offset for every plane and stage
+    const char* ub = (const char*)base + (((int64_t)(k0 >> 4) * nrows + row0) << 5);
+#pragma unroll
+    for (int q = 0; q < (ROWS * 2 + NT - 1) / NT; ++q) {
+      const int f = tid + NT * q;
+      const bool mine = ((ROWS * 2) % NT == 0 || f < ROWS * 2) && (MODE == 0 || (row0 + (f >> 1) < nrows && k0 < nk));
+      const uint32_t lo = 16u * (uint32_t)f;
+#pragma unroll
+      for (int pl = 0; pl < 3; ++pl)
+        st.v[q][pl] = mine ? *reinterpret_cast<const uint4*>(ub + 2 * pl * ld + lo) : make_uint4(0u, 0u, 0u, 0u);
     }
   } else if constexpr (SRC == SRC_F32_RC) {
     const float* b = (const float*)base;
@@ -365,7 +405,7 @@ __device__ __forceinline__ void split3_pack(float x0, float x1, uint32_t (&w)[3]
 template <int SRC, int ROWS, int NT, int HK>
 constexpr int hstage_items() {
   return SRC == SRC_F32_KC ? ROWS * (HK / 4) / NT
-       : SRC == SRC_BF16_KC ? (ROWS * (HK / 8) + NT - 1) / NT
+       : (SRC == SRC_BF16_KC || SRC == SRC_BF16P_KB) ? (ROWS * (HK / 8) + NT - 1) / NT
        : SRC == SRC_F32_RC ? ROWS * HK / 8 / NT
                            : (ROWS * HK / 16 + NT - 1) / NT;
 }
@@ -375,9 +415,16 @@ template <int SRC, int ROWS, int NT, int SPLIT, int PLANE, int HK>
 __device__ __forceinline__ void hstore_item(const HStage<SRC, ROWS, NT, HK>& st, int q,
                                             uint16_t* __restrict__ lds, int tid) {
   constexpr int HSTRIDE = HK + 8;
-  static_assert(SPLIT == 1 || SRC == SRC_F32_KC || SRC == SRC_F32_RC, "only fp32 sources are split");
+  static_assert((SPLIT == 3) == (SRC == SRC_BF16P_KB) || SRC == SRC_F32_KC || SRC == SRC_F32_RC,
+                "fp32 sources are split on the way to LDS, plane sources arrive split");
   const int f = tid + NT * q;
-  if constexpr (SRC == SRC_F32_KC) {
+  if constexpr (SRC == SRC_BF16P_KB) {
+    if ((ROWS * 2) % NT == 0 || f < ROWS * 2) {
+#pragma unroll
+      for (int pl = 0; pl < 3; ++pl)
+        *reinterpret_cast<uint4*>(lds + pl * PLANE + (f >> 1) * HSTRIDE + 8 * (f & 1)) = st.v[q][pl];
+    }
+  } else if constexpr (SRC == SRC_F32_KC) {
     uint16_t* dst = lds + (f / (HK / 4)) * HSTRIDE + 4 * (f % (HK / 4));
     if constexpr (SPLIT == 1) {
       uint2 w;
@@ -469,8 +516,10 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
   const int tn = rem - tm * g.tiles_n;
   const int m0 = tm * TBM, n0 = tn * TBN;
 
-  constexpr int A_ES = (ASRC == SRC_BF16_KC || ASRC == SRC_BF16_RC) ? 2 : 4;
-  constexpr int B_ES = (BSRC == SRC_BF16_KC || BSRC == SRC_BF16_RC) ? 2 : 4;
+  constexpr int A_ES = (ASRC == SRC_BF16_KC || ASRC == SRC_BF16_RC || ASRC == SRC_BF16P_KB) ? 2 : 4;
+  constexpr int B_ES = (BSRC == SRC_BF16_KC || BSRC == SRC_BF16_RC || BSRC == SRC_BF16P_KB) ? 2 : 4;
+  const int64_t lda = ASRC == SRC_BF16P_KB ? g.planeA : g.lda;
+  const int64_t ldb = BSRC == SRC_BF16P_KB ? g.planeB : g.ldb;
   const char* A = (const char*)g.A + (int64_t)p * g.sA * A_ES;
   const char* B = (const char*)g.B + (int64_t)p * g.sB * B_ES;
   float* __restrict__ C = g.C + (int64_t)p * g.sC;
@@ -491,7 +540,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
   // Read-modify-write of the output tile (the coded update): with two workgroups of this shape on
   // a CU there are registers to spare, so the old values are requested before the first stage
   // and have arrived long before the epilogue needs them.
-  constexpr bool kPrefetchC = SPLIT == 3 && MI * NJ <= 4;
+  constexpr bool kPrefetchC = SPLIT == 3 && MI * NJ <= 4 && ASRC != SRC_BF16P_KB;
   float oldc[kPrefetchC ? MI * NJ * 16 : 1];
   if constexpr (kPrefetchC) {
     if (g.beta != 0.f) {
@@ -514,22 +563,22 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
 
   const int nchunks = (g.K + HK - 1) / HK;
   auto kof = [&](int c) { return c * HK; };
-  HStage<ASRC, TBM, NT, HK> sa;
-  HStage<BSRC, TBN, NT, HK> sb;
-  hload<ASRC, MODE, TBM, NT, HK>(sa, A, g.lda, m0, kof(0), g.M, g.K, tid);
-  hload<BSRC, MODE, TBN, NT, HK>(sb, B, g.ldb, n0, kof(0), g.N, g.K, tid);
-  hstore<ASRC, TBM, NT, SPLIT, PA, HK>(sa, lds_a[0], tid);
-  hstore<BSRC, TBN, NT, SPLIT, PB, HK>(sb, lds_b[0], tid);
   union Frag { uint4 u; bf16x8 v; };
 
   constexpr bool kDeep = SPLIT == 3 || WGM * WGN == 8;
   if constexpr (!kDeep) {
+    HStage<ASRC, TBM, NT, HK> sa;
+    HStage<BSRC, TBN, NT, HK> sb;
+    hload<ASRC, MODE, TBM, NT, HK>(sa, A, lda, m0, kof(0), g.M, g.K, tid);
+    hload<BSRC, MODE, TBN, NT, HK>(sb, B, ldb, n0, kof(0), g.N, g.K, tid);
+    hstore<ASRC, TBM, NT, SPLIT, PA, HK>(sa, lds_a[0], tid);
+    hstore<BSRC, TBN, NT, SPLIT, PB, HK>(sb, lds_b[0], tid);
     __syncthreads();
     for (int c = 0; c < nchunks; ++c) {
       const int cur = c & 1;
       if (c + 1 < nchunks) {
-        hload<ASRC, MODE, TBM, NT, HK>(sa, A, g.lda, m0, kof(c + 1), g.M, g.K, tid);
-        hload<BSRC, MODE, TBN, NT, HK>(sb, B, g.ldb, n0, kof(c + 1), g.N, g.K, tid);
+        hload<ASRC, MODE, TBM, NT, HK>(sa, A, lda, m0, kof(c + 1), g.M, g.K, tid);
+        hload<BSRC, MODE, TBN, NT, HK>(sb, B, ldb, n0, kof(c + 1), g.N, g.K, tid);
       }
       const uint16_t* __restrict__ as = lds_a[cur];
       const uint16_t* __restrict__ bs = lds_b[cur];
@@ -554,7 +603,120 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
       }
       __syncthreads();
     }
-  } else if constexpr (SPLIT == 1) {
+  } else if constexpr (ASRC == SRC_BF16P_KB && BSRC == SRC_BF16P_KB) {
+    // Operands that arrive split: nothing to convert, so the loop is matrix instructions, LDS
+    // traffic and global loads only, and every latency is taken off the critical path:
+    //  - global loads run R - 1 stages ahead, in R register sets that are addressed statically
+    //    (the loop is unrolled R times; rotating the sets by copies would make every iteration
+    //    wait for the loads it has just issued);
+    //  - the fragments of stage c + 1 are read from LDS right after the barrier that publishes
+    //    them, in a second set of fragment registers, while the last two of the six partial
+    //    products of stage c are still being issued.
+    static_assert(SPLIT == 3 && HK == 16, "plane operands are multiplied as six partial products");
+    constexpr int R = kRingOf(ASRC, BSRC, TBM);
+    constexpr int IA = hstage_items<ASRC, TBM, NT, HK>(), IB = hstage_items<BSRC, TBN, NT, HK>();
+    constexpr int PER = (IA + IB + 3) / 4;                   // LDS-write items after each of the first four groups
+    HStage<ASRC, TBM, NT, HK> sa[R];
+    HStage<BSRC, TBN, NT, HK> sb[R];
+    hload<ASRC, MODE, TBM, NT, HK>(sa[0], A, lda, m0, kof(0), g.M, g.K, tid);
+    hload<BSRC, MODE, TBN, NT, HK>(sb[0], B, ldb, n0, kof(0), g.N, g.K, tid);
+#pragma unroll
+    for (int u = 1; u < R; ++u) {
+      if (u < nchunks) {
+        hload<ASRC, MODE, TBM, NT, HK>(sa[u], A, lda, m0, kof(u), g.M, g.K, tid);
+        hload<BSRC, MODE, TBN, NT, HK>(sb[u], B, ldb, n0, kof(u), g.N, g.K, tid);
+      }
+    }
+    hstore<ASRC, TBM, NT, SPLIT, PA, HK>(sa[0], lds_a[0], tid);
+    hstore<BSRC, TBN, NT, SPLIT, PB, HK>(sb[0], lds_b[0], tid);
+    __syncthreads();
+
+    struct FragSet { Frag a[MI][3]; Frag b2[NJ]; };          // all planes of A, the lo plane of B
+    auto read_frags = [&](FragSet& f, int buf) __attribute__((always_inline)) {
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int pl = 0; pl < 3; ++pl)
+          f.a[i][pl].u = *reinterpret_cast<const uint4*>(lds_a[buf] + pl * PA + (wm + 32 * i + li) * HSTRIDE + 8 * lg);
+#pragma unroll
+      for (int j = 0; j < NJ; ++j)
+        f.b2[j].u = *reinterpret_cast<const uint4*>(lds_b[buf] + 2 * PB + (wn + 32 * j + li) * HSTRIDE + 8 * lg);
+    };
+    FragSet fr[2];
+    read_frags(fr[0], 0);
+
+    // one stage c: la / lb is the register set stage c has left (stage c + R is loaded into it if
+    // load), ca / cb the set that holds stage c + 1 (written to LDS if next), fc / fn the
+    // fragments of stage c and c + 1
+    auto stage = [&](HStage<ASRC, TBM, NT, HK>& la, HStage<BSRC, TBN, NT, HK>& lb,
+                     const HStage<ASRC, TBM, NT, HK>& ca, const HStage<BSRC, TBN, NT, HK>& cb, const FragSet& fc,
+                     FragSet& fn, int c, bool load, bool next) __attribute__((always_inline)) {
+      const int cur = c & 1;
+      if (load) {
+        hload<ASRC, MODE, TBM, NT, HK>(la, A, lda, m0, kof(c + R), g.M, g.K, tid);
+        hload<BSRC, MODE, TBN, NT, HK>(lb, B, ldb, n0, kof(c + R), g.N, g.K, tid);
+      }
+      const uint16_t* __restrict__ bs = lds_b[cur];
+      auto put = [&](int group) __attribute__((always_inline)) {
+        if (next) {
+#pragma unroll
+          for (int it = group * PER; it < (group + 1) * PER && it < IA + IB; ++it) {
+            if (it < IA) hstore_item<ASRC, TBM, NT, SPLIT, PA, HK>(ca, it, lds_a[cur ^ 1], tid);
+            else hstore_item<BSRC, TBN, NT, SPLIT, PB, HK>(cb, it - IA, lds_b[cur ^ 1], tid);
+          }
+        }
+      };
+      auto products = [&](int pa, const Frag (&fb)[NJ]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+          for (int j = 0; j < NJ; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fc.a[i][pa].v, fb[j].v, acc[i][j], 0, 0, 0);
+      };
+      Frag fb1[NJ], fb0[NJ];
+#pragma unroll
+      for (int j = 0; j < NJ; ++j)
+        fb1[j].u = *reinterpret_cast<const uint4*>(bs + PB + (wn + 32 * j + li) * HSTRIDE + 8 * lg);
+      products(0, fc.b2);                       // hi * lo
+      put(0);
+#pragma unroll
+      for (int j = 0; j < NJ; ++j)
+        fb0[j].u = *reinterpret_cast<const uint4*>(bs + (wn + 32 * j + li) * HSTRIDE + 8 * lg);
+      products(1, fb1);                         // mid * mid
+      put(1);
+      products(0, fb1);                         // hi * mid
+      put(2);
+      products(2, fb0);                         // lo * hi
+      put(3);
+      __syncthreads();
+      if (next) read_frags(fn, cur ^ 1);
+      products(1, fb0);                         // mid * hi
+      products(0, fb0);                         // hi * hi
+    };
+
+    // Steady state: every iteration loads, so the number of younger loads in flight when a
+    // stage is needed is the same each time and the wait for it leaves them in flight (the
+    // load counter is relative: code shared with the tail, where fewer loads follow, would
+    // have to wait for everything).  The host only takes this path when the number of stages
+    // is a multiple of R, and R is even.
+    static_assert(R % 2 == 0, "the fragment sets alternate with the stage parity");
+    int c0 = 0;
+    for (; c0 + 2 * R <= nchunks; c0 += R) {
+#pragma unroll
+      for (int u = 0; u < R; ++u)
+        stage(sa[u], sb[u], sa[(u + 1) % R], sb[(u + 1) % R], fr[u & 1], fr[(u + 1) & 1], c0 + u, true, true);
+    }
+#pragma unroll
+    for (int u = 0; u < R; ++u)
+      stage(sa[u], sb[u], sa[(u + 1) % R], sb[(u + 1) % R], fr[u & 1], fr[(u + 1) & 1], c0 + u, false, u + 1 < R);
+  } else {
+  HStage<ASRC, TBM, NT, HK> sa;
+  HStage<BSRC, TBN, NT, HK> sb;
+  hload<ASRC, MODE, TBM, NT, HK>(sa, A, lda, m0, kof(0), g.M, g.K, tid);
+  hload<BSRC, MODE, TBN, NT, HK>(sb, B, ldb, n0, kof(0), g.N, g.K, tid);
+  hstore<ASRC, TBM, NT, SPLIT, PA, HK>(sa, lds_a[0], tid);
+  hstore<BSRC, TBN, NT, SPLIT, PB, HK>(sb, lds_b[0], tid);
+  if constexpr (SPLIT == 1) {
     // Three stages in flight (8 wavefronts with 256 registers each): stage c is multiplied from
     // LDS, stage c + 1 (loaded one iteration ago) is converted and written to the other LDS
     // buffer after each half of the products, the global loads of stage c + 2 are issued.  Two
@@ -563,8 +725,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
     constexpr int IA = hstage_items<ASRC, TBM, NT, HK>(), IB = hstage_items<BSRC, TBN, NT, HK>();
     constexpr int HALF = (IA + IB + 1) / 2;
     if (nchunks > 1) {
-      hload<ASRC, MODE, TBM, NT, HK>(sa, A, g.lda, m0, kof(1), g.M, g.K, tid);
-      hload<BSRC, MODE, TBN, NT, HK>(sb, B, g.ldb, n0, kof(1), g.N, g.K, tid);
+      hload<ASRC, MODE, TBM, NT, HK>(sa, A, lda, m0, kof(1), g.M, g.K, tid);
+      hload<BSRC, MODE, TBN, NT, HK>(sb, B, ldb, n0, kof(1), g.N, g.K, tid);
     }
     __syncthreads();
     for (int c = 0; c < nchunks; ++c) {
@@ -572,8 +734,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
       HStage<ASRC, TBM, NT, HK> na = sa;
       HStage<BSRC, TBN, NT, HK> nb = sb;
       if (c + 2 < nchunks) {
-        hload<ASRC, MODE, TBM, NT, HK>(na, A, g.lda, m0, kof(c + 2), g.M, g.K, tid);
-        hload<BSRC, MODE, TBN, NT, HK>(nb, B, g.ldb, n0, kof(c + 2), g.N, g.K, tid);
+        hload<ASRC, MODE, TBM, NT, HK>(na, A, lda, m0, kof(c + 2), g.M, g.K, tid);
+        hload<BSRC, MODE, TBN, NT, HK>(nb, B, ldb, n0, kof(c + 2), g.N, g.K, tid);
       }
       const bool conv = c + 1 < nchunks;
       const uint16_t* __restrict__ as = lds_a[cur];
@@ -613,8 +775,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
     constexpr int IA = hstage_items<ASRC, TBM, NT, HK>(), IB = hstage_items<BSRC, TBN, NT, HK>();
     static_assert(IA + IB <= 6, "one conversion slot per partial product");
     if (nchunks > 1) {
-      hload<ASRC, MODE, TBM, NT, HK>(sa, A, g.lda, m0, kof(1), g.M, g.K, tid);
-      hload<BSRC, MODE, TBN, NT, HK>(sb, B, g.ldb, n0, kof(1), g.N, g.K, tid);
+      hload<ASRC, MODE, TBM, NT, HK>(sa, A, lda, m0, kof(1), g.M, g.K, tid);
+      hload<BSRC, MODE, TBN, NT, HK>(sb, B, ldb, n0, kof(1), g.N, g.K, tid);
     }
     __syncthreads();
     for (int c = 0; c < nchunks; ++c) {
@@ -622,8 +784,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
       HStage<ASRC, TBM, NT, HK> na = sa;
       HStage<BSRC, TBN, NT, HK> nb = sb;
       if (c + 2 < nchunks) {
-        hload<ASRC, MODE, TBM, NT, HK>(na, A, g.lda, m0, kof(c + 2), g.M, g.K, tid);
-        hload<BSRC, MODE, TBN, NT, HK>(nb, B, g.ldb, n0, kof(c + 2), g.N, g.K, tid);
+        hload<ASRC, MODE, TBM, NT, HK>(na, A, lda, m0, kof(c + 2), g.M, g.K, tid);
+        hload<BSRC, MODE, TBN, NT, HK>(nb, B, ldb, n0, kof(c + 2), g.N, g.K, tid);
       }
       const bool conv = c + 1 < nchunks;
       const uint16_t* __restrict__ as = lds_a[cur];
@@ -660,34 +822,47 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
       sb = nb;
     }
   }
+  }
 
+  // Read-modify-write of the output tile.  All old values of a group of 32 x 32 blocks are
+  // requested before any is used: one memory latency per group.  Where two workgroups of four
+  // wavefronts share a CU the group is the whole tile (the registers of the staging sets and
+  // fragments are free by now), elsewhere one block.
+  constexpr int NB = MI * NJ, GB = (SPLIT == 3 && MI * NJ <= 4) ? 4 : 1;
+  static_assert(NB % GB == 0, "whole groups of blocks");
 #pragma unroll
-  for (int i = 0; i < MI; ++i)
+  for (int b0 = 0; b0 < NB; b0 += GB) {
+    float old[GB][16];
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) {
+    for (int bb = 0; bb < GB; ++bb) {
+      const int i = (b0 + bb) / NJ, j = (b0 + bb) % NJ;
       const int col = n0 + wn + 32 * j + li;
-      // with beta != 0 all 16 old values of the block are requested before any is used
-      float old[16];
       if constexpr (kPrefetchC) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) old[v] = oldc[(i * NJ + j) * 16 + v];
+        for (int v = 0; v < 16; ++v) old[bb][v] = oldc[(i * NJ + j) * 16 + v];
       } else if (g.beta != 0.f) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * lg + (v & 3);
-          old[v] = (MODE == 0 || (row < g.M && col < g.N)) ? C[(int64_t)row * g.ldc + col] : 0.f;
+          old[bb][v] = (MODE == 0 || (row < g.M && col < g.N)) ? C[(int64_t)row * g.ldc + col] : 0.f;
         }
       } else {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) old[v] = 0.f;
+        for (int v = 0; v < 16; ++v) old[bb][v] = 0.f;
       }
+    }
+#pragma unroll
+    for (int bb = 0; bb < GB; ++bb) {
+      const int i = (b0 + bb) / NJ, j = (b0 + bb) % NJ;
+      const int col = n0 + wn + 32 * j + li;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * lg + (v & 3);
         if (MODE == 0 || (row < g.M && col < g.N))
-          C[(int64_t)row * g.ldc + col] = fmaf(g.beta, old[v], g.alpha * acc[i][j][v]);
+          C[(int64_t)row * g.ldc + col] = fmaf(g.beta, old[bb][v], g.alpha * acc[i][j][v]);
       }
     }
+  }
 }
 
 template <int ASRC, int BSRC, int SPLIT>
@@ -696,7 +871,8 @@ gpd_status_t launch_bf16_t(hipStream_t stream, HGemmParams p, int64_t batch, boo
   // (the split kernel with a short contraction is dominated by the read-modify-write of its
   // output tile: two small workgroups per CU overlap one's epilogue with the other's products)
   const bool large = aligned && p.M % 256 == 0 && p.N % 256 == 0 && p.K % hk_of(SPLIT) == 0 && p.K > 0 &&
-                     (int64_t)(p.M / 256) * (p.N / 256) * batch >= 256 && (SPLIT == 1 || p.K >= 1024);
+                     (int64_t)(p.M / 256) * (p.N / 256) * batch >= 256 && (SPLIT == 1 || p.K >= 1024) &&
+                     ASRC != SRC_BF16P_KB;     // (plane operands: the small shape only)
   const int tbm = large ? 256 : 128, tbn = large ? 256 : 128;
   p.tiles_m = (p.M + tbm - 1) / tbm;
   p.tiles_n = (p.N + tbn - 1) / tbn;
@@ -709,7 +885,9 @@ gpd_status_t launch_bf16_t(hipStream_t stream, HGemmParams p, int64_t batch, boo
     // the split kernel keeps three planes of A in registers, and a kernel that streams fp32
     // weights needs two stages of global loads in flight: 8 wavefronts of 128 x 64 (256
     // registers each) instead of 16 of 64 x 64 (128 registers)
-    if constexpr (SPLIT == 3 || ASRC == SRC_F32_KC || ASRC == SRC_F32_RC)
+    if constexpr (ASRC == SRC_BF16P_KB)
+      return fail(GPD_E_UNSUPPORTED, "gemm: no large shape for plane operands");
+    else if constexpr (SPLIT == 3 || ASRC == SRC_F32_KC || ASRC == SRC_F32_RC)
       hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 0, 256, 256, 2, 4, SPLIT>), grid, dim3(512), 0, stream, p);
     else
       hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 0, 256, 256, 4, 4, SPLIT>), grid, dim3(1024), 0, stream, p);
@@ -766,16 +944,28 @@ gpd_status_t launch_gemm(hipStream_t stream, const GemmArgs& a) {
     return fail(GPD_E_INVALID, "gemm: bf16 operands need the bf16 multiply");
   if (a.split3 && (!a.mfma_bf16 || a.a_bf16 || a.b_bf16))
     return fail(GPD_E_INVALID, "gemm: the three-way split needs fp32 operands and the bf16 multiply");
+  const bool planes = a.planeA != 0 || a.planeB != 0;
+  if (planes) {
+    if (!a.split3 || a.planeA <= 0 || a.planeB <= 0)
+      return fail(GPD_E_INVALID, "gemm: split planes need the three-way split, for both operands");
+    if (a.K % 64 || a.K < 64 || a.planeA % 8 || a.planeB % 8 || a.strideA % 8 || a.strideB % 8 ||
+        (uintptr_t)a.A % 16 || (uintptr_t)a.B % 16)
+      return fail(GPD_E_SHAPE, "gemm: split planes need K %% 64 == 0 and 16-byte aligned planes");
+    if (a.batch > 1 && (a.strideA < a.M * a.K || a.strideB < a.N * a.K))
+      return fail(GPD_E_SHAPE, "gemm: batch stride of a plane operand overlaps");
+    if (a.planeA < (a.batch - 1) * a.strideA + a.M * a.K || a.planeB < (a.batch - 1) * a.strideB + a.N * a.K)
+      return fail(GPD_E_SHAPE, "gemm: planes overlap");
+  }
   if (a.mfma_bf16 && !a.split3 && (a.transB || (a.transA && a.a_bf16)))
     return fail(GPD_E_UNSUPPORTED, "gemm: this operand layout has no bf16 kernel");
   // operand shapes must match what the kernel and its grid assume
   const int64_t a_rows = a.transA ? a.K : a.M, a_cols = a.transA ? a.M : a.K;
   const int64_t b_rows = a.transB ? a.N : a.K, b_cols = a.transB ? a.K : a.N;
-  if (a.lda < a_cols || a.ldb < b_cols || a.ldc < a.N)
+  if ((!planes && (a.lda < a_cols || a.ldb < b_cols)) || a.ldc < a.N)
     return fail(GPD_E_SHAPE, "gemm: leading dimension smaller than the row length");
-  if (a.batch > 1 && (a.strideA < (a_rows - 1) * a.lda + a_cols && a.strideA != 0))
+  if (!planes && a.batch > 1 && (a.strideA < (a_rows - 1) * a.lda + a_cols && a.strideA != 0))
     return fail(GPD_E_SHAPE, "gemm: batch stride of A overlaps");
-  if (a.batch > 1 && (a.strideB < (b_rows - 1) * a.ldb + b_cols && a.strideB != 0))
+  if (!planes && a.batch > 1 && (a.strideB < (b_rows - 1) * a.ldb + b_cols && a.strideB != 0))
     return fail(GPD_E_SHAPE, "gemm: batch stride of B overlaps");
   if (a.batch > 1 && a.strideC < (a.M - 1) * a.ldc + a.N)
     return fail(GPD_E_SHAPE, "gemm: batch stride of C overlaps");
@@ -787,6 +977,8 @@ gpd_status_t launch_gemm(hipStream_t stream, const GemmArgs& a) {
     h.lda = a.lda; h.ldb = a.ldb; h.ldc = a.ldc;
     h.sA = a.strideA; h.sB = a.strideB; h.sC = a.strideC;
     h.alpha = a.alpha; h.beta = a.beta;
+    h.planeA = a.planeA; h.planeB = a.planeB;
+    if (planes) return launch_bf16_t<SRC_BF16P_KB, SRC_BF16P_KB, 3>(stream, h, a.batch, true);
     const int a_es = a.a_bf16 ? 2 : 4, b_es = a.b_bf16 ? 2 : 4;
     const bool al = ((uintptr_t)a.A % 16 == 0) && ((uintptr_t)a.B % 16 == 0) &&
                     (a.lda * a_es) % 16 == 0 && (a.ldb * b_es) % 16 == 0 &&

@@ -158,10 +158,12 @@ struct ScreenArgs {               // soft-error screen fused into the decode pas
   int32_t cap = 0;
 };
 
-// out_q[r][c] = sum_s coef[q][s] in_s[r][c]; blocks are rows x cols; fp32 in; OutT fp32/bf16.
+// out_q[r][c] = sum_s coef[q][s] in_s[r][c]; blocks are rows x cols; fp32 in.  out_kind: 0 fp32,
+// 1 bf16, 2 the fp32 value as three bf16 planes (hi, mid, lo) out_plane elements apart, each
+// block k-blocked ([cols / 16][rows][16]; cols a multiple of 16, out_ld = cols, no block limits).
 gpd_status_t launch_combine(hipStream_t stream, const CombineTable& t, const float* in,
-                            int64_t in_ld, void* out, int64_t out_ld, bool out_bf16,
-                            int64_t rows, int64_t cols, const ScreenArgs& screen);
+                            int64_t in_ld, void* out, int64_t out_ld, int out_kind,
+                            int64_t rows, int64_t cols, const ScreenArgs& screen, int64_t out_plane = 0);
 
 struct GemmArgs {
   const void* A = nullptr;        // op(A) is M x K
@@ -177,6 +179,11 @@ struct GemmArgs {
   bool mfma_bf16 = false;         // multiply in bf16 (fp32 inputs are rounded on the way)
   bool split3 = false;            // with mfma_bf16 and fp32 operands: each operand as the sum of three
                                   // bf16 values, six partial products: fp32-level accuracy
+  // with split3: the operand is already stored as three bf16 planes (hi, mid, lo), plane stride
+  // in elements (0: fp32 operand), each batch entry k-blocked: [K / 16][rows][16] with rows = M
+  // (N for B); needs K % 64 == 0, ignores lda / transA (ldb / transB); the batch stride then
+  // counts bf16 elements of one plane
+  int64_t planeA = 0, planeB = 0;
   float alpha = 1.f, beta = 0.f;  // C = beta*C + alpha*op(A)op(B)
 };
 gpd_status_t launch_gemm(hipStream_t stream, const GemmArgs& g);

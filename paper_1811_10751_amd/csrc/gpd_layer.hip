@@ -245,6 +245,7 @@ struct gpd_layer {
   // workspace layout (byte offsets)
   size_t off_Xt = 0, off_St = 0, off_Dt = 0, off_Ct = 0, off_Dh = 0, off_Xh = 0, off_part = 0,
          off_dec = 0, ws_bytes = 0;
+  bool upd_planes = false;         // update operands stored as three bf16 planes
   int nchunks = 0;
   int64_t flag_cap = 0, loc_cap = 0;
   size_t dec_bytes = 0;
@@ -330,8 +331,12 @@ extern "C" gpd_status_t gpd_layer_create(const gpd_layer_desc_t* d, gpd_layer_t*
   L->off_St = take((size_t)P * L->wr * L->nb1 * 4);
   L->off_Dt = take((size_t)P * L->wr * L->nb2 * 4);
   L->off_Ct = take((size_t)P * L->wc * L->nb2 * 4);
-  L->off_Dh = take((size_t)P * L->wr * d->batch * 4);
-  L->off_Xh = take((size_t)P * L->wc * d->batch * 4);
+  // update operands: fp32 stacks, or (layers whose update runs as six bf16 partial products, batch
+  // a multiple of 64) three bf16 planes hi / mid / lo written by the encode itself
+  L->upd_planes = d->worker_dtype != GPD_F32 && d->batch % 64 == 0;
+  const size_t ues = L->upd_planes ? 6 : 4;
+  L->off_Dh = take((size_t)P * L->wr * d->batch * ues);
+  L->off_Xh = take((size_t)P * L->wc * d->batch * ues);
   L->off_part = take((size_t)P * L->nchunks * L->wc * L->nb2 * 4);
   const int64_t ncw = std::max(L->wr * L->nb1, L->wc * L->nb2);
   decode_workspace_layout(ncw, &L->flag_cap, &L->loc_cap, &L->dec_bytes);
@@ -688,7 +693,8 @@ extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, floa
       return GPD_OK;
     }, s, &t);
     if (st != GPD_OK) return st;
-    st = launch_combine(s, t, Dlt, d.batch, Dh, d.batch, false, L->wr, d.batch, none);
+    st = launch_combine(s, t, Dlt, d.batch, Dh, d.batch, L->upd_planes ? 2 : 0, L->wr, d.batch, none,
+                        P * L->wr * d.batch);
     if (st != GPD_OK) return st;
     st = L->ring.cached("encXh", [&](HostCombineTable* hx) {
       *hx = encode_table(c.pts, L->eUx, c.n, 1, L->wc, d.batch, d.batch);
@@ -696,7 +702,8 @@ extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, floa
       return GPD_OK;
     }, s, &t);
     if (st != GPD_OK) return st;
-    st = launch_combine(s, t, X, d.batch, Xh, d.batch, false, L->wc, d.batch, none);
+    st = launch_combine(s, t, X, d.batch, Xh, d.batch, L->upd_planes ? 2 : 0, L->wc, d.batch, none,
+                        P * L->wc * d.batch);
     if (st != GPD_OK) return st;
   }
   const float keep = 1.f - decay;
@@ -739,6 +746,7 @@ extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, floa
     g.strideA = L->wr * d.batch; g.strideB = L->wc * d.batch; g.strideC = L->wr * L->wc;
     g.batch = P; g.alpha = eta; g.beta = keep;
     g.mfma_bf16 = g.split3 = bf16;
+    if (L->upd_planes) { g.planeA = P * L->wr * d.batch; g.planeB = P * L->wc * d.batch; }
     st = launch_gemm(s, g);
     if (st != GPD_OK) return st;
   }

@@ -60,6 +60,8 @@ LAYER_CASES = [
     (256, 384, 128, 2, 4, 1, 1, 32),      # cfg3's code, full tiles
     (300, 200, 24, 2, 4, 1, 1, 32),       # ragged tiles
     (130, 260, 48, 2, 2, 2, 3, 20),       # d1, d2 > 1
+    (300, 200, 64, 2, 4, 1, 1, 32),       # update operands as bf16 planes, ragged tiles, one ring of stages
+    (512, 1024, 192, 2, 4, 1, 1, 32),     # planes, full tiles, steady-state loop and tail
 ]
 
 
@@ -145,7 +147,19 @@ def test_cfg3_full_size_one_layer_step():
     C, _ = G.gpd_coded_layer_step(L, G.GPD_STEP_BACKWARD_UPDATE, Wt, to_dev(X), Dlt=to_dev(D), eta=0.01, decay=0.0)
     torch.cuda.synchronize()
     Dt, Ct = to_np(L.view(2, DEV)), to_np(L.view(3, DEV))
-    Dh, Xh = to_np(L.view(4, DEV)), to_np(L.view(5, DEV))
+    # update operands as the kernel holds them: three bf16 planes, [P][batch/16][rows][16] each
+    def planes(v):
+        s = v.double().sum(0).permute(0, 2, 1, 3)          # [P][rows][batch/16][16]
+        return s.reshape(s.shape[0], s.shape[1], -1).cpu().numpy()
+    Dh, Xh = planes(L.view(4, DEV)), planes(L.view(5, DEV))
+    for p in sample_p:
+        # the planes add up to the encoded operands Dhat_p = sum_i Delta_i a_p^i, Xhat_p = sum_j X_j b_p^j
+        Dh_o = sum(D[i * (N // m):(i + 1) * (N // m)].astype(np.float64) * O.int_power(olp.points[p], olp.eUd[i])
+                   for i in range(m))
+        Xh_o = sum(X[j * (N // n):(j + 1) * (N // n)].astype(np.float64) * O.int_power(olp.points[p], olp.eUx[j])
+                   for j in range(n))
+        assert np.abs(Dh[p] - Dh_o).max() <= 2.0 ** -22 * np.abs(Dh_o).max()
+        assert np.abs(Xh[p] - Xh_o).max() <= 2.0 ** -22 * np.abs(Xh_o).max()
     for p in sample_p:
         # update on sampled rows: W~_p[r,:] + eta * Dh_p[r,:] Xh_p^T
         ref = Wt_rows_before[p] + np.float32(0.01) * (Dh[p][rows_s].astype(np.float64) @ Xh[p].astype(np.float64).T)

@@ -72,7 +72,8 @@ def test_split_handles_wide_dynamic_range():
     assert worst["split"] <= 4.0 * worst["fp32 MFMA"]
 
 
-LAYERS = [(256, 384, 128, 2, 4, 1, 1, 32), (300, 200, 24, 2, 4, 1, 1, 32), (130, 260, 48, 2, 2, 2, 3, 20)]
+LAYERS = [(256, 384, 128, 2, 4, 1, 1, 32), (300, 200, 24, 2, 4, 1, 1, 32), (130, 260, 48, 2, 2, 2, 3, 20),
+          (300, 200, 64, 2, 4, 1, 1, 32), (512, 1024, 192, 2, 4, 1, 1, 32)]
 
 
 @pytest.mark.parametrize("N_out,N_in,batch,m,n,d1,d2,P", LAYERS)
