@@ -709,6 +709,99 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
 #pragma unroll
     for (int u = 0; u < R; ++u)
       stage(sa[u], sb[u], sa[(u + 1) % R], sb[(u + 1) % R], fr[u & 1], fr[(u + 1) & 1], c0 + u, false, u + 1 < R);
+  } else if constexpr (MODE == 0 && SPLIT == 3) {
+    // fp32 operands in plain layouts, full tiles, an even number of stages (the host sends
+    // everything else to the bounds-checked kernel): two statically addressed register
+    // sets.  Stage c is multiplied from LDS buffer c & 1; stage c + 1, already in registers, is
+    // converted and written to the other buffer in pieces placed between the groups of matrix
+    // instructions (the plain ALU work runs while the matrix pipe is busy); the global loads of
+    // stage c + 2 go into the set stage c has left.
+    constexpr int R = 2;
+    constexpr int IA = hstage_items<ASRC, TBM, NT, HK>(), IB = hstage_items<BSRC, TBN, NT, HK>();
+    constexpr int GROUPS = SPLIT == 3 ? 6 : HK / 16;         // groups of MI x NJ matrix instructions per stage
+    constexpr int PER = (IA + IB + GROUPS - 1) / GROUPS;     // conversion items after each group
+    HStage<ASRC, TBM, NT, HK> sa[R];
+    HStage<BSRC, TBN, NT, HK> sb[R];
+    hload<ASRC, MODE, TBM, NT, HK>(sa[0], A, lda, m0, kof(0), g.M, g.K, tid);
+    hload<BSRC, MODE, TBN, NT, HK>(sb[0], B, ldb, n0, kof(0), g.N, g.K, tid);
+    hload<ASRC, MODE, TBM, NT, HK>(sa[1], A, lda, m0, kof(1), g.M, g.K, tid);
+    hload<BSRC, MODE, TBN, NT, HK>(sb[1], B, ldb, n0, kof(1), g.N, g.K, tid);
+    hstore<ASRC, TBM, NT, SPLIT, PA, HK>(sa[0], lds_a[0], tid);
+    hstore<BSRC, TBN, NT, SPLIT, PB, HK>(sb[0], lds_b[0], tid);
+    __syncthreads();
+
+    auto stage = [&](HStage<ASRC, TBM, NT, HK>& la, HStage<BSRC, TBN, NT, HK>& lb,
+                     const HStage<ASRC, TBM, NT, HK>& ca, const HStage<BSRC, TBN, NT, HK>& cb, int c, bool load,
+                     bool conv) __attribute__((always_inline)) {
+      const int cur = c & 1;
+      if (load) {
+        hload<ASRC, MODE, TBM, NT, HK>(la, A, lda, m0, kof(c + R), g.M, g.K, tid);
+        hload<BSRC, MODE, TBN, NT, HK>(lb, B, ldb, n0, kof(c + R), g.N, g.K, tid);
+      }
+      const uint16_t* __restrict__ as = lds_a[cur];
+      const uint16_t* __restrict__ bs = lds_b[cur];
+      auto convert = [&](int group) __attribute__((always_inline)) {
+        if (conv) {
+#pragma unroll
+          for (int it = group * PER; it < (group + 1) * PER && it < IA + IB; ++it) {
+            if (it < IA) hstore_item<ASRC, TBM, NT, SPLIT, PA, HK>(ca, it, lds_a[cur ^ 1], tid);
+            else hstore_item<BSRC, TBN, NT, SPLIT, PB, HK>(cb, it - IA, lds_b[cur ^ 1], tid);
+          }
+        }
+      };
+      if constexpr (SPLIT == 1) {
+#pragma unroll
+        for (int h = 0; h < HK / 16; ++h) {
+          Frag fa[MI], fb[NJ];
+#pragma unroll
+          for (int i = 0; i < MI; ++i)
+            fa[i].u = *reinterpret_cast<const uint4*>(as + (wm + 32 * i + li) * HSTRIDE + 16 * h + 8 * lg);
+#pragma unroll
+          for (int j = 0; j < NJ; ++j)
+            fb[j].u = *reinterpret_cast<const uint4*>(bs + (wn + 32 * j + li) * HSTRIDE + 16 * h + 8 * lg);
+#pragma unroll
+          for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i].v, fb[j].v, acc[i][j], 0, 0, 0);
+          convert(h);
+        }
+      } else {
+        Frag fa[MI][3];
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+          for (int pl = 0; pl < 3; ++pl)
+            fa[i][pl].u = *reinterpret_cast<const uint4*>(as + pl * PA + (wm + 32 * i + li) * HSTRIDE + 8 * lg);
+        int group = 0;
+#pragma unroll
+        for (int pb = 2; pb >= 0; --pb) {
+          Frag fb[NJ];
+#pragma unroll
+          for (int j = 0; j < NJ; ++j)
+            fb[j].u = *reinterpret_cast<const uint4*>(bs + pb * PB + (wn + 32 * j + li) * HSTRIDE + 8 * lg);
+#pragma unroll
+          for (int pa = 2 - pb; pa >= 0; --pa) {
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+              for (int j = 0; j < NJ; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i][pa].v, fb[j].v, acc[i][j], 0, 0, 0);
+            convert(group);
+            ++group;
+          }
+        }
+      }
+      __syncthreads();
+    };
+    // steady state with loads in every iteration (see above), then the last two stages
+    int c0 = 0;
+    for (; c0 + 2 * R <= nchunks; c0 += R) {
+      stage(sa[0], sb[0], sa[1], sb[1], c0, true, true);
+      stage(sa[1], sb[1], sa[0], sb[0], c0 + 1, true, true);
+    }
+    stage(sa[0], sb[0], sa[1], sb[1], c0, false, true);
+    stage(sa[1], sb[1], sa[0], sb[0], c0 + 1, false, false);
   } else {
   HStage<ASRC, TBM, NT, HK> sa;
   HStage<BSRC, TBN, NT, HK> sb;
@@ -870,7 +963,9 @@ gpd_status_t launch_bf16_t(hipStream_t stream, HGemmParams p, int64_t batch, boo
   // same two workgroup shapes as the fp32 kernel; the large one needs full aligned tiles
   // (the split kernel with a short contraction is dominated by the read-modify-write of its
   // output tile: two small workgroups per CU overlap one's epilogue with the other's products)
-  const bool large = aligned && p.M % 256 == 0 && p.N % 256 == 0 && p.K % hk_of(SPLIT) == 0 && p.K > 0 &&
+  // (the pipelined kernels for full tiles take an even number of stages)
+  const bool even = p.K % (2 * hk_of(SPLIT)) == 0;
+  const bool large = aligned && (SPLIT == 1 ? p.K % hk_of(SPLIT) == 0 : even) && p.M % 256 == 0 && p.N % 256 == 0 && p.K > 0 &&
                      (int64_t)(p.M / 256) * (p.N / 256) * batch >= 256 && (SPLIT == 1 || p.K >= 1024) &&
                      ASRC != SRC_BF16P_KB;     // (plane operands: the small shape only)
   const int tbm = large ? 256 : 128, tbn = large ? 256 : 128;
@@ -892,7 +987,8 @@ gpd_status_t launch_bf16_t(hipStream_t stream, HGemmParams p, int64_t batch, boo
     else
       hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 0, 256, 256, 4, 4, SPLIT>), grid, dim3(1024), 0, stream, p);
   } else {
-    const bool full = aligned && p.M % 128 == 0 && p.N % 128 == 0 && p.K % hk_of(SPLIT) == 0 && p.K > 0;
+    const bool full = aligned && p.M % 128 == 0 && p.N % 128 == 0 && p.K % hk_of(SPLIT) == 0 && p.K > 0 &&
+                      (SPLIT == 1 || even);
     if (full) hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 0, 128, 128, 2, 2, SPLIT>), grid, dim3(256), 0, stream, p);
     else hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 1, 128, 128, 2, 2, SPLIT>), grid, dim3(256), 0, stream, p);
   }
