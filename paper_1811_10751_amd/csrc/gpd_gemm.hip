@@ -389,6 +389,107 @@ __device__ __forceinline__ void hload(HStage<SRC, ROWS, NT, HK>& st, const void*
   }
 }
 
+// ---- loads of full tiles through buffer instructions
+//
+// The descriptor covers one batch entry of the operand, starting at the tile's first row (or
+// column); every access of a full tile lies inside it.  voff is the byte offset of the lane's
+// first item inside the stage at k = 0; the items of a lane, the two k-rows of a patch, the
+// three planes and the stage itself only add wavefront-uniform amounts.
+struct BufSrc {
+  __amdgpu_buffer_rsrc_t rsrc;
+  uint32_t voff;
+  uint32_t kblock;      // plane sources: bytes per 16-k block of all rows
+  uint32_t voff_lane;   // the lane's index in the workgroup
+};
+__device__ __forceinline__ uint4 bload16(const BufSrc& b, uint32_t soff) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(b.rsrc, b.voff, soff, 0);
+  return make_uint4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ float4 bload16f(const BufSrc& b, uint32_t soff) {
+  const uint4 v = bload16(b, soff);
+  return make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+}
+
+template <int SRC, int ROWS, int NT, int HK>
+__device__ __forceinline__ BufSrc make_bufsrc(const void* base, int64_t ld, int row0, int nrows, int nk, int tid) {
+  BufSrc b;
+  // bytes from the tile's origin to the end of the batch entry (the host has checked that this
+  // is below 2^31 for every operand that takes this path)
+  int64_t origin, extent;
+  if constexpr (SRC == SRC_F32_KC) {
+    origin = (int64_t)row0 * ld * 4; extent = (((int64_t)nrows - 1) * ld + nk) * 4;
+    b.voff = (uint32_t)(((tid / (HK / 4)) * ld + 4 * (tid % (HK / 4))) * 4);
+    static_assert(NT % (HK / 4) == 0, "items of a lane differ by whole rows");
+  } else if constexpr (SRC == SRC_BF16_KC) {
+    origin = (int64_t)row0 * ld * 2; extent = (((int64_t)nrows - 1) * ld + nk) * 2;
+    b.voff = (uint32_t)(((tid / (HK / 8)) * ld + 8 * (tid % (HK / 8))) * 2);
+    static_assert(NT % (HK / 8) == 0, "items of a lane differ by whole rows");
+  } else if constexpr (SRC == SRC_F32_RC) {
+    origin = (int64_t)row0 * 4; extent = (((int64_t)nk - 1) * ld + nrows) * 4;
+    b.voff = (uint32_t)((2 * ((tid & 3) + 4 * (tid / ROWS)) * ld + 4 * ((tid >> 2) % (ROWS / 4))) * 4);
+    static_assert(NT % ROWS == 0 || ROWS % NT == 0, "items of a lane differ by whole k-rows");
+  } else if constexpr (SRC == SRC_BF16_RC) {
+    origin = (int64_t)row0 * 2; extent = (((int64_t)nk - 1) * ld + nrows) * 2;
+    b.voff = (uint32_t)((2 * ((tid & 3) + 4 * (tid / (ROWS / 2))) * ld + 8 * ((tid >> 2) % (ROWS / 8))) * 2);
+  } else {
+    // ld: elements between planes
+    origin = (int64_t)row0 * 32; extent = 4 * ld + (int64_t)(nk >> 4) * nrows * 32;
+    b.voff = 16u * (uint32_t)tid;
+  }
+  b.kblock = (uint32_t)nrows * 32u;
+  b.voff_lane = (uint32_t)tid;
+  const int64_t left = extent - origin;
+  b.rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>((const char*)base + origin), 0,
+                                             (int)(left > 0x7fffffffLL ? 0x7fffffffLL : left), 0x00020000);
+  return b;
+}
+
+// the stage at k0 of a full tile (same items and order as hload)
+template <int SRC, int ROWS, int NT, int HK>
+__device__ __forceinline__ void hload_buf(HStage<SRC, ROWS, NT, HK>& st, const BufSrc& b, int64_t ld, int k0) {
+  if constexpr (SRC == SRC_F32_KC) {
+    const uint32_t step = (uint32_t)((NT / (HK / 4)) * ld * 4);
+#pragma unroll
+    for (int q = 0; q < ROWS * (HK / 4) / NT; ++q) st.v[q] = bload16f(b, (uint32_t)k0 * 4u + q * step);
+  } else if constexpr (SRC == SRC_BF16_KC) {
+    constexpr int COUNT = ROWS * (HK / 8);
+    const uint32_t step = (uint32_t)((NT / (HK / 8)) * ld * 2);
+#pragma unroll
+    for (int q = 0; q < (COUNT + NT - 1) / NT; ++q) {
+      const bool mine = COUNT % NT == 0 || (int)(b.voff_lane + NT * q) < COUNT;
+      st.v[q] = mine ? bload16(b, (uint32_t)k0 * 2u + q * step) : make_uint4(0u, 0u, 0u, 0u);
+    }
+  } else if constexpr (SRC == SRC_F32_RC) {
+    // f = tid + NT q: kp grows by 4 NT / ROWS per item (NT a multiple of ROWS)
+    static_assert(NT % ROWS == 0, "an item step is a whole number of k-pairs");
+    const uint32_t row_b = (uint32_t)(ld * 4), step = (uint32_t)(8 * (NT / ROWS)) * row_b;
+#pragma unroll
+    for (int q = 0; q < ROWS * HK / 8 / NT; ++q)
+#pragma unroll
+      for (int par = 0; par < 2; ++par) st.v[q][par] = bload16f(b, (uint32_t)k0 * row_b + q * step + par * row_b);
+  } else if constexpr (SRC == SRC_BF16_RC) {
+    static_assert(NT % (ROWS / 2) == 0, "an item step is a whole number of k-pairs");
+    constexpr int COUNT = ROWS * HK / 16;                   // patches per stage; lanes beyond idle
+    const uint32_t row_b = (uint32_t)(ld * 2), step = (uint32_t)(8 * (NT / (ROWS / 2))) * row_b;
+#pragma unroll
+    for (int q = 0; q < (COUNT + NT - 1) / NT; ++q) {
+      const bool mine = COUNT % NT == 0 || (int)(b.voff_lane + NT * q) < COUNT;
+#pragma unroll
+      for (int par = 0; par < 2; ++par)
+        st.v[q][par] = mine ? bload16(b, (uint32_t)k0 * row_b + q * step + par * row_b) : make_uint4(0u, 0u, 0u, 0u);
+    }
+  } else {
+    static_assert((ROWS * 2) % NT == 0, "every lane has the same number of items");
+    // ld: elements between planes
+#pragma unroll
+    for (int q = 0; q < ROWS * 2 / NT; ++q)
+#pragma unroll
+      for (int pl = 0; pl < 3; ++pl)
+        st.v[q][pl] = bload16(b, (uint32_t)(k0 >> 4) * b.kblock + (uint32_t)(pl * ld * 2) + q * NT * 16u);
+  }
+}
+
 // An fp32 value as the sum of three bf16 values (8 + 8 + 8 significand bits; what is left is
 // below 2^-26 of the value): hi = bf16(x), mid = bf16(x - hi), lo = bf16(x - hi - mid), all
 // round-to-nearest-even, both subtractions exact.  Two values at a time, packed.
@@ -564,21 +665,37 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
   const int nchunks = (g.K + HK - 1) / HK;
   auto kof = [&](int c) { return c * HK; };
   union Frag { uint4 u; bf16x8 v; };
+  // Full tiles are loaded through buffer instructions: the descriptor and the per-stage offset
+  // live in scalar registers, and one 32-bit lane offset per operand serves every load (64-bit
+  // per-load pointers would cost two registers and an add per load and stage).
+  [[maybe_unused]] BufSrc bufA, bufB;
+  if constexpr (MODE == 0) {
+    bufA = make_bufsrc<ASRC, TBM, NT, HK>(A, lda, m0, g.M, g.K, tid);
+    bufB = make_bufsrc<BSRC, TBN, NT, HK>(B, ldb, n0, g.N, g.K, tid);
+  }
+  auto loadA = [&](HStage<ASRC, TBM, NT, HK>& st, int k0) __attribute__((always_inline)) {
+    if constexpr (MODE == 0) hload_buf<ASRC, TBM, NT, HK>(st, bufA, lda, k0);
+    else hload<ASRC, MODE, TBM, NT, HK>(st, A, lda, m0, k0, g.M, g.K, tid);
+  };
+  auto loadB = [&](HStage<BSRC, TBN, NT, HK>& st, int k0) __attribute__((always_inline)) {
+    if constexpr (MODE == 0) hload_buf<BSRC, TBN, NT, HK>(st, bufB, ldb, k0);
+    else hload<BSRC, MODE, TBN, NT, HK>(st, B, ldb, n0, k0, g.N, g.K, tid);
+  };
 
   constexpr bool kDeep = SPLIT == 3 || WGM * WGN == 8;
   if constexpr (!kDeep) {
     HStage<ASRC, TBM, NT, HK> sa;
     HStage<BSRC, TBN, NT, HK> sb;
-    hload<ASRC, MODE, TBM, NT, HK>(sa, A, lda, m0, kof(0), g.M, g.K, tid);
-    hload<BSRC, MODE, TBN, NT, HK>(sb, B, ldb, n0, kof(0), g.N, g.K, tid);
+    loadA(sa, kof(0));
+    loadB(sb, kof(0));
     hstore<ASRC, TBM, NT, SPLIT, PA, HK>(sa, lds_a[0], tid);
     hstore<BSRC, TBN, NT, SPLIT, PB, HK>(sb, lds_b[0], tid);
     __syncthreads();
     for (int c = 0; c < nchunks; ++c) {
       const int cur = c & 1;
       if (c + 1 < nchunks) {
-        hload<ASRC, MODE, TBM, NT, HK>(sa, A, lda, m0, kof(c + 1), g.M, g.K, tid);
-        hload<BSRC, MODE, TBN, NT, HK>(sb, B, ldb, n0, kof(c + 1), g.N, g.K, tid);
+        loadA(sa, kof(c + 1));
+        loadB(sb, kof(c + 1));
       }
       const uint16_t* __restrict__ as = lds_a[cur];
       const uint16_t* __restrict__ bs = lds_b[cur];
@@ -618,13 +735,13 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
     constexpr int PER = (IA + IB + 3) / 4;                   // LDS-write items after each of the first four groups
     HStage<ASRC, TBM, NT, HK> sa[R];
     HStage<BSRC, TBN, NT, HK> sb[R];
-    hload<ASRC, MODE, TBM, NT, HK>(sa[0], A, lda, m0, kof(0), g.M, g.K, tid);
-    hload<BSRC, MODE, TBN, NT, HK>(sb[0], B, ldb, n0, kof(0), g.N, g.K, tid);
+    loadA(sa[0], kof(0));
+    loadB(sb[0], kof(0));
 #pragma unroll
     for (int u = 1; u < R; ++u) {
       if (u < nchunks) {
-        hload<ASRC, MODE, TBM, NT, HK>(sa[u], A, lda, m0, kof(u), g.M, g.K, tid);
-        hload<BSRC, MODE, TBN, NT, HK>(sb[u], B, ldb, n0, kof(u), g.N, g.K, tid);
+        loadA(sa[u], kof(u));
+        loadB(sb[u], kof(u));
       }
     }
     hstore<ASRC, TBM, NT, SPLIT, PA, HK>(sa[0], lds_a[0], tid);
@@ -653,8 +770,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
                      FragSet& fn, int c, bool load, bool next) __attribute__((always_inline)) {
       const int cur = c & 1;
       if (load) {
-        hload<ASRC, MODE, TBM, NT, HK>(la, A, lda, m0, kof(c + R), g.M, g.K, tid);
-        hload<BSRC, MODE, TBN, NT, HK>(lb, B, ldb, n0, kof(c + R), g.N, g.K, tid);
+        loadA(la, kof(c + R));
+        loadB(lb, kof(c + R));
       }
       const uint16_t* __restrict__ bs = lds_b[cur];
       auto put = [&](int group) __attribute__((always_inline)) {
@@ -709,9 +826,9 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
 #pragma unroll
     for (int u = 0; u < R; ++u)
       stage(sa[u], sb[u], sa[(u + 1) % R], sb[(u + 1) % R], fr[u & 1], fr[(u + 1) & 1], c0 + u, false, u + 1 < R);
-  } else if constexpr (MODE == 0 && SPLIT == 3) {
-    // fp32 operands in plain layouts, full tiles, an even number of stages (the host sends
-    // everything else to the bounds-checked kernel): two statically addressed register
+  } else if constexpr (MODE == 0) {
+    // fp32 or bf16 operands in plain layouts, full tiles, an even number of stages (the host
+    // sends everything else to the bounds-checked kernel): two statically addressed register
     // sets.  Stage c is multiplied from LDS buffer c & 1; stage c + 1, already in registers, is
     // converted and written to the other buffer in pieces placed between the groups of matrix
     // instructions (the plain ALU work runs while the matrix pipe is busy); the global loads of
@@ -722,10 +839,10 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
     constexpr int PER = (IA + IB + GROUPS - 1) / GROUPS;     // conversion items after each group
     HStage<ASRC, TBM, NT, HK> sa[R];
     HStage<BSRC, TBN, NT, HK> sb[R];
-    hload<ASRC, MODE, TBM, NT, HK>(sa[0], A, lda, m0, kof(0), g.M, g.K, tid);
-    hload<BSRC, MODE, TBN, NT, HK>(sb[0], B, ldb, n0, kof(0), g.N, g.K, tid);
-    hload<ASRC, MODE, TBM, NT, HK>(sa[1], A, lda, m0, kof(1), g.M, g.K, tid);
-    hload<BSRC, MODE, TBN, NT, HK>(sb[1], B, ldb, n0, kof(1), g.N, g.K, tid);
+    loadA(sa[0], kof(0));
+    loadB(sb[0], kof(0));
+    loadA(sa[1], kof(1));
+    loadB(sb[1], kof(1));
     hstore<ASRC, TBM, NT, SPLIT, PA, HK>(sa[0], lds_a[0], tid);
     hstore<BSRC, TBN, NT, SPLIT, PB, HK>(sb[0], lds_b[0], tid);
     __syncthreads();
@@ -735,8 +852,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
                      bool conv) __attribute__((always_inline)) {
       const int cur = c & 1;
       if (load) {
-        hload<ASRC, MODE, TBM, NT, HK>(la, A, lda, m0, kof(c + R), g.M, g.K, tid);
-        hload<BSRC, MODE, TBN, NT, HK>(lb, B, ldb, n0, kof(c + R), g.N, g.K, tid);
+        loadA(la, kof(c + R));
+        loadB(lb, kof(c + R));
       }
       const uint16_t* __restrict__ as = lds_a[cur];
       const uint16_t* __restrict__ bs = lds_b[cur];
@@ -805,8 +922,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
   } else {
   HStage<ASRC, TBM, NT, HK> sa;
   HStage<BSRC, TBN, NT, HK> sb;
-  hload<ASRC, MODE, TBM, NT, HK>(sa, A, lda, m0, kof(0), g.M, g.K, tid);
-  hload<BSRC, MODE, TBN, NT, HK>(sb, B, ldb, n0, kof(0), g.N, g.K, tid);
+  loadA(sa, kof(0));
+  loadB(sb, kof(0));
   hstore<ASRC, TBM, NT, SPLIT, PA, HK>(sa, lds_a[0], tid);
   hstore<BSRC, TBN, NT, SPLIT, PB, HK>(sb, lds_b[0], tid);
   if constexpr (SPLIT == 1) {
@@ -818,8 +935,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
     constexpr int IA = hstage_items<ASRC, TBM, NT, HK>(), IB = hstage_items<BSRC, TBN, NT, HK>();
     constexpr int HALF = (IA + IB + 1) / 2;
     if (nchunks > 1) {
-      hload<ASRC, MODE, TBM, NT, HK>(sa, A, lda, m0, kof(1), g.M, g.K, tid);
-      hload<BSRC, MODE, TBN, NT, HK>(sb, B, ldb, n0, kof(1), g.N, g.K, tid);
+      loadA(sa, kof(1));
+      loadB(sb, kof(1));
     }
     __syncthreads();
     for (int c = 0; c < nchunks; ++c) {
@@ -827,8 +944,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
       HStage<ASRC, TBM, NT, HK> na = sa;
       HStage<BSRC, TBN, NT, HK> nb = sb;
       if (c + 2 < nchunks) {
-        hload<ASRC, MODE, TBM, NT, HK>(na, A, lda, m0, kof(c + 2), g.M, g.K, tid);
-        hload<BSRC, MODE, TBN, NT, HK>(nb, B, ldb, n0, kof(c + 2), g.N, g.K, tid);
+        loadA(na, kof(c + 2));
+        loadB(nb, kof(c + 2));
       }
       const bool conv = c + 1 < nchunks;
       const uint16_t* __restrict__ as = lds_a[cur];
@@ -868,8 +985,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
     constexpr int IA = hstage_items<ASRC, TBM, NT, HK>(), IB = hstage_items<BSRC, TBN, NT, HK>();
     static_assert(IA + IB <= 6, "one conversion slot per partial product");
     if (nchunks > 1) {
-      hload<ASRC, MODE, TBM, NT, HK>(sa, A, lda, m0, kof(1), g.M, g.K, tid);
-      hload<BSRC, MODE, TBN, NT, HK>(sb, B, ldb, n0, kof(1), g.N, g.K, tid);
+      loadA(sa, kof(1));
+      loadB(sb, kof(1));
     }
     __syncthreads();
     for (int c = 0; c < nchunks; ++c) {
@@ -877,8 +994,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
       HStage<ASRC, TBM, NT, HK> na = sa;
       HStage<BSRC, TBN, NT, HK> nb = sb;
       if (c + 2 < nchunks) {
-        hload<ASRC, MODE, TBM, NT, HK>(na, A, lda, m0, kof(c + 2), g.M, g.K, tid);
-        hload<BSRC, MODE, TBN, NT, HK>(nb, B, ldb, n0, kof(c + 2), g.N, g.K, tid);
+        loadA(na, kof(c + 2));
+        loadB(nb, kof(c + 2));
       }
       const bool conv = c + 1 < nchunks;
       const uint16_t* __restrict__ as = lds_a[cur];
@@ -965,7 +1082,7 @@ gpd_status_t launch_bf16_t(hipStream_t stream, HGemmParams p, int64_t batch, boo
   // output tile: two small workgroups per CU overlap one's epilogue with the other's products)
   // (the pipelined kernels for full tiles take an even number of stages)
   const bool even = p.K % (2 * hk_of(SPLIT)) == 0;
-  const bool large = aligned && (SPLIT == 1 ? p.K % hk_of(SPLIT) == 0 : even) && p.M % 256 == 0 && p.N % 256 == 0 && p.K > 0 &&
+  const bool large = aligned && even && p.M % 256 == 0 && p.N % 256 == 0 && p.K > 0 &&
                      (int64_t)(p.M / 256) * (p.N / 256) * batch >= 256 && (SPLIT == 1 || p.K >= 1024) &&
                      ASRC != SRC_BF16P_KB;     // (plane operands: the small shape only)
   const int tbm = large ? 256 : 128, tbn = large ? 256 : 128;
@@ -1074,11 +1191,16 @@ gpd_status_t launch_gemm(hipStream_t stream, const GemmArgs& a) {
     h.sA = a.strideA; h.sB = a.strideB; h.sC = a.strideC;
     h.alpha = a.alpha; h.beta = a.beta;
     h.planeA = a.planeA; h.planeB = a.planeB;
-    if (planes) return launch_bf16_t<SRC_BF16P_KB, SRC_BF16P_KB, 3>(stream, h, a.batch, true);
     const int a_es = a.a_bf16 ? 2 : 4, b_es = a.b_bf16 ? 2 : 4;
-    const bool al = ((uintptr_t)a.A % 16 == 0) && ((uintptr_t)a.B % 16 == 0) &&
+    // full tiles are read through buffer instructions with 32-bit offsets: one batch entry of
+    // each operand has to stay below 2^31 bytes
+    const int64_t ext_a = planes ? 4 * a.planeA + a.M * a.K * 2 : ((a_rows - 1) * a.lda + a_cols) * a_es;
+    const int64_t ext_b = planes ? 4 * a.planeB + a.N * a.K * 2 : ((b_rows - 1) * a.ldb + b_cols) * b_es;
+    const bool fits = ext_a < 0x7fffffffLL && ext_b < 0x7fffffffLL;
+    const bool al = fits && ((uintptr_t)a.A % 16 == 0) && ((uintptr_t)a.B % 16 == 0) &&
                     (a.lda * a_es) % 16 == 0 && (a.ldb * b_es) % 16 == 0 &&
                     (a.strideA * a_es) % 16 == 0 && (a.strideB * b_es) % 16 == 0;
+    if (planes) return launch_bf16_t<SRC_BF16P_KB, SRC_BF16P_KB, 3>(stream, h, a.batch, fits);
     if (a.split3) {
       if (!a.transA && !a.transB) return launch_bf16_t<SRC_F32_KC, SRC_F32_RC, 3>(stream, h, a.batch, al);
       if (!a.transA && a.transB) return launch_bf16_t<SRC_F32_KC, SRC_F32_KC, 3>(stream, h, a.batch, al);
