@@ -8,8 +8,6 @@
 // order of k inside a tile is permuted so that a lane fetches its four consecutive
 // k-values of a k-contiguous operand with one 128-bit LDS read.
 #include "gpd_internal.hpp"
-#include <type_traits>
-#include <utility>
 
 namespace gpd {
 
@@ -237,40 +235,20 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? 3 : 1) void gemm
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>): a loop whose index is a
-// compile-time constant inside the body
-template <typename F, int... I>
-__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
-  (f(std::integral_constant<int, I>{}), ...);
-}
-template <int N, typename F>
-__device__ __forceinline__ void static_for(F&& f) {
-  static_for_impl(f, std::make_integer_sequence<int, N>{});
-}
-
 // k-values per LDS stage: HK = 32 for the plain kernel, 16 for the three-way split (three planes
 // per operand, still double-buffered); a row of a tile is HK + 8 bf16 elements apart from the
 // next (80 or 48 bytes: the 128-bit reads of 8 consecutive rows fall on 32 different banks)
 constexpr int hk_of(int split) { return split == 1 ? 32 : 16; }
 
 
-// SRC_BF16P_KB: the fp32 operand already split into three bf16 planes (hi, mid, lo), each stored
-// k-blocked, [k / 16][row][k % 16]: one stage of a tile is one contiguous run per plane
-enum { SRC_F32_KC = 0, SRC_BF16_KC = 1, SRC_F32_RC = 2, SRC_BF16_RC = 3, SRC_BF16P_KB = 4 };
-
-// register sets of staged global loads the deep pipeline keeps (R - 1 stages ahead of the one
-// being multiplied, plus the one being written to LDS): plane sources need 6 registers per
-// operand and stage, fp32 sources 8 to 16
-constexpr int kRingOf(int asrc, int bsrc, int tbm) {
-  return (asrc == SRC_BF16P_KB && bsrc == SRC_BF16P_KB) ? (tbm <= 128 ? 4 : 2) : 2;
-}
+enum { SRC_F32_KC = 0, SRC_BF16_KC = 1, SRC_F32_RC = 2, SRC_BF16_RC = 3 };
 
 struct HGemmParams {
   const void* A; const void* B; float* C;
   int M, N, K;
   int64_t lda, ldb, ldc;
   int64_t sA, sB, sC;
-  int64_t planeA, planeB;    // elements between the planes of a SRC_BF16P_KB operand
+  int64_t planeA, planeB;    // elements between the three planes of a pre-split operand
   int tiles_m, tiles_n, total_tiles, tiles_per_xcd;
   float alpha, beta;
 };
@@ -315,11 +293,9 @@ template <int ROWS, int NT, int HK> struct HStage<SRC_F32_KC, ROWS, NT, HK> { fl
 template <int ROWS, int NT, int HK> struct HStage<SRC_BF16_KC, ROWS, NT, HK> { uint4 v[(ROWS * (HK / 8) + NT - 1) / NT]; };
 template <int ROWS, int NT, int HK> struct HStage<SRC_F32_RC, ROWS, NT, HK> { float4 v[ROWS * HK / 8 / NT][2]; };
 template <int ROWS, int NT, int HK> struct HStage<SRC_BF16_RC, ROWS, NT, HK> { uint4 v[(ROWS * HK / 16 + NT - 1) / NT][2]; };
-template <int ROWS, int NT, int HK> struct HStage<SRC_BF16P_KB, ROWS, NT, HK> { uint4 v[(ROWS * (HK / 8) + NT - 1) / NT][3]; };
 
 // base: start of the operand for this batch entry; "row" is the m (or n) index, k the
-// contraction index.  KC sources are [row][k] with leading dimension ld, RC sources [k][row];
-// for the k-blocked planes ld is the distance between planes and nk a multiple of 16.
+// contraction index.  KC sources are [row][k] with leading dimension ld, RC sources [k][row].
 template <int SRC, int MODE, int ROWS, int NT, int HK>
 __device__ __forceinline__ void hload(HStage<SRC, ROWS, NT, HK>& st, const void* base, int64_t ld, int row0,
                                       int k0, int nrows, int nk, int tid) {
@@ -341,20 +317,6 @@ __device__ __forceinline__ void hload(HStage<SRC, ROWS, NT, HK>& st, const void*
       const bool mine = f < ROWS * (HK / 8);
       const int nv = !mine ? 0 : ((MODE == 0) ? 8 : (row < nrows ? clampi(nk - k, 0, 8) : 0));
       st.v[q] = (nv > 0) ? load8h<MODE>(b + (int64_t)row * ld + k, nv) : make_uint4(0u, 0u, 0u, 0u);
-    }
-  } else if constexpr (SRC == SRC_BF16P_KB) {
-    static_assert(HK == 16, "a stage is one 16-k block");
-    // one stage of a tile is ROWS * 32 contiguous bytes per plane: a uniform base (scalar
-    // registers) plus 16 bytes per item, the same 32-bit lane offset for every plane and stage
-    const char* ub = (const char*)base + (((int64_t)(k0 >> 4) * nrows + row0) << 5);
-#pragma unroll
-    for (int q = 0; q < (ROWS * 2 + NT - 1) / NT; ++q) {
-      const int f = tid + NT * q;
-      const bool mine = ((ROWS * 2) % NT == 0 || f < ROWS * 2) && (MODE == 0 || (row0 + (f >> 1) < nrows && k0 < nk));
-      const uint32_t lo = 16u * (uint32_t)f;
-#pragma unroll
-      for (int pl = 0; pl < 3; ++pl)
-        st.v[q][pl] = mine ? *reinterpret_cast<const uint4*>(ub + 2 * pl * ld + lo) : make_uint4(0u, 0u, 0u, 0u);
     }
   } else if constexpr (SRC == SRC_F32_RC) {
     const float* b = (const float*)base;
@@ -393,12 +355,11 @@ __device__ __forceinline__ void hload(HStage<SRC, ROWS, NT, HK>& st, const void*
 //
 // The descriptor covers one batch entry of the operand, starting at the tile's first row (or
 // column); every access of a full tile lies inside it.  voff is the byte offset of the lane's
-// first item inside the stage at k = 0; the items of a lane, the two k-rows of a patch, the
-// three planes and the stage itself only add wavefront-uniform amounts.
+// first item inside the stage at k = 0; the items of a lane, the two k-rows of a patch and the
+// stage itself only add wavefront-uniform amounts.
 struct BufSrc {
   __amdgpu_buffer_rsrc_t rsrc;
   uint32_t voff;
-  uint32_t kblock;      // plane sources: bytes per 16-k block of all rows
   uint32_t voff_lane;   // the lane's index in the workgroup
 };
 __device__ __forceinline__ uint4 bload16(const BufSrc& b, uint32_t soff) {
@@ -429,15 +390,11 @@ __device__ __forceinline__ BufSrc make_bufsrc(const void* base, int64_t ld, int 
     origin = (int64_t)row0 * 4; extent = (((int64_t)nk - 1) * ld + nrows) * 4;
     b.voff = (uint32_t)((2 * ((tid & 3) + 4 * (tid / ROWS)) * ld + 4 * ((tid >> 2) % (ROWS / 4))) * 4);
     static_assert(NT % ROWS == 0 || ROWS % NT == 0, "items of a lane differ by whole k-rows");
-  } else if constexpr (SRC == SRC_BF16_RC) {
+  } else {
+    static_assert(SRC == SRC_BF16_RC, "four source layouts");
     origin = (int64_t)row0 * 2; extent = (((int64_t)nk - 1) * ld + nrows) * 2;
     b.voff = (uint32_t)((2 * ((tid & 3) + 4 * (tid / (ROWS / 2))) * ld + 8 * ((tid >> 2) % (ROWS / 8))) * 2);
-  } else {
-    // ld: elements between planes
-    origin = (int64_t)row0 * 32; extent = 4 * ld + (int64_t)(nk >> 4) * nrows * 32;
-    b.voff = 16u * (uint32_t)tid;
   }
-  b.kblock = (uint32_t)nrows * 32u;
   b.voff_lane = (uint32_t)tid;
   const int64_t left = extent - origin;
   b.rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>((const char*)base + origin), 0,
@@ -468,8 +425,8 @@ __device__ __forceinline__ void hload_buf(HStage<SRC, ROWS, NT, HK>& st, const B
     for (int q = 0; q < ROWS * HK / 8 / NT; ++q)
 #pragma unroll
       for (int par = 0; par < 2; ++par) st.v[q][par] = bload16f(b, (uint32_t)k0 * row_b + q * step + par * row_b);
-  } else if constexpr (SRC == SRC_BF16_RC) {
-    static_assert(NT % (ROWS / 2) == 0, "an item step is a whole number of k-pairs");
+  } else {
+    static_assert(SRC == SRC_BF16_RC && NT % (ROWS / 2) == 0, "an item step is a whole number of k-pairs");
     constexpr int COUNT = ROWS * HK / 16;                   // patches per stage; lanes beyond idle
     const uint32_t row_b = (uint32_t)(ld * 2), step = (uint32_t)(8 * (NT / (ROWS / 2))) * row_b;
 #pragma unroll
@@ -479,14 +436,6 @@ __device__ __forceinline__ void hload_buf(HStage<SRC, ROWS, NT, HK>& st, const B
       for (int par = 0; par < 2; ++par)
         st.v[q][par] = mine ? bload16(b, (uint32_t)k0 * row_b + q * step + par * row_b) : make_uint4(0u, 0u, 0u, 0u);
     }
-  } else {
-    static_assert((ROWS * 2) % NT == 0, "every lane has the same number of items");
-    // ld: elements between planes
-#pragma unroll
-    for (int q = 0; q < ROWS * 2 / NT; ++q)
-#pragma unroll
-      for (int pl = 0; pl < 3; ++pl)
-        st.v[q][pl] = bload16(b, (uint32_t)(k0 >> 4) * b.kblock + (uint32_t)(pl * ld * 2) + q * NT * 16u);
   }
 }
 
@@ -506,7 +455,7 @@ __device__ __forceinline__ void split3_pack(float x0, float x1, uint32_t (&w)[3]
 template <int SRC, int ROWS, int NT, int HK>
 constexpr int hstage_items() {
   return SRC == SRC_F32_KC ? ROWS * (HK / 4) / NT
-       : (SRC == SRC_BF16_KC || SRC == SRC_BF16P_KB) ? (ROWS * (HK / 8) + NT - 1) / NT
+       : SRC == SRC_BF16_KC ? (ROWS * (HK / 8) + NT - 1) / NT
        : SRC == SRC_F32_RC ? ROWS * HK / 8 / NT
                            : (ROWS * HK / 16 + NT - 1) / NT;
 }
@@ -516,16 +465,9 @@ template <int SRC, int ROWS, int NT, int SPLIT, int PLANE, int HK>
 __device__ __forceinline__ void hstore_item(const HStage<SRC, ROWS, NT, HK>& st, int q,
                                             uint16_t* __restrict__ lds, int tid) {
   constexpr int HSTRIDE = HK + 8;
-  static_assert((SPLIT == 3) == (SRC == SRC_BF16P_KB) || SRC == SRC_F32_KC || SRC == SRC_F32_RC,
-                "fp32 sources are split on the way to LDS, plane sources arrive split");
+  static_assert(SPLIT == 1 || SRC == SRC_F32_KC || SRC == SRC_F32_RC, "only fp32 sources are split");
   const int f = tid + NT * q;
-  if constexpr (SRC == SRC_BF16P_KB) {
-    if ((ROWS * 2) % NT == 0 || f < ROWS * 2) {
-#pragma unroll
-      for (int pl = 0; pl < 3; ++pl)
-        *reinterpret_cast<uint4*>(lds + pl * PLANE + (f >> 1) * HSTRIDE + 8 * (f & 1)) = st.v[q][pl];
-    }
-  } else if constexpr (SRC == SRC_F32_KC) {
+  if constexpr (SRC == SRC_F32_KC) {
     uint16_t* dst = lds + (f / (HK / 4)) * HSTRIDE + 4 * (f % (HK / 4));
     if constexpr (SPLIT == 1) {
       uint2 w;
@@ -617,10 +559,9 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
   const int tn = rem - tm * g.tiles_n;
   const int m0 = tm * TBM, n0 = tn * TBN;
 
-  constexpr int A_ES = (ASRC == SRC_BF16_KC || ASRC == SRC_BF16_RC || ASRC == SRC_BF16P_KB) ? 2 : 4;
-  constexpr int B_ES = (BSRC == SRC_BF16_KC || BSRC == SRC_BF16_RC || BSRC == SRC_BF16P_KB) ? 2 : 4;
-  const int64_t lda = ASRC == SRC_BF16P_KB ? g.planeA : g.lda;
-  const int64_t ldb = BSRC == SRC_BF16P_KB ? g.planeB : g.ldb;
+  constexpr int A_ES = (ASRC == SRC_BF16_KC || ASRC == SRC_BF16_RC) ? 2 : 4;
+  constexpr int B_ES = (BSRC == SRC_BF16_KC || BSRC == SRC_BF16_RC) ? 2 : 4;
+  const int64_t lda = g.lda, ldb = g.ldb;
   const char* A = (const char*)g.A + (int64_t)p * g.sA * A_ES;
   const char* B = (const char*)g.B + (int64_t)p * g.sB * B_ES;
   float* __restrict__ C = g.C + (int64_t)p * g.sC;
@@ -641,7 +582,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
   // Read-modify-write of the output tile (the coded update): with two workgroups of this shape on
   // a CU there are registers to spare, so the old values are requested before the first stage
   // and have arrived long before the epilogue needs them.
-  constexpr bool kPrefetchC = SPLIT == 3 && MI * NJ <= 4 && ASRC != SRC_BF16P_KB;
+  constexpr bool kPrefetchC = SPLIT == 3 && MI * NJ <= 4;
   float oldc[kPrefetchC ? MI * NJ * 16 : 1];
   if constexpr (kPrefetchC) {
     if (g.beta != 0.f) {
@@ -720,112 +661,6 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
       }
       __syncthreads();
     }
-  } else if constexpr (ASRC == SRC_BF16P_KB && BSRC == SRC_BF16P_KB) {
-    // Operands that arrive split: nothing to convert, so the loop is matrix instructions, LDS
-    // traffic and global loads only, and every latency is taken off the critical path:
-    //  - global loads run R - 1 stages ahead, in R register sets that are addressed statically
-    //    (the loop is unrolled R times; rotating the sets by copies would make every iteration
-    //    wait for the loads it has just issued);
-    //  - the fragments of stage c + 1 are read from LDS right after the barrier that publishes
-    //    them, in a second set of fragment registers, while the last two of the six partial
-    //    products of stage c are still being issued.
-    static_assert(SPLIT == 3 && HK == 16, "plane operands are multiplied as six partial products");
-    constexpr int R = kRingOf(ASRC, BSRC, TBM);
-    constexpr int IA = hstage_items<ASRC, TBM, NT, HK>(), IB = hstage_items<BSRC, TBN, NT, HK>();
-    constexpr int PER = (IA + IB + 3) / 4;                   // LDS-write items after each of the first four groups
-    HStage<ASRC, TBM, NT, HK> sa[R];
-    HStage<BSRC, TBN, NT, HK> sb[R];
-    loadA(sa[0], kof(0));
-    loadB(sb[0], kof(0));
-#pragma unroll
-    for (int u = 1; u < R; ++u) {
-      if (u < nchunks) {
-        loadA(sa[u], kof(u));
-        loadB(sb[u], kof(u));
-      }
-    }
-    hstore<ASRC, TBM, NT, SPLIT, PA, HK>(sa[0], lds_a[0], tid);
-    hstore<BSRC, TBN, NT, SPLIT, PB, HK>(sb[0], lds_b[0], tid);
-    __syncthreads();
-
-    struct FragSet { Frag a[MI][3]; Frag b2[NJ]; };          // all planes of A, the lo plane of B
-    auto read_frags = [&](FragSet& f, int buf) __attribute__((always_inline)) {
-#pragma unroll
-      for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int pl = 0; pl < 3; ++pl)
-          f.a[i][pl].u = *reinterpret_cast<const uint4*>(lds_a[buf] + pl * PA + (wm + 32 * i + li) * HSTRIDE + 8 * lg);
-#pragma unroll
-      for (int j = 0; j < NJ; ++j)
-        f.b2[j].u = *reinterpret_cast<const uint4*>(lds_b[buf] + 2 * PB + (wn + 32 * j + li) * HSTRIDE + 8 * lg);
-    };
-    FragSet fr[2];
-    read_frags(fr[0], 0);
-
-    // one stage c: la / lb is the register set stage c has left (stage c + R is loaded into it if
-    // load), ca / cb the set that holds stage c + 1 (written to LDS if next), fc / fn the
-    // fragments of stage c and c + 1
-    auto stage = [&](HStage<ASRC, TBM, NT, HK>& la, HStage<BSRC, TBN, NT, HK>& lb,
-                     const HStage<ASRC, TBM, NT, HK>& ca, const HStage<BSRC, TBN, NT, HK>& cb, const FragSet& fc,
-                     FragSet& fn, int c, bool load, bool next) __attribute__((always_inline)) {
-      const int cur = c & 1;
-      if (load) {
-        loadA(la, kof(c + R));
-        loadB(lb, kof(c + R));
-      }
-      const uint16_t* __restrict__ bs = lds_b[cur];
-      auto put = [&](int group) __attribute__((always_inline)) {
-        if (next) {
-#pragma unroll
-          for (int it = group * PER; it < (group + 1) * PER && it < IA + IB; ++it) {
-            if (it < IA) hstore_item<ASRC, TBM, NT, SPLIT, PA, HK>(ca, it, lds_a[cur ^ 1], tid);
-            else hstore_item<BSRC, TBN, NT, SPLIT, PB, HK>(cb, it - IA, lds_b[cur ^ 1], tid);
-          }
-        }
-      };
-      auto products = [&](int pa, const Frag (&fb)[NJ]) __attribute__((always_inline)) {
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-          for (int j = 0; j < NJ; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fc.a[i][pa].v, fb[j].v, acc[i][j], 0, 0, 0);
-      };
-      Frag fb1[NJ], fb0[NJ];
-#pragma unroll
-      for (int j = 0; j < NJ; ++j)
-        fb1[j].u = *reinterpret_cast<const uint4*>(bs + PB + (wn + 32 * j + li) * HSTRIDE + 8 * lg);
-      products(0, fc.b2);                       // hi * lo
-      put(0);
-#pragma unroll
-      for (int j = 0; j < NJ; ++j)
-        fb0[j].u = *reinterpret_cast<const uint4*>(bs + (wn + 32 * j + li) * HSTRIDE + 8 * lg);
-      products(1, fb1);                         // mid * mid
-      put(1);
-      products(0, fb1);                         // hi * mid
-      put(2);
-      products(2, fb0);                         // lo * hi
-      put(3);
-      __syncthreads();
-      if (next) read_frags(fn, cur ^ 1);
-      products(1, fb0);                         // mid * hi
-      products(0, fb0);                         // hi * hi
-    };
-
-    // Steady state: every iteration loads, so the number of younger loads in flight when a
-    // stage is needed is the same each time and the wait for it leaves them in flight (the
-    // load counter is relative: code shared with the tail, where fewer loads follow, would
-    // have to wait for everything).  The host only takes this path when the number of stages
-    // is a multiple of R, and R is even.
-    static_assert(R % 2 == 0, "the fragment sets alternate with the stage parity");
-    int c0 = 0;
-    for (; c0 + 2 * R <= nchunks; c0 += R) {
-#pragma unroll
-      for (int u = 0; u < R; ++u)
-        stage(sa[u], sb[u], sa[(u + 1) % R], sb[(u + 1) % R], fr[u & 1], fr[(u + 1) & 1], c0 + u, true, true);
-    }
-#pragma unroll
-    for (int u = 0; u < R; ++u)
-      stage(sa[u], sb[u], sa[(u + 1) % R], sb[(u + 1) % R], fr[u & 1], fr[(u + 1) & 1], c0 + u, false, u + 1 < R);
   } else if constexpr (MODE == 0) {
     // fp32 or bf16 operands in plain layouts, full tiles, an even number of stages (the host
     // sends everything else to the bounds-checked kernel): two statically addressed register
@@ -1075,6 +910,180 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
   }
 }
 
+
+// ------------------------------------------------------------------ rank-B update from split planes
+//
+// C_p = beta C_p + alpha A_p B_p^T for operands that arrive as three bf16 planes (hi, mid, lo of
+// the fp32 value), k-blocked ([k / 16][row][16]): the coded update W~_p += eta Dhat_p Xhat_p^T with
+// a contraction over the mini-batch only, so the read-modify-write of the output tile weighs as
+// much as the six partial products.  128 x 128 tile, four wavefronts of 64 x 64, 16 k per stage.
+// A stage of a tile is 4 KB per plane and operand, contiguous in memory and stored to LDS as it
+// is (32-byte rows; the 16-byte halves of a row are swapped in every second group of four rows,
+// which keeps the 128-bit fragment reads of 8 consecutive lanes on 32 different banks without
+// padding): 24 KB per stage, two stages, three workgroups per CU, so that while one workgroup
+// reads and writes its output tile two others keep the matrix pipe busy.
+template <int MODE, int R>
+__global__ __launch_bounds__(256, 3) void gemm_planes_kernel(HGemmParams g) {
+  constexpr int TB = 128, MI = 2, NJ = 2;
+  constexpr int PLANE_B = TB * 32, STAGE_B = 6 * PLANE_B;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[2][STAGE_B];
+
+  const int xcd = blockIdx.x & 7;
+  const int slot = blockIdx.x >> 3;
+  const int tile = xcd * g.tiles_per_xcd + slot;
+  if (tile >= g.total_tiles) return;
+  const int per_batch = g.tiles_m * g.tiles_n;
+  const int p = tile / per_batch;
+  const int rem = tile - p * per_batch;
+  const int tm = rem / g.tiles_n;
+  const int tn = rem - tm * g.tiles_n;
+  const int m0 = tm * TB, n0 = tn * TB;
+  float* __restrict__ C = g.C + (int64_t)p * g.sC;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 31, lg = lane >> 5;
+  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+
+  // one batch entry of each operand behind a buffer descriptor that starts at the tile's first
+  // row; a lane's 16 bytes of a stage are at 16 * tid, planes and stages add uniform offsets
+  const char* Ab = (const char*)g.A + ((int64_t)p * g.sA + (int64_t)m0 * 16) * 2;
+  const char* Bb = (const char*)g.B + ((int64_t)p * g.sB + (int64_t)n0 * 16) * 2;
+  const int64_t extA = 4 * g.planeA + (int64_t)(g.K >> 4) * g.M * 32 - (int64_t)m0 * 32;
+  const int64_t extB = 4 * g.planeB + (int64_t)(g.K >> 4) * g.N * 32 - (int64_t)n0 * 32;
+  const __amdgpu_buffer_rsrc_t rA = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(Ab), 0, (int)extA, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rB = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(Bb), 0, (int)extB, 0x00020000);
+  const uint32_t voff = 16u * (uint32_t)tid;
+  const uint32_t kbA = (uint32_t)g.M * 32u, kbB = (uint32_t)g.N * 32u;
+  const uint32_t plA = (uint32_t)(g.planeA * 2), plB = (uint32_t)(g.planeB * 2);
+  const bool okA = MODE == 0 || m0 + (tid >> 1) < g.M;
+  const bool okB = MODE == 0 || n0 + (tid >> 1) < g.N;
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  struct Set { u32x4 a[3], b[3]; };
+  auto load = [&](Set& st, int c) __attribute__((always_inline)) {
+#pragma unroll
+    for (int pl = 0; pl < 3; ++pl) {
+      st.a[pl] = okA ? __builtin_amdgcn_raw_buffer_load_b128(rA, voff, (uint32_t)c * kbA + pl * plA, 0) : u32x4{0u, 0u, 0u, 0u};
+      st.b[pl] = okB ? __builtin_amdgcn_raw_buffer_load_b128(rB, voff, (uint32_t)c * kbB + pl * plB, 0) : u32x4{0u, 0u, 0u, 0u};
+    }
+  };
+  // LDS positions: a lane stores its 16 bytes of row tid / 2, and reads rows wm (wn) + 32 i + li
+  const uint32_t swz_w = ((tid & 1) ^ ((tid >> 3) & 1)) * 16u, swz_r = ((uint32_t)lg ^ ((li >> 2) & 1)) * 16u;
+  const uint32_t wr_off = (uint32_t)(tid >> 1) * 32u + swz_w;
+  const uint32_t rdA = (uint32_t)(wm + li) * 32u + swz_r, rdB = 3 * PLANE_B + (uint32_t)(wn + li) * 32u + swz_r;
+  auto put = [&](const Set& st, int buf, int item) __attribute__((always_inline)) {
+    *reinterpret_cast<u32x4*>(lds[buf] + wr_off + item * PLANE_B) = item < 3 ? st.a[item] : st.b[item - 3];
+  };
+  union Frag { u32x4 u; bf16x8 v; };
+  auto frag = [&](int buf, uint32_t off) __attribute__((always_inline)) {
+    Frag f;
+    f.u = *reinterpret_cast<const u32x4*>(lds[buf] + off);
+    return f;
+  };
+
+  floatx16 acc[MI][NJ];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const int nchunks = g.K >> 4;            // a multiple of R (the host checks K % 64 == 0)
+  Set st[R];
+#pragma unroll
+  for (int u = 0; u < R; ++u) load(st[u], u);
+#pragma unroll
+  for (int it = 0; it < 6; ++it) put(st[0], 0, it);
+  __syncthreads();
+
+  // stage c: the global loads of stage c + R go into the register set stage c has left (set
+  // u = c % R, addressed statically: the loop is unrolled R times), stage c + 1 moves from its
+  // set to the other LDS buffer between the groups of matrix instructions, and the six partial
+  // products hi*lo, mid*mid, hi*mid, lo*hi, mid*hi, hi*hi of stage c are accumulated
+  auto stage = [&](Set& ld_set, const Set& nx_set, int c, bool do_load, bool do_next) __attribute__((always_inline)) {
+    const int cur = c & 1;
+    if (do_load) load(ld_set, c + R);
+    Frag fa[MI][3], fb[NJ];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int pl = 0; pl < 3; ++pl) fa[i][pl] = frag(cur, rdA + pl * PLANE_B + i * 1024);
+    int item = 0;
+#pragma unroll
+    for (int pb = 2; pb >= 0; --pb) {
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) fb[j] = frag(cur, rdB + pb * PLANE_B + j * 1024);
+#pragma unroll
+      for (int pa = 2 - pb; pa >= 0; --pa) {
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+          for (int j = 0; j < NJ; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i][pa].v, fb[j].v, acc[i][j], 0, 0, 0);
+        if (do_next) put(nx_set, cur ^ 1, item);
+        ++item;
+      }
+    }
+    __syncthreads();
+  };
+  // steady state with loads in every iteration: the number of younger loads in flight when a
+  // set is needed is then the same each time, and the wait for it leaves them in flight (the
+  // load counter is relative: code shared with the last R stages, after which nothing is
+  // loaded, would have to wait for everything)
+  int c0 = 0;
+  for (; c0 + 2 * R <= nchunks; c0 += R) {
+#pragma unroll
+    for (int u = 0; u < R; ++u) stage(st[u], st[(u + 1) % R], c0 + u, true, true);
+  }
+#pragma unroll
+  for (int u = 0; u < R; ++u) stage(st[u], st[(u + 1) % R], c0 + u, false, u + 1 < R);
+
+  // read-modify-write of the output tile, two 32 x 32 blocks at a time: the 32 old values of a
+  // pair are requested before any is used
+  constexpr int GB = 2;
+#pragma unroll
+  for (int b0 = 0; b0 < MI * NJ; b0 += GB) {
+    float old[GB][16];
+#pragma unroll
+    for (int bb = 0; bb < GB; ++bb) {
+      const int i = (b0 + bb) / NJ, j = (b0 + bb) % NJ;
+      const int col = n0 + wn + 32 * j + li;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * lg + (v & 3);
+        old[bb][v] = (g.beta != 0.f && (MODE == 0 || (row < g.M && col < g.N))) ? C[(int64_t)row * g.ldc + col] : 0.f;
+      }
+    }
+#pragma unroll
+    for (int bb = 0; bb < GB; ++bb) {
+      const int i = (b0 + bb) / NJ, j = (b0 + bb) % NJ;
+      const int col = n0 + wn + 32 * j + li;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * lg + (v & 3);
+        if (MODE == 0 || (row < g.M && col < g.N))
+          C[(int64_t)row * g.ldc + col] = fmaf(g.beta, old[bb][v], g.alpha * acc[i][j][v]);
+      }
+    }
+  }
+}
+
+
+gpd_status_t launch_planes(hipStream_t stream, HGemmParams p, int64_t batch) {
+  p.tiles_m = (p.M + 127) / 128;
+  p.tiles_n = (p.N + 127) / 128;
+  const int64_t total = (int64_t)p.tiles_m * p.tiles_n * batch;
+  if (total > 0x0fffffff) return fail(GPD_E_SHAPE, "gemm: too many tiles");
+  p.total_tiles = (int)total;
+  p.tiles_per_xcd = (int)((total + 7) / 8);
+  dim3 grid((unsigned)(p.tiles_per_xcd * 8));
+  if (p.M % 128 == 0 && p.N % 128 == 0) hipLaunchKernelGGL((gemm_planes_kernel<0, 2>), grid, dim3(256), 0, stream, p);
+  else hipLaunchKernelGGL((gemm_planes_kernel<1, 2>), grid, dim3(256), 0, stream, p);
+  GPD_HIP(hipGetLastError());
+  return GPD_OK;
+}
+
 template <int ASRC, int BSRC, int SPLIT>
 gpd_status_t launch_bf16_t(hipStream_t stream, HGemmParams p, int64_t batch, bool aligned) {
   // same two workgroup shapes as the fp32 kernel; the large one needs full aligned tiles
@@ -1083,8 +1092,7 @@ gpd_status_t launch_bf16_t(hipStream_t stream, HGemmParams p, int64_t batch, boo
   // (the pipelined kernels for full tiles take an even number of stages)
   const bool even = p.K % (2 * hk_of(SPLIT)) == 0;
   const bool large = aligned && even && p.M % 256 == 0 && p.N % 256 == 0 && p.K > 0 &&
-                     (int64_t)(p.M / 256) * (p.N / 256) * batch >= 256 && (SPLIT == 1 || p.K >= 1024) &&
-                     ASRC != SRC_BF16P_KB;     // (plane operands: the small shape only)
+                     (int64_t)(p.M / 256) * (p.N / 256) * batch >= 256 && (SPLIT == 1 || p.K >= 1024);
   const int tbm = large ? 256 : 128, tbn = large ? 256 : 128;
   p.tiles_m = (p.M + tbm - 1) / tbm;
   p.tiles_n = (p.N + tbn - 1) / tbn;
@@ -1097,9 +1105,7 @@ gpd_status_t launch_bf16_t(hipStream_t stream, HGemmParams p, int64_t batch, boo
     // the split kernel keeps three planes of A in registers, and a kernel that streams fp32
     // weights needs two stages of global loads in flight: 8 wavefronts of 128 x 64 (256
     // registers each) instead of 16 of 64 x 64 (128 registers)
-    if constexpr (ASRC == SRC_BF16P_KB)
-      return fail(GPD_E_UNSUPPORTED, "gemm: no large shape for plane operands");
-    else if constexpr (SPLIT == 3 || ASRC == SRC_F32_KC || ASRC == SRC_F32_RC)
+    if constexpr (SPLIT == 3 || ASRC == SRC_F32_KC || ASRC == SRC_F32_RC)
       hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 0, 256, 256, 2, 4, SPLIT>), grid, dim3(512), 0, stream, p);
     else
       hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 0, 256, 256, 4, 4, SPLIT>), grid, dim3(1024), 0, stream, p);
@@ -1200,7 +1206,10 @@ gpd_status_t launch_gemm(hipStream_t stream, const GemmArgs& a) {
     const bool al = fits && ((uintptr_t)a.A % 16 == 0) && ((uintptr_t)a.B % 16 == 0) &&
                     (a.lda * a_es) % 16 == 0 && (a.ldb * b_es) % 16 == 0 &&
                     (a.strideA * a_es) % 16 == 0 && (a.strideB * b_es) % 16 == 0;
-    if (planes) return launch_bf16_t<SRC_BF16P_KB, SRC_BF16P_KB, 3>(stream, h, a.batch, fits);
+    if (planes) {
+      if (!fits) return fail(GPD_E_SHAPE, "gemm: plane operands above 2^31 bytes");
+      return launch_planes(stream, h, a.batch);
+    }
     if (a.split3) {
       if (!a.transA && !a.transB) return launch_bf16_t<SRC_F32_KC, SRC_F32_RC, 3>(stream, h, a.batch, al);
       if (!a.transA && a.transB) return launch_bf16_t<SRC_F32_KC, SRC_F32_KC, 3>(stream, h, a.batch, al);

@@ -62,6 +62,7 @@ LAYER_CASES = [
     (130, 260, 48, 2, 2, 2, 3, 20),       # d1, d2 > 1
     (300, 200, 64, 2, 4, 1, 1, 32),       # update operands as bf16 planes, ragged tiles, one ring of stages
     (512, 1024, 192, 2, 4, 1, 1, 32),     # planes, full tiles, steady-state loop and tail
+    (1024, 1024, 128, 2, 4, 1, 1, 32),    # planes, 256 full tiles
 ]
 
 
