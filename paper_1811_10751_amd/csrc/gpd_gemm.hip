@@ -935,8 +935,21 @@ __global__ __launch_bounds__(256, 3) void gemm_planes_kernel(HGemmParams g) {
   const int per_batch = g.tiles_m * g.tiles_n;
   const int p = tile / per_batch;
   const int rem = tile - p * per_batch;
-  const int tm = rem / g.tiles_n;
-  const int tn = rem - tm * g.tiles_n;
+  // Tiles that run at the same time should share operand panels: a panel of 128 rows is 96 KB
+  // per 128 k, the workgroups of an XCD run about 96 tiles at once, and its L2 holds 4 MB.  Row
+  // by row (16 or more tiles of one row of tiles, then the next row) every B panel comes back
+  // only after a whole row's worth of traffic and has left the L2 by then; in blocks of 8 x 8
+  // tiles 16 panels serve 64 tiles.
+  constexpr int SM = 8, SN = 8;            // tiles per block, along m and n
+  int tm, tn;
+  if (g.tiles_m % SM == 0 && g.tiles_n % SN == 0) {
+    const int blk = rem / (SM * SN), in = rem % (SM * SN), bn = g.tiles_n / SN;
+    tm = (blk / bn) * SM + in / SN;
+    tn = (blk % bn) * SN + in % SN;
+  } else {
+    tm = rem / g.tiles_n;
+    tn = rem - tm * g.tiles_n;
+  }
   const int m0 = tm * TB, n0 = tn * TB;
   float* __restrict__ C = g.C + (int64_t)p * g.sC;
 
@@ -1040,7 +1053,8 @@ __global__ __launch_bounds__(256, 3) void gemm_planes_kernel(HGemmParams g) {
   for (int u = 0; u < R; ++u) stage(st[u], st[(u + 1) % R], c0 + u, false, u + 1 < R);
 
   // read-modify-write of the output tile, two 32 x 32 blocks at a time: the 32 old values of a
-  // pair are requested before any is used
+  // pair are requested before any is used.  The tile is touched once: its loads and stores are
+  // marked non-temporal so that they do not push the operand panels out of the L2.
   constexpr int GB = 2;
 #pragma unroll
   for (int b0 = 0; b0 < MI * NJ; b0 += GB) {
@@ -1052,7 +1066,7 @@ __global__ __launch_bounds__(256, 3) void gemm_planes_kernel(HGemmParams g) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * lg + (v & 3);
-        old[bb][v] = (g.beta != 0.f && (MODE == 0 || (row < g.M && col < g.N))) ? C[(int64_t)row * g.ldc + col] : 0.f;
+        old[bb][v] = (g.beta != 0.f && (MODE == 0 || (row < g.M && col < g.N))) ? __builtin_nontemporal_load(&C[(int64_t)row * g.ldc + col]) : 0.f;
       }
     }
 #pragma unroll
@@ -1063,7 +1077,7 @@ __global__ __launch_bounds__(256, 3) void gemm_planes_kernel(HGemmParams g) {
       for (int v = 0; v < 16; ++v) {
         const int row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * lg + (v & 3);
         if (MODE == 0 || (row < g.M && col < g.N))
-          C[(int64_t)row * g.ldc + col] = fmaf(g.beta, old[bb][v], g.alpha * acc[i][j][v]);
+          __builtin_nontemporal_store(fmaf(g.beta, old[bb][v], g.alpha * acc[i][j][v]), &C[(int64_t)row * g.ldc + col]);
       }
     }
   }
