@@ -17,6 +17,9 @@ SHAPES = [
     (1024, 2048, 1024, 2, 2, 2, 16),    # 16 x 4 tiles of 256: the large shape, K = 1024
     (300, 204, 140, 2, 2, 2, 11),       # ragged
     (264, 520, 136, 1, 4, 1, 9),        # long contraction, n = 4
+    (256, 96, 256, 2, 2, 2, 12),        # full tiles, 3 stages of 16 k (odd: bounds-checked kernel)
+    (2048, 2048, 2048, 2, 2, 2, 16),    # 256 tiles of 256 x 256: the 8-wavefront shape, 64 stages
+    (2048, 2080, 2048, 2, 2, 2, 16),    # the same with 65 stages (odd: small shape)
 ]
 
 
