@@ -623,23 +623,13 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
     else hload<BSRC, MODE, TBN, NT, HK>(st, B, ldb, n0, k0, g.N, g.K, tid);
   };
 
-  constexpr bool kDeep = SPLIT == 3 || WGM * WGN == 8;
-  if constexpr (!kDeep) {
-    HStage<ASRC, TBM, NT, HK> sa;
-    HStage<BSRC, TBN, NT, HK> sb;
-    loadA(sa, kof(0));
-    loadB(sb, kof(0));
-    hstore<ASRC, TBM, NT, SPLIT, PA, HK>(sa, lds_a[0], tid);
-    hstore<BSRC, TBN, NT, SPLIT, PB, HK>(sb, lds_b[0], tid);
-    __syncthreads();
-    for (int c = 0; c < nchunks; ++c) {
-      const int cur = c & 1;
-      if (c + 1 < nchunks) {
-        loadA(sa, kof(c + 1));
-        loadB(sb, kof(c + 1));
-      }
-      const uint16_t* __restrict__ as = lds_a[cur];
-      const uint16_t* __restrict__ bs = lds_b[cur];
+  // the matrix instructions of one stage held in LDS buffer cur; between(g) runs after group g
+  // of MI x NJ instructions (SPLIT == 1: HK / 16 groups, one per 16 k; SPLIT == 3: the six
+  // partial products hi*lo, mid*mid, hi*mid, lo*hi, mid*hi, hi*hi)
+  auto multiply = [&](int cur, auto&& between) __attribute__((always_inline)) {
+    const uint16_t* __restrict__ as = lds_a[cur];
+    const uint16_t* __restrict__ bs = lds_b[cur];
+    if constexpr (SPLIT == 1) {
 #pragma unroll
       for (int h = 0; h < HK / 16; ++h) {
         Frag fa[MI], fb[NJ];
@@ -654,194 +644,17 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
 #pragma unroll
           for (int j = 0; j < NJ; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i].v, fb[j].v, acc[i][j], 0, 0, 0);
+        between(h);
       }
-      if (c + 1 < nchunks) {
-        hstore<ASRC, TBM, NT, SPLIT, PA, HK>(sa, lds_a[cur ^ 1], tid);
-        hstore<BSRC, TBN, NT, SPLIT, PB, HK>(sb, lds_b[cur ^ 1], tid);
-      }
-      __syncthreads();
-    }
-  } else if constexpr (MODE == 0) {
-    // fp32 or bf16 operands in plain layouts, full tiles, an even number of stages (the host
-    // sends everything else to the bounds-checked kernel): two statically addressed register
-    // sets.  Stage c is multiplied from LDS buffer c & 1; stage c + 1, already in registers, is
-    // converted and written to the other buffer in pieces placed between the groups of matrix
-    // instructions (the plain ALU work runs while the matrix pipe is busy); the global loads of
-    // stage c + 2 go into the set stage c has left.
-    constexpr int R = 2;
-    constexpr int IA = hstage_items<ASRC, TBM, NT, HK>(), IB = hstage_items<BSRC, TBN, NT, HK>();
-    constexpr int GROUPS = SPLIT == 3 ? 6 : HK / 16;         // groups of MI x NJ matrix instructions per stage
-    constexpr int PER = (IA + IB + GROUPS - 1) / GROUPS;     // conversion items after each group
-    HStage<ASRC, TBM, NT, HK> sa[R];
-    HStage<BSRC, TBN, NT, HK> sb[R];
-    loadA(sa[0], kof(0));
-    loadB(sb[0], kof(0));
-    loadA(sa[1], kof(1));
-    loadB(sb[1], kof(1));
-    hstore<ASRC, TBM, NT, SPLIT, PA, HK>(sa[0], lds_a[0], tid);
-    hstore<BSRC, TBN, NT, SPLIT, PB, HK>(sb[0], lds_b[0], tid);
-    __syncthreads();
-
-    auto stage = [&](HStage<ASRC, TBM, NT, HK>& la, HStage<BSRC, TBN, NT, HK>& lb,
-                     const HStage<ASRC, TBM, NT, HK>& ca, const HStage<BSRC, TBN, NT, HK>& cb, int c, bool load,
-                     bool conv) __attribute__((always_inline)) {
-      const int cur = c & 1;
-      if (load) {
-        loadA(la, kof(c + R));
-        loadB(lb, kof(c + R));
-      }
-      const uint16_t* __restrict__ as = lds_a[cur];
-      const uint16_t* __restrict__ bs = lds_b[cur];
-      auto convert = [&](int group) __attribute__((always_inline)) {
-        if (conv) {
-#pragma unroll
-          for (int it = group * PER; it < (group + 1) * PER && it < IA + IB; ++it) {
-            if (it < IA) hstore_item<ASRC, TBM, NT, SPLIT, PA, HK>(ca, it, lds_a[cur ^ 1], tid);
-            else hstore_item<BSRC, TBN, NT, SPLIT, PB, HK>(cb, it - IA, lds_b[cur ^ 1], tid);
-          }
-        }
-      };
-      if constexpr (SPLIT == 1) {
-#pragma unroll
-        for (int h = 0; h < HK / 16; ++h) {
-          Frag fa[MI], fb[NJ];
-#pragma unroll
-          for (int i = 0; i < MI; ++i)
-            fa[i].u = *reinterpret_cast<const uint4*>(as + (wm + 32 * i + li) * HSTRIDE + 16 * h + 8 * lg);
-#pragma unroll
-          for (int j = 0; j < NJ; ++j)
-            fb[j].u = *reinterpret_cast<const uint4*>(bs + (wn + 32 * j + li) * HSTRIDE + 16 * h + 8 * lg);
-#pragma unroll
-          for (int i = 0; i < MI; ++i)
-#pragma unroll
-            for (int j = 0; j < NJ; ++j)
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i].v, fb[j].v, acc[i][j], 0, 0, 0);
-          convert(h);
-        }
-      } else {
-        Frag fa[MI][3];
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-          for (int pl = 0; pl < 3; ++pl)
-            fa[i][pl].u = *reinterpret_cast<const uint4*>(as + pl * PA + (wm + 32 * i + li) * HSTRIDE + 8 * lg);
-        int group = 0;
-#pragma unroll
-        for (int pb = 2; pb >= 0; --pb) {
-          Frag fb[NJ];
-#pragma unroll
-          for (int j = 0; j < NJ; ++j)
-            fb[j].u = *reinterpret_cast<const uint4*>(bs + pb * PB + (wn + 32 * j + li) * HSTRIDE + 8 * lg);
-#pragma unroll
-          for (int pa = 2 - pb; pa >= 0; --pa) {
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-              for (int j = 0; j < NJ; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i][pa].v, fb[j].v, acc[i][j], 0, 0, 0);
-            convert(group);
-            ++group;
-          }
-        }
-      }
-      __syncthreads();
-    };
-    // steady state with loads in every iteration (see above), then the last two stages
-    int c0 = 0;
-    for (; c0 + 2 * R <= nchunks; c0 += R) {
-      stage(sa[0], sb[0], sa[1], sb[1], c0, true, true);
-      stage(sa[1], sb[1], sa[0], sb[0], c0 + 1, true, true);
-    }
-    stage(sa[0], sb[0], sa[1], sb[1], c0, false, true);
-    stage(sa[1], sb[1], sa[0], sb[0], c0 + 1, false, false);
-  } else {
-  HStage<ASRC, TBM, NT, HK> sa;
-  HStage<BSRC, TBN, NT, HK> sb;
-  loadA(sa, kof(0));
-  loadB(sb, kof(0));
-  hstore<ASRC, TBM, NT, SPLIT, PA, HK>(sa, lds_a[0], tid);
-  hstore<BSRC, TBN, NT, SPLIT, PB, HK>(sb, lds_b[0], tid);
-  if constexpr (SPLIT == 1) {
-    // Three stages in flight (8 wavefronts with 256 registers each): stage c is multiplied from
-    // LDS, stage c + 1 (loaded one iteration ago) is converted and written to the other LDS
-    // buffer after each half of the products, the global loads of stage c + 2 are issued.  Two
-    // stages of global loads in flight is what keeps HBM busy when the kernel streams fp32
-    // weights with one workgroup per CU.
-    constexpr int IA = hstage_items<ASRC, TBM, NT, HK>(), IB = hstage_items<BSRC, TBN, NT, HK>();
-    constexpr int HALF = (IA + IB + 1) / 2;
-    if (nchunks > 1) {
-      loadA(sa, kof(1));
-      loadB(sb, kof(1));
-    }
-    __syncthreads();
-    for (int c = 0; c < nchunks; ++c) {
-      const int cur = c & 1;
-      HStage<ASRC, TBM, NT, HK> na = sa;
-      HStage<BSRC, TBN, NT, HK> nb = sb;
-      if (c + 2 < nchunks) {
-        loadA(na, kof(c + 2));
-        loadB(nb, kof(c + 2));
-      }
-      const bool conv = c + 1 < nchunks;
-      const uint16_t* __restrict__ as = lds_a[cur];
-      const uint16_t* __restrict__ bs = lds_b[cur];
-#pragma unroll
-      for (int h = 0; h < HK / 16; ++h) {
-        Frag fa[MI], fb[NJ];
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-          fa[i].u = *reinterpret_cast<const uint4*>(as + (wm + 32 * i + li) * HSTRIDE + 16 * h + 8 * lg);
-#pragma unroll
-        for (int j = 0; j < NJ; ++j)
-          fb[j].u = *reinterpret_cast<const uint4*>(bs + (wn + 32 * j + li) * HSTRIDE + 16 * h + 8 * lg);
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-          for (int j = 0; j < NJ; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i].v, fb[j].v, acc[i][j], 0, 0, 0);
-        if (conv) {
-#pragma unroll
-          for (int it = h * HALF; it < (h + 1) * HALF && it < IA + IB; ++it) {
-            if (it < IA) hstore_item<ASRC, TBM, NT, SPLIT, PA, HK>(sa, it, lds_a[cur ^ 1], tid);
-            else hstore_item<BSRC, TBN, NT, SPLIT, PB, HK>(sb, it - IA, lds_b[cur ^ 1], tid);
-          }
-        }
-      }
-      __syncthreads();
-      sa = na;
-      sb = nb;
-    }
-  } else {
-    // Three stages in flight: stage c is multiplied from LDS, stage c + 1 (loaded one iteration
-    // ago, so already in registers) is split and written to the other LDS buffer in pieces
-    // placed between the groups of matrix instructions, so that the plain ALU work runs while
-    // the matrix pipe is busy, and the global loads of stage c + 2 are issued.
-    static_assert(HK == 16, "one matrix-instruction step per stage");
-    constexpr int IA = hstage_items<ASRC, TBM, NT, HK>(), IB = hstage_items<BSRC, TBN, NT, HK>();
-    static_assert(IA + IB <= 6, "one conversion slot per partial product");
-    if (nchunks > 1) {
-      loadA(sa, kof(1));
-      loadB(sb, kof(1));
-    }
-    __syncthreads();
-    for (int c = 0; c < nchunks; ++c) {
-      const int cur = c & 1;
-      HStage<ASRC, TBM, NT, HK> na = sa;
-      HStage<BSRC, TBN, NT, HK> nb = sb;
-      if (c + 2 < nchunks) {
-        loadA(na, kof(c + 2));
-        loadB(nb, kof(c + 2));
-      }
-      const bool conv = c + 1 < nchunks;
-      const uint16_t* __restrict__ as = lds_a[cur];
-      const uint16_t* __restrict__ bs = lds_b[cur];
+    } else {
+      static_assert(SPLIT == 1 || HK == 16, "one matrix-instruction step per stage");
       Frag fa[MI][3];
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int pl = 0; pl < 3; ++pl)
           fa[i][pl].u = *reinterpret_cast<const uint4*>(as + pl * PA + (wm + 32 * i + li) * HSTRIDE + 8 * lg);
-      int slot_id = 0;
+      int group = 0;
 #pragma unroll
       for (int pb = 2; pb >= 0; --pb) {
         Frag fb[NJ];
@@ -855,18 +668,88 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
 #pragma unroll
             for (int j = 0; j < NJ; ++j)
               acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i][pa].v, fb[j].v, acc[i][j], 0, 0, 0);
-          if (conv) {
-            if (slot_id < IA) hstore_item<ASRC, TBM, NT, SPLIT, PA, HK>(sa, slot_id, lds_a[cur ^ 1], tid);
-            else if (slot_id < IA + IB) hstore_item<BSRC, TBN, NT, SPLIT, PB, HK>(sb, slot_id - IA, lds_b[cur ^ 1], tid);
-          }
-          ++slot_id;
+          between(group);
+          ++group;
         }
       }
-      __syncthreads();
-      sa = na;
-      sb = nb;
     }
-  }
+  };
+
+  // Deep: the 8-wavefront shapes (256 registers per wavefront) and the split kernels keep two
+  // stages of global loads in flight; needs full tiles and an even number of stages (the host
+  // sends everything else to the bounds-checked kernel).
+  constexpr bool kDeep = (SPLIT == 3 || WGM * WGN == 8) && MODE == 0;
+  if constexpr (!kDeep) {
+    // one register set: the loads of stage c + 1 are issued before stage c is multiplied and
+    // written to the other LDS buffer after it
+    HStage<ASRC, TBM, NT, HK> sa;
+    HStage<BSRC, TBN, NT, HK> sb;
+    loadA(sa, kof(0));
+    loadB(sb, kof(0));
+    hstore<ASRC, TBM, NT, SPLIT, PA, HK>(sa, lds_a[0], tid);
+    hstore<BSRC, TBN, NT, SPLIT, PB, HK>(sb, lds_b[0], tid);
+    __syncthreads();
+    for (int c = 0; c < nchunks; ++c) {
+      const int cur = c & 1;
+      if (c + 1 < nchunks) {
+        loadA(sa, kof(c + 1));
+        loadB(sb, kof(c + 1));
+      }
+      multiply(cur, [](int) {});
+      if (c + 1 < nchunks) {
+        hstore<ASRC, TBM, NT, SPLIT, PA, HK>(sa, lds_a[cur ^ 1], tid);
+        hstore<BSRC, TBN, NT, SPLIT, PB, HK>(sb, lds_b[cur ^ 1], tid);
+      }
+      __syncthreads();
+    }
+  } else {
+    // Two statically addressed register sets.  Stage c is multiplied from LDS buffer c & 1;
+    // stage c + 1, already in registers, is converted and written to the other buffer in pieces
+    // placed between the groups of matrix instructions (the plain ALU work runs while the
+    // matrix pipe is busy); the global loads of stage c + 2 go into the set stage c has left.
+    // Rotating the sets by copies would make every iteration wait for the loads it has just
+    // issued; and the load counter is relative, so the steady state (every iteration loads: the
+    // number of younger loads in flight when a set is needed is always the same) is a loop of
+    // its own and the last two stages, after which nothing is loaded, are peeled.
+    constexpr int R = 2;
+    constexpr int IA = hstage_items<ASRC, TBM, NT, HK>(), IB = hstage_items<BSRC, TBN, NT, HK>();
+    constexpr int GROUPS = SPLIT == 3 ? 6 : HK / 16;
+    constexpr int PER = (IA + IB + GROUPS - 1) / GROUPS;     // conversion items after each group
+    HStage<ASRC, TBM, NT, HK> sa[R];
+    HStage<BSRC, TBN, NT, HK> sb[R];
+    loadA(sa[0], kof(0));
+    loadB(sb[0], kof(0));
+    loadA(sa[1], kof(1));
+    loadB(sb[1], kof(1));
+    hstore<ASRC, TBM, NT, SPLIT, PA, HK>(sa[0], lds_a[0], tid);
+    hstore<BSRC, TBN, NT, SPLIT, PB, HK>(sb[0], lds_b[0], tid);
+    __syncthreads();
+    auto stage = [&](HStage<ASRC, TBM, NT, HK>& la, HStage<BSRC, TBN, NT, HK>& lb,
+                     const HStage<ASRC, TBM, NT, HK>& ca, const HStage<BSRC, TBN, NT, HK>& cb, int c, bool load,
+                     bool conv) __attribute__((always_inline)) {
+      const int cur = c & 1;
+      if (load) {
+        loadA(la, kof(c + R));
+        loadB(lb, kof(c + R));
+      }
+      multiply(cur, [&](int group) __attribute__((always_inline)) {
+        if (conv) {
+#pragma unroll
+          for (int it = group * PER; it < (group + 1) * PER && it < IA + IB; ++it) {
+            if (it < IA) hstore_item<ASRC, TBM, NT, SPLIT, PA, HK>(ca, it, lds_a[cur ^ 1], tid);
+            else hstore_item<BSRC, TBN, NT, SPLIT, PB, HK>(cb, it - IA, lds_b[cur ^ 1], tid);
+          }
+        }
+      });
+      __syncthreads();
+    };
+    int c0 = 0;
+    for (; c0 + 2 * R <= nchunks; c0 += R) {
+      stage(sa[0], sb[0], sa[1], sb[1], c0, true, true);
+      stage(sa[1], sb[1], sa[0], sb[0], c0 + 1, true, true);
+    }
+    stage(sa[0], sb[0], sa[1], sb[1], c0, false, true);
+    stage(sa[1], sb[1], sa[0], sb[0], c0 + 1, false, false);
   }
 
   // Read-modify-write of the output tile.  All old values of a group of 32 x 32 blocks are
