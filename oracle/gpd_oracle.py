@@ -25,7 +25,11 @@ Readings taken where the paper is silent (all restated in the design notes):
   * after location the coefficients are interpolated by least squares from all
     remaining (clean, present) nodes;
   * whole-node errors (Sec. III error models) are located once for a whole stack
-    by the same search run on the aggregate of all element codewords (locate_nodes).
+    by the same search run on the aggregate of all element codewords (locate_nodes);
+  * the polynomial-time locator the remark after Thm 3 asks for is the classical
+    algebraic one (locator polynomial from the syndromes, in the Chebyshev basis),
+    valid inside the adversarial radius floor((P-Q)/2) and accepted by Algorithm 1's
+    own criterion (algebraic_locate).
 Parity pins: see tests/test_oracle_*.py.  Unpinned: the numeric value of rho
 (this build's choice).
 """
@@ -273,6 +277,99 @@ def algorithm1(z: np.ndarray, H: np.ndarray, tau: float, forced=()):
     return "failed", forced, np.zeros(len(forced))
 
 
+# --------------------------------------------------------------------------- algebraic locator
+
+
+def dual_syndromes(z: np.ndarray, pts: np.ndarray, count: int) -> np.ndarray:
+    """S_j = sum_s w_s T_j(x_s) z_s for j < count, with the barycentric weights
+    w_s = 1 / prod_{q != s} (x_s - x_q) (scaled to max |w| = 1) and T_j the Chebyshev
+    polynomials in the variable mapped affinely so that the points span [-1, 1].
+    sum_s w_s q(x_s) is the (len(pts)-1)-th divided difference of q: zero for every
+    polynomial q of degree <= len(pts) - 2, so S_j vanishes on the evaluations of a
+    polynomial with K coefficients as long as j <= len(pts) - K - 1: these are the
+    syndromes of the same (P, Q) MDS code (Sec. V) in another basis of the parity space."""
+    x = _unit_interval(pts)
+    n = len(x)
+    w = np.ones(n)
+    for s_ in range(n):
+        for q in range(n):
+            if q != s_:
+                w[s_] /= (x[s_] - x[q])
+    w /= np.abs(w).max()
+    T = _chebyshev_table(x, count)
+    return T @ (w * np.asarray(z, dtype=np.float64))
+
+
+def _unit_interval(pts: np.ndarray) -> np.ndarray:
+    pts = np.asarray(pts, dtype=np.float64)
+    lo, hi = pts.min(), pts.max()
+    return (2.0 * pts - (lo + hi)) / (hi - lo) if hi > lo else np.zeros_like(pts)
+
+
+def _chebyshev_table(x: np.ndarray, count: int) -> np.ndarray:
+    T = np.ones((max(count, 1), len(x)))
+    if count > 1:
+        T[1] = x
+    for j in range(2, count):
+        T[j] = 2.0 * x * T[j - 1] - T[j - 2]
+    return T[:count]
+
+
+def algebraic_locate(z: np.ndarray, H: np.ndarray, pts: np.ndarray, tau: float, forced=()):
+    """Polynomial-time error location inside the adversarial radius |A| <= floor((P-Q)/2)
+    (Sec. V, definition of the adversarial error model; the remark after Thm 3 asks for a
+    polynomial-time reconstruction in place of the exhaustive search of Algorithm 1).
+    This is the classical decoder of a real-number Reed-Solomon / MDS code:
+
+      errors e at the nodes A turn the syndromes into S_j = sum_{i in A} a_i T_j(x_i)
+      (a_i = w_i e_i).  For the locator polynomial L(x) = T_t(x) + sum_{k<t} c_k T_k(x),
+      zero exactly at the x_i, sum_i a_i T_j(x_i) L(x_i) = 0 for every j, and with
+      T_j T_k = (T_{j+k} + T_{|j-k|}) / 2 this is the linear system
+          sum_{k<t} c_k (S_{j+k} + S_{|j-k|}) = -(S_{j+t} + S_{|j-t|}),  j = 0 .. r - t - 1,
+      with r syndromes: solvable for t <= r / 2.
+
+    For t = 1, 2, ... the system is solved in the least-squares sense, the t nodes where
+    |L| is smallest are the candidate, and the candidate is accepted by the criterion of
+    Algorithm 1 (residual of H z on the span of those columns of H <= tau), so a wrong
+    candidate is never accepted silently.  Known-bad (forced) nodes are erasures: they are
+    left out of the syndromes, which costs one syndrome each.
+    Returns (status, support, e_hat) like algorithm1."""
+    r_full, ns = H.shape
+    y = H @ z
+    forced = tuple(sorted(int(f) for f in forced))
+    if not forced and np.linalg.norm(y) <= tau:
+        return "clean", (), np.zeros(0)
+    free = np.array([q for q in range(ns) if q not in forced], dtype=np.int64)
+    r = r_full - len(forced)
+    if forced:
+        res, e = support_residual(H, y, forced)
+        if res <= tau and len(forced) <= r_full - 1:
+            return "located", forced, e
+    if r < 2:
+        return "failed", forced, np.zeros(len(forced))
+    S = dual_syndromes(np.asarray(z, dtype=np.float64)[free], np.asarray(pts, dtype=np.float64)[free], r)
+    x = _unit_interval(np.asarray(pts, dtype=np.float64)[free])
+    for t in range(1, r // 2 + 1):
+        if len(forced) + t > r_full - 1:
+            break
+        rows = r - t
+        M = np.empty((rows, t))
+        b = np.empty(rows)
+        for j in range(rows):
+            for k in range(t):
+                M[j, k] = S[j + k] + S[abs(j - k)]
+            b[j] = -(S[j + t] + S[abs(j - t)])
+        c, *_ = np.linalg.lstsq(M, b, rcond=None)
+        T = _chebyshev_table(x, t + 1)
+        L = T[t] + c @ T[:t]
+        order = np.argsort(np.abs(L), kind="stable")[:t]
+        supp = tuple(sorted(forced + tuple(int(free[q]) for q in order)))
+        res, e = support_residual(H, y, supp)
+        if res <= tau:
+            return "located", supp, e
+    return "failed", forced, np.zeros(len(forced))
+
+
 # --------------------------------------------------------------------------- decode
 
 
@@ -315,7 +412,7 @@ def interpolate(Z: np.ndarray, pts: np.ndarray, K: int, mode: str) -> np.ndarray
 
 def decode_coefficients(Zt: np.ndarray, points: np.ndarray, K: int, useful,
                         present=None, mode: str = "first_k", correct: bool = False,
-                        rho: float = 2.0 ** -12, abs_floor: float = 0.0):
+                        rho: float = 2.0 ** -12, abs_floor: float = 0.0, locator: str = "search"):
     """Generic decoder: Zt[P, rows, cols] are evaluations at `points` of a matrix
     polynomial with K coefficients; returns {e: coefficient block} for e in `useful`
     and a DecodeReport.  (Remark after Thm 2; Sec. V Algorithm 1; App. 'Decoding
@@ -358,7 +455,10 @@ def decode_coefficients(Zt: np.ndarray, points: np.ndarray, K: int, useful,
     for idx in np.flatnonzero(flagged):
         r_, c_ = divmod(int(idx), cols)
         forced = tuple(np.flatnonzero(~finite[:, idx]))
-        status, supp, e_hat = algorithm1(Zs[:, idx], H, float(tau[idx]), forced)
+        if locator == "algebraic":
+            status, supp, e_hat = algebraic_locate(Zs[:, idx], H, pts, float(tau[idx]), forced)
+        else:
+            status, supp, e_hat = algorithm1(Zs[:, idx], H, float(tau[idx]), forced)
         if status == "failed":
             rep.n_failed += 1
             rep.failed.append((r_, c_))
@@ -380,12 +480,12 @@ def decode_coefficients(Zt: np.ndarray, points: np.ndarray, K: int, useful,
 
 
 def decode(Ct: np.ndarray, plan: Plan, present=None, mode: str = "first_k",
-           correct: bool = False, rho: float = 2.0 ** -12, abs_floor: float = 0.0):
+           correct: bool = False, rho: float = 2.0 ** -12, abs_floor: float = 0.0, locator: str = "search"):
     """C (N1 x Nc) from the node outputs Ct[P, N1/m, Nc/d]: block (i,k) of C is the
     coefficient of b^eC(i,k) (proof of Thm 2)."""
     useful = sorted(set(int(e) for e in plan.eC.ravel()))
     coeffs, rep = decode_coefficients(Ct, plan.points, plan.K, useful, present, mode,
-                                      correct, rho, abs_floor)
+                                      correct, rho, abs_floor, locator)
     rows, cols = Ct.shape[1], Ct.shape[2]
     C = np.zeros((plan.m * rows, plan.d * cols))
     for i in range(plan.m):
