@@ -328,10 +328,10 @@ def algebraic_locate(z: np.ndarray, H: np.ndarray, pts: np.ndarray, tau: float, 
           sum_{k<t} c_k (S_{j+k} + S_{|j-k|}) = -(S_{j+t} + S_{|j-t|}),  j = 0 .. r - t - 1,
       with r syndromes: solvable for t <= r / 2.
 
-    For t = 1, 2, ... the system is solved in the least-squares sense, the t nodes where
-    |L| is smallest are the candidate, and the candidate is accepted by the criterion of
-    Algorithm 1 (residual of H z on the span of those columns of H <= tau), so a wrong
-    candidate is never accepted silently.  Known-bad (forced) nodes are erasures: they are
+    For t = 1, 2, ... the system is solved in the least-squares sense; of the t + 2 nodes
+    where |L| is smallest the t with the largest fitted error values are the candidate, and
+    the candidate is accepted by the criterion of Algorithm 1 (residual of H z on the span of
+    those columns of H <= tau), so a wrong candidate is never accepted silently.  Known-bad (forced) nodes are erasures: they are
     left out of the syndromes, which costs one syndrome each.
     Returns (status, support, e_hat) like algorithm1."""
     r_full, ns = H.shape
@@ -362,8 +362,15 @@ def algebraic_locate(z: np.ndarray, H: np.ndarray, pts: np.ndarray, tau: float, 
         c, *_ = np.linalg.lstsq(M, b, rcond=None)
         T = _chebyshev_table(x, t + 1)
         L = T[t] + c @ T[:t]
-        order = np.argsort(np.abs(L), kind="stable")[:t]
-        supp = tuple(sorted(forced + tuple(int(free[q]) for q in order)))
+        # two guard nodes: with rounding, a neighbour of an erroneous node can have a smaller
+        # |L| than the node itself; the error values fitted on the t + 2 best nodes tell them apart
+        guard = max(0, min(2, r_full - 1 - len(forced) - t, len(free) - t))
+        order = np.argsort(np.abs(L), kind="stable")[:t + guard]
+        wide = tuple(sorted(forced + tuple(int(free[q]) for q in order)))
+        _, e_wide = support_residual(H, y, wide)
+        mag = {node: abs(v) for node, v in zip(wide, e_wide) if node not in forced}
+        picked = sorted(mag, key=lambda node: (-mag[node], node))[:t]
+        supp = tuple(sorted(forced + tuple(picked)))
         res, e = support_residual(H, y, supp)
         if res <= tau:
             return "located", supp, e

@@ -245,8 +245,10 @@ gpd_status_t decode_table(const std::vector<double>& pts, int K, const uint8_t* 
   t->out_off.resize(t->nout);
   t->coef.resize((size_t)t->nout * t->nin);
   t->H.resize((size_t)t->r * t->nin);
+  if (with_H) t->pts.resize(t->nin);
   for (int c = 0; c < t->nin; ++c) {
     t->node[c] = S[keep[c]];
+    if (with_H) t->pts[c] = pts[S[keep[c]]];
     t->in_off[c] = (int64_t)S[keep[c]] * bh * bw;
     for (int u = 0; u < t->nout; ++u) t->coef[(size_t)u * t->nin + c] = D[(size_t)u * ns + keep[c]];
     for (int i = 0; i < t->r; ++i) t->H[(size_t)i * t->nin + c] = H[(size_t)i * ns + keep[c]];

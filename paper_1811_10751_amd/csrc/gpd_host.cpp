@@ -418,6 +418,7 @@ size_t HostCombineTable::bytes() const {
   b += align_up(sizeof(double) * nout * nin, 16);
   b += align_up(sizeof(double) * r * nin, 16);
   b += align_up(sizeof(int32_t) * nin, 16);
+  b += align_up(sizeof(double) * nin, 16);
   b += 2 * align_up(sizeof(int32_t) * nin, 16) + 2 * align_up(sizeof(int32_t) * nout, 16);
   return align_up(b, 256);
 }
@@ -445,6 +446,7 @@ CombineTable HostCombineTable::pack(void* dst, const void* dev_base) const {
   t.coef64 = (const double*)put(coef.data(), sizeof(double) * nout * nin);
   t.H64 = (const double*)put(H.data(), sizeof(double) * r * nin);
   t.node = (const int32_t*)put(node.data(), sizeof(int32_t) * nin);
+  if (!pts.empty()) t.pts64 = (const double*)put(pts.data(), sizeof(double) * nin);
   if (!in_rows.empty() || !out_rows.empty()) {
     // limits given for one side only mean "no limit" on the other
     std::vector<int32_t> ir(in_rows), ic(in_cols), orow(out_rows), oc(out_cols);

@@ -80,7 +80,7 @@ void fill_node_report(const NodeSearchResult& res, const std::vector<int>& S, gp
 // One "combine" operation: out_q = sum_s coef[q][s] * in_s over equally shaped blocks.
 // The table lives in device memory as
 //   int64 in_off[nin]; int64 out_off[nout]; float coef[nout*nin]; float H[r*nin];
-//   double coef64[nout*nin]; double H64[r*nin]; int32 node[nin];
+//   double coef64[nout*nin]; double H64[r*nin]; int32 node[nin]; double pts64[nin] (decode tables)
 //   int32 in_rows[nin], in_cols[nin], out_rows[nout], out_cols[nout]   (only with limits)
 // With limits, rows/columns of a block at or beyond its limit read as zero (inputs) or are
 // not written (outputs): this is how zero-padded ragged edge blocks are handled.
@@ -94,6 +94,7 @@ struct CombineTable {
   const double* coef64 = nullptr;
   const double* H64 = nullptr;
   const int32_t* node = nullptr;
+  const double* pts64 = nullptr;       // evaluation points of the inputs (tables with H only)
   const int32_t* in_rows = nullptr;    // all four null when there are no limits
   const int32_t* in_cols = nullptr;
   const int32_t* out_rows = nullptr;
@@ -106,6 +107,7 @@ struct HostCombineTable {
   std::vector<int64_t> in_off, out_off;
   std::vector<double> coef, H;         // fp64 masters
   std::vector<int32_t> node;
+  std::vector<double> pts;             // evaluation point of every input (empty = not needed)
   std::vector<int32_t> in_rows, in_cols, out_rows, out_cols;   // empty = no limits
   size_t bytes() const;
   // serialise into `dst` (host) and return the device-side view relative to `dev_base`

@@ -12,6 +12,15 @@
 //            modified Gram-Schmidt, and the smallest residual <= tau wins (ties: the first
 //            support in lexicographic order).
 //   step 3   supports larger than |S| - K - 1 are never tried: decoding failure.
+// The exhaustive search is exponential in the support size (Algorithm 1's problem is NP-hard in
+// general, remark after Thm 3).  Once a size has more than 2^12 supports the wavefront first
+// tries the classical algebraic locator, which works inside the adversarial radius
+// floor((|S| - K) / 2) of Sec. V in polynomial time: syndromes in the Chebyshev basis of the
+// parity space (barycentric weights), locator polynomial from a small least-squares problem,
+// of the t + 2 nodes where it is smallest the t with the largest fitted errors as the
+// candidate, and Algorithm 1's own criterion (residual
+// of Hz on the candidate's columns <= tau) as the acceptance test, so a wrong candidate is
+// never accepted.  If that fails the exhaustive search goes on up to its budget.
 // Correction: e_hat solves H_A e = y in the least-squares sense; the outputs are the rows of
 // the all-node least-squares decoding matrix applied to z - e_hat, which equals least squares
 // over the nodes outside the support.
@@ -22,9 +31,11 @@ namespace gpd {
 
 namespace {
 
-constexpr int S_MAX = 8;                       // largest support size searched
+constexpr int S_MAX = 8;                       // largest support size searched exhaustively
+constexpr int A_MAX = 24;                      // largest support the algebraic locator may return
 constexpr int R_MAX = 64;                      // largest number of parity rows
-constexpr unsigned long long kBudget = 1ull << 22;   // supports tried per size, at most
+constexpr unsigned long long kFirstBudget = 1ull << 12;   // supports per size before the algebraic locator is tried
+constexpr unsigned long long kBudget = 1ull << 22;        // supports tried per size, at most
 
 struct LocateParams {
   CombineTable t;
@@ -42,6 +53,54 @@ __device__ __forceinline__ double wave_sum(double v) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
   return v;
+}
+
+__device__ __forceinline__ double wave_min(double v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmin(v, __shfl_xor(v, off));
+  return v;
+}
+__device__ __forceinline__ double wave_max(double v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmax(v, __shfl_xor(v, off));
+  return v;
+}
+
+// Least squares by the whole wavefront: the ncols columns are in Q[j][lane] (one element per
+// lane, zero beyond the rows in use), yv is the lane's element of the right-hand side.
+// Modified Gram-Schmidt with the right-hand side orthogonalised along; returns the residual
+// norm and leaves the coefficients in coef[0 .. ncols) (LDS).  One wavefront per workgroup.
+__device__ double wave_lsq(double (*Q)[64], double (*R)[A_MAX], double* coef, int ncols, double yv, int lane) {
+  for (int j = 0; j < ncols; ++j) {
+    double v = Q[j][lane];
+    for (int l = 0; l < j; ++l) {
+      const double ql = Q[l][lane];
+      const double dot = wave_sum(ql * v);
+      if (lane == 0) R[l][j] = dot;
+      v -= dot * ql;
+    }
+    const double nrm = sqrt(wave_sum(v * v));
+    if (lane == 0) R[j][j] = nrm;
+    Q[j][lane] = nrm > 0.0 ? v / nrm : 0.0;
+  }
+  double w = yv;
+  for (int j = 0; j < ncols; ++j) {
+    const double qj = Q[j][lane];
+    const double dot = wave_sum(qj * w);
+    if (lane == 0) coef[j] = dot;
+    w -= dot * qj;
+  }
+  const double res = sqrt(wave_sum(w * w));
+  __syncthreads();
+  if (lane == 0) {
+    for (int j = ncols - 1; j >= 0; --j) {
+      double acc = coef[j];
+      for (int l = j + 1; l < ncols; ++l) acc -= R[j][l] * coef[l];
+      coef[j] = R[j][j] > 0.0 ? acc / R[j][j] : 0.0;
+    }
+  }
+  __syncthreads();
+  return res;
 }
 
 // Residual of y against the columns `supp[0..size)` of H (r x ns, row-major) by modified
@@ -93,6 +152,12 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
   __shared__ unsigned long long binom[65][S_MAX + 1];
   __shared__ int freelist[64];
   __shared__ int forcedlist[64];
+  __shared__ double lsq_q[A_MAX][64];
+  __shared__ double lsq_r[A_MAX][A_MAX];
+  __shared__ double lsq_c[A_MAX];
+  __shared__ double syn[R_MAX];
+  __shared__ double xs[64];
+  __shared__ int supp_s[A_MAX];
 
   const int lane = threadIdx.x;
   const int ns = p.t.nin, r = p.t.r, nout = p.t.nout;
@@ -147,92 +212,211 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
     }
     __syncthreads();
     const int nfree = ns - nforced;
-    int max_size = r - 1;                                  // step 3: |A| <= |S| - K - 1
-    if (max_size > S_MAX) max_size = S_MAX;
+    const int max_size = r - 1;                            // step 3: |A| <= |S| - K - 1
 
     bool found = false;
     int best_size = 0;
-    unsigned long long best_c = 0;
     int supp[S_MAX];
-    for (int size = nforced > 1 ? nforced : 1; size <= max_size && !found; ++size) {
-      const int tpick = size - nforced;
-      const unsigned long long total = binom[nfree][tpick];
-      if (total > kBudget) break;
-      double my_res = 1.0e300;
-      unsigned long long my_c = ~0ull;
-      for (unsigned long long c = lane; c < total; c += 64) {
-        // unrank c among the tpick-subsets of the free nodes, lexicographic order
-        for (int f = 0; f < nforced; ++f) supp[f] = forcedlist[f];
-        unsigned long long rest = c;
-        int x = 0;
-        for (int i = 0; i < tpick; ++i) {
-          for (;; ++x) {
-            const unsigned long long cnt = binom[nfree - x - 1][tpick - i - 1];
-            if (rest < cnt) break;
-            rest -= cnt;
-          }
-          supp[nforced + i] = freelist[x];
-          ++x;
+    int size = nforced > 1 ? nforced : 1;
+    for (int phase = 0; phase < 3 && !found; ++phase) {
+      if (phase == 1) {
+        // ---- algebraic locator (see the head of this file); rr syndromes, t <= rr / 2
+        const int rr = r - nforced;
+        if (p.t.pts64 == nullptr || rr < 2 || size > max_size) continue;
+        const bool isfree = lane < ns && !((forced_mask >> lane) & 1ull);
+        const double x_raw = lane < ns ? p.t.pts64[lane] : 0.0;
+        const double lo = wave_min(isfree ? x_raw : 1.0e300), hi = wave_max(isfree ? x_raw : -1.0e300);
+        const double x = hi > lo ? (2.0 * x_raw - (lo + hi)) / (hi - lo) : 0.0;
+        xs[lane] = x;
+        __syncthreads();
+        double wgt = 0.0;
+        if (isfree) {
+          wgt = 1.0;
+          for (int q = 0; q < ns; ++q)
+            if (q != lane && !((forced_mask >> q) & 1ull)) wgt /= (x - xs[q]);
         }
-        const double res = support_residual(p.t.H64, r, ns, ys, supp, size, nullptr);
-        if (res <= tau && res < my_res) { my_res = res; my_c = c; }
-      }
-      // wave-wide arg-min (smallest residual, then smallest index)
+        const double wmax = wave_max(fabs(wgt));
+        const double a = wmax > 0.0 ? wgt / wmax * zs[lane] : 0.0;
+        {
+          double t0 = 1.0, t1 = x;
+          for (int j = 0; j < rr; ++j) {
+            const double tj = j == 0 ? 1.0 : t1;
+            const double sj = wave_sum(a * tj);
+            if (lane == 0) syn[j] = sj;
+            if (j >= 1) { const double t2 = 2.0 * x * t1 - t0; t0 = t1; t1 = t2; }
+          }
+        }
+        __syncthreads();
+        // (t = 0, the non-finite entries alone, only when there are too many of them for the
+        // exhaustive search to have tried that)
+        for (int t = size - nforced; t <= rr / 2 && t + nforced <= max_size && t + nforced <= A_MAX && !found; ++t) {
+          const int rows = rr - t;
+          unsigned long long cand = 0ull;
+          double lval = 0.0;
+          if (t > 0) {
+            for (int k = 0; k < t; ++k) {
+              const int d = lane > k ? lane - k : k - lane;
+              lsq_q[k][lane] = lane < rows ? syn[lane + k] + syn[d] : 0.0;
+            }
+            const int dt = lane > t ? lane - t : t - lane;
+            const double rhs = lane < rows ? -(syn[lane + t] + syn[dt]) : 0.0;
+            wave_lsq(lsq_q, lsq_r, lsq_c, t, rhs, lane);
+            // |L(x)| at this lane's node: T_t(x) + sum_k c_k T_k(x)
+            double t0 = 1.0, t1 = x;
+            for (int k = 0; k <= t; ++k) {
+              const double tk = k == 0 ? 1.0 : t1;
+              lval += (k < t ? lsq_c[k] : 1.0) * tk;
+              if (k >= 1) { const double t2 = 2.0 * x * t1 - t0; t0 = t1; t1 = t2; }
+            }
+            lval = isfree ? fabs(lval) : 1.0e300;
+          }
+          // The t + guard nodes where |L| is smallest (ties: the lowest node); with rounding a
+          // neighbour of an erroneous node can have a smaller |L| than the node itself, so up
+          // to two guard nodes are taken along and the error values fitted on all of them tell
+          // which t to keep (largest |e|, ties: the lowest node).
+          int guard = max_size - nforced - t;
+          if (guard > nfree - t) guard = nfree - t;
+          if (guard > A_MAX - nforced - t) guard = A_MAX - nforced - t;
+          guard = guard < 0 ? 0 : (guard > 2 ? 2 : guard);
+          unsigned long long wide = 0ull;
+          for (int i = 0; i < t + guard; ++i) {
+            double mv = ((wide >> lane) & 1ull) ? 1.0e300 : lval;
+            int mi = lane;
 #pragma unroll
-      for (int off = 32; off > 0; off >>= 1) {
-        const double o_res = __shfl_xor(my_res, off);
-        const unsigned long long o_c = __shfl_xor(my_c, off);
-        if (o_res < my_res || (o_res == my_res && o_c < my_c)) { my_res = o_res; my_c = o_c; }
+            for (int off = 32; off > 0; off >>= 1) {
+              const double ov = __shfl_xor(mv, off);
+              const int oi = __shfl_xor(mi, off);
+              if (ov < mv || (ov == mv && oi < mi)) { mv = ov; mi = oi; }
+            }
+            wide |= 1ull << mi;
+          }
+          if (guard > 0 && t > 0) {
+            const unsigned long long wall = wide | forced_mask;
+            const int wsize = t + guard + nforced;
+            __syncthreads();
+            if (lane == 0) {
+              int n = 0;
+              for (int q = 0; q < ns; ++q)
+                if ((wall >> q) & 1ull) supp_s[n++] = q;
+            }
+            __syncthreads();
+            for (int j = 0; j < wsize; ++j) lsq_q[j][lane] = lane < r ? p.t.H64[(int64_t)lane * ns + supp_s[j]] : 0.0;
+            wave_lsq(lsq_q, lsq_r, lsq_c, wsize, lane < r ? ys[lane] : 0.0, lane);
+            // lane j < wsize speaks for node supp_s[j]
+            const int my_node = lane < wsize ? supp_s[lane] : 64;
+            const bool eligible = lane < wsize && !((forced_mask >> my_node) & 1ull);
+            const double mag = eligible ? fabs(lsq_c[lane]) : -1.0;
+            for (int i = 0; i < t; ++i) {
+              double mv = (my_node < 64 && ((cand >> my_node) & 1ull)) ? -1.0 : mag;
+              int mi = my_node;
+#pragma unroll
+              for (int off = 32; off > 0; off >>= 1) {
+                const double ov = __shfl_xor(mv, off);
+                const int oi = __shfl_xor(mi, off);
+                if (ov > mv || (ov == mv && oi < mi)) { mv = ov; mi = oi; }
+              }
+              cand |= 1ull << mi;
+            }
+          } else {
+            cand = wide;
+          }
+          const unsigned long long all = cand | forced_mask;
+          const int csize = t + nforced;
+          if (lane == 0) {
+            int n = 0;
+            for (int q = 0; q < ns; ++q)
+              if ((all >> q) & 1ull) supp_s[n++] = q;
+          }
+          __syncthreads();
+          for (int j = 0; j < csize; ++j) lsq_q[j][lane] = lane < r ? p.t.H64[(int64_t)lane * ns + supp_s[j]] : 0.0;
+          __syncthreads();
+          const double res = wave_lsq(lsq_q, lsq_r, lsq_c, csize, lane < r ? ys[lane] : 0.0, lane);
+          if (res <= tau) { found = true; best_size = csize; }
+        }
+        continue;
       }
-      if (my_c != ~0ull) { found = true; best_size = size; best_c = my_c; }
+      const unsigned long long budget = phase == 0 ? kFirstBudget : kBudget;
+      unsigned long long best_c = 0;
+      for (; size <= max_size && size <= S_MAX && !found; ++size) {
+        const int tpick = size - nforced;
+        const unsigned long long total = binom[nfree][tpick];
+        if (total > budget) break;
+        double my_res = 1.0e300;
+        unsigned long long my_c = ~0ull;
+        for (unsigned long long c = lane; c < total; c += 64) {
+          // unrank c among the tpick-subsets of the free nodes, lexicographic order
+          for (int f = 0; f < nforced; ++f) supp[f] = forcedlist[f];
+          unsigned long long rest = c;
+          int x = 0;
+          for (int i = 0; i < tpick; ++i) {
+            for (;; ++x) {
+              const unsigned long long cnt = binom[nfree - x - 1][tpick - i - 1];
+              if (rest < cnt) break;
+              rest -= cnt;
+            }
+            supp[nforced + i] = freelist[x];
+            ++x;
+          }
+          const double res = support_residual(p.t.H64, r, ns, ys, supp, size, nullptr);
+          if (res <= tau && res < my_res) { my_res = res; my_c = c; }
+        }
+        // wave-wide arg-min (smallest residual, then smallest index)
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+          const double o_res = __shfl_xor(my_res, off);
+          const unsigned long long o_c = __shfl_xor(my_c, off);
+          if (o_res < my_res || (o_res == my_res && o_c < my_c)) { my_res = o_res; my_c = o_c; }
+        }
+        if (my_c != ~0ull) { found = true; best_size = size; best_c = my_c; }
+      }
+      if (found) {
+        // the winning support, for all lanes
+        const int tpick = best_size - nforced;
+        __syncthreads();
+        if (lane == 0) {
+          for (int f = 0; f < nforced; ++f) supp_s[f] = forcedlist[f];
+          unsigned long long rest = best_c;
+          int x = 0;
+          for (int i = 0; i < tpick; ++i) {
+            for (;; ++x) {
+              const unsigned long long cnt = binom[nfree - x - 1][tpick - i - 1];
+              if (rest < cnt) break;
+              rest -= cnt;
+            }
+            supp_s[nforced + i] = freelist[x];
+            ++x;
+          }
+        }
+        __syncthreads();
+      }
     }
 
     if (!found) {
       if (lane == 0) atomicAdd(&p.counters[3], 1u);
+      __syncthreads();
       continue;
     }
 
-    // ---- correction: every lane rebuilds the winning support and its e_hat
-    const int tpick = best_size - nforced;
-    for (int f = 0; f < nforced; ++f) supp[f] = forcedlist[f];
-    {
-      unsigned long long rest = best_c;
-      int x = 0;
-      for (int i = 0; i < tpick; ++i) {
-        for (;; ++x) {
-          const unsigned long long cnt = binom[nfree - x - 1][tpick - i - 1];
-          if (rest < cnt) break;
-          rest -= cnt;
-        }
-        supp[nforced + i] = freelist[x];
-        ++x;
-      }
-    }
-    // The located entries are now treated as erasures: set them to zero, recompute the
-    // syndrome and solve H_A e' = H z' for the values the code predicts there (-e').  This
-    // keeps all arithmetic at the scale of the clean responses however large the error was.
-    double z_orig[S_MAX];
-    for (int j = 0; j < best_size; ++j) z_orig[j] = zs[supp[j]];
+    // ---- correction.  The located entries are now treated as erasures: set them to zero,
+    // recompute the syndrome and solve H_A e' = H z' for the values the code predicts there
+    // (-e').  This keeps all arithmetic at the scale of the clean responses however large the
+    // error was.
+    const double z_orig = lane < best_size ? zs[supp_s[lane]] : 0.0;
     __syncthreads();
-    if (lane == 0)
-      for (int j = 0; j < best_size; ++j) zs[supp[j]] = 0.0;
+    if (lane < best_size) zs[supp_s[lane]] = 0.0;
     __syncthreads();
     double y2 = 0.0;
     if (lane < r) {
       const double* __restrict__ hrow = p.t.H64 + (int64_t)lane * ns;
       for (int s = 0; s < ns; ++s) y2 += hrow[s] * zs[s];
     }
+    for (int j = 0; j < best_size; ++j) lsq_q[j][lane] = lane < r ? p.t.H64[(int64_t)lane * ns + supp_s[j]] : 0.0;
     __syncthreads();
-    ys[lane] = y2;
-    __syncthreads();
-    double e_hat[S_MAX];
-    support_residual(p.t.H64, r, ns, ys, supp, best_size, e_hat);
-    __syncthreads();
-    if (lane == 0)
-      for (int j = 0; j < best_size; ++j) zs[supp[j]] = -e_hat[j];
+    wave_lsq(lsq_q, lsq_r, lsq_c, best_size, y2, lane);
+    if (lane < best_size) zs[supp_s[lane]] = -lsq_c[lane];
     __syncthreads();
     // estimated error value = received - predicted
-    for (int j = 0; j < best_size; ++j) e_hat[j] = z_orig[j] + e_hat[j];
+    const double e_hat = lane < best_size ? z_orig + lsq_c[lane] : 0.0;
     bool write = lane < nout;
     if (write && p.t.out_rows) write = row < p.t.out_rows[lane] && col < p.t.out_cols[lane];
     if (write) {
@@ -245,13 +429,13 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
     if (lane == 0) base = atomicAdd(&p.counters[4], (uint32_t)best_size);
     base = __shfl(base, 0);
     if (lane < best_size) {
-      const int s = supp[lane];
+      const int s = supp_s[lane];
       const int node = p.t.node[s];
       atomicAdd(&p.node_err[node], 1);
       if ((int64_t)base + lane < p.located_cap) {
         gpd_located_t rec;
         rec.node = node; rec.row = (int32_t)row; rec.col = (int32_t)col;
-        rec.magnitude = ((forced_mask >> s) & 1ull) ? __uint_as_float(0x7fc00000u) : (float)e_hat[lane];
+        rec.magnitude = ((forced_mask >> s) & 1ull) ? __uint_as_float(0x7fc00000u) : (float)e_hat;
         p.located[base + lane] = rec;
       }
     }
