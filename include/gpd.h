@@ -307,6 +307,8 @@ gpd_status_t gpd_coded_layer_step(gpd_layer_t* layer, int32_t phase, float* Wt,
  * 1 = S~_p (forward node outputs, what the all-gather of Sec. VII would carry), 2 = Delta~_p
  * stored (N_out/m) x (batch/d2), 3 = C~_p stored (N_in/n) x (batch/d2) (backward node
  * outputs), 4 = Dhat_p, 5 = Xhat_p (update operands).  For inspection and fault injection.
+ * Layers with worker_dtype == GPD_BF16 hold 0 and 2 (the operands of the bf16 products) as bf16
+ * stacks of the same shape.
  * Layers with worker_dtype != GPD_F32 and batch % 64 == 0 hold 4 and 5 in another form: each
  * fp32 value v as three bf16 values hi = bf16(v), mid = bf16(v - hi), lo = bf16(v - hi - mid)
  * (round to nearest even), in three planes P*rows*cols elements apart, every plane

@@ -377,6 +377,8 @@ class Layer:
         _check(load_library().gpd_layer_workspace_view(self.handle, which, C.byref(off), C.byref(r), C.byref(c)))
         ws = self.workspace(device)
         n = self.P * r.value * c.value
+        if which in (0, 2) and self.worker_dtype == GPD_BF16:
+            return ws[off.value:off.value + 2 * n].view(torch.bfloat16).view(self.P, r.value, c.value)
         if which >= 4 and self.worker_dtype != GPD_F32 and self.batch % 64 == 0:
             # three bf16 planes (hi, mid, lo), each [P][cols/16][rows][16]
             return ws[off.value:off.value + 6 * n].view(torch.bfloat16).view(3, self.P, c.value // 16, r.value, 16)

@@ -634,6 +634,7 @@ extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, floa
   const bool split = d.worker_dtype == GPD_F32_SPLIT;
   const bool bf16 = d.worker_dtype == GPD_BF16 || split;       // products on the bf16 matrix cores
   const bool skinny = skinny_ok(L) && !bf16;
+  const bool xt_bf16 = bf16 && !split;      // X~_p, Delta~_p are stored in bf16
 
   if (phase == GPD_STEP_FORWARD) {
     if (!out) return fail(GPD_E_INVALID, "forward: out is null");
@@ -645,7 +646,9 @@ extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, floa
       return GPD_OK;
     }, s, &t);
     if (st != GPD_OK) return st;
-    st = launch_combine(s, t, X, d.batch, Xt, L->nb1, false, L->wc, L->nb1, none);
+    // (bf16 layers: rounded to bf16 here instead of on the way into the product's LDS tile: the
+    // same round-to-nearest-even of the same fp32 value, half the bytes for the product to read)
+    st = launch_combine(s, t, X, d.batch, Xt, L->nb1, xt_bf16 ? 1 : 0, L->wc, L->nb1, none);
     if (st != GPD_OK) return st;
     // S~_p = W~_p X~_p   (step O1 on every node)
     if (skinny) {
@@ -656,7 +659,7 @@ extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, floa
       g.M = L->wr; g.K = L->wc; g.N = L->nb1;
       g.lda = L->wc; g.ldb = L->nb1; g.ldc = L->nb1;
       g.strideA = L->wr * L->wc; g.strideB = L->wc * L->nb1; g.strideC = L->wr * L->nb1;
-      g.batch = P; g.mfma_bf16 = bf16; g.split3 = split;
+      g.batch = P; g.mfma_bf16 = bf16; g.split3 = split; g.b_bf16 = xt_bf16;
       st = launch_gemm(s, g);
     }
     if (st != GPD_OK) return st;
@@ -682,7 +685,7 @@ extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, floa
       return GPD_OK;
     }, s, &t);
     if (st != GPD_OK) return st;
-    st = launch_combine(s, t, Dlt, d.batch, Dt, L->nb2, false, L->wr, L->nb2, none);
+    st = launch_combine(s, t, Dlt, d.batch, Dt, L->nb2, xt_bf16 ? 1 : 0, L->wr, L->nb2, none);
     if (st != GPD_OK) return st;
   }
   {
@@ -733,7 +736,7 @@ extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, floa
       g.M = L->wc; g.K = L->wr; g.N = L->nb2;
       g.lda = L->wc; g.ldb = L->nb2; g.ldc = L->nb2;
       g.strideA = L->wr * L->wc; g.strideB = L->wr * L->nb2; g.strideC = L->wc * L->nb2;
-      g.batch = P; g.mfma_bf16 = bf16; g.split3 = split;
+      g.batch = P; g.mfma_bf16 = bf16; g.split3 = split; g.b_bf16 = xt_bf16;
       st = launch_gemm(s, g);
       if (st != GPD_OK) return st;
     }
