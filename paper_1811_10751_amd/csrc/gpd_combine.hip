@@ -9,6 +9,8 @@
 // and produces the nout outputs one after the other; the coefficient table is read with
 // wave-uniform addresses (scalar loads), so no LDS is needed.
 #include "gpd_internal.hpp"
+#include <cstring>
+#include <type_traits>
 
 namespace gpd {
 
@@ -110,6 +112,15 @@ struct CombineParams {
   uint32_t* counters;
   int32_t* list;
   int32_t cap;
+  // Tables as kernel arguments (scalar loads, independent of the vector memory counter: a
+  // table entry read from memory between two stores of the output loop would have to wait for
+  // the first store to complete).  The block offsets always; coef and H when karg is set (they
+  // fit), else those two are read from memory.
+  int32_t karg;
+  int64_t in_off_k[64];
+  int64_t out_off_k[64];
+  float coef_k[256];
+  float H_k[256];
 };
 
 // NIN_MAX: compile-time bound on nin (register array); VEC: columns per thread.
@@ -135,18 +146,26 @@ __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
     col = active ? (idx - row * p.cols_vec) * VEC : 0;
   }
 
+  // All inputs are requested back to back: the address of an input that is not to be read
+  // (beyond nin, beyond a block limit, an idle thread) is replaced by that of the first input's
+  // first element and the value discarded afterwards, so that there is no branch, and no wait
+  // for a table entry, between two loads.  The block offsets are kernel arguments.
   float z[NIN_MAX][VEC];
+  const int64_t lane_off = row * p.in_ld + col;
+  bool take[NIN_MAX];
 #pragma unroll
   for (int s = 0; s < NIN_MAX; ++s) {
-    bool take = s < p.nin && active;
-    if constexpr (LIMITS) take = take && row < p.in_rows[s] && col < p.in_cols[s];
-    if (take) {
-      load_vec<VEC>(p.in + p.in_off[s] + row * p.in_ld + col, z[s]);
-    } else {
-#pragma unroll
-      for (int v = 0; v < VEC; ++v) z[s][v] = 0.f;
-    }
+    take[s] = s < p.nin && active;
+    if constexpr (LIMITS) take[s] = take[s] && row < p.in_rows[s < p.nin ? s : 0] && col < p.in_cols[s < p.nin ? s : 0];
   }
+#pragma unroll
+  for (int s = 0; s < NIN_MAX; ++s)
+    load_vec<VEC>(p.in + (take[s] ? p.in_off_k[s] + lane_off : p.in_off_k[0]), z[s]);
+#pragma unroll
+  for (int s = 0; s < NIN_MAX; ++s)
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) z[s][v] = take[s] ? z[s][v] : 0.f;
+  const bool karg = p.karg != 0;
 
   // non-finite responses are replaced by zero everywhere (and always passed on, below)
   bool bad[VEC];
@@ -170,22 +189,27 @@ __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
     float sig2[VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) sig2[v] = 0.f;
-    for (int i = 0; i < p.r; ++i) {
-      float y[VEC];
+    auto syndromes = [&](auto from_args) __attribute__((always_inline)) {
+      constexpr bool K = decltype(from_args)::value;
+      for (int i = 0; i < p.r; ++i) {
+        float y[VEC];
 #pragma unroll
-      for (int v = 0; v < VEC; ++v) y[v] = 0.f;
-      const float* __restrict__ hrow = p.H + (int64_t)i * p.nin;
+        for (int v = 0; v < VEC; ++v) y[v] = 0.f;
+        const float* __restrict__ hrow = K ? p.H_k + i * p.nin : p.H + (int64_t)i * p.nin;
 #pragma unroll
-      for (int s = 0; s < NIN_MAX; ++s) {
-        if (s < p.nin) {
-          const float h = hrow[s];
+        for (int s = 0; s < NIN_MAX; ++s) {
+          if (s < p.nin) {
+            const float h = hrow[s];
 #pragma unroll
-          for (int v = 0; v < VEC; ++v) y[v] = fmaf(h, z[s][v], y[v]);
+            for (int v = 0; v < VEC; ++v) y[v] = fmaf(h, z[s][v], y[v]);
+          }
         }
-      }
 #pragma unroll
-      for (int v = 0; v < VEC; ++v) sig2[v] = fmaf(y[v], y[v], sig2[v]);
-    }
+        for (int v = 0; v < VEC; ++v) sig2[v] = fmaf(y[v], y[v], sig2[v]);
+      }
+    };
+    if (karg) syndromes(std::true_type{});
+    else syndromes(std::false_type{});
     float ratio = 0.f;
 #pragma unroll
     for (int v = 0; v < VEC; ++v) {
@@ -216,30 +240,38 @@ __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
   if (!active) return;
   const int q_begin = blockIdx.y * p.q_chunk;
   const int q_end = min(p.nout, q_begin + p.q_chunk);
-  for (int q = q_begin; q < q_end; ++q) {
-    float acc[VEC];
+  // (two copies of the loop, so that the copy that reads its tables from the kernel arguments
+  // contains no vector load at all and its stores are never waited for)
+  auto outputs = [&](auto from_args) __attribute__((always_inline)) {
+    constexpr bool K = decltype(from_args)::value;
+    for (int q = q_begin; q < q_end; ++q) {
+      float acc[VEC];
 #pragma unroll
-    for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
-    const float* __restrict__ crow = p.coef + (int64_t)q * p.nin;
+      for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
+      const float* __restrict__ crow = K ? p.coef_k + q * p.nin : p.coef + (int64_t)q * p.nin;
 #pragma unroll
-    for (int s = 0; s < NIN_MAX; ++s) {
-      if (s < p.nin) {
-        const float c = crow[s];
+      for (int s = 0; s < NIN_MAX; ++s) {
+        if (s < p.nin) {
+          const float c = crow[s];
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) acc[v] = fmaf(c, z[s][v], acc[v]);
+          for (int v = 0; v < VEC; ++v) acc[v] = fmaf(c, z[s][v], acc[v]);
+        }
       }
+      if constexpr (LIMITS) {
+        if (!(row < p.out_rows[q] && col < p.out_cols[q])) continue;
+      }
+      const int64_t oq = p.out_off_k[q];
+      const int64_t o = oq + row * p.out_ld + col;
+      if constexpr (OUT == 2) {
+        // k-blocked: [col / 16][row][col % 16], what the split GEMM reads as one contiguous stage
+        const int64_t ob = oq + ((col >> 4) * p.rows + row) * 16 + (col & 15);
+        store_vec_split3<VEC>(reinterpret_cast<uint16_t*>(p.out) + ob, p.out_plane, acc);
+      } else if constexpr (OUT == 1) store_vec_bf16<VEC>(reinterpret_cast<uint16_t*>(p.out) + o, acc);
+      else store_vec<VEC>(reinterpret_cast<float*>(p.out) + o, acc);
     }
-    if constexpr (LIMITS) {
-      if (!(row < p.out_rows[q] && col < p.out_cols[q])) continue;
-    }
-    const int64_t o = p.out_off[q] + row * p.out_ld + col;
-    if constexpr (OUT == 2) {
-      // k-blocked: [col / 16][row][col % 16], what the split GEMM reads as one contiguous stage
-      const int64_t ob = p.out_off[q] + ((col >> 4) * p.rows + row) * 16 + (col & 15);
-      store_vec_split3<VEC>(reinterpret_cast<uint16_t*>(p.out) + ob, p.out_plane, acc);
-    } else if constexpr (OUT == 1) store_vec_bf16<VEC>(reinterpret_cast<uint16_t*>(p.out) + o, acc);
-    else store_vec<VEC>(reinterpret_cast<float*>(p.out) + o, acc);
-  }
+  };
+  if (karg) outputs(std::true_type{});
+  else outputs(std::false_type{});
 }
 
 template <int NIN_MAX, int VEC>
@@ -303,6 +335,14 @@ gpd_status_t launch_combine(hipStream_t stream, const CombineTable& t, const flo
   p.in_rows = t.in_rows; p.in_cols = t.in_cols; p.out_rows = t.out_rows; p.out_cols = t.out_cols;
   p.rho = screen.rho; p.rho_screen = 0.5f * screen.rho; p.abs_floor = screen.abs_floor;
   p.counters = screen.counters; p.list = screen.list; p.cap = screen.cap;
+  if (!t.k_offsets) return fail(GPD_E_UNSUPPORTED, "combine: more than 64 inputs or outputs");
+  std::memcpy(p.in_off_k, t.k_in_off, sizeof(p.in_off_k));
+  std::memcpy(p.out_off_k, t.k_out_off, sizeof(p.out_off_k));
+  p.karg = t.k_coefs ? 1 : 0;
+  if (p.karg) {
+    std::memcpy(p.coef_k, t.k_coef, sizeof(p.coef_k));
+    std::memcpy(p.H_k, t.k_H, sizeof(p.H_k));
+  }
 
   // widest vector the shapes, leading dimensions, block offsets and base addresses allow
   const size_t out_elem = out_kind ? 2 : 4;

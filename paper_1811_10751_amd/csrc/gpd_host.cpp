@@ -446,6 +446,16 @@ CombineTable HostCombineTable::pack(void* dst, const void* dev_base) const {
   t.coef64 = (const double*)put(coef.data(), sizeof(double) * nout * nin);
   t.H64 = (const double*)put(H.data(), sizeof(double) * r * nin);
   t.node = (const int32_t*)put(node.data(), sizeof(int32_t) * nin);
+  if (nin <= 64 && nout <= 64) {
+    t.k_offsets = true;
+    for (int i = 0; i < nin; ++i) t.k_in_off[i] = in_off[i];
+    for (int i = 0; i < nout; ++i) t.k_out_off[i] = out_off[i];
+    if (nout * nin <= 256 && r * nin <= 256) {
+      t.k_coefs = true;
+      for (int i = 0; i < nout * nin; ++i) t.k_coef[i] = c32[i];
+      for (int i = 0; i < r * nin; ++i) t.k_H[i] = h32[i];
+    }
+  }
   if (!pts.empty()) t.pts64 = (const double*)put(pts.data(), sizeof(double) * nin);
   if (!in_rows.empty() || !out_rows.empty()) {
     // limits given for one side only mean "no limit" on the other

@@ -100,6 +100,12 @@ struct CombineTable {
   const int32_t* out_rows = nullptr;
   const int32_t* out_cols = nullptr;
   int limit_align = 4;                 // largest of 1, 2, 4 dividing every column limit
+  // Host copies of the small parts, handed to the kernels as kernel arguments (those are always
+  // read through the scalar cache, whatever the kernel stores meanwhile): the block offsets
+  // (nin, nout <= 64) and, when they fit (nout * nin <= 256 and r * nin <= 256), coef and H.
+  bool k_offsets = false, k_coefs = false;
+  int64_t k_in_off[64] = {}, k_out_off[64] = {};
+  float k_coef[256] = {}, k_H[256] = {};
 };
 
 struct HostCombineTable {
