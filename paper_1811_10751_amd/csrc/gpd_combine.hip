@@ -119,8 +119,8 @@ struct CombineParams {
   int32_t karg;
   int64_t in_off_k[64];
   int64_t out_off_k[64];
-  float coef_k[256];
-  float H_k[256];
+  float coef_k[256 + 64];    // (64 more, zero: a row is always read NIN_MAX entries long)
+  float H_k[256 + 64];
 };
 
 // NIN_MAX: compile-time bound on nin (register array); VEC: columns per thread.
@@ -195,13 +195,24 @@ __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
         float y[VEC];
 #pragma unroll
         for (int v = 0; v < VEC; ++v) y[v] = 0.f;
-        const float* __restrict__ hrow = K ? p.H_k + i * p.nin : p.H + (int64_t)i * p.nin;
+        if constexpr (K) {
+          const float* __restrict__ hrow = p.H_k + i * p.nin;
+          float h[NIN_MAX];
 #pragma unroll
-        for (int s = 0; s < NIN_MAX; ++s) {
-          if (s < p.nin) {
-            const float h = hrow[s];
+          for (int s = 0; s < NIN_MAX; ++s) h[s] = hrow[s];
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) y[v] = fmaf(h, z[s][v], y[v]);
+          for (int s = 0; s < NIN_MAX; ++s)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) y[v] = fmaf(h[s], z[s][v], y[v]);
+        } else {
+          const float* __restrict__ hrow = p.H + (int64_t)i * p.nin;
+#pragma unroll
+          for (int s = 0; s < NIN_MAX; ++s) {
+            if (s < p.nin) {
+              const float h = hrow[s];
+#pragma unroll
+              for (int v = 0; v < VEC; ++v) y[v] = fmaf(h, z[s][v], y[v]);
+            }
           }
         }
 #pragma unroll
@@ -248,13 +259,25 @@ __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
       float acc[VEC];
 #pragma unroll
       for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
-      const float* __restrict__ crow = K ? p.coef_k + q * p.nin : p.coef + (int64_t)q * p.nin;
+      if constexpr (K) {
+        // the whole row in one go (entries beyond nin meet inputs that are zero)
+        const float* __restrict__ crow = p.coef_k + q * p.nin;
+        float c[NIN_MAX];
 #pragma unroll
-      for (int s = 0; s < NIN_MAX; ++s) {
-        if (s < p.nin) {
-          const float c = crow[s];
+        for (int s = 0; s < NIN_MAX; ++s) c[s] = crow[s];
 #pragma unroll
-          for (int v = 0; v < VEC; ++v) acc[v] = fmaf(c, z[s][v], acc[v]);
+        for (int s = 0; s < NIN_MAX; ++s)
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) acc[v] = fmaf(c[s], z[s][v], acc[v]);
+      } else {
+        const float* __restrict__ crow = p.coef + (int64_t)q * p.nin;
+#pragma unroll
+        for (int s = 0; s < NIN_MAX; ++s) {
+          if (s < p.nin) {
+            const float c = crow[s];
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[v] = fmaf(c, z[s][v], acc[v]);
+          }
         }
       }
       if constexpr (LIMITS) {
@@ -339,9 +362,11 @@ gpd_status_t launch_combine(hipStream_t stream, const CombineTable& t, const flo
   std::memcpy(p.in_off_k, t.k_in_off, sizeof(p.in_off_k));
   std::memcpy(p.out_off_k, t.k_out_off, sizeof(p.out_off_k));
   p.karg = t.k_coefs ? 1 : 0;
+  std::memset(p.coef_k, 0, sizeof(p.coef_k));
+  std::memset(p.H_k, 0, sizeof(p.H_k));
   if (p.karg) {
-    std::memcpy(p.coef_k, t.k_coef, sizeof(p.coef_k));
-    std::memcpy(p.H_k, t.k_H, sizeof(p.H_k));
+    std::memcpy(p.coef_k, t.k_coef, sizeof(t.k_coef));
+    std::memcpy(p.H_k, t.k_H, sizeof(t.k_H));
   }
 
   // widest vector the shapes, leading dimensions, block offsets and base addresses allow
