@@ -27,60 +27,74 @@ constexpr int kRowChunk = 64;           // rows of W~_p one workgroup of the bac
 // ---------------------------------------------------------------- skinny forward
 
 // S~[p][r][b] = sum_c W~[p][r][c] * X~[p][c][b];  NB = per-node batch (columns of X~_p).
-// A workgroup owns kFwdRows consecutive rows of W~_p, i.e. one contiguous piece of memory, and
+// A workgroup owns FR consecutive rows of W~_p, i.e. one contiguous piece of memory, and
 // walks through it like a copy kernel (thread t reads 16 bytes at column 4t, 4t+1024, ...), so
 // that concurrent workgroups spread over all HBM channels.  The X~ values of a thread's
-// columns are fetched once and reused for every row.  Row sums: wavefront shuffle, then LDS.
-constexpr int kFwdRows = 8;
+// columns are fetched once and reused for every row.  All FR row loads of a strip are issued
+// before the first is used; rows beyond the matrix (last group only) re-read its last row and
+// are never stored, so that the loop has no branch.  Row sums: wavefront shuffle, then LDS.
+constexpr int fwd_rows(int nb) { return nb == 1 ? 2 : 4; }
 
 template <int NB>
 __global__ __launch_bounds__(256) void skinny_forward_kernel(const float* __restrict__ Wt,
                                                              const float* __restrict__ Xt,
                                                              float* __restrict__ St, int rows,
                                                              int cols) {
-  __shared__ float part[4][kFwdRows][NB];
+  constexpr int FR = fwd_rows(NB);
+  __shared__ float part[4][FR][NB];
   const int p = blockIdx.y;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int row0 = blockIdx.x * kFwdRows;
+  const int row0 = blockIdx.x * FR;
   const float* __restrict__ x = Xt + (int64_t)p * cols * NB;
-  const float* __restrict__ w0 = Wt + ((int64_t)p * rows + row0) * cols;
-  const int nrows = min(kFwdRows, rows - row0);
-  float acc[kFwdRows][NB];
+  const int nrows = min(FR, rows - row0);
+  const float* wr[FR];
 #pragma unroll
-  for (int r = 0; r < kFwdRows; ++r)
+  for (int r = 0; r < FR; ++r) wr[r] = Wt + ((int64_t)p * rows + row0 + min(r, nrows - 1)) * cols;
+  float acc[FR][NB];
+#pragma unroll
+  for (int r = 0; r < FR; ++r)
 #pragma unroll
     for (int b = 0; b < NB; ++b) acc[r][b] = 0.f;
-  const bool vec_ok = (cols & 3) == 0;
-  if (vec_ok) {
+  if ((cols & 3) == 0) {
     for (int c = tid * 4; c < cols; c += 1024) {
-      float xv[4][NB];
+      float4 wv[FR];
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
+      for (int r = 0; r < FR; ++r) wv[r] = *reinterpret_cast<const float4*>(wr[r] + c);
+      float xv[4 * NB];                      // X~[c .. c+3][0 .. NB-1], contiguous
+      if constexpr ((NB & 3) == 0 || NB == 1) {
 #pragma unroll
-        for (int b = 0; b < NB; ++b) xv[e][b] = x[(int64_t)(c + e) * NB + b];
-#pragma unroll
-      for (int r = 0; r < kFwdRows; ++r) {
-        if (r < nrows) {
-          const float4 wv = *reinterpret_cast<const float4*>(w0 + (int64_t)r * cols + c);
-          const float we[4] = {wv.x, wv.y, wv.z, wv.w};
-#pragma unroll
-          for (int e = 0; e < 4; ++e)
-#pragma unroll
-            for (int b = 0; b < NB; ++b) acc[r][b] = fmaf(we[e], xv[e][b], acc[r][b]);
+        for (int q = 0; q < NB; ++q) {
+          const float4 t = *reinterpret_cast<const float4*>(x + (int64_t)c * NB + 4 * q);
+          xv[4 * q] = t.x; xv[4 * q + 1] = t.y; xv[4 * q + 2] = t.z; xv[4 * q + 3] = t.w;
         }
+      } else {
+#pragma unroll
+        for (int q = 0; q < 4 * NB; ++q) xv[q] = x[(int64_t)c * NB + q];
+      }
+#pragma unroll
+      for (int r = 0; r < FR; ++r) {
+        const float we[4] = {wv[r].x, wv[r].y, wv[r].z, wv[r].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int b = 0; b < NB; ++b) acc[r][b] = fmaf(we[e], xv[e * NB + b], acc[r][b]);
       }
     }
   } else {
-    for (int c = tid; c < cols; c += 256)
+    for (int c = tid; c < cols; c += 256) {
+      float wv[FR];
 #pragma unroll
-      for (int r = 0; r < kFwdRows; ++r)
-        if (r < nrows)
+      for (int r = 0; r < FR; ++r) wv[r] = wr[r][c];
 #pragma unroll
-          for (int b = 0; b < NB; ++b)
-            acc[r][b] = fmaf(w0[(int64_t)r * cols + c], x[(int64_t)c * NB + b], acc[r][b]);
+      for (int b = 0; b < NB; ++b) {
+        const float xb = x[(int64_t)c * NB + b];
+#pragma unroll
+        for (int r = 0; r < FR; ++r) acc[r][b] = fmaf(wv[r], xb, acc[r][b]);
+      }
+    }
   }
 #pragma unroll
-  for (int r = 0; r < kFwdRows; ++r)
+  for (int r = 0; r < FR; ++r)
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
       float v = acc[r][b];
@@ -89,7 +103,7 @@ __global__ __launch_bounds__(256) void skinny_forward_kernel(const float* __rest
       if (lane == 0) part[wave][r][b] = v;
     }
   __syncthreads();
-  if (tid < kFwdRows * NB) {
+  if (tid < FR * NB) {
     const int r = tid / NB, b = tid % NB;
     if (r < nrows)
       St[((int64_t)p * rows + row0 + r) * NB + b] = (part[0][r][b] + part[1][r][b]) + (part[2][r][b] + part[3][r][b]);
@@ -127,15 +141,8 @@ __global__ __launch_bounds__(256) void skinny_backward_update_kernel(
 #pragma unroll
     for (int b = 0; b < (NB2 > 0 ? NB2 : 1); ++b) cs[e][b] = 0.f;
 
-  for (int r = r0; r < r1; ++r) {
-    float* wp = Wt + ((int64_t)p * rows + r) * cols + c0;
-    float w[4] = {0.f, 0.f, 0.f, 0.f};
-    if (vec) {
-      const float4 t = *reinterpret_cast<const float4*>(wp);
-      w[0] = t.x; w[1] = t.y; w[2] = t.z; w[3] = t.w;
-    } else {
-      for (int e = 0; e < 4; ++e) if (c0 + e < cols) w[e] = wp[e];
-    }
+  // one row: w is the old value; returns through nw the updated one
+  auto row_math = [&](int r, const float (&w)[4], float (&nw)[4]) {
     if constexpr (DO_BWD) {
       const float* __restrict__ d = Dt + ((int64_t)p * rows + r) * NB2;
 #pragma unroll
@@ -147,7 +154,6 @@ __global__ __launch_bounds__(256) void skinny_backward_update_kernel(
     }
     if constexpr (DO_UPD) {
       const float* __restrict__ dh = Dh + ((int64_t)p * rows + r) * NBU;
-      float nw[4];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         float u = 0.f;
@@ -155,6 +161,38 @@ __global__ __launch_bounds__(256) void skinny_backward_update_kernel(
         for (int b = 0; b < NBU; ++b) u = fmaf(dh[b], xh[e][b], u);
         nw[e] = fmaf(keep, w[e], eta * u);
       }
+    }
+  };
+  int r = r0;
+  if (vec) {
+    // four rows in flight per thread: all loads first, then the arithmetic and the stores
+    constexpr int RU = 4;
+    for (; r + RU <= r1; r += RU) {
+      float* wp = Wt + ((int64_t)p * rows + r) * cols + c0;
+      float4 t[RU];
+#pragma unroll
+      for (int k = 0; k < RU; ++k) t[k] = *reinterpret_cast<const float4*>(wp + (int64_t)k * cols);
+#pragma unroll
+      for (int k = 0; k < RU; ++k) {
+        const float w[4] = {t[k].x, t[k].y, t[k].z, t[k].w};
+        float nw[4];
+        row_math(r + k, w, nw);
+        if constexpr (DO_UPD)
+          *reinterpret_cast<float4*>(wp + (int64_t)k * cols) = make_float4(nw[0], nw[1], nw[2], nw[3]);
+      }
+    }
+  }
+  for (; r < r1; ++r) {
+    float* wp = Wt + ((int64_t)p * rows + r) * cols + c0;
+    float w[4] = {0.f, 0.f, 0.f, 0.f}, nw[4];
+    if (vec) {
+      const float4 t = *reinterpret_cast<const float4*>(wp);
+      w[0] = t.x; w[1] = t.y; w[2] = t.z; w[3] = t.w;
+    } else {
+      for (int e = 0; e < 4; ++e) if (c0 + e < cols) w[e] = wp[e];
+    }
+    row_math(r, w, nw);
+    if constexpr (DO_UPD) {
       if (vec) {
         *reinterpret_cast<float4*>(wp) = make_float4(nw[0], nw[1], nw[2], nw[3]);
       } else {
@@ -547,7 +585,8 @@ namespace {
 
 template <int NB>
 void launch_skinny_fwd(hipStream_t s, const float* Wt, const float* Xt, float* St, int rows, int cols, int P) {
-  hipLaunchKernelGGL((skinny_forward_kernel<NB>), dim3((rows + kFwdRows - 1) / kFwdRows, P), dim3(256), 0, s, Wt, Xt,
+  constexpr int FR = fwd_rows(NB);
+  hipLaunchKernelGGL((skinny_forward_kernel<NB>), dim3((rows + FR - 1) / FR, P), dim3(256), 0, s, Wt, Xt,
                      St, rows, cols);
 }
 
