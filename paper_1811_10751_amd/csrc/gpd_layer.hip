@@ -24,6 +24,45 @@ namespace {
 constexpr int kSkinnyMaxBatch = 8;      // widest per-node batch the streaming kernels take
 constexpr int kRowChunk = 64;           // rows of W~_p one workgroup of the backward pass owns
 
+// ---------------------------------------------------------------- small operand encodes
+
+// The three operand encodes of a small-batch backward / update step (Delta~, Dhat, Xhat: a few
+// KB each) in one launch; blockIdx.y is the job.
+//   out[p][r][b] = sum_s coef[p][s] * in[off[s] + r * ld + b], block s reading as zero at
+//   r >= lim_r[s] or b >= lim_c[s] (zero padding of ragged edge blocks).
+constexpr int kSmallMaxIn = 8;
+struct SmallEnc {
+  const float* in = nullptr;           // the unencoded matrix (device)
+  const float* coef = nullptr;         // device, [P][nin]: evaluation point powers
+  float* out = nullptr;                // [P][rows][nb]
+  int32_t ld = 0, nin = 0, rows = 0, nb = 0;
+  int32_t count = 0;                   // P * rows * nb
+  int64_t off[kSmallMaxIn] = {};
+  int32_t lim_r[kSmallMaxIn] = {}, lim_c[kSmallMaxIn] = {};
+};
+struct SmallEncJobs { SmallEnc job[3]; };
+
+__global__ __launch_bounds__(256) void encode_small_kernel(const SmallEncJobs jobs) {
+  const SmallEnc& j = jobs.job[blockIdx.y];
+  const uint32_t i = blockIdx.x * 256u + threadIdx.x;      // count < 2^31 (host-checked)
+  if (i >= (uint32_t)j.count) return;
+  const uint32_t pr = i / (uint32_t)j.nb;
+  const int b = (int)(i - pr * (uint32_t)j.nb);
+  const int p = (int)(pr / (uint32_t)j.rows), r = (int)(pr - (uint32_t)p * (uint32_t)j.rows);
+  float z[kSmallMaxIn], cs[kSmallMaxIn];
+  // one round of loads: blocks beyond nin re-read the last one with weight 0
+#pragma unroll
+  for (int s = 0; s < kSmallMaxIn; ++s) {
+    const int sc = min(s, j.nin - 1);
+    cs[s] = s < j.nin ? j.coef[p * j.nin + sc] : 0.f;
+    z[s] = (r < j.lim_r[sc] && b < j.lim_c[sc]) ? j.in[j.off[sc] + (int64_t)r * j.ld + b] : 0.f;
+  }
+  float a = 0.f;
+#pragma unroll
+  for (int s = 0; s < kSmallMaxIn; ++s) a = fmaf(cs[s], z[s], a);
+  j.out[i] = a;
+}
+
 // ---------------------------------------------------------------- skinny forward
 
 // S~[p][r][b] = sum_c W~[p][r][c] * X~[p][c][b];  NB = per-node batch (columns of X~_p).
@@ -636,6 +675,26 @@ gpd_status_t skinny_bu_nbu(hipStream_t s, float* Wt, const float* Dt, const floa
   }
 }
 
+// In-kernel form of an encode table over a grid_r x grid_c grid of bh x bw blocks of a
+// total_rows x total_cols matrix; false when the table does not fit it.
+bool make_small(const CombineTable& t, const float* in, int64_t ld, int64_t total_rows, int64_t total_cols,
+                int grid_r, int grid_c, int64_t bh, int64_t bw, float* out, int P, SmallEnc* f) {
+  if (!t.k_offsets || t.nin != grid_r * grid_c || t.nin > kSmallMaxIn || t.nout != P || ld > INT32_MAX ||
+      bh > INT32_MAX || bw > INT32_MAX)
+    return false;
+  f->in = in; f->coef = t.coef; f->out = out;
+  f->ld = (int32_t)ld; f->nin = t.nin; f->rows = (int32_t)bh; f->nb = (int32_t)bw;
+  if ((int64_t)P * bh * bw > INT32_MAX - 256) return false;
+  f->count = (int32_t)(P * bh * bw);
+  const std::vector<int32_t> lr = limits(total_rows, bh, grid_r), lc = limits(total_cols, bw, grid_c);
+  for (int i = 0; i < grid_r; ++i)
+    for (int j = 0; j < grid_c; ++j) {
+      const int q = i * grid_c + j;
+      f->off[q] = t.k_in_off[q]; f->lim_r[q] = lr[i]; f->lim_c[q] = lc[j];
+    }
+  return true;
+}
+
 bool skinny_ok(const gpd_layer_t* L) {
   const int64_t b = L->desc.batch;
   const bool bu = b == 1 || b == 2 || b == 4 || b == 8;
@@ -715,36 +774,53 @@ extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, floa
   // ---- BACKWARD_UPDATE
   if (!Dlt) return fail(GPD_E_INVALID, "backward: Dlt is null");
   const bool do_bwd = out != nullptr;
-  CombineTable t;
+  CombineTable tD, tDh, tXh;
   if (do_bwd) {
     // Delta~_p = sum_{i,k} Delta_{i,k} b_p^eD(i,k), stored (N_out/m) x (batch/d2)
     st = L->ring.cached("encD", [&](HostCombineTable* ht) {
       *ht = encode_table(c.pts, L->eD, c.m, d.d2, L->wr, L->nb2, d.batch);
       grid_limits(d.N_out, d.batch, c.m, d.d2, L->wr, L->nb2, &ht->in_rows, &ht->in_cols);
       return GPD_OK;
-    }, s, &t);
-    if (st != GPD_OK) return st;
-    st = launch_combine(s, t, Dlt, d.batch, Dt, L->nb2, xt_bf16 ? 1 : 0, L->wr, L->nb2, none);
+    }, s, &tD);
     if (st != GPD_OK) return st;
   }
-  {
-    // update operands: Dhat_p = sum_i Delta_i a_p^i,  Xhat_p = sum_j X_j b_p^j
-    st = L->ring.cached("encDh", [&](HostCombineTable* hd) {
-      *hd = encode_table(c.pts, L->eUd, c.m, 1, L->wr, d.batch, d.batch);
-      grid_limits(d.N_out, d.batch, c.m, 1, L->wr, d.batch, &hd->in_rows, &hd->in_cols);
-      return GPD_OK;
-    }, s, &t);
-    if (st != GPD_OK) return st;
-    st = launch_combine(s, t, Dlt, d.batch, Dh, d.batch, L->upd_planes ? 2 : 0, L->wr, d.batch, none,
+  // update operands: Dhat_p = sum_i Delta_i a_p^i,  Xhat_p = sum_j X_j b_p^j
+  st = L->ring.cached("encDh", [&](HostCombineTable* hd) {
+    *hd = encode_table(c.pts, L->eUd, c.m, 1, L->wr, d.batch, d.batch);
+    grid_limits(d.N_out, d.batch, c.m, 1, L->wr, d.batch, &hd->in_rows, &hd->in_cols);
+    return GPD_OK;
+  }, s, &tDh);
+  if (st != GPD_OK) return st;
+  st = L->ring.cached("encXh", [&](HostCombineTable* hx) {
+    *hx = encode_table(c.pts, L->eUx, c.n, 1, L->wc, d.batch, d.batch);
+    grid_limits(d.N_in, d.batch, c.n, 1, L->wc, d.batch, &hx->in_rows, &hx->in_cols);
+    return GPD_OK;
+  }, s, &tXh);
+  if (st != GPD_OK) return st;
+  // small batches on the streaming path: the two or three encodes (a few KB each) in one launch
+  SmallEncJobs sj;
+  int nj = 0;
+  bool small = skinny;
+  if (small && do_bwd)
+    small = make_small(tD, Dlt, d.batch, d.N_out, d.batch, c.m, d.d2, L->wr, L->nb2, Dt, P, &sj.job[nj++]);
+  small = small && make_small(tDh, Dlt, d.batch, d.N_out, d.batch, c.m, 1, L->wr, d.batch, Dh, P, &sj.job[nj++]) &&
+          make_small(tXh, X, d.batch, d.N_in, d.batch, c.n, 1, L->wc, d.batch, Xh, P, &sj.job[nj++]);
+  if (small) {
+    int64_t most = 0;
+    for (int q = 0; q < nj; ++q) most = std::max<int64_t>(most, sj.job[q].count);
+    if (most > 0) {
+      hipLaunchKernelGGL(encode_small_kernel, dim3((unsigned)((most + 255) / 256), nj), dim3(256), 0, s, sj);
+      GPD_HIP(hipGetLastError());
+    }
+  } else {
+    if (do_bwd) {
+      st = launch_combine(s, tD, Dlt, d.batch, Dt, L->nb2, xt_bf16 ? 1 : 0, L->wr, L->nb2, none);
+      if (st != GPD_OK) return st;
+    }
+    st = launch_combine(s, tDh, Dlt, d.batch, Dh, d.batch, L->upd_planes ? 2 : 0, L->wr, d.batch, none,
                         P * L->wr * d.batch);
     if (st != GPD_OK) return st;
-    st = L->ring.cached("encXh", [&](HostCombineTable* hx) {
-      *hx = encode_table(c.pts, L->eUx, c.n, 1, L->wc, d.batch, d.batch);
-      grid_limits(d.N_in, d.batch, c.n, 1, L->wc, d.batch, &hx->in_rows, &hx->in_cols);
-      return GPD_OK;
-    }, s, &t);
-    if (st != GPD_OK) return st;
-    st = launch_combine(s, t, X, d.batch, Xh, d.batch, L->upd_planes ? 2 : 0, L->wc, d.batch, none,
+    st = launch_combine(s, tXh, X, d.batch, Xh, d.batch, L->upd_planes ? 2 : 0, L->wc, d.batch, none,
                         P * L->wc * d.batch);
     if (st != GPD_OK) return st;
   }

@@ -20,6 +20,8 @@ CASES = [
     (64, 96, 1, 4, 2, 1, 1, 24, "auto"),          # cfg2's code at a small size (skinny kernels)
     (64, 96, 1, 4, 2, 1, 1, 24, "u=v^n"),
     (10, 96, 1, 4, 2, 1, 1, 24, "auto"),          # 10 rows, m = 4: padded to 12
+    (70, 50, 2, 2, 4, 1, 1, 20, "u=v^n"),         # batch 2, N_in padded to 52: encodes inside the product kernels
+    (66, 54, 2, 2, 2, 2, 2, 16, "auto"),          # batch 2 split over d1 = d2 = 2 (per-node batch 1)
     (70, 50, 4, 2, 4, 1, 1, 20, "u=v^n"),         # N_in = 50, n = 4: padded to 52; batch 4 skinny
     (130, 260, 8, 2, 2, 2, 2, 16, "u=v^n"),       # d1 = d2 = 2, skinny kernels
     (66, 36, 8, 2, 2, 1, 4, 24, "u=v^n"),         # d2 = 4: K_b = 18, ill-conditioned (amp ~1e5)
