@@ -21,6 +21,18 @@ namespace gpd {
 
 namespace {
 
+// W~ is read (and rewritten) exactly once per pass: streaming accesses that do not displace the
+// small operands from the caches and leave no dirty lines behind for the end of the kernel
+typedef float v4f __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 stream_load4(const float* p) {
+  const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+  return make_float4(t.x, t.y, t.z, t.w);
+}
+__device__ __forceinline__ void stream_store4(float* p, float a, float b, float c, float d) {
+  v4f t; t.x = a; t.y = b; t.z = c; t.w = d;
+  __builtin_nontemporal_store(t, reinterpret_cast<v4f*>(p));
+}
+
 constexpr int kSkinnyMaxBatch = 8;      // widest per-node batch the streaming kernels take
 constexpr int kRowChunk = 64;           // rows of W~_p one workgroup of the backward pass owns
 
@@ -98,7 +110,7 @@ __global__ __launch_bounds__(256) void skinny_forward_kernel(const float* __rest
     for (int c = tid * 4; c < cols; c += 1024) {
       float4 wv[FR];
 #pragma unroll
-      for (int r = 0; r < FR; ++r) wv[r] = *reinterpret_cast<const float4*>(wr[r] + c);
+      for (int r = 0; r < FR; ++r) wv[r] = stream_load4(wr[r] + c);
       float xv[4 * NB];                      // X~[c .. c+3][0 .. NB-1], contiguous
       if constexpr ((NB & 3) == 0 || NB == 1) {
 #pragma unroll
@@ -210,14 +222,14 @@ __global__ __launch_bounds__(256) void skinny_backward_update_kernel(
       float* wp = Wt + ((int64_t)p * rows + r) * cols + c0;
       float4 t[RU];
 #pragma unroll
-      for (int k = 0; k < RU; ++k) t[k] = *reinterpret_cast<const float4*>(wp + (int64_t)k * cols);
+      for (int k = 0; k < RU; ++k) t[k] = stream_load4(wp + (int64_t)k * cols);
 #pragma unroll
       for (int k = 0; k < RU; ++k) {
         const float w[4] = {t[k].x, t[k].y, t[k].z, t[k].w};
         float nw[4];
         row_math(r + k, w, nw);
         if constexpr (DO_UPD)
-          *reinterpret_cast<float4*>(wp + (int64_t)k * cols) = make_float4(nw[0], nw[1], nw[2], nw[3]);
+          stream_store4(wp + (int64_t)k * cols, nw[0], nw[1], nw[2], nw[3]);
       }
     }
   }
