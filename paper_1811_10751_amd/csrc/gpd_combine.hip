@@ -45,9 +45,20 @@ __device__ __forceinline__ void load_vec(const float* p, float (&v)[VEC]) {
   }
 }
 
-template <int VEC>
+// NT: streaming (nontemporal) store, for outputs nothing on the device reads next
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+template <int VEC, bool NT = false>
 __device__ __forceinline__ void store_vec(float* p, const float (&v)[VEC]) {
-  if constexpr (VEC == 4) {
+  if constexpr (NT && VEC == 4) {
+    v4f t; t.x = v[0]; t.y = v[1]; t.z = v[2]; t.w = v[3];
+    __builtin_nontemporal_store(t, reinterpret_cast<v4f*>(p));
+  } else if constexpr (NT && VEC == 2) {
+    v2f t; t.x = v[0]; t.y = v[1];
+    __builtin_nontemporal_store(t, reinterpret_cast<v2f*>(p));
+  } else if constexpr (NT) {
+    __builtin_nontemporal_store(v[0], p);
+  } else if constexpr (VEC == 4) {
     *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
   } else if constexpr (VEC == 2) {
     *reinterpret_cast<float2*>(p) = make_float2(v[0], v[1]);
@@ -290,7 +301,7 @@ __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
         const int64_t ob = oq + ((col >> 4) * p.rows + row) * 16 + (col & 15);
         store_vec_split3<VEC>(reinterpret_cast<uint16_t*>(p.out) + ob, p.out_plane, acc);
       } else if constexpr (OUT == 1) store_vec_bf16<VEC>(reinterpret_cast<uint16_t*>(p.out) + o, acc);
-      else store_vec<VEC>(reinterpret_cast<float*>(p.out) + o, acc);
+      else store_vec<VEC, SCREEN>(reinterpret_cast<float*>(p.out) + o, acc);
     }
   };
   if (karg) outputs(std::true_type{});
