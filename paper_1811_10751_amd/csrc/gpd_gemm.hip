@@ -981,6 +981,78 @@ gpd_status_t launch_planes(hipStream_t stream, HGemmParams p, int64_t batch) {
   return GPD_OK;
 }
 
+// ---------------------------------------------------------------- bf16 products with very few rows
+
+// C = beta C + alpha A B with M <= 8 rows of fp32 A (row-major) and row-major bf16 B: the
+// output layer of a classifier.  A 128-row matrix-core tile would be 1/16 full and its k-loop one
+// chain of dependent steps on a few workgroups, so this is a streaming kernel instead: a
+// workgroup of 16 wavefronts owns 64 output columns of one batch entry, each wavefront 1/16 of
+// k, a lane one column.  A goes through LDS in chunks of kShortKC values of k, rounded to bf16
+// (nearest even) like on the matrix cores; products are summed in fp32.
+constexpr int kShortM = 8, kShortKC = 1024, kShortWaves = 16;
+
+__device__ __forceinline__ float bf16_round(float x) { return __uint_as_float(pack_bf16(x, 0.f) << 16); }
+
+__global__ __launch_bounds__(64 * kShortWaves) void short_m_bf16_kernel(const HGemmParams g) {
+  __shared__ float4 As[kShortKC][2];                     // [k][rows 0-3 | rows 4-7], zero beyond M
+  __shared__ float part[kShortWaves][kShortM][64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n = blockIdx.x * 64 + lane;
+  const int nc = min(n, g.N - 1);                        // lanes beyond N re-read the last column
+  const float* __restrict__ A = reinterpret_cast<const float*>(g.A) + (int64_t)blockIdx.y * g.sA;
+  const uint16_t* __restrict__ B = reinterpret_cast<const uint16_t*>(g.B) + (int64_t)blockIdx.y * g.sB + nc;
+  float acc[kShortM];
+#pragma unroll
+  for (int r = 0; r < kShortM; ++r) acc[r] = 0.f;
+  constexpr int KW = kShortKC / kShortWaves;             // values of k per wavefront and chunk
+  constexpr int U = 16;
+  static_assert(KW % U == 0, "whole groups of loads");
+  for (int kc = 0; kc < g.K; kc += kShortKC) {
+    __syncthreads();                                     // the previous chunk has been consumed
+    {
+      const int k = kc + tid;                            // kShortKC == number of threads
+      float a[kShortM];
+#pragma unroll
+      for (int r = 0; r < kShortM; ++r) a[r] = (r < g.M && k < g.K) ? bf16_round(A[(int64_t)r * g.lda + k]) : 0.f;
+      As[tid][0] = make_float4(a[0], a[1], a[2], a[3]);
+      As[tid][1] = make_float4(a[4], a[5], a[6], a[7]);
+    }
+    __syncthreads();
+    const int kw = wave * KW;                            // offset of this wavefront's values inside the chunk
+#pragma unroll 1
+    for (int u0 = 0; u0 < KW; u0 += U) {
+      float b[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int k = min(kc + kw + u0 + u, g.K - 1);    // beyond K: A is zero there
+        b[u] = __uint_as_float((uint32_t)B[(int64_t)k * g.ldb] << 16);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const float4 lo = As[kw + u0 + u][0], hi = As[kw + u0 + u][1];
+        acc[0] = fmaf(lo.x, b[u], acc[0]); acc[1] = fmaf(lo.y, b[u], acc[1]);
+        acc[2] = fmaf(lo.z, b[u], acc[2]); acc[3] = fmaf(lo.w, b[u], acc[3]);
+        acc[4] = fmaf(hi.x, b[u], acc[4]); acc[5] = fmaf(hi.y, b[u], acc[5]);
+        acc[6] = fmaf(hi.z, b[u], acc[6]); acc[7] = fmaf(hi.w, b[u], acc[7]);
+      }
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < kShortM; ++r) part[wave][r][lane] = acc[r];
+  __syncthreads();
+  // thread (r, column) adds the 16 partial sums in wavefront order
+  if (tid < kShortM * 64) {
+    const int r = tid >> 6;
+    float v = 0.f;
+#pragma unroll
+    for (int w = 0; w < kShortWaves; ++w) v += part[w][r][lane];
+    if (r < g.M && n < g.N) {
+      float* c = g.C + (int64_t)blockIdx.y * g.sC + (int64_t)r * g.ldc + n;
+      *c = g.beta != 0.f ? fmaf(g.beta, *c, g.alpha * v) : g.alpha * v;
+    }
+  }
+}
+
 template <int ASRC, int BSRC, int SPLIT>
 gpd_status_t launch_bf16_t(hipStream_t stream, HGemmParams p, int64_t batch, bool aligned) {
   // same two workgroup shapes as the fp32 kernel; the large one needs full aligned tiles
@@ -1112,6 +1184,14 @@ gpd_status_t launch_gemm(hipStream_t stream, const GemmArgs& a) {
       if (!a.transA && a.transB) return launch_bf16_t<SRC_F32_KC, SRC_F32_KC, 3>(stream, h, a.batch, al);
       if (a.transA && !a.transB) return launch_bf16_t<SRC_F32_RC, SRC_F32_RC, 3>(stream, h, a.batch, al);
       return launch_bf16_t<SRC_F32_RC, SRC_F32_KC, 3>(stream, h, a.batch, al);
+    }
+    if (!a.transA && !a.a_bf16 && a.b_bf16 && a.M >= 1 && a.M <= kShortM && a.N > 0 && a.K > 0 && a.batch > 0 &&
+        a.batch <= 65535) {
+      static_assert(kShortKC == 64 * kShortWaves, "one thread per value of k of a chunk");
+      const dim3 grid((unsigned)((a.N + 63) / 64), (unsigned)a.batch);
+      hipLaunchKernelGGL(short_m_bf16_kernel, grid, dim3(64 * kShortWaves), 0, stream, h);
+      GPD_HIP(hipGetLastError());
+      return GPD_OK;
     }
     if (!a.transA && !a.a_bf16 && !a.b_bf16) return launch_bf16_t<SRC_F32_KC, SRC_F32_RC, 1>(stream, h, a.batch, al);
     if (!a.transA && !a.a_bf16 && a.b_bf16) return launch_bf16_t<SRC_F32_KC, SRC_BF16_RC, 1>(stream, h, a.batch, al);

@@ -63,6 +63,8 @@ LAYER_CASES = [
     (300, 200, 64, 2, 4, 1, 1, 32),       # update operands as bf16 planes, ragged tiles, one ring of stages
     (512, 1024, 192, 2, 4, 1, 1, 32),     # planes, full tiles, steady-state loop and tail
     (1024, 1024, 128, 2, 4, 1, 1, 32),    # planes, 256 full tiles
+    (10, 1000, 64, 2, 4, 1, 1, 32),       # output layer: 5 rows per node (few-row forward kernel)
+    (7, 520, 24, 1, 4, 1, 1, 20),         # 7 rows, batch 24 (ragged 64-column groups)
 ]
 
 
