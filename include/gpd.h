@@ -263,7 +263,17 @@ typedef struct {
   void* hip_stream;
 } gpd_layer_desc_t;
 
-typedef enum { GPD_STEP_FORWARD = 0, GPD_STEP_BACKWARD_UPDATE = 1 } gpd_phase_t;
+typedef enum {
+  GPD_STEP_FORWARD = 0,
+  GPD_STEP_BACKWARD_UPDATE = 1,
+  /* OR-ed into the phase: the master's element-wise step that follows the decode (Sec. VII,
+   * steps C1 / C2, logistic activation) is applied by the decode itself:
+   *   FORWARD:          out = f(S), f(s) = 1 / (1 + exp(-s))
+   *   BACKWARD_UPDATE:  out = C o X o (1 - X)  (Hadamard products): the error Delta of the layer
+   *                     below when X, this layer's input, is that layer's logistic output.
+   * Same values as gpd_sigmoid_fwd / gpd_sigmoid_bwd applied to the plain output. */
+  GPD_STEP_FUSE_SIGMOID = 0x100
+} gpd_phase_t;
 
 /* One coded layer (Sec. VII for batch 1, Sec. IX for batch > 1). */
 gpd_status_t gpd_layer_create(const gpd_layer_desc_t* desc, gpd_layer_t** out);

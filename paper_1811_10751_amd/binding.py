@@ -22,6 +22,7 @@ GPD_F32, GPD_BF16, GPD_F32_SPLIT = 0, 1, 2
 GPD_SUB_AUTO, GPD_SUB_U_VN, GPD_SUB_V_UM = 0, 1, 2
 GPD_DEC_FIRST_K, GPD_DEC_LSQ_ALL = 0, 1
 GPD_STEP_FORWARD, GPD_STEP_BACKWARD_UPDATE = 0, 1
+GPD_STEP_FUSE_SIGMOID = 0x100
 GPD_CORRECT_NONE, GPD_CORRECT_ELEMENTS, GPD_CORRECT_NODES = 0, 1, 2
 GPD_STACK_WEIGHTS, GPD_STACK_FORWARD, GPD_STACK_BACKWARD = 0, 1, 2
 
@@ -435,8 +436,10 @@ def gpd_layer_decode_weights(layer: Layer, Wt, present=None, W=None):
 
 def gpd_coded_layer_step(layer: Layer, phase, Wt, X, Dlt=None, eta=0.0, decay=0.0, out=None,
                          present=None, correct_errors=False, want_report=False, located_cap=4096,
-                         skip_output=False):
-    """FORWARD: returns (S, report); BACKWARD_UPDATE: returns (C or None, report); Wt updated in place."""
+                         skip_output=False, fuse_sigmoid=False):
+    """FORWARD: returns (S, report); BACKWARD_UPDATE: returns (C or None, report); Wt updated in place.
+    fuse_sigmoid: the element-wise step after the decode is applied in the same pass (FORWARD:
+    the logistic function of S is returned; BACKWARD_UPDATE: C o X o (1 - X))."""
     import torch
     lib = load_library()
     _require_f32_cuda(Wt, "Wt")
@@ -459,7 +462,8 @@ def gpd_coded_layer_step(layer: Layer, phase, Wt, X, Dlt=None, eta=0.0, decay=0.
     rep = buf = None
     if want_report:
         rep, buf = _make_report(located_cap)
-    st = lib.gpd_coded_layer_step(layer.handle, phase, _ptr(Wt), _ptr(X), _ptr(Dlt), eta, decay,
+    st = lib.gpd_coded_layer_step(layer.handle, phase | (GPD_STEP_FUSE_SIGMOID if fuse_sigmoid else 0),
+                                  _ptr(Wt), _ptr(X), _ptr(Dlt), eta, decay,
                                   _ptr(out), _ptr(pres), int(correct_errors),
                                   ws.data_ptr(), ws.numel(), C.byref(rep) if rep is not None else None)
     _check(st, ok=(GPD_OK, GPD_E_DECODE_FAIL))

@@ -400,7 +400,8 @@ gpd_status_t run_decode(hipStream_t stream, TableRing* ring, const DecodeJob& jo
     sc.enabled = true; sc.rho = (float)job.rho; sc.abs_floor = (float)job.abs_floor;
     sc.counters = counters; sc.list = list; sc.cap = (int32_t)job.flag_cap;
   }
-  st = launch_combine(stream, t, Zt, job.bw, out, ld_out, false, job.bh, job.bw, sc);
+  if (corr && job.epi.kind != 0) return fail(GPD_E_INVALID, "decode: element-wise step with element correction");
+  st = launch_combine(stream, t, Zt, job.bw, out, ld_out, false, job.bh, job.bw, sc, 0, job.epi);
   if (st != GPD_OK) return st;
   if (corr) {
     LocateArgs la;

@@ -128,11 +128,17 @@ struct CombineParams {
   // the first store to complete).  The block offsets always; coef and H when karg is set (they
   // fit), else those two are read from memory.
   int32_t karg;
+  // element-wise step on fp32 outputs: 0 none, 1 logistic function, 2 times y (1 - y) with y
+  // read from epi_y at the output's own offset
+  int32_t epi;
+  const float* epi_y;
   int64_t in_off_k[64];
   int64_t out_off_k[64];
   float coef_k[256 + 64];    // (64 more, zero: a row is always read NIN_MAX entries long)
   float H_k[256 + 64];
 };
+
+static_assert(sizeof(CombineParams) <= 4096, "kernel arguments are limited to 4 KB");
 
 // NIN_MAX: compile-time bound on nin (register array); VEC: columns per thread.
 // OUT: 0 fp32, 1 bf16, 2 three bf16 planes (hi, mid, lo of the fp32 value), each block stored
@@ -301,7 +307,20 @@ __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
         const int64_t ob = oq + ((col >> 4) * p.rows + row) * 16 + (col & 15);
         store_vec_split3<VEC>(reinterpret_cast<uint16_t*>(p.out) + ob, p.out_plane, acc);
       } else if constexpr (OUT == 1) store_vec_bf16<VEC>(reinterpret_cast<uint16_t*>(p.out) + o, acc);
-      else store_vec<VEC, SCREEN>(reinterpret_cast<float*>(p.out) + o, acc);
+      else {
+        if constexpr (!SCREEN) {
+          if (p.epi == 1) {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[v] = 1.f / (1.f + expf(-acc[v]));
+          } else if (p.epi == 2) {
+            float y[VEC];
+            load_vec<VEC>(p.epi_y + o, y);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[v] = acc[v] * y[v] * (1.f - y[v]);
+          }
+        }
+        store_vec<VEC, SCREEN>(reinterpret_cast<float*>(p.out) + o, acc);
+      }
     }
   };
   if (karg) outputs(std::true_type{});
@@ -354,7 +373,8 @@ gpd_status_t launch_v(hipStream_t stream, const CombineParams& p, int out_kind, 
 
 gpd_status_t launch_combine(hipStream_t stream, const CombineTable& t, const float* in,
                             int64_t in_ld, void* out, int64_t out_ld, int out_kind,
-                            int64_t rows, int64_t cols, const ScreenArgs& screen, int64_t out_plane) {
+                            int64_t rows, int64_t cols, const ScreenArgs& screen, int64_t out_plane,
+                            const Epilogue& epi) {
   if (t.nin < 1 || t.nin > GPD_MAX_BLOCKS || t.nout < 1)
     return fail(GPD_E_INVALID, "combine: nin = %d, nout = %d", t.nin, t.nout);
   if (rows * cols > 0x7fffffffLL) return fail(GPD_E_SHAPE, "block has more than 2^31 elements");
@@ -363,6 +383,10 @@ gpd_status_t launch_combine(hipStream_t stream, const CombineTable& t, const flo
   if (out_kind < 0 || out_kind > 2) return fail(GPD_E_INVALID, "combine: unknown output kind");
   if (out_kind == 2 && (out_plane % 8 || cols % 16 || out_ld != cols || screen.enabled))
     return fail(GPD_E_INVALID, "combine: split planes need full blocks of a multiple of 16 columns");
+  if (epi.kind < 0 || epi.kind > 2 || (epi.kind == 2 && !epi.y) ||
+      (epi.kind != 0 && (out_kind != 0 || screen.enabled)))
+    return fail(GPD_E_INVALID, "combine: element-wise step needs a plain fp32 output");
+  p.epi = epi.kind; p.epi_y = epi.kind == 2 ? epi.y : nullptr;
   p.rows = rows; p.cols = cols;
   p.nin = t.nin; p.nout = t.nout; p.r = screen.enabled ? t.r : 0;
   p.in_off = t.in_off; p.out_off = t.out_off; p.coef = t.coef; p.H = t.H;
@@ -386,6 +410,7 @@ gpd_status_t launch_combine(hipStream_t stream, const CombineTable& t, const flo
     if (cols % vec || in_ld % vec || out_ld % vec || t.off_align % vec) return false;
     if (t.in_rows && t.limit_align % vec) return false;
     if (((uintptr_t)in) % (4 * vec) || ((uintptr_t)out) % (out_elem * vec)) return false;
+    if (p.epi_y && ((uintptr_t)p.epi_y) % (4 * vec)) return false;
     return true;
   };
   int vec = 1;

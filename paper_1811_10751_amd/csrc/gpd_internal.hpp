@@ -166,12 +166,21 @@ struct ScreenArgs {               // soft-error screen fused into the decode pas
   int32_t cap = 0;
 };
 
+// Element-wise step applied to an fp32 output of launch_combine before it is stored (the
+// post-processing steps C1 / C2 of Sec. VII done by the kernel that produces their input):
+//   1: v -> 1 / (1 + exp(-v));  2: v -> v * y * (1 - y), y read at the output's own position
+//   from a matrix laid out like the output (same leading dimension).
+struct Epilogue {
+  int kind = 0;
+  const float* y = nullptr;
+};
+
 // out_q[r][c] = sum_s coef[q][s] in_s[r][c]; blocks are rows x cols; fp32 in.  out_kind: 0 fp32,
 // 1 bf16, 2 the fp32 value as three bf16 planes (hi, mid, lo) out_plane elements apart, each
 // block k-blocked ([cols / 16][rows][16]; cols a multiple of 16, out_ld = cols, no block limits).
 gpd_status_t launch_combine(hipStream_t stream, const CombineTable& t, const float* in,
                             int64_t in_ld, void* out, int64_t out_ld, int out_kind,
-                            int64_t rows, int64_t cols, const ScreenArgs& screen, int64_t out_plane = 0);
+                            int64_t rows, int64_t cols, const ScreenArgs& screen, int64_t out_plane = 0, const Epilogue& epi = Epilogue());
 
 struct GemmArgs {
   const void* A = nullptr;        // op(A) is M x K
@@ -229,6 +238,8 @@ struct DecodeJob {
   int64_t flag_cap = 0, loc_cap = 0;
   size_t workspace_bytes = 0;
   std::vector<int32_t> out_rows, out_cols;     // limits of the output blocks (empty = none)
+  Epilogue epi;                                // applied to the decoded values (decodes without
+                                               // element-wise correction only)
 };
 gpd_status_t run_decode(hipStream_t stream, TableRing* ring, const DecodeJob& job, const float* Zt,
                         const uint8_t* present, int mode, int correct, float* out, int64_t ld_out,

@@ -14,6 +14,7 @@
 #include <cmath>
 #include <cstring>
 #include <new>
+#include <string>
 
 #include "gpd_internal.hpp"
 
@@ -722,8 +723,25 @@ extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, floa
                                              void* workspace, size_t workspace_bytes,
                                              gpd_report_t* report) {
   if (!L || !Wt || !X) return fail(GPD_E_INVALID, "gpd_coded_layer_step: null argument");
+  // the element-wise step after the decode (C1: logistic function of S; C2: Hadamard product of
+  // C with X (1 - X), X being the logistic output of the layer below) on request in the same pass
+  const bool fuse_act = (phase & GPD_STEP_FUSE_SIGMOID) != 0;
+  phase &= ~GPD_STEP_FUSE_SIGMOID;
   if (phase != GPD_STEP_FORWARD && phase != GPD_STEP_BACKWARD_UPDATE)
     return fail(GPD_E_INVALID, "unknown phase %d", phase);
+  // a decode with element-wise correction patches single outputs after the pass: the step then
+  // follows as a launch of its own
+  const bool act_in_decode = fuse_act && correct_errors != GPD_CORRECT_ELEMENTS;
+  auto act_after = [&](gpd_status_t dst, float* o, int64_t n) -> gpd_status_t {
+    if (!fuse_act || act_in_decode || !o || n == 0 || (dst != GPD_OK && dst != GPD_E_DECODE_FAIL)) return dst;
+    const std::string why = dst == GPD_OK ? std::string() : std::string(gpd_last_error());
+    const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+    if (phase == GPD_STEP_FORWARD) hipLaunchKernelGGL(sigmoid_fwd_kernel, grid, block, 0, L->stream, o, o, n);
+    else hipLaunchKernelGGL(sigmoid_bwd_kernel, grid, block, 0, L->stream, o, X, o, n);
+    GPD_HIP(hipGetLastError());
+    if (dst != GPD_OK) return fail(dst, "%s", why.c_str());
+    return dst;
+  };
   if (!workspace || workspace_bytes < L->ws_bytes || ((uintptr_t)workspace & 255))
     return fail(GPD_E_WORKSPACE, "layer step: workspace of %zu aligned bytes needed", L->ws_bytes);
   const gpd_layer_desc_t& d = L->desc;
@@ -779,8 +797,9 @@ extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, floa
     job.rho = L->rho; job.abs_floor = L->abs_floor;
     job.flag_cap = L->flag_cap; job.loc_cap = L->loc_cap; job.workspace_bytes = L->dec_bytes;
     grid_limits(d.N_out, d.batch, c.m, c.d, L->wr, L->nb1, &job.out_rows, &job.out_cols);
-    return run_decode(s, &L->ring, job, St, present, GPD_DEC_LSQ_ALL, correct_errors, out, d.batch, dec_ws,
-                      L->dec_bytes, report);
+    if (act_in_decode) job.epi.kind = 1;
+    return act_after(run_decode(s, &L->ring, job, St, present, GPD_DEC_LSQ_ALL, correct_errors, out, d.batch,
+                                dec_ws, L->dec_bytes, report), out, d.N_out * d.batch);
   }
 
   // ---- BACKWARD_UPDATE
@@ -890,8 +909,9 @@ extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, floa
   job.rho = L->rho; job.abs_floor = L->abs_floor;
   job.flag_cap = L->flag_cap; job.loc_cap = L->loc_cap; job.workspace_bytes = L->dec_bytes;
   grid_limits(d.N_in, d.batch, c.n, d.d2, L->wc, L->nb2, &job.out_rows, &job.out_cols);
-  return run_decode(s, &L->ring, job, Ct, present, GPD_DEC_LSQ_ALL, correct_errors, out, d.batch, dec_ws,
-                    L->dec_bytes, report);
+  if (act_in_decode) { job.epi.kind = 2; job.epi.y = X; }
+  return act_after(run_decode(s, &L->ring, job, Ct, present, GPD_DEC_LSQ_ALL, correct_errors, out, d.batch,
+                              dec_ws, L->dec_bytes, report), out, d.N_in * d.batch);
 }
 
 // ---------------------------------------------------------------- element-wise steps

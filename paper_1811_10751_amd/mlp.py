@@ -74,27 +74,29 @@ class CodedMLP:
             return False
 
         for l, (L, Wt) in enumerate(zip(self.layers, self.Wts)):
-            S, rf = B.gpd_coded_layer_step(L, B.GPD_STEP_FORWARD, Wt, acts[-1],
-                                           correct_errors=correct_errors, want_report=want_report)
+            # (the logistic function, step C1, is applied by the decode itself)
+            act, rf = B.gpd_coded_layer_step(L, B.GPD_STEP_FORWARD, Wt, acts[-1],
+                                             correct_errors=correct_errors, want_report=want_report,
+                                             fuse_sigmoid=True)
             reps.append([rf, None])
             if failed(rf):
                 return None, reps
             if regenerate:
                 self.repaired += [(l, "forward", p) for p in self._regenerate(l, rf)]
-            acts.append(B.gpd_sigmoid_fwd(S, stream=self.stream))
+            acts.append(act)
         delta = B.gpd_l2_delta(Y, acts[-1], 2.0 / self.batch, stream=self.stream)
         for l in range(len(self.layers) - 1, -1, -1):
             C, rb = B.gpd_coded_layer_step(self.layers[l], B.GPD_STEP_BACKWARD_UPDATE, self.Wts[l],
                                            acts[l], Dlt=delta, eta=eta, decay=decay,
                                            correct_errors=correct_errors, want_report=want_report,
-                                           skip_output=(l == 0))
+                                           skip_output=(l == 0), fuse_sigmoid=True)
             reps[l][1] = rb
             if failed(rb):
                 return None, reps
             if regenerate and l > 0:
                 self.repaired += [(l, "backward", p) for p in self._regenerate(l, rb)]
             if l > 0:
-                delta = B.gpd_sigmoid_bwd(C, acts[l], stream=self.stream)
+                delta = C                 # already C o Y (1 - Y), step C2, Y = acts[l]
         return acts[-1], reps
 
 

@@ -67,6 +67,24 @@ def test_layer_forward_backward_update(N_out, N_in, batch, m, n, d1, d2, P, subs
     assert rel_fro(to_np(S), S_o) <= 2e-6 * max(ampf, 1.0)
     assert rel_fro(to_np(S), W.astype(np.float64) @ X) <= max(1e-3, 4e-6 * ampf)
 
+    # the element-wise step C1 done by the decode itself: the same values as the separate kernel
+    # on the plain output, whichever decode path runs (plain, element correction, node search)
+    for corr in (G.GPD_CORRECT_NONE, G.GPD_CORRECT_ELEMENTS, G.GPD_CORRECT_NODES):
+        S_c, _ = G.gpd_coded_layer_step(L, G.GPD_STEP_FORWARD, Wt, to_dev(X), correct_errors=corr)
+        Y_f, _ = G.gpd_coded_layer_step(L, G.GPD_STEP_FORWARD, Wt, to_dev(X), correct_errors=corr,
+                                        fuse_sigmoid=True)
+        assert torch.equal(Y_f, G.gpd_sigmoid_fwd(S_c)), corr
+        assert np.abs(to_np(Y_f) - 1 / (1 + np.exp(-S_o))).max() < 1e-5 * max(ampf, 1.0)
+    # step C2 likewise: C o Xs (1 - Xs) for an input Xs in (0, 1); eta = 0 leaves the weights alone
+    Xs = to_dev((0.5 * (X + 1)).astype(np.float32).clip(0.01, 0.99))
+    for corr in (G.GPD_CORRECT_NONE, G.GPD_CORRECT_ELEMENTS, G.GPD_CORRECT_NODES):
+        C_c, _ = G.gpd_coded_layer_step(L, G.GPD_STEP_BACKWARD_UPDATE, Wt, Xs, Dlt=to_dev(D), eta=0.0,
+                                        decay=0.0, correct_errors=corr)
+        D_f, _ = G.gpd_coded_layer_step(L, G.GPD_STEP_BACKWARD_UPDATE, Wt, Xs, Dlt=to_dev(D), eta=0.0,
+                                        decay=0.0, correct_errors=corr, fuse_sigmoid=True)
+        assert torch.equal(D_f, G.gpd_sigmoid_bwd(C_c, Xs)), corr
+    assert np.array_equal(to_np(Wt), Wt_h)
+
     # backward + update in one call; backward uses the pre-update weights
     eta, decay = 0.05, 0.01
     C, _ = G.gpd_coded_layer_step(L, G.GPD_STEP_BACKWARD_UPDATE, Wt, to_dev(X), Dlt=to_dev(D), eta=eta, decay=decay)
