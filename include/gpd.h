@@ -256,8 +256,13 @@ typedef struct {
   const double* points;         /* as in gpd_problem_t                                        */
   int32_t worker_dtype;         /* GPD_BF16: forward/backward products in bf16 MFMA; W~ itself,
                                    encode and decode stay fp32.  The update W~_p += eta Dhat Xhat^T
-                                   is an fp32 product: fp32 MFMA for GPD_F32 layers, the
-                                   three-way bf16 split (see gpd_dtype_t) otherwise           */
+                                   keeps fp32-level accuracy on every layer: fp32 MFMA for GPD_F32
+                                   layers; for GPD_F32_SPLIT the three-way bf16 split (see
+                                   gpd_dtype_t); for GPD_BF16 each operand, divided by a power of
+                                   two taken from the largest finite |Delta| (|X|) of the call, as
+                                   the sum of two fp16 values and three partial products (error
+                                   below 2^-20 of a product's magnitude; batch a multiple of 64,
+                                   else the three-way bf16 split)                              */
   int32_t subst;
   double rho_detect, abs_floor;
   void* hip_stream;
@@ -319,10 +324,14 @@ gpd_status_t gpd_coded_layer_step(gpd_layer_t* layer, int32_t phase, float* Wt,
  * outputs), 4 = Dhat_p, 5 = Xhat_p (update operands).  For inspection and fault injection.
  * Layers with worker_dtype == GPD_BF16 hold 0 and 2 (the operands of the bf16 products) as bf16
  * stacks of the same shape.
- * Layers with worker_dtype != GPD_F32 and batch % 64 == 0 hold 4 and 5 in another form: each
- * fp32 value v as three bf16 values hi = bf16(v), mid = bf16(v - hi), lo = bf16(v - hi - mid)
- * (round to nearest even), in three planes P*rows*cols elements apart, every plane
- * [P][cols/16][rows][16] (16 consecutive batch columns of a row contiguous). */
+ * Layers with worker_dtype != GPD_F32 and batch % 64 == 0 hold 4 and 5 in another form, as
+ * planes P*rows*cols elements apart, every plane [P][cols/16][rows][16] (16 consecutive batch
+ * columns of a row contiguous):
+ *   GPD_F32_SPLIT: each fp32 value v as three bf16 values hi = bf16(v), mid = bf16(v - hi),
+ *                  lo = bf16(v - hi - mid) (round to nearest even);
+ *   GPD_BF16:      each value v as two fp16 values of w = v / 2^E: hi = fp16(w), lo = fp16(w - hi);
+ *                  which = 6 gives the two exponents (int32 E of Dhat, E of Xhat; rows = 1,
+ *                  cols = 2) of the last BACKWARD_UPDATE call, and fails on any other layer. */
 gpd_status_t gpd_layer_workspace_view(const gpd_layer_t* layer, int32_t which, size_t* byte_offset,
                                       int64_t* rows, int64_t* cols);
 

@@ -372,12 +372,22 @@ class Layer:
 
     def view(self, which, device):
         """fp32 tensor [P, rows, cols] aliasing one of the per-node intermediates in the workspace
-        (0 X~, 1 S~, 2 Delta~, 3 C~, 4 Dhat, 5 Xhat)."""
+        (0 X~, 1 S~, 2 Delta~, 3 C~, 4 Dhat, 5 Xhat); 6: int32 [2], the exponents E of Dhat and
+        Xhat when those are held as fp16 planes (hi + lo) * 2^E."""
         import torch
+        lib = load_library()
         off, r, c = C.c_size_t(), C.c_int64(), C.c_int64()
-        _check(load_library().gpd_layer_workspace_view(self.handle, which, C.byref(off), C.byref(r), C.byref(c)))
         ws = self.workspace(device)
+        fp16 = lib.gpd_layer_workspace_view(self.handle, 6, C.byref(off), C.byref(r), C.byref(c)) == GPD_OK
+        if which == 6:
+            if not fp16:
+                raise ValueError("this layer holds no fp16 planes")
+            return ws[off.value:off.value + 8].view(torch.int32)
+        _check(lib.gpd_layer_workspace_view(self.handle, which, C.byref(off), C.byref(r), C.byref(c)))
         n = self.P * r.value * c.value
+        if which >= 4 and fp16:
+            # two fp16 planes (hi, lo) of the operand / 2^E, each [P][cols/16][rows][16]
+            return ws[off.value:off.value + 4 * n].view(torch.float16).view(2, self.P, c.value // 16, r.value, 16)
         if which in (0, 2) and self.worker_dtype == GPD_BF16:
             return ws[off.value:off.value + 2 * n].view(torch.bfloat16).view(self.P, r.value, c.value)
         if which >= 4 and self.worker_dtype != GPD_F32 and self.batch % 64 == 0:

@@ -101,6 +101,42 @@ __device__ __forceinline__ void store_vec_split3(uint16_t* p, int64_t plane, con
   }
 }
 
+// An fp32 value, scaled by the power of two `inv`, as two fp16 values (hi = fp16(x), lo =
+// fp16(x - hi), round-to-nearest-even, the subtraction exact), stored in two planes `plane`
+// elements apart: |x - hi - lo| <= 2^-22 |x| while lo is a normal fp16 number.
+__device__ __forceinline__ uint32_t f16_bits(float x) {
+  union { _Float16 h; uint16_t u; } cv;
+  cv.h = (_Float16)x;
+  return cv.u;
+}
+template <int VEC>
+__device__ __forceinline__ void store_vec_split2h(uint16_t* p, int64_t plane, const float (&v)[VEC], float inv) {
+  uint32_t hi[VEC], lo[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) {
+    const float x = v[e] * inv;
+    union { _Float16 h; uint16_t u; } cv;
+    cv.h = (_Float16)x;
+    hi[e] = cv.u;
+    lo[e] = f16_bits(x - (float)cv.h);
+  }
+#pragma unroll
+  for (int pl = 0; pl < 2; ++pl) {
+    const uint32_t* w = pl == 0 ? hi : lo;
+    uint16_t* q = p + pl * plane;
+    if constexpr (VEC == 4) {
+      uint2 t;
+      t.x = w[0] | (w[1] << 16);
+      t.y = w[2] | (w[3] << 16);
+      *reinterpret_cast<uint2*>(q) = t;
+    } else if constexpr (VEC == 2) {
+      *reinterpret_cast<uint32_t*>(q) = w[0] | (w[1] << 16);
+    } else {
+      *q = (uint16_t)w[0];
+    }
+  }
+}
+
 struct CombineParams {
   const float* in;
   int64_t in_ld;
@@ -132,6 +168,12 @@ struct CombineParams {
   // read from epi_y at the output's own offset
   int32_t epi;
   const float* epi_y;
+  // output kind 3 (two fp16 planes of out / 2^E): E = exponent of the largest finite input
+  // magnitude (amax_parts: amax_n partial maxima as float bit patterns) - 14 + exp_extra, so
+  // that |out| / 2^E < 2^15; written to exp_out for the kernel that reads the planes
+  const uint32_t* amax_parts;
+  int32_t amax_n, exp_extra;
+  int32_t* exp_out;
   int64_t in_off_k[64];
   int64_t out_off_k[64];
   float coef_k[256 + 64];    // (64 more, zero: a row is always read NIN_MAX entries long)
@@ -142,14 +184,15 @@ static_assert(sizeof(CombineParams) <= 4096, "kernel arguments are limited to 4 
 
 // NIN_MAX: compile-time bound on nin (register array); VEC: columns per thread.
 // OUT: 0 fp32, 1 bf16, 2 three bf16 planes (hi, mid, lo of the fp32 value), each block stored
-// k-blocked: 16 consecutive columns of a row are contiguous, rows next, column groups outermost
+// k-blocked: 16 consecutive columns of a row are contiguous, rows next, column groups outermost;
+// 3 two fp16 planes (hi, lo) of the value divided by a power of two, k-blocked in the same way
 template <int NIN_MAX, int VEC, int OUT, bool SCREEN, bool LIMITS>
 __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t total = p.rows * p.cols_vec;
   const bool active = idx < total;
   int64_t row, col;
-  if constexpr (OUT == 2) {
+  if constexpr (OUT >= 2) {
     // threads follow the k-blocked output order (16 / VEC threads per row of a 16-column group,
     // rows next): the stores of a wavefront are contiguous in every plane, and the inputs, whose
     // rows are then read in pieces, are P times smaller than the outputs
@@ -183,6 +226,18 @@ __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
 #pragma unroll
     for (int v = 0; v < VEC; ++v) z[s][v] = take[s] ? z[s][v] : 0.f;
   const bool karg = p.karg != 0;
+
+  float inv = 1.f;
+  if constexpr (OUT == 3) {
+    // (one wavefront per workgroup) largest partial maximum, its exponent, the scale
+    uint32_t m = 0;
+    for (int i = threadIdx.x; i < p.amax_n; i += 64) m = max(m, p.amax_parts[i]);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off));
+    const int E = max((int)(m >> 23) - 127, -100) - 14 + p.exp_extra;
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *p.exp_out = E;
+    inv = ldexpf(1.f, -E);
+  }
 
   // non-finite responses are replaced by zero everywhere (and always passed on, below)
   bool bad[VEC];
@@ -302,10 +357,11 @@ __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
       }
       const int64_t oq = p.out_off_k[q];
       const int64_t o = oq + row * p.out_ld + col;
-      if constexpr (OUT == 2) {
+      if constexpr (OUT >= 2) {
         // k-blocked: [col / 16][row][col % 16], what the split GEMM reads as one contiguous stage
         const int64_t ob = oq + ((col >> 4) * p.rows + row) * 16 + (col & 15);
-        store_vec_split3<VEC>(reinterpret_cast<uint16_t*>(p.out) + ob, p.out_plane, acc);
+        if constexpr (OUT == 2) store_vec_split3<VEC>(reinterpret_cast<uint16_t*>(p.out) + ob, p.out_plane, acc);
+        else store_vec_split2h<VEC>(reinterpret_cast<uint16_t*>(p.out) + ob, p.out_plane, acc, inv);
       } else if constexpr (OUT == 1) store_vec_bf16<VEC>(reinterpret_cast<uint16_t*>(p.out) + o, acc);
       else {
         if constexpr (!SCREEN) {
@@ -341,6 +397,9 @@ gpd_status_t launch_t(hipStream_t stream, const CombineParams& p, int out_kind, 
     if (out_kind != 0) return fail(GPD_E_UNSUPPORTED, "screen with bf16 output");
     if (lim) hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, 0, true, true>), grid, block, 0, stream, p);
     else hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, 0, true, false>), grid, block, 0, stream, p);
+  } else if (out_kind == 3) {
+    if (lim) hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, 3, false, true>), grid, block, 0, stream, p);
+    else hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, 3, false, false>), grid, block, 0, stream, p);
   } else if (out_kind == 2) {
     if (lim) hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, 2, false, true>), grid, block, 0, stream, p);
     else hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, 2, false, false>), grid, block, 0, stream, p);
@@ -374,15 +433,20 @@ gpd_status_t launch_v(hipStream_t stream, const CombineParams& p, int out_kind, 
 gpd_status_t launch_combine(hipStream_t stream, const CombineTable& t, const float* in,
                             int64_t in_ld, void* out, int64_t out_ld, int out_kind,
                             int64_t rows, int64_t cols, const ScreenArgs& screen, int64_t out_plane,
-                            const Epilogue& epi) {
+                            const Epilogue& epi, const PlaneScale& scale) {
   if (t.nin < 1 || t.nin > GPD_MAX_BLOCKS || t.nout < 1)
     return fail(GPD_E_INVALID, "combine: nin = %d, nout = %d", t.nin, t.nout);
   if (rows * cols > 0x7fffffffLL) return fail(GPD_E_SHAPE, "block has more than 2^31 elements");
   CombineParams p;
   p.in = in; p.in_ld = in_ld; p.out = out; p.out_ld = out_ld; p.out_plane = out_plane;
-  if (out_kind < 0 || out_kind > 2) return fail(GPD_E_INVALID, "combine: unknown output kind");
-  if (out_kind == 2 && (out_plane % 8 || cols % 16 || out_ld != cols || screen.enabled))
+  if (out_kind < 0 || out_kind > 3) return fail(GPD_E_INVALID, "combine: unknown output kind");
+  if (out_kind >= 2 && (out_plane % 8 || cols % 16 || out_ld != cols || screen.enabled))
     return fail(GPD_E_INVALID, "combine: split planes need full blocks of a multiple of 16 columns");
+  if (out_kind == 3 && (!scale.amax_parts || scale.amax_n < 1 || !scale.exp_out || scale.exp_extra < 0 ||
+                        scale.exp_extra > 16))
+    return fail(GPD_E_INVALID, "combine: fp16 planes need the partial maxima of the input");
+  p.amax_parts = scale.amax_parts; p.amax_n = scale.amax_n; p.exp_extra = scale.exp_extra;
+  p.exp_out = scale.exp_out;
   if (epi.kind < 0 || epi.kind > 2 || (epi.kind == 2 && !epi.y) ||
       (epi.kind != 0 && (out_kind != 0 || screen.enabled)))
     return fail(GPD_E_INVALID, "combine: element-wise step needs a plain fp32 output");

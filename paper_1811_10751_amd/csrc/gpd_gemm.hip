@@ -251,9 +251,11 @@ struct HGemmParams {
   int64_t planeA, planeB;    // elements between the three planes of a pre-split operand
   int tiles_m, tiles_n, total_tiles, tiles_per_xcd;
   float alpha, beta;
+  const int32_t* exps;       // device, {E_A, E_B}: plane operands are two fp16 planes scaled by 2^-E (null: three bf16 planes)
 };
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
 
 // two fp32 -> packed bf16, round to nearest even (one v_cvt_pk_bf16_f32)
@@ -805,10 +807,15 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? (SPLIT == 1 ? 3 
 // which keeps the 128-bit fragment reads of 8 consecutive lanes on 32 different banks without
 // padding): 24 KB per stage, two stages, three workgroups per CU, so that while one workgroup
 // reads and writes its output tile two others keep the matrix pipe busy.
-template <int MODE, int R>
+// FMT 0: three bf16 planes per operand (hi, mid, lo), six partial products; FMT 1: two fp16
+// planes (hi, lo) of the operand divided by 2^E (E per operand, g.exps), three partial products,
+// the result multiplied by 2^(E_A + E_B).
+template <int MODE, int R, int FMT>
 __global__ __launch_bounds__(256, 3) void gemm_planes_kernel(HGemmParams g) {
   constexpr int TB = 128, MI = 2, NJ = 2;
-  constexpr int PLANE_B = TB * 32, STAGE_B = 6 * PLANE_B;
+  constexpr int NPL = FMT == 0 ? 3 : 2;            // planes per operand
+  constexpr int NG = NPL * (NPL + 1) / 2;          // partial products
+  constexpr int PLANE_B = TB * 32, STAGE_B = 2 * NPL * PLANE_B;
   __shared__ __attribute__((aligned(16))) unsigned char lds[2][STAGE_B];
 
   const int xcd = blockIdx.x & 7;
@@ -845,8 +852,8 @@ __global__ __launch_bounds__(256, 3) void gemm_planes_kernel(HGemmParams g) {
   // row; a lane's 16 bytes of a stage are at 16 * tid, planes and stages add uniform offsets
   const char* Ab = (const char*)g.A + ((int64_t)p * g.sA + (int64_t)m0 * 16) * 2;
   const char* Bb = (const char*)g.B + ((int64_t)p * g.sB + (int64_t)n0 * 16) * 2;
-  const int64_t extA = 4 * g.planeA + (int64_t)(g.K >> 4) * g.M * 32 - (int64_t)m0 * 32;
-  const int64_t extB = 4 * g.planeB + (int64_t)(g.K >> 4) * g.N * 32 - (int64_t)n0 * 32;
+  const int64_t extA = 2 * (NPL - 1) * g.planeA + (int64_t)(g.K >> 4) * g.M * 32 - (int64_t)m0 * 32;
+  const int64_t extB = 2 * (NPL - 1) * g.planeB + (int64_t)(g.K >> 4) * g.N * 32 - (int64_t)n0 * 32;
   const __amdgpu_buffer_rsrc_t rA = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(Ab), 0, (int)extA, 0x00020000);
   const __amdgpu_buffer_rsrc_t rB = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(Bb), 0, (int)extB, 0x00020000);
   const uint32_t voff = 16u * (uint32_t)tid;
@@ -855,10 +862,10 @@ __global__ __launch_bounds__(256, 3) void gemm_planes_kernel(HGemmParams g) {
   const bool okA = MODE == 0 || m0 + (tid >> 1) < g.M;
   const bool okB = MODE == 0 || n0 + (tid >> 1) < g.N;
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-  struct Set { u32x4 a[3], b[3]; };
+  struct Set { u32x4 a[NPL], b[NPL]; };
   auto load = [&](Set& st, int c) __attribute__((always_inline)) {
 #pragma unroll
-    for (int pl = 0; pl < 3; ++pl) {
+    for (int pl = 0; pl < NPL; ++pl) {
       st.a[pl] = okA ? __builtin_amdgcn_raw_buffer_load_b128(rA, voff, (uint32_t)c * kbA + pl * plA, 0) : u32x4{0u, 0u, 0u, 0u};
       st.b[pl] = okB ? __builtin_amdgcn_raw_buffer_load_b128(rB, voff, (uint32_t)c * kbB + pl * plB, 0) : u32x4{0u, 0u, 0u, 0u};
     }
@@ -866,11 +873,11 @@ __global__ __launch_bounds__(256, 3) void gemm_planes_kernel(HGemmParams g) {
   // LDS positions: a lane stores its 16 bytes of row tid / 2, and reads rows wm (wn) + 32 i + li
   const uint32_t swz_w = ((tid & 1) ^ ((tid >> 3) & 1)) * 16u, swz_r = ((uint32_t)lg ^ ((li >> 2) & 1)) * 16u;
   const uint32_t wr_off = (uint32_t)(tid >> 1) * 32u + swz_w;
-  const uint32_t rdA = (uint32_t)(wm + li) * 32u + swz_r, rdB = 3 * PLANE_B + (uint32_t)(wn + li) * 32u + swz_r;
+  const uint32_t rdA = (uint32_t)(wm + li) * 32u + swz_r, rdB = NPL * PLANE_B + (uint32_t)(wn + li) * 32u + swz_r;
   auto put = [&](const Set& st, int buf, int item) __attribute__((always_inline)) {
-    *reinterpret_cast<u32x4*>(lds[buf] + wr_off + item * PLANE_B) = item < 3 ? st.a[item] : st.b[item - 3];
+    *reinterpret_cast<u32x4*>(lds[buf] + wr_off + item * PLANE_B) = item < NPL ? st.a[item] : st.b[item - NPL];
   };
-  union Frag { u32x4 u; bf16x8 v; };
+  union Frag { u32x4 u; bf16x8 v; f16x8 h; };
   auto frag = [&](int buf, uint32_t off) __attribute__((always_inline)) {
     Frag f;
     f.u = *reinterpret_cast<const u32x4*>(lds[buf] + off);
@@ -890,35 +897,44 @@ __global__ __launch_bounds__(256, 3) void gemm_planes_kernel(HGemmParams g) {
 #pragma unroll
   for (int u = 0; u < R; ++u) load(st[u], u);
 #pragma unroll
-  for (int it = 0; it < 6; ++it) put(st[0], 0, it);
+  for (int it = 0; it < 2 * NPL; ++it) put(st[0], 0, it);
   __syncthreads();
 
   // stage c: the global loads of stage c + R go into the register set stage c has left (set
   // u = c % R, addressed statically: the loop is unrolled R times), stage c + 1 moves from its
   // set to the other LDS buffer between the groups of matrix instructions, and the six partial
-  // products hi*lo, mid*mid, hi*mid, lo*hi, mid*hi, hi*hi of stage c are accumulated
+  // products hi*lo, mid*mid, hi*mid, lo*hi, mid*hi, hi*hi (fp16 planes: hi*lo, lo*hi, hi*hi) of
+  // stage c are accumulated
   auto stage = [&](Set& ld_set, const Set& nx_set, int c, bool do_load, bool do_next) __attribute__((always_inline)) {
     const int cur = c & 1;
     if (do_load) load(ld_set, c + R);
-    Frag fa[MI][3], fb[NJ];
+    Frag fa[MI][NPL], fb[NJ];
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
-      for (int pl = 0; pl < 3; ++pl) fa[i][pl] = frag(cur, rdA + pl * PLANE_B + i * 1024);
-    int item = 0;
+      for (int pl = 0; pl < NPL; ++pl) fa[i][pl] = frag(cur, rdA + pl * PLANE_B + i * 1024);
+    int grp = 0;
 #pragma unroll
-    for (int pb = 2; pb >= 0; --pb) {
+    for (int pb = NPL - 1; pb >= 0; --pb) {
 #pragma unroll
       for (int j = 0; j < NJ; ++j) fb[j] = frag(cur, rdB + pb * PLANE_B + j * 1024);
 #pragma unroll
-      for (int pa = 2 - pb; pa >= 0; --pa) {
+      for (int pa = NPL - 1 - pb; pa >= 0; --pa) {
 #pragma unroll
         for (int i = 0; i < MI; ++i)
 #pragma unroll
-          for (int j = 0; j < NJ; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i][pa].v, fb[j].v, acc[i][j], 0, 0, 0);
-        if (do_next) put(nx_set, cur ^ 1, item);
-        ++item;
+          for (int j = 0; j < NJ; ++j) {
+            if constexpr (FMT == 0)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i][pa].v, fb[j].v, acc[i][j], 0, 0, 0);
+            else
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i][pa].h, fb[j].h, acc[i][j], 0, 0, 0);
+          }
+        // the 2 NPL pieces of the next stage are spread over the NG groups of matrix instructions
+        if (do_next) {
+#pragma unroll
+          for (int it = grp * 2 * NPL / NG; it < (grp + 1) * 2 * NPL / NG; ++it) put(nx_set, cur ^ 1, it);
+        }
+        ++grp;
       }
     }
     __syncthreads();
@@ -939,6 +955,8 @@ __global__ __launch_bounds__(256, 3) void gemm_planes_kernel(HGemmParams g) {
   // pair are requested before any is used.  The tile is touched once: its loads and stores are
   // marked non-temporal so that they do not push the operand panels out of the L2.
   constexpr int GB = 2;
+  int esum = 0;                              // fp16 planes: the product is scaled by 2^(E_A + E_B)
+  if constexpr (FMT == 1) esum = g.exps[0] + g.exps[1];
 #pragma unroll
   for (int b0 = 0; b0 < MI * NJ; b0 += GB) {
     float old[GB][16];
@@ -960,7 +978,8 @@ __global__ __launch_bounds__(256, 3) void gemm_planes_kernel(HGemmParams g) {
       for (int v = 0; v < 16; ++v) {
         const int row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * lg + (v & 3);
         if (MODE == 0 || (row < g.M && col < g.N))
-          __builtin_nontemporal_store(fmaf(g.beta, old[bb][v], g.alpha * acc[i][j][v]), &C[(int64_t)row * g.ldc + col]);
+          __builtin_nontemporal_store(fmaf(g.beta, old[bb][v], FMT == 1 ? ldexpf(g.alpha * acc[i][j][v], esum) : g.alpha * acc[i][j][v]),
+                                      &C[(int64_t)row * g.ldc + col]);
       }
     }
   }
@@ -975,8 +994,14 @@ gpd_status_t launch_planes(hipStream_t stream, HGemmParams p, int64_t batch) {
   p.total_tiles = (int)total;
   p.tiles_per_xcd = (int)((total + 7) / 8);
   dim3 grid((unsigned)(p.tiles_per_xcd * 8));
-  if (p.M % 128 == 0 && p.N % 128 == 0) hipLaunchKernelGGL((gemm_planes_kernel<0, 2>), grid, dim3(256), 0, stream, p);
-  else hipLaunchKernelGGL((gemm_planes_kernel<1, 2>), grid, dim3(256), 0, stream, p);
+  const bool full = p.M % 128 == 0 && p.N % 128 == 0;
+  if (p.exps) {
+    if (full) hipLaunchKernelGGL((gemm_planes_kernel<0, 2, 1>), grid, dim3(256), 0, stream, p);
+    else hipLaunchKernelGGL((gemm_planes_kernel<1, 2, 1>), grid, dim3(256), 0, stream, p);
+  } else {
+    if (full) hipLaunchKernelGGL((gemm_planes_kernel<0, 2, 0>), grid, dim3(256), 0, stream, p);
+    else hipLaunchKernelGGL((gemm_planes_kernel<1, 2, 0>), grid, dim3(256), 0, stream, p);
+  }
   GPD_HIP(hipGetLastError());
   return GPD_OK;
 }
@@ -1166,6 +1191,7 @@ gpd_status_t launch_gemm(hipStream_t stream, const GemmArgs& a) {
     h.sA = a.strideA; h.sB = a.strideB; h.sC = a.strideC;
     h.alpha = a.alpha; h.beta = a.beta;
     h.planeA = a.planeA; h.planeB = a.planeB;
+    h.exps = planes ? a.plane_exps : nullptr;
     const int a_es = a.a_bf16 ? 2 : 4, b_es = a.b_bf16 ? 2 : 4;
     // full tiles are read through buffer instructions with 32-bit offsets: one batch entry of
     // each operand has to stay below 2^31 bytes

@@ -175,12 +175,24 @@ struct Epilogue {
   const float* y = nullptr;
 };
 
+// For output kind 3 of launch_combine: where the partial maxima of |input| are (device, amax_n
+// float bit patterns, non-finite values left out), how many bits the outputs can exceed the
+// inputs by (2^exp_extra >= the largest absolute row sum of the coefficients), and where the
+// kernel leaves the exponent E it has scaled the planes by (device).
+struct PlaneScale {
+  const uint32_t* amax_parts = nullptr;
+  int amax_n = 0, exp_extra = 0;
+  int32_t* exp_out = nullptr;
+};
+
 // out_q[r][c] = sum_s coef[q][s] in_s[r][c]; blocks are rows x cols; fp32 in.  out_kind: 0 fp32,
 // 1 bf16, 2 the fp32 value as three bf16 planes (hi, mid, lo) out_plane elements apart, each
-// block k-blocked ([cols / 16][rows][16]; cols a multiple of 16, out_ld = cols, no block limits).
+// block k-blocked ([cols / 16][rows][16]; cols a multiple of 16, out_ld = cols, no block limits);
+// 3 the value divided by 2^E as two fp16 planes (hi, lo), k-blocked likewise (PlaneScale).
 gpd_status_t launch_combine(hipStream_t stream, const CombineTable& t, const float* in,
                             int64_t in_ld, void* out, int64_t out_ld, int out_kind,
-                            int64_t rows, int64_t cols, const ScreenArgs& screen, int64_t out_plane = 0, const Epilogue& epi = Epilogue());
+                            int64_t rows, int64_t cols, const ScreenArgs& screen, int64_t out_plane = 0, const Epilogue& epi = Epilogue(),
+                            const PlaneScale& scale = PlaneScale());
 
 struct GemmArgs {
   const void* A = nullptr;        // op(A) is M x K
@@ -201,6 +213,10 @@ struct GemmArgs {
   // (N for B); needs K % 64 == 0, ignores lda / transA (ldb / transB); the batch stride then
   // counts bf16 elements of one plane
   int64_t planeA = 0, planeB = 0;
+  // plane operands in the other format: two fp16 planes (hi, lo) of the operand divided by
+  // 2^E, E_A and E_B in device memory (read by the kernel: no host synchronisation), three
+  // partial products, error below 2^-20 of a product's magnitude
+  const int32_t* plane_exps = nullptr;
   float alpha = 1.f, beta = 0.f;  // C = beta*C + alpha*op(A)op(B)
 };
 gpd_status_t launch_gemm(hipStream_t stream, const GemmArgs& g);

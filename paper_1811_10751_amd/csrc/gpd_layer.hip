@@ -262,6 +262,35 @@ __global__ __launch_bounds__(256) void skinny_backward_update_kernel(
   }
 }
 
+// Largest finite |x| of up to two arrays (blockIdx.y = array), as kAmaxParts partial maxima per
+// array: for non-negative floats the order of the bit patterns is the order of the values, so
+// the partial results are plain unsigned maxima (order-free, hence reproducible).
+constexpr int kAmaxParts = 256;
+struct AbsMaxJobs { const float* x[2]; int64_t n[2]; uint32_t* parts; };
+
+__global__ __launch_bounds__(256) void absmax_kernel(const AbsMaxJobs j) {
+  __shared__ uint32_t wmax[4];
+  const float* __restrict__ x = j.x[blockIdx.y];
+  const int64_t n = j.n[blockIdx.y];
+  uint32_t m = 0;
+  auto take = [&](float v) {
+    const uint32_t b = __float_as_uint(v) & 0x7fffffffu;
+    if (b < 0x7f800000u) m = max(m, b);
+  };
+  const int64_t n4 = ((uintptr_t)x % 16 == 0) ? n / 4 : 0;          // 16-byte pieces, then the rest
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)kAmaxParts * 256) {
+    const float4 v = reinterpret_cast<const float4*>(x)[i];
+    take(v.x); take(v.y); take(v.z); take(v.w);
+  }
+  for (int64_t i = 4 * n4 + (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)kAmaxParts * 256) take(x[i]);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off));
+  if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0)
+    j.parts[blockIdx.y * kAmaxParts + blockIdx.x] = max(max(wmax[0], wmax[1]), max(wmax[2], wmax[3]));
+}
+
 // Ct[p][c][b] = sum_chunk part[p][chunk][c][b], in chunk order (deterministic).
 __global__ void reduce_chunks_kernel(const float* __restrict__ part, float* __restrict__ Ct,
                                      int64_t per_node, int nchunks, int64_t total) {
@@ -335,7 +364,10 @@ struct gpd_layer {
   // workspace layout (byte offsets)
   size_t off_Xt = 0, off_St = 0, off_Dt = 0, off_Ct = 0, off_Dh = 0, off_Xh = 0, off_part = 0,
          off_dec = 0, ws_bytes = 0;
-  bool upd_planes = false;         // update operands stored as three bf16 planes
+  bool upd_planes = false;         // update operands stored as planes: three bf16 planes, or
+  bool upd_fp16 = false;           // (bf16 layers) two fp16 planes of the operand / 2^E
+  int exp_Dh = 0, exp_Xh = 0;      // bits the encoded update operands can exceed Delta, X by
+  size_t off_scal = 0;             // partial maxima of |Delta|, |X| and the two exponents E
   int nchunks = 0;
   int64_t flag_cap = 0, loc_cap = 0;
   size_t dec_bytes = 0;
@@ -421,13 +453,29 @@ extern "C" gpd_status_t gpd_layer_create(const gpd_layer_desc_t* d, gpd_layer_t*
   L->off_St = take((size_t)P * L->wr * L->nb1 * 4);
   L->off_Dt = take((size_t)P * L->wr * L->nb2 * 4);
   L->off_Ct = take((size_t)P * L->wc * L->nb2 * 4);
-  // update operands: fp32 stacks, or (layers whose update runs as six bf16 partial products, batch
-  // a multiple of 64) three bf16 planes hi / mid / lo written by the encode itself
+  // update operands: fp32 stacks, or (batch a multiple of 64) planes written by the encode itself:
+  // three bf16 planes hi / mid / lo (GPD_F32_SPLIT layers: six partial products, fp32-exact) or
+  // two fp16 planes hi / lo of the operand divided by a power of two (GPD_BF16 layers: three
+  // partial products, error below 2^-20 of a product)
   L->upd_planes = d->worker_dtype != GPD_F32 && d->batch % 64 == 0;
-  const size_t ues = L->upd_planes ? 6 : 4;
+  L->upd_fp16 = L->upd_planes && d->worker_dtype == GPD_BF16;
+  {
+    // |Dhat_p| <= (sum_i |a_p|^eUd[i]) max |Delta|, likewise Xhat: the bound as a power of two
+    double bd = 1, bx = 1;
+    for (double x : c.pts) {
+      double sd = 0, sx = 0;
+      for (int e : L->eUd) sd += std::pow(std::fabs(x), e);
+      for (int e : L->eUx) sx += std::pow(std::fabs(x), e);
+      bd = std::max(bd, sd); bx = std::max(bx, sx);
+    }
+    L->exp_Dh = (int)std::ceil(std::log2(bd)); L->exp_Xh = (int)std::ceil(std::log2(bx));
+    if (L->exp_Dh > 16 || L->exp_Xh > 16) L->upd_fp16 = false;    // (points far outside [-1, 1])
+  }
+  const size_t ues = L->upd_planes && !L->upd_fp16 ? 6 : 4;
   L->off_Dh = take((size_t)P * L->wr * d->batch * ues);
   L->off_Xh = take((size_t)P * L->wc * d->batch * ues);
   L->off_part = take((size_t)P * L->nchunks * L->wc * L->nb2 * 4);
+  L->off_scal = take((size_t)(2 * kAmaxParts + 2) * 4);
   const int64_t ncw = std::max(L->wr * L->nb1, L->wc * L->nb2);
   decode_workspace_layout(ncw, &L->flag_cap, &L->loc_cap, &L->dec_bytes);
   // the node search needs room for its partial Gram matrices (forward, backward and weight stacks)
@@ -475,6 +523,9 @@ extern "C" gpd_status_t gpd_layer_workspace_view(const gpd_layer_t* L, int32_t w
     case 3: *byte_offset = L->off_Ct; *rows = L->wc; *cols = L->nb2; break;
     case 4: *byte_offset = L->off_Dh; *rows = L->wr; *cols = L->desc.batch; break;
     case 5: *byte_offset = L->off_Xh; *rows = L->wc; *cols = L->desc.batch; break;
+    case 6:
+      if (!L->upd_fp16) return fail(GPD_E_INVALID, "gpd_layer_workspace_view: the layer holds no fp16 planes");
+      *byte_offset = L->off_scal + (size_t)2 * kAmaxParts * 4; *rows = 1; *cols = 2; break;
     default: return fail(GPD_E_INVALID, "gpd_layer_workspace_view: unknown buffer %d", which);
   }
   return GPD_OK;
@@ -755,6 +806,8 @@ extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, floa
   float* Dh = (float*)(ws + L->off_Dh);
   float* Xh = (float*)(ws + L->off_Xh);
   float* part = (float*)(ws + L->off_part);
+  uint32_t* scal = (uint32_t*)(ws + L->off_scal);
+  int32_t* exps = (int32_t*)(scal + 2 * kAmaxParts);
   void* dec_ws = ws + L->off_dec;
   hipStream_t s = L->stream;
   ScreenArgs none;
@@ -848,11 +901,24 @@ extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, floa
       st = launch_combine(s, tD, Dlt, d.batch, Dt, L->nb2, xt_bf16 ? 1 : 0, L->wr, L->nb2, none);
       if (st != GPD_OK) return st;
     }
-    st = launch_combine(s, tDh, Dlt, d.batch, Dh, d.batch, L->upd_planes ? 2 : 0, L->wr, d.batch, none,
-                        P * L->wr * d.batch);
+    const int kind = L->upd_fp16 ? 3 : (L->upd_planes ? 2 : 0);
+    PlaneScale sd, sx;
+    if (L->upd_fp16) {
+      // the fp16 planes hold the operands divided by a power of two chosen from the largest
+      // finite |Delta| and |X| of this call (one small pass over both, results stay on the device)
+      AbsMaxJobs aj;
+      aj.x[0] = Dlt; aj.n[0] = d.N_out * d.batch; aj.x[1] = X; aj.n[1] = d.N_in * d.batch;
+      aj.parts = scal;
+      hipLaunchKernelGGL(absmax_kernel, dim3(kAmaxParts, 2), dim3(256), 0, s, aj);
+      GPD_HIP(hipGetLastError());
+      sd.amax_parts = scal; sd.amax_n = kAmaxParts; sd.exp_extra = L->exp_Dh; sd.exp_out = exps;
+      sx.amax_parts = scal + kAmaxParts; sx.amax_n = kAmaxParts; sx.exp_extra = L->exp_Xh; sx.exp_out = exps + 1;
+    }
+    st = launch_combine(s, tDh, Dlt, d.batch, Dh, d.batch, kind, L->wr, d.batch, none, P * L->wr * d.batch,
+                        Epilogue(), sd);
     if (st != GPD_OK) return st;
-    st = launch_combine(s, tXh, X, d.batch, Xh, d.batch, L->upd_planes ? 2 : 0, L->wc, d.batch, none,
-                        P * L->wc * d.batch);
+    st = launch_combine(s, tXh, X, d.batch, Xh, d.batch, kind, L->wc, d.batch, none, P * L->wc * d.batch,
+                        Epilogue(), sx);
     if (st != GPD_OK) return st;
   }
   const float keep = 1.f - decay;
@@ -896,6 +962,7 @@ extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, floa
     g.batch = P; g.alpha = eta; g.beta = keep;
     g.mfma_bf16 = g.split3 = bf16;
     if (L->upd_planes) { g.planeA = P * L->wr * d.batch; g.planeB = P * L->wc * d.batch; }
+    if (L->upd_fp16) g.plane_exps = exps;
     st = launch_gemm(s, g);
     if (st != GPD_OK) return st;
   }

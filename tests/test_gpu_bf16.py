@@ -152,22 +152,88 @@ def test_cfg3_full_size_one_layer_step():
     C, _ = G.gpd_coded_layer_step(L, G.GPD_STEP_BACKWARD_UPDATE, Wt, to_dev(X), Dlt=to_dev(D), eta=0.01, decay=0.0)
     torch.cuda.synchronize()
     Dt, Ct = to_np(L.view(2, DEV).float()), to_np(L.view(3, DEV))
-    # update operands as the kernel holds them: three bf16 planes, [P][batch/16][rows][16] each
-    def planes(v):
-        s = v.double().sum(0).permute(0, 2, 1, 3)          # [P][rows][batch/16][16]
+    # update operands as the kernel holds them: two fp16 planes (hi, lo) of the operand / 2^E,
+    # [P][batch/16][rows][16] each, E per operand
+    def planes(v, e):
+        s = v.double().sum(0).permute(0, 2, 1, 3) * 2.0 ** e   # [P][rows][batch/16][16]
         return s.reshape(s.shape[0], s.shape[1], -1).cpu().numpy()
-    Dh, Xh = planes(L.view(4, DEV)), planes(L.view(5, DEV))
+    exps = L.view(6, DEV).cpu().numpy()
+    Dh, Xh = planes(L.view(4, DEV), int(exps[0])), planes(L.view(5, DEV), int(exps[1]))
+    # the scale leaves headroom: every fp16 value is finite and below 2^15, and uses at most the
+    # bits the bound on the encode's row sums gives away (2 terms for Dhat, 4 for Xhat)
+    for v, lo_bits in ((L.view(4, DEV), 1), (L.view(5, DEV), 2)):
+        top = float(v[0].abs().max())
+        assert 2.0 ** (13 - lo_bits) <= top < 2.0 ** 15, top
     for p in sample_p:
         # the planes add up to the encoded operands Dhat_p = sum_i Delta_i a_p^i, Xhat_p = sum_j X_j b_p^j
         Dh_o = sum(D[i * (N // m):(i + 1) * (N // m)].astype(np.float64) * O.int_power(olp.points[p], olp.eUd[i])
                    for i in range(m))
         Xh_o = sum(X[j * (N // n):(j + 1) * (N // n)].astype(np.float64) * O.int_power(olp.points[p], olp.eUx[j])
                    for j in range(n))
-        assert np.abs(Dh[p] - Dh_o).max() <= 2.0 ** -22 * np.abs(Dh_o).max()
-        assert np.abs(Xh[p] - Xh_o).max() <= 2.0 ** -22 * np.abs(Xh_o).max()
+        # hi + lo carries 22 significand bits, the fp32 encode in front of it 24
+        assert np.abs(Dh[p] - Dh_o).max() <= 2.0 ** -21 * np.abs(Dh_o).max()
+        assert np.abs(Xh[p] - Xh_o).max() <= 2.0 ** -21 * np.abs(Xh_o).max()
     for p in sample_p:
         # update on sampled rows: W~_p[r,:] + eta * Dh_p[r,:] Xh_p^T
         ref = Wt_rows_before[p] + np.float32(0.01) * (Dh[p][rows_s].astype(np.float64) @ Xh[p].astype(np.float64).T)
         got = to_np(Wt[p][torch.from_numpy(rows_s).to(DEV)])
         assert np.abs(got - ref).max() <= 1e-5 * np.abs(ref).max()
     say("  cfg3 L2 backward vs exact: %.3g" % rel_fro(to_np(C), W.astype(np.float64).T @ D))
+
+
+@pytest.mark.parametrize("regime", ["unit", "tiny", "huge", "spread", "zero", "nonfinite"])
+def test_bf16_layer_update_scale_regimes(regime):
+    # The update operands of a bf16 layer are two fp16 planes of Dhat_p / 2^E and Xhat_p / 2^E with
+    # E taken from the largest finite |Delta| and |X| of the call: the update must keep fp32-level
+    # accuracy whatever the magnitude of Delta, and a non-finite entry must stay in its own row.
+    say("bf16 update, Delta regime", regime)
+    N_out, N_in, batch, m, n, P = 256, 384, 128, 2, 4, 32
+    rng = np.random.default_rng(17)
+    W = (rng.standard_normal((N_out, N_in)) / 16).astype(np.float32)
+    X = rng.uniform(0, 1, (N_in, batch)).astype(np.float32)
+    D = rng.standard_normal((N_out, batch)).astype(np.float32)
+    if regime == "tiny":
+        D = (D * 1e-30).astype(np.float32)
+    elif regime == "huge":
+        D = (D * 1e25).astype(np.float32)
+    elif regime == "spread":
+        D = (D * np.exp(rng.uniform(-40, 0, D.shape))).astype(np.float32)
+    elif regime == "zero":
+        D[:] = 0
+    elif regime == "nonfinite":
+        D[5, 7] = np.inf
+        D[130, 0] = np.nan
+    olp = O.make_layer_plan(N_out, N_in, batch, m, n, 1, 1, P, "auto")
+    L = G.gpd_layer_create(N_out, N_in, batch, m, n, 1, 1, P, worker_dtype=G.GPD_BF16)
+    Wt = G.gpd_layer_encode_weights(L, to_dev(W))
+    Wt0 = to_np(Wt).copy()
+    # eta such that the update is of the order of the weights (the sum's own fp32 rounding then
+    # stays below the bound)
+    finite = np.abs(D[np.isfinite(D)])
+    eta = np.float32(1.0 if finite.max() == 0 else 2.0 ** -np.ceil(np.log2(finite.max() * 8)))
+    G.gpd_coded_layer_step(L, G.GPD_STEP_BACKWARD_UPDATE, Wt, to_dev(X), Dlt=to_dev(D), eta=float(eta), decay=0.0,
+                           skip_output=True)
+    torch.cuda.synchronize()
+    got = to_np(Wt)
+    if regime == "nonfinite":
+        # Dhat_p rows 5 and 130 - 128 = 2 of every node carry the non-finite entries (m = 2 blocks of
+        # 128 rows); every other row is what the same call gives with those two entries at zero
+        bad_rows = {5, 2}
+        D0 = D.copy()
+        D0[5, 7] = 0
+        D0[130, 0] = 0
+        ref = O.layer_update(Wt0, D0, X, olp, eta, 0.0)
+        keep = np.array([r not in bad_rows for r in range(got.shape[1])])
+        assert np.isfinite(got[:, keep]).all()
+        assert not np.isfinite(got[:, ~keep]).any()
+        upd = np.abs(ref - Wt0)[:, keep].max()
+        assert np.abs(got[:, keep] - ref[:, keep]).max() <= 2e-6 * upd
+        return
+    ref = O.layer_update(Wt0, D, X, olp, eta, 0.0)
+    if regime == "zero":
+        assert np.array_equal(got, Wt0)
+        return
+    upd = np.abs(ref - Wt0).max()
+    err = np.abs(got - ref).max()
+    say("  max|err| / max|update| = %.3g (update / weights = %.3g)" % (err / upd, upd / np.abs(Wt0).max()))
+    assert err <= 2e-6 * upd
