@@ -120,6 +120,9 @@ def bench_mlp(args, cfg):
            "dtype": cfg["worker"], "data": "synthetic", "hip_graph": bool(args.graph),
            "config": {"workload": f"coded MLP {sizes} batch {batch} m={m} n={n} P={P} "
                                   f"K_f={mlp.layers[0].Kf} K_b={mlp.layers[0].Kb}"},
+           "update_arithmetic": ("operands as two fp16 planes of value / 2^E, three partial products, fp32 "
+                                 "accumulation: error below 2^-20 of a product" if cfg["worker"] == "bf16"
+                                 else "fp32 (batch <= 8: vector units; else fp32 matrix cores)"),
            "weight_stream_GBps": alg_bytes / (ms * 1e-3) / 1e9,
            "weight_stream_bytes_per_step": alg_bytes}
     print(json.dumps(out), flush=True)

@@ -953,7 +953,7 @@ extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, floa
       if (st != GPD_OK) return st;
     }
     // W~_p <- keep * W~_p + eta * Dhat_p Xhat_p^T   (step O3 in coded form, fp32: on the fp32
-    // matrix cores for fp32 layers, as six bf16 partial products otherwise)
+    // matrix cores for fp32 layers, as six bf16 or three fp16 partial products otherwise)
     GemmArgs g;
     g.A = Dh; g.B = Xh; g.transB = true; g.C = Wt;
     g.M = L->wr; g.K = d.batch; g.N = L->wc;
