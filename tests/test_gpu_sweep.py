@@ -63,3 +63,57 @@ def test_random_shapes(seed):
             TB.test_bf16_layer_stagewise(*a)
         else:
             TS.test_split_layer_step(*a)
+
+
+@pytest.mark.parametrize("seed", [21, 22])
+def test_random_soft_errors(seed):
+    """Random codes (K <= 12, P - K from 2 to 8), random erasures, and in up to a quarter of the
+    codewords between 0 and one more error than Algorithm 1 can correct: offsets, huge values,
+    non-finite values and single bit flips.  The GPU must take the oracle's decisions exactly."""
+    import test_gpu_errors as TE
+    import paper_1811_10751_amd as G
+    from gpu_util import to_dev, to_np
+    rng = np.random.default_rng(seed)
+    done = 0
+    while done < 30:
+        m, n, d = (int(rng.integers(1, 4)) for _ in range(3))
+        K = m * n * d + n - 1
+        if K > 12:
+            continue
+        r = int(rng.integers(2, 9))
+        P = K + r
+        N1, N0, Nc = (q * int(rng.integers(2, 20)) for q in (m, n, d))
+        A, B, plan, Ct = TE.gpu_responses(N1, N0, Nc, m, n, d, P, seed * 1000 + done)
+        Ct_h = to_np(Ct).copy()
+        n_er = int(rng.integers(0, max(1, r - 1)))
+        present = np.ones(P, dtype=np.uint8)
+        if n_er:
+            present[rng.choice(P, n_er, replace=False)] = 0
+        room = r - n_er - 1                       # errors Algorithm 1 can correct per codeword
+        rows, cols = Ct_h.shape[1:]
+        ncw = rows * cols
+        nbad = int(rng.integers(0, max(2, ncw // 4)))
+        for cw in rng.choice(ncw, nbad, replace=False):
+            t = int(rng.integers(0, room + 2))
+            for p in rng.choice(np.flatnonzero(present), min(t, int(present.sum())), replace=False):
+                i, j = cw // cols, cw % cols
+                v = Ct_h[p, i, j]
+                how = rng.integers(0, 4)
+                if how == 0:
+                    Ct_h[p, i, j] = v + np.float32(rng.standard_normal() * 10 * (abs(v) + 1))
+                elif how == 1:
+                    Ct_h[p, i, j] = np.float32(rng.standard_normal() * 1e20)
+                elif how == 2:
+                    Ct_h[p, i, j] = np.float32(np.inf if rng.random() < .5 else np.nan)
+                else:
+                    w = np.array([v], dtype=np.float32).view(np.uint32)
+                    w ^= np.uint32(1 << int(rng.integers(0, 32)))
+                    Ct_h[p, i, j] = w.view(np.float32)[0]
+        say("soft-error sweep", seed, (N1, N0, Nc, m, n, d, P), "erasures", n_er, "codewords hit", nbad)
+        opl = O.make_plan(m, n, d, P)
+        C_o, orep = O.decode(Ct_h, opl, present, correct=True)
+        C, rep = G.gpd_decode(plan, to_dev(Ct_h), present=present, mode=G.GPD_DEC_LSQ_ALL, correct_errors=True,
+                              located_cap=100000)
+        TE.compare_reports(rep, orep, P)
+        TE.check_outputs(C, C_o, orep, plan, tol=max(2e-5, 1e-6 * O.amplification(opl, present, "lsq_all")))
+        done += 1
