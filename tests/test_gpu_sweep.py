@@ -117,3 +117,27 @@ def test_random_soft_errors(seed):
         TE.compare_reports(rep, orep, P)
         TE.check_outputs(C, C_o, orep, plan, tol=max(2e-5, 1e-6 * O.amplification(opl, present, "lsq_all")))
         done += 1
+
+
+@pytest.mark.parametrize("seed", [31])
+def test_random_node_searches(seed):
+    """Random codes up to P = 64 nodes with absent nodes and up to four erroneous ones (kept small
+    enough for the oracle's exhaustive search): Gram matrix, threshold and located set."""
+    from math import comb
+    import test_gpu_nodes as TN
+    rng = np.random.default_rng(seed)
+    for _ in range(40):
+        K = int(rng.integers(1, 25))
+        P = K + int(rng.integers(0, min(40, 64 - K) + 1))
+        n_abs = int(rng.integers(0, min(4, P - K) + 1))
+        present_n = P - n_abs
+        t = int(rng.integers(0, max(0, min(present_n - K - 1, 4)) + 1))
+        while t > 0 and comb(present_n, t) > 1000:
+            t -= 1
+        nodes = rng.permutation(P)
+        absent = tuple(sorted(int(x) for x in nodes[:n_abs]))
+        bad = tuple(sorted(int(x) for x in nodes[n_abs:n_abs + t]))
+        rows, cols = int(rng.integers(1, 70)), int(rng.integers(1, 70))
+        if rows * cols < 8 * max(1, t):
+            rows, cols = 16, 16                  # enough codewords to tell the nodes apart
+        TN.test_gram_matrix_and_node_search(P, K, rows, cols, bad, absent)
