@@ -237,3 +237,30 @@ def test_bf16_layer_update_scale_regimes(regime):
     err = np.abs(got - ref).max()
     say("  max|err| / max|update| = %.3g (update / weights = %.3g)" % (err / upd, upd / np.abs(Wt0).max()))
     assert err <= 2e-6 * upd
+
+
+def test_bf16_layer_update_with_points_outside_the_unit_interval():
+    # Evaluation points of magnitude up to 1.3 (m = 2, n = 4: Xhat_p sums |b_p|^j up to the cube):
+    # the bound on the encode's row sums grows and the exponent leaves more headroom.  Points far
+    # outside [-1, 1] (bound above 2^16) make the layer fall back to the three-way bf16 split;
+    # both give the oracle's update.
+    N_out, N_in, batch, m, n, P = 128, 256, 64, 2, 4, 16
+    rng = np.random.default_rng(23)
+    W = (rng.standard_normal((N_out, N_in)) / 16).astype(np.float32)
+    X = rng.uniform(0, 1, (N_in, batch)).astype(np.float32)
+    D = rng.standard_normal((N_out, batch)).astype(np.float32)
+    for stretch, fp16 in ((1.3, True), (40.0, False)):
+        pts = O.chebyshev_points(P) * stretch
+        olp = O.make_layer_plan(N_out, N_in, batch, m, n, 1, 1, P, "auto", points=pts)
+        L = G.gpd_layer_create(N_out, N_in, batch, m, n, 1, 1, P, points=pts, worker_dtype=G.GPD_BF16)
+        Wt = G.gpd_layer_encode_weights(L, to_dev(W))
+        Wt0 = to_np(Wt).copy()
+        G.gpd_coded_layer_step(L, G.GPD_STEP_BACKWARD_UPDATE, Wt, to_dev(X), Dlt=to_dev(D), eta=0.01, decay=0.0,
+                               skip_output=True)
+        torch.cuda.synchronize()
+        assert (L.view(4, DEV).dtype == torch.float16) == fp16
+        ref = O.layer_update(Wt0, D, X, olp, np.float32(0.01), 0.0)
+        upd = np.abs(ref - Wt0).max()
+        err = np.abs(to_np(Wt) - ref).max()
+        say("  points x %.1f: fp16 planes %s, max|err| / max|update| = %.3g" % (stretch, fp16, err / upd))
+        assert err <= 2e-6 * upd + 2.0 ** -23 * np.abs(ref).max()
