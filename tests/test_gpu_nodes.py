@@ -184,7 +184,8 @@ def test_bad_arguments():
 LAYERS = [
     (96, 80, 1, 4, 2, 1, 1, 14),          # batch 1 (vectors), v = u^m
     (301, 204, 3, 2, 3, 1, 1, 20),        # rows padded to 302
-    (256, 384, 32, 2, 4, 1, 1, 32),       # the cfg3 code
+    (256, 384, 32, 2, 4, 1, 1, 32),       # the cfg3 code (projection on the matrix cores, 32 nodes)
+    (128, 64, 1, 4, 2, 1, 1, 24),         # the cfg2 code, 1024-element blocks (the same, 24 nodes)
 ]
 
 
