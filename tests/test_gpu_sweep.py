@@ -141,3 +141,46 @@ def test_random_node_searches(seed):
         if rows * cols < 8 * max(1, t):
             rows, cols = 16, 16                  # enough codewords to tell the nodes apart
         TN.test_gram_matrix_and_node_search(P, K, rows, cols, bad, absent)
+
+
+@pytest.mark.parametrize("seed", [41])
+def test_random_projections(seed):
+    """Projection of a drifted weight stack onto the code for random block grids, node counts on
+    both sides of 32 (matrix-core kernel / vector-unit kernel), block sizes on and off a multiple of
+    128 elements, and absent nodes whose blocks hold garbage."""
+    import torch
+    import paper_1811_10751_amd as G
+    from gpu_util import to_dev, to_np
+    rng = np.random.default_rng(seed)
+    done = 0
+    while done < 40:
+        m, n = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        K = m * n
+        P = min(K + int(rng.integers(1, 33)), 40 if rng.random() < 0.2 else 32)
+        if P <= K:
+            continue
+        wr, wc = int(rng.choice([4, 8, 16, 32, 48, 64])), int(rng.choice([8, 16, 32, 64, 96, 128]))
+        if rng.random() < 0.2:
+            wc += 3
+        N_out, N_in = wr * m, wc * n
+        olp = O.make_layer_plan(N_out, N_in, 1, m, n, 1, 1, P, "auto")
+        L = G.gpd_layer_create(N_out, N_in, 1, m, n, 1, 1, P)
+        W = (rng.standard_normal((N_out, N_in)) / 8).astype(np.float32)
+        Wt = G.gpd_layer_encode_weights(L, to_dev(W))
+        clean = to_np(Wt).copy()
+        n_abs = int(rng.integers(0, P - K + 1)) if rng.random() < 0.6 else 0
+        present = np.ones(P, dtype=np.uint8)
+        if n_abs:
+            present[rng.choice(P, n_abs, replace=False)] = 0
+        noisy = clean + (rng.standard_normal(clean.shape) * 1e-3).astype(np.float32)
+        noisy[present == 0] = 777.0
+        say("projection sweep", (N_out, N_in, m, n, P), "absent", n_abs, "block", wr * wc)
+        Wt.copy_(to_dev(noisy))
+        G.gpd_layer_project(L, Wt, present if n_abs else None)
+        torch.cuda.synchronize()
+        ref = O.layer_project(noisy, olp, present if n_abs else None)
+        V = O.vandermonde(olp.points[present.astype(bool)], K)
+        amp = max(np.abs(O.vandermonde(olp.points, K) @ np.linalg.pinv(V)).sum(axis=1).max(), 1.0)
+        assert np.abs(to_np(Wt) - ref).max() <= 4e-6 * amp * np.abs(clean).max()
+        L.close()
+        done += 1
