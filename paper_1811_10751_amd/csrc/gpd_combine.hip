@@ -186,7 +186,9 @@ static_assert(sizeof(CombineParams) <= 4096, "kernel arguments are limited to 4 
 // OUT: 0 fp32, 1 bf16, 2 three bf16 planes (hi, mid, lo of the fp32 value), each block stored
 // k-blocked: 16 consecutive columns of a row are contiguous, rows next, column groups outermost;
 // 3 two fp16 planes (hi, lo) of the value divided by a power of two, k-blocked in the same way
-template <int NIN_MAX, int VEC, int OUT, bool SCREEN, bool LIMITS>
+// TAB: the coefficient tables come through LDS (too large for the kernel arguments); else they
+// are kernel arguments.  Two kernels, so that neither carries the other's code and registers.
+template <int NIN_MAX, int VEC, int OUT, bool SCREEN, bool LIMITS, bool TAB>
 __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t total = p.rows * p.cols_vec;
@@ -225,7 +227,30 @@ __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
   for (int s = 0; s < NIN_MAX; ++s)
 #pragma unroll
     for (int v = 0; v < VEC; ++v) z[s][v] = take[s] ? z[s][v] : 0.f;
-  const bool karg = p.karg != 0;
+  constexpr bool karg = !TAB;
+
+  // Tables too large for the kernel arguments go through LDS (dynamic, sized by the host; none
+  // when karg): the rows this workgroup needs, padded with zeros to NIN_MAX entries so that a row
+  // is read whole and without a branch, like the kernel-argument form.  LDS reads do not share a
+  // counter with the output stores, so they never wait for them.
+  extern __shared__ float tab_lds[];
+  const int q_first = blockIdx.y * p.q_chunk;
+  const int q_count = min(p.nout, q_first + p.q_chunk) - q_first;
+  float* coef_s = tab_lds;
+  float* H_s = tab_lds + p.q_chunk * NIN_MAX;
+  if constexpr (!karg) {
+    for (int idx = threadIdx.x; idx < q_count * NIN_MAX; idx += blockDim.x) {
+      const int q = idx / NIN_MAX, s2 = idx - q * NIN_MAX;
+      coef_s[idx] = s2 < p.nin ? p.coef[(int64_t)(q_first + q) * p.nin + s2] : 0.f;
+    }
+    if constexpr (SCREEN) {
+      for (int idx = threadIdx.x; idx < p.r * NIN_MAX; idx += blockDim.x) {
+        const int i = idx / NIN_MAX, s2 = idx - i * NIN_MAX;
+        H_s[idx] = s2 < p.nin ? p.H[(int64_t)i * p.nin + s2] : 0.f;
+      }
+    }
+    __syncthreads();
+  }
 
   float inv = 1.f;
   if constexpr (OUT == 3) {
@@ -277,22 +302,20 @@ __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) y[v] = fmaf(h[s], z[s][v], y[v]);
         } else {
-          const float* __restrict__ hrow = p.H + (int64_t)i * p.nin;
+          const float* hrow = H_s + i * NIN_MAX;
+          float h[NIN_MAX];
 #pragma unroll
-          for (int s = 0; s < NIN_MAX; ++s) {
-            if (s < p.nin) {
-              const float h = hrow[s];
+          for (int s = 0; s < NIN_MAX; ++s) h[s] = hrow[s];
 #pragma unroll
-              for (int v = 0; v < VEC; ++v) y[v] = fmaf(h, z[s][v], y[v]);
-            }
-          }
+          for (int s = 0; s < NIN_MAX; ++s)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) y[v] = fmaf(h[s], z[s][v], y[v]);
         }
 #pragma unroll
         for (int v = 0; v < VEC; ++v) sig2[v] = fmaf(y[v], y[v], sig2[v]);
       }
     };
-    if (karg) syndromes(std::true_type{});
-    else syndromes(std::false_type{});
+    syndromes(std::integral_constant<bool, karg>{});
     float ratio = 0.f;
 #pragma unroll
     for (int v = 0; v < VEC; ++v) {
@@ -342,15 +365,14 @@ __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
 #pragma unroll
           for (int v = 0; v < VEC; ++v) acc[v] = fmaf(c[s], z[s][v], acc[v]);
       } else {
-        const float* __restrict__ crow = p.coef + (int64_t)q * p.nin;
+        const float* crow = coef_s + (q - q_first) * NIN_MAX;
+        float c[NIN_MAX];
 #pragma unroll
-        for (int s = 0; s < NIN_MAX; ++s) {
-          if (s < p.nin) {
-            const float c = crow[s];
+        for (int s = 0; s < NIN_MAX; ++s) c[s] = crow[s];
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) acc[v] = fmaf(c, z[s][v], acc[v]);
-          }
-        }
+        for (int s = 0; s < NIN_MAX; ++s)
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) acc[v] = fmaf(c[s], z[s][v], acc[v]);
       }
       if constexpr (LIMITS) {
         if (!(row < p.out_rows[q] && col < p.out_cols[q])) continue;
@@ -379,8 +401,7 @@ __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
       }
     }
   };
-  if (karg) outputs(std::true_type{});
-  else outputs(std::false_type{});
+  outputs(std::integral_constant<bool, karg>{});
 }
 
 template <int NIN_MAX, int VEC>
@@ -393,22 +414,32 @@ gpd_status_t launch_t(hipStream_t stream, const CombineParams& p, int out_kind, 
   if (blocks > 0x7fffffffLL) return fail(GPD_E_SHAPE, "block too large for one launch");
   dim3 grid((unsigned)blocks, (unsigned)((p.nout + p.q_chunk - 1) / p.q_chunk)), block(64);
   const bool lim = p.in_rows != nullptr;
+  // tables that do not travel as kernel arguments are staged in LDS: q_chunk coefficient rows and,
+  // with the screen, r parity-check rows of NIN_MAX entries each
+  const size_t lds = p.karg ? 0 : (size_t)(p.q_chunk + (screen ? p.r : 0)) * NIN_MAX * sizeof(float);
+  if (lds > 64 * 1024) return fail(GPD_E_UNSUPPORTED, "combine: tables of %zu bytes do not fit the LDS", lds);
+  auto go = [&](auto out_c, auto screen_c) {
+    constexpr int O = decltype(out_c)::value;
+    constexpr bool S = decltype(screen_c)::value;
+    if (p.karg) {
+      if (lim) hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, O, S, true, false>), grid, block, lds, stream, p);
+      else hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, O, S, false, false>), grid, block, lds, stream, p);
+    } else {
+      if (lim) hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, O, S, true, true>), grid, block, lds, stream, p);
+      else hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, O, S, false, true>), grid, block, lds, stream, p);
+    }
+  };
   if (screen) {
     if (out_kind != 0) return fail(GPD_E_UNSUPPORTED, "screen with bf16 output");
-    if (lim) hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, 0, true, true>), grid, block, 0, stream, p);
-    else hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, 0, true, false>), grid, block, 0, stream, p);
+    go(std::integral_constant<int, 0>{}, std::true_type{});
   } else if (out_kind == 3) {
-    if (lim) hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, 3, false, true>), grid, block, 0, stream, p);
-    else hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, 3, false, false>), grid, block, 0, stream, p);
+    go(std::integral_constant<int, 3>{}, std::false_type{});
   } else if (out_kind == 2) {
-    if (lim) hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, 2, false, true>), grid, block, 0, stream, p);
-    else hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, 2, false, false>), grid, block, 0, stream, p);
+    go(std::integral_constant<int, 2>{}, std::false_type{});
   } else if (out_kind == 1) {
-    if (lim) hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, 1, false, true>), grid, block, 0, stream, p);
-    else hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, 1, false, false>), grid, block, 0, stream, p);
+    go(std::integral_constant<int, 1>{}, std::false_type{});
   } else {
-    if (lim) hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, 0, false, true>), grid, block, 0, stream, p);
-    else hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, 0, false, false>), grid, block, 0, stream, p);
+    go(std::integral_constant<int, 0>{}, std::false_type{});
   }
   GPD_HIP(hipGetLastError());
   return GPD_OK;
