@@ -31,7 +31,7 @@ PEAK_HBM_GBS = 8000.0             # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the worker-product kernel on the default workload, from the committed
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/coded_matmul_4096_fp32.md):
 # 393672 KiB x 2.0 (copy-kernel calibration) fetched + 262144 KiB written
-GEMM_TRAFFIC_BYTES_CFG1 = (393488 * 2.0 + 262144) * 1024   # FETCH_SIZE x 2.0 + WRITE_SIZE, KiB per launch (profiles/coded_matmul_4096_fp32.md)
+GEMM_TRAFFIC_BYTES_CFG1 = (393520 * 2.0 + 262144) * 1024   # FETCH_SIZE x 2.0 + WRITE_SIZE, KiB per launch (profiles/coded_matmul_4096_fp32.md)
 
 
 def cpu_baseline(cfg, n_threads):
