@@ -1078,6 +1078,59 @@ __global__ __launch_bounds__(64 * kShortWaves) void short_m_bf16_kernel(const HG
   }
 }
 
+// The same layer's backward product: C = beta C + alpha A^T B with a contraction over at most 8
+// rows (A stored K x M fp32, B K x N bf16, both row-major).  Nothing to tile: a thread owns four
+// consecutive columns of kShortRows consecutive output rows, reads its K 8-byte pieces of B once
+// and K x kShortRows values of A (two 16-byte loads per k, the same for all lanes that share the
+// rows), rounds A to bf16 like the matrix cores would, and stores 16 bytes per row; the kernel
+// is bound by writing C.
+constexpr int kShortRows = 8;
+
+__global__ __launch_bounds__(256) void short_k_bf16_kernel(const HGemmParams g) {
+  const int n4 = g.N >> 2;                                   // N % 4 == 0, M % 8 == 0 (host-checked)
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (int64_t)(g.M / kShortRows) * n4) return;
+  const int row = (int)(idx / n4) * kShortRows, n = (int)(idx % n4) * 4;
+  const float* __restrict__ A = reinterpret_cast<const float*>(g.A) + (int64_t)blockIdx.y * g.sA + row;
+  const uint16_t* __restrict__ B = reinterpret_cast<const uint16_t*>(g.B) + (int64_t)blockIdx.y * g.sB + n;
+  float4 a[kShortM][2];
+  uint2 b[kShortM];
+#pragma unroll
+  for (int k = 0; k < kShortM; ++k) {
+    const int kc = min(k, g.K - 1);                          // beyond K: re-read the last, weight 0
+    a[k][0] = *reinterpret_cast<const float4*>(A + (int64_t)kc * g.lda);
+    a[k][1] = *reinterpret_cast<const float4*>(A + (int64_t)kc * g.lda + 4);
+    b[k] = k < g.K ? *reinterpret_cast<const uint2*>(B + (int64_t)kc * g.ldb) : make_uint2(0u, 0u);
+  }
+  float acc[kShortRows][4];
+#pragma unroll
+  for (int r = 0; r < kShortRows; ++r)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) acc[r][c] = 0.f;
+#pragma unroll
+  for (int k = 0; k < kShortM; ++k) {
+    const float bv[4] = {__uint_as_float(b[k].x << 16), __uint_as_float(b[k].x & 0xffff0000u),
+                         __uint_as_float(b[k].y << 16), __uint_as_float(b[k].y & 0xffff0000u)};
+    const float av[kShortRows] = {a[k][0].x, a[k][0].y, a[k][0].z, a[k][0].w, a[k][1].x, a[k][1].y, a[k][1].z, a[k][1].w};
+#pragma unroll
+    for (int r = 0; r < kShortRows; ++r) {
+      const float ar = bf16_round(av[r]);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) acc[r][c] = fmaf(ar, bv[c], acc[r][c]);
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < kShortRows; ++r) {
+    float4* c = reinterpret_cast<float4*>(g.C + (int64_t)blockIdx.y * g.sC + (int64_t)(row + r) * g.ldc + n);
+    float4 o = make_float4(g.alpha * acc[r][0], g.alpha * acc[r][1], g.alpha * acc[r][2], g.alpha * acc[r][3]);
+    if (g.beta != 0.f) {
+      const float4 old = *c;
+      o = make_float4(fmaf(g.beta, old.x, o.x), fmaf(g.beta, old.y, o.y), fmaf(g.beta, old.z, o.z), fmaf(g.beta, old.w, o.w));
+    }
+    *c = o;
+  }
+}
+
 template <int ASRC, int BSRC, int SPLIT>
 gpd_status_t launch_bf16_t(hipStream_t stream, HGemmParams p, int64_t batch, bool aligned) {
   // same two workgroup shapes as the fp32 kernel; the large one needs full aligned tiles
@@ -1216,6 +1269,16 @@ gpd_status_t launch_gemm(hipStream_t stream, const GemmArgs& a) {
       static_assert(kShortKC == 64 * kShortWaves, "one thread per value of k of a chunk");
       const dim3 grid((unsigned)((a.N + 63) / 64), (unsigned)a.batch);
       hipLaunchKernelGGL(short_m_bf16_kernel, grid, dim3(64 * kShortWaves), 0, stream, h);
+      GPD_HIP(hipGetLastError());
+      return GPD_OK;
+    }
+    if (a.transA && !a.a_bf16 && a.b_bf16 && a.K >= 1 && a.K <= kShortM && a.M > 0 && a.M % kShortRows == 0 &&
+        a.N > 0 && a.N % 4 == 0 && a.lda % 4 == 0 && a.strideA % 4 == 0 && (uintptr_t)a.A % 16 == 0 &&
+        a.ldb % 4 == 0 && a.strideB % 4 == 0 && (uintptr_t)a.B % 8 == 0 && a.ldc % 4 == 0 && a.strideC % 4 == 0 &&
+        (uintptr_t)a.C % 16 == 0 && a.batch > 0 && a.batch <= 65535 &&
+        (a.M / kShortRows) * (a.N / 4) < 0x7fffffffLL * 256) {
+      const dim3 grid((unsigned)(((a.M / kShortRows) * (a.N / 4) + 255) / 256), (unsigned)a.batch);
+      hipLaunchKernelGGL(short_k_bf16_kernel, grid, dim3(256), 0, stream, h);
       GPD_HIP(hipGetLastError());
       return GPD_OK;
     }

@@ -65,6 +65,8 @@ LAYER_CASES = [
     (1024, 1024, 128, 2, 4, 1, 1, 32),    # planes, 256 full tiles
     (10, 1000, 64, 2, 4, 1, 1, 32),       # output layer: 5 rows per node (few-row forward kernel)
     (7, 520, 24, 1, 4, 1, 1, 20),         # 7 rows, batch 24 (ragged 64-column groups)
+    (10, 1024, 64, 2, 4, 1, 1, 32),       # output layer whose backward product takes the few-row kernel too
+    (16, 512, 128, 2, 2, 2, 2, 20),       # 8 rows per node, d1 = d2 = 2
 ]
 
 
