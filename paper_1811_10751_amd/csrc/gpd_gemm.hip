@@ -1012,8 +1012,10 @@ gpd_status_t launch_planes(hipStream_t stream, HGemmParams p, int64_t batch) {
 // output layer of a classifier.  A 128-row matrix-core tile would be 1/16 full and its k-loop one
 // chain of dependent steps on a few workgroups, so this is a streaming kernel instead: a
 // workgroup of 16 wavefronts owns 64 output columns of one batch entry, each wavefront 1/16 of
-// k, a lane one column.  A goes through LDS in chunks of kShortKC values of k, rounded to bf16
-// (nearest even) like on the matrix cores; products are summed in fp32.
+// k; a lane owns four columns (one 8-byte load per k) of every fourth k of its wavefront, so a
+// load instruction covers four rows of B.  A goes through LDS in chunks of kShortKC values of k,
+// rounded to bf16 (nearest even) like on the matrix cores; products are summed in fp32, the four
+// k-phases of a wavefront by shuffles, the 16 wavefronts through LDS in wavefront order.
 constexpr int kShortM = 8, kShortKC = 1024, kShortWaves = 16;
 
 __device__ __forceinline__ float bf16_round(float x) { return __uint_as_float(pack_bf16(x, 0.f) << 16); }
@@ -1022,16 +1024,18 @@ __global__ __launch_bounds__(64 * kShortWaves) void short_m_bf16_kernel(const HG
   __shared__ float4 As[kShortKC][2];                     // [k][rows 0-3 | rows 4-7], zero beyond M
   __shared__ float part[kShortWaves][kShortM][64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int n = blockIdx.x * 64 + lane;
-  const int nc = min(n, g.N - 1);                        // lanes beyond N re-read the last column
+  const int ks = lane >> 4, cg = lane & 15;              // k-phase, group of four columns
+  const int n = blockIdx.x * 64 + 4 * cg;
+  const int nc = min(n, g.N - 4);                        // groups beyond N re-read the last one (N % 4 == 0)
   const float* __restrict__ A = reinterpret_cast<const float*>(g.A) + (int64_t)blockIdx.y * g.sA;
   const uint16_t* __restrict__ B = reinterpret_cast<const uint16_t*>(g.B) + (int64_t)blockIdx.y * g.sB + nc;
-  float acc[kShortM];
+  float acc[kShortM][4];
 #pragma unroll
-  for (int r = 0; r < kShortM; ++r) acc[r] = 0.f;
+  for (int r = 0; r < kShortM; ++r)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) acc[r][c] = 0.f;
   constexpr int KW = kShortKC / kShortWaves;             // values of k per wavefront and chunk
-  constexpr int U = 16;
-  static_assert(KW % U == 0, "whole groups of loads");
+  constexpr int U = KW / 4;                              // ... per lane
   for (int kc = 0; kc < g.K; kc += kShortKC) {
     __syncthreads();                                     // the previous chunk has been consumed
     {
@@ -1043,36 +1047,43 @@ __global__ __launch_bounds__(64 * kShortWaves) void short_m_bf16_kernel(const HG
       As[tid][1] = make_float4(a[4], a[5], a[6], a[7]);
     }
     __syncthreads();
-    const int kw = wave * KW;                            // offset of this wavefront's values inside the chunk
-#pragma unroll 1
-    for (int u0 = 0; u0 < KW; u0 += U) {
-      float b[U];
+    const int kw = wave * KW + ks;                       // this lane's first k inside the chunk
+    uint2 b[U];
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int k = min(kc + kw + u0 + u, g.K - 1);    // beyond K: A is zero there
-        b[u] = __uint_as_float((uint32_t)B[(int64_t)k * g.ldb] << 16);
-      }
+    for (int u = 0; u < U; ++u) {
+      const int k = min(kc + kw + 4 * u, g.K - 1);       // beyond K: A is zero there
+      b[u] = *reinterpret_cast<const uint2*>(B + (int64_t)k * g.ldb);
+    }
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const float4 lo = As[kw + u0 + u][0], hi = As[kw + u0 + u][1];
-        acc[0] = fmaf(lo.x, b[u], acc[0]); acc[1] = fmaf(lo.y, b[u], acc[1]);
-        acc[2] = fmaf(lo.z, b[u], acc[2]); acc[3] = fmaf(lo.w, b[u], acc[3]);
-        acc[4] = fmaf(hi.x, b[u], acc[4]); acc[5] = fmaf(hi.y, b[u], acc[5]);
-        acc[6] = fmaf(hi.z, b[u], acc[6]); acc[7] = fmaf(hi.w, b[u], acc[7]);
-      }
+    for (int u = 0; u < U; ++u) {
+      const float4 lo = As[kw + 4 * u][0], hi = As[kw + 4 * u][1];
+      const float av[kShortM] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+      const float bv[4] = {__uint_as_float(b[u].x << 16), __uint_as_float(b[u].x & 0xffff0000u),
+                           __uint_as_float(b[u].y << 16), __uint_as_float(b[u].y & 0xffff0000u)};
+#pragma unroll
+      for (int r = 0; r < kShortM; ++r)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[r][c] = fmaf(av[r], bv[c], acc[r][c]);
     }
   }
 #pragma unroll
-  for (int r = 0; r < kShortM; ++r) part[wave][r][lane] = acc[r];
+  for (int r = 0; r < kShortM; ++r)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      float v = acc[r][c];
+      v += __shfl_xor(v, 16);
+      v += __shfl_xor(v, 32);
+      if (ks == 0) part[wave][r][4 * cg + c] = v;
+    }
   __syncthreads();
   // thread (r, column) adds the 16 partial sums in wavefront order
   if (tid < kShortM * 64) {
-    const int r = tid >> 6;
+    const int r = tid >> 6, col = blockIdx.x * 64 + lane;
     float v = 0.f;
 #pragma unroll
     for (int w = 0; w < kShortWaves; ++w) v += part[w][r][lane];
-    if (r < g.M && n < g.N) {
-      float* c = g.C + (int64_t)blockIdx.y * g.sC + (int64_t)r * g.ldc + n;
+    if (r < g.M && col < g.N) {
+      float* c = g.C + (int64_t)blockIdx.y * g.sC + (int64_t)r * g.ldc + col;
       *c = g.beta != 0.f ? fmaf(g.beta, *c, g.alpha * v) : g.alpha * v;
     }
   }
@@ -1264,8 +1275,8 @@ gpd_status_t launch_gemm(hipStream_t stream, const GemmArgs& a) {
       if (a.transA && !a.transB) return launch_bf16_t<SRC_F32_RC, SRC_F32_RC, 3>(stream, h, a.batch, al);
       return launch_bf16_t<SRC_F32_RC, SRC_F32_KC, 3>(stream, h, a.batch, al);
     }
-    if (!a.transA && !a.a_bf16 && a.b_bf16 && a.M >= 1 && a.M <= kShortM && a.N > 0 && a.K > 0 && a.batch > 0 &&
-        a.batch <= 65535) {
+    if (!a.transA && !a.a_bf16 && a.b_bf16 && a.M >= 1 && a.M <= kShortM && a.N >= 4 && a.N % 4 == 0 && a.K > 0 &&
+        a.ldb % 4 == 0 && a.strideB % 4 == 0 && (uintptr_t)a.B % 8 == 0 && a.batch > 0 && a.batch <= 65535) {
       static_assert(kShortKC == 64 * kShortWaves, "one thread per value of k of a chunk");
       const dim3 grid((unsigned)((a.N + 63) / 64), (unsigned)a.batch);
       hipLaunchKernelGGL(short_m_bf16_kernel, grid, dim3(64 * kShortWaves), 0, stream, h);
