@@ -146,6 +146,44 @@ __device__ double support_residual(const double* __restrict__ H, int r, int ns,
   return sqrt(res);
 }
 
+// Cheap test that comes before support_residual in the exhaustive search: the squared residual
+// of y against the columns A of H from the normal equations, ||y||^2 - b_A^T G_AA^-1 b_A with
+// G = H^T H and b = H^T y (both in LDS; a Cholesky factor of at most 8 x 8 in registers).  It only
+// ever rejects: a support is passed on to the exact computation whenever the estimate is within
+// lim2 (16 tau^2 plus a rounding allowance) or a pivot shows nearly dependent columns, where the
+// normal equations lose too many digits.  With pivots above 1e-6 of the largest diagonal entry the
+// estimate is off by at most about 1e-9 ||y||^2, far inside the margin for rho >= 1e-4 (the
+// caller skips the test below that), so the decisions are those of the exact computation alone.
+__device__ __forceinline__ bool may_explain(const double* Gs, const double* bs, int ns, const int* supp,
+                                            int size, double yy, double lim2) {
+  double L[S_MAX][S_MAX], inv[S_MAX], c[S_MAX];
+  double expl = 0.0, dmax = 0.0;
+  bool suspicious = false;
+#pragma unroll
+  for (int j = 0; j < S_MAX; ++j) {
+    if (j < size) {
+      const int sj = supp[j];
+      double d = Gs[sj * ns + sj], cj = bs[sj];
+      dmax = fmax(dmax, d);
+#pragma unroll
+      for (int l = 0; l < j; ++l) {
+        double v = Gs[sj * ns + supp[l]];
+#pragma unroll
+        for (int q = 0; q < l; ++q) v -= L[j][q] * L[l][q];
+        v *= inv[l];
+        L[j][l] = v;
+        d -= v * v;
+        cj -= v * c[l];
+      }
+      if (!(d > 1e-6 * dmax)) { suspicious = true; d = dmax > 0.0 ? dmax : 1.0; }
+      inv[j] = 1.0 / sqrt(d);
+      c[j] = cj * inv[j];
+      expl += c[j] * c[j];
+    }
+  }
+  return suspicious || yy - expl <= lim2;
+}
+
 __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
   __shared__ double zs[64];
   __shared__ double ys[R_MAX];
@@ -158,6 +196,7 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
   __shared__ double syn[R_MAX];
   __shared__ double xs[64];
   __shared__ int supp_s[A_MAX];
+  __shared__ double bs[64];
 
   const int lane = threadIdx.x;
   const int ns = p.t.nin, r = p.t.r, nout = p.t.nout;
@@ -165,6 +204,22 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
   uint32_t n_list = p.counters[0];
   if (n_list > (uint32_t)p.cap) n_list = (uint32_t)p.cap;
   if (blockIdx.x >= n_list) return;                        // nothing screened for this wavefront
+
+  // H (r x ns) and G = H^T H (ns x ns) in LDS (dynamic, sized by the host), once per workgroup
+  extern __shared__ double hg_lds[];
+  double* Hs = hg_lds;
+  double* Gs = hg_lds + r * ns;
+  for (int idx = lane; idx < r * ns; idx += 64) Hs[idx] = p.t.H64[idx];
+  __syncthreads();
+  if (lane < ns) {
+    for (int t = 0; t < ns; ++t) {
+      double g = 0.0;
+      for (int i = 0; i < r; ++i) g += Hs[i * ns + lane] * Hs[i * ns + t];
+      Gs[lane * ns + t] = g;
+    }
+  }
+  __syncthreads();
+  const bool use_filter = p.rho >= 1e-4;
 
   // Pascal's triangle for the unranking of supports: row a is built by lane b from row a - 1
   if (lane <= S_MAX) binom[0][lane] = lane == 0 ? 1ull : 0ull;
@@ -192,7 +247,7 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
     __syncthreads();
     double y = 0.0;
     if (lane < r) {
-      const double* __restrict__ hrow = p.t.H64 + (int64_t)lane * ns;
+      const double* hrow = Hs + lane * ns;
       for (int s = 0; s < ns; ++s) y += hrow[s] * zs[s];
     }
     if (lane < R_MAX) ys[lane] = y;
@@ -202,6 +257,15 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
     __syncthreads();
     if (nforced == 0 && sigma <= tau) continue;            // clean (wave-uniform)
     if (lane == 0) atomicAdd(&p.counters[2], 1u);
+    // b = H^T y and the limit of the search's first test (see may_explain)
+    {
+      double b = 0.0;
+      if (lane < ns)
+        for (int i = 0; i < r; ++i) b += Hs[i * ns + lane] * ys[i];
+      bs[lane] = b;
+    }
+    const double yy = sigma * sigma, lim2 = 16.0 * tau * tau + 9.1e-13 * yy;
+    __syncthreads();
 
     // ---- step 2: free / forced node lists (positions inside the present set)
     if (lane == 0) {
@@ -300,7 +364,7 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
                 if ((wall >> q) & 1ull) supp_s[n++] = q;
             }
             __syncthreads();
-            for (int j = 0; j < wsize; ++j) lsq_q[j][lane] = lane < r ? p.t.H64[(int64_t)lane * ns + supp_s[j]] : 0.0;
+            for (int j = 0; j < wsize; ++j) lsq_q[j][lane] = lane < r ? Hs[lane * ns + supp_s[j]] : 0.0;
             wave_lsq(lsq_q, lsq_r, lsq_c, wsize, lane < r ? ys[lane] : 0.0, lane);
             // lane j < wsize speaks for node supp_s[j]
             const int my_node = lane < wsize ? supp_s[lane] : 64;
@@ -328,7 +392,7 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
               if ((all >> q) & 1ull) supp_s[n++] = q;
           }
           __syncthreads();
-          for (int j = 0; j < csize; ++j) lsq_q[j][lane] = lane < r ? p.t.H64[(int64_t)lane * ns + supp_s[j]] : 0.0;
+          for (int j = 0; j < csize; ++j) lsq_q[j][lane] = lane < r ? Hs[lane * ns + supp_s[j]] : 0.0;
           __syncthreads();
           const double res = wave_lsq(lsq_q, lsq_r, lsq_c, csize, lane < r ? ys[lane] : 0.0, lane);
           if (res <= tau) { found = true; best_size = csize; }
@@ -357,7 +421,8 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
             supp[nforced + i] = freelist[x];
             ++x;
           }
-          const double res = support_residual(p.t.H64, r, ns, ys, supp, size, nullptr);
+          if (use_filter && !may_explain(Gs, bs, ns, supp, size, yy, lim2)) continue;
+          const double res = support_residual(Hs, r, ns, ys, supp, size, nullptr);
           if (res <= tau && res < my_res) { my_res = res; my_c = c; }
         }
         // wave-wide arg-min (smallest residual, then smallest index)
@@ -407,10 +472,10 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
     __syncthreads();
     double y2 = 0.0;
     if (lane < r) {
-      const double* __restrict__ hrow = p.t.H64 + (int64_t)lane * ns;
+      const double* hrow = Hs + lane * ns;
       for (int s = 0; s < ns; ++s) y2 += hrow[s] * zs[s];
     }
-    for (int j = 0; j < best_size; ++j) lsq_q[j][lane] = lane < r ? p.t.H64[(int64_t)lane * ns + supp_s[j]] : 0.0;
+    for (int j = 0; j < best_size; ++j) lsq_q[j][lane] = lane < r ? Hs[lane * ns + supp_s[j]] : 0.0;
     __syncthreads();
     wave_lsq(lsq_q, lsq_r, lsq_c, best_size, y2, lane);
     if (lane < best_size) zs[supp_s[lane]] = -lsq_c[lane];
@@ -468,7 +533,15 @@ gpd_status_t launch_locate(hipStream_t stream, const LocateArgs& a) {
   p.located = a.located; p.located_cap = a.located_cap; p.node_err = a.node_err;
   // every wavefront strides over the screened list and leaves when it runs out
   const int blocks = a.n_list < 2048 ? (a.n_list > 0 ? a.n_list : 1) : 2048;
-  hipLaunchKernelGGL(locate_kernel, dim3(blocks), dim3(64), 0, stream, p);
+  const size_t lds = (size_t)(a.t.r * a.t.nin + a.t.nin * a.t.nin) * sizeof(double);
+  // (static + dynamic LDS can pass 64 KB for codes of 64 nodes: the limit is raised once)
+  static bool raised = false;
+  if (!raised) {
+    GPD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(locate_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 2 * R_MAX * 64 * (int)sizeof(double)));
+    raised = true;
+  }
+  hipLaunchKernelGGL(locate_kernel, dim3(blocks), dim3(64), lds, stream, p);
   GPD_HIP(hipGetLastError());
   return GPD_OK;
 }
