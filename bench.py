@@ -190,6 +190,28 @@ def bench_faults(args, cfg):
                                                  correct_errors=G.GPD_CORRECT_ELEMENTS, workspace=ws, C_out=C,
                                                  want_report=False), flip, flip)
 
+    # (1b) many codewords to correct: 10 000 element codewords with three erroneous nodes each
+    n_many, t_many = 10000, 3
+    rngm = np.random.default_rng(77)
+    cw_many = rngm.choice(blk, n_many, replace=False)
+    pm_idx = torch.from_numpy(np.concatenate([rngm.choice(P, t_many, replace=False) for _ in range(n_many)])).to(dev)
+    em_idx = torch.from_numpy(np.repeat(cw_many, t_many)).to(dev)
+    vm = torch.from_numpy((rngm.choice([-1.0, 1.0], n_many * t_many) *
+                           rngm.uniform(50.0, 200.0, n_many * t_many)).astype(np.float32)).to(dev)
+    Ctm = Ct.clone()
+    Ctm.view(P, -1)[pm_idx, em_idx] += vm
+    many_rep = [None]
+
+    def many_elements(t):
+        _, many_rep[0] = G.gpd_decode(plan, Ctm, mode=G.GPD_DEC_LSQ_ALL, correct_errors=G.GPD_CORRECT_ELEMENTS,
+                                      workspace=ws, C_out=C, located_cap=16)
+
+    ms_many = timed(many_elements)
+    ms_many_async = timed(lambda t: G.gpd_decode(plan, Ctm, mode=G.GPD_DEC_LSQ_ALL,
+                                                 correct_errors=G.GPD_CORRECT_ELEMENTS, workspace=ws, C_out=C,
+                                                 want_report=False))
+    del Ctm
+
     # (2) whole-node errors: Gram pass + host search, then the decode without the bad nodes
     noise = torch.randn((rows, cols), generator=torch.Generator(device=dev).manual_seed(1), device=dev)
     bad_sets = [tuple(sorted(np.random.default_rng(9000 + t).choice(P, 1 + t % 3, replace=False).tolist()))
@@ -257,6 +279,10 @@ def bench_faults(args, cfg):
                                      "note": "with the host report (stream wait + copies)",
                                      "ms_without_report": ms_elem_async,
                                      "GBps_without_report": gb(4.0 * blk * (P + m * d), ms_elem_async)},
+           "decode_screen_correct_many": {"ms": ms_many, "ms_without_report": ms_many_async,
+                                          "codewords": n_many, "errors_per_codeword": t_many,
+                                          "located": int(many_rep[0].n_located), "failed": int(many_rep[0].n_failed),
+                                          "ns_per_codeword_without_report": ms_many_async * 1e6 / n_many},
            "locate_nodes": {"ms": ms_nodes, "GBps": gb(4.0 * blk * P, ms_nodes), "all_sets_found": ok[0],
                             "note": "Gram pass over 16 x 16 MiB + reduction + host search"},
            "decode_nodes": {"ms": ms_nodes_dec, "GBps": gb(4.0 * blk * (2 * P - 2 + m * d), ms_nodes_dec)},

@@ -437,13 +437,15 @@ gpd_status_t run_decode(hipStream_t stream, TableRing* ring, const DecodeJob& jo
     if (have > 0) {
       std::vector<gpd_located_t> tmp((size_t)have);
       GPD_HIP(hipMemcpy(tmp.data(), located, sizeof(gpd_located_t) * have, hipMemcpyDeviceToHost));
-      std::sort(tmp.begin(), tmp.end(), [](const gpd_located_t& a, const gpd_located_t& b) {
-        if (a.node != b.node) return a.node < b.node;
-        if (a.row != b.row) return a.row < b.row;
-        return a.col < b.col;
-      });
+      // the caller gets the first located_cap entries in (node, row, column) order: only those
+      // need to be put in order (a full sort of several 100 000 entries took longer than the kernels)
       if (report->located && report->located_cap > 0) {
         const int64_t n = std::min<int64_t>(have, report->located_cap);
+        std::partial_sort(tmp.begin(), tmp.begin() + n, tmp.end(), [](const gpd_located_t& a, const gpd_located_t& b) {
+          if (a.node != b.node) return a.node < b.node;
+          if (a.row != b.row) return a.row < b.row;
+          return a.col < b.col;
+        });
         std::memcpy(report->located, tmp.data(), sizeof(gpd_located_t) * n);
       }
     }
