@@ -107,13 +107,16 @@ namespace gpd {
 
 constexpr size_t kHeaderBytes = 512;        // counters[64] + node_err[64]
 
+static int64_t screen_words(int64_t n_codewords) { return (n_codewords + 63) / 64 + 8; }
+
 void decode_workspace_layout(int64_t n_codewords, int64_t* flag_cap, int64_t* loc_cap, size_t* bytes) {
   int64_t cap = std::min<int64_t>(n_codewords, 1 << 18);
   if (cap < 1) cap = 1;
-  *flag_cap = cap;
+  // one bit per codeword for the screen (plus the words a last, partly idle wavefront writes)
+  *flag_cap = screen_words(n_codewords);
   *loc_cap = cap * 8;
   size_t b = kHeaderBytes;
-  b += ((size_t)cap * 4 + 255) / 256 * 256;
+  b += ((size_t)(*flag_cap) * 8 + 255) / 256 * 256;
   b += (size_t)(*loc_cap) * sizeof(gpd_located_t);
   *bytes = (b + 255) / 256 * 256;
 }
@@ -388,17 +391,23 @@ gpd_status_t run_decode(hipStream_t stream, TableRing* ring, const DecodeJob& jo
   char* ws = (char*)workspace;
   uint32_t* counters = nullptr;
   int32_t* node_err = nullptr;
-  int32_t* list = nullptr;
+  unsigned long long* flag_bits = nullptr;
+  int64_t flag_words = 0;
   gpd_located_t* located = nullptr;
   if (corr) {
     counters = (uint32_t*)ws;
     node_err = (int32_t*)(ws + 256);
-    list = (int32_t*)(ws + kHeaderBytes);
-    located = (gpd_located_t*)(ws + kHeaderBytes + ((size_t)job.flag_cap * 4 + 255) / 256 * 256);
+    // (the map and the list of located entries are laid out for the largest block of the plan or
+    // layer; a smaller block uses the front of each)
+    flag_bits = (unsigned long long*)(ws + kHeaderBytes);
+    flag_words = screen_words(job.bh * job.bw);
+    if (flag_words > job.flag_cap)
+      return fail(GPD_E_WORKSPACE, "decode: the screen's bit map does not fit the workspace");
+    located = (gpd_located_t*)(ws + kHeaderBytes + ((size_t)job.flag_cap * 8 + 255) / 256 * 256);
     st = launch_zero_words(stream, ws, (int)(kHeaderBytes / 4));
     if (st != GPD_OK) return st;
     sc.enabled = true; sc.rho = (float)job.rho; sc.abs_floor = (float)job.abs_floor;
-    sc.counters = counters; sc.list = list; sc.cap = (int32_t)job.flag_cap;
+    sc.counters = counters; sc.flag_bits = flag_bits; sc.flag_words = flag_words;
   }
   if (corr && job.epi.kind != 0) return fail(GPD_E_INVALID, "decode: element-wise step with element correction");
   st = launch_combine(stream, t, Zt, job.bw, out, ld_out, false, job.bh, job.bw, sc, 0, job.epi);
@@ -407,7 +416,7 @@ gpd_status_t run_decode(hipStream_t stream, TableRing* ring, const DecodeJob& jo
     LocateArgs la;
     la.t = t; la.in = Zt; la.in_ld = job.bw; la.out = out; la.out_ld = ld_out;
     la.rows = job.bh; la.cols = job.bw; la.rho = job.rho; la.abs_floor = job.abs_floor;
-    la.counters = counters; la.list = list; la.n_list = (int32_t)job.flag_cap;
+    la.counters = counters; la.flag_bits = flag_bits;
     la.located = located; la.located_cap = job.loc_cap; la.node_err = node_err;
     st = launch_locate(stream, la);
     if (st != GPD_OK) return st;
@@ -428,11 +437,6 @@ gpd_status_t run_decode(hipStream_t stream, TableRing* ring, const DecodeJob& jo
     std::memcpy(&ratio, &hc[1], 4);
     report->max_syndrome_ratio = ratio;
     for (int p = 0; p < GPD_MAX_P; ++p) report->node_err_count[p] = hn[p];
-    if ((int64_t)hc[0] > job.flag_cap) {
-      report->status = GPD_E_WORKSPACE;
-      return fail(GPD_E_WORKSPACE, "decode: %u codewords screened, list holds %lld", hc[0],
-                  (long long)job.flag_cap);
-    }
     const int64_t have = std::min<int64_t>(hc[4], job.loc_cap);
     if (have > 0) {
       std::vector<gpd_located_t> tmp((size_t)have);

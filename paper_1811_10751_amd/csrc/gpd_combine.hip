@@ -157,8 +157,8 @@ struct CombineParams {
   float abs_floor;
   float rho;                 // for the ratio statistic
   uint32_t* counters;
-  int32_t* list;
-  int32_t cap;
+  unsigned long long* flag_bits;   // the screen's bit map (bit = codeword index row * cols + col)
+  int64_t flag_words;
   // Tables as kernel arguments (scalar loads, independent of the vector memory counter: a
   // table entry read from memory between two stores of the output loop would have to wait for
   // the first store to complete).  The block offsets always; coef and H when karg is set (they
@@ -188,6 +188,24 @@ static_assert(sizeof(CombineParams) <= 4096, "kernel arguments are limited to 4 
 // 3 two fp16 planes (hi, lo) of the value divided by a power of two, k-blocked in the same way
 // TAB: the coefficient tables come through LDS (too large for the kernel arguments); else they
 // are kernel arguments.  Two kernels, so that neither carries the other's code and registers.
+// The low 64 / VEC bits of x moved to every VEC-th bit position (bit j to bit j * VEC).
+template <int VEC>
+__device__ __forceinline__ unsigned long long spread_bits(unsigned long long x) {
+  if constexpr (VEC == 4) {
+    x = (x | (x << 24)) & 0x000000ff000000ffull;
+    x = (x | (x << 12)) & 0x000f000f000f000full;
+    x = (x | (x << 6)) & 0x0303030303030303ull;
+    x = (x | (x << 3)) & 0x1111111111111111ull;
+  } else if constexpr (VEC == 2) {
+    x = (x | (x << 16)) & 0x0000ffff0000ffffull;
+    x = (x | (x << 8)) & 0x00ff00ff00ff00ffull;
+    x = (x | (x << 4)) & 0x0f0f0f0f0f0f0f0full;
+    x = (x | (x << 2)) & 0x3333333333333333ull;
+    x = (x | (x << 1)) & 0x5555555555555555ull;
+  }
+  return x;
+}
+
 template <int NIN_MAX, int VEC, int OUT, bool SCREEN, bool LIMITS, bool TAB>
 __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -316,7 +334,14 @@ __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
       }
     };
     syndromes(std::integral_constant<bool, karg>{});
+    // The codewords passed on are marked in a bit map, bit row * cols + col of 64-bit words: a
+    // wavefront covers 64 * VEC consecutive codewords, lane l the VEC codewords from l * VEC on, and
+    // writes the VEC words of its own (all of them, also when no bit is set: nothing has to be
+    // cleared beforehand, nothing is counted and no wavefront waits for another's atomic).
     float ratio = 0.f;
+    unsigned long long words[VEC];
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) words[k] = 0ull;
 #pragma unroll
     for (int v = 0; v < VEC; ++v) {
       const float nz = sqrtf(nz2[v]);
@@ -324,13 +349,18 @@ __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
       const float base = fmaxf(nz, p.abs_floor);
       const float thr = fmaxf(p.rho_screen * base - 1.52587890625e-05f * nz, 0.f);
       const bool flag = active && (bad[v] || !(sig <= thr));
-      if (flag) {
-        const uint32_t pos = atomicAdd(&p.counters[0], 1u);
-        if (pos < (uint32_t)p.cap) p.list[pos] = (int32_t)(row * p.cols + col + v);
-      } else if (active) {
+      if (!flag && active) {
         const float tau = p.rho * base;
         if (tau > 0.f) ratio = fmaxf(ratio, sig / tau);
       }
+      const unsigned long long b = __ballot(flag);       // bit l: lane l, component v
+#pragma unroll
+      for (int k = 0; k < VEC; ++k)
+        words[k] |= spread_bits<VEC>((b >> (k * (64 / VEC))) & (~0ull >> (64 - 64 / VEC))) << v;
+    }
+    if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) p.flag_bits[(int64_t)blockIdx.x * VEC + k] = words[k];
     }
     // wave-wide maximum, one atomic per wave
 #pragma unroll
@@ -412,6 +442,9 @@ gpd_status_t launch_t(hipStream_t stream, const CombineParams& p, int out_kind, 
   // the rest of a larger workgroup (decode launches measured 6-9 % faster than with 256 threads)
   const int64_t blocks = (total + 63) / 64;
   if (blocks > 0x7fffffffLL) return fail(GPD_E_SHAPE, "block too large for one launch");
+  if (screen && blocks * VEC > p.flag_words)
+    return fail(GPD_E_WORKSPACE, "combine: the screen's bit map needs %lld words, %lld given",
+                (long long)(blocks * VEC), (long long)p.flag_words);
   dim3 grid((unsigned)blocks, (unsigned)((p.nout + p.q_chunk - 1) / p.q_chunk)), block(64);
   const bool lim = p.in_rows != nullptr;
   // tables that do not travel as kernel arguments are staged in LDS: q_chunk coefficient rows and,
@@ -487,7 +520,7 @@ gpd_status_t launch_combine(hipStream_t stream, const CombineTable& t, const flo
   p.in_off = t.in_off; p.out_off = t.out_off; p.coef = t.coef; p.H = t.H;
   p.in_rows = t.in_rows; p.in_cols = t.in_cols; p.out_rows = t.out_rows; p.out_cols = t.out_cols;
   p.rho = screen.rho; p.rho_screen = 0.5f * screen.rho; p.abs_floor = screen.abs_floor;
-  p.counters = screen.counters; p.list = screen.list; p.cap = screen.cap;
+  p.counters = screen.counters; p.flag_bits = screen.flag_bits; p.flag_words = screen.flag_words;
   if (!t.k_offsets) return fail(GPD_E_UNSUPPORTED, "combine: more than 64 inputs or outputs");
   std::memcpy(p.in_off_k, t.k_in_off, sizeof(p.in_off_k));
   std::memcpy(p.out_off_k, t.k_out_off, sizeof(p.out_off_k));

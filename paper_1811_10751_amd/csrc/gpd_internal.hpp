@@ -161,9 +161,11 @@ inline void key_add_bytes(std::string* k, const void* p, size_t n) { k->append((
 struct ScreenArgs {               // soft-error screen fused into the decode pass
   bool enabled = false;
   float rho = 0.f, abs_floor = 0.f;
-  uint32_t* counters = nullptr;   // [0] number of screened codewords, [1] max ratio bits
-  int32_t* list = nullptr;        // codeword indices row*cols+col
-  int32_t cap = 0;
+  uint32_t* counters = nullptr;   // [1] max ratio bits
+  // bit map of the codewords passed on, bit row*cols+col of 64-bit words; the kernel writes every
+  // word that covers a codeword (and up to 3 words after the last of them)
+  unsigned long long* flag_bits = nullptr;
+  int64_t flag_words = 0;         // words the map can hold
 };
 
 // Element-wise step applied to an fp32 output of launch_combine before it is stored (the
@@ -228,7 +230,7 @@ struct LocateArgs {
   int64_t rows = 0, cols = 0;
   double rho = 0, abs_floor = 0;
   uint32_t* counters = nullptr;   // see gpd_decode.hip for the layout
-  const int32_t* list = nullptr; int32_t n_list = 0;
+  const unsigned long long* flag_bits = nullptr;   // the screen's bit map (see ScreenArgs)
   gpd_located_t* located = nullptr; int64_t located_cap = 0;
   int32_t* node_err = nullptr;    // [GPD_MAX_P]
 };
@@ -251,7 +253,7 @@ struct DecodeJob {
   int grid_r = 0, grid_c = 0;
   int64_t bh = 0, bw = 0;
   double rho = 0, abs_floor = 0;
-  int64_t flag_cap = 0, loc_cap = 0;
+  int64_t flag_cap = 0, loc_cap = 0;   // words of the screen's bit map, entries of the located list
   size_t workspace_bytes = 0;
   std::vector<int32_t> out_rows, out_cols;     // limits of the output blocks (empty = none)
   Epilogue epi;                                // applied to the decoded values (decodes without

@@ -7,9 +7,11 @@
 //            and every entry is finite (this fp64 test is the decision; the fp32 screen only
 //            preselects).
 //   step 2   supports of increasing size (always containing the non-finite entries, which
-//            are set to zero first); inside one size the lanes share out the supports, each
-//            computes the least-squares residual of y against the support's columns of H by
-//            modified Gram-Schmidt, and the smallest residual <= tau wins (ties: the first
+//            are set to zero first); inside one size the lanes share out the supports, 64 at a
+//            time; a lane first puts its support through a register-only test on the normal
+//            equations that can only reject, the wavefront then computes together, for each
+//            support left, the least-squares residual of y against the support's columns of H
+//            by modified Gram-Schmidt, and the smallest residual <= tau wins (ties: the first
 //            support in lexicographic order).
 //   step 3   supports larger than |S| - K - 1 are never tried: decoding failure.
 // The exhaustive search is exponential in the support size (Algorithm 1's problem is NP-hard in
@@ -24,7 +26,10 @@
 // Correction: e_hat solves H_A e = y in the least-squares sense; the outputs are the rows of
 // the all-node least-squares decoding matrix applied to z - e_hat, which equals least squares
 // over the nodes outside the support.
-// Latency-bound plain-ALU work on a handful of codewords; not on the bandwidth path.
+// The screen marks its codewords in a bit map (one bit per codeword, written by the decode pass
+// without any atomic); the workgroups here share out the map in chunks of 4096 codewords and, inside
+// a chunk, the marked codewords in turn, so that a burst of errors is not one workgroup's work.
+// Latency-bound plain-ALU work; not on the bandwidth path.
 #include "gpd_internal.hpp"
 
 namespace gpd {
@@ -35,6 +40,10 @@ constexpr int S_MAX = 8;                       // largest support size searched 
 constexpr int A_MAX = 24;                      // largest support the algebraic locator may return
 constexpr int R_MAX = 64;                      // largest number of parity rows
 constexpr unsigned long long kFirstBudget = 1ull << 12;   // supports per size before the algebraic locator is tried
+// workgroups of one launch: four per compute unit are resident at once with this kernel's LDS, and the
+// set-up of a workgroup (tables into LDS) is shared by the codewords it takes
+constexpr int kLocateGrid = 1024;
+constexpr int kKeptChunks = 16;                // chunks of the screen's bit map a workgroup keeps in LDS
 constexpr unsigned long long kBudget = 1ull << 22;        // supports tried per size, at most
 
 struct LocateParams {
@@ -43,8 +52,10 @@ struct LocateParams {
   float* out; int64_t out_ld;
   int64_t cols;
   double rho, abs_floor;
-  uint32_t* counters;         // [0] screened, [2] flagged, [3] failed, [4] located
-  const int32_t* list; int32_t cap;
+  uint32_t* counters;         // [0] screened (counted here), [2] flagged, [3] failed, [4] located
+  const unsigned long long* flag_bits;   // the screen's bit map, n_words words
+  int64_t n_words, n_codewords;
+  int share, chunks_per_team; // workgroups of a team, chunks of the map a team takes
   gpd_located_t* located; int64_t located_cap;
   int32_t* node_err;
 };
@@ -103,50 +114,7 @@ __device__ double wave_lsq(double (*Q)[64], double (*R)[A_MAX], double* coef, in
   return res;
 }
 
-// Residual of y against the columns `supp[0..size)` of H (r x ns, row-major) by modified
-// Gram-Schmidt; optionally returns the least-squares coefficients.
-__device__ double support_residual(const double* __restrict__ H, int r, int ns,
-                                   const double* __restrict__ y, const int* supp, int size,
-                                   double* e_out) {
-  double Q[S_MAX][R_MAX];
-  double R[S_MAX][S_MAX];
-  double qty[S_MAX];
-  for (int j = 0; j < size; ++j) {
-    for (int i = 0; i < r; ++i) Q[j][i] = H[(int64_t)i * ns + supp[j]];
-    for (int l = 0; l < j; ++l) {
-      double dot = 0.0;
-      for (int i = 0; i < r; ++i) dot += Q[l][i] * Q[j][i];
-      R[l][j] = dot;
-      for (int i = 0; i < r; ++i) Q[j][i] -= dot * Q[l][i];
-    }
-    double nrm = 0.0;
-    for (int i = 0; i < r; ++i) nrm += Q[j][i] * Q[j][i];
-    nrm = sqrt(nrm);
-    R[j][j] = nrm;
-    const double inv = nrm > 0.0 ? 1.0 / nrm : 0.0;
-    for (int i = 0; i < r; ++i) Q[j][i] *= inv;
-  }
-  double w[R_MAX];
-  for (int i = 0; i < r; ++i) w[i] = y[i];
-  for (int j = 0; j < size; ++j) {
-    double dot = 0.0;
-    for (int i = 0; i < r; ++i) dot += Q[j][i] * w[i];
-    qty[j] = dot;
-    for (int i = 0; i < r; ++i) w[i] -= dot * Q[j][i];
-  }
-  double res = 0.0;
-  for (int i = 0; i < r; ++i) res += w[i] * w[i];
-  if (e_out) {
-    for (int j = size - 1; j >= 0; --j) {
-      double acc = qty[j];
-      for (int l = j + 1; l < size; ++l) acc -= R[j][l] * e_out[l];
-      e_out[j] = R[j][j] > 0.0 ? acc / R[j][j] : 0.0;
-    }
-  }
-  return sqrt(res);
-}
-
-// Cheap test that comes before support_residual in the exhaustive search: the squared residual
+// Cheap test that comes before the exact residual in the exhaustive search: the squared residual
 // of y against the columns A of H from the normal equations, ||y||^2 - b_A^T G_AA^-1 b_A with
 // G = H^T H and b = H^T y (both in LDS; a Cholesky factor of at most 8 x 8 in registers).  It only
 // ever rejects: a support is passed on to the exact computation whenever the estimate is within
@@ -197,47 +165,159 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
   __shared__ double xs[64];
   __shared__ int supp_s[A_MAX];
   __shared__ double bs[64];
+  __shared__ int cand_supp[64][S_MAX];
+  __shared__ int node_err_s[64];
+  __shared__ int node_s[64];                               // worker node of each present response
+  __shared__ gpd_located_t rec_s[64];                      // located entries not yet handed over
+  __shared__ unsigned long long words_s[kKeptChunks][64];  // the team's first chunks of the screen's map
 
   const int lane = threadIdx.x;
   const int ns = p.t.nin, r = p.t.r, nout = p.t.nout;
 
-  uint32_t n_list = p.counters[0];
-  if (n_list > (uint32_t)p.cap) n_list = (uint32_t)p.cap;
-  if (blockIdx.x >= n_list) return;                        // nothing screened for this wavefront
+  // The screen's bit map is dealt out in chunks of 64 words (one word per lane, 4096 codewords).
+  // The workgroups form n_teams teams of `share` workgroups; a team takes chunks_per_team
+  // consecutive chunks, and of the marked codewords in them, counted from the first, member `sub`
+  // takes those whose count is sub modulo share: marked codewords that lie close together (a burst,
+  // a whole block) are spread over a team's workgroups all the same, and a small map is one team's,
+  // shared out evenly.  A workgroup with no codeword to take leaves at once.
+  const int team = blockIdx.x / p.share, sub = blockIdx.x - team * p.share;
+  const int64_t n_chunks = (p.n_words + 63) / 64;
+  const int64_t chunk_first = (int64_t)team * p.chunks_per_team;
+  const int64_t chunk_end = chunk_first + p.chunks_per_team < n_chunks ? chunk_first + p.chunks_per_team : n_chunks;
+  auto chunk_word = [&](int64_t chunk) {
+    const int64_t j = chunk * 64 + lane;
+    const unsigned long long v = p.flag_bits[j < p.n_words ? j : p.n_words - 1];
+    return j < p.n_words ? v : 0ull;
+  };
+  {
+    // the team's first kKeptChunks chunks are requested together and kept in LDS for the pass below
+    // (a chunk beyond the team's last reads a valid word and counts as empty)
+    unsigned long long w[kKeptChunks];
+#pragma unroll
+    for (int k = 0; k < kKeptChunks; ++k) w[k] = chunk_word(chunk_first + k);
+    uint32_t marked = 0;
+#pragma unroll
+    for (int k = 0; k < kKeptChunks; ++k) {
+      if (chunk_first + k >= chunk_end) w[k] = 0ull;
+      words_s[k][lane] = w[k];
+      marked += (uint32_t)__popcll(w[k]);
+    }
+    for (int64_t chunk = chunk_first + kKeptChunks; chunk < chunk_end; ++chunk) marked += (uint32_t)__popcll(chunk_word(chunk));
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) marked += __shfl_xor(marked, off);
+    if (marked <= (uint32_t)sub) return;                   // (uniform)
+  }
 
-  // H (r x ns) and G = H^T H (ns x ns) in LDS (dynamic, sized by the host), once per workgroup
+  // H (r x ns), G = H^T H (ns x ns) and the decoding rows in LDS (dynamic, sized by the host), once
+  // per workgroup
   extern __shared__ double hg_lds[];
   double* Hs = hg_lds;
   double* Gs = hg_lds + r * ns;
+  double* Ds = Gs + ns * ns;                              // decoding rows [nout][ns]
+  for (int idx = lane; idx < nout * ns; idx += 64) Ds[idx] = p.t.coef64[idx];
   for (int idx = lane; idx < r * ns; idx += 64) Hs[idx] = p.t.H64[idx];
   __syncthreads();
-  if (lane < ns) {
-    for (int t = 0; t < ns; ++t) {
-      double g = 0.0;
-      for (int i = 0; i < r; ++i) g += Hs[i * ns + lane] * Hs[i * ns + t];
-      Gs[lane * ns + t] = g;
-    }
+  for (int idx = lane; idx < ns * ns; idx += 64) {
+    const int a = idx / ns, b = idx - a * ns;
+    double g = 0.0;
+    for (int i = 0; i < r; ++i) g += Hs[i * ns + a] * Hs[i * ns + b];
+    Gs[idx] = g;
   }
-  __syncthreads();
   const bool use_filter = p.rho >= 1e-4;
 
-  // Pascal's triangle for the unranking of supports: row a is built by lane b from row a - 1
-  if (lane <= S_MAX) binom[0][lane] = lane == 0 ? 1ull : 0ull;
-  __syncthreads();
-  for (int a = 1; a <= 64; ++a) {
-    if (lane <= S_MAX) binom[a][lane] = lane == 0 ? 1ull : binom[a - 1][lane - 1] + binom[a - 1][lane];
-    __syncthreads();
+  // Binomial coefficients for the unranking of supports, C(a, b) for a <= 64, b <= S_MAX: lane a
+  // builds row a by C(a, b) = C(a, b - 1) (a - b + 1) / b.  Every product stays below 2^53 and every
+  // quotient is an integer, so the fp64 arithmetic is exact (and rounded to the integer in any case).
+  for (int a = lane; a <= 64; a += 64) {
+    double c = 1.0;
+    binom[a][0] = 1ull;
+    for (int b = 1; b <= S_MAX; ++b) {
+      c = b <= a ? rint(c * (double)(a - b + 1) / (double)b) : 0.0;
+      binom[a][b] = (unsigned long long)c;
+    }
   }
 
-  for (uint32_t w = blockIdx.x; w < n_list; w += gridDim.x) {
-    const int32_t cw = p.list[w];
-    const int64_t row = cw / p.cols, col = cw % p.cols;
+  // Counts are kept per workgroup and added to the global ones once at the end, and located entries
+  // are collected in LDS and handed over 64 at a time: with thousands of screened codewords the
+  // global counters are a handful of addresses that every wavefront would otherwise hit with an
+  // atomic per codeword.
+  node_err_s[lane] = 0;
+  uint32_t n_flag_local = 0, n_fail_local = 0;
+  int n_rec = 0;                                           // entries waiting in rec_s (wave-uniform)
+  auto flush_records = [&]() {
+    uint32_t base = 0;
+    if (lane == 0) base = atomicAdd(&p.counters[4], (uint32_t)n_rec);
+    base = __shfl(base, 0);
+    if (lane < n_rec && (int64_t)base + lane < p.located_cap) p.located[base + lane] = rec_s[lane];
+    n_rec = 0;
+    __syncthreads();
+  };
+  __syncthreads();
+  // What a lane needs of the tables is read once, and the responses are read one codeword ahead, so
+  // that no load waits in front of the arithmetic (the responses of one codeword lie in as many
+  // different pages as there are nodes).
+  const int32_t cols32 = (int32_t)p.cols;
+  const int64_t my_in_off = p.t.in_off[lane < ns ? lane : 0];
+  const int64_t my_out_off = p.t.out_off[lane < nout ? lane : 0];
+  int32_t my_out_rows = 0x7fffffff, my_out_cols = 0x7fffffff;
+  if (p.t.out_rows) { my_out_rows = p.t.out_rows[lane < nout ? lane : 0]; my_out_cols = p.t.out_cols[lane < nout ? lane : 0]; }
+  node_s[lane] = p.t.node[lane < ns ? lane : 0];
+  auto response_of = [&](int32_t cw_) {
+    const int32_t row_ = cw_ / cols32, col_ = cw_ - row_ * cols32;
+    return p.in[my_in_off + (int64_t)row_ * p.in_ld + col_];
+  };
+  const int32_t cw_last = (int32_t)(p.n_codewords - 1);
+  uint32_t n_screened_local = 0;
+  __syncthreads();
+  uint32_t count_base = 0;                                 // marked codewords in the team's earlier chunks
+  for (int64_t chunk = chunk_first; chunk < chunk_end; ++chunk) {
+  unsigned long long word = chunk - chunk_first < kKeptChunks ? words_s[chunk - chunk_first][lane] : chunk_word(chunk);
+  {
+    // this member's share of the chunk: the bits whose count within the team is sub modulo share
+    const uint32_t cnt = (uint32_t)__popcll(word);
+    if (sub == 0) n_screened_local += cnt;
+    uint32_t incl = cnt;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t o = __shfl_up(incl, off);
+      if (lane >= off) incl += o;
+    }
+    uint32_t count = count_base + incl - cnt;              // marked codewords before this lane's word
+    count_base += __shfl(incl, 63);
+    unsigned long long rest = word, keep = 0ull;
+    while (rest) {
+      const unsigned long long low = rest & (0ull - rest);
+      if (count % (uint32_t)p.share == (uint32_t)sub) keep |= low;
+      rest ^= low;
+      ++count;
+    }
+    word = keep;
+  }
+  // the next codeword of this member (lowest word first, lowest bit first), -1 when none is left
+  auto pop = [&]() -> int32_t {
+    const unsigned long long m = __ballot(word != 0ull);
+    if (m == 0ull) return -1;
+    const int l = __ffsll((long long)m) - 1;
+    const unsigned long long wl = __shfl(word, l);
+    const int bit = __ffsll((long long)wl) - 1;
+    if (lane == l) word &= word - 1ull;
+    const int64_t c = (chunk * 64 + l) * 64 + bit;
+    return c <= cw_last ? (int32_t)c : -1;                 // (no bit is ever set beyond the last codeword)
+  };
+  int32_t cw_cur = pop();
+  float zf_cur = response_of(cw_cur < 0 ? 0 : cw_cur);
+  while (cw_cur >= 0) {
+    const int32_t cw = cw_cur;
+    const float zf_here = zf_cur;
+    cw_cur = pop();
+    zf_cur = response_of(cw_cur < 0 ? 0 : cw_cur);         // (the next codeword's responses, ahead of use)
+    const int32_t row = cw / cols32, col = cw - row * cols32;
 
     // ---- step 1 in fp64
     double z = 0.0;
     bool bad = false;
     if (lane < ns) {
-      const float zf = p.in[p.t.in_off[lane] + row * p.in_ld + col];
+      const float zf = zf_here;
       bad = !(fabsf(zf) <= 3.4028234664e38f);
       z = bad ? 0.0 : (double)zf;
     }
@@ -256,7 +336,7 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
     const double tau = p.rho * fmax(znorm, p.abs_floor);
     __syncthreads();
     if (nforced == 0 && sigma <= tau) continue;            // clean (wave-uniform)
-    if (lane == 0) atomicAdd(&p.counters[2], 1u);
+    ++n_flag_local;
     // b = H^T y and the limit of the search's first test (see may_explain)
     {
       double b = 0.0;
@@ -280,7 +360,6 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
 
     bool found = false;
     int best_size = 0;
-    int supp[S_MAX];
     int size = nforced > 1 ? nforced : 1;
     for (int phase = 0; phase < 3 && !found; ++phase) {
       if (phase == 1) {
@@ -407,23 +486,40 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
         if (total > budget) break;
         double my_res = 1.0e300;
         unsigned long long my_c = ~0ull;
-        for (unsigned long long c = lane; c < total; c += 64) {
-          // unrank c among the tpick-subsets of the free nodes, lexicographic order
-          for (int f = 0; f < nforced; ++f) supp[f] = forcedlist[f];
-          unsigned long long rest = c;
-          int x = 0;
-          for (int i = 0; i < tpick; ++i) {
-            for (;; ++x) {
-              const unsigned long long cnt = binom[nfree - x - 1][tpick - i - 1];
-              if (rest < cnt) break;
-              rest -= cnt;
+        for (unsigned long long base = 0; base < total; base += 64) {
+          const unsigned long long c = base + lane;
+          bool cand = c < total;
+          int* supp = cand_supp[lane];                     // this lane's support (LDS)
+          if (cand) {
+            // unrank c among the tpick-subsets of the free nodes, lexicographic order
+            for (int f = 0; f < nforced; ++f) supp[f] = forcedlist[f];
+            unsigned long long rest = c;
+            int x = 0;
+            for (int i = 0; i < tpick; ++i) {
+              for (;; ++x) {
+                const unsigned long long cnt = binom[nfree - x - 1][tpick - i - 1];
+                if (rest < cnt) break;
+                rest -= cnt;
+              }
+              supp[nforced + i] = freelist[x];
+              ++x;
             }
-            supp[nforced + i] = freelist[x];
-            ++x;
+            if (use_filter) cand = may_explain(Gs, bs, ns, supp, size, yy, lim2);
           }
-          if (use_filter && !may_explain(Gs, bs, ns, supp, size, yy, lim2)) continue;
-          const double res = support_residual(Hs, r, ns, ys, supp, size, nullptr);
-          if (res <= tau && res < my_res) { my_res = res; my_c = c; }
+          unsigned long long todo = __ballot(cand);
+          __syncthreads();
+          // what is left (after the first test: the support that explains y and few others) is
+          // decided by the exact residual, one support at a time on the whole wavefront: rows
+          // over lanes, modified Gram-Schmidt by wavefront reductions (no per-lane arrays, so
+          // the kernel needs no scratch memory)
+          while (todo) {
+            const int src = __ffsll((long long)todo) - 1;
+            todo &= todo - 1ull;
+            for (int j = 0; j < size; ++j) lsq_q[j][lane] = lane < r ? Hs[lane * ns + cand_supp[src][j]] : 0.0;
+            __syncthreads();
+            const double res = wave_lsq(lsq_q, lsq_r, lsq_c, size, lane < r ? ys[lane] : 0.0, lane);
+            if (lane == src && res <= tau && res < my_res) { my_res = res; my_c = c; }
+          }
         }
         // wave-wide arg-min (smallest residual, then smallest index)
 #pragma unroll
@@ -457,7 +553,7 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
     }
 
     if (!found) {
-      if (lane == 0) atomicAdd(&p.counters[3], 1u);
+      ++n_fail_local;
       __syncthreads();
       continue;
     }
@@ -483,29 +579,36 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
     // estimated error value = received - predicted
     const double e_hat = lane < best_size ? z_orig + lsq_c[lane] : 0.0;
     bool write = lane < nout;
-    if (write && p.t.out_rows) write = row < p.t.out_rows[lane] && col < p.t.out_cols[lane];
+    if (write) write = row < my_out_rows && col < my_out_cols;
     if (write) {
-      const double* __restrict__ drow = p.t.coef64 + (int64_t)lane * ns;
+      const double* drow = Ds + lane * ns;
       double acc = 0.0;
       for (int s = 0; s < ns; ++s) acc += drow[s] * zs[s];
-      p.out[p.t.out_off[lane] + row * p.out_ld + col] = (float)acc;
+      p.out[my_out_off + (int64_t)row * p.out_ld + col] = (float)acc;
     }
-    uint32_t base = 0;
-    if (lane == 0) base = atomicAdd(&p.counters[4], (uint32_t)best_size);
-    base = __shfl(base, 0);
+    if (n_rec + best_size > 64) flush_records();
     if (lane < best_size) {
       const int s = supp_s[lane];
-      const int node = p.t.node[s];
-      atomicAdd(&p.node_err[node], 1);
-      if ((int64_t)base + lane < p.located_cap) {
-        gpd_located_t rec;
-        rec.node = node; rec.row = (int32_t)row; rec.col = (int32_t)col;
-        rec.magnitude = ((forced_mask >> s) & 1ull) ? __uint_as_float(0x7fc00000u) : (float)e_hat;
-        p.located[base + lane] = rec;
-      }
+      const int node = node_s[s];
+      atomicAdd(&node_err_s[node], 1);
+      gpd_located_t rec;
+      rec.node = node; rec.row = (int32_t)row; rec.col = (int32_t)col;
+      rec.magnitude = ((forced_mask >> s) & 1ull) ? __uint_as_float(0x7fc00000u) : (float)e_hat;
+      rec_s[n_rec + lane] = rec;
     }
+    n_rec += best_size;
     __syncthreads();
   }
+  }
+  if (n_rec > 0) flush_records();
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) n_screened_local += __shfl_xor(n_screened_local, off);
+  if (lane == 0) {
+    if (n_screened_local) atomicAdd(&p.counters[0], n_screened_local);
+    if (n_flag_local) atomicAdd(&p.counters[2], n_flag_local);
+    if (n_fail_local) atomicAdd(&p.counters[3], n_fail_local);
+  }
+  if (node_err_s[lane] != 0) atomicAdd(&p.node_err[lane], node_err_s[lane]);
 }
 
 __global__ void zero_words_kernel(uint32_t* p, int n) {
@@ -526,19 +629,31 @@ gpd_status_t launch_zero_words(hipStream_t stream, void* p, int n_words) {
 gpd_status_t launch_locate(hipStream_t stream, const LocateArgs& a) {
   if (a.t.nin > 64 || a.t.r > R_MAX || a.t.nout > 64)
     return fail(GPD_E_UNSUPPORTED, "locate: more than 64 nodes, parity rows or outputs");
-  LocateParams p;
+  if (!a.in || !a.out || !a.counters || !a.flag_bits || !a.located || !a.node_err || a.located_cap < 0)
+    return fail(GPD_E_INVALID, "locate: missing buffer");
+  LocateParams p{};
   p.t = a.t; p.in = a.in; p.in_ld = a.in_ld; p.out = a.out; p.out_ld = a.out_ld;
   p.cols = a.cols; p.rho = a.rho; p.abs_floor = a.abs_floor;
-  p.counters = a.counters; p.list = a.list; p.cap = a.n_list;
+  p.counters = a.counters; p.flag_bits = a.flag_bits;
   p.located = a.located; p.located_cap = a.located_cap; p.node_err = a.node_err;
-  // every wavefront strides over the screened list and leaves when it runs out
-  const int blocks = a.n_list < 2048 ? (a.n_list > 0 ? a.n_list : 1) : 2048;
-  const size_t lds = (size_t)(a.t.r * a.t.nin + a.t.nin * a.t.nin) * sizeof(double);
+  p.n_codewords = a.rows * a.cols;
+  if (p.n_codewords <= 0) return GPD_OK;
+  p.n_words = (p.n_codewords + 63) / 64;
+  // a team reads at most 16 chunks (8 KB) per workgroup as long as that leaves 64 teams or fewer
+  const int64_t n_chunks = (p.n_words + 63) / 64;
+  int64_t cpt = std::min<int64_t>(kKeptChunks, n_chunks);
+  if ((n_chunks + cpt - 1) / cpt > 64) cpt = (n_chunks + 63) / 64;
+  const int64_t n_teams = (n_chunks + cpt - 1) / cpt;
+  if (cpt > 0x7fffffffLL) return fail(GPD_E_SHAPE, "locate: block too large");
+  p.chunks_per_team = (int)cpt;
+  p.share = (int)(kLocateGrid / n_teams);
+  const int blocks = (int)(p.share * n_teams);
+  const size_t lds = (size_t)(a.t.r * a.t.nin + a.t.nin * a.t.nin + a.t.nout * a.t.nin) * sizeof(double);
   // (static + dynamic LDS can pass 64 KB for codes of 64 nodes: the limit is raised once)
   static bool raised = false;
   if (!raised) {
     GPD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(locate_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 2 * R_MAX * 64 * (int)sizeof(double)));
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 3 * R_MAX * 64 * (int)sizeof(double)));
     raised = true;
   }
   hipLaunchKernelGGL(locate_kernel, dim3(blocks), dim3(64), lds, stream, p);
