@@ -223,3 +223,34 @@ def test_cfg4_full_size_bit_flips():
     say("cfg4:", n_trials, "trials,", n_flips, "flips,", n_loc, "located")
     assert torch.equal(Cf, Ct)
     assert n_flips > 300 and n_loc > 100
+
+
+def test_bursts_of_errors_across_the_screens_map():
+    # 81 920 codewords: the screen's bit map has 1280 words, 20 chunks of 64 words shared by two teams
+    # of workgroups.  A burst of 300 neighbouring codewords (one team member each, in turn), a burst
+    # in the second team's part, the map's last codewords and scattered ones must all be found,
+    # each exactly once, and nothing else.
+    say("bursts of soft errors")
+    A, B, plan, Ct = gpu_responses(512, 16, 640, 2, 2, 2, 14, 5)
+    Ct_h = to_np(Ct).copy()
+    P, rows, cols = Ct_h.shape
+    ncw = rows * cols
+    assert ncw == 81920
+    rng = np.random.default_rng(11)
+    flat = Ct_h.reshape(P, ncw)
+    hit = {}
+    for cw in list(range(4000, 4300)) + list(range(70000, 70100)) + list(range(ncw - 3, ncw)):
+        hit[cw] = [3 if cw < 65536 else 7]
+    for cw in rng.choice(ncw, 60, replace=False):
+        hit.setdefault(int(cw), [int(x) for x in rng.choice(P, 2, replace=False)])
+    for cw, nodes in hit.items():
+        for p in nodes:
+            flat[p, cw] += float(rng.choice([-1.0, 1.0]) * rng.uniform(20.0, 100.0))
+    opl = O.make_plan(2, 2, 2, 14)
+    C_o, orep = O.decode(Ct_h, opl, correct=True)
+    assert orep.n_flagged == len(hit) and orep.n_failed == 0
+    C, rep = G.gpd_decode(plan, to_dev(Ct_h), mode=G.GPD_DEC_LSQ_ALL, correct_errors=True, located_cap=10000)
+    compare_reports(rep, orep, 14)
+    assert rep.status == G.GPD_OK
+    assert sorted((r, c) for (_, r, c, _) in rep.located) == sorted((cw // cols, cw % cols) for cw, nd in hit.items() for _ in nd)
+    check_outputs(C, C_o, orep, plan)
