@@ -122,34 +122,59 @@ __device__ double wave_lsq(double (*Q)[64], double (*R)[A_MAX], double* coef, in
 // normal equations lose too many digits.  With pivots above 1e-6 of the largest diagonal entry the
 // estimate is off by at most about 1e-9 ||y||^2, far inside the margin for rho >= 1e-4 (the
 // caller skips the test below that), so the decisions are those of the exact computation alone.
-__device__ __forceinline__ bool may_explain(const double* Gs, const double* bs, int ns, const int* supp,
-                                            int size, double yy, double lim2) {
+// It is done in two steps, for supports that share all but their last column: the Cholesky factor of
+// the shared columns (n of them, at most S_MAX - 1) is computed once and kept in registers ...
+struct SharedColumns {
   double L[S_MAX][S_MAX], inv[S_MAX], c[S_MAX];
-  double expl = 0.0, dmax = 0.0;
-  bool suspicious = false;
+  double expl, dmax;
+  bool suspicious;
+};
+__device__ __forceinline__ void factor_shared(SharedColumns& f, const double* Gs, const double* bs, int ns,
+                                              const int* supp, int n) {
+  f.expl = 0.0; f.dmax = 0.0; f.suspicious = false;
 #pragma unroll
-  for (int j = 0; j < S_MAX; ++j) {
-    if (j < size) {
+  for (int j = 0; j < S_MAX - 1; ++j) {
+    if (j < n) {
       const int sj = supp[j];
       double d = Gs[sj * ns + sj], cj = bs[sj];
-      dmax = fmax(dmax, d);
+      f.dmax = fmax(f.dmax, d);
 #pragma unroll
       for (int l = 0; l < j; ++l) {
         double v = Gs[sj * ns + supp[l]];
 #pragma unroll
-        for (int q = 0; q < l; ++q) v -= L[j][q] * L[l][q];
-        v *= inv[l];
-        L[j][l] = v;
+        for (int q = 0; q < l; ++q) v -= f.L[j][q] * f.L[l][q];
+        v *= f.inv[l];
+        f.L[j][l] = v;
         d -= v * v;
-        cj -= v * c[l];
+        cj -= v * f.c[l];
       }
-      if (!(d > 1e-6 * dmax)) { suspicious = true; d = dmax > 0.0 ? dmax : 1.0; }
-      inv[j] = 1.0 / sqrt(d);
-      c[j] = cj * inv[j];
-      expl += c[j] * c[j];
+      if (!(d > 1e-6 * f.dmax)) { f.suspicious = true; d = f.dmax > 0.0 ? f.dmax : 1.0; }
+      f.inv[j] = 1.0 / sqrt(d);
+      f.c[j] = cj * f.inv[j];
+      f.expl += f.c[j] * f.c[j];
     }
   }
-  return suspicious || yy - expl <= lim2;
+}
+// ... and one more column, node s, costs one row of the factor.
+__device__ __forceinline__ bool may_explain_with(const SharedColumns& f, const double* Gs, const double* bs,
+                                                 int ns, const int* supp, int n, int s, double yy, double lim2) {
+  double row[S_MAX];
+  double d = Gs[s * ns + s], cj = bs[s];
+  const double dmax = fmax(f.dmax, d);
+#pragma unroll
+  for (int l = 0; l < S_MAX - 1; ++l) {
+    if (l < n) {
+      double v = Gs[s * ns + supp[l]];
+#pragma unroll
+      for (int q = 0; q < l; ++q) v -= row[q] * f.L[l][q];
+      v *= f.inv[l];
+      row[l] = v;
+      d -= v * v;
+      cj -= v * f.c[l];
+    }
+  }
+  if (f.suspicious || !(d > 1e-6 * dmax)) return true;
+  return yy - (f.expl + cj * cj / d) <= lim2;
 }
 
 __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
@@ -485,50 +510,88 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
         const unsigned long long total = binom[nfree][tpick];
         if (total > budget) break;
         double my_res = 1.0e300;
-        unsigned long long my_c = ~0ull;
-        for (unsigned long long base = 0; base < total; base += 64) {
-          const unsigned long long c = base + lane;
-          bool cand = c < total;
-          int* supp = cand_supp[lane];                     // this lane's support (LDS)
-          if (cand) {
-            // unrank c among the tpick-subsets of the free nodes, lexicographic order
-            for (int f = 0; f < nforced; ++f) supp[f] = forcedlist[f];
-            unsigned long long rest = c;
-            int x = 0;
-            for (int i = 0; i < tpick; ++i) {
-              for (;; ++x) {
-                const unsigned long long cnt = binom[nfree - x - 1][tpick - i - 1];
-                if (rest < cnt) break;
-                rest -= cnt;
+        unsigned long long my_key = ~0ull;
+        // A lane takes supports that share all but their last node: the forced nodes and the first
+        // tpick - 1 free ones (unranked once, lexicographic order), and runs over the last node.  The
+        // first test's factor of the shared columns is computed once per lane, a support then costs
+        // one more row.  Supports of one size are ordered by `key`, their free nodes' positions in
+        // 6-bit fields, first node in the highest: the order of the lexicographic rank.
+        // (tpick == 1: no shared free node, the lanes take one last node each; tpick == 0: the forced
+        // nodes alone, lane 0.)
+        int* supp = cand_supp[lane];                       // this lane's support (LDS)
+        const int nshared = size - 1;
+        const unsigned long long n_prefix = tpick >= 2 ? binom[nfree][tpick - 1] : 1ull;
+        for (unsigned long long base = 0; base < n_prefix; base += 64) {
+          bool have;
+          int x_next = 0;
+          unsigned long long key_prefix = 0ull;
+          if (tpick >= 2) {
+            const unsigned long long q = base + lane;
+            have = q < n_prefix;
+            if (have) {
+              for (int f = 0; f < nforced; ++f) supp[f] = forcedlist[f];
+              unsigned long long rest = q;
+              int x = 0;
+              for (int i = 0; i < tpick - 1; ++i) {
+                for (;; ++x) {
+                  const unsigned long long cnt = binom[nfree - x - 1][tpick - i - 2];
+                  if (rest < cnt) break;
+                  rest -= cnt;
+                }
+                supp[nforced + i] = freelist[x];
+                key_prefix |= (unsigned long long)x << (6 * (S_MAX - 1 - i));
+                ++x;
               }
-              supp[nforced + i] = freelist[x];
-              ++x;
+              x_next = x;
             }
-            if (use_filter) cand = may_explain(Gs, bs, ns, supp, size, yy, lim2);
+          } else {
+            have = tpick == 1 ? lane < nfree : lane == 0;
+            if (have) {
+              for (int f = 0; f < nforced; ++f) supp[f] = forcedlist[f];
+              x_next = lane;
+            }
           }
-          unsigned long long todo = __ballot(cand);
-          __syncthreads();
-          // what is left (after the first test: the support that explains y and few others) is
-          // decided by the exact residual, one support at a time on the whole wavefront: rows
-          // over lanes, modified Gram-Schmidt by wavefront reductions (no per-lane arrays, so
-          // the kernel needs no scratch memory)
-          while (todo) {
-            const int src = __ffsll((long long)todo) - 1;
-            todo &= todo - 1ull;
-            for (int j = 0; j < size; ++j) lsq_q[j][lane] = lane < r ? Hs[lane * ns + cand_supp[src][j]] : 0.0;
+          SharedColumns fac;
+          if (have && use_filter && tpick >= 1) factor_shared(fac, Gs, bs, ns, supp, nshared);
+          const int n_last = have ? (tpick >= 2 ? nfree - x_next : 1) : 0;
+          int n_iter = n_last;
+#pragma unroll
+          for (int off = 32; off > 0; off >>= 1) n_iter = max(n_iter, __shfl_xor(n_iter, off));
+          for (int k = 0; k < n_iter; ++k) {
+            bool cand = k < n_last;
+            unsigned long long key = 0ull;
+            if (cand && tpick >= 1) {
+              const int x = x_next + k;
+              const int s = freelist[x];
+              key = key_prefix | ((unsigned long long)x << (6 * (S_MAX - tpick)));
+              if (use_filter) cand = may_explain_with(fac, Gs, bs, ns, supp, nshared, s, yy, lim2);
+              if (cand) supp[size - 1] = s;
+            }
+            unsigned long long todo = __ballot(cand);
             __syncthreads();
-            const double res = wave_lsq(lsq_q, lsq_r, lsq_c, size, lane < r ? ys[lane] : 0.0, lane);
-            if (lane == src && res <= tau && res < my_res) { my_res = res; my_c = c; }
+            // what is left (after the first test: the support that explains y and few others) is
+            // decided by the exact residual, one support at a time on the whole wavefront: rows
+            // over lanes, modified Gram-Schmidt by wavefront reductions (no per-lane arrays, so
+            // the kernel needs no scratch memory)
+            while (todo) {
+              const int src = __ffsll((long long)todo) - 1;
+              todo &= todo - 1ull;
+              for (int j = 0; j < size; ++j) lsq_q[j][lane] = lane < r ? Hs[lane * ns + cand_supp[src][j]] : 0.0;
+              __syncthreads();
+              const double res = wave_lsq(lsq_q, lsq_r, lsq_c, size, lane < r ? ys[lane] : 0.0, lane);
+              if (lane == src && res <= tau && (res < my_res || (res == my_res && key < my_key))) { my_res = res; my_key = key; }
+            }
+            __syncthreads();
           }
         }
-        // wave-wide arg-min (smallest residual, then smallest index)
+        // wave-wide arg-min (smallest residual, then first in lexicographic order)
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) {
           const double o_res = __shfl_xor(my_res, off);
-          const unsigned long long o_c = __shfl_xor(my_c, off);
-          if (o_res < my_res || (o_res == my_res && o_c < my_c)) { my_res = o_res; my_c = o_c; }
+          const unsigned long long o_key = __shfl_xor(my_key, off);
+          if (o_res < my_res || (o_res == my_res && o_key < my_key)) { my_res = o_res; my_key = o_key; }
         }
-        if (my_c != ~0ull) { found = true; best_size = size; best_c = my_c; }
+        if (my_key != ~0ull) { found = true; best_size = size; best_c = my_key; }
       }
       if (found) {
         // the winning support, for all lanes
@@ -536,17 +599,7 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
         __syncthreads();
         if (lane == 0) {
           for (int f = 0; f < nforced; ++f) supp_s[f] = forcedlist[f];
-          unsigned long long rest = best_c;
-          int x = 0;
-          for (int i = 0; i < tpick; ++i) {
-            for (;; ++x) {
-              const unsigned long long cnt = binom[nfree - x - 1][tpick - i - 1];
-              if (rest < cnt) break;
-              rest -= cnt;
-            }
-            supp_s[nforced + i] = freelist[x];
-            ++x;
-          }
+          for (int i = 0; i < tpick; ++i) supp_s[nforced + i] = freelist[(best_c >> (6 * (S_MAX - 1 - i))) & 63ull];
         }
         __syncthreads();
       }
