@@ -77,31 +77,40 @@ __device__ __forceinline__ double wave_max(double v) {
   return v;
 }
 
+// Sum over the first `width` lanes (a power of two; the lanes beyond hold zeros), valid in those
+// lanes: the same additions, in the same order, as the last log2(width) steps of wave_sum.
+__device__ __forceinline__ double group_sum(double v, int width) {
+  for (int off = width >> 1; off > 0; off >>= 1) v += __shfl_xor(v, off);
+  return v;
+}
+
 // Least squares by the whole wavefront: the ncols columns are in Q[j][lane] (one element per
-// lane, zero beyond the rows in use), yv is the lane's element of the right-hand side.
+// lane, zero beyond the rows in use, which all lie in the first `width` lanes), yv is the lane's
+// element of the right-hand side.
 // Modified Gram-Schmidt with the right-hand side orthogonalised along; returns the residual
 // norm and leaves the coefficients in coef[0 .. ncols) (LDS).  One wavefront per workgroup.
-__device__ double wave_lsq(double (*Q)[64], double (*R)[A_MAX], double* coef, int ncols, double yv, int lane) {
+__device__ double wave_lsq(double (*Q)[64], double (*R)[A_MAX], double* coef, int ncols, double yv, int lane,
+                           int width) {
   for (int j = 0; j < ncols; ++j) {
     double v = Q[j][lane];
     for (int l = 0; l < j; ++l) {
       const double ql = Q[l][lane];
-      const double dot = wave_sum(ql * v);
+      const double dot = group_sum(ql * v, width);
       if (lane == 0) R[l][j] = dot;
       v -= dot * ql;
     }
-    const double nrm = sqrt(wave_sum(v * v));
+    const double nrm = sqrt(group_sum(v * v, width));
     if (lane == 0) R[j][j] = nrm;
     Q[j][lane] = nrm > 0.0 ? v / nrm : 0.0;
   }
   double w = yv;
   for (int j = 0; j < ncols; ++j) {
     const double qj = Q[j][lane];
-    const double dot = wave_sum(qj * w);
+    const double dot = group_sum(qj * w, width);
     if (lane == 0) coef[j] = dot;
     w -= dot * qj;
   }
-  const double res = sqrt(wave_sum(w * w));
+  const double res = __shfl(sqrt(group_sum(w * w, width)), 0);
   __syncthreads();
   if (lane == 0) {
     for (int j = ncols - 1; j >= 0; --j) {
@@ -249,6 +258,8 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
     Gs[idx] = g;
   }
   const bool use_filter = p.rho >= 1e-4;
+  // (columns of H have their r entries in the first lanes: reductions over them need log2(rwidth) steps)
+  const int rwidth = r <= 1 ? 1 : 1 << (32 - __clz(r - 1));
 
   // Binomial coefficients for the unranking of supports, C(a, b) for a <= 64, b <= S_MAX: lane a
   // builds row a by C(a, b) = C(a, b - 1) (a - b + 1) / b.  Every product stays below 2^53 and every
@@ -428,7 +439,7 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
             }
             const int dt = lane > t ? lane - t : t - lane;
             const double rhs = lane < rows ? -(syn[lane + t] + syn[dt]) : 0.0;
-            wave_lsq(lsq_q, lsq_r, lsq_c, t, rhs, lane);
+            wave_lsq(lsq_q, lsq_r, lsq_c, t, rhs, lane, rwidth);
             // |L(x)| at this lane's node: T_t(x) + sum_k c_k T_k(x)
             double t0 = 1.0, t1 = x;
             for (int k = 0; k <= t; ++k) {
@@ -469,7 +480,7 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
             }
             __syncthreads();
             for (int j = 0; j < wsize; ++j) lsq_q[j][lane] = lane < r ? Hs[lane * ns + supp_s[j]] : 0.0;
-            wave_lsq(lsq_q, lsq_r, lsq_c, wsize, lane < r ? ys[lane] : 0.0, lane);
+            wave_lsq(lsq_q, lsq_r, lsq_c, wsize, lane < r ? ys[lane] : 0.0, lane, rwidth);
             // lane j < wsize speaks for node supp_s[j]
             const int my_node = lane < wsize ? supp_s[lane] : 64;
             const bool eligible = lane < wsize && !((forced_mask >> my_node) & 1ull);
@@ -498,7 +509,7 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
           __syncthreads();
           for (int j = 0; j < csize; ++j) lsq_q[j][lane] = lane < r ? Hs[lane * ns + supp_s[j]] : 0.0;
           __syncthreads();
-          const double res = wave_lsq(lsq_q, lsq_r, lsq_c, csize, lane < r ? ys[lane] : 0.0, lane);
+          const double res = wave_lsq(lsq_q, lsq_r, lsq_c, csize, lane < r ? ys[lane] : 0.0, lane, rwidth);
           if (res <= tau) { found = true; best_size = csize; }
         }
         continue;
@@ -578,7 +589,7 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
               todo &= todo - 1ull;
               for (int j = 0; j < size; ++j) lsq_q[j][lane] = lane < r ? Hs[lane * ns + cand_supp[src][j]] : 0.0;
               __syncthreads();
-              const double res = wave_lsq(lsq_q, lsq_r, lsq_c, size, lane < r ? ys[lane] : 0.0, lane);
+              const double res = wave_lsq(lsq_q, lsq_r, lsq_c, size, lane < r ? ys[lane] : 0.0, lane, rwidth);
               if (lane == src && res <= tau && (res < my_res || (res == my_res && key < my_key))) { my_res = res; my_key = key; }
             }
             __syncthreads();
@@ -626,7 +637,7 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
     }
     for (int j = 0; j < best_size; ++j) lsq_q[j][lane] = lane < r ? Hs[lane * ns + supp_s[j]] : 0.0;
     __syncthreads();
-    wave_lsq(lsq_q, lsq_r, lsq_c, best_size, y2, lane);
+    wave_lsq(lsq_q, lsq_r, lsq_c, best_size, y2, lane, rwidth);
     if (lane < best_size) zs[supp_s[lane]] = -lsq_c[lane];
     __syncthreads();
     // estimated error value = received - predicted
