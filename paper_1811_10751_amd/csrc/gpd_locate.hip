@@ -136,6 +136,7 @@ __device__ double wave_lsq(double (*Q)[64], double (*R)[A_MAX], double* coef, in
 struct SharedColumns {
   double L[S_MAX][S_MAX], inv[S_MAX], c[S_MAX];
   double expl, dmax;
+  int row_of[S_MAX];          // shared node l's row of G starts at Gs[row_of[l]]
   bool suspicious;
 };
 __device__ __forceinline__ void factor_shared(SharedColumns& f, const double* Gs, const double* bs, int ns,
@@ -143,8 +144,10 @@ __device__ __forceinline__ void factor_shared(SharedColumns& f, const double* Gs
   f.expl = 0.0; f.dmax = 0.0; f.suspicious = false;
 #pragma unroll
   for (int j = 0; j < S_MAX - 1; ++j) {
+    f.row_of[j] = 0;
     if (j < n) {
       const int sj = supp[j];
+      f.row_of[j] = sj * ns;
       double d = Gs[sj * ns + sj], cj = bs[sj];
       f.dmax = fmax(f.dmax, d);
 #pragma unroll
@@ -166,14 +169,18 @@ __device__ __forceinline__ void factor_shared(SharedColumns& f, const double* Gs
 }
 // ... and one more column, node s, costs one row of the factor.
 __device__ __forceinline__ bool may_explain_with(const SharedColumns& f, const double* Gs, const double* bs,
-                                                 int ns, const int* supp, int n, int s, double yy, double lim2) {
-  double row[S_MAX];
+                                                 int ns, int n, int s, double yy, double lim2) {
+  double row[S_MAX], g[S_MAX];
+  // (G is symmetric: the entries come from the shared nodes' rows, whose offsets are in registers,
+  // so all of them are requested at once)
+#pragma unroll
+  for (int l = 0; l < S_MAX - 1; ++l) g[l] = Gs[f.row_of[l] + s];
   double d = Gs[s * ns + s], cj = bs[s];
   const double dmax = fmax(f.dmax, d);
 #pragma unroll
   for (int l = 0; l < S_MAX - 1; ++l) {
     if (l < n) {
-      double v = Gs[s * ns + supp[l]];
+      double v = g[l];
 #pragma unroll
       for (int q = 0; q < l; ++q) v -= row[q] * f.L[l][q];
       v *= f.inv[l];
@@ -183,7 +190,7 @@ __device__ __forceinline__ bool may_explain_with(const SharedColumns& f, const d
     }
   }
   if (f.suspicious || !(d > 1e-6 * dmax)) return true;
-  return yy - (f.expl + cj * cj / d) <= lim2;
+  return (yy - f.expl - lim2) * d <= cj * cj;              // yy - (expl + cj^2 / d) <= lim2, d > 0
 }
 
 __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
@@ -575,10 +582,11 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
               const int x = x_next + k;
               const int s = freelist[x];
               key = key_prefix | ((unsigned long long)x << (6 * (S_MAX - tpick)));
-              if (use_filter) cand = may_explain_with(fac, Gs, bs, ns, supp, nshared, s, yy, lim2);
+              if (use_filter) cand = may_explain_with(fac, Gs, bs, ns, nshared, s, yy, lim2);
               if (cand) supp[size - 1] = s;
             }
             unsigned long long todo = __ballot(cand);
+            if (todo == 0ull) continue;                    // (uniform; the usual case)
             __syncthreads();
             // what is left (after the first test: the support that explains y and few others) is
             // decided by the exact residual, one support at a time on the whole wavefront: rows
