@@ -315,7 +315,7 @@ def _chebyshev_table(x: np.ndarray, count: int) -> np.ndarray:
     return T[:count]
 
 
-def algebraic_locate(z: np.ndarray, H: np.ndarray, pts: np.ndarray, tau: float, forced=()):
+def algebraic_locate(z: np.ndarray, H: np.ndarray, pts: np.ndarray, tau: float, forced=(), guard_nodes: int = 2):
     """Polynomial-time error location inside the adversarial radius |A| <= floor((P-Q)/2)
     (Sec. V, definition of the adversarial error model; the remark after Thm 3 asks for a
     polynomial-time reconstruction in place of the exhaustive search of Algorithm 1).
@@ -331,8 +331,11 @@ def algebraic_locate(z: np.ndarray, H: np.ndarray, pts: np.ndarray, tau: float, 
     For t = 1, 2, ... the system is solved in the least-squares sense; of the t + 2 nodes
     where |L| is smallest the t with the largest fitted error values are the candidate, and
     the candidate is accepted by the criterion of Algorithm 1 (residual of H z on the span of
-    those columns of H <= tau), so a wrong candidate is never accepted silently.  Known-bad (forced) nodes are erasures: they are
-    left out of the syndromes, which costs one syndrome each.
+    those columns of H <= tau), so a wrong candidate is never accepted silently.  Known-bad
+    (forced) nodes are erasures: they are left out of the syndromes, which costs one syndrome each.
+    guard_nodes = 0 is the textbook form (the t nodes where |L| is smallest, nothing fitted);
+    in exact arithmetic both forms return the same support, since L vanishes on the erroneous
+    nodes only.
     Returns (status, support, e_hat) like algorithm1."""
     r_full, ns = H.shape
     y = H @ z
@@ -364,7 +367,7 @@ def algebraic_locate(z: np.ndarray, H: np.ndarray, pts: np.ndarray, tau: float, 
         L = T[t] + c @ T[:t]
         # two guard nodes: with rounding, a neighbour of an erroneous node can have a smaller
         # |L| than the node itself; the error values fitted on the t + 2 best nodes tell them apart
-        guard = max(0, min(2, r_full - 1 - len(forced) - t, len(free) - t))
+        guard = max(0, min(int(guard_nodes), r_full - 1 - len(forced) - t, len(free) - t))
         order = np.argsort(np.abs(L), kind="stable")[:t + guard]
         wide = tuple(sorted(forced + tuple(int(free[q]) for q in order)))
         _, e_wide = support_residual(H, y, wide)

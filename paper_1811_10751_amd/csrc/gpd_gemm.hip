@@ -1189,14 +1189,10 @@ gpd_status_t launch_f32_shape(hipStream_t stream, const GemmParams& p, int mode)
 
 template <bool A_KC, bool B_KC>
 gpd_status_t launch_f32(hipStream_t stream, GemmParams p, int64_t batch, bool aligned) {
-#ifdef GPD_FORCE_SMALL
-  const bool large = false;
-#else
   // short contractions are dominated by per-tile prologue / epilogue, which only overlap with
   // matrix work when several workgroups share a CU: keep the small shape for them
   const bool large = aligned && p.M % 256 == 0 && p.N % 256 == 0 && p.K % BK == 0 && p.K >= 1024 &&
                      (int64_t)(p.M / 256) * (p.N / 256) * batch >= 256;
-#endif
   const int tbm = large ? 256 : 128, tbn = large ? 256 : 128;
   p.tiles_m = (p.M + tbm - 1) / tbm;
   p.tiles_n = (p.N + tbn - 1) / tbn;

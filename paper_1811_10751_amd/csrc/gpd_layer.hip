@@ -1045,7 +1045,14 @@ extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, floa
     if (st != GPD_OK) return st;
   }
   if (!do_bwd) {
-    if (report) { std::memset(report, 0, sizeof(*report)); report->n_present = P; }
+    if (report) {
+      // (the caller's list and its capacity stay as they were given, as in every decode)
+      gpd_located_t* keep_ptr = report->located;
+      const int64_t keep_cap = report->located_cap;
+      std::memset(report, 0, sizeof(*report));
+      report->located = keep_ptr; report->located_cap = keep_cap;
+      report->n_present = P;
+    }
     return GPD_OK;
   }
   DecodeJob job;

@@ -408,7 +408,8 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
       if (phase == 1) {
         // ---- algebraic locator (see the head of this file); rr syndromes, t <= rr / 2
         const int rr = r - nforced;
-        if (p.t.pts64 == nullptr || rr < 2 || size > max_size) continue;
+        // (rr < 2 leaves only t = 0 below: the non-finite entries alone)
+        if (p.t.pts64 == nullptr || size > max_size) continue;
         const bool isfree = lane < ns && !((forced_mask >> lane) & 1ull);
         const double x_raw = lane < ns ? p.t.pts64[lane] : 0.0;
         const double lo = wave_min(isfree ? x_raw : 1.0e300), hi = wave_max(isfree ? x_raw : -1.0e300);
@@ -464,6 +465,7 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
           if (guard > nfree - t) guard = nfree - t;
           if (guard > A_MAX - nforced - t) guard = A_MAX - nforced - t;
           guard = guard < 0 ? 0 : (guard > 2 ? 2 : guard);
+          if (t == 0) guard = 0;                         // nothing to pick: the forced nodes alone are tested
           unsigned long long wide = 0ull;
           for (int i = 0; i < t + guard; ++i) {
             double mv = ((wide >> lane) & 1ull) ? 1.0e300 : lval;

@@ -156,3 +156,53 @@ def test_decode_with_algebraic_locator_matches_search():
     assert [l[:3] for l in r1.located] == [l[:3] for l in r2.located]
     assert np.allclose(C1, C2, rtol=1e-10, atol=1e-12)
     assert np.abs(C2 - A @ B).max() < 1e-4
+
+
+@pytest.mark.parametrize("P,K", [(16, 9), (24, 9), (32, 12), (48, 9)])
+def test_guard_nodes_change_nothing_in_exact_arithmetic(P, K):
+    # Inside the radius floor((P-Q)/2) (Sec. V, adversarial model) the locator polynomial vanishes
+    # on the erroneous nodes and nowhere else, so the textbook form (the t nodes of smallest |L|,
+    # guard_nodes = 0) and the form with two guard nodes must accept the same support, the planted
+    # one, on exact fp64 words with a tiny threshold.
+    rng = np.random.default_rng(3 * P + K)
+    pts = O.chebyshev_points(P)
+    H = O.parity_check(pts, K)
+    r = P - K
+    for t in range(1, min(r // 2, 8) + 1):
+        for _ in range(4):
+            z = codeword(pts, K, rng)
+            z2, A, e = plant(z, t, rng, scale=1.0)
+            tau = 1e-9 * np.linalg.norm(z2)
+            plain = O.algebraic_locate(z2, H, pts, tau, guard_nodes=0)
+            guarded = O.algebraic_locate(z2, H, pts, tau)
+            assert plain[0] == guarded[0] == "located"
+            assert plain[1] == guarded[1] == A
+            assert np.allclose(plain[2], guarded[2], rtol=1e-9, atol=1e-12)
+            assert np.allclose(guarded[2], e, atol=1e-6)
+
+
+def test_the_case_that_needs_the_guard_nodes():
+    # fp32-rounded responses of a (24, 9) code with 7 errors (the radius): the t nodes of smallest
+    # |L| are not the erroneous ones (a neighbour on the Chebyshev grid comes out ahead), the textbook
+    # form reports a failure; with two guard nodes the fitted error values single out the right 7.
+    # Either way nothing wrong is ever accepted: acceptance is Algorithm 1's criterion.
+    P, K = 24, 9
+    rng = np.random.default_rng(0)
+    pts = O.chebyshev_points(P)
+    H = O.parity_check(pts, K)
+    found = None
+    for _ in range(2000):
+        t = int(rng.integers(1, (P - K) // 2 + 1))
+        z = O.round_to_f32(O.vandermonde(pts, K) @ rng.standard_normal(K))
+        nodes = np.sort(rng.choice(P, t, replace=False))
+        z2 = z.copy()
+        z2[nodes] += rng.choice([-1, 1], t) * rng.uniform(0.5, 2, t) * np.abs(z).max()
+        tau = 2.0 ** -12 * np.linalg.norm(z2)
+        plain = O.algebraic_locate(z2, H, pts, tau, guard_nodes=0)
+        guarded = O.algebraic_locate(z2, H, pts, tau)
+        want = tuple(int(q) for q in nodes)
+        for res in (plain, guarded):
+            assert res[0] == "failed" or res[1] == want          # never a wrong support
+        if guarded[0] == "located" and plain[0] == "failed" and found is None:
+            found = (t, want)
+    assert found is not None and found[0] >= 5

@@ -124,3 +124,50 @@ def test_workload_generators_are_seeded():
     x = np.ones((2, 2, 2), dtype=np.float32)
     y = WL.apply_bitflips(x, [(1, 3, 31)])
     assert y[1, 1, 1] == -1.0 and x[1, 1, 1] == 1.0 and (y != x).sum() == 1
+
+
+def test_amplification_closed_forms():
+    # the decoder's noise amplification is pinned by cases that can be inverted by hand
+    # (a) m = n = d = 1: K = 1, replication; the single coefficient is the mean of the present
+    #     responses (lsq_all: row (1/|S|, ..., 1/|S|), norm 1/sqrt|S|) or the first one (first_k: 1)
+    pl = O.make_plan(1, 1, 1, 7)
+    assert pl.K == 1
+    assert abs(O.amplification(pl, None, "lsq_all") - 1 / np.sqrt(7)) < 1e-14
+    assert abs(O.amplification(pl, None, "first_k") - 1.0) < 1e-14
+    present = np.array([0, 1, 1, 0, 1, 1, 0], dtype=np.uint8)
+    assert abs(O.amplification(pl, present, "lsq_all") - 0.5) < 1e-14
+    # (b) m = 2, n = d = 1: K = 2, both coefficients useful; two points a, b:
+    #     [[1, a], [1, b]]^-1 = [[b, -a], [-1, 1]] / (b - a); the larger row norm is sqrt 2 / |b - a|
+    #     when a^2 + b^2 <= 2
+    a, b = 0.5, -0.25
+    pl = O.make_plan(2, 1, 1, 2, points=[a, b])
+    assert pl.K == 2 and sorted(pl.eC.ravel().tolist()) == [0, 1]
+    assert abs(O.amplification(pl, None, "first_k") - np.sqrt(2.0) / 0.75) < 1e-13
+    # (c) the useful row only, and nodes that first_k must ignore: m = d = 1, n = 2 (MatDot) has
+    #     K = 3 and the single useful exponent 1.  Points -2, -1, 1, 2: by symmetry the least-squares
+    #     coefficient of b is sum b z / sum b^2 = (-2 z_0 - z_1 + z_2 + 2 z_3) / 10, norm 1 / sqrt 10
+    #     (the other two rows have norms 0.97 and 1/3); the parabola through the first three points
+    #     has the linear coefficient (z_2 - z_1) / 2 (Lagrange basis), norm 1 / sqrt 2
+    pl = O.make_plan(1, 2, 1, 4, points=[-2.0, -1.0, 1.0, 2.0])
+    assert pl.K == 3 and pl.eC.ravel().tolist() == [1]
+    assert abs(O.amplification(pl, None, "lsq_all") - 1 / np.sqrt(10.0)) < 1e-14
+    assert abs(O.amplification(pl, None, "first_k") - 1 / np.sqrt(2.0)) < 1e-14
+
+
+@pytest.mark.parametrize("mode", ["first_k", "lsq_all"])
+def test_amplification_is_the_noise_gain_of_the_decoder(mode):
+    # independent unit-variance noise in the responses comes out of O.decode with a standard
+    # deviation, in the worst useful block, equal to the amplification: measured through the decoder
+    # itself on 40 000 noise codewords, not through the decoding matrix
+    pl = O.make_plan(2, 2, 2, 16)
+    present = WL.erasure_trial(1003, 16, 4)
+    rng = np.random.default_rng(8)
+    noise = rng.standard_normal((16, 200, 200))
+    C, _ = O.decode(noise, pl, present, mode)
+    stds = [C[i * 200:(i + 1) * 200, k * 200:(k + 1) * 200].std() for i in range(2) for k in range(2)]
+    amp = O.amplification(pl, present, mode)
+    assert abs(max(stds) / amp - 1.0) < 0.03, (max(stds), amp)
+    # and it is no bound on anything else: the dropped nodes' values are never read
+    noise[present == 0] = 1e30
+    C2, _ = O.decode(noise, pl, present, mode)
+    assert np.array_equal(C, C2)
