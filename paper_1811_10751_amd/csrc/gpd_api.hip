@@ -20,6 +20,7 @@ gpd_status_t TableRing::init(size_t bytes_per_slot) {
   GPD_HIP(hipMalloc((void**)&arena, kArenaBytes));
   arena_used = 0;
   GPD_HIP(hipStreamCreateWithFlags(&up, hipStreamNonBlocking));
+  GPD_HIP(hipHostMalloc((void**)&report_host, kReportBytes, hipHostMallocDefault));
   return GPD_OK;
 }
 
@@ -56,6 +57,7 @@ void TableRing::destroy() {
     if (ev[i]) { (void)hipEventDestroy(ev[i]); ev[i] = nullptr; }
   if (up) { (void)hipStreamSynchronize(up); (void)hipStreamDestroy(up); up = nullptr; }
   if (host) { (void)hipHostFree(host); host = nullptr; }
+  if (report_host) { (void)hipHostFree(report_host); report_host = nullptr; }
   if (dev) { (void)hipFree(dev); dev = nullptr; }
   if (arena) { (void)hipFree(arena); arena = nullptr; }
   cache.clear();
@@ -423,12 +425,16 @@ gpd_status_t run_decode(hipStream_t stream, TableRing* ring, const DecodeJob& jo
   }
   if (!report) return GPD_OK;
 
+  // counters and per-node counts (the workspace's first 512 bytes) come back with one
+  // stream-ordered copy into pinned memory; the wait for the stream covers it
+  static_assert(kHeaderBytes <= TableRing::kReportBytes, "report staging too small");
+  if (corr) GPD_HIP(hipMemcpyAsync(ring->report_host, ws, kHeaderBytes, hipMemcpyDeviceToHost, stream));
   GPD_HIP(hipStreamSynchronize(stream));
   if (corr) {
     uint32_t hc[64];
     int32_t hn[64];
-    GPD_HIP(hipMemcpy(hc, counters, sizeof(hc), hipMemcpyDeviceToHost));
-    GPD_HIP(hipMemcpy(hn, node_err, sizeof(hn), hipMemcpyDeviceToHost));
+    std::memcpy(hc, ring->report_host, sizeof(hc));
+    std::memcpy(hn, ring->report_host + 256, sizeof(hn));
     report->n_screened = hc[0];
     report->n_flagged = hc[2];
     report->n_failed = hc[3];

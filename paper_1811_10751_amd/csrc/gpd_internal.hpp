@@ -146,6 +146,10 @@ struct TableRing {
   char* arena = nullptr;
   size_t arena_used = 0;
   hipStream_t up = nullptr;            // uploads into the arena (default priority, non-blocking)
+  // pinned landing place for the counters a decode with a host report reads back (one
+  // stream-ordered copy; the caller waits for the stream afterwards)
+  static constexpr size_t kReportBytes = 512;
+  char* report_host = nullptr;
   std::map<std::string, CombineTable> cache;
   gpd_status_t cached(const std::string& key, const std::function<gpd_status_t(HostCombineTable*)>& build,
                       hipStream_t stream, CombineTable* out);

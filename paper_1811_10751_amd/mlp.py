@@ -22,6 +22,10 @@ class CodedMLP:
         self._ckpt = None
         self.repaired = []
         self.restored = False
+        # device tensors of the last iteration, for inspection: acts[l] = input of layer l (acts[0]
+        # = X, acts[L] = network output), deltas[l] = error Delta of layer l
+        self.acts = []
+        self.deltas = []
 
     def encode_weights(self, Ws):
         """Ws: list of float32 CUDA tensors (N_out x N_in).  Done once before training."""
@@ -85,7 +89,10 @@ class CodedMLP:
                 self.repaired += [(l, "forward", p) for p in self._regenerate(l, rf)]
             acts.append(act)
         delta = B.gpd_l2_delta(Y, acts[-1], 2.0 / self.batch, stream=self.stream)
+        self.acts = acts
+        self.deltas = [None] * len(self.layers)
         for l in range(len(self.layers) - 1, -1, -1):
+            self.deltas[l] = delta
             C, rb = B.gpd_coded_layer_step(self.layers[l], B.GPD_STEP_BACKWARD_UPDATE, self.Wts[l],
                                            acts[l], Dlt=delta, eta=eta, decay=decay,
                                            correct_errors=correct_errors, want_report=want_report,
