@@ -184,6 +184,27 @@ gpd_status_t gpd_decode(const gpd_plan_t* plan, const float* Ct, const uint8_t* 
                         int32_t mode, int32_t correct_errors, float* C, int64_t ldc,
                         void* workspace, size_t workspace_bytes, gpd_report_t* report);
 
+/* gpd_decode for callers that cannot allocate device memory and have no workspace to pass: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels and
+ * same results as gpd_decode, but the scratch memory of the soft-error path (counters, the
+ * screen's bit map, the list of located entries) is a fixed array inside the library, about 1.5 MiB
+ * on every GPU the library runs on, held until the process ends.  The call allocates no device
+ * memory and frees none.
+ *   correct_errors: GPD_CORRECT_NONE or GPD_CORRECT_ELEMENTS (GPD_CORRECT_NODES ->
+ *            GPD_E_UNSUPPORTED).
+ *   limits:  blocks of at most GPD_STATIC_MAX_CODEWORDS elements ((N1/m) * (Nc/d)), else
+ *            GPD_E_WORKSPACE and nothing is touched; at most GPD_STATIC_LOCATED_CAP located entries
+ *            are listed (n_located still counts all of them).
+ *   Every call on one GPU uses that GPU's one array: it keeps the last call's contents (the call
+ *   clears what must start at zero itself, with a kernel), and two calls that overlap on one GPU
+ *   (different streams or threads) race.  The device that owns the plan's stream must be current.
+ * Everything else as for gpd_decode. */
+#define GPD_STATIC_MAX_CODEWORDS (1 << 22)
+#define GPD_STATIC_LOCATED_CAP (1 << 16)
+gpd_status_t gpd_decode_static(const gpd_plan_t* plan, const float* Ct, const uint8_t* present,
+                               int32_t mode, int32_t correct_errors, float* C, int64_t ldc,
+                               gpd_report_t* report);
+
 /* ------------------------------------------------------------------ node-level faults */
 
 /* Host-side result of a node search. */

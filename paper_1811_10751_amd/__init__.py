@@ -7,4 +7,5 @@ from .binding import (GpdError, Layer, Plan, Report, load_library, gpd_coded_lay
                       gpd_sigmoid_bwd, gpd_sigmoid_fwd, gpd_version, gpd_worker_products,
                       NodeReport, gpd_locate_nodes, gpd_layer_locate_nodes, gpd_layer_regenerate,
                       gpd_layer_project, gpd_host_parity_check, gpd_host_locate_nodes,
-                      VerifyReport, gpd_verify_decode, gpd_row_mean, gpd_sigmoid_bwd_sparse)
+                      VerifyReport, gpd_verify_decode, gpd_row_mean, gpd_sigmoid_bwd_sparse,
+                      gpd_decode_static)

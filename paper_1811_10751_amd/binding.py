@@ -37,7 +37,7 @@ EXPORTS = [
     "gpd_host_code", "gpd_host_decode_matrices", "gpd_last_error", "gpd_version",
     "gpd_locate_nodes", "gpd_layer_locate_nodes", "gpd_layer_regenerate", "gpd_layer_project",
     "gpd_host_parity_check", "gpd_host_locate_nodes", "gpd_verify_decode",
-    "gpd_row_mean", "gpd_sigmoid_bwd_sparse",
+    "gpd_row_mean", "gpd_sigmoid_bwd_sparse", "gpd_decode_static",
 ]
 
 
@@ -112,6 +112,7 @@ def load_library():
     lib.gpd_encode.argtypes = [vp, vp, i64, vp, i64, vp, vp]
     lib.gpd_worker_products.argtypes = [vp, vp, vp, vp]
     lib.gpd_decode.argtypes = [vp, vp, vp, i32, i32, vp, i64, vp, sz, C.POINTER(_Report)]
+    lib.gpd_decode_static.argtypes = [vp, vp, vp, i32, i32, vp, i64, C.POINTER(_Report)]
     lib.gpd_layer_create.argtypes = [C.POINTER(_LayerDesc), C.POINTER(vp)]
     lib.gpd_layer_info.argtypes = [vp, C.POINTER(i32), C.POINTER(i32), C.POINTER(i64),
                                    C.POINTER(i64), C.POINTER(sz)]
@@ -345,6 +346,28 @@ def gpd_decode(plan: Plan, Ct, present=None, mode=GPD_DEC_FIRST_K, correct_error
     _check(st, ok=(GPD_OK,) if raise_on_fail else (GPD_OK, GPD_E_DECODE_FAIL))
     return C_out, (_read_report(rep, buf, plan.P, int(correct_errors) != GPD_CORRECT_NODES)
                    if rep is not None else None)
+
+
+def gpd_decode_static(plan: Plan, Ct, C_out, present=None, mode=GPD_DEC_FIRST_K, correct_errors=False,
+                      want_report=True, located_cap=4096, raise_on_fail=False):
+    """gpd_decode without a workspace: the library's fixed scratch array is used.  C_out must be
+    given (this call allocates nothing on the device).  Returns (C_out, Report or None)."""
+    import torch
+    lib = load_library()
+    _require_f32_cuda(Ct, "Ct")
+    sh = (plan.P, plan.N1 // plan.m, plan.Nc // plan.d)
+    if tuple(Ct.shape) != sh or not Ct.is_contiguous():
+        raise ValueError("Ct does not match the plan")
+    if tuple(C_out.shape) != (plan.N1, plan.Nc) or C_out.stride(1) != 1 or C_out.dtype != torch.float32:
+        raise ValueError("C_out does not match the plan")
+    pres = _present_array(present, plan.P)
+    rep = buf = None
+    if want_report:
+        rep, buf = _make_report(located_cap)
+    st = lib.gpd_decode_static(plan.handle, _ptr(Ct), _ptr(pres), mode, int(correct_errors),
+                               _ptr(C_out), C_out.stride(0), C.byref(rep) if rep is not None else None)
+    _check(st, ok=(GPD_OK,) if raise_on_fail else (GPD_OK, GPD_E_DECODE_FAIL))
+    return C_out, (_read_report(rep, buf, plan.P) if rep is not None else None)
 
 
 # ------------------------------------------------------------------ coded DNN layer

@@ -4,6 +4,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "gpd_internal.hpp"
@@ -530,6 +531,72 @@ extern "C" gpd_status_t gpd_verify_decode(const gpd_plan_t* plc, const float* Ct
   job.bh = pl->ahC; job.bw = pl->awC;
   job.rho = pl->rho; job.abs_floor = pl->abs_floor;
   return run_verify(pl->stream, job, Ct, present, mode, bad, C, ldc, n_check, workspace, workspace_bytes, report);
+}
+
+// ---------------------------------------------------------------- decode without a workspace argument
+
+namespace {
+
+// Scratch of gpd_decode_static: the same layout run_decode gives a caller's workspace (counters
+// and per-node counts, the screen's bit map, the list of located entries), sized for blocks of up
+// to kStaticMaxCodewords codewords and a list of kStaticLocCap entries.  Every GPU the library
+// runs on holds its own copy until the process ends.
+constexpr int64_t kStaticMaxCodewords = (int64_t)GPD_STATIC_MAX_CODEWORDS;
+constexpr int64_t kStaticLocCap = (int64_t)GPD_STATIC_LOCATED_CAP;
+constexpr int64_t kStaticFlagWords = (kStaticMaxCodewords + 63) / 64 + 8;
+constexpr size_t kStaticScratchBytes =
+    gpd::kHeaderBytes + ((size_t)kStaticFlagWords * 8 + 255) / 256 * 256 + (size_t)kStaticLocCap * sizeof(gpd_located_t);
+
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kStaticScratchBytes];
+
+// The array's address on the current device (the name `scratch` is a host-side stand-in, never
+// passed to a kernel): asked for once per device, with that device current, and kept.
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void* scratch_ptr[kMaxDevices] = {};
+
+gpd_status_t scratch_of_current_device(void** out) {
+  int dev = -1;
+  GPD_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(GPD_E_DEVICE, "gpd_decode_static: device index %d", dev);
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (!scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    GPD_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr || ((uintptr_t)ptr & 255)) return fail(GPD_E_DEVICE, "gpd_decode_static: bad scratch address");
+    scratch_ptr[dev] = ptr;
+  }
+  *out = scratch_ptr[dev];
+  return GPD_OK;
+}
+
+}  // namespace
+
+extern "C" gpd_status_t gpd_decode_static(const gpd_plan_t* plc, const float* Ct, const uint8_t* present,
+                                          int32_t mode, int32_t correct_errors, float* C, int64_t ldc,
+                                          gpd_report_t* report) {
+  gpd_plan_t* pl = const_cast<gpd_plan_t*>(plc);
+  if (!pl) return fail(GPD_E_INVALID, "gpd_decode_static: null plan");
+  if (correct_errors != GPD_CORRECT_NONE && correct_errors != GPD_CORRECT_ELEMENTS)
+    return fail(GPD_E_UNSUPPORTED, "gpd_decode_static: correct_errors must be GPD_CORRECT_NONE or "
+                                   "GPD_CORRECT_ELEMENTS (the node search needs a caller's workspace)");
+  const int64_t ncw = pl->ahC * pl->awC;
+  if (ncw > kStaticMaxCodewords)
+    return fail(GPD_E_WORKSPACE, "gpd_decode_static: blocks of %lld elements exceed the limit of %lld",
+                (long long)ncw, (long long)kStaticMaxCodewords);
+  void* ws = nullptr;
+  if (correct_errors != GPD_CORRECT_NONE) {
+    gpd_status_t st = scratch_of_current_device(&ws);
+    if (st != GPD_OK) return st;
+  }
+  DecodeJob job;
+  job.pts = &pl->code.pts; job.K = pl->code.K; job.useful = pl->code.eC;
+  job.grid_r = pl->code.m; job.grid_c = pl->code.d;
+  job.bh = pl->ahC; job.bw = pl->awC;
+  job.rho = pl->rho; job.abs_floor = pl->abs_floor;
+  job.flag_cap = kStaticFlagWords; job.loc_cap = kStaticLocCap; job.workspace_bytes = kStaticScratchBytes;
+  return run_decode(pl->stream, &pl->ring, job, Ct, present, mode, correct_errors, C, ldc,
+                    ws, ws ? kStaticScratchBytes : 0, report);
 }
 
 extern "C" gpd_status_t gpd_decode(const gpd_plan_t* plc, const float* Ct, const uint8_t* present,
