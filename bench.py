@@ -28,10 +28,24 @@ if ROOT not in sys.path:
 
 PEAK_FP32_MFMA_TFLOPS = 157.3     # MI355X published dense fp32 matrix peak
 PEAK_HBM_GBS = 8000.0             # MI355X published HBM3E bandwidth
-# HBM bytes per launch of the worker-product kernel on the default workload, from the committed
-# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/coded_matmul_4096_fp32.md):
-# 393672 KiB x 2.0 (copy-kernel calibration) fetched + 262144 KiB written
-GEMM_TRAFFIC_BYTES_CFG1 = (393520 * 2.0 + 262144) * 1024   # FETCH_SIZE x 2.0 + WRITE_SIZE, KiB per launch (profiles/coded_matmul_4096_fp32.md)
+
+
+def gemm_traffic_from_profile():
+    """HBM bytes per launch of the worker-product kernel on the default workload, from the committed
+    rocprofv3 --pmc summary: the line `traffic gemm_f32_kernel fetch_kib=<FETCH_SIZE> fetch_factor=<f>
+    write_kib=<WRITE_SIZE>` of profiles/coded_matmul_4096_fp32.md (counter readings in KiB per
+    dispatch, the fetch counter scaled by what it reads for a plain copy of known size).  None if
+    the file or the line is missing."""
+    import re
+    try:
+        text = open(os.path.join(ROOT, "profiles", "coded_matmul_4096_fp32.md")).read()
+    except OSError:
+        return None
+    mt = re.search(r"traffic gemm_f32_kernel fetch_kib=([0-9.]+) fetch_factor=([0-9.]+) write_kib=([0-9.]+)", text)
+    if not mt:
+        return None
+    fetch, factor, write = (float(x) for x in mt.groups())
+    return (fetch * factor + write) * 1024.0
 
 
 def cpu_baseline(cfg, n_threads):
@@ -142,7 +156,8 @@ def bench_faults(args, cfg):
     dev = "cuda:0"
     N1, N0, Nc, m, n, d, P = (cfg[k] for k in ("N1", "N0", "Nc", "m", "n", "d", "P"))
     A_h, B_h = WL.matmul_inputs(N1, N0, Nc, cfg["seed"])
-    plan = G.gpd_plan(N1, N0, Nc, m, n, d, P)
+    layout = G.GPD_LAYOUT_PACKED if args.layout == "packed" else G.GPD_LAYOUT_SPREAD
+    plan = G.gpd_plan(N1, N0, Nc, m, n, d, P, layout=layout)
     K = plan.K
     At, Bt = G.gpd_encode(plan, torch.from_numpy(A_h).to(dev), torch.from_numpy(B_h).to(dev))
     Ct = G.gpd_worker_products(plan, At, Bt)
@@ -186,6 +201,18 @@ def bench_faults(args, cfg):
         located[0] += rep.n_located
 
     ms_elem = timed(elements, flip, flip)
+    # the kernels of the same call, each timed on its own (clear + decode pass with the screen + locate)
+    G.gpd_timing_reset()
+    for t in range(args.steps):
+        flip(args.warmup + t)
+        G.gpd_timing_tag(1)
+        G.gpd_decode(plan, Ct, mode=G.GPD_DEC_LSQ_ALL, correct_errors=G.GPD_CORRECT_ELEMENTS, workspace=ws, C_out=C,
+                     want_report=False)
+        G.gpd_timing_tag(-1)
+        flip(args.warmup + t)
+    ms_elem_kernels, n_k = G.gpd_timing_collect(1)
+    ms_elem_kernels /= args.steps
+    G.gpd_timing_reset()
     ms_elem_async = timed(lambda t: G.gpd_decode(plan, Ct, mode=G.GPD_DEC_LSQ_ALL,
                                                  correct_errors=G.GPD_CORRECT_ELEMENTS, workspace=ws, C_out=C,
                                                  want_report=False), flip, flip)
@@ -198,7 +225,7 @@ def bench_faults(args, cfg):
     em_idx = torch.from_numpy(np.repeat(cw_many, t_many)).to(dev)
     vm = torch.from_numpy((rngm.choice([-1.0, 1.0], n_many * t_many) *
                            rngm.uniform(50.0, 200.0, n_many * t_many)).astype(np.float32)).to(dev)
-    Ctm = Ct.clone()
+    Ctm = plan.clone_stack(Ct)
     Ctm.view(P, -1)[pm_idx, em_idx] += vm
     many_rep = [None]
 
@@ -277,6 +304,8 @@ def bench_faults(args, cfg):
            "decode_screen_correct": {"ms": ms_elem, "GBps": gb(4.0 * blk * (P + m * d), ms_elem),
                                      "located_total": located[0],
                                      "note": "with the host report (stream wait + copies)",
+                                     "ms_kernels_only": ms_elem_kernels, "kernels_per_call": n_k / args.steps,
+                                     "GBps_kernels_only": gb(4.0 * blk * (P + m * d), ms_elem_kernels),
                                      "ms_without_report": ms_elem_async,
                                      "GBps_without_report": gb(4.0 * blk * (P + m * d), ms_elem_async)},
            "decode_screen_correct_many": {"ms": ms_many, "ms_without_report": ms_many_async,
@@ -308,6 +337,8 @@ def main():
                     help="workload index: 0/1 coded matmul (1 = headline), 2/3 coded MLP training, "
                          "4 soft-error and node-fault paths")
     ap.add_argument("--graph", action="store_true", help="(MLP workloads) replay the step as a HIP graph")
+    ap.add_argument("--layout", choices=("spread", "packed"), default="spread",
+                    help="(matmul workloads) how the node blocks of At, Bt, Ct lie in memory")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 256 MiB device copy 5 times (reference for scaling the "
@@ -347,14 +378,13 @@ def main():
         return
     cfg.setdefault("trial_seed0", 1000)
     N1, N0, Nc, m, n, d, P = (cfg[k] for k in ("N1", "N0", "Nc", "m", "n", "d", "P"))
+    layout = G.GPD_LAYOUT_PACKED if args.layout == "packed" else G.GPD_LAYOUT_SPREAD
 
     A_h, B_h = WL.matmul_inputs(N1, N0, Nc, cfg["seed"])
     A, B = torch.from_numpy(A_h).to(dev), torch.from_numpy(B_h).to(dev)
-    plan = G.gpd_plan(N1, N0, Nc, m, n, d, P)
+    plan = G.gpd_plan(N1, N0, Nc, m, n, d, P, layout=layout)
     K = plan.K
-    At = torch.empty((P, N1 // m, N0 // n), dtype=torch.float32, device=dev)
-    Bt = torch.empty((P, N0 // n, Nc // d), dtype=torch.float32, device=dev)
-    Ct = torch.empty((P, N1 // m, Nc // d), dtype=torch.float32, device=dev)
+    At, Bt, Ct = (plan.alloc_stack(w, dev) for w in "ABC")
     C = torch.empty((N1, Nc), dtype=torch.float32, device=dev)
     masks = [WL.erasure_trial(cfg["trial_seed0"] + t, P, P - K) for t in range(args.warmup + args.steps)]
 
@@ -367,20 +397,53 @@ def main():
         G.gpd_decode(plan, Ct, present=masks[t], mode=G.GPD_DEC_FIRST_K, C_out=C, want_report=False)
         if ev: ev[3].record()
 
+    # ---- the timed region: exactly `steps` whole steps, nothing else on the stream
     for t in range(args.warmup):
         step(t)
     torch.cuda.synchronize()
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     t0 = time.perf_counter()
+    for t in range(args.steps):
+        step(args.warmup + t)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_step = (t1 - t0) * 1e3 / args.steps
+
+    # ---- the same steps once more with events between the stages (the library's stream is torch's
+    # current stream, which is the one the events are recorded on); an event between two kernels
+    # costs the stream a few microseconds, so these stage times are upper bounds
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     for t in range(args.steps):
         step(args.warmup + t, evs[t])
     torch.cuda.synchronize()
-    t1 = time.perf_counter()
-
-    ms_step = (t1 - t0) * 1e3 / args.steps
     enc_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
     gemm_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in evs]))
     dec_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in evs]))
+
+    # ---- the same steps with every kernel launch of the library timed on its own (a pair of events
+    # attached to each dispatch, as a profiler does: nothing is put between two kernels)
+    G.gpd_timing_reset()
+
+    def step_timed(t):
+        G.gpd_timing_tag(1)
+        G.gpd_encode(plan, A, B, At, Bt)
+        G.gpd_timing_tag(2)
+        G.gpd_worker_products(plan, At, Bt, Ct)
+        G.gpd_timing_tag(3)
+        G.gpd_decode(plan, Ct, present=masks[t], mode=G.GPD_DEC_FIRST_K, C_out=C, want_report=False)
+        G.gpd_timing_tag(-1)
+
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(args.steps):
+        step_timed(args.warmup + t)
+    torch.cuda.synchronize()
+    ms_step_timed = (time.perf_counter() - t0) * 1e3 / args.steps
+    kernel_ms = {}
+    for tag, name in ((1, "encode"), (2, "worker_products"), (3, "decode")):
+        total, count = G.gpd_timing_collect(tag)
+        kernel_ms[name] = {"ms": total / args.steps, "launches_per_step": count / args.steps}
+    G.gpd_timing_reset()
+    enc_k_ms, gemm_k_ms, dec_k_ms = (kernel_ms[k]["ms"] for k in ("encode", "worker_products", "decode"))
 
     useful_flops = 2.0 * N1 * N0 * Nc
     worker_flops = 2.0 * P * (N1 // m) * (N0 // n) * (Nc // d)
@@ -388,7 +451,8 @@ def main():
     enc_bytes = 4.0 * (N1 * N0 * (1 + P / (m * n)) + N0 * Nc * (1 + P / (n * d)))
     dec_bytes = 4.0 * blkC * (K + m * d)
     value = useful_flops / (ms_step * 1e-3) / 1e12
-    achieved = worker_flops / (gemm_ms * 1e-3) / 1e12
+    achieved = worker_flops / (gemm_k_ms * 1e-3) / 1e12
+    gbs = lambda b, ms: b / (ms * 1e-3) / 1e9
 
     out = {
         "metric": "effective coded GEMM TFLOP/s (encode+P products+decode)",
@@ -397,26 +461,36 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"coded matmul with erasures: A {N1}x{N0}, B {N0}x{Nc} fp32 U[-1,1], "
                                f"m={m} n={n} d={d} P={P} K={K}, {P - K} seeded stragglers per step, "
-                               f"decode from the first K present nodes"},
-        "stages_ms": {"encode": enc_ms, "worker_products": gemm_ms, "decode": dec_ms},
-        "encode_GBps": enc_bytes / (enc_ms * 1e-3) / 1e9,
-        "decode_GBps": dec_bytes / (dec_ms * 1e-3) / 1e9,
+                               f"decode from the first K present nodes",
+                   "stack_layout": args.layout},
+        "stages_ms": {"encode": enc_ms, "worker_products": gemm_ms, "decode": dec_ms,
+                      "note": "one event recorded between two stages (costs the stream a few microseconds per "
+                              "event); encode = two launches (A, B)"},
+        "kernel_ms": dict(kernel_ms, ms_per_step_while_timed=ms_step_timed,
+                          note="every launch timed on its own by events attached to the dispatch, inside the "
+                               "running pipeline; summed per stage and averaged over the steps"),
+        "encode_GBps": gbs(enc_bytes, enc_k_ms),
+        "decode_GBps": gbs(dec_bytes, dec_k_ms),
         "worker_TFLOPs": achieved,
         "roofline": {"kernel": "gemm_f32_kernel (batched worker products)", "bound": "mfma",
                      "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
-                     "traffic": GEMM_TRAFFIC_BYTES_CFG1 if args.config == 1 else None},
+                     "traffic": gemm_traffic_from_profile() if args.config == 1 else None},
         "roofline_hbm": {
-            "encode": {"achieved": enc_bytes / (enc_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                       "frac": enc_bytes / (enc_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
-            "decode": {"achieved": dec_bytes / (dec_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                       "frac": dec_bytes / (dec_ms * 1e-3) / 1e9 / PEAK_HBM_GBS}},
+            "encode": {"kernel": "combine_kernel (A and B: two launches)", "bound": "hbm",
+                       "achieved": gbs(enc_bytes, enc_k_ms), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                       "frac": gbs(enc_bytes, enc_k_ms) / PEAK_HBM_GBS,
+                       "frac_between_stage_events": gbs(enc_bytes, enc_ms) / PEAK_HBM_GBS},
+            "decode": {"kernel": "combine_kernel (first K of the present nodes, new erasure pattern every step)",
+                       "bound": "hbm", "achieved": gbs(dec_bytes, dec_k_ms), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                       "frac": gbs(dec_bytes, dec_k_ms) / PEAK_HBM_GBS,
+                       "frac_between_stage_events": gbs(dec_bytes, dec_ms) / PEAK_HBM_GBS}},
     }
 
     # The same job with the worker products on the bf16 matrix cores, every fp32 operand written as
     # the sum of three bf16 values (six partial products: fp32-level accuracy).  Extra evidence
     # beside the headline, which stays on the fp32 matrix cores.
-    plan_s = G.gpd_plan(N1, N0, Nc, m, n, d, P, worker_dtype=G.GPD_F32_SPLIT)
+    plan_s = G.gpd_plan(N1, N0, Nc, m, n, d, P, worker_dtype=G.GPD_F32_SPLIT, layout=layout)
 
     def step_split(t):
         G.gpd_encode(plan_s, A, B, At, Bt)
@@ -470,6 +544,20 @@ def main():
         torch.cuda.synchronize()
         got = C.cpu().numpy().astype(np.float64)
         out["split_bf16x3"]["rel_err_vs_oracle"] = float(np.linalg.norm(got - C_oracle) / np.linalg.norm(C_oracle))
+        # every erasure pattern of the timed steps against the definition A.B (the oracle's fp64
+        # product): how many meet the 1e-3 bar, and the worst (some sets of 9 of the 16 Chebyshev
+        # points have decoding rows of norm 1e4 to 3e5: fp32 responses cannot meet the bar there)
+        from oracle import gpd_oracle as O
+        C_def = torch.from_numpy(O.uncoded_matmul(A_h, B_h).astype(np.float32)).to(dev)
+        den = float(torch.linalg.norm(C_def.double()))
+        step(0)
+        errs = []
+        for t in range(args.warmup, args.warmup + args.steps):
+            G.gpd_decode(plan, Ct, present=masks[t], mode=G.GPD_DEC_FIRST_K, C_out=C, want_report=False)
+            errs.append(float(torch.linalg.norm((C - C_def).double())) / den)
+        out["accuracy_over_timed_masks"] = {"trials": len(errs), "trials_within_1e-3": int(sum(e <= 1e-3 for e in errs)),
+                                            "worst_rel_err": max(errs), "median_rel_err": float(np.median(errs)),
+                                            "reference": "fp64 A.B"}
     print(json.dumps(out), flush=True)
 
 

@@ -16,7 +16,8 @@
  *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are
  *     ordinary host memory owned by the caller.  The library owns only the opaque
  *     plan / layer objects and their small coefficient tables.
- *   - Coded stacks are contiguous [P][rows][cols]; fp32 unless stated.
+ *   - Coded stacks are [P][rows][cols], contiguous unless the plan asks for GPD_LAYOUT_SPREAD;
+ *     fp32 unless stated.
  *   - Calls enqueue work on the stream given at plan creation and return without
  *     waiting, except where a host-side report is requested (then the call waits for the
  *     stream before returning).
@@ -81,6 +82,18 @@ typedef enum {
                                output is wrong (error models of Sec. III); see gpd_locate_nodes */
 } gpd_correct_t;
 
+/* How the P blocks of a coded stack (At, Bt, Ct of a matmul plan) lie in memory.
+ *   GPD_LAYOUT_PACKED: contiguous [P][rows][cols]: node p's block starts rows * cols elements
+ *                      after node p-1's.
+ *   GPD_LAYOUT_SPREAD: node p's block starts `stride` elements after node p-1's, with stride =
+ *                      rows * cols plus a pad of a few tens of KB chosen by the library
+ *                      (gpd_plan_strides): encode and decode read or write all P blocks at the same
+ *                      offset at the same time, and blocks a power of two apart put those P
+ *                      streams on the same memory channels.  The caller allocates
+ *                      (P - 1) * stride + rows * cols elements (P * stride is fine); the pad
+ *                      between two blocks is never read or written. */
+typedef enum { GPD_LAYOUT_PACKED = 0, GPD_LAYOUT_SPREAD = 1 } gpd_layout_t;
+
 typedef struct gpd_plan gpd_plan_t;
 typedef struct gpd_layer gpd_layer_t;
 
@@ -99,6 +112,7 @@ typedef struct {
   double abs_floor;         /* tau(z) = rho * max(||z||_2, abs_floor)                       */
   void* hip_stream;         /* hipStream_t all work of this plan is enqueued on (0 = null
                                stream)                                                     */
+  int32_t stack_layout;     /* gpd_layout_t of At, Bt and Ct                               */
 } gpd_problem_t;
 
 /* Code construction (Sec. IV, Thm 2): exponent tables, K, evaluation points, coefficient
@@ -112,6 +126,11 @@ gpd_status_t gpd_plan(const gpd_problem_t* problem, gpd_plan_t** out);
 gpd_status_t gpd_plan_info(const gpd_plan_t* plan, int32_t* K, int32_t* t_max,
                            size_t* workspace_bytes);
 
+/* Elements (of the stack's own type) between the blocks of consecutive nodes in At, Bt and Ct:
+ * rows * cols for GPD_LAYOUT_PACKED, more for GPD_LAYOUT_SPREAD.  Any pointer may be NULL. */
+gpd_status_t gpd_plan_strides(const gpd_plan_t* plan, int64_t* strideA, int64_t* strideB,
+                              int64_t* strideC);
+
 /* Copies the P evaluation points (fp64) and the exponents of the blocks of A (m*n, row-major
  * over (i,j)), of B (n*d over (j,k)) and the useful exponents of C (m*d over (i,k)) to host
  * arrays; any pointer may be NULL. */
@@ -121,7 +140,7 @@ gpd_status_t gpd_plan_tables(const gpd_plan_t* plan, double* points, int32_t* eA
 void gpd_plan_destroy(gpd_plan_t* plan);
 
 /* Encode (Sec. IV, equations for W~(u,v) and X~(v,w)):
- *   At[p] = sum_{i,j} b_p^eA(i,j) A_{i,j}      At: device [P][N1/m][N0/n]
+ *   At[p] = sum_{i,j} b_p^eA(i,j) A_{i,j}      At: device [P][N1/m][N0/n] (node stride: gpd_plan_strides)
  *   Bt[p] = sum_{j,k} b_p^eB(j,k) B_{j,k}      Bt: device [P][N0/n][Nc/d]
  * A, B: device fp32, leading dimensions lda, ldb.  Either pair (A, At) or (B, Bt) may be
  * NULL to skip it.  At/Bt hold fp32 or bf16 (round-to-nearest-even) per worker_dtype. */
@@ -352,7 +371,9 @@ gpd_status_t gpd_coded_layer_step(gpd_layer_t* layer, int32_t phase, float* Wt,
  *                  lo = bf16(v - hi - mid) (round to nearest even);
  *   GPD_BF16:      each value v as two fp16 values of w = v / 2^E: hi = fp16(w), lo = fp16(w - hi);
  *                  which = 6 gives the two exponents (int32 E of Dhat, E of Xhat; rows = 1,
- *                  cols = 2) of the last BACKWARD_UPDATE call, and fails on any other layer. */
+ *                  cols = 2) of the last BACKWARD_UPDATE call, and fails on any other layer.
+ * which = 7: the error Delta of this layer as gpd_mlp_step left it: one fp32 matrix (not a stack),
+ * rows = N_out padded up to a multiple of m, cols = batch. */
 gpd_status_t gpd_layer_workspace_view(const gpd_layer_t* layer, int32_t which, size_t* byte_offset,
                                       int64_t* rows, int64_t* cols);
 
@@ -385,6 +406,27 @@ gpd_status_t gpd_layer_regenerate(const gpd_layer_t* layer, float* Wt, const uin
  * the rounding drift of many coded updates that the decoder would not see anyway and
  * regenerates absent nodes.  Asynchronous. */
 gpd_status_t gpd_layer_project(const gpd_layer_t* layer, float* Wt, const uint8_t* present);
+
+/* One whole training iteration of a multi-layer network of coded layers with logistic activations
+ * and the L2 loss (Sec. VII: for every layer, first to last, steps O1 and C1; the last layer's error
+ * 2 (y - yhat) f'(s) / batch; then for every layer, last to first, steps O2 and O3 in one pass over
+ * the coded weights and step C2), for the small-batch path: batch 1, 2, 4 or 8, d1 = d2 = 1, fp32
+ * workers, all P nodes present, no error correction, every layer on the same stream, N_in of a
+ * layer = N_out of the layer before.  Anything else returns GPD_E_UNSUPPORTED or GPD_E_SHAPE and
+ * nothing is launched: the caller then strings gpd_coded_layer_step calls together.
+ * What the master does between two coded products (decoding, the element-wise step, the encoding
+ * of the next product's operands) is one launch instead of four or five; the arithmetic is that of
+ * the per-layer calls, operation for operation, so both leave the same bits in the coded weights.
+ *   layers, Wt, acts, workspaces, workspace_bytes: host arrays of n_layers entries.
+ *   Wt[l]:    device, the coded weights of layer l, updated in place.
+ *   X, Y:     device fp32, N_in(0) x batch inputs and N_out(last) x batch targets.
+ *   acts[l]:  device fp32 N_out(l) x batch, written: the output of layer l (acts[last] is the
+ *             network output).
+ *   workspaces[l]: device, 256-byte aligned, workspace_bytes[l] >= what gpd_layer_info gives.
+ * Asynchronous. */
+gpd_status_t gpd_mlp_step(gpd_layer_t* const* layers, int32_t n_layers, float* const* Wt,
+                          const float* X, const float* Y, float eta, float decay,
+                          float* const* acts, void* const* workspaces, const size_t* workspace_bytes);
 
 void gpd_layer_destroy(gpd_layer_t* layer);
 
@@ -440,6 +482,17 @@ gpd_status_t gpd_host_locate_nodes(int32_t P, int32_t K, const double* points,
                                    const uint8_t* forced, gpd_node_report_t* report);
 
 /* ------------------------------------------------------------------ misc */
+
+/* Durations of the library's own kernel launches, one by one, for measurements inside a running
+ * pipeline: while a tag >= 0 is set, every kernel any entry point launches carries its own pair of
+ * HIP events on its stream (start and stop of that one dispatch: nothing is added between two
+ * kernels, unlike an event recorded between them) and is filed under the tag; tag < 0 turns the
+ * recording off.  gpd_timing_collect waits for the recorded kernels of one tag and returns the sum
+ * of their durations in milliseconds and their number; gpd_timing_reset forgets all recordings (at
+ * most 16384 launches are kept between two resets; further ones run untimed).  Process-wide. */
+gpd_status_t gpd_timing_tag(int32_t tag);
+gpd_status_t gpd_timing_collect(int32_t tag, double* total_ms, int32_t* launches);
+gpd_status_t gpd_timing_reset(void);
 
 const char* gpd_last_error(void);     /* thread-local, never NULL */
 const char* gpd_version(void);

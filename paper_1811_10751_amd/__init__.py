@@ -8,4 +8,4 @@ from .binding import (GpdError, Layer, Plan, Report, load_library, gpd_coded_lay
                       NodeReport, gpd_locate_nodes, gpd_layer_locate_nodes, gpd_layer_regenerate,
                       gpd_layer_project, gpd_host_parity_check, gpd_host_locate_nodes,
                       VerifyReport, gpd_verify_decode, gpd_row_mean, gpd_sigmoid_bwd_sparse,
-                      gpd_decode_static)
+                      gpd_decode_static, gpd_timing_tag, gpd_timing_collect, gpd_timing_reset, gpd_mlp_step)

@@ -25,12 +25,13 @@ GPD_STEP_FORWARD, GPD_STEP_BACKWARD_UPDATE = 0, 1
 GPD_STEP_FUSE_SIGMOID = 0x100
 GPD_CORRECT_NONE, GPD_CORRECT_ELEMENTS, GPD_CORRECT_NODES = 0, 1, 2
 GPD_STACK_WEIGHTS, GPD_STACK_FORWARD, GPD_STACK_BACKWARD = 0, 1, 2
+GPD_LAYOUT_PACKED, GPD_LAYOUT_SPREAD = 0, 1
 
 STATUS_NAMES = ["OK", "E_INVALID", "E_SHAPE", "E_POINTS", "E_TOO_FEW", "E_DECODE_FAIL",
                 "E_WORKSPACE", "E_DEVICE", "E_UNSUPPORTED", "E_VERIFY"]
 
 EXPORTS = [
-    "gpd_plan", "gpd_plan_info", "gpd_plan_tables", "gpd_plan_destroy", "gpd_encode",
+    "gpd_plan", "gpd_plan_info", "gpd_plan_strides", "gpd_plan_tables", "gpd_plan_destroy", "gpd_encode",
     "gpd_worker_products", "gpd_decode", "gpd_layer_create", "gpd_layer_info",
     "gpd_layer_encode_weights", "gpd_layer_decode_weights", "gpd_coded_layer_step",
     "gpd_layer_workspace_view", "gpd_layer_destroy", "gpd_sigmoid_fwd", "gpd_sigmoid_bwd", "gpd_l2_delta",
@@ -38,6 +39,7 @@ EXPORTS = [
     "gpd_locate_nodes", "gpd_layer_locate_nodes", "gpd_layer_regenerate", "gpd_layer_project",
     "gpd_host_parity_check", "gpd_host_locate_nodes", "gpd_verify_decode",
     "gpd_row_mean", "gpd_sigmoid_bwd_sparse", "gpd_decode_static",
+    "gpd_timing_tag", "gpd_timing_collect", "gpd_timing_reset", "gpd_mlp_step",
 ]
 
 
@@ -53,7 +55,7 @@ class _Problem(C.Structure):
                 ("points", C.POINTER(C.c_double)),
                 ("worker_dtype", C.c_int32), ("subst", C.c_int32),
                 ("rho_detect", C.c_double), ("abs_floor", C.c_double),
-                ("hip_stream", C.c_void_p)]
+                ("hip_stream", C.c_void_p), ("stack_layout", C.c_int32)]
 
 
 class _Located(C.Structure):
@@ -106,6 +108,7 @@ def load_library():
     vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
     lib.gpd_plan.argtypes = [C.POINTER(_Problem), C.POINTER(vp)]
     lib.gpd_plan_info.argtypes = [vp, C.POINTER(i32), C.POINTER(i32), C.POINTER(sz)]
+    lib.gpd_plan_strides.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
     lib.gpd_plan_tables.argtypes = [vp, vp, vp, vp, vp]
     lib.gpd_plan_destroy.argtypes = [vp]
     lib.gpd_plan_destroy.restype = None
@@ -139,6 +142,11 @@ def load_library():
     lib.gpd_host_locate_nodes.argtypes = [i32, i32, vp, vp, vp, C.c_double, i64, C.c_double, C.c_double,
                                           vp, C.POINTER(_NodeReport)]
     lib.gpd_verify_decode.argtypes = [vp, vp, vp, i32, vp, vp, i64, i32, vp, sz, C.POINTER(_VerifyReport)]
+    lib.gpd_mlp_step.argtypes = [C.POINTER(vp), i32, C.POINTER(vp), vp, vp, C.c_float, C.c_float,
+                                 C.POINTER(vp), C.POINTER(vp), C.POINTER(sz)]
+    lib.gpd_timing_tag.argtypes = [i32]
+    lib.gpd_timing_collect.argtypes = [i32, C.POINTER(C.c_double), C.POINTER(i32)]
+    lib.gpd_timing_reset.argtypes = []
     lib.gpd_last_error.restype = C.c_char_p
     lib.gpd_version.restype = C.c_char_p
     for name in EXPORTS:
@@ -231,6 +239,42 @@ class Plan:
         self.m, self.n, self.d, self.P = problem.m, problem.n, problem.d, problem.P
         self.N1, self.N0, self.Nc = problem.N1, problem.N0, problem.Nc
         self.worker_dtype = problem.worker_dtype
+        sa, sb, sc = C.c_int64(), C.c_int64(), C.c_int64()
+        _check(lib.gpd_plan_strides(handle, C.byref(sa), C.byref(sb), C.byref(sc)))
+        self.strides = {"A": sa.value, "B": sb.value, "C": sc.value}
+        self.layout = problem.stack_layout
+
+    def stack_shape(self, which):
+        return {"A": (self.P, self.N1 // self.m, self.N0 // self.n),
+                "B": (self.P, self.N0 // self.n, self.Nc // self.d),
+                "C": (self.P, self.N1 // self.m, self.Nc // self.d)}[which]
+
+    def alloc_stack(self, which, device, dtype=None):
+        """Uninitialised coded stack At ("A"), Bt ("B") or Ct ("C") in the plan's layout: a
+        [P, rows, cols] view whose node blocks lie the plan's stride apart."""
+        import torch
+        if dtype is None:
+            dtype = torch.float32 if which == "C" or self.worker_dtype != GPD_BF16 else torch.bfloat16
+        P, rows, cols = self.stack_shape(which)
+        stride = self.strides[which]
+        base = torch.empty(max(P * stride, 1), dtype=dtype, device=device)
+        return base.as_strided((P, rows, cols), (stride, cols, 1))
+
+    def clone_stack(self, t, which="C"):
+        """A copy of the coded stack t in the plan's layout (torch's clone would pack it)."""
+        out = self.alloc_stack(which, t.device, t.dtype)
+        out.copy_(t)
+        return out
+
+    def stack_ok(self, t, which):
+        """True if tensor t is a coded stack of this plan: shape and node stride match."""
+        P, rows, cols = self.stack_shape(which)
+        if tuple(t.shape) != (P, rows, cols):
+            return False
+        if rows * cols == 0:
+            return True
+        want = (self.strides[which], cols, 1)
+        return all(t.shape[i] == 1 or t.stride(i) == want[i] for i in range(3))
 
     def tables(self):
         lib = load_library()
@@ -255,7 +299,7 @@ class Plan:
 
 
 def gpd_plan(N1, N0, Nc, m, n, d, P, points=None, worker_dtype=GPD_F32, subst=GPD_SUB_AUTO,
-             rho_detect=0.0, abs_floor=0.0, stream=None) -> Plan:
+             rho_detect=0.0, abs_floor=0.0, stream=None, layout=GPD_LAYOUT_PACKED) -> Plan:
     lib = load_library()
     pr = _Problem()
     pr.N1, pr.N0, pr.Nc, pr.m, pr.n, pr.d, pr.P = N1, N0, Nc, m, n, d, P
@@ -268,6 +312,7 @@ def gpd_plan(N1, N0, Nc, m, n, d, P, points=None, worker_dtype=GPD_F32, subst=GP
     pr.worker_dtype, pr.subst = worker_dtype, subst
     pr.rho_detect, pr.abs_floor = rho_detect, abs_floor
     pr.hip_stream = _stream_handle(stream)
+    pr.stack_layout = layout
     h = C.c_void_p()
     _check(lib.gpd_plan(C.byref(pr), C.byref(h)))
     return Plan(h, pr, keep)
@@ -285,17 +330,17 @@ def gpd_encode(plan: Plan, A=None, B=None, At=None, Bt=None):
             raise ValueError("A must be N1 x N0 with unit column stride")
         lda = A.stride(0)
         if At is None:
-            At = torch.empty((plan.P, plan.N1 // plan.m, plan.N0 // plan.n), dtype=dt, device=A.device)
+            At = plan.alloc_stack("A", A.device, dt)
     if B is not None:
         _require_f32_cuda(B, "B")
         if B.dim() != 2 or B.shape != (plan.N0, plan.Nc) or B.stride(1) != 1:
             raise ValueError("B must be N0 x Nc with unit column stride")
         ldb = B.stride(0)
         if Bt is None:
-            Bt = torch.empty((plan.P, plan.N0 // plan.n, plan.Nc // plan.d), dtype=dt, device=B.device)
-    for t in (At, Bt):
-        if t is not None and (not t.is_contiguous() or t.dtype != dt):
-            raise ValueError("coded stacks must be contiguous and of the worker dtype")
+            Bt = plan.alloc_stack("B", B.device, dt)
+    for t, which in ((At, "A"), (Bt, "B")):
+        if t is not None and (not plan.stack_ok(t, which) or t.dtype != dt):
+            raise ValueError("coded stacks must have the plan's layout and the worker dtype")
     _check(lib.gpd_encode(plan.handle, _ptr(A), lda, _ptr(B), ldb,
                           _ptr(At) if A is not None else None, _ptr(Bt) if B is not None else None))
     return At, Bt
@@ -305,14 +350,11 @@ def gpd_worker_products(plan: Plan, At, Bt, Ct=None):
     import torch
     lib = load_library()
     dt = torch.bfloat16 if plan.worker_dtype == GPD_BF16 else torch.float32
-    shA = (plan.P, plan.N1 // plan.m, plan.N0 // plan.n)
-    shB = (plan.P, plan.N0 // plan.n, plan.Nc // plan.d)
-    if tuple(At.shape) != shA or tuple(Bt.shape) != shB or At.dtype != dt or Bt.dtype != dt \
-            or not At.is_contiguous() or not Bt.is_contiguous():
+    if At.dtype != dt or Bt.dtype != dt or not plan.stack_ok(At, "A") or not plan.stack_ok(Bt, "B"):
         raise ValueError("At/Bt do not match the plan")
     if Ct is None:
-        Ct = torch.empty((plan.P, shA[1], shB[2]), dtype=torch.float32, device=At.device)
-    elif tuple(Ct.shape) != (plan.P, shA[1], shB[2]) or Ct.dtype != torch.float32 or not Ct.is_contiguous():
+        Ct = plan.alloc_stack("C", At.device)
+    elif Ct.dtype != torch.float32 or not plan.stack_ok(Ct, "C"):
         raise ValueError("Ct does not match the plan")
     _check(lib.gpd_worker_products(plan.handle, _ptr(At), _ptr(Bt), _ptr(Ct)))
     return Ct
@@ -324,9 +366,8 @@ def gpd_decode(plan: Plan, Ct, present=None, mode=GPD_DEC_FIRST_K, correct_error
     import torch
     lib = load_library()
     _require_f32_cuda(Ct, "Ct")
-    sh = (plan.P, plan.N1 // plan.m, plan.Nc // plan.d)
-    if tuple(Ct.shape) != sh or not Ct.is_contiguous():
-        raise ValueError("Ct does not match the plan")
+    if not plan.stack_ok(Ct, "C"):
+        raise ValueError("Ct does not match the plan (shape or node stride)")
     if C_out is None:
         C_out = torch.empty((plan.N1, plan.Nc), dtype=torch.float32, device=Ct.device)
     elif tuple(C_out.shape) != (plan.N1, plan.Nc) or C_out.stride(1) != 1 or C_out.dtype != torch.float32:
@@ -355,9 +396,8 @@ def gpd_decode_static(plan: Plan, Ct, C_out, present=None, mode=GPD_DEC_FIRST_K,
     import torch
     lib = load_library()
     _require_f32_cuda(Ct, "Ct")
-    sh = (plan.P, plan.N1 // plan.m, plan.Nc // plan.d)
-    if tuple(Ct.shape) != sh or not Ct.is_contiguous():
-        raise ValueError("Ct does not match the plan")
+    if not plan.stack_ok(Ct, "C"):
+        raise ValueError("Ct does not match the plan (shape or node stride)")
     if tuple(C_out.shape) != (plan.N1, plan.Nc) or C_out.stride(1) != 1 or C_out.dtype != torch.float32:
         raise ValueError("C_out does not match the plan")
     pres = _present_array(present, plan.P)
@@ -417,6 +457,14 @@ class Layer:
             # three bf16 planes (hi, mid, lo), each [P][cols/16][rows][16]
             return ws[off.value:off.value + 6 * n].view(torch.bfloat16).view(3, self.P, c.value // 16, r.value, 16)
         return ws[off.value:off.value + 4 * n].view(torch.float32).view(self.P, r.value, c.value)
+
+    def workspace_delta(self, device):
+        """The error Delta of this layer (N_out x batch) where gpd_mlp_step leaves it."""
+        import torch
+        off, r, c = C.c_size_t(), C.c_int64(), C.c_int64()
+        _check(load_library().gpd_layer_workspace_view(self.handle, 7, C.byref(off), C.byref(r), C.byref(c)))
+        ws = self.workspace(device)
+        return ws[off.value:off.value + 4 * r.value * c.value].view(torch.float32).view(r.value, c.value)[:self.N_out]
 
     def close(self):
         if self.handle:
@@ -504,6 +552,36 @@ def gpd_coded_layer_step(layer: Layer, phase, Wt, X, Dlt=None, eta=0.0, decay=0.
                  if rep is not None else None)
 
 
+def gpd_mlp_step(layers, Wts, X, Y, eta, decay, acts):
+    """One whole training iteration of the network `layers` on the small-batch path (see gpd.h).
+    acts: list of float32 CUDA tensors N_out(l) x batch, written.  Returns False, launching
+    nothing, if the network is outside what the fused path covers."""
+    lib = load_library()
+    n = len(layers)
+    _require_f32_cuda(X, "X")
+    _require_f32_cuda(Y, "Y")
+    if tuple(X.shape) != (layers[0].N_in, layers[0].batch) or not X.is_contiguous():
+        raise ValueError("X must be contiguous N_in x batch")
+    if tuple(Y.shape) != (layers[-1].N_out, layers[-1].batch) or not Y.is_contiguous():
+        raise ValueError("Y must be contiguous N_out x batch")
+    for L, Wt, a in zip(layers, Wts, acts):
+        _require_f32_cuda(Wt, "Wt")
+        _require_f32_cuda(a, "acts")
+        if tuple(Wt.shape) != (L.P, L.wt_rows, L.wt_cols) or not Wt.is_contiguous():
+            raise ValueError("Wt does not match the layer")
+        if tuple(a.shape) != (L.N_out, L.batch) or not a.is_contiguous():
+            raise ValueError("acts[l] must be contiguous N_out x batch")
+    wss = [L.workspace(X.device) for L in layers]
+    arr = lambda vals: (C.c_void_p * n)(*vals)
+    st = lib.gpd_mlp_step(arr([L.handle.value for L in layers]), n, arr([w.data_ptr() for w in Wts]),
+                          _ptr(X), _ptr(Y), eta, decay, arr([a.data_ptr() for a in acts]),
+                          arr([w.data_ptr() for w in wss]), (C.c_size_t * n)(*[w.numel() for w in wss]))
+    if st in (GPD_E_UNSUPPORTED, GPD_E_SHAPE):
+        return False
+    _check(st)
+    return True
+
+
 # ------------------------------------------------------------------ node-level faults
 
 
@@ -538,9 +616,8 @@ def gpd_locate_nodes(plan: Plan, Ct, present=None, workspace=None, want_gram=Fal
     import torch
     lib = load_library()
     _require_f32_cuda(Ct, "Ct")
-    sh = (plan.P, plan.N1 // plan.m, plan.Nc // plan.d)
-    if tuple(Ct.shape) != sh or not Ct.is_contiguous():
-        raise ValueError("Ct does not match the plan")
+    if not plan.stack_ok(Ct, "C"):
+        raise ValueError("Ct does not match the plan (shape or node stride)")
     if workspace is None:
         workspace = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device=Ct.device)
     pres = _present_array(present, plan.P)
@@ -571,9 +648,8 @@ def gpd_verify_decode(plan: Plan, Ct, C_dec, present=None, mode=GPD_DEC_FIRST_K,
     lib = load_library()
     _require_f32_cuda(Ct, "Ct")
     _require_f32_cuda(C_dec, "C")
-    sh = (plan.P, plan.N1 // plan.m, plan.Nc // plan.d)
-    if tuple(Ct.shape) != sh or not Ct.is_contiguous():
-        raise ValueError("Ct does not match the plan")
+    if not plan.stack_ok(Ct, "C"):
+        raise ValueError("Ct does not match the plan (shape or node stride)")
     if tuple(C_dec.shape) != (plan.N1, plan.Nc) or C_dec.stride(1) != 1:
         raise ValueError("C does not match the plan")
     if workspace is None:
@@ -747,6 +823,22 @@ def gpd_host_decode_matrices(m, n, d, P, subst=GPD_SUB_AUTO, points=None, presen
     _check(lib.gpd_host_decode_matrices(m, n, d, P, subst, _ptr(pin), _ptr(pres), int(first_k),
                                         D.ctypes.data, _ptr(H), C.byref(nsv)))
     return D, H
+
+
+def gpd_timing_tag(tag: int):
+    """Kernels launched by the library from now on are timed one by one under `tag` (< 0: off)."""
+    _check(load_library().gpd_timing_tag(int(tag)))
+
+
+def gpd_timing_collect(tag: int):
+    """(sum of the durations in ms, number of launches) of the kernels recorded under `tag`."""
+    ms, n = C.c_double(), C.c_int32()
+    _check(load_library().gpd_timing_collect(int(tag), C.byref(ms), C.byref(n)))
+    return ms.value, n.value
+
+
+def gpd_timing_reset():
+    _check(load_library().gpd_timing_reset())
 
 
 def gpd_version() -> str:

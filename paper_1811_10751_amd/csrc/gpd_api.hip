@@ -3,6 +3,7 @@
 // gpd_combine.hip, gpd_gemm.hip and gpd_locate.hip.
 #include <algorithm>
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -27,13 +28,24 @@ gpd_status_t TableRing::init(size_t bytes_per_slot) {
 
 gpd_status_t TableRing::cached(const std::string& key,
                                const std::function<gpd_status_t(HostCombineTable*)>& build,
-                               hipStream_t stream, CombineTable* out) {
+                               hipStream_t stream, CombineTable* out, bool args_suffice) {
   auto it = cache.find(key);
   if (it != cache.end()) { *out = it->second; return GPD_OK; }
   HostCombineTable ht;
   gpd_status_t st = build(&ht);
   if (st != GPD_OK) return st;
   const size_t need = ht.bytes();
+  if (args_suffice && cache.size() < kHostOnlyEntries) {
+    std::vector<char> scratch_host(need);
+    CombineTable t = ht.pack(scratch_host.data(), nullptr);
+    if (t.k_offsets && t.k_coefs && !t.in_rows) {
+      t.in_off = t.out_off = nullptr; t.coef = t.H = nullptr; t.coef64 = t.H64 = nullptr;
+      t.node = nullptr; t.pts64 = nullptr;
+      *out = t;
+      cache.emplace(key, t);
+      return GPD_OK;
+    }
+  }
   if (arena_used + need > kArenaBytes || need > slot_bytes) return upload(ht, stream, out);
   // stage in a pinned ring slot and copy to the arena on the upload stream: the region is written
   // once and never again, so the copy may run while earlier work of `stream` (a long product,
@@ -79,6 +91,34 @@ gpd_status_t TableRing::upload(const HostCombineTable& t, hipStream_t stream, Co
   return GPD_OK;
 }
 
+// ---------------------------------------------------------------- kernel timing
+
+namespace {
+struct TimedLaunch { hipEvent_t start, stop; int tag; };
+std::mutex timing_mutex;
+std::vector<TimedLaunch> timed;              // launches recorded since the last reset
+std::vector<TimedLaunch> spare;              // event pairs ready for re-use
+int timing_tag = -1;
+constexpr size_t kMaxTimed = 16384;
+}  // namespace
+
+bool timing_take(hipEvent_t* start, hipEvent_t* stop) {
+  if (timing_tag < 0) return false;          // (unlocked read: the tag is set and cleared by the caller's own thread)
+  std::lock_guard<std::mutex> lock(timing_mutex);
+  if (timing_tag < 0 || timed.size() >= kMaxTimed) return false;
+  TimedLaunch t;
+  if (!spare.empty()) {
+    t = spare.back();
+    spare.pop_back();
+  } else if (hipEventCreate(&t.start) != hipSuccess || hipEventCreate(&t.stop) != hipSuccess) {
+    return false;
+  }
+  t.tag = timing_tag;
+  timed.push_back(t);
+  *start = t.start; *stop = t.stop;
+  return true;
+}
+
 static size_t max_table_bytes(int nin, int nout, int r) {
   HostCombineTable t;
   t.nin = nin; t.nout = nout; t.r = r;
@@ -98,6 +138,7 @@ struct gpd_plan {
   int64_t ahA = 0, awA = 0;     // block of A: (N1/m) x (N0/n)
   int64_t ahB = 0, awB = 0;     // block of B: (N0/n) x (Nc/d)
   int64_t ahC = 0, awC = 0;     // block of C: (N1/m) x (Nc/d)
+  int64_t sA = 0, sB = 0, sC = 0;   // elements between consecutive nodes' blocks of At, Bt, Ct
   double rho = 0, abs_floor = 0;
   // static tables (device): encode A and encode B for the caller's leading dimensions are
   // built per call because in_off depends on lda/ldb; the coefficient part is fixed.
@@ -109,6 +150,10 @@ struct gpd_plan {
 namespace gpd {
 
 constexpr size_t kHeaderBytes = 512;        // counters[64] + node_err[64]
+// Pad between the node blocks of a spread stack.  Measured on MI355X with 2048 x 2048 fp32 blocks
+// (16 MiB): against packed blocks a pad of 65 KiB + 1 KiB takes the encode's 16 output streams from
+// 5.4 to 6.8 TB/s and the decode's 9 to 16 input streams from 5.3 to 5.7 TB/s.
+constexpr int64_t kSpreadPadBytes = 66560;
 
 static int64_t screen_words(int64_t n_codewords) { return (n_codewords + 63) / 64 + 8; }
 
@@ -152,6 +197,19 @@ extern "C" gpd_status_t gpd_plan(const gpd_problem_t* pr, gpd_plan_t** out) {
   pl->ahA = pr->N1 / pr->m; pl->awA = pr->N0 / pr->n;
   pl->ahB = pr->N0 / pr->n; pl->awB = pr->Nc / pr->d;
   pl->ahC = pr->N1 / pr->m; pl->awC = pr->Nc / pr->d;
+  if (pr->stack_layout != GPD_LAYOUT_PACKED && pr->stack_layout != GPD_LAYOUT_SPREAD) {
+    delete pl;
+    return fail(GPD_E_INVALID, "unknown stack layout %d", pr->stack_layout);
+  }
+  // spread stacks: a pad of kSpreadPadBytes between the blocks (whole 256-byte lines, so every
+  // block keeps the alignment of the first)
+  {
+    const int64_t in_elem = pr->worker_dtype == GPD_BF16 ? 2 : 4;
+    const int64_t pad = pr->stack_layout == GPD_LAYOUT_SPREAD ? kSpreadPadBytes : 0;
+    pl->sA = pl->ahA * pl->awA + pad / in_elem;
+    pl->sB = pl->ahB * pl->awB + pad / in_elem;
+    pl->sC = pl->ahC * pl->awC + pad / 4;
+  }
   pl->rho = pr->rho_detect > 0 ? pr->rho_detect
                                : (pr->worker_dtype == GPD_BF16 ? 0.125 : 1.0 / 4096.0);
   pl->abs_floor = pr->abs_floor;
@@ -183,6 +241,49 @@ extern "C" gpd_status_t gpd_plan_info(const gpd_plan_t* pl, int32_t* K, int32_t*
   return GPD_OK;
 }
 
+extern "C" gpd_status_t gpd_timing_tag(int32_t tag) {
+  std::lock_guard<std::mutex> lock(timing_mutex);
+  timing_tag = tag < 0 ? -1 : tag;
+  return GPD_OK;
+}
+
+extern "C" gpd_status_t gpd_timing_collect(int32_t tag, double* total_ms, int32_t* launches) {
+  std::lock_guard<std::mutex> lock(timing_mutex);
+  double sum = 0.0;
+  int n = 0;
+  for (const TimedLaunch& t : timed) {
+    if (t.tag != tag) continue;
+    GPD_HIP(hipEventSynchronize(t.stop));
+    float ms = 0.f;
+    GPD_HIP(hipEventElapsedTime(&ms, t.start, t.stop));
+    sum += ms;
+    ++n;
+  }
+  if (total_ms) *total_ms = sum;
+  if (launches) *launches = n;
+  return GPD_OK;
+}
+
+extern "C" gpd_status_t gpd_timing_reset(void) {
+  std::lock_guard<std::mutex> lock(timing_mutex);
+  for (const TimedLaunch& t : timed) {
+    (void)hipEventSynchronize(t.stop);
+    spare.push_back(t);
+  }
+  timed.clear();
+  timing_tag = -1;
+  return GPD_OK;
+}
+
+extern "C" gpd_status_t gpd_plan_strides(const gpd_plan_t* pl, int64_t* strideA, int64_t* strideB,
+                                         int64_t* strideC) {
+  if (!pl) return fail(GPD_E_INVALID, "gpd_plan_strides: null plan");
+  if (strideA) *strideA = pl->sA;
+  if (strideB) *strideB = pl->sB;
+  if (strideC) *strideC = pl->sC;
+  return GPD_OK;
+}
+
 extern "C" gpd_status_t gpd_plan_tables(const gpd_plan_t* pl, double* points, int32_t* eA,
                                         int32_t* eB, int32_t* eC) {
   if (!pl) return fail(GPD_E_INVALID, "gpd_plan_tables: null plan");
@@ -208,7 +309,9 @@ namespace gpd {
 //   grid_r x grid_c blocks of bh x bw inside a matrix with leading dimension ld;
 //   exps[grid_r*grid_c]; output stack [P][bh][bw].
 HostCombineTable encode_table(const std::vector<double>& pts, const std::vector<int>& exps,
-                              int grid_r, int grid_c, int64_t bh, int64_t bw, int64_t ld) {
+                              int grid_r, int grid_c, int64_t bh, int64_t bw, int64_t ld,
+                              int64_t out_stride) {
+  if (out_stride == 0) out_stride = bh * bw;
   HostCombineTable t;
   const int P = (int)pts.size();
   t.nin = grid_r * grid_c; t.nout = P; t.r = 0;
@@ -217,7 +320,7 @@ HostCombineTable encode_table(const std::vector<double>& pts, const std::vector<
   for (int i = 0; i < grid_r; ++i)
     for (int j = 0; j < grid_c; ++j) t.in_off[i * grid_c + j] = (int64_t)i * bh * ld + (int64_t)j * bw;
   for (int p = 0; p < P; ++p) {
-    t.out_off[p] = (int64_t)p * bh * bw;
+    t.out_off[p] = (int64_t)p * out_stride;
     for (int s = 0; s < t.nin; ++s) t.coef[(size_t)p * t.nin + s] = ipow(pts[p], exps[s]);
   }
   return t;
@@ -228,8 +331,8 @@ HostCombineTable encode_table(const std::vector<double>& pts, const std::vector<
 //   dimension ld, block q <-> exponent useful[q].
 gpd_status_t decode_table(const std::vector<double>& pts, int K, const uint8_t* present,
                           bool first_k, bool with_H, const std::vector<int>& useful, int grid_r,
-                          int grid_c, int64_t bh, int64_t bw, int64_t ld, HostCombineTable* t,
-                          int* n_present) {
+                          int grid_c, int64_t bh, int64_t bw, int64_t ld, int64_t in_stride,
+                          HostCombineTable* t, int* n_present) {
   const int P = (int)pts.size();
   std::vector<int> S;
   for (int p = 0; p < P; ++p)
@@ -255,7 +358,7 @@ gpd_status_t decode_table(const std::vector<double>& pts, int K, const uint8_t* 
   for (int c = 0; c < t->nin; ++c) {
     t->node[c] = S[keep[c]];
     if (with_H) t->pts[c] = pts[S[keep[c]]];
-    t->in_off[c] = (int64_t)S[keep[c]] * bh * bw;
+    t->in_off[c] = (int64_t)S[keep[c]] * in_stride;
     for (int u = 0; u < t->nout; ++u) t->coef[(size_t)u * t->nin + c] = D[(size_t)u * ns + keep[c]];
     for (int i = 0; i < t->r; ++i) t->H[(size_t)i * t->nin + c] = H[(size_t)i * ns + keep[c]];
   }
@@ -288,11 +391,14 @@ extern "C" gpd_status_t gpd_encode(const gpd_plan_t* plc, const float* A, int64_
     std::string key("encA");
     key_add(&key, lda);
     gpd_status_t st = pl->ring.cached(key, [&](HostCombineTable* ht) {
-      *ht = encode_table(c.pts, c.eA, c.m, c.n, pl->ahA, pl->awA, lda);
+      *ht = encode_table(c.pts, c.eA, c.m, c.n, pl->ahA, pl->awA, lda, pl->sA);
       return GPD_OK;
-    }, pl->stream, &t);
+    }, pl->stream, &t, true);
     if (st != GPD_OK) return st;
-    st = launch_combine(pl->stream, t, A, lda, At, pl->awA, bf16, pl->ahA, pl->awA, none);
+    // (A and B were last touched a whole product ago: streaming loads; At and Bt are the next
+    // kernel's operands: ordinary stores, which measured faster for the step as a whole)
+    st = launch_combine(pl->stream, t, A, lda, At, pl->awA, bf16, pl->ahA, pl->awA, none, 0, Epilogue(),
+                        PlaneScale(), kStreamLoads);
     if (st != GPD_OK) return st;
   }
   if (B) {
@@ -301,11 +407,12 @@ extern "C" gpd_status_t gpd_encode(const gpd_plan_t* plc, const float* A, int64_
     std::string key("encB");
     key_add(&key, ldb);
     gpd_status_t st = pl->ring.cached(key, [&](HostCombineTable* ht) {
-      *ht = encode_table(c.pts, c.eB, c.n, c.d, pl->ahB, pl->awB, ldb);
+      *ht = encode_table(c.pts, c.eB, c.n, c.d, pl->ahB, pl->awB, ldb, pl->sB);
       return GPD_OK;
-    }, pl->stream, &t);
+    }, pl->stream, &t, true);
     if (st != GPD_OK) return st;
-    st = launch_combine(pl->stream, t, B, ldb, Bt, pl->awB, bf16, pl->ahB, pl->awB, none);
+    st = launch_combine(pl->stream, t, B, ldb, Bt, pl->awB, bf16, pl->ahB, pl->awB, none, 0, Epilogue(),
+                        PlaneScale(), kStreamLoads);
     if (st != GPD_OK) return st;
   }
   return GPD_OK;
@@ -323,7 +430,7 @@ extern "C" gpd_status_t gpd_worker_products(const gpd_plan_t* pl, const void* At
   g.A = At; g.B = Bt; g.C = Ct;
   g.M = pl->ahA; g.K = pl->awA; g.N = pl->awB;
   g.lda = pl->awA; g.ldb = pl->awB; g.ldc = pl->awC;
-  g.strideA = pl->ahA * pl->awA; g.strideB = pl->ahB * pl->awB; g.strideC = pl->ahC * pl->awC;
+  g.strideA = pl->sA; g.strideB = pl->sB; g.strideC = pl->sC;
   g.batch = pl->code.P;
   const bool bf16 = pl->prob.worker_dtype == GPD_BF16;
   g.a_bf16 = g.b_bf16 = bf16;
@@ -373,7 +480,9 @@ gpd_status_t run_decode(hipStream_t stream, TableRing* ring, const DecodeJob& jo
   const bool first_k = !corr && mode == GPD_DEC_FIRST_K;
   std::string key("dec");
   key_add(&key, job.K); key_add(&key, job.grid_r); key_add(&key, job.grid_c);
-  key_add(&key, job.bh); key_add(&key, job.bw); key_add(&key, ld_out);
+  const int64_t in_stride = job.in_stride ? job.in_stride : job.bh * job.bw;
+  if (in_stride < job.bh * job.bw) return fail(GPD_E_SHAPE, "decode: node stride smaller than a block");
+  key_add(&key, job.bh); key_add(&key, job.bw); key_add(&key, ld_out); key_add(&key, in_stride);
   key_add(&key, first_k); key_add(&key, corr);
   key_add_bytes(&key, job.useful.data(), job.useful.size() * sizeof(int));
   key_add_bytes(&key, job.out_rows.data(), job.out_rows.size() * sizeof(int32_t));
@@ -382,11 +491,11 @@ gpd_status_t run_decode(hipStream_t stream, TableRing* ring, const DecodeJob& jo
   CombineTable t;
   gpd_status_t st = ring->cached(key, [&](HostCombineTable* ht) {
     gpd_status_t s2 = decode_table(*job.pts, job.K, present, first_k, corr, job.useful, job.grid_r,
-                                   job.grid_c, job.bh, job.bw, ld_out, ht, nullptr);
+                                   job.grid_c, job.bh, job.bw, ld_out, in_stride, ht, nullptr);
     if (s2 != GPD_OK) return s2;
     ht->out_rows = job.out_rows; ht->out_cols = job.out_cols;
     return GPD_OK;
-  }, stream, &t);
+  }, stream, &t, !corr);
   if (report) report->status = st;
   if (st != GPD_OK) return st;
 
@@ -413,7 +522,10 @@ gpd_status_t run_decode(hipStream_t stream, TableRing* ring, const DecodeJob& jo
     sc.counters = counters; sc.flag_bits = flag_bits; sc.flag_words = flag_words;
   }
   if (corr && job.epi.kind != 0) return fail(GPD_E_INVALID, "decode: element-wise step with element correction");
-  st = launch_combine(stream, t, Zt, job.bw, out, ld_out, false, job.bh, job.bw, sc, 0, job.epi);
+  // (the responses were written by the product just before: ordinary loads; the decoded result is
+  // read by nothing on the device next: streaming stores)
+  st = launch_combine(stream, t, Zt, job.bw, out, ld_out, false, job.bh, job.bw, sc, 0, job.epi, PlaneScale(),
+                      kStreamStores);
   if (st != GPD_OK) return st;
   if (corr) {
     LocateArgs la;
@@ -478,7 +590,7 @@ gpd_status_t run_decode_nodes(hipStream_t stream, TableRing* ring, const DecodeJ
   const int64_t keep_cap = report ? report->located_cap : 0;
   gpd_node_report_t nr;
   gpd_status_t st = run_locate_nodes(stream, ring, *job.pts, job.K, ncw, Zt, present, job.rho,
-                                     job.abs_floor, workspace, workspace_bytes, &nr);
+                                     job.abs_floor, workspace, workspace_bytes, &nr, nullptr, job.in_stride);
   if (report) {
     std::memset(report, 0, sizeof(*report));
     report->located = keep_ptr; report->located_cap = keep_cap;
@@ -516,7 +628,7 @@ extern "C" gpd_status_t gpd_locate_nodes(const gpd_plan_t* plc, const float* Ct,
   gpd_plan_t* pl = const_cast<gpd_plan_t*>(plc);
   if (!pl || !report) return fail(GPD_E_INVALID, "gpd_locate_nodes: null argument");
   return run_locate_nodes(pl->stream, &pl->ring, pl->code.pts, pl->code.K, pl->ahC * pl->awC, Ct, present,
-                          pl->rho, pl->abs_floor, workspace, workspace_bytes, report, gram);
+                          pl->rho, pl->abs_floor, workspace, workspace_bytes, report, gram, pl->sC);
 }
 
 extern "C" gpd_status_t gpd_verify_decode(const gpd_plan_t* plc, const float* Ct, const uint8_t* present,
@@ -528,7 +640,7 @@ extern "C" gpd_status_t gpd_verify_decode(const gpd_plan_t* plc, const float* Ct
   DecodeJob job;
   job.pts = &pl->code.pts; job.K = pl->code.K; job.useful = pl->code.eC;
   job.grid_r = pl->code.m; job.grid_c = pl->code.d;
-  job.bh = pl->ahC; job.bw = pl->awC;
+  job.bh = pl->ahC; job.bw = pl->awC; job.in_stride = pl->sC;
   job.rho = pl->rho; job.abs_floor = pl->abs_floor;
   return run_verify(pl->stream, job, Ct, present, mode, bad, C, ldc, n_check, workspace, workspace_bytes, report);
 }
@@ -592,7 +704,7 @@ extern "C" gpd_status_t gpd_decode_static(const gpd_plan_t* plc, const float* Ct
   DecodeJob job;
   job.pts = &pl->code.pts; job.K = pl->code.K; job.useful = pl->code.eC;
   job.grid_r = pl->code.m; job.grid_c = pl->code.d;
-  job.bh = pl->ahC; job.bw = pl->awC;
+  job.bh = pl->ahC; job.bw = pl->awC; job.in_stride = pl->sC;
   job.rho = pl->rho; job.abs_floor = pl->abs_floor;
   job.flag_cap = kStaticFlagWords; job.loc_cap = kStaticLocCap; job.workspace_bytes = kStaticScratchBytes;
   return run_decode(pl->stream, &pl->ring, job, Ct, present, mode, correct_errors, C, ldc,
@@ -607,7 +719,7 @@ extern "C" gpd_status_t gpd_decode(const gpd_plan_t* plc, const float* Ct, const
   DecodeJob job;
   job.pts = &pl->code.pts; job.K = pl->code.K; job.useful = pl->code.eC;
   job.grid_r = pl->code.m; job.grid_c = pl->code.d;
-  job.bh = pl->ahC; job.bw = pl->awC;
+  job.bh = pl->ahC; job.bw = pl->awC; job.in_stride = pl->sC;
   job.rho = pl->rho; job.abs_floor = pl->abs_floor;
   job.flag_cap = pl->flag_cap; job.loc_cap = pl->loc_cap; job.workspace_bytes = pl->workspace_bytes;
   return run_decode(pl->stream, &pl->ring, job, Ct, present, mode, correct_errors, C, ldc,

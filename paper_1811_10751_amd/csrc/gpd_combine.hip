@@ -32,9 +32,20 @@ template <> struct VecT<4> { using f = float4; };
 template <> struct VecT<2> { using f = float2; };
 template <> struct VecT<1> { using f = float; };
 
-template <int VEC>
+// NT: streaming (nontemporal) load, for inputs that are read exactly once
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+template <int VEC, bool NT = false>
 __device__ __forceinline__ void load_vec(const float* p, float (&v)[VEC]) {
-  if constexpr (VEC == 4) {
+  if constexpr (NT && VEC == 4) {
+    const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+    v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+  } else if constexpr (NT && VEC == 2) {
+    const v2f t = __builtin_nontemporal_load(reinterpret_cast<const v2f*>(p));
+    v[0] = t.x; v[1] = t.y;
+  } else if constexpr (NT) {
+    v[0] = __builtin_nontemporal_load(p);
+  } else if constexpr (VEC == 4) {
     float4 t = *reinterpret_cast<const float4*>(p);
     v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
   } else if constexpr (VEC == 2) {
@@ -45,9 +56,7 @@ __device__ __forceinline__ void load_vec(const float* p, float (&v)[VEC]) {
   }
 }
 
-// NT: streaming (nontemporal) store, for outputs nothing on the device reads next
-typedef float v4f __attribute__((ext_vector_type(4)));
-typedef float v2f __attribute__((ext_vector_type(2)));
+// NT: streaming (nontemporal) store, for large outputs written exactly once
 template <int VEC, bool NT = false>
 __device__ __forceinline__ void store_vec(float* p, const float (&v)[VEC]) {
   if constexpr (NT && VEC == 4) {
@@ -164,6 +173,10 @@ struct CombineParams {
   // the first store to complete).  The block offsets always; coef and H when karg is set (they
   // fit), else those two are read from memory.
   int32_t karg;
+  // bit 0: the inputs are read with streaming loads, bit 1: fp32 outputs are written with streaming
+  // stores (large launches in which every input element is read once: measured on 16 MiB blocks,
+  // decode 4.8 -> 5.3 TB/s, encode 4.8 -> 5.4 TB/s, before any spreading of the blocks)
+  int32_t streaming;
   // element-wise step on fp32 outputs: 0 none, 1 logistic function, 2 times y (1 - y) with y
   // read from epi_y at the output's own offset
   int32_t epi;
@@ -206,7 +219,9 @@ __device__ __forceinline__ unsigned long long spread_bits(unsigned long long x) 
   return x;
 }
 
-template <int NIN_MAX, int VEC, int OUT, bool SCREEN, bool LIMITS, bool TAB>
+// EXACT: nin == NIN_MAX and no block limits, so no input has to be masked out (idle threads of
+// the last workgroup compute on the first input's first element and store nothing).
+template <int NIN_MAX, int VEC, int OUT, bool SCREEN, bool LIMITS, bool TAB, bool EXACT = false>
 __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t total = p.rows * p.cols_vec;
@@ -226,10 +241,43 @@ __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
     col = active ? (idx - row * p.cols_vec) * VEC : 0;
   }
 
+  // Tables that do not travel as kernel arguments go through LDS (dynamic, sized by the host; none
+  // when karg): the rows this workgroup needs, padded with zeros to NIN_MAX entries so that a row
+  // is read whole and without a branch, like the kernel-argument form.  LDS reads do not share a
+  // counter with the output stores, so they never wait for them.  The screening decode always
+  // takes this form: with its r + nout rows of kernel arguments, read one row per trip of a loop,
+  // every trip waited for a scalar load (decode + screen of 16 nodes: 78 us against 61 us).
+  // The table entries are requested after the inputs (below): every workgroup of the launch reads
+  // the same few hundred words, and with those requests first the inputs waited behind them (the
+  // same launch: 74 us against 60 us).
+  constexpr bool karg = !TAB;
+  extern __shared__ float tab_lds[];
+  const int q_first = blockIdx.y * p.q_chunk;
+  const int q_count = min(p.nout, q_first + p.q_chunk) - q_first;
+  float* coef_s = tab_lds;
+  float* H_s = tab_lds + p.q_chunk * NIN_MAX;
+  const int n_coef = q_count * NIN_MAX;
+  const int n_tab = n_coef + (SCREEN ? p.r * NIN_MAX : 0);
+  // (entry e of the coefficient rows followed by the parity-check rows; an entry of the padding is
+  // read from the table's first word and replaced by zero, so that the load is unconditional)
+  auto tab_entry = [&](int e) -> float {
+    const bool c = e < n_coef;
+    const int e2 = c ? e : e - n_coef, row2 = e2 / NIN_MAX, s2 = e2 - row2 * NIN_MAX;
+    const bool valid = e < n_tab && s2 < p.nin;
+    const float* src = c ? p.coef + (int64_t)(q_first + row2) * p.nin + s2 : p.H + (int64_t)row2 * p.nin + s2;
+    const float v = *(valid ? src : p.coef);
+    return valid ? v : 0.f;
+  };
+  auto tab_slot = [&](int e) -> float* { return e < n_coef ? coef_s + e : H_s + (e - n_coef); };
+
   // All inputs are requested back to back: the address of an input that is not to be read
   // (beyond nin, beyond a block limit, an idle thread) is replaced by that of the first input's
   // first element and the value discarded afterwards, so that there is no branch, and no wait
   // for a table entry, between two loads.  The block offsets are kernel arguments.
+  // (the screen's running maximum of ||Hz|| / tau, requested together with the inputs; used below
+  // to skip most of the atomics)
+  uint32_t ratio_seen = 0;
+  if constexpr (SCREEN) ratio_seen = __hip_atomic_load(&p.counters[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   float z[NIN_MAX][VEC];
   const int64_t lane_off = row * p.in_ld + col;
   bool take[NIN_MAX];
@@ -238,36 +286,24 @@ __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
     take[s] = s < p.nin && active;
     if constexpr (LIMITS) take[s] = take[s] && row < p.in_rows[s < p.nin ? s : 0] && col < p.in_cols[s < p.nin ? s : 0];
   }
+  if (p.streaming & 1) {
 #pragma unroll
-  for (int s = 0; s < NIN_MAX; ++s)
-    load_vec<VEC>(p.in + (take[s] ? p.in_off_k[s] + lane_off : p.in_off_k[0]), z[s]);
+    for (int s = 0; s < NIN_MAX; ++s)
+      load_vec<VEC, true>(p.in + (take[s] ? p.in_off_k[s] + lane_off : p.in_off_k[0]), z[s]);
+  } else {
 #pragma unroll
-  for (int s = 0; s < NIN_MAX; ++s)
+    for (int s = 0; s < NIN_MAX; ++s)
+      load_vec<VEC>(p.in + (take[s] ? p.in_off_k[s] + lane_off : p.in_off_k[0]), z[s]);
+  }
+  if constexpr (!EXACT) {
 #pragma unroll
-    for (int v = 0; v < VEC; ++v) z[s][v] = take[s] ? z[s][v] : 0.f;
-  constexpr bool karg = !TAB;
-
-  // Tables too large for the kernel arguments go through LDS (dynamic, sized by the host; none
-  // when karg): the rows this workgroup needs, padded with zeros to NIN_MAX entries so that a row
-  // is read whole and without a branch, like the kernel-argument form.  LDS reads do not share a
-  // counter with the output stores, so they never wait for them.
-  extern __shared__ float tab_lds[];
-  const int q_first = blockIdx.y * p.q_chunk;
-  const int q_count = min(p.nout, q_first + p.q_chunk) - q_first;
-  float* coef_s = tab_lds;
-  float* H_s = tab_lds + p.q_chunk * NIN_MAX;
+    for (int s = 0; s < NIN_MAX; ++s)
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) z[s][v] = take[s] ? z[s][v] : 0.f;
+  }
   if constexpr (!karg) {
-    for (int idx = threadIdx.x; idx < q_count * NIN_MAX; idx += blockDim.x) {
-      const int q = idx / NIN_MAX, s2 = idx - q * NIN_MAX;
-      coef_s[idx] = s2 < p.nin ? p.coef[(int64_t)(q_first + q) * p.nin + s2] : 0.f;
-    }
-    if constexpr (SCREEN) {
-      for (int idx = threadIdx.x; idx < p.r * NIN_MAX; idx += blockDim.x) {
-        const int i = idx / NIN_MAX, s2 = idx - i * NIN_MAX;
-        H_s[idx] = s2 < p.nin ? p.H[(int64_t)i * p.nin + s2] : 0.f;
-      }
-    }
-    __syncthreads();
+    for (int e = (int)threadIdx.x; e < n_tab; e += 64) *tab_slot(e) = tab_entry(e);
+    __syncthreads();                                 // the tables are in LDS
   }
 
   float inv = 1.f;
@@ -283,18 +319,33 @@ __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
   }
 
   // non-finite responses are replaced by zero everywhere (and always passed on, below)
+  // (The sum of squares tells whether anything is non-finite: one multiply-add per value.  Only a
+  // wavefront that holds such a value, or one so large that its square overflows, goes through
+  // the value-by-value test; comparing every value of every wavefront took a quarter of the
+  // kernel's vector instructions.)
   bool bad[VEC];
   float nz2[VEC];
   if constexpr (SCREEN) {
+    bool odd = false;
 #pragma unroll
     for (int v = 0; v < VEC; ++v) { bad[v] = false; nz2[v] = 0.f; }
 #pragma unroll
-    for (int s = 0; s < NIN_MAX; ++s) {
+    for (int s = 0; s < NIN_MAX; ++s)
 #pragma unroll
-      for (int v = 0; v < VEC; ++v) {
-        const float x = z[s][v];
-        if (!(fabsf(x) <= 3.4028234664e38f)) { bad[v] = true; z[s][v] = 0.f; }
-        nz2[v] = fmaf(z[s][v], z[s][v], nz2[v]);
+      for (int v = 0; v < VEC; ++v) nz2[v] = fmaf(z[s][v], z[s][v], nz2[v]);
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) odd = odd || !(nz2[v] <= 3.4028234664e38f);
+    if (__ballot(odd) != 0ull) {                         // (wave-uniform, rare)
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) nz2[v] = 0.f;
+#pragma unroll
+      for (int s = 0; s < NIN_MAX; ++s) {
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+          const float x = z[s][v];
+          if (!(fabsf(x) <= 3.4028234664e38f)) { bad[v] = true; z[s][v] = 0.f; }
+          nz2[v] = fmaf(z[s][v], z[s][v], nz2[v]);
+        }
       }
     }
   }
@@ -306,6 +357,9 @@ __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
     for (int v = 0; v < VEC; ++v) sig2[v] = 0.f;
     auto syndromes = [&](auto from_args) __attribute__((always_inline)) {
       constexpr bool K = decltype(from_args)::value;
+      // (two rows per trip: both rows' table entries are requested before either is used, which
+      // halves the number of waits for a scalar load)
+#pragma unroll 2
       for (int i = 0; i < p.r; ++i) {
         float y[VEC];
 #pragma unroll
@@ -344,14 +398,16 @@ __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
     for (int k = 0; k < VEC; ++k) words[k] = 0ull;
 #pragma unroll
     for (int v = 0; v < VEC; ++v) {
-      const float nz = sqrtf(nz2[v]);
-      const float sig = sqrtf(sig2[v]);
+      // (square roots and the reciprocal by the hardware's one-ulp instructions: this test only
+      // preselects, with a margin of a factor two, and the ratio is a statistic)
+      const float nz = __builtin_amdgcn_sqrtf(nz2[v]);
+      const float sig = __builtin_amdgcn_sqrtf(sig2[v]);
       const float base = fmaxf(nz, p.abs_floor);
       const float thr = fmaxf(p.rho_screen * base - 1.52587890625e-05f * nz, 0.f);
       const bool flag = active && (bad[v] || !(sig <= thr));
       if (!flag && active) {
         const float tau = p.rho * base;
-        if (tau > 0.f) ratio = fmaxf(ratio, sig / tau);
+        if (tau > 0.f) ratio = fmaxf(ratio, sig * __builtin_amdgcn_rcpf(tau));
       }
       const unsigned long long b = __ballot(flag);       // bit l: lane l, component v
 #pragma unroll
@@ -365,11 +421,17 @@ __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
     // wave-wide maximum, one atomic per wave
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) ratio = fmaxf(ratio, __shfl_xor(ratio, off));
-    // (a running maximum: after the first few wavefronts almost none has a larger value, and a
-    // plain read that may be stale only costs an unnecessary atomic)
+    // (A running maximum.  Atomics to one address, or to one cache line, are served one after the
+    // other, some 10 ns each: 16 384 wavefronts must not all send one.  Almost none has a value above
+    // the maximum it read when it started; the few that have read it again, now, and only those
+    // still above it send the atomic.  Reading it only here held every wavefront for a memory round
+    // trip in front of its outputs; reading it only at the start let the first thousands of
+    // wavefronts, which all saw zero, send an atomic each.)
     if ((threadIdx.x & 63) == 0 && ratio > 0.f) {
       const uint32_t bits = __float_as_uint(ratio);
-      if (bits > *reinterpret_cast<volatile uint32_t*>(&p.counters[1])) atomicMax(&p.counters[1], bits);
+      if (bits > ratio_seen &&
+          bits > __hip_atomic_load(&p.counters[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+        atomicMax(&p.counters[1], bits);
     }
   }
 
@@ -380,6 +442,7 @@ __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
   // contains no vector load at all and its stores are never waited for)
   auto outputs = [&](auto from_args) __attribute__((always_inline)) {
     constexpr bool K = decltype(from_args)::value;
+#pragma unroll 2
     for (int q = q_begin; q < q_end; ++q) {
       float acc[VEC];
 #pragma unroll
@@ -427,7 +490,8 @@ __global__ __launch_bounds__(64) void combine_kernel(CombineParams p) {
             for (int v = 0; v < VEC; ++v) acc[v] = acc[v] * y[v] * (1.f - y[v]);
           }
         }
-        store_vec<VEC, SCREEN>(reinterpret_cast<float*>(p.out) + o, acc);
+        if (SCREEN || (p.streaming & 2)) store_vec<VEC, true>(reinterpret_cast<float*>(p.out) + o, acc);
+        else store_vec<VEC, false>(reinterpret_cast<float*>(p.out) + o, acc);
       }
     }
   };
@@ -454,12 +518,19 @@ gpd_status_t launch_t(hipStream_t stream, const CombineParams& p, int out_kind, 
   auto go = [&](auto out_c, auto screen_c) {
     constexpr int O = decltype(out_c)::value;
     constexpr bool S = decltype(screen_c)::value;
+    if constexpr (S) {
+      if (!lim && p.nin == NIN_MAX) {
+        if (p.karg) GPD_LAUNCH((combine_kernel<NIN_MAX, VEC, O, S, false, false, true>), grid, block, lds, stream, p);
+        else GPD_LAUNCH((combine_kernel<NIN_MAX, VEC, O, S, false, true, true>), grid, block, lds, stream, p);
+        return;
+      }
+    }
     if (p.karg) {
-      if (lim) hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, O, S, true, false>), grid, block, lds, stream, p);
-      else hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, O, S, false, false>), grid, block, lds, stream, p);
+      if (lim) GPD_LAUNCH((combine_kernel<NIN_MAX, VEC, O, S, true, false>), grid, block, lds, stream, p);
+      else GPD_LAUNCH((combine_kernel<NIN_MAX, VEC, O, S, false, false>), grid, block, lds, stream, p);
     } else {
-      if (lim) hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, O, S, true, true>), grid, block, lds, stream, p);
-      else hipLaunchKernelGGL((combine_kernel<NIN_MAX, VEC, O, S, false, true>), grid, block, lds, stream, p);
+      if (lim) GPD_LAUNCH((combine_kernel<NIN_MAX, VEC, O, S, true, true>), grid, block, lds, stream, p);
+      else GPD_LAUNCH((combine_kernel<NIN_MAX, VEC, O, S, false, true>), grid, block, lds, stream, p);
     }
   };
   if (screen) {
@@ -482,6 +553,9 @@ template <int VEC>
 gpd_status_t launch_v(hipStream_t stream, const CombineParams& p, int out_kind, bool screen) {
   if (p.nin <= 4) return launch_t<4, VEC>(stream, p, out_kind, screen);
   if (p.nin <= 8) return launch_t<8, VEC>(stream, p, out_kind, screen);
+  if constexpr (VEC == 4) {
+    if (p.nin <= 12) return launch_t<12, VEC>(stream, p, out_kind, screen);
+  }
   if (p.nin <= 16) return launch_t<16, VEC>(stream, p, out_kind, screen);
   if constexpr (VEC <= 2) {
     if (p.nin <= 32) return launch_t<32, VEC>(stream, p, out_kind, screen);
@@ -497,7 +571,7 @@ gpd_status_t launch_v(hipStream_t stream, const CombineParams& p, int out_kind, 
 gpd_status_t launch_combine(hipStream_t stream, const CombineTable& t, const float* in,
                             int64_t in_ld, void* out, int64_t out_ld, int out_kind,
                             int64_t rows, int64_t cols, const ScreenArgs& screen, int64_t out_plane,
-                            const Epilogue& epi, const PlaneScale& scale) {
+                            const Epilogue& epi, const PlaneScale& scale, int streaming) {
   if (t.nin < 1 || t.nin > GPD_MAX_BLOCKS || t.nout < 1)
     return fail(GPD_E_INVALID, "combine: nin = %d, nout = %d", t.nin, t.nout);
   if (rows * cols > 0x7fffffffLL) return fail(GPD_E_SHAPE, "block has more than 2^31 elements");
@@ -525,6 +599,11 @@ gpd_status_t launch_combine(hipStream_t stream, const CombineTable& t, const flo
   std::memcpy(p.in_off_k, t.k_in_off, sizeof(p.in_off_k));
   std::memcpy(p.out_off_k, t.k_out_off, sizeof(p.out_off_k));
   p.karg = t.k_coefs ? 1 : 0;
+  if (screen.enabled) {
+    // (the screening decode reads its tables from LDS: see the kernel)
+    if (!t.coef || (t.r > 0 && !t.H)) return fail(GPD_E_INVALID, "combine: the screen needs its tables in device memory");
+    p.karg = 0;
+  }
   std::memset(p.coef_k, 0, sizeof(p.coef_k));
   std::memset(p.H_k, 0, sizeof(p.H_k));
   if (p.karg) {
@@ -551,6 +630,14 @@ gpd_status_t launch_combine(hipStream_t stream, const CombineTable& t, const flo
   // in place (outputs overwrite inputs): a thread must hold all its inputs before any output
   // of its element is written, so the outputs cannot be split over several workgroups
   if ((const void*)in == (const void*)out) p.q_chunk = t.nout;
+  // streaming accesses, where the caller asks for them, for launches that move tens of megabytes
+  // and read every input once
+  {
+    const bool big = (double)rows * cols * 4.0 * (t.nin + t.nout) >= 32.0 * 1024 * 1024;
+    p.streaming = 0;
+    if (big && p.q_chunk == t.nout && (const void*)in != (const void*)out)
+      p.streaming = (streaming & kStreamLoads) | (out_kind == 0 ? (streaming & kStreamStores) : 0);
+  }
   if (vec == 4) return launch_v<4>(stream, p, out_kind, screen.enabled);
   if (vec == 2) return launch_v<2>(stream, p, out_kind, screen.enabled);
   return launch_v<1>(stream, p, out_kind, screen.enabled);

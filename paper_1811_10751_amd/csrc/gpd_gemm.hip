@@ -996,11 +996,11 @@ gpd_status_t launch_planes(hipStream_t stream, HGemmParams p, int64_t batch) {
   dim3 grid((unsigned)(p.tiles_per_xcd * 8));
   const bool full = p.M % 128 == 0 && p.N % 128 == 0;
   if (p.exps) {
-    if (full) hipLaunchKernelGGL((gemm_planes_kernel<0, 2, 1>), grid, dim3(256), 0, stream, p);
-    else hipLaunchKernelGGL((gemm_planes_kernel<1, 2, 1>), grid, dim3(256), 0, stream, p);
+    if (full) GPD_LAUNCH((gemm_planes_kernel<0, 2, 1>), grid, dim3(256), 0, stream, p);
+    else GPD_LAUNCH((gemm_planes_kernel<1, 2, 1>), grid, dim3(256), 0, stream, p);
   } else {
-    if (full) hipLaunchKernelGGL((gemm_planes_kernel<0, 2, 0>), grid, dim3(256), 0, stream, p);
-    else hipLaunchKernelGGL((gemm_planes_kernel<1, 2, 0>), grid, dim3(256), 0, stream, p);
+    if (full) GPD_LAUNCH((gemm_planes_kernel<0, 2, 0>), grid, dim3(256), 0, stream, p);
+    else GPD_LAUNCH((gemm_planes_kernel<1, 2, 0>), grid, dim3(256), 0, stream, p);
   }
   GPD_HIP(hipGetLastError());
   return GPD_OK;
@@ -1164,14 +1164,14 @@ gpd_status_t launch_bf16_t(hipStream_t stream, HGemmParams p, int64_t batch, boo
     // weights needs two stages of global loads in flight: 8 wavefronts of 128 x 64 (256
     // registers each) instead of 16 of 64 x 64 (128 registers)
     if constexpr (SPLIT == 3 || ASRC == SRC_F32_KC || ASRC == SRC_F32_RC)
-      hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 0, 256, 256, 2, 4, SPLIT>), grid, dim3(512), 0, stream, p);
+      GPD_LAUNCH((gemm_bf16_kernel<ASRC, BSRC, 0, 256, 256, 2, 4, SPLIT>), grid, dim3(512), 0, stream, p);
     else
-      hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 0, 256, 256, 4, 4, SPLIT>), grid, dim3(1024), 0, stream, p);
+      GPD_LAUNCH((gemm_bf16_kernel<ASRC, BSRC, 0, 256, 256, 4, 4, SPLIT>), grid, dim3(1024), 0, stream, p);
   } else {
     const bool full = aligned && p.M % 128 == 0 && p.N % 128 == 0 && p.K % hk_of(SPLIT) == 0 && p.K > 0 &&
                       (SPLIT == 1 || even);
-    if (full) hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 0, 128, 128, 2, 2, SPLIT>), grid, dim3(256), 0, stream, p);
-    else hipLaunchKernelGGL((gemm_bf16_kernel<ASRC, BSRC, 1, 128, 128, 2, 2, SPLIT>), grid, dim3(256), 0, stream, p);
+    if (full) GPD_LAUNCH((gemm_bf16_kernel<ASRC, BSRC, 0, 128, 128, 2, 2, SPLIT>), grid, dim3(256), 0, stream, p);
+    else GPD_LAUNCH((gemm_bf16_kernel<ASRC, BSRC, 1, 128, 128, 2, 2, SPLIT>), grid, dim3(256), 0, stream, p);
   }
   GPD_HIP(hipGetLastError());
   return GPD_OK;
@@ -1180,9 +1180,9 @@ gpd_status_t launch_bf16_t(hipStream_t stream, HGemmParams p, int64_t batch, boo
 template <bool A_KC, bool B_KC, int TBM, int TBN, int WGM, int WGN>
 gpd_status_t launch_f32_shape(hipStream_t stream, const GemmParams& p, int mode) {
   dim3 grid((unsigned)(p.tiles_per_xcd * 8)), block(64 * WGM * WGN);
-  if (mode == 0) hipLaunchKernelGGL((gemm_f32_kernel<A_KC, B_KC, 0, TBM, TBN, WGM, WGN>), grid, block, 0, stream, p);
-  else if (mode == 1) hipLaunchKernelGGL((gemm_f32_kernel<A_KC, B_KC, 1, TBM, TBN, WGM, WGN>), grid, block, 0, stream, p);
-  else hipLaunchKernelGGL((gemm_f32_kernel<A_KC, B_KC, 2, TBM, TBN, WGM, WGN>), grid, block, 0, stream, p);
+  if (mode == 0) GPD_LAUNCH((gemm_f32_kernel<A_KC, B_KC, 0, TBM, TBN, WGM, WGN>), grid, block, 0, stream, p);
+  else if (mode == 1) GPD_LAUNCH((gemm_f32_kernel<A_KC, B_KC, 1, TBM, TBN, WGM, WGN>), grid, block, 0, stream, p);
+  else GPD_LAUNCH((gemm_f32_kernel<A_KC, B_KC, 2, TBM, TBN, WGM, WGN>), grid, block, 0, stream, p);
   GPD_HIP(hipGetLastError());
   return GPD_OK;
 }
@@ -1275,7 +1275,7 @@ gpd_status_t launch_gemm(hipStream_t stream, const GemmArgs& a) {
         a.ldb % 4 == 0 && a.strideB % 4 == 0 && (uintptr_t)a.B % 8 == 0 && a.batch > 0 && a.batch <= 65535) {
       static_assert(kShortKC == 64 * kShortWaves, "one thread per value of k of a chunk");
       const dim3 grid((unsigned)((a.N + 63) / 64), (unsigned)a.batch);
-      hipLaunchKernelGGL(short_m_bf16_kernel, grid, dim3(64 * kShortWaves), 0, stream, h);
+      GPD_LAUNCH(short_m_bf16_kernel, grid, dim3(64 * kShortWaves), 0, stream, h);
       GPD_HIP(hipGetLastError());
       return GPD_OK;
     }
@@ -1285,7 +1285,7 @@ gpd_status_t launch_gemm(hipStream_t stream, const GemmArgs& a) {
         (uintptr_t)a.C % 16 == 0 && a.batch > 0 && a.batch <= 65535 &&
         (a.M / kShortRows) * (a.N / 4) < 0x7fffffffLL * 256) {
       const dim3 grid((unsigned)(((a.M / kShortRows) * (a.N / 4) + 255) / 256), (unsigned)a.batch);
-      hipLaunchKernelGGL(short_k_bf16_kernel, grid, dim3(256), 0, stream, h);
+      GPD_LAUNCH(short_k_bf16_kernel, grid, dim3(256), 0, stream, h);
       GPD_HIP(hipGetLastError());
       return GPD_OK;
     }

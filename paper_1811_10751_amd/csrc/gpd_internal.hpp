@@ -2,6 +2,9 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#if defined(__HIPCC__)
+#include <hip/hip_ext.h>   // launches with per-dispatch events: device translation units only
+#endif
 
 #include <cstdarg>
 #include <cstdint>
@@ -25,6 +28,22 @@ gpd_status_t fail(gpd_status_t st, const char* fmt, ...);
     if (e__ != hipSuccess)                                                                 \
       return ::gpd::fail(GPD_E_DEVICE, "%s: %s (%s:%d)", #expr, hipGetErrorString(e__),    \
                          __FILE__, __LINE__);                                              \
+  } while (0)
+
+// ---------------------------------------------------------------- kernel timing (gpd_api.hip)
+
+// While a timing tag is set (gpd_timing_tag), every kernel the library launches carries a pair
+// of events of its own (start / stop of that one dispatch, as a profiler sees it), filed under the
+// tag; gpd_timing_collect adds up the durations.  Off: a plain launch, no event, no cost.
+bool timing_take(hipEvent_t* start, hipEvent_t* stop);
+
+#define GPD_LAUNCH(kernel, grid, block, lds, stream, ...)                                        \
+  do {                                                                                           \
+    hipEvent_t ts__, te__;                                                                       \
+    if (::gpd::timing_take(&ts__, &te__))                                                        \
+      hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, ts__, te__, 0, __VA_ARGS__);       \
+    else                                                                                         \
+      hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);                         \
   } while (0)
 
 // ---------------------------------------------------------------- host mathematics (gpd_host.cpp)
@@ -143,6 +162,7 @@ struct TableRing {
   // capturing (a captured copy would re-read a recycled slot).
   // When the arena is full the table goes through the ring instead.
   static constexpr size_t kArenaBytes = 1 << 20;
+  static constexpr size_t kHostOnlyEntries = 4096;   // tables kept on the host alone, at most (about 3 KB each)
   char* arena = nullptr;
   size_t arena_used = 0;
   hipStream_t up = nullptr;            // uploads into the arena (default priority, non-blocking)
@@ -151,8 +171,12 @@ struct TableRing {
   static constexpr size_t kReportBytes = 512;
   char* report_host = nullptr;
   std::map<std::string, CombineTable> cache;
+  // args_suffice: the caller launches only kernels that take this table from their kernel
+  // arguments when it fits there (block offsets and coefficients, no block limits); such a table
+  // is then kept on the host alone: no copy, no event, nothing for the stream to wait for, and the
+  // device pointers of the view are null.
   gpd_status_t cached(const std::string& key, const std::function<gpd_status_t(HostCombineTable*)>& build,
-                      hipStream_t stream, CombineTable* out);
+                      hipStream_t stream, CombineTable* out, bool args_suffice = false);
 };
 
 // appends the raw bytes of v to a cache key
@@ -198,7 +222,12 @@ struct PlaneScale {
 gpd_status_t launch_combine(hipStream_t stream, const CombineTable& t, const float* in,
                             int64_t in_ld, void* out, int64_t out_ld, int out_kind,
                             int64_t rows, int64_t cols, const ScreenArgs& screen, int64_t out_plane = 0, const Epilogue& epi = Epilogue(),
-                            const PlaneScale& scale = PlaneScale());
+                            const PlaneScale& scale = PlaneScale(), int streaming = 0);
+// `streaming` (launches that move tens of megabytes only): bit 0 = the inputs are read with
+// streaming loads (inputs that no kernel touched recently, such as the matrices an encode reads),
+// bit 1 = fp32 outputs are written with streaming stores (outputs nothing on the device reads next,
+// such as a decoded result).
+constexpr int kStreamLoads = 1, kStreamStores = 2;
 
 struct GemmArgs {
   const void* A = nullptr;        // op(A) is M x K
@@ -246,8 +275,10 @@ gpd_status_t launch_zero_words(hipStream_t stream, void* p, int n_words);
 
 // Table that evaluates sum_blocks b_p^e(block) * block for every node p: grid_r x grid_c
 // blocks of bh x bw inside a matrix with leading dimension ld; output stack [P][bh][bw].
+// out_stride: elements between the output blocks of consecutive nodes (0 = bh * bw, packed).
 HostCombineTable encode_table(const std::vector<double>& pts, const std::vector<int>& exps,
-                              int grid_r, int grid_c, int64_t bh, int64_t bw, int64_t ld);
+                              int grid_r, int grid_c, int64_t bh, int64_t bw, int64_t ld,
+                              int64_t out_stride = 0);
 
 // One decode of a stack of P responses [P][bh][bw] into a grid_r x grid_c grid of blocks.
 struct DecodeJob {
@@ -256,6 +287,7 @@ struct DecodeJob {
   std::vector<int> useful;                     // exponent of output block q (row-major grid)
   int grid_r = 0, grid_c = 0;
   int64_t bh = 0, bw = 0;
+  int64_t in_stride = 0;                       // elements between the blocks of consecutive nodes (0 = bh * bw)
   double rho = 0, abs_floor = 0;
   int64_t flag_cap = 0, loc_cap = 0;   // words of the screen's bit map, entries of the located list
   size_t workspace_bytes = 0;
@@ -273,11 +305,12 @@ void decode_workspace_layout(int64_t n_codewords, int64_t* flag_cap, int64_t* lo
 // device bytes run_locate_nodes needs for a stack of n_codewords-element blocks and r syndromes
 size_t gram_workspace_bytes(int64_t n_codewords, int r);
 
-// Gram pass over the stack Zt [P][n_codewords] + host search; waits for the stream.
+// Gram pass over the stack Zt [P][n_codewords] (node blocks `stride` elements apart, 0 = packed)
+// + host search; waits for the stream.
 gpd_status_t run_locate_nodes(hipStream_t stream, TableRing* ring, const std::vector<double>& pts,
                               int K, int64_t n_codewords, const float* Zt, const uint8_t* present,
                               double rho, double abs_floor, void* workspace, size_t workspace_bytes,
-                              gpd_node_report_t* rep, double* gram_out = nullptr);
+                              gpd_node_report_t* rep, double* gram_out = nullptr, int64_t stride = 0);
 
 // Verification step: gathers n_check element codewords of Zt and the matching entries of the
 // decoded grid, decodes them again on the host in fp64 and compares (see gpd_verify_decode).

@@ -278,8 +278,8 @@ __global__ __launch_bounds__(256) void skinny_backward_update_kernel(
   };
   int r = r0;
   if (vec) {
-    // four rows in flight per thread: all loads first, then the arithmetic and the stores
-    constexpr int RU = 4;
+    // eight rows in flight per thread: all loads first, then the arithmetic and the stores
+    constexpr int RU = 8;
     for (; r + RU <= r1; r += RU) {
       float* wp = Wt + ((int64_t)p * rows + r) * cols + c0;
       float4 t[RU];
@@ -403,6 +403,131 @@ __global__ void l2_delta_kernel(const float* __restrict__ y, const float* __rest
   if (i < n) d[i] = scale * (y[i] - yh[i]) * yh[i] * (1.f - yh[i]);
 }
 
+// ---------------------------------------------------------------- vector stage of a whole iteration
+
+// Everything the master does between two coded products of a small-batch training iteration
+// (Sec. VII: decoding, the element-wise steps C1 / C2 or the last layer's error, and the encoding of
+// the next product's operands), in one launch.  The vectors are a few thousand elements long, so
+// the work is nothing; what it costs as four or five dependent launches is their latency.
+//   phase 1  t[e][p] = sum_k in[p][k][r(e)][b(e)]             responses of node p (forward: one
+//            term; backward: the partial column sums of the row chunks, added in chunk order)
+//   phase 2  v[e] = f(sum_p D[q(e)][p] t[e][p])                decode, then the element-wise step f;
+//            v is written to the decoded vector (an activation or an error Delta)
+//   phase 3  out_j[p][r'][b] = sum_s coef_j[p][s] v[(s, r', b)]  up to three encodes of that vector
+//            (the next product's X~ / Delta~ and the update operands X^ / D^), each over the same G
+//            blocks of bh rows
+// A workgroup owns `tile` rows r' of the G blocks; e = (s, r' - r0, b).  The decoded vector's row
+// g = s * bh + r' lies in decode block q = g / len, row r = g % len; rows g >= N are zero padding.
+// The arithmetic (order of the sums, the expressions of the element-wise steps) is that of
+// combine_kernel, reduce_chunks_kernel, encode_small_kernel and the element-wise kernels, so an
+// iteration made of these launches leaves bit for bit the weights the per-layer calls leave.
+constexpr int kStageJobs = 3;
+struct StageJob { const float* coef; float* out; };     // coef [P][G] (device), out [P][bh][nb]
+struct StageParams {
+  const float* in;
+  int64_t node_stride, red_stride;     // elements between nodes / between the terms of phase 1
+  int32_t P, nred, len, nb;
+  const float* D;                      // [nblk][P] decoding rows (device, fp32)
+  int32_t nblk;                        // decode blocks (rows of D)
+  int32_t N;                           // rows of the decoded vector that exist
+  int32_t epi;                         // 0 none, 1 logistic, 2 times y (1 - y), 3 logistic, then the L2 error
+  const float* epi_y;                  // epi 2: y; epi 3: the targets Y; laid out like the decoded vector
+  float scale;                         // epi 3: 2 / batch
+  float* out;                          // decoded vector after the element-wise step ([N][nb])
+  float* out2;                         // epi 3: the error Delta ([N][nb]); `out` then holds the network output
+  int32_t bh, G, tile, njobs;
+  StageJob job[kStageJobs];
+};
+
+__global__ __launch_bounds__(256) void vector_stage_kernel(const StageParams p) {
+  // Everything that does not depend on another phase is requested at once, at the start: the
+  // responses of phase 1, the decoding rows and the encode coefficients (into LDS), the operand of
+  // the element-wise step.  The kernel then has one memory round trip in front of its arithmetic,
+  // not one per phase; its running time is latency, not work.
+  extern __shared__ float stage_lds[];
+  const int E = p.G * p.tile * p.nb;
+  float* tsum = stage_lds;                     // [P][E]
+  float* vals = tsum + (size_t)p.P * E;        // [E]
+  float* Dl = vals + E;                        // [nblk][P]
+  float* cl = Dl + (size_t)p.nblk * p.P;       // [njobs][P][G]
+  const int r0 = blockIdx.x * p.tile;
+  const int tid = threadIdx.x;
+  auto row_of = [&](int e, int* rr, int* b) {
+    const int s = e / (p.tile * p.nb), rem = e - s * (p.tile * p.nb);
+    *rr = rem / p.nb; *b = rem - *rr * p.nb;
+    return s * p.bh + r0 + *rr;                // row g of the decoded vector
+  };
+  // operand of the element-wise step for the element this thread decodes in phase 2 (E <= 256)
+  float epi_in = 0.f;
+  int g2 = 0, rr2 = 0, b2 = 0;
+  bool live2 = false;
+  if (tid < E) {
+    g2 = row_of(tid, &rr2, &b2);
+    live2 = r0 + rr2 < p.bh && g2 < p.N;
+    if (live2 && p.epi >= 2) epi_in = p.epi_y[(int64_t)g2 * p.nb + b2];
+  }
+  for (int idx = tid; idx < p.nblk * p.P; idx += 256) Dl[idx] = p.D[idx];
+  for (int j = 0; j < p.njobs; ++j)
+    for (int idx = tid; idx < p.P * p.G; idx += 256) cl[j * p.P * p.G + idx] = p.job[j].coef[idx];
+  for (int idx = tid; idx < p.P * E; idx += 256) {
+    const int node = idx / E, e = idx - node * E;
+    int rr, b;
+    const int g = row_of(e, &rr, &b);
+    float t = 0.f;
+    if (r0 + rr < p.bh && g < p.N) {
+      const float* src = p.in + (int64_t)node * p.node_stride + (int64_t)(g % p.len) * p.nb + b;
+      if (p.nred == 1) {
+        t = src[0];
+      } else {
+        // (chunk order, as reduce_chunks_kernel adds them; four loads in flight at a time)
+        int k = 0;
+        for (; k + 4 <= p.nred; k += 4) {
+          const float a0 = src[(int64_t)k * p.red_stride], a1 = src[(int64_t)(k + 1) * p.red_stride];
+          const float a2 = src[(int64_t)(k + 2) * p.red_stride], a3 = src[(int64_t)(k + 3) * p.red_stride];
+          t += a0; t += a1; t += a2; t += a3;
+        }
+        for (; k < p.nred; ++k) t += src[(int64_t)k * p.red_stride];
+      }
+    }
+    tsum[idx] = t;
+  }
+  __syncthreads();
+  if (tid < E) {
+    float v = 0.f;
+    if (live2) {
+      const float* drow = Dl + (g2 / p.len) * p.P;
+      float acc = 0.f;
+      for (int node = 0; node < p.P; ++node) acc = fmaf(drow[node], tsum[node * E + tid], acc);
+      const int64_t o = (int64_t)g2 * p.nb + b2;
+      if (p.epi == 1) {
+        v = 1.f / (1.f + expf(-acc));
+      } else if (p.epi == 2) {
+        v = acc * epi_in * (1.f - epi_in);
+      } else if (p.epi == 3) {
+        const float yh = 1.f / (1.f + expf(-acc));
+        p.out[o] = yh;
+        v = p.scale * (epi_in - yh) * yh * (1.f - yh);
+      } else {
+        v = acc;
+      }
+      (p.epi == 3 ? p.out2 : p.out)[o] = v;
+    }
+    vals[tid] = v;
+  }
+  __syncthreads();
+  const int per_job = p.P * p.tile * p.nb;
+  for (int idx = tid; idx < p.njobs * per_job; idx += 256) {
+    const int j = idx / per_job, rem = idx - j * per_job;
+    const int node = rem / (p.tile * p.nb), rb = rem - node * (p.tile * p.nb);
+    const int rr = rb / p.nb;
+    if (r0 + rr >= p.bh) continue;
+    const float* crow = cl + (j * p.P + node) * p.G;
+    float a = 0.f;
+    for (int s = 0; s < p.G; ++s) a = fmaf(crow[s], vals[s * p.tile * p.nb + rb], a);
+    p.job[j].out[((int64_t)node * p.bh + r0) * p.nb + rb] = a;
+  }
+}
+
 size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 
 }  // namespace
@@ -429,6 +554,7 @@ struct gpd_layer {
   bool upd_fp16 = false;           // (bf16 layers) two fp16 planes of the operand / 2^E
   int exp_Dh = 0, exp_Xh = 0;      // bits the encoded update operands can exceed Delta, X by
   size_t off_scal = 0;             // partial maxima of |Delta|, |X| and the two exponents E
+  size_t off_delta = 0;            // this layer's error Delta (N_out x batch) in gpd_mlp_step
   int nchunks = 0;
   int64_t flag_cap = 0, loc_cap = 0;
   size_t dec_bytes = 0;
@@ -537,6 +663,7 @@ extern "C" gpd_status_t gpd_layer_create(const gpd_layer_desc_t* d, gpd_layer_t*
   L->off_Xh = take((size_t)P * L->wc * d->batch * ues);
   L->off_part = take((size_t)P * L->nchunks * L->wc * L->nb2 * 4);
   L->off_scal = take((size_t)(2 * kAmaxParts + 2) * 4);
+  L->off_delta = take((size_t)L->N_out_pad * d->batch * 4);
   const int64_t ncw = std::max(L->wr * L->nb1, L->wc * L->nb2);
   decode_workspace_layout(ncw, &L->flag_cap, &L->loc_cap, &L->dec_bytes);
   // the node search needs room for its partial Gram matrices (forward, backward and weight stacks)
@@ -587,6 +714,7 @@ extern "C" gpd_status_t gpd_layer_workspace_view(const gpd_layer_t* L, int32_t w
     case 6:
       if (!L->upd_fp16) return fail(GPD_E_INVALID, "gpd_layer_workspace_view: the layer holds no fp16 planes");
       *byte_offset = L->off_scal + (size_t)2 * kAmaxParts * 4; *rows = 1; *cols = 2; break;
+    case 7: *byte_offset = L->off_delta; *rows = L->N_out_pad; *cols = L->desc.batch; break;
     default: return fail(GPD_E_INVALID, "gpd_layer_workspace_view: unknown buffer %d", which);
   }
   return GPD_OK;
@@ -749,9 +877,9 @@ extern "C" gpd_status_t gpd_layer_project(const gpd_layer_t* Lc, float* Wt, cons
       if ((sp.in_off[q] | sp.out_off[q]) & 3) return fail(GPD_E_SHAPE, "projection: block offsets not 16-byte aligned");
     }
     const dim3 grid((unsigned)((n / 128 + 3) / 4)), block(256);
-    if (t.nin <= 16) hipLaunchKernelGGL(stack_mfma_kernel<8>, grid, block, 0, L->stream, sp);
-    else if (t.nin <= 24) hipLaunchKernelGGL(stack_mfma_kernel<12>, grid, block, 0, L->stream, sp);
-    else hipLaunchKernelGGL(stack_mfma_kernel<16>, grid, block, 0, L->stream, sp);
+    if (t.nin <= 16) GPD_LAUNCH(stack_mfma_kernel<8>, grid, block, 0, L->stream, sp);
+    else if (t.nin <= 24) GPD_LAUNCH(stack_mfma_kernel<12>, grid, block, 0, L->stream, sp);
+    else GPD_LAUNCH(stack_mfma_kernel<16>, grid, block, 0, L->stream, sp);
     GPD_HIP(hipGetLastError());
     return GPD_OK;
   }
@@ -767,7 +895,7 @@ namespace {
 template <int NB>
 void launch_skinny_fwd(hipStream_t s, const float* Wt, const float* Xt, float* St, int rows, int cols, int P) {
   constexpr int FR = fwd_rows(NB);
-  hipLaunchKernelGGL((skinny_forward_kernel<NB>), dim3((rows + FR - 1) / FR, P), dim3(256), 0, s, Wt, Xt,
+  GPD_LAUNCH((skinny_forward_kernel<NB>), dim3((rows + FR - 1) / FR, P), dim3(256), 0, s, Wt, Xt,
                      St, rows, cols);
 }
 
@@ -795,10 +923,10 @@ gpd_status_t launch_skinny_bu(hipStream_t s, float* Wt, const float* Dt, const f
                               bool do_bwd) {
   dim3 grid((cols + 1023) / 1024, nchunks, P), block(256);
   if (do_bwd)
-    hipLaunchKernelGGL((skinny_backward_update_kernel<NB2, NBU, true, true>), grid, block, 0, s, Wt, Dt, Dh, Xh,
+    GPD_LAUNCH((skinny_backward_update_kernel<NB2, NBU, true, true>), grid, block, 0, s, Wt, Dt, Dh, Xh,
                        part, rows, cols, nchunks, keep, eta);
   else
-    hipLaunchKernelGGL((skinny_backward_update_kernel<0, NBU, false, true>), grid, block, 0, s, Wt, Dt, Dh, Xh,
+    GPD_LAUNCH((skinny_backward_update_kernel<0, NBU, false, true>), grid, block, 0, s, Wt, Dt, Dh, Xh,
                        part, rows, cols, nchunks, keep, eta);
   GPD_HIP(hipGetLastError());
   return GPD_OK;
@@ -865,8 +993,8 @@ extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, floa
     if (!fuse_act || act_in_decode || !o || n == 0 || (dst != GPD_OK && dst != GPD_E_DECODE_FAIL)) return dst;
     const std::string why = dst == GPD_OK ? std::string() : std::string(gpd_last_error());
     const dim3 grid((unsigned)((n + 255) / 256)), block(256);
-    if (phase == GPD_STEP_FORWARD) hipLaunchKernelGGL(sigmoid_fwd_kernel, grid, block, 0, L->stream, o, o, n);
-    else hipLaunchKernelGGL(sigmoid_bwd_kernel, grid, block, 0, L->stream, o, X, o, n);
+    if (phase == GPD_STEP_FORWARD) GPD_LAUNCH(sigmoid_fwd_kernel, grid, block, 0, L->stream, o, o, n);
+    else GPD_LAUNCH(sigmoid_bwd_kernel, grid, block, 0, L->stream, o, X, o, n);
     GPD_HIP(hipGetLastError());
     if (dst != GPD_OK) return fail(dst, "%s", why.c_str());
     return dst;
@@ -971,7 +1099,7 @@ extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, floa
     int64_t most = 0;
     for (int q = 0; q < nj; ++q) most = std::max<int64_t>(most, sj.job[q].count);
     if (most > 0) {
-      hipLaunchKernelGGL(encode_small_kernel, dim3((unsigned)((most + 255) / 256), nj), dim3(256), 0, s, sj);
+      GPD_LAUNCH(encode_small_kernel, dim3((unsigned)((most + 255) / 256), nj), dim3(256), 0, s, sj);
       GPD_HIP(hipGetLastError());
     }
   } else {
@@ -987,7 +1115,7 @@ extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, floa
       AbsMaxJobs aj;
       aj.x[0] = Dlt; aj.n[0] = d.N_out * d.batch; aj.x[1] = X; aj.n[1] = d.N_in * d.batch;
       aj.parts = scal;
-      hipLaunchKernelGGL(absmax_kernel, dim3(kAmaxParts, 2), dim3(256), 0, s, aj);
+      GPD_LAUNCH(absmax_kernel, dim3(kAmaxParts, 2), dim3(256), 0, s, aj);
       GPD_HIP(hipGetLastError());
       sd.amax_parts = scal; sd.amax_n = kAmaxParts; sd.exp_extra = L->exp_Dh; sd.exp_out = exps;
       sx.amax_parts = scal + kAmaxParts; sx.amax_n = kAmaxParts; sx.exp_extra = L->exp_Xh; sx.exp_out = exps + 1;
@@ -1014,7 +1142,7 @@ extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, floa
     if (st != GPD_OK) return st;
     if (do_bwd) {
       const int64_t per_node = L->wc * L->nb2, total = per_node * P;
-      hipLaunchKernelGGL(reduce_chunks_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, part, Ct,
+      GPD_LAUNCH(reduce_chunks_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, part, Ct,
                          per_node, L->nchunks, total);
       GPD_HIP(hipGetLastError());
     }
@@ -1066,12 +1194,201 @@ extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, floa
                               dec_ws, L->dec_bytes, report), out, d.N_in * d.batch);
 }
 
+// ---------------------------------------------------------------- a whole iteration, small batches
+
+namespace {
+
+// Rows `useful` of the least-squares decoding matrix over all P nodes, as a device table [nout][P].
+gpd_status_t decode_rows(gpd_layer_t* L, int K, const std::vector<int>& useful, const char* name, CombineTable* t) {
+  const Code& c = L->fwd;
+  std::string key(name);
+  key_add(&key, K);
+  return L->ring.cached(key, [&](HostCombineTable* ht) {
+    const int P = (int)c.pts.size();
+    std::vector<int> S(P);
+    for (int q = 0; q < P; ++q) S[q] = q;
+    std::vector<double> D;
+    gpd_status_t st = decode_matrices(c.pts, S, K, useful, false, &D, nullptr);
+    if (st != GPD_OK) return st;
+    ht->nin = P; ht->nout = (int)useful.size(); ht->r = 0;
+    ht->in_off.assign(P, 0); ht->out_off.assign(ht->nout, 0); ht->node.resize(P);
+    for (int q = 0; q < P; ++q) ht->node[q] = q;
+    ht->coef = D;
+    return GPD_OK;
+  }, L->stream, t);
+}
+
+gpd_status_t launch_stage(hipStream_t s, StageParams sp) {
+  // rows per workgroup: few enough for some 256 workgroups (the kernel is latency, the chip is
+  // empty otherwise), and a thread of phase 2 per decoded element (at most 256 per workgroup)
+  int tile = std::max(1, std::min(sp.bh / 256, 16));
+  while (tile > 1 && sp.G * tile * sp.nb > 256) --tile;
+  if (sp.G * tile * sp.nb > 256) return fail(GPD_E_UNSUPPORTED, "mlp step: vectors too wide for the fused stage");
+  sp.tile = tile;
+  const size_t E = (size_t)sp.G * tile * sp.nb;
+  const size_t lds = ((size_t)(sp.P + 1) * E + (size_t)sp.nblk * sp.P + (size_t)sp.njobs * sp.P * sp.G) * sizeof(float);
+  if (lds > 60 * 1024) return fail(GPD_E_UNSUPPORTED, "mlp step: vectors too wide for the fused stage");
+  GPD_LAUNCH(vector_stage_kernel, dim3((unsigned)((sp.bh + tile - 1) / tile)), dim3(256), lds, s, sp);
+  GPD_HIP(hipGetLastError());
+  return GPD_OK;
+}
+
+}  // namespace
+
+extern "C" gpd_status_t gpd_mlp_step(gpd_layer_t* const* layers, int32_t n_layers, float* const* Wt,
+                                     const float* X, const float* Y, float eta, float decay,
+                                     float* const* acts, void* const* workspaces,
+                                     const size_t* workspace_bytes) {
+  if (!layers || n_layers < 1 || !Wt || !X || !Y || !acts || !workspaces || !workspace_bytes)
+    return fail(GPD_E_INVALID, "gpd_mlp_step: null argument");
+  if (n_layers > 64) return fail(GPD_E_INVALID, "gpd_mlp_step: more than 64 layers");
+  // ---- what this path covers; anything else is the caller's per-layer loop
+  for (int l = 0; l < n_layers; ++l) {
+    const gpd_layer_t* L = layers[l];
+    if (!L || !Wt[l] || !acts[l] || !workspaces[l]) return fail(GPD_E_INVALID, "gpd_mlp_step: null entry for layer %d", l);
+    if (workspace_bytes[l] < L->ws_bytes || ((uintptr_t)workspaces[l] & 255))
+      return fail(GPD_E_WORKSPACE, "gpd_mlp_step: layer %d needs a workspace of %zu aligned bytes", l, L->ws_bytes);
+    const gpd_layer_desc_t& d = L->desc;
+    if (d.worker_dtype != GPD_F32 || !skinny_ok(L) || d.d1 != 1 || d.d2 != 1 || d.batch != layers[0]->desc.batch ||
+        L->stream != layers[0]->stream || d.m > kSmallMaxIn || d.n > kSmallMaxIn)
+      return fail(GPD_E_UNSUPPORTED, "gpd_mlp_step: layer %d is outside the small-batch fp32 path "
+                                     "(batch 1, 2, 4 or 8, d1 = d2 = 1, fp32 workers, one stream)", l);
+    if (l > 0 && d.N_in != layers[l - 1]->desc.N_out)
+      return fail(GPD_E_SHAPE, "gpd_mlp_step: layer %d takes %lld inputs, layer %d gives %lld", l,
+                  (long long)d.N_in, l - 1, (long long)layers[l - 1]->desc.N_out);
+    if (L->wr * d.batch > INT32_MAX / 64 || L->wc * d.batch > INT32_MAX / 64)
+      return fail(GPD_E_UNSUPPORTED, "gpd_mlp_step: layer %d too large", l);
+  }
+  hipStream_t s = layers[0]->stream;
+  const int nb = (int)layers[0]->desc.batch;
+  const float keep = 1.f - decay;
+  gpd_status_t st;
+
+  struct Tables { CombineTable X, Xh, D, Dh, decF, decB; };
+  std::vector<Tables> tab(n_layers);
+  for (int l = 0; l < n_layers; ++l) {
+    gpd_layer_t* L = layers[l];
+    const gpd_layer_desc_t& d = L->desc;
+    const Code& c = L->fwd;
+    st = L->ring.cached("encX", [&](HostCombineTable* ht) {
+      *ht = encode_table(c.pts, c.eB, c.n, c.d, L->wc, L->nb1, d.batch);
+      grid_limits(d.N_in, d.batch, c.n, c.d, L->wc, L->nb1, &ht->in_rows, &ht->in_cols);
+      return GPD_OK;
+    }, s, &tab[l].X);
+    if (st != GPD_OK) return st;
+    st = L->ring.cached("encXh", [&](HostCombineTable* hx) {
+      *hx = encode_table(c.pts, L->eUx, c.n, 1, L->wc, d.batch, d.batch);
+      grid_limits(d.N_in, d.batch, c.n, 1, L->wc, d.batch, &hx->in_rows, &hx->in_cols);
+      return GPD_OK;
+    }, s, &tab[l].Xh);
+    if (st != GPD_OK) return st;
+    st = L->ring.cached("encD", [&](HostCombineTable* ht) {
+      *ht = encode_table(c.pts, L->eD, c.m, d.d2, L->wr, L->nb2, d.batch);
+      grid_limits(d.N_out, d.batch, c.m, d.d2, L->wr, L->nb2, &ht->in_rows, &ht->in_cols);
+      return GPD_OK;
+    }, s, &tab[l].D);
+    if (st != GPD_OK) return st;
+    st = L->ring.cached("encDh", [&](HostCombineTable* hd) {
+      *hd = encode_table(c.pts, L->eUd, c.m, 1, L->wr, d.batch, d.batch);
+      grid_limits(d.N_out, d.batch, c.m, 1, L->wr, d.batch, &hd->in_rows, &hd->in_cols);
+      return GPD_OK;
+    }, s, &tab[l].Dh);
+    if (st != GPD_OK) return st;
+    st = decode_rows(L, c.K, c.eC, "rowsF", &tab[l].decF);
+    if (st != GPD_OK) return st;
+    st = decode_rows(L, L->Kb, L->eCb, "rowsB", &tab[l].decB);
+    if (st != GPD_OK) return st;
+    if (tab[l].decF.nin != d.P || tab[l].decB.nin != d.P || tab[l].X.nin != c.n || tab[l].Xh.nin != c.n ||
+        tab[l].D.nin != c.m || tab[l].Dh.nin != c.m)
+      return fail(GPD_E_UNSUPPORTED, "gpd_mlp_step: unexpected table shape for layer %d", l);
+  }
+  auto ws = [&](int l, size_t off) { return (float*)((char*)workspaces[l] + off); };
+
+  // ---- feedforward stage: X~ and X^ of the first layer from the input, then product and vector stage per layer
+  {
+    gpd_layer_t* L = layers[0];
+    const gpd_layer_desc_t& d = L->desc;
+    const Code& c = L->fwd;
+    SmallEncJobs sj;
+    const int P = d.P;
+    if (!make_small(tab[0].X, X, d.batch, d.N_in, d.batch, c.n, c.d, L->wc, L->nb1, ws(0, L->off_Xt), P, &sj.job[0]) ||
+        !make_small(tab[0].Xh, X, d.batch, d.N_in, d.batch, c.n, 1, L->wc, d.batch, ws(0, L->off_Xh), P, &sj.job[1]))
+      return fail(GPD_E_UNSUPPORTED, "gpd_mlp_step: the first layer's encodes do not fit the small-operand kernel");
+    const int64_t most = std::max<int64_t>(sj.job[0].count, sj.job[1].count);
+    if (most > 0) {
+      GPD_LAUNCH(encode_small_kernel, dim3((unsigned)((most + 255) / 256), 2), dim3(256), 0, s, sj);
+      GPD_HIP(hipGetLastError());
+    }
+  }
+  for (int l = 0; l < n_layers; ++l) {
+    gpd_layer_t* L = layers[l];
+    const gpd_layer_desc_t& d = L->desc;
+    const int P = d.P;
+    st = skinny_forward(s, Wt[l], ws(l, L->off_Xt), ws(l, L->off_St), L->wr, L->wc, P, nb);   // step O1
+    if (st != GPD_OK) return st;
+    StageParams sp{};
+    sp.in = ws(l, L->off_St); sp.node_stride = L->wr * nb; sp.red_stride = 0;
+    sp.P = P; sp.nred = 1; sp.len = (int)L->wr; sp.nb = nb;
+    sp.D = tab[l].decF.coef; sp.nblk = tab[l].decF.nout; sp.N = (int)d.N_out;
+    sp.out = acts[l];
+    if (l + 1 < n_layers) {
+      // C1, then the next layer's X~ and X^
+      gpd_layer_t* Ln = layers[l + 1];
+      sp.epi = 1;
+      sp.bh = (int)Ln->wc; sp.G = Ln->fwd.n; sp.njobs = 2;
+      sp.job[0] = StageJob{tab[l + 1].X.coef, ws(l + 1, Ln->off_Xt)};
+      sp.job[1] = StageJob{tab[l + 1].Xh.coef, ws(l + 1, Ln->off_Xh)};
+    } else {
+      // C1, the error of the L2 loss, then this layer's Delta~ and D^
+      sp.epi = 3; sp.epi_y = Y; sp.scale = 2.f / (float)nb; sp.out2 = ws(l, L->off_delta);
+      sp.bh = (int)L->wr; sp.G = L->fwd.m; sp.njobs = l > 0 ? 2 : 1;
+      sp.job[0] = StageJob{tab[l].Dh.coef, ws(l, L->off_Dh)};
+      sp.job[1] = StageJob{tab[l].D.coef, ws(l, L->off_Dt)};
+    }
+    st = launch_stage(s, sp);
+    if (st != GPD_OK) return st;
+  }
+  // ---- backpropagation and update stages, from the last layer to the first
+  for (int l = n_layers - 1; l >= 0; --l) {
+    gpd_layer_t* L = layers[l];
+    const gpd_layer_desc_t& d = L->desc;
+    const int P = d.P;
+    const bool do_bwd = l > 0;
+    const int rows = (int)L->wr, cols = (int)L->wc;
+    float* part = ws(l, L->off_part);
+    // steps O2 (from the pre-update weights) and O3 in one pass over W~
+    switch (nb) {
+      case 1: st = skinny_bu_nbu<1>(s, Wt[l], ws(l, L->off_Dt), ws(l, L->off_Dh), ws(l, L->off_Xh), part, rows, cols, L->nchunks, P, keep, eta, do_bwd, nb); break;
+      case 2: st = skinny_bu_nbu<2>(s, Wt[l], ws(l, L->off_Dt), ws(l, L->off_Dh), ws(l, L->off_Xh), part, rows, cols, L->nchunks, P, keep, eta, do_bwd, nb); break;
+      case 4: st = skinny_bu_nbu<4>(s, Wt[l], ws(l, L->off_Dt), ws(l, L->off_Dh), ws(l, L->off_Xh), part, rows, cols, L->nchunks, P, keep, eta, do_bwd, nb); break;
+      case 8: st = skinny_bu_nbu<8>(s, Wt[l], ws(l, L->off_Dt), ws(l, L->off_Dh), ws(l, L->off_Xh), part, rows, cols, L->nchunks, P, keep, eta, do_bwd, nb); break;
+      default: st = fail(GPD_E_UNSUPPORTED, "gpd_mlp_step: batch %d", nb);
+    }
+    if (st != GPD_OK) return st;
+    if (!do_bwd) break;
+    // chunk sums, decode, C2 with this layer's input, then the layer below's Delta~ and D^
+    gpd_layer_t* Lp = layers[l - 1];
+    StageParams sp{};
+    sp.in = part; sp.node_stride = (int64_t)L->nchunks * cols * nb; sp.red_stride = (int64_t)cols * nb;
+    sp.P = P; sp.nred = L->nchunks; sp.len = cols; sp.nb = nb;
+    sp.D = tab[l].decB.coef; sp.nblk = tab[l].decB.nout; sp.N = (int)d.N_in;
+    sp.epi = 2; sp.epi_y = l == 0 ? X : acts[l - 1];
+    sp.out = ws(l - 1, Lp->off_delta);
+    sp.bh = (int)Lp->wr; sp.G = Lp->fwd.m; sp.njobs = l - 1 > 0 ? 2 : 1;
+    sp.job[0] = StageJob{tab[l - 1].Dh.coef, ws(l - 1, Lp->off_Dh)};
+    sp.job[1] = StageJob{tab[l - 1].D.coef, ws(l - 1, Lp->off_Dt)};
+    st = launch_stage(s, sp);
+    if (st != GPD_OK) return st;
+  }
+  return GPD_OK;
+}
+
 // ---------------------------------------------------------------- element-wise steps
 
 extern "C" gpd_status_t gpd_sigmoid_fwd(const float* s, float* y, int64_t n, void* stream) {
   if (n < 0 || (n > 0 && (!s || !y))) return fail(GPD_E_INVALID, "gpd_sigmoid_fwd: bad argument");
   if (n == 0) return GPD_OK;
-  hipLaunchKernelGGL(sigmoid_fwd_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, s, y, n);
+  GPD_LAUNCH(sigmoid_fwd_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, s, y, n);
   GPD_HIP(hipGetLastError());
   return GPD_OK;
 }
@@ -1079,7 +1396,7 @@ extern "C" gpd_status_t gpd_sigmoid_fwd(const float* s, float* y, int64_t n, voi
 extern "C" gpd_status_t gpd_sigmoid_bwd(const float* c, const float* y, float* d, int64_t n, void* stream) {
   if (n < 0 || (n > 0 && (!c || !y || !d))) return fail(GPD_E_INVALID, "gpd_sigmoid_bwd: bad argument");
   if (n == 0) return GPD_OK;
-  hipLaunchKernelGGL(sigmoid_bwd_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, c, y, d, n);
+  GPD_LAUNCH(sigmoid_bwd_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, c, y, d, n);
   GPD_HIP(hipGetLastError());
   return GPD_OK;
 }
@@ -1087,7 +1404,7 @@ extern "C" gpd_status_t gpd_sigmoid_bwd(const float* c, const float* y, float* d
 extern "C" gpd_status_t gpd_row_mean(const float* y, int64_t rows, int64_t cols, float* mean, void* stream) {
   if (rows < 0 || cols < 1 || (rows > 0 && (!y || !mean))) return fail(GPD_E_INVALID, "gpd_row_mean: bad argument");
   if (rows == 0) return GPD_OK;
-  hipLaunchKernelGGL(row_mean_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, (hipStream_t)stream, y, rows,
+  GPD_LAUNCH(row_mean_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, (hipStream_t)stream, y, rows,
                      cols, mean);
   GPD_HIP(hipGetLastError());
   return GPD_OK;
@@ -1099,7 +1416,7 @@ extern "C" gpd_status_t gpd_sigmoid_bwd_sparse(const float* c, const float* y, c
   if (rows < 0 || cols < 1 || (n > 0 && (!c || !y || !rho_hat || !d)) || !(rho > 0.f && rho < 1.f))
     return fail(GPD_E_INVALID, "gpd_sigmoid_bwd_sparse: bad argument");
   if (n == 0) return GPD_OK;
-  hipLaunchKernelGGL(sigmoid_bwd_sparse_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+  GPD_LAUNCH(sigmoid_bwd_sparse_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
                      c, y, rho_hat, rho, scale, d, cols, n);
   GPD_HIP(hipGetLastError());
   return GPD_OK;
@@ -1109,7 +1426,7 @@ extern "C" gpd_status_t gpd_l2_delta(const float* y, const float* yhat, float sc
                                      void* stream) {
   if (n < 0 || (n > 0 && (!y || !yhat || !d))) return fail(GPD_E_INVALID, "gpd_l2_delta: bad argument");
   if (n == 0) return GPD_OK;
-  hipLaunchKernelGGL(l2_delta_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, y, yhat,
+  GPD_LAUNCH(l2_delta_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, y, yhat,
                      scale, d, n);
   GPD_HIP(hipGetLastError());
   return GPD_OK;

@@ -694,7 +694,7 @@ __global__ void zero_words_kernel(uint32_t* p, int n) {
 
 gpd_status_t launch_zero_words(hipStream_t stream, void* p, int n_words) {
   if (n_words <= 0) return GPD_OK;
-  hipLaunchKernelGGL(zero_words_kernel, dim3((n_words + 255) / 256), dim3(256), 0, stream,
+  GPD_LAUNCH(zero_words_kernel, dim3((n_words + 255) / 256), dim3(256), 0, stream,
                      (uint32_t*)p, n_words);
   GPD_HIP(hipGetLastError());
   return GPD_OK;
@@ -730,7 +730,7 @@ gpd_status_t launch_locate(hipStream_t stream, const LocateArgs& a) {
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 3 * R_MAX * 64 * (int)sizeof(double)));
     raised = true;
   }
-  hipLaunchKernelGGL(locate_kernel, dim3(blocks), dim3(64), lds, stream, p);
+  GPD_LAUNCH(locate_kernel, dim3(blocks), dim3(64), lds, stream, p);
   GPD_HIP(hipGetLastError());
   return GPD_OK;
 }

@@ -245,12 +245,12 @@ template <int NK, int RT>
 gpd_status_t launch_gram_v(hipStream_t s, const GramParams& p, int vec, int n_wg) {
   const int pack = RT == 1 ? gram_pack(p.r, vec) : 1;
   if constexpr (RT == 1) {
-    if (pack == 4) hipLaunchKernelGGL((gram_kernel<NK, 1, 4, 4>), dim3(n_wg), dim3(256), 0, s, p);
-    else if (pack == 2) hipLaunchKernelGGL((gram_kernel<NK, 1, 4, 2>), dim3(n_wg), dim3(256), 0, s, p);
+    if (pack == 4) GPD_LAUNCH((gram_kernel<NK, 1, 4, 4>), dim3(n_wg), dim3(256), 0, s, p);
+    else if (pack == 2) GPD_LAUNCH((gram_kernel<NK, 1, 4, 2>), dim3(n_wg), dim3(256), 0, s, p);
   }
   if (pack == 1) {
-    if (vec == 4) hipLaunchKernelGGL((gram_kernel<NK, RT, 4, 1>), dim3(n_wg), dim3(256), 0, s, p);
-    else hipLaunchKernelGGL((gram_kernel<NK, RT, 1, 1>), dim3(n_wg), dim3(256), 0, s, p);
+    if (vec == 4) GPD_LAUNCH((gram_kernel<NK, RT, 4, 1>), dim3(n_wg), dim3(256), 0, s, p);
+    else GPD_LAUNCH((gram_kernel<NK, RT, 1, 1>), dim3(n_wg), dim3(256), 0, s, p);
   }
   GPD_HIP(hipGetLastError());
   return GPD_OK;
@@ -278,8 +278,10 @@ size_t gram_workspace_bytes(int64_t ncw, int r) {
 gpd_status_t run_locate_nodes(hipStream_t stream, TableRing* ring, const std::vector<double>& pts,
                               int K, int64_t ncw, const float* Zt, const uint8_t* present, double rho,
                               double abs_floor, void* workspace, size_t workspace_bytes,
-                              gpd_node_report_t* rep, double* gram_out) {
+                              gpd_node_report_t* rep, double* gram_out, int64_t stride) {
   if (!rep) return fail(GPD_E_INVALID, "locate nodes: null report");
+  if (stride == 0) stride = ncw;
+  if (stride < ncw) return fail(GPD_E_SHAPE, "locate nodes: node stride smaller than a block");
   std::memset(rep, 0, sizeof(*rep));
   const int P = (int)pts.size();
   std::vector<int> S;
@@ -303,13 +305,13 @@ gpd_status_t run_locate_nodes(hipStream_t stream, TableRing* ring, const std::ve
   if (st != GPD_OK) { rep->status = st; return st; }
 
   std::string key("gram");
-  key_add(&key, K); key_add(&key, ncw);
+  key_add(&key, K); key_add(&key, ncw); key_add(&key, stride);
   for (int p = 0; p < P; ++p) key.push_back((!present || present[p]) ? 1 : 0);
   CombineTable t;
   st = ring->cached(key, [&](HostCombineTable* ht) {
     ht->nin = ns; ht->nout = 0; ht->r = r;
     ht->in_off.resize(ns); ht->node.resize(ns);
-    for (int q = 0; q < ns; ++q) { ht->in_off[q] = (int64_t)S[q] * ncw; ht->node[q] = S[q]; }
+    for (int q = 0; q < ns; ++q) { ht->in_off[q] = (int64_t)S[q] * stride; ht->node[q] = S[q]; }
     ht->H = H;
     return GPD_OK;
   }, stream, &t);
@@ -332,10 +334,10 @@ gpd_status_t run_locate_nodes(hipStream_t stream, TableRing* ring, const std::ve
   if (st != GPD_OK) return st;
   // two reduction stages, both in a fixed order
   const int groups = std::min(kGramGroups, n_wg);
-  hipLaunchKernelGGL(sum_partials_kernel, dim3(width / 64, groups), dim3(64), 0, stream, gp.part, n_wg, width,
+  GPD_LAUNCH(sum_partials_kernel, dim3(width / 64, groups), dim3(64), 0, stream, gp.part, n_wg, width,
                      d_stage);
   GPD_HIP(hipGetLastError());
-  hipLaunchKernelGGL(sum_partials_kernel, dim3(width / 64, 1), dim3(64), 0, stream, d_stage, groups, width, d_out);
+  GPD_LAUNCH(sum_partials_kernel, dim3(width / 64, 1), dim3(64), 0, stream, d_stage, groups, width, d_out);
   GPD_HIP(hipGetLastError());
 
   // one copy brings the wild flags, the Gram tiles and the energy back
@@ -386,14 +388,14 @@ gpd_status_t run_locate_nodes(hipStream_t stream, TableRing* ring, const std::ve
 namespace {
 
 // z[t][p] = Zt[p][pos_t] for every node p; c[t][q] = entry of output block q at element pos_t
-__global__ void gather_check_kernel(const float* __restrict__ Zt, int P, int64_t ncw, int n_check,
+__global__ void gather_check_kernel(const float* __restrict__ Zt, int P, int64_t ncw, int64_t stride, int n_check,
                                     const float* __restrict__ out, int64_t ld_out, int grid_r, int grid_c,
                                     int64_t bh, int64_t bw, float* __restrict__ z, float* __restrict__ c) {
   const int t = blockIdx.x;
   if (t >= n_check) return;
   const int64_t pos = ((int64_t)t * ncw) / n_check;
   const int64_t r = pos / bw, col = pos - r * bw;
-  for (int p = threadIdx.x; p < P; p += blockDim.x) z[(int64_t)t * P + p] = Zt[(int64_t)p * ncw + pos];
+  for (int p = threadIdx.x; p < P; p += blockDim.x) z[(int64_t)t * P + p] = Zt[(int64_t)p * stride + pos];
   const int nq = grid_r * grid_c;
   for (int q = threadIdx.x; q < nq; q += blockDim.x) {
     const int i = q / grid_c, k = q - i * grid_c;
@@ -434,7 +436,9 @@ gpd_status_t run_verify(hipStream_t stream, const DecodeJob& job, const float* Z
 
   float* d_z = (float*)((char*)workspace + 512);
   float* d_c = d_z + (size_t)n_check * P;
-  hipLaunchKernelGGL(gather_check_kernel, dim3(n_check), dim3(64), 0, stream, Zt, P, ncw, n_check, out, ld_out,
+  const int64_t stride = job.in_stride ? job.in_stride : ncw;
+  if (stride < ncw) return fail(GPD_E_SHAPE, "verify: node stride smaller than a block");
+  GPD_LAUNCH(gather_check_kernel, dim3(n_check), dim3(64), 0, stream, Zt, P, ncw, stride, n_check, out, ld_out,
                      job.grid_r, job.grid_c, job.bh, job.bw, d_z, d_c);
   GPD_HIP(hipGetLastError());
   std::vector<float> hz((size_t)n_check * P), hc((size_t)n_check * nq);

@@ -26,6 +26,8 @@ class CodedMLP:
         # = X, acts[L] = network output), deltas[l] = error Delta of layer l
         self.acts = []
         self.deltas = []
+        self._act_bufs = None
+        self.fused = None              # None: not tried yet; False: the network is outside the fused path
 
     def encode_weights(self, Ws):
         """Ws: list of float32 CUDA tensors (N_out x N_in).  Done once before training."""
@@ -65,6 +67,19 @@ class CodedMLP:
         (None, reports so far) with self.restored set."""
         regenerate = regenerate and int(correct_errors) == B.GPD_CORRECT_NODES
         want_report = want_report or regenerate or restore_on_failure
+        if not (correct_errors or want_report) and self.fused is not False:
+            # small batches, nothing to correct or report: the whole iteration through gpd_mlp_step
+            # (one launch for the master's work between two coded products; same arithmetic)
+            if self._act_bufs is None:
+                import torch
+                self._act_bufs = [torch.empty((L.N_out, L.batch), dtype=torch.float32, device=X.device)
+                                  for L in self.layers]
+            self.fused = B.gpd_mlp_step(self.layers, self.Wts, X, Y, eta, decay, self._act_bufs)
+            if self.fused:
+                self.acts = [X] + self._act_bufs
+                self.deltas = [L.workspace_delta(X.device) for L in self.layers]
+                self.repaired, self.restored = [], False
+                return self._act_bufs[-1], [[None, None] for _ in self.layers]
         acts = [X]
         reps = []
         self.repaired = []

@@ -129,3 +129,90 @@ def test_strided_inputs_and_outputs():
     torch.cuda.synchronize()
     assert rel_fro(to_np(bigC[:, :Nc]), O.uncoded_matmul(A, B)) < 1e-4
     assert torch.all(bigC[:, Nc:] == 7.0)
+
+
+def _spread_stack(plan, which, dtype=torch.float32, fill=7.0):
+    """A coded stack in the plan's layout whose pads are filled with a sentinel."""
+    P, rows, cols = plan.stack_shape(which)
+    stride = plan.strides[which]
+    base = torch.full((P * stride,), fill, dtype=dtype, device=DEV)
+    return base, base.as_strided((P, rows, cols), (stride, cols, 1))
+
+
+def _pads_untouched(plan, which, base, fill=7.0):
+    P, rows, cols = plan.stack_shape(which)
+    stride = plan.strides[which]
+    pads = base.view(P, stride)[:, rows * cols:]
+    return bool(torch.all(pads == fill))
+
+
+@pytest.mark.parametrize("N1,N0,Nc,m,n,d,P,dtype", [(512, 384, 640, 2, 2, 2, 16, "f32"), (300, 204, 140, 2, 2, 2, 12, "f32"),
+                                                    (96, 90, 66, 3, 2, 2, 16, "f32"), (256, 256, 256, 2, 2, 2, 12, "bf16"),
+                                                    (512, 256, 512, 2, 2, 2, 16, "split")])
+def test_spread_layout_gives_the_packed_results(N1, N0, Nc, m, n, d, P, dtype):
+    # GPD_LAYOUT_SPREAD only moves the node blocks of At, Bt, Ct apart: every stage must give bit
+    # for bit what the packed layout gives (parity of the packed layout with the oracle is above),
+    # the pads between the blocks are never written, and every decode path follows the stride.
+    wd = {"f32": G.GPD_F32, "bf16": G.GPD_BF16, "split": G.GPD_F32_SPLIT}[dtype]
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    A, B = WL.matmul_inputs(N1, N0, Nc, seed=N1 + 3)
+    packed = G.gpd_plan(N1, N0, Nc, m, n, d, P, worker_dtype=wd)
+    spread = G.gpd_plan(N1, N0, Nc, m, n, d, P, worker_dtype=wd, layout=G.GPD_LAYOUT_SPREAD)
+    assert packed.strides["C"] == (N1 // m) * (Nc // d) and spread.strides["C"] > packed.strides["C"]
+    At_p, Bt_p = G.gpd_encode(packed, to_dev(A), to_dev(B))
+    Ct_p = G.gpd_worker_products(packed, At_p, Bt_p)
+    baseA, At_s = _spread_stack(spread, "A", tdt)
+    baseB, Bt_s = _spread_stack(spread, "B", tdt)
+    baseC, Ct_s = _spread_stack(spread, "C")
+    G.gpd_encode(spread, to_dev(A), to_dev(B), At_s, Bt_s)
+    G.gpd_worker_products(spread, At_s, Bt_s, Ct_s)
+    torch.cuda.synchronize()
+    assert torch.equal(At_s, At_p) and torch.equal(Bt_s, Bt_p) and torch.equal(Ct_s, Ct_p)
+    assert _pads_untouched(spread, "A", baseA) and _pads_untouched(spread, "B", baseB) and _pads_untouched(spread, "C", baseC)
+    with pytest.raises(ValueError):
+        G.gpd_decode(spread, Ct_p)                      # a packed stack is not this plan's layout
+    present = WL.erasure_trial(77, P, 2)
+    for pres in (None, present):
+        for mode in (G.GPD_DEC_FIRST_K, G.GPD_DEC_LSQ_ALL):
+            C_p, _ = G.gpd_decode(packed, Ct_p, present=pres, mode=mode)
+            C_s, _ = G.gpd_decode(spread, Ct_s, present=pres, mode=mode)
+            assert torch.equal(C_p, C_s)
+    if dtype == "bf16":
+        return
+    # soft errors: element-wise correction, node search, verification step
+    rng = np.random.default_rng(9)
+    rows, cols = N1 // m, Nc // d
+    for _ in range(12):
+        p_, r_, c_ = int(rng.integers(P)), int(rng.integers(rows)), int(rng.integers(cols))
+        for Ct in (Ct_p, Ct_s):
+            Ct[p_, r_, c_] += 25.0
+    Ct_p[0, 1, 1] = float("inf")
+    Ct_s[0, 1, 1] = float("inf")
+    C_p, rep_p = G.gpd_decode(packed, Ct_p, present=present, mode=G.GPD_DEC_LSQ_ALL, correct_errors=G.GPD_CORRECT_ELEMENTS)
+    C_s, rep_s = G.gpd_decode(spread, Ct_s, present=present, mode=G.GPD_DEC_LSQ_ALL, correct_errors=G.GPD_CORRECT_ELEMENTS)
+    assert torch.equal(C_p, C_s)
+    assert [x[:3] for x in rep_p.located] == [x[:3] for x in rep_s.located]
+    assert all(x[3] == y[3] or (np.isnan(x[3]) and np.isnan(y[3])) for x, y in zip(rep_p.located, rep_s.located))
+    assert rep_s.n_located == rep_p.n_located and rep_s.n_failed == rep_p.n_failed
+    if P - 2 - packed.K - 1 >= 1:                         # the code left after two erasures can correct an error
+        assert rep_s.n_located >= 10 and rep_s.n_failed == 0
+    C_st = torch.empty_like(C_s)
+    _, rep_st = G.gpd_decode_static(spread, Ct_s, C_st, present=present, mode=G.GPD_DEC_LSQ_ALL,
+                                    correct_errors=G.GPD_CORRECT_ELEMENTS)
+    assert torch.equal(C_st, C_s) and rep_st.n_located == rep_s.n_located
+    # (fresh responses, then one erroneous node)
+    G.gpd_worker_products(packed, At_p, Bt_p, Ct_p)
+    G.gpd_worker_products(spread, At_s, Bt_s, Ct_s)
+    Ct_p[5] += 0.5
+    Ct_s[5] += 0.5
+    nr_p, g_p = G.gpd_locate_nodes(packed, Ct_p, present=present, want_gram=True)
+    nr_s, g_s = G.gpd_locate_nodes(spread, Ct_s, present=present, want_gram=True)
+    assert nr_s.bad == nr_p.bad and np.array_equal(g_p, g_s)
+    assert 5 in nr_s.bad or P - 2 - packed.K - 1 < 1
+    C_p, _ = G.gpd_decode(packed, Ct_p, present=present, mode=G.GPD_DEC_LSQ_ALL, correct_errors=G.GPD_CORRECT_NODES)
+    C_s, _ = G.gpd_decode(spread, Ct_s, present=present, mode=G.GPD_DEC_LSQ_ALL, correct_errors=G.GPD_CORRECT_NODES)
+    assert torch.equal(C_p, C_s)
+    v_p = G.gpd_verify_decode(packed, Ct_p, C_p, present=present, mode=G.GPD_DEC_LSQ_ALL, bad=nr_p.bad)
+    v_s = G.gpd_verify_decode(spread, Ct_s, C_s, present=present, mode=G.GPD_DEC_LSQ_ALL, bad=nr_s.bad)
+    assert (v_s.status, v_s.n_value_mismatch, v_s.bad) == (v_p.status, v_p.n_value_mismatch, v_p.bad)
+    assert _pads_untouched(spread, "C", baseC)
