@@ -6,7 +6,8 @@ paper and independent of the GPU library (no shared code, tables or helpers).
 Only tests, the smoke check and the benchmark's cpu_baseline leg may import it.
 
 Every function names the passage of the paper it follows.  Library primitives
-used as single steps: numpy matmul, numpy.linalg.solve / lstsq / qr.
+used as single steps: numpy matmul, numpy.linalg.solve / lstsq / qr, and
+scipy.optimize.linprog for the one linear program (l1_locate).
 
 Notation (paper -> here): W -> A (N1 x N0, split m x n), X -> B (N0 x Nc, split
 n x d), S -> C (split m x d); b_p are the P distinct evaluation points; the
@@ -29,7 +30,10 @@ Readings taken where the paper is silent (all restated in the design notes):
   * the polynomial-time locator the remark after Thm 3 asks for is the classical
     algebraic one (locator polynomial from the syndromes, in the Chebyshev basis),
     valid inside the adversarial radius floor((P-Q)/2) and accepted by Algorithm 1's
-    own criterion (algebraic_locate).
+    own criterion (algebraic_locate);
+  * the L1-norm relaxation the same remark names is the linear program min ||e||_1 subject to
+    H e = H z; its solution only proposes supports (its largest entries), Algorithm 1's
+    criterion accepts (l1_locate).
 Parity pins: see tests/test_oracle_*.py.  Unpinned: the numeric value of rho
 (this build's choice).
 """
@@ -380,6 +384,70 @@ def algebraic_locate(z: np.ndarray, H: np.ndarray, pts: np.ndarray, tau: float, 
     return "failed", forced, np.zeros(len(forced))
 
 
+# --------------------------------------------------------------------------- L1 relaxation
+
+
+def l1_minimiser(H: np.ndarray, y: np.ndarray, free_cost=None) -> np.ndarray:
+    """argmin sum_i cost_i |e_i| subject to H e = y (cost_i = 1, or 0 for entries that
+    may take any value at no cost), as the linear program in e = e+ - e-, e+, e- >= 0:
+    the L1-norm relaxation of arg-min ||e||_0 (remark after Thm 3, "decoding by linear
+    programming").  Equivalently the least-absolute-deviations fit of a codeword to z:
+    e = z - V c with c = argmin ||z - V c||_1, since H e = H z fixes e up to a codeword."""
+    from scipy.optimize import linprog
+
+    r, n = H.shape
+    cost = np.ones(n) if free_cost is None else np.asarray(free_cost, dtype=np.float64)
+    scale = float(np.abs(y).max())
+    if scale == 0.0:
+        return np.zeros(n)
+    # (solved for y / max|y| with the solver's tightest tolerances, so that entries at the level of
+    # the responses' rounding noise are not cut off as infeasibilities)
+    res = linprog(np.concatenate([cost, cost]), A_eq=np.hstack([H, -H]), b_eq=y / scale,
+                  bounds=[(0, None)] * (2 * n), method="highs-ds",
+                  options={"primal_feasibility_tolerance": 1e-10, "dual_feasibility_tolerance": 1e-10})
+    if res.status != 0:
+        raise RuntimeError(f"linear program not solved: {res.message}")
+    return scale * (res.x[:n] - res.x[n:])
+
+
+def l1_locate(z: np.ndarray, H: np.ndarray, tau: float, forced=()):
+    """Error location by L1-norm relaxation (remark after Thm 3: the arg-min ||e||_0 of
+    Algorithm 1 is NP-hard in general; an L1-norm relaxation is one of the polynomial-time
+    sparse reconstructions it suggests).
+
+      e* = argmin ||e||_1 subject to H e = H z (entries at known-bad, forced nodes cost nothing);
+      the nodes are ranked by |e*| (largest first, ties: the lowest node); for sizes 1, 2, ...
+      the forced nodes plus the first nodes of that ranking are the candidate support, and the
+      first candidate that meets the criterion of Algorithm 1 (residual of H z on the span of
+      those columns of H <= tau, at most P - Q - 1 nodes) is returned with its least-squares
+      error values.
+
+    The linear program only proposes: what is accepted passes Algorithm 1's own test.  In exact
+    arithmetic (tau -> 0) a wrong support of at most P - Q - 1 nodes passes it with probability
+    zero (Thm 3), so what is accepted is the support the exhaustive search would return; with a
+    finite tau a larger support can pass where the ranking went wrong, which the search, trying
+    small supports first, would not return.  Where no prefix of the ranking passes, the word is a
+    decoding failure although the search might still succeed: the relaxation recovers fewer
+    errors than P - Q - 1 (how many depends on H; measured in the tests).
+    Returns (status, support, e_hat) like algorithm1."""
+    r, ns = H.shape
+    y = H @ z
+    forced = tuple(sorted(int(f) for f in forced))
+    if not forced and np.linalg.norm(y) <= tau:
+        return "clean", (), np.zeros(0)
+    cost = np.ones(ns)
+    cost[list(forced)] = 0.0
+    e_star = l1_minimiser(H, y, cost)
+    free = [q for q in range(ns) if q not in forced]
+    ranking = sorted(free, key=lambda q: (-abs(e_star[q]), q))
+    for size in range(max(len(forced), 1), r):
+        supp = tuple(sorted(forced + tuple(ranking[:size - len(forced)])))
+        res, e = support_residual(H, y, supp)
+        if res <= tau:
+            return "located", supp, e
+    return "failed", forced, np.zeros(len(forced))
+
+
 # --------------------------------------------------------------------------- decode
 
 
@@ -467,6 +535,8 @@ def decode_coefficients(Zt: np.ndarray, points: np.ndarray, K: int, useful,
         forced = tuple(np.flatnonzero(~finite[:, idx]))
         if locator == "algebraic":
             status, supp, e_hat = algebraic_locate(Zs[:, idx], H, pts, float(tau[idx]), forced)
+        elif locator == "l1":
+            status, supp, e_hat = l1_locate(Zs[:, idx], H, float(tau[idx]), forced)
         else:
             status, supp, e_hat = algorithm1(Zs[:, idx], H, float(tau[idx]), forced)
         if status == "failed":
