@@ -410,12 +410,25 @@ def l1_minimiser(H: np.ndarray, y: np.ndarray, free_cost=None) -> np.ndarray:
     return scale * (res.x[:n] - res.x[n:])
 
 
+def l1_costs(ns: int) -> np.ndarray:
+    """Costs 1 + 1e-6 frac((s + 1)^2 phi), phi = (sqrt(5) - 1) / 2, of an error at node s of ns.
+    With equal costs the linear program of l1_locate often has several optimal vertices on
+    symmetric point sets such as the Chebyshev points (two vertices can differ by a codeword
+    whose few non-zero values cancel in the sum of magnitudes), and which of them a solver
+    returns is the solver's affair; slightly unequal costs in no regular pattern leave one
+    (a rotation frac(s phi) does not: its differences between neighbours are all equal and
+    cancel in exactly those sums).  This build's choice; the paper only names the relaxation."""
+    s = np.arange(1, ns + 1, dtype=np.float64)
+    return 1.0 + 1e-6 * ((s * s * 0.6180339887498949) % 1.0)
+
+
 def l1_locate(z: np.ndarray, H: np.ndarray, tau: float, forced=()):
     """Error location by L1-norm relaxation (remark after Thm 3: the arg-min ||e||_0 of
     Algorithm 1 is NP-hard in general; an L1-norm relaxation is one of the polynomial-time
     sparse reconstructions it suggests).
 
-      e* = argmin ||e||_1 subject to H e = H z (entries at known-bad, forced nodes cost nothing);
+      e* = argmin sum_s c_s |e_s| subject to H e = H z, with c_s = 1 up to a tie-breaking 1e-6
+      (l1_costs) and c_s = 0 at known-bad (forced) nodes;
       the nodes are ranked by |e*| (largest first, ties: the lowest node); for sizes 1, 2, ...
       the forced nodes plus the first nodes of that ranking are the candidate support, and the
       first candidate that meets the criterion of Algorithm 1 (residual of H z on the span of
@@ -435,7 +448,7 @@ def l1_locate(z: np.ndarray, H: np.ndarray, tau: float, forced=()):
     forced = tuple(sorted(int(f) for f in forced))
     if not forced and np.linalg.norm(y) <= tau:
         return "clean", (), np.zeros(0)
-    cost = np.ones(ns)
+    cost = l1_costs(ns)
     cost[list(forced)] = 0.0
     e_star = l1_minimiser(H, y, cost)
     free = [q for q in range(ns) if q not in forced]

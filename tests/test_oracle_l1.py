@@ -41,15 +41,16 @@ def test_l1_minimiser_equals_brute_force_over_vertices(P, K):
         pts = np.sort(rng.uniform(-1, 1, P)) if generic else O.chebyshev_points(P)
         H, V = O.parity_check(pts, K), O.vandermonde(pts, K)
         z = rng.standard_normal(P)
-        cost = np.ones(P)
+        # the locator's costs (1 up to a tie-breaking 1e-6) where the points are symmetric, else ones
+        cost = np.ones(P) if generic else O.l1_costs(P)
         if trial >= 3:
             cost[rng.choice(P, 1)] = 0.0                   # a known-bad entry costs nothing
         e = O.l1_minimiser(H, H @ z, cost)
         f_ref, e_ref = _brute_force_lad(z, V, cost)
         assert np.abs(H @ e - H @ z).max() < 1e-10         # feasible: e differs from z by a codeword
         assert abs(np.sum(cost * np.abs(e)) - f_ref) < 1e-9 * max(1.0, f_ref)
-        if generic:
-            assert np.abs(e - e_ref).max() < 1e-8          # (the optimum is unique for generic data)
+        # (the optimum is unique for generic data, and on Chebyshev points with the tie-breaking costs)
+        assert np.abs(e - e_ref).max() < 1e-8
 
 
 def test_l1_minimiser_one_parity_row_closed_form():
@@ -160,3 +161,36 @@ def test_decode_with_the_l1_locator_corrects_what_it_locates():
     C, rep = O.decode(Ct, plan, mode="lsq_all", correct=True, rho=1e-9, locator="l1")
     assert rep.n_failed == 0 and [(n, r, c) for n, r, c, _ in rep.located] == [(3, 1, 2), (12, 3, 0)]
     assert np.abs(C - A @ B).max() < 1e-8
+
+
+def test_tie_breaking_costs_leave_one_optimum_on_chebyshev_points():
+    """On the (12, 9) Chebyshev code about every third word with one or two errors has several
+    optimal vertices under equal costs (equal objective, different e); with the locator's costs the
+    brute-force minimum over all vertices is attained once, and it is the solver's answer."""
+    P, K = 12, 9
+    pts, H, V = _code(P, K)
+    cost = O.l1_costs(P)
+    assert np.all(cost >= 1.0) and np.all(cost < 1.0 + 1e-6) and len(set(cost.tolist())) == P
+    rng = np.random.default_rng(1)
+    ties = 0
+    for trial in range(12):
+        z = (V @ rng.standard_normal(K)).astype(np.float32).astype(np.float64)
+        A = rng.choice(P, 1 + trial % 2, replace=False)
+        z[A] += rng.uniform(1, 3, len(A)) * rng.choice([-1.0, 1.0], len(A))
+        vals = []
+        import itertools as it_
+        for B in it_.combinations(range(P), K):
+            e = z - V @ np.linalg.solve(V[list(B)], z[list(B)])
+            e[list(B)] = 0.0
+            vals.append((float(np.sum(cost * np.abs(e))), float(np.sum(np.abs(e))), e))
+        vals.sort(key=lambda v: v[0])
+        best = vals[0]
+        # no other vertex within 1e-9 of the weighted optimum unless it is the same point up to entries
+        # at the level of the responses' rounding (1e-7 of the largest)
+        for v in vals[1:6]:
+            assert v[0] - best[0] > 1e-9 * best[0] or np.abs(v[2] - best[2]).max() < 1e-7 * np.abs(best[2]).max()
+        plain = sorted(vals, key=lambda v: v[1])
+        ties += any(abs(v[1] - plain[0][1]) < 1e-12 and np.abs(v[2] - plain[0][2]).max() > 1e-6 for v in plain[1:4])
+        e_lp = O.l1_minimiser(H, H @ z, cost)
+        assert np.abs(e_lp - best[2]).max() < 1e-7 * np.abs(best[2]).max()
+    assert ties >= 2                                        # (equal costs: the ties are really there)
