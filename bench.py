@@ -237,6 +237,15 @@ def bench_faults(args, cfg):
     ms_many_async = timed(lambda t: G.gpd_decode(plan, Ctm, mode=G.GPD_DEC_LSQ_ALL,
                                                  correct_errors=G.GPD_CORRECT_ELEMENTS, workspace=ws, C_out=C,
                                                  want_report=False))
+    # (the same stack with the search replaced by the L1 relaxation: a linear program per screened
+    # codeword, solved by simplex steps on the wavefront)
+    l1_rep = [None, None]
+
+    def many_l1(t):
+        _, l1_rep[0] = G.gpd_decode(plan, Ctm, mode=G.GPD_DEC_LSQ_ALL, correct_errors=G.GPD_CORRECT_ELEMENTS_L1,
+                                    workspace=ws, C_out=C, located_cap=16)
+
+    ms_l1 = timed(many_l1)
     del Ctm
 
     # (2) whole-node errors: Gram pass + host search, then the decode without the bad nodes
@@ -296,6 +305,13 @@ def bench_faults(args, cfg):
 
     ms_alg = timed(many)
 
+    # (L1 relaxation on this stack too)
+    def many_l1_long(t):
+        _, l1_rep[1] = G.gpd_decode(plan4, Ct4, mode=G.GPD_DEC_LSQ_ALL, correct_errors=G.GPD_CORRECT_ELEMENTS_L1,
+                                    workspace=ws4, C_out=C4, located_cap=16)
+
+    ms_l1_long = timed(many_l1_long)
+
     gb = lambda b, ms: b / (ms * 1e-3) / 1e9
     out = {"metric": "fault-path stage times", "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "data": "synthetic", "dtype": "f32",
@@ -323,7 +339,16 @@ def bench_faults(args, cfg):
                                 "us_per_codeword": ms_alg * 1e3 / n_cw,
                                 "note": "P = 48, K = 9 (39 syndromes), 256 of 65536 codewords with 8 errors each: whole "
                                         "decode call incl. screen and report; the exhaustive search would have to try "
-                                        "C(48, 8) = 3.8e8 supports per codeword"}}
+                                        "C(48, 8) = 3.8e8 supports per codeword"},
+           "l1_relaxation": {"ms": ms_l1, "codewords": n_many, "errors_per_codeword": t_many,
+                             "located": int(l1_rep[0].n_located), "failed": int(l1_rep[0].n_failed),
+                             "ns_per_codeword": ms_l1 * 1e6 / n_many,
+                             "P48": {"ms": ms_l1_long, "codewords": n_cw, "errors_per_codeword": t_err,
+                                     "located": int(l1_rep[1].n_located), "failed": int(l1_rep[1].n_failed),
+                                     "us_per_codeword": ms_l1_long * 1e3 / n_cw},
+                             "note": "GPD_CORRECT_ELEMENTS_L1 on the stacks of decode_screen_correct_many (P = 16, "
+                                     "K = 9) and algebraic_locate (P = 48, K = 9): whole decode call with report; "
+                                     "codewords whose L1 ranking has no admissible prefix count as failed"}}
     print(json.dumps(out), flush=True)
 
 

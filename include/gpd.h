@@ -78,8 +78,17 @@ typedef enum {
 typedef enum {
   GPD_CORRECT_NONE = 0,     /* erasures only                                                  */
   GPD_CORRECT_ELEMENTS = 1, /* Algorithm 1 on every element codeword (errors anywhere)        */
-  GPD_CORRECT_NODES = 2     /* Algorithm 1 once for the whole stack: an erroneous node's whole
+  GPD_CORRECT_NODES = 2,    /* Algorithm 1 once for the whole stack: an erroneous node's whole
                                output is wrong (error models of Sec. III); see gpd_locate_nodes */
+  GPD_CORRECT_ELEMENTS_L1 = 3 /* like GPD_CORRECT_ELEMENTS with the search of step 2 replaced by the
+                               L1-norm relaxation the remark after Thm 3 names: e* = argmin ||e||_1
+                               subject to H e = H z (a linear program, solved exactly by simplex
+                               steps per screened codeword; non-finite entries cost nothing), the
+                               nodes ranked by |e*|, and the first prefix of that ranking (with the
+                               non-finite entries) that meets Algorithm 1's criterion is the support.
+                               Polynomial time for any code length, but it locates fewer errors
+                               than the search: a codeword whose ranking has no such prefix of at
+                               most min(|S| - K - 1, 24) nodes is a decoding failure. */
 } gpd_correct_t;
 
 /* How the P blocks of a coded stack (At, Bt, Ct of a matmul plan) lie in memory.
@@ -209,8 +218,8 @@ gpd_status_t gpd_decode(const gpd_plan_t* plan, const float* Ct, const uint8_t* 
  * screen's bit map, the list of located entries) is a fixed array inside the library, about 1.5 MiB
  * on every GPU the library runs on, held until the process ends.  The call allocates no device
  * memory and frees none.
- *   correct_errors: GPD_CORRECT_NONE or GPD_CORRECT_ELEMENTS (GPD_CORRECT_NODES ->
- *            GPD_E_UNSUPPORTED).
+ *   correct_errors: GPD_CORRECT_NONE, GPD_CORRECT_ELEMENTS or GPD_CORRECT_ELEMENTS_L1
+ *            (GPD_CORRECT_NODES -> GPD_E_UNSUPPORTED).
  *   limits:  blocks of at most GPD_STATIC_MAX_CODEWORDS elements ((N1/m) * (Nc/d)), else
  *            GPD_E_WORKSPACE and nothing is touched; at most GPD_STATIC_LOCATED_CAP located entries
  *            are listed (n_located still counts all of them).

@@ -23,7 +23,7 @@ GPD_SUB_AUTO, GPD_SUB_U_VN, GPD_SUB_V_UM = 0, 1, 2
 GPD_DEC_FIRST_K, GPD_DEC_LSQ_ALL = 0, 1
 GPD_STEP_FORWARD, GPD_STEP_BACKWARD_UPDATE = 0, 1
 GPD_STEP_FUSE_SIGMOID = 0x100
-GPD_CORRECT_NONE, GPD_CORRECT_ELEMENTS, GPD_CORRECT_NODES = 0, 1, 2
+GPD_CORRECT_NONE, GPD_CORRECT_ELEMENTS, GPD_CORRECT_NODES, GPD_CORRECT_ELEMENTS_L1 = 0, 1, 2, 3
 GPD_STACK_WEIGHTS, GPD_STACK_FORWARD, GPD_STACK_BACKWARD = 0, 1, 2
 GPD_LAYOUT_PACKED, GPD_LAYOUT_SPREAD = 0, 1
 

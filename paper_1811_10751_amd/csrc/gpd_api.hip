@@ -455,7 +455,7 @@ gpd_status_t run_decode(hipStream_t stream, TableRing* ring, const DecodeJob& jo
   if (correct == GPD_CORRECT_NODES)
     return run_decode_nodes(stream, ring, job, Zt, present, mode, out, ld_out, workspace,
                             workspace_bytes, report);
-  if (correct != GPD_CORRECT_NONE && correct != GPD_CORRECT_ELEMENTS)
+  if (correct != GPD_CORRECT_NONE && correct != GPD_CORRECT_ELEMENTS && correct != GPD_CORRECT_ELEMENTS_L1)
     return fail(GPD_E_INVALID, "decode: unknown correct_errors %d", correct);
   const bool corr = correct != 0;
   if (corr) {
@@ -533,6 +533,7 @@ gpd_status_t run_decode(hipStream_t stream, TableRing* ring, const DecodeJob& jo
     la.rows = job.bh; la.cols = job.bw; la.rho = job.rho; la.abs_floor = job.abs_floor;
     la.counters = counters; la.flag_bits = flag_bits;
     la.located = located; la.located_cap = job.loc_cap; la.node_err = node_err;
+    la.locator = correct == GPD_CORRECT_ELEMENTS_L1 ? 1 : 0;
     st = launch_locate(stream, la);
     if (st != GPD_OK) return st;
   }
@@ -689,9 +690,10 @@ extern "C" gpd_status_t gpd_decode_static(const gpd_plan_t* plc, const float* Ct
                                           gpd_report_t* report) {
   gpd_plan_t* pl = const_cast<gpd_plan_t*>(plc);
   if (!pl) return fail(GPD_E_INVALID, "gpd_decode_static: null plan");
-  if (correct_errors != GPD_CORRECT_NONE && correct_errors != GPD_CORRECT_ELEMENTS)
-    return fail(GPD_E_UNSUPPORTED, "gpd_decode_static: correct_errors must be GPD_CORRECT_NONE or "
-                                   "GPD_CORRECT_ELEMENTS (the node search needs a caller's workspace)");
+  if (correct_errors != GPD_CORRECT_NONE && correct_errors != GPD_CORRECT_ELEMENTS &&
+      correct_errors != GPD_CORRECT_ELEMENTS_L1)
+    return fail(GPD_E_UNSUPPORTED, "gpd_decode_static: correct_errors must be GPD_CORRECT_NONE, GPD_CORRECT_ELEMENTS "
+                                   "or GPD_CORRECT_ELEMENTS_L1 (the node search needs a caller's workspace)");
   const int64_t ncw = pl->ahC * pl->awC;
   if (ncw > kStaticMaxCodewords)
     return fail(GPD_E_WORKSPACE, "gpd_decode_static: blocks of %lld elements exceed the limit of %lld",

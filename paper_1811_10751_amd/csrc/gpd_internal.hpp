@@ -266,6 +266,7 @@ struct LocateArgs {
   const unsigned long long* flag_bits = nullptr;   // the screen's bit map (see ScreenArgs)
   gpd_located_t* located = nullptr; int64_t located_cap = 0;
   int32_t* node_err = nullptr;    // [GPD_MAX_P]
+  int locator = 0;                // 0: Algorithm 1's search (helped by the algebraic locator); 1: L1 relaxation
 };
 gpd_status_t launch_locate(hipStream_t stream, const LocateArgs& a);
 

@@ -988,7 +988,7 @@ extern "C" gpd_status_t gpd_coded_layer_step(gpd_layer_t* L, int32_t phase, floa
     return fail(GPD_E_INVALID, "unknown phase %d", phase);
   // a decode with element-wise correction patches single outputs after the pass: the step then
   // follows as a launch of its own
-  const bool act_in_decode = fuse_act && correct_errors != GPD_CORRECT_ELEMENTS;
+  const bool act_in_decode = fuse_act && correct_errors != GPD_CORRECT_ELEMENTS && correct_errors != GPD_CORRECT_ELEMENTS_L1;
   auto act_after = [&](gpd_status_t dst, float* o, int64_t n) -> gpd_status_t {
     if (!fuse_act || act_in_decode || !o || n == 0 || (dst != GPD_OK && dst != GPD_E_DECODE_FAIL)) return dst;
     const std::string why = dst == GPD_OK ? std::string() : std::string(gpd_last_error());

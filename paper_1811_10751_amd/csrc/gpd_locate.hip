@@ -58,6 +58,7 @@ struct LocateParams {
   int share, chunks_per_team; // workgroups of a team, chunks of the map a team takes
   gpd_located_t* located; int64_t located_cap;
   int32_t* node_err;
+  int locator;                // 0: search helped by the algebraic locator; 1: L1 relaxation
 };
 
 __device__ __forceinline__ double wave_sum(double v) {
@@ -193,6 +194,9 @@ __device__ __forceinline__ bool may_explain_with(const SharedColumns& f, const d
   return (yy - f.expl - lim2) * d <= cj * cj;              // yy - (expl + cj^2 / d) <= lim2, d > 0
 }
 
+// LOCATOR 0: Algorithm 1's search, helped by the algebraic locator; 1: the L1 relaxation in its place
+// (two kernels: the search keeps the registers and the code it had before the relaxation existed).
+template <int LOCATOR>
 __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
   __shared__ double zs[64];
   __shared__ double ys[R_MAX];
@@ -211,6 +215,7 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
   __shared__ int node_s[64];                               // worker node of each present response
   __shared__ gpd_located_t rec_s[64];                      // located entries not yet handed over
   __shared__ unsigned long long words_s[kKeptChunks][64];  // the team's first chunks of the screen's map
+  __shared__ double l1_w[64], l1_wz[64], l1_sn[64], l1_q[64], l1_a[64];   // L1 relaxation: per-node values
 
   const int lane = threadIdx.x;
   const int ns = p.t.nin, r = p.t.r, nout = p.t.nout;
@@ -404,7 +409,7 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
     bool found = false;
     int best_size = 0;
     int size = nforced > 1 ? nforced : 1;
-    for (int phase = 0; phase < 3 && !found; ++phase) {
+    for (int phase = 0; phase < (LOCATOR == 0 ? 3 : 0) && !found; ++phase) {
       if (phase == 1) {
         // ---- algebraic locator (see the head of this file); rr syndromes, t <= rr / 2
         const int rr = r - nforced;
@@ -626,6 +631,159 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
       }
     }
 
+    if constexpr (LOCATOR == 1) if (nforced <= max_size && nforced <= A_MAX) {
+      // ---- L1 relaxation (remark after Thm 3) in place of the search.  e* = argmin ||e||_1 subject
+      // to H e = H z, the non-finite entries free of cost, is z minus the least-absolute-deviations
+      // fit of a codeword to the finite entries: min over polynomials q with Kc coefficients of
+      // sum_i |z_i - q(x_i)|.  A vertex of that linear program interpolates Kc of the nodes (the
+      // basis); the simplex steps below exchange one basis node at a time.  With the Lagrange
+      // polynomials l_j of the basis and the costs c_i of the nodes (1 up to a tie-breaking 1e-6, see
+      // below), releasing basis node j changes the objective at the rate c_j - |u_j|, u_j = sum_{i not
+      // in basis} c_i sign(res_i) l_j(x_i): the basis is optimal when every |u_j| <= c_j (these u are
+      // the dual variables, |H^T lambda| <= c).  Otherwise the node with the
+      // largest |u_j| leaves, the fit moves along that edge until the slope of the (piecewise
+      // linear, convex) objective turns non-negative, and the node whose residual vanishes there
+      // enters.  l_j(x_i) = w_j N_i / (x_i - x_j) with N_i = prod_k (x_i - x_k) over the basis and
+      // w_j the barycentric weights: recomputed from the points in every step, so nothing is
+      // carried along that rounding could degrade.  The solution only ranks the nodes (largest
+      // |e*| first, ties: the lowest node): the forced nodes plus the first nodes of the ranking
+      // are tested by Algorithm 1's criterion, smallest candidate first.
+      const bool isfree = lane < ns && !((forced_mask >> lane) & 1ull);
+      const double x = lane < ns ? p.t.pts64[lane] : 0.0;
+      xs[lane] = x;
+      const int Kc = ns - r;
+      // cost of an error at this node: 1 + 1e-6 frac((s + 1)^2 phi), s the node's place among the
+      // present ones.  With equal costs the program often has several optimal vertices (the
+      // Chebyshev points are symmetric: two vertices can differ by a codeword whose few non-zero
+      // values cancel in the sum of magnitudes), and which one a solver returns is its own affair;
+      // costs that differ a little, in no regular pattern, leave one.
+      const double sq = (double)((lane + 1) * (lane + 1)) * 0.6180339887498949;
+      const double cost = 1.0 + 1e-6 * (sq - floor(sq));
+      __syncthreads();
+      if (nforced > 0) {
+        // the non-finite entries alone
+        for (int j = 0; j < nforced; ++j) lsq_q[j][lane] = lane < r ? Hs[lane * ns + forcedlist[j]] : 0.0;
+        if (lane < nforced) supp_s[lane] = forcedlist[lane];
+        __syncthreads();
+        const double res = wave_lsq(lsq_q, lsq_r, lsq_c, nforced, lane < r ? ys[lane] : 0.0, lane, rwidth);
+        if (res <= tau) { found = true; best_size = nforced; }
+      }
+      if (!found) {
+        // initial basis: Kc of the nfree (> Kc) finite nodes, evenly spread over them
+        unsigned long long bmask = 0ull;
+        for (int k = 0; k < Kc; ++k) bmask |= 1ull << freelist[((2 * k + 1) * nfree) / (2 * Kc)];
+        const double kInf = 1.0e300;
+        double resid = 0.0;
+        const int maxit = 8 * nfree;                       // (a vertex is reached long before: see the tests)
+        for (int it = 0;; ++it) {
+          const bool inB = (bmask >> lane) & 1ull;
+          double w = 0.0;
+          if (inB) {
+            double d = 1.0;
+            for (unsigned long long m = bmask & ~(1ull << lane); m; m &= m - 1ull) d *= x - xs[__ffsll((long long)m) - 1];
+            w = 1.0 / d;
+          }
+          l1_w[lane] = w;
+          l1_wz[lane] = w * zs[lane];
+          __syncthreads();
+          const bool nb = isfree && !inB;
+          double Np = 0.0, rs = 0.0;
+          if (nb) {
+            double d = 1.0, acc = 0.0;
+            for (unsigned long long m = bmask; m; m &= m - 1ull) {
+              const int k = __ffsll((long long)m) - 1;
+              const double dx = x - xs[k];
+              d *= dx;
+              acc += l1_wz[k] / dx;
+            }
+            Np = d;
+            rs = zs[lane] - d * acc;                       // residual of the fit at this node
+          }
+          l1_sn[lane] = nb ? (rs > 0.0 ? cost * Np : (rs < 0.0 ? -cost * Np : 0.0)) : 0.0;
+          __syncthreads();
+          double u = 0.0;
+          if (inB) {
+            double acc = 0.0;
+            for (int i = 0; i < ns; ++i) {
+              const double sv = l1_sn[i];
+              if (sv != 0.0) acc += sv / (xs[i] - x);
+            }
+            u = w * acc;
+          }
+          double mv = inB ? fabs(u) - cost : -1.0e300;     // rate of descent on releasing this basis node
+          int mi = lane;
+#pragma unroll
+          for (int off = 32; off > 0; off >>= 1) {
+            const double ov = __shfl_xor(mv, off);
+            const int oi = __shfl_xor(mi, off);
+            if (ov > mv || (ov == mv && oi < mi)) { mv = ov; mi = oi; }
+          }
+          resid = rs;
+          if (!(mv > 1e-10) || it >= maxit) break;         // optimal, or the cap (wave-uniform)
+          const int js = mi;
+          const double sg = __shfl(u, js) > 0.0 ? 1.0 : -1.0;
+          const double wst = l1_w[js], xst = xs[js];
+          double q = kInf, a = 0.0;
+          if (nb) {
+            const double T = wst * Np / (x - xst);        // l_js at this node
+            const double st = sg * T;
+            if (rs * st > 0.0) { q = rs / st; a = cost * fabs(T); }
+          }
+          l1_q[lane] = q;
+          l1_a[lane] = a;
+          __syncthreads();
+          // slope of the objective just after this node's breakpoint: cost_js - |u_js| + 2 sum of
+          // cost |l_js| over the breakpoints up to it
+          double c = 0.0;
+          if (q < kInf)
+            for (int k = 0; k < ns; ++k) {
+              const double qk = l1_q[k];
+              if (qk < q || (qk == q && k <= lane)) c += l1_a[k];
+            }
+          double bv = (q < kInf && 2.0 * c - mv >= 0.0) ? q : kInf;
+          int bi = lane;
+#pragma unroll
+          for (int off = 32; off > 0; off >>= 1) {
+            const double ov = __shfl_xor(bv, off);
+            const int oi = __shfl_xor(bi, off);
+            if (ov < bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+          }
+          if (!(bv < kInf)) break;                         // (no breakpoint ahead: keep this vertex)
+          bmask = (bmask & ~(1ull << js)) | (1ull << bi);
+          __syncthreads();
+        }
+        const double mag = isfree ? (((bmask >> lane) & 1ull) ? 0.0 : fabs(resid)) : -1.0;
+        unsigned long long cand = 0ull;
+        int npicked = 0;
+        for (size = nforced > 1 ? nforced : 1; size <= max_size && size <= A_MAX && !found; ++size) {
+          while (npicked < size - nforced) {
+            double pv = ((cand >> lane) & 1ull) ? -1.0 : mag;
+            int pi = lane;
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) {
+              const double ov = __shfl_xor(pv, off);
+              const int oi = __shfl_xor(pi, off);
+              if (ov > pv || (ov == pv && oi < pi)) { pv = ov; pi = oi; }
+            }
+            cand |= 1ull << pi;
+            ++npicked;
+          }
+          const unsigned long long all = cand | forced_mask;
+          __syncthreads();
+          if (lane == 0) {
+            int n = 0;
+            for (int q = 0; q < ns; ++q)
+              if ((all >> q) & 1ull) supp_s[n++] = q;
+          }
+          __syncthreads();
+          for (int j = 0; j < size; ++j) lsq_q[j][lane] = lane < r ? Hs[lane * ns + supp_s[j]] : 0.0;
+          __syncthreads();
+          const double res = wave_lsq(lsq_q, lsq_r, lsq_c, size, lane < r ? ys[lane] : 0.0, lane, rwidth);
+          if (res <= tau) { found = true; best_size = size; }
+        }
+      }
+    }
+
     if (!found) {
       ++n_fail_local;
       __syncthreads();
@@ -710,6 +868,9 @@ gpd_status_t launch_locate(hipStream_t stream, const LocateArgs& a) {
   p.cols = a.cols; p.rho = a.rho; p.abs_floor = a.abs_floor;
   p.counters = a.counters; p.flag_bits = a.flag_bits;
   p.located = a.located; p.located_cap = a.located_cap; p.node_err = a.node_err;
+  p.locator = a.locator;
+  if (a.locator != 0 && a.locator != 1) return fail(GPD_E_INVALID, "locate: unknown locator %d", a.locator);
+  if (a.locator == 1 && !a.t.pts64) return fail(GPD_E_INVALID, "locate: the L1 relaxation needs the evaluation points");
   p.n_codewords = a.rows * a.cols;
   if (p.n_codewords <= 0) return GPD_OK;
   p.n_words = (p.n_codewords + 63) / 64;
@@ -726,11 +887,14 @@ gpd_status_t launch_locate(hipStream_t stream, const LocateArgs& a) {
   // (static + dynamic LDS can pass 64 KB for codes of 64 nodes: the limit is raised once)
   static bool raised = false;
   if (!raised) {
-    GPD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(locate_kernel),
+    GPD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(locate_kernel<0>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 3 * R_MAX * 64 * (int)sizeof(double)));
+    GPD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(locate_kernel<1>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 3 * R_MAX * 64 * (int)sizeof(double)));
     raised = true;
   }
-  GPD_LAUNCH(locate_kernel, dim3(blocks), dim3(64), lds, stream, p);
+  if (a.locator == 1) GPD_LAUNCH(locate_kernel<1>, dim3(blocks), dim3(64), lds, stream, p);
+  else GPD_LAUNCH(locate_kernel<0>, dim3(blocks), dim3(64), lds, stream, p);
   GPD_HIP(hipGetLastError());
   return GPD_OK;
 }
