@@ -54,7 +54,24 @@ def build(verbose: bool = True) -> str:
         raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
     if verbose:
         print(f"built {LIB}")
+    build_probe(verbose)
     return LIB
+
+
+PROBE_SRC = os.path.join(CSRC, "probes", "overlap_probe.hip")
+PROBE = os.path.join(HERE, "overlap_probe")
+
+
+def build_probe(verbose: bool = True) -> str:
+    """The stand-alone measurement program csrc/probes/overlap_probe.hip (no part of the library)."""
+    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", PROBE_SRC, "-o", PROBE]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed on {PROBE_SRC}:\n{r.stdout}\n{r.stderr}")
+    if verbose:
+        print(f"built {PROBE}")
+    return PROBE
 
 
 if __name__ == "__main__":

@@ -986,9 +986,157 @@ __global__ __launch_bounds__(256, 3) void gemm_planes_kernel(HGemmParams g) {
 }
 
 
+// ------------------------------------------------ rank-B update from fp16 planes, B panel resident
+//
+// The same update C_p = beta C_p + alpha A_p B_p^T from two fp16 planes per operand as
+// gemm_planes_kernel<.., FMT 1>, organised around what that kernel's counters showed: per 128 x 128
+// tile its matrix instructions, its traffic through the vector memory path (operands to LDS, the
+// output tile) and its LDS traffic (operands written and read) each take about 6100 cycles of
+// their unit, and they added up instead of overlapping.  Here a workgroup owns 128 columns of one
+// batch entry for the whole height of C: the B panel of those columns (K <= 256: 128 KB, both
+// planes) is copied to LDS once and only read from then on, a wavefront owns a strip of 32 rows x 128
+// columns and takes its A fragments straight from memory (in the k-blocked plane layout the
+// 32 x 16 fragment of a plane is one contiguous KB, already in the lane order the matrix
+// instruction wants), so the loop over k has no LDS write and no barrier, every wavefront runs on
+// its own, and per 128 x 128 of output the vector memory path carries a third less and the LDS
+// half as much.  Products are accumulated in the order hi*lo, lo*hi, hi*hi per 16 k, as there.
+template <int NW, int R>
+__global__ __launch_bounds__(64 * NW, 1) void planes_sweep_kernel(HGemmParams g) {
+  constexpr int NJ = 4;
+  extern __shared__ __attribute__((aligned(16))) unsigned char bpan[];   // [K / 16][plane][128 columns x 32 B]
+  const int xcd = blockIdx.x & 7;
+  const int slot = blockIdx.x >> 3;
+  const int sweep = xcd * g.tiles_per_xcd + slot;
+  if (sweep >= g.total_tiles) return;
+  const int p = sweep / g.tiles_n;
+  const int n0 = (sweep - p * g.tiles_n) * 128;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 31, lg = lane >> 5;
+  const int nchunks = g.K >> 4;              // a multiple of R (the host checks)
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+  {
+    // stage c, plane pl of the panel is one run of 4 KB in memory (128 columns x 16 k); the halves of
+    // its 32-byte rows are swapped in every second group of four rows, which keeps the 128-bit
+    // fragment reads of 8 consecutive lanes on 32 different banks
+    const char* Bb = (const char*)g.B + ((int64_t)p * g.sB + (int64_t)n0 * 16) * 2;
+    const int n_items = nchunks * 2 * 256;   // 16-byte pieces
+    for (int base = 0; base < n_items; base += 64 * NW * 4) {
+      u32x4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int idx = base + u * 64 * NW + tid;
+        const int item = idx >> 8, q = idx & 255;
+        v[u] = u32x4{0u, 0u, 0u, 0u};
+        if (idx < n_items)
+          v[u] = *reinterpret_cast<const u32x4*>(Bb + (int64_t)(item >> 1) * g.N * 32 + (int64_t)(item & 1) * g.planeB * 2 + q * 16);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int idx = base + u * 64 * NW + tid;
+        const int item = idx >> 8, q = idx & 255;
+        if (idx < n_items)
+          *reinterpret_cast<u32x4*>(bpan + item * 4096 + (q >> 1) * 32 + (((q & 1) ^ ((q >> 3) & 1)) * 16)) = v[u];
+      }
+    }
+  }
+  __syncthreads();
+
+  union Frag { u32x4 u; f16x8 h; };
+  const uint32_t rdB = (uint32_t)li * 32u + ((uint32_t)lg ^ ((li >> 2) & 1)) * 16u;
+  auto fragB = [&](int c, int pl, int j) __attribute__((always_inline)) {
+    Frag f;
+    f.u = *reinterpret_cast<const u32x4*>(bpan + (c * 2 + pl) * 4096 + j * 1024 + rdB);
+    return f;
+  };
+  const char* Ab = (const char*)g.A + (int64_t)p * g.sA * 2;
+  const int64_t extA = 2 * g.planeA + (int64_t)nchunks * g.M * 32;
+  const __amdgpu_buffer_rsrc_t rA = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(Ab), 0, (int)extA, 0x00020000);
+  const uint32_t kbA = (uint32_t)g.M * 32u, plA = (uint32_t)(g.planeA * 2);
+  float* __restrict__ Cn = g.C + (int64_t)p * g.sC + n0 + li;
+  const int esum = g.exps[0] + g.exps[1];
+
+  for (int s = wave; s < (g.M >> 5); s += NW) {
+    const int r0 = s * 32;
+    const uint32_t voff = (uint32_t)(r0 + li) * 32u + (uint32_t)lg * 16u;
+    Frag fa[R][2];
+    auto loadA = [&](int u, int c) __attribute__((always_inline)) {
+#pragma unroll
+      for (int pl = 0; pl < 2; ++pl) fa[u][pl].u = __builtin_amdgcn_raw_buffer_load_b128(rA, voff, (uint32_t)c * kbA + pl * plA, 0);
+    };
+#pragma unroll
+    for (int u = 0; u < R; ++u) loadA(u, u);
+    floatx16 acc[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+    auto stage = [&](int u, int c, bool more) __attribute__((always_inline)) {
+      Frag fb[NJ];
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) fb[j] = fragB(c, 1, j);
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[u][0].h, fb[j].h, acc[j], 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) fb[j] = fragB(c, 0, j);
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[u][1].h, fb[j].h, acc[j], 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[u][0].h, fb[j].h, acc[j], 0, 0, 0);
+      if (more) loadA(u, c + R);
+    };
+    int c0 = 0;
+    for (; c0 + 2 * R <= nchunks; c0 += R) {
+#pragma unroll
+      for (int u = 0; u < R; ++u) stage(u, c0 + u, true);
+    }
+#pragma unroll
+    for (int u = 0; u < R; ++u) stage(u, c0 + u, false);
+
+    // read-modify-write of the strip, two 32 x 32 blocks at a time, non-temporal (touched once)
+    float* Cs = Cn + (int64_t)(r0 + 4 * lg) * g.ldc;
+#pragma unroll
+    for (int j0 = 0; j0 < NJ; j0 += 2) {
+      float old[2][16];
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          old[jj][v] = g.beta != 0.f ? __builtin_nontemporal_load(Cs + (int64_t)(8 * (v >> 2) + (v & 3)) * g.ldc + 32 * (j0 + jj)) : 0.f;
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          __builtin_nontemporal_store(fmaf(g.beta, old[jj][v], ldexpf(g.alpha * acc[j0 + jj][v], esum)),
+                                      Cs + (int64_t)(8 * (v >> 2) + (v & 3)) * g.ldc + 32 * (j0 + jj));
+    }
+  }
+}
+
+
 gpd_status_t launch_planes(hipStream_t stream, HGemmParams p, int64_t batch) {
   p.tiles_m = (p.M + 127) / 128;
   p.tiles_n = (p.N + 127) / 128;
+  // fp16 planes, whole strips and a B panel that fits the LDS: the kernel with the resident panel
+  // (measured on the 8192 x 8192 and 8192 x 4096 layers at batch 256: 450 us per launch on average
+  // against 488 us; 8 wavefronts with four A stages in flight were as fast as 12 or 16 wavefronts
+  // or deeper staging)
+  if (p.exps && p.M % 32 == 0 && p.M >= 256 && p.N % 128 == 0 && p.K % 64 == 0 && p.K <= 256) {
+    const int64_t sweeps = (int64_t)p.tiles_n * batch;
+    if (sweeps > 0x0fffffff) return fail(GPD_E_SHAPE, "gemm: too many tiles");
+    p.total_tiles = (int)sweeps;
+    p.tiles_per_xcd = (int)((sweeps + 7) / 8);
+    const size_t lds = (size_t)(p.K >> 4) * 2 * 4096;      // at most 128 KB
+    static bool raised = false;
+    if (!raised) {
+      GPD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(planes_sweep_kernel<8, 4>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 131072));
+      raised = true;
+    }
+    GPD_LAUNCH((planes_sweep_kernel<8, 4>), dim3((unsigned)(p.tiles_per_xcd * 8)), dim3(512), lds, stream, p);
+    GPD_HIP(hipGetLastError());
+    return GPD_OK;
+  }
   const int64_t total = (int64_t)p.tiles_m * p.tiles_n * batch;
   if (total > 0x0fffffff) return fail(GPD_E_SHAPE, "gemm: too many tiles");
   p.total_tiles = (int)total;
