@@ -127,7 +127,10 @@ def bench_mlp(args, cfg):
     ms = (t1 - t0) * 1e3 / args.steps
     flops = sum(6.0 * sizes[l + 1] * sizes[l] * batch for l in range(len(sizes) - 1))
     wbytes = sum(4.0 * P * L.wt_rows * L.wt_cols for L in mlp.layers)
-    alg_bytes = 3.0 * wbytes          # forward reads W~ once; backward+update reads and rewrites it
+    # forward reads W~ once, backward product + update read and rewrite it in one pass; on the
+    # matrix-core path (batch > 8) the backward product of every layer but the first is a pass of its own
+    alg_bytes = sum(4.0 * P * L.wt_rows * L.wt_cols * (3.0 + (1.0 if (batch > 8 and i > 0) else 0.0))
+                    for i, L in enumerate(mlp.layers))
     out = {"metric": "coded MLP training step (forward + backward + coded update, all layers)",
            "value": flops / (ms * 1e-3) / 1e12, "unit": "TFLOP/s (useful, uncoded flops)", "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
@@ -138,7 +141,11 @@ def bench_mlp(args, cfg):
                                  "accumulation: error below 2^-20 of a product" if cfg["worker"] == "bf16"
                                  else "fp32 (batch <= 8: vector units; else fp32 matrix cores)"),
            "weight_stream_GBps": alg_bytes / (ms * 1e-3) / 1e9,
-           "weight_stream_bytes_per_step": alg_bytes}
+           "weight_stream_bytes_per_step": alg_bytes,
+           # whole iteration against the HBM roofline (bytes of coded weights moved, see alg_bytes)
+           "roofline": {"kernel": "whole iteration (weight-streaming kernels and the small launches between them)",
+                        "bound": "hbm", "achieved": alg_bytes / (ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                        "unit": "GB/s", "frac": alg_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None}}
     print(json.dumps(out), flush=True)
 
 

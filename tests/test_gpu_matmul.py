@@ -216,3 +216,49 @@ def test_spread_layout_gives_the_packed_results(N1, N0, Nc, m, n, d, P, dtype):
     v_s = G.gpd_verify_decode(spread, Ct_s, C_s, present=present, mode=G.GPD_DEC_LSQ_ALL, bad=nr_s.bad)
     assert (v_s.status, v_s.n_value_mismatch, v_s.bad) == (v_p.status, v_p.n_value_mismatch, v_p.bad)
     assert _pads_untouched(spread, "C", baseC)
+
+
+def test_per_launch_timing():
+    # gpd_timing_tag: every kernel the library launches while a tag is set carries its own pair of
+    # events; the sums per tag must count the launches of each stage and agree with what events
+    # around the (otherwise idle) stream measure
+    N1, N0, Nc, m, n, d, P = 1024, 1024, 1024, 2, 2, 2, 12
+    A, B = WL.matmul_inputs(N1, N0, Nc, seed=3)
+    plan = G.gpd_plan(N1, N0, Nc, m, n, d, P)
+    Ad, Bd = to_dev(A), to_dev(B)
+    At, Bt = G.gpd_encode(plan, Ad, Bd)
+    Ct = G.gpd_worker_products(plan, At, Bt)
+    C, _ = G.gpd_decode(plan, Ct, mode=G.GPD_DEC_LSQ_ALL, want_report=False)
+    torch.cuda.synchronize()
+    ref = to_np(C).copy()
+    G.gpd_timing_reset()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 5
+    e0.record()
+    for _ in range(reps):
+        G.gpd_timing_tag(1)
+        G.gpd_encode(plan, Ad, Bd, At, Bt)
+        G.gpd_timing_tag(2)
+        G.gpd_worker_products(plan, At, Bt, Ct)
+        G.gpd_timing_tag(3)
+        G.gpd_decode(plan, Ct, mode=G.GPD_DEC_LSQ_ALL, C_out=C, want_report=False)
+        G.gpd_timing_tag(-1)
+    e1.record()
+    e1.synchronize()
+    wall = e0.elapsed_time(e1)
+    t_enc, n_enc = G.gpd_timing_collect(1)
+    t_mul, n_mul = G.gpd_timing_collect(2)
+    t_dec, n_dec = G.gpd_timing_collect(3)
+    say("  encode %.3f ms / %d launches, products %.3f / %d, decode %.3f / %d, stream %.3f ms"
+        % (t_enc, n_enc, t_mul, n_mul, t_dec, n_dec, wall))
+    assert (n_enc, n_mul, n_dec) == (2 * reps, reps, reps)
+    assert min(t_enc, t_mul, t_dec) > 0.0
+    assert t_enc + t_mul + t_dec <= wall * 1.02 and t_enc + t_mul + t_dec >= 0.3 * wall
+    assert G.gpd_timing_collect(7) == (0.0, 0)
+    assert np.array_equal(to_np(C), ref)                   # timing changes no result
+    G.gpd_timing_reset()
+    assert G.gpd_timing_collect(1) == (0.0, 0)
+    # untagged launches are not recorded
+    G.gpd_encode(plan, Ad, Bd, At, Bt)
+    torch.cuda.synchronize()
+    assert G.gpd_timing_collect(1) == (0.0, 0)
