@@ -56,6 +56,7 @@ gpd_status_t TableRing::cached(const std::string& key,
   char* h = host + (size_t)sl * slot_bytes;
   char* d = arena + arena_used;
   *out = ht.pack(h, d);
+  out->persistent = true;
   GPD_HIP(hipMemcpyAsync(d, h, need, hipMemcpyHostToDevice, up));
   GPD_HIP(hipEventRecord(ev[sl], up));
   GPD_HIP(hipStreamWaitEvent(stream, ev[sl], 0));

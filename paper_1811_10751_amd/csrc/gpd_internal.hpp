@@ -123,6 +123,9 @@ struct CombineTable {
   // read through the scalar cache, whatever the kernel stores meanwhile): the block offsets
   // (nin, nout <= 64) and, when they fit (nout * nin <= 256 and r * nin <= 256), coef and H.
   bool k_offsets = false, k_coefs = false;
+  // the device pointers stay valid for the life of the ring (a table in its arena); false: a
+  // staging slot that a later upload of the same ring overwrites, good for the next launches only
+  bool persistent = false;
   int64_t k_in_off[64] = {}, k_out_off[64] = {};
   float k_coef[256] = {}, k_H[256] = {};
 };

@@ -1301,6 +1301,11 @@ extern "C" gpd_status_t gpd_mlp_step(gpd_layer_t* const* layers, int32_t n_layer
     if (tab[l].decF.nin != d.P || tab[l].decB.nin != d.P || tab[l].X.nin != c.n || tab[l].Xh.nin != c.n ||
         tab[l].D.nin != c.m || tab[l].Dh.nin != c.m)
       return fail(GPD_E_UNSUPPORTED, "gpd_mlp_step: unexpected table shape for layer %d", l);
+    // all tables of the iteration are fetched before the first launch: each must be one that stays
+    // where it is (the layer's table arena can be full after thousands of distinct erasure patterns)
+    if (!(tab[l].decF.persistent && tab[l].decB.persistent && tab[l].X.persistent && tab[l].Xh.persistent &&
+          tab[l].D.persistent && tab[l].Dh.persistent))
+      return fail(GPD_E_UNSUPPORTED, "gpd_mlp_step: the table arena of layer %d is full", l);
   }
   auto ws = [&](int l, size_t off) { return (float*)((char*)workspaces[l] + off); };
 
