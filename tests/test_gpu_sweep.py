@@ -65,17 +65,19 @@ def test_random_shapes(seed):
             TS.test_split_layer_step(*a)
 
 
-@pytest.mark.parametrize("seed", [21, 22])
-def test_random_soft_errors(seed):
+@pytest.mark.parametrize("seed,locator", [(21, "search"), (22, "search"), (23, "l1"), (24, "l1")])
+def test_random_soft_errors(seed, locator):
     """Random codes (K <= 12, P - K from 2 to 8), random erasures, and in up to a quarter of the
     codewords between 0 and one more error than Algorithm 1 can correct: offsets, huge values,
-    non-finite values and single bit flips.  The GPU must take the oracle's decisions exactly."""
+    non-finite values and single bit flips.  The GPU must take the oracle's decisions exactly, with
+    Algorithm 1's search and with the L1 relaxation in its place."""
     import test_gpu_errors as TE
     import paper_1811_10751_amd as G
     from gpu_util import to_dev, to_np
     rng = np.random.default_rng(seed)
     done = 0
-    while done < 30:
+    mode = G.GPD_CORRECT_ELEMENTS_L1 if locator == "l1" else G.GPD_CORRECT_ELEMENTS
+    while done < (16 if locator == "l1" else 30):
         m, n, d = (int(rng.integers(1, 4)) for _ in range(3))
         K = m * n * d + n - 1
         if K > 12:
@@ -111,8 +113,8 @@ def test_random_soft_errors(seed):
                     Ct_h[p, i, j] = w.view(np.float32)[0]
         say("soft-error sweep", seed, (N1, N0, Nc, m, n, d, P), "erasures", n_er, "codewords hit", nbad)
         opl = O.make_plan(m, n, d, P)
-        C_o, orep = O.decode(Ct_h, opl, present, correct=True)
-        C, rep = G.gpd_decode(plan, to_dev(Ct_h), present=present, mode=G.GPD_DEC_LSQ_ALL, correct_errors=True,
+        C_o, orep = O.decode(Ct_h, opl, present, correct=True, locator=locator)
+        C, rep = G.gpd_decode(plan, to_dev(Ct_h), present=present, mode=G.GPD_DEC_LSQ_ALL, correct_errors=mode,
                               located_cap=100000)
         TE.compare_reports(rep, orep, P)
         TE.check_outputs(C, C_o, orep, plan, tol=max(2e-5, 1e-6 * O.amplification(opl, present, "lsq_all")))
