@@ -134,3 +134,42 @@ def test_l1_locator_full_size_bit_flips():
     say("L1, full size: 150 trials,", n_flips, "flips,", n_loc, "located,", n_fail, "codewords given up")
     assert torch.equal(Cf, Ct)
     assert n_loc > 30
+
+
+def test_layer_forward_with_l1_correction_and_static_decode():
+    # the same locator behind the two other entry points that take a correction mode: the coded
+    # layer step (stragglers + one node whose stored W~_p was corrupted: one error in every
+    # codeword) and the decode that allocates nothing
+    N_out, N_in, P = 64, 96, 24
+    rng = np.random.default_rng(3)
+    W = (rng.standard_normal((N_out, N_in)) / 8).astype(np.float32)
+    X = rng.uniform(-1, 1, (N_in, 1)).astype(np.float32)
+    olp = O.make_layer_plan(N_out, N_in, 1, 4, 2, 1, 1, P, "auto")
+    L = G.gpd_layer_create(N_out, N_in, 1, 4, 2, 1, 1, P)
+    Wt = G.gpd_layer_encode_weights(L, to_dev(W))
+    noise = np.random.default_rng(11).standard_normal(tuple(Wt[7].shape)).astype(np.float32)
+    Wt[7] += 0.05 * to_dev(noise)
+    present = np.ones(P, dtype=np.uint8)
+    present[[1, 20]] = 0
+    S, rep = G.gpd_coded_layer_step(L, G.GPD_STEP_FORWARD, Wt, to_dev(X), present=present,
+                                    correct_errors=G.GPD_CORRECT_ELEMENTS_L1, want_report=True)
+    St_o = O.worker_products(to_np(Wt), O.layer_encode_x(X, olp))
+    S_o, orep = O.decode(St_o, olp.fwd, present, "lsq_all", True, locator="l1")
+    say("  layer: flagged %d located %d failed %d (oracle %d %d)"
+        % (rep.n_flagged, rep.n_located, rep.n_failed, len(orep.located), orep.n_failed))
+    assert rep.n_flagged == orep.n_flagged and rep.n_failed == orep.n_failed
+    assert [x[:3] for x in rep.located] == [x[:3] for x in orep.located]
+    assert rep.n_located > 0 and set(x[0] for x in rep.located) == {7}
+    assert orep.n_failed == 0                              # (node 7 is one the relaxation finds in every codeword)
+    assert rel_fro(to_np(S), S_o[:N_out]) < 1e-4
+
+    # gpd_decode_static in L1 mode against gpd_decode in L1 mode
+    m = n = d = 2
+    A, B, plan, Ct = gpu_responses(64, 32, 32, m, n, d, 16, seed=5)
+    bad_ct, planted = plant(Ct, np.random.default_rng(6), [(1, 2), (7, 3), (30, 15)], [1, 2, 1], 0.0, 1.0)
+    C1, rep1 = G.gpd_decode(plan, bad_ct, mode=G.GPD_DEC_LSQ_ALL, correct_errors=G.GPD_CORRECT_ELEMENTS_L1)
+    C2 = torch.empty_like(C1)
+    _, rep2 = G.gpd_decode_static(plan, bad_ct, C2, mode=G.GPD_DEC_LSQ_ALL, correct_errors=G.GPD_CORRECT_ELEMENTS_L1)
+    assert rep1.n_flagged == rep2.n_flagged == 3 and rep1.n_failed == rep2.n_failed
+    assert [x[:3] for x in rep1.located] == [x[:3] for x in rep2.located]
+    assert torch.equal(C1, C2)
