@@ -519,6 +519,24 @@ def main():
                        "frac_between_stage_events": gbs(dec_bytes, dec_ms) / PEAK_HBM_GBS}},
     }
 
+    # The rate a plain device-to-device copy of 256 MiB reaches on this chip, as a second denominator
+    # for the two streaming stages (bytes read + bytes written over the time of one copy)
+    src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev).uniform_(-1, 1)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(10):
+        dst.copy_(src)
+    c1.record()
+    c1.synchronize()
+    copy_gbs = 2.0 * src.numel() * 4 / (c0.elapsed_time(c1) / 10 * 1e-3) / 1e9
+    del src, dst
+    out["roofline_hbm"]["plain_copy_GBps"] = copy_gbs
+    out["roofline_hbm"]["encode"]["frac_of_plain_copy"] = gbs(enc_bytes, enc_k_ms) / copy_gbs
+    out["roofline_hbm"]["decode"]["frac_of_plain_copy"] = gbs(dec_bytes, dec_k_ms) / copy_gbs
+
     # The same job with the worker products on the bf16 matrix cores, every fp32 operand written as
     # the sum of three bf16 values (six partial products: fp32-level accuracy).  Extra evidence
     # beside the headline, which stays on the fp32 matrix cores.
