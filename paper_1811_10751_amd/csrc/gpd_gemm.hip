@@ -163,14 +163,17 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? 3 : 1) void gemm
   TileRegs<TBN, NT> rb = load_tile<B_KC, MODE, TBN, NT>(B, g.ldb, n0, 0, g.N, g.K, tid);
   store_tile<A_KC, TBM, NT>(lds_a[0], tid, ra);
   store_tile<B_KC, TBN, NT>(lds_b[0], tid, rb);
+  // (the loads of a stage are requested at the end of the stage before the one that moves them to
+  // LDS, ahead of the barrier: behind the barrier nothing but the fragment reads stands between a
+  // wavefront and its first matrix instruction, and all wavefronts of a SIMD arrive there together)
+  if (nchunks > 1) {
+    ra = load_tile<A_KC, MODE, TBM, NT>(A, g.lda, m0, BK, g.M, g.K, tid);
+    rb = load_tile<B_KC, MODE, TBN, NT>(B, g.ldb, n0, BK, g.N, g.K, tid);
+  }
   __syncthreads();
 
   for (int c = 0; c < nchunks; ++c) {
     const int cur = c & 1;
-    if (c + 1 < nchunks) {
-      ra = load_tile<A_KC, MODE, TBM, NT>(A, g.lda, m0, (c + 1) * BK, g.M, g.K, tid);
-      rb = load_tile<B_KC, MODE, TBN, NT>(B, g.ldb, n0, (c + 1) * BK, g.N, g.K, tid);
-    }
     const float* __restrict__ as = lds_a[cur];
     const float* __restrict__ bs = lds_b[cur];
 #pragma unroll
@@ -191,6 +194,10 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4) ? 3 : 1) void gemm
     if (c + 1 < nchunks) {
       store_tile<A_KC, TBM, NT>(lds_a[cur ^ 1], tid, ra);
       store_tile<B_KC, TBN, NT>(lds_b[cur ^ 1], tid, rb);
+      if (c + 2 < nchunks) {
+        ra = load_tile<A_KC, MODE, TBM, NT>(A, g.lda, m0, (c + 2) * BK, g.M, g.K, tid);
+        rb = load_tile<B_KC, MODE, TBN, NT>(B, g.ldb, n0, (c + 2) * BK, g.N, g.K, tid);
+      }
     }
     __syncthreads();
   }
