@@ -12,6 +12,7 @@
 //   products only           192 v_mfma_f32_32x32x16_f16 per strip on register data
 //   both, one wavefront     old values requested, then the products, then the values written
 //   both, roles split       8 wavefronts of a workgroup only move data, 4 (one per SIMD) only multiply
+//   two kernels, two streams  the traffic-only and the products-only kernel launched side by side
 // Build:  hipcc --offload-arch=gfx950 -O3 -std=c++17 -Xclang -target-feature -Xclang -packed-fp32-ops
 //         overlap_probe.hip -o overlap_probe        (paper_1811_10751_amd/build.py does it)
 // Run:    ./overlap_probe          prints microseconds per launch (10 launches after 3 warm-ups)
@@ -177,6 +178,38 @@ int main(int argc, char** argv) {
   time("products only (412 GFLOP)", [&] { hipLaunchKernelGGL((one_wavefront_kernel<false, true>), grid, block, 0, 0, C, 0.5f); });
   time("both, in one wavefront", [&] { hipLaunchKernelGGL((one_wavefront_kernel<true, true>), grid, block, 0, 0, C, 0.5f); });
   time("both, roles split over wavefronts", [&] { hipLaunchKernelGGL(split_roles_kernel, grid, block, 0, 0, C, 0.5f); });
+  {
+    // the two kernels side by side on two streams (default priority): each launch of one is paired with
+    // a launch of the other; the time is that of both streams, from a common start
+    hipStream_t s1, s2;
+    CK(hipStreamCreate(&s1));
+    CK(hipStreamCreate(&s2));
+    hipEvent_t start, d1, d2;
+    CK(hipEventCreate(&start)); CK(hipEventCreate(&d1)); CK(hipEventCreate(&d2));
+    for (int rep = 0; rep < 2; ++rep) {
+      CK(hipDeviceSynchronize());
+      CK(hipEventRecord(start, 0));
+      CK(hipStreamWaitEvent(s1, start, 0));
+      CK(hipStreamWaitEvent(s2, start, 0));
+      for (int i = 0; i < 10; ++i) {
+        hipLaunchKernelGGL((one_wavefront_kernel<true, false>), grid, block, 0, s1, C, 0.5f);
+        hipLaunchKernelGGL((one_wavefront_kernel<false, true>), grid, block, 0, s2, C, 0.5f);
+      }
+      CK(hipEventRecord(d1, s1));
+      CK(hipEventRecord(d2, s2));
+      CK(hipEventSynchronize(d1));
+      CK(hipEventSynchronize(d2));
+      float m1 = 0.f, m2 = 0.f;
+      CK(hipEventElapsedTime(&m1, start, d1));
+      CK(hipEventElapsedTime(&m2, start, d2));
+      if (rep == 1)
+        std::printf("%-34s %8.1f us  (traffic stream done after %.1f us per pair, products stream after %.1f)\n",
+                    "two kernels on two streams", (m1 > m2 ? m1 : m2) * 100.0, m1 * 100.0, m2 * 100.0);
+    }
+    CK(hipGetLastError());
+    CK(hipStreamDestroy(s1));
+    CK(hipStreamDestroy(s2));
+  }
   CK(hipDeviceSynchronize());
   CK(hipFree(C));
   std::printf("done\n");
