@@ -265,9 +265,15 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
   __syncthreads();
   for (int idx = lane; idx < ns * ns; idx += 64) {
     const int a = idx / ns, b = idx - a * ns;
-    double g = 0.0;
-    for (int i = 0; i < r; ++i) g += Hs[i * ns + a] * Hs[i * ns + b];
-    Gs[idx] = g;
+    if constexpr (LOCATOR == 0) {
+      double g = 0.0;
+      for (int i = 0; i < r; ++i) g += Hs[i * ns + a] * Hs[i * ns + b];
+      Gs[idx] = g;
+    } else {
+      // (the relaxation has no use for G: the same region holds 1 / (x_b - x_a), row a, so that a lane
+      // reads its own column of a row: consecutive lanes, consecutive words)
+      Gs[idx] = a != b ? 1.0 / (p.t.pts64[b] - p.t.pts64[a]) : 0.0;
+    }
   }
   const bool use_filter = p.rho >= 1e-4;
   // (columns of H have their r entries in the first lanes: reductions over them need log2(rwidth) steps)
@@ -692,9 +698,8 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
             double d = 1.0, acc = 0.0;
             for (unsigned long long m = bmask; m; m &= m - 1ull) {
               const int k = __ffsll((long long)m) - 1;
-              const double dx = x - xs[k];
-              d *= dx;
-              acc += l1_wz[k] / dx;
+              d *= x - xs[k];
+              acc += l1_wz[k] * Gs[k * ns + lane];         // w_k z_k / (x - x_k)
             }
             Np = d;
             rs = zs[lane] - d * acc;                       // residual of the fit at this node
@@ -704,10 +709,7 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
           double u = 0.0;
           if (inB) {
             double acc = 0.0;
-            for (int i = 0; i < ns; ++i) {
-              const double sv = l1_sn[i];
-              if (sv != 0.0) acc += sv / (xs[i] - x);
-            }
+            for (int i = 0; i < ns; ++i) acc -= l1_sn[i] * Gs[i * ns + lane];   // sn_i / (x_i - x)
             u = w * acc;
           }
           double mv = inB ? fabs(u) - cost : -1.0e300;     // rate of descent on releasing this basis node
@@ -722,10 +724,10 @@ __global__ __launch_bounds__(64) void locate_kernel(LocateParams p) {
           if (!(mv > 1e-10) || it >= maxit) break;         // optimal, or the cap (wave-uniform)
           const int js = mi;
           const double sg = __shfl(u, js) > 0.0 ? 1.0 : -1.0;
-          const double wst = l1_w[js], xst = xs[js];
+          const double wst = l1_w[js];
           double q = kInf, a = 0.0;
           if (nb) {
-            const double T = wst * Np / (x - xst);        // l_js at this node
+            const double T = wst * Np * Gs[js * ns + lane];   // l_js at this node: w_js N / (x - x_js)
             const double st = sg * T;
             if (rs * st > 0.0) { q = rs / st; a = cost * fabs(T); }
           }
